@@ -1,0 +1,441 @@
+"""Pins for the CPU oracle: checks against things the paper and the mathematics fix.
+
+None of the expected values here is produced by the oracle.  They come from: the shape examples the
+paper prints, hand-evaluated cases (tests/golden/), an explicit im2col matrix multiplied with numpy
+in float64 (the equivalence the paper's Section 7 relies on when it contrasts im2col+GEMM with
+direct convolution), closed forms, algebraic identities, and exact rational arithmetic.
+
+Every pin is a plain function that raises AssertionError.  test_oracle_pins.py runs each of them
+against the real oracle; test_oracle_mutants.py re-runs them against builds of the oracle with one
+planted mistake each and requires a failure.
+"""
+from __future__ import annotations
+
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+
+import oracle
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _rows(name):
+    out = []
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                out.append(line.split())
+    return out
+
+
+# ---------------------------------------------------------------------------------------------------
+# independent reference: explicit im2col matrix + numpy float64 matmul
+# ---------------------------------------------------------------------------------------------------
+
+def im2col_matmul(x, w, bias, stride, pads, groups, pad_value=0.0):
+    """Direct construction of the patch matrix, then one float64 matmul per group."""
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    n, h, wd, c = x.shape
+    k, r, s, cg = w.shape
+    sh, sw = stride
+    pt, pl, pb, pr = pads
+    xp = np.full((n, h + pt + pb, wd + pl + pr, c), pad_value, dtype=np.float64)
+    xp[:, pt:pt + h, pl:pl + wd, :] = x
+    oh = (h + pt + pb - r) // sh + 1
+    ow = (wd + pl + pr - s) // sw + 1
+    kg = k // groups
+    y = np.zeros((n, oh, ow, k), dtype=np.float64)
+    for g in range(groups):
+        cols = np.empty((n, oh, ow, r, s, cg), dtype=np.float64)
+        for i in range(oh):
+            for j in range(ow):
+                cols[:, i, j] = xp[:, i * sh:i * sh + r, j * sw:j * sw + s, g * cg:(g + 1) * cg]
+        a = cols.reshape(n * oh * ow, r * s * cg)
+        b = w[g * kg:(g + 1) * kg].reshape(kg, r * s * cg).T
+        y[..., g * kg:(g + 1) * kg] = (a @ b).reshape(n, oh, ow, kg)
+    if bias is not None:
+        y += np.asarray(bias, dtype=np.float64)
+    return y
+
+
+TINY_SHAPES = [
+    # n  h  w  c  k  r  s  stride   pads(t,l,b,r)  groups
+    (1, 5, 5, 1, 1, 3, 3, (1, 1), (1, 1, 1, 1), 1),
+    (2, 7, 6, 3, 4, 3, 2, (1, 1), (0, 0, 0, 0), 1),
+    (2, 9, 8, 4, 6, 3, 3, (2, 2), (1, 1, 1, 1), 1),
+    (1, 8, 11, 2, 3, 5, 3, (2, 1), (2, 0, 1, 2), 1),
+    (3, 6, 6, 4, 6, 3, 3, (1, 2), (1, 2, 0, 1), 2),
+    (1, 10, 10, 6, 9, 1, 1, (1, 1), (0, 0, 0, 0), 3),
+    (2, 12, 12, 3, 5, 7, 7, (2, 2), (3, 3, 3, 3), 1),
+    (1, 4, 4, 8, 8, 4, 4, (1, 1), (0, 0, 0, 0), 8),
+]
+
+
+def _rand(rng, shape):
+    return rng.uniform(-1, 1, size=shape).astype(np.float32)
+
+
+def pin_shape_examples():
+    for in_, k, s, p, out in _rows("paper_shape_examples.txt"):
+        assert oracle.out_dim(int(in_), int(k), int(s), int(p), int(p)) == int(out)
+    # the listing's convolution end to end: 8x28x28x1 with 16x5x5x1, [5 1 2 16] -> 8x28x28x16
+    x = np.zeros((8, 28, 28, 1), np.float32)
+    w = np.zeros((16, 5, 5, 1), np.float32)
+    y = oracle.conv2d_f32(x, w, np.zeros(16, np.float32), (1, 1), (2, 2, 2, 2))
+    assert y.shape == (8, 28, 28, 16)
+    assert oracle.out_dim(4, 5, 1, 0, 0) == 0          # kernel larger than the padded input
+    assert oracle.out_dim(7, 3, 2, 0, 1) == 3          # floor((7+1-3)/2)+1
+
+
+def pin_conv_vs_im2col():
+    rng = np.random.default_rng(11)
+    for (n, h, w, c, k, r, s, st, pd, g) in TINY_SHAPES:
+        x = _rand(rng, (n, h, w, c)); wt = _rand(rng, (k, r, s, c // g)); b = _rand(rng, (k,))
+        ref = im2col_matmul(x, wt, b, st, pd, g)
+        got = oracle.conv2d_f32(x, wt, b, st, pd, g)
+        assert got.shape == ref.shape
+        # the oracle rounds a float64 sum once to float32
+        np.testing.assert_allclose(got.astype(np.float64), ref, rtol=1e-6, atol=1e-6)
+        ref_relu = np.maximum(ref, 0.0)
+        got_relu = oracle.conv2d_f32(x, wt, b, st, pd, g, act=oracle.ACT_RELU)
+        np.testing.assert_allclose(got_relu.astype(np.float64), ref_relu, rtol=1e-6, atol=1e-6)
+        # no bias
+        got_nb = oracle.conv2d_f32(x, wt, None, st, pd, g)
+        np.testing.assert_allclose(got_nb.astype(np.float64), im2col_matmul(x, wt, None, st, pd, g),
+                                   rtol=1e-6, atol=1e-6)
+
+
+def pin_conv_points_match_definition():
+    rng = np.random.default_rng(12)
+    for (n, h, w, c, k, r, s, st, pd, g) in TINY_SHAPES[2:5]:
+        x = _rand(rng, (n, h, w, c)); wt = _rand(rng, (k, r, s, c // g)); b = _rand(rng, (k,))
+        ref = np.maximum(im2col_matmul(x, wt, b, st, pd, g), 0.0).reshape(-1)
+        idx = rng.permutation(ref.size)[: max(1, ref.size // 3)].astype(np.int64)
+        got = oracle.conv2d_f32_points(x, wt, b, idx, st, pd, g, act=oracle.ACT_RELU)
+        np.testing.assert_allclose(got.astype(np.float64), ref[idx], rtol=1e-6, atol=1e-6)
+
+
+def pin_identity_and_delta_filters():
+    rng = np.random.default_rng(13)
+    x = _rand(rng, (2, 6, 7, 5))
+    b = _rand(rng, (5,))
+    # 1x1 identity filter: Y = X + b (exactly representable sums of two floats rounded once)
+    eye = np.eye(5, dtype=np.float32).reshape(5, 1, 1, 5)
+    y = oracle.conv2d_f32(x, eye, b)
+    np.testing.assert_array_equal(y, (x.astype(np.float64) + b.astype(np.float64)).astype(np.float32))
+    # centred delta 3x3 with pad 1: Y = X
+    d = np.zeros((5, 3, 3, 5), np.float32)
+    for ch in range(5):
+        d[ch, 1, 1, ch] = 1.0
+    np.testing.assert_array_equal(oracle.conv2d_f32(x, d, None, (1, 1), (1, 1, 1, 1)), x)
+    # delta at filter position (r=0, s=2): Y[oh,ow] = X[oh-1, ow+1], zero outside -> no filter flip
+    d = np.zeros((5, 3, 3, 5), np.float32)
+    for ch in range(5):
+        d[ch, 0, 2, ch] = 1.0
+    y = oracle.conv2d_f32(x, d, None, (1, 1), (1, 1, 1, 1))
+    exp = np.zeros_like(x)
+    exp[:, 1:, :-1, :] = x[:, :-1, 1:, :]
+    np.testing.assert_array_equal(y, exp)
+    # asymmetric hand example, one channel: x = [[1,2],[3,4]], w = [[10,20],[30,40]], no pad -> 300
+    x2 = np.array([1, 2, 3, 4], np.float32).reshape(1, 2, 2, 1)
+    w2 = np.array([10, 20, 30, 40], np.float32).reshape(1, 2, 2, 1)
+    assert float(oracle.conv2d_f32(x2, w2)[0, 0, 0, 0]) == 1 * 10 + 2 * 20 + 3 * 30 + 4 * 40
+    # filter index order [k][r][s][c]: r walks rows (H), s walks columns (W)
+    x3 = np.arange(12, dtype=np.float32).reshape(1, 3, 4, 1)
+    w3 = np.zeros((1, 2, 3, 1), np.float32); w3[0, 1, 2, 0] = 1.0
+    y3 = oracle.conv2d_f32(x3, w3)
+    np.testing.assert_array_equal(y3[0, :, :, 0], x3[0, 1:3, 2:4, 0])
+
+
+def pin_linearity_in_filter():
+    rng = np.random.default_rng(14)
+    # small integers: every product and sum is exact in double, so linearity must hold exactly
+    x = rng.integers(-8, 9, size=(2, 7, 7, 4)).astype(np.float32)
+    w1 = rng.integers(-8, 9, size=(6, 3, 3, 2)).astype(np.float32)
+    w2 = rng.integers(-8, 9, size=(6, 3, 3, 2)).astype(np.float32)
+    args = dict(stride=(2, 1), pads=(1, 1, 1, 1), groups=2)
+    y1 = oracle.conv2d_f32(x, w1, None, **args).astype(np.float64)
+    y2 = oracle.conv2d_f32(x, w2, None, **args).astype(np.float64)
+    y12 = oracle.conv2d_f32(x, 3 * w1 - 2 * w2, None, **args).astype(np.float64)
+    np.testing.assert_array_equal(y12, 3 * y1 - 2 * y2)
+
+
+def pin_all_ones_closed_form():
+    n, h, w, c, k, r, s = 1, 6, 5, 3, 2, 3, 3
+    x = np.ones((n, h, w, c), np.float32); wt = np.ones((k, r, s, c), np.float32)
+    y = oracle.conv2d_f32(x, wt, None, (1, 1), (1, 1, 1, 1))
+    rows = np.array([min(i + 1, h - 1) - max(i - 1, 0) + 1 for i in range(h)])
+    cols = np.array([min(j + 1, w - 1) - max(j - 1, 0) + 1 for j in range(w)])
+    exp = (rows[:, None] * cols[None, :] * c).astype(np.float32)
+    for kk in range(k):
+        np.testing.assert_array_equal(y[0, :, :, kk], exp)
+    assert y[0, 0, 0, 0] == 4 * c and y[0, 2, 2, 0] == 9 * c and y[0, 0, 2, 1] == 6 * c
+
+
+def pin_pointwise_is_matmul():
+    rng = np.random.default_rng(15)
+    x = _rand(rng, (2, 5, 4, 16)); wt = _rand(rng, (24, 1, 1, 16)); b = _rand(rng, (24,))
+    ref = x.reshape(-1, 16).astype(np.float64) @ wt.reshape(24, 16).astype(np.float64).T + b
+    np.testing.assert_allclose(oracle.conv2d_f32(x, wt, b).reshape(-1, 24), ref, rtol=1e-6, atol=1e-6)
+
+
+def pin_fc():
+    rng = np.random.default_rng(16)
+    a = _rand(rng, (5, 37)); w = _rand(rng, (37, 11)); b = _rand(rng, (11,))
+    ref = a.astype(np.float64) @ w.astype(np.float64) + b.astype(np.float64)
+    np.testing.assert_allclose(oracle.fc_f32(a, w, b), ref, rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(oracle.fc_f32(a, w, None), ref - b, rtol=1e-6, atol=1e-6)
+    np.testing.assert_allclose(oracle.fc_f32(a, w, b, act=oracle.ACT_RELU), np.maximum(ref, 0), rtol=1e-6,
+                               atol=1e-6)
+    # FC equals a 1x1 convolution on a 1x1 map with the filter being the transposed weight
+    yc = oracle.conv2d_f32(a.reshape(5, 1, 1, 37), np.ascontiguousarray(w.T).reshape(11, 1, 1, 37), b)
+    np.testing.assert_array_equal(yc.reshape(5, 11), oracle.fc_f32(a, w, b))
+    # non-square operands with distinct integer entries catch a transposed operand exactly
+    a2 = np.arange(6, dtype=np.float32).reshape(2, 3)
+    w2 = np.arange(12, dtype=np.float32).reshape(3, 4) - 5
+    np.testing.assert_array_equal(oracle.fc_f32(a2, w2, None), (a2.astype(np.float64) @ w2).astype(np.float32))
+
+
+def pin_relu_sign_pattern():
+    rng = np.random.default_rng(17)
+    x = _rand(rng, (1, 6, 6, 3)); wt = _rand(rng, (4, 3, 3, 3)); b = _rand(rng, (4,))
+    pre = im2col_matmul(x, wt, b, (1, 1), (1, 1, 1, 1), 1)
+    y = oracle.conv2d_f32(x, wt, b, (1, 1), (1, 1, 1, 1), act=oracle.ACT_RELU)
+    neg = pre < 0
+    assert neg.any() and (~neg).any()
+    assert np.all(y[neg] == 0.0) and not np.any(np.signbit(y[neg]))
+    np.testing.assert_allclose(y[~neg], pre[~neg], rtol=1e-6, atol=1e-6)
+
+
+def pin_dequantize_hand_cases():
+    for scale, off, q, val in _rows("dequantize_hand_cases.txt"):
+        got = oracle.dequantize(np.array([int(q)], np.int8), float(scale), int(off))[0]
+        assert got == float(val), (scale, off, q, val, got)
+
+
+def pin_quantize_round_trip():
+    codes = np.arange(-128, 128).astype(np.int8)
+    for scale, off in [(0.5, -3), (0.0123, 17), (0.1, -128), (0.07, 127), (3.0, 0)]:
+        v = oracle.dequantize(codes, scale, off)
+        np.testing.assert_array_equal(oracle.quantize(v, scale, off), codes)
+    # saturation and ties-to-even of the helper
+    q = oracle.quantize(np.array([1000.0, -1000.0, 0.25, 0.75, 1.25]), 0.5, 0)
+    np.testing.assert_array_equal(q, np.array([127, -128, 0, 2, 2], np.int8))
+
+
+def pin_int_accumulator_vs_real_domain():
+    """Dequantize everything, convolve in float64 (im2col reference), divide by sx*sw: must equal
+    the integer accumulator exactly (small integers times a power-of-two scale are exact)."""
+    rng = np.random.default_rng(18)
+    for (n, h, w, c, k, r, s, st, pd, g) in TINY_SHAPES[1:6]:
+        xq = rng.integers(-128, 128, size=(n, h, w, c), dtype=np.int8)
+        wq = rng.integers(-128, 128, size=(k, r, s, c // g), dtype=np.int8)
+        bq = rng.integers(-5000, 5000, size=(k,), dtype=np.int32)
+        sx, x_off, sw, w_off = 0.25, int(rng.integers(-20, 21)), 0.125, int(rng.integers(-5, 6))
+        xr = (xq.astype(np.float64) - x_off) * sx
+        wr = (wq.astype(np.float64) - w_off) * sw
+        real = im2col_matmul(xr, wr, bq.astype(np.float64) * sx * sw, st, pd, g)   # zero padding, real domain
+        acc_ref = real / (sx * sw)
+        assert np.all(acc_ref == np.rint(acc_ref))
+        _, acc = oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, 1.0, 0, st, pd, g, return_acc=True)
+        np.testing.assert_array_equal(acc.astype(np.float64), acc_ref)
+    # FC
+    aq = rng.integers(-128, 128, size=(4, 19), dtype=np.int8)
+    wq = rng.integers(-128, 128, size=(19, 7), dtype=np.int8)
+    bq = rng.integers(-5000, 5000, size=(7,), dtype=np.int32)
+    _, acc = oracle.qfc(aq, 0.5, 3, wq, 0.25, -2, bq, 1.0, 0, return_acc=True)
+    ref = (aq.astype(np.int64) - 3) @ (wq.astype(np.int64) + 2) + bq
+    np.testing.assert_array_equal(acc, ref)
+
+
+def _exact_requant(acc, mant, shift, y_off, lo):
+    """Exact rational arithmetic: floor(acc*mant/2^shift + 1/2) + y_off, saturated."""
+    q = math.floor(Fraction(acc * mant, 1 << shift) + Fraction(1, 2)) + y_off
+    return max(lo, min(127, q))
+
+
+def pin_requantize_hand_cases():
+    for sx, sw, sy, acc, y_off, lo, exp in _rows("requantize_hand_cases.txt"):
+        m, sh = oracle.requant_params(float(sx), float(sw), float(sy))
+        got = oracle.requantize(int(acc), m, sh, int(y_off), int(lo))
+        assert got == int(exp), (sx, sw, sy, acc, y_off, lo, exp, got)
+
+
+def pin_requant_params():
+    # powers of two: mantissa 2^30, shift = 30 + k   (Mr = 2^-k)
+    for k in range(0, 20):
+        m, sh = oracle.requant_params(2.0 ** -k, 1.0, 1.0)
+        assert (m, sh) == (1 << 30, 30 + k), (k, m, sh)
+    # general: m * 2^-sh within 2^-31 relative of the double product, m in [2^30, 2^31)
+    rng = np.random.default_rng(19)
+    for _ in range(2000):
+        sx, sw, sy = (float(np.float32(v)) for v in rng.uniform(0.001, 0.2, size=3))
+        m, sh = oracle.requant_params(sx, sw, sy)
+        mr = Fraction(sx) * Fraction(sw) / Fraction(sy)
+        assert (1 << 30) <= m < (1 << 31)
+        assert abs(Fraction(m, 1 << sh) - mr) <= mr / (1 << 31)
+    # just below a power of two, mantissa still representable: f = 1 - 2^-24, no carry
+    below = float(np.nextafter(np.float32(0.5), np.float32(0)))   # 0.5 - 2^-25
+    m, sh = oracle.requant_params(below, 1.0, 1.0)
+    assert Fraction(m, 1 << sh) == Fraction(below), (m, sh)
+    assert m == (1 << 31) - (1 << 7) and sh == 32, (m, sh)
+    # carry case: (1 + 2^-17)(1 - 2^-17) = 1 - 2^-34 is exact in double; f * 2^31 = 2^31 - 1/8 rounds
+    # to 2^31, which must be renormalised to 2^30 with the exponent bumped -> the same as Mr = 1
+    m, sh = oracle.requant_params(1.0 + 2.0 ** -17, 1.0 - 2.0 ** -17, 1.0)
+    assert (m, sh) == (1 << 30, 30), (m, sh)
+    m, sh = oracle.requant_params(0.125 * (1.0 + 2.0 ** -17), 1.0 - 2.0 ** -17, 1.0)
+    assert (m, sh) == (1 << 30, 33), (m, sh)
+    for bad in [(0.0, 1.0, 1.0), (-1.0, 1.0, 1.0), (1.0, float("nan"), 1.0), (1.0, 1.0, float("inf")),
+                (1e30, 1e30, 1e-30), (1e-30, 1e-30, 1e30)]:
+        try:
+            oracle.requant_params(*bad)
+        except oracle.OracleError as e:
+            assert e.code == oracle.BAD_QUANT
+        else:
+            raise AssertionError(f"accepted {bad}")
+
+
+def pin_requantize_exact_rational():
+    rng = np.random.default_rng(20)
+    edge = [0, 1, -1, 2, -2, 2**31 - 1, -2**31, 2**30, -2**30]
+    for _ in range(60):
+        sx, sw, sy = (float(np.float32(v)) for v in rng.uniform(0.001, 0.3, size=3))
+        m, sh = oracle.requant_params(sx, sw, sy)
+        y_off = int(rng.integers(-128, 128))
+        lo = int(rng.choice([-128, max(-128, y_off)]))
+        accs = edge + [1 << (sh - 1 - 30) if sh > 31 else 1, -(1 << max(0, sh - 31))]
+        accs += [int(v) for v in rng.integers(-2**31, 2**31, size=300)]
+        accs += [int(v) for v in rng.integers(-40000, 40000, size=1300)]
+        for a in accs:
+            assert oracle.requantize(a, m, sh, y_off, lo) == _exact_requant(a, m, sh, y_off, lo), (a, m, sh)
+    # exact ties with an odd power-of-two multiplier: acc = (2j+1) * 2^(k-1) -> j+1 (half up), both signs
+    for k in (1, 3, 7):
+        m, sh = oracle.requant_params(2.0 ** -k, 1.0, 1.0)
+        for j in range(-40, 40):
+            acc = (2 * j + 1) << (k - 1)
+            assert oracle.requantize(acc, m, sh, 0, -128) == j + 1
+            assert oracle.requantize(acc, m, sh, 0, -128) == math.floor((acc + (1 << (k - 1))) / (1 << k))
+
+
+def pin_requantize_vs_real_formula():
+    """Within one half code (plus the 2^-31 mantissa error) of the real-valued rule of Section 4.1,
+    monotone in the accumulator, saturating at both rails."""
+    rng = np.random.default_rng(21)
+    for _ in range(40):
+        sx, sw, sy = (float(np.float32(v)) for v in rng.uniform(0.002, 0.2, size=3))
+        m, sh = oracle.requant_params(sx, sw, sy)
+        mr = sx * sw / sy
+        y_off = int(rng.integers(-20, 21))
+        span = int(200 / mr)
+        accs = np.sort(rng.integers(-span, span, size=400))
+        prev = -129
+        for a in accs:
+            q = oracle.requantize(int(a), m, sh, y_off, -128)
+            real = a * mr + y_off
+            if -128 < real < 127:
+                assert abs(q - real) <= 0.5 + 2.0 ** -30 * abs(a * mr) + 1e-9
+            assert q >= prev
+            prev = q
+        assert oracle.requantize(2**31 - 1, m, sh, y_off, -128) == 127 or (2**31 - 1) * mr + y_off < 127.5
+        assert oracle.requantize(10 * span, m, sh, y_off, -128) == 127
+        assert oracle.requantize(-10 * span, m, sh, y_off, -128) == -128
+
+
+def pin_quantized_relu():
+    rng = np.random.default_rng(22)
+    xq = rng.integers(-128, 128, size=(1, 6, 6, 4), dtype=np.int8)
+    wq = rng.integers(-127, 128, size=(5, 3, 3, 4), dtype=np.int8)
+    bq = rng.integers(-300, 300, size=(5,), dtype=np.int32)
+    for y_off in (-128, -20, 0, 20, 127):
+        args = (xq, 0.05, 3, wq, 0.01, 0, bq, 0.4, y_off, (1, 1), (1, 1, 1, 1), 1)
+        plain = oracle.qconv2d(*args, act=oracle.ACT_NONE).astype(np.int32)
+        relu = oracle.qconv2d(*args, act=oracle.ACT_RELU).astype(np.int32)
+        # max on same-scale operands is a plain integer compare against the code of real zero
+        np.testing.assert_array_equal(relu, np.maximum(plain, max(-128, y_off)))
+        assert relu.min() >= max(-128, y_off)
+        if y_off in (-20, 0, 20):
+            assert (plain < y_off).any() and (plain > y_off).any()
+
+
+def pin_zero_point_and_padding():
+    """Input constantly equal to its offset is the real value 0 everywhere, padding included, so
+    every output is requantize(bias)."""
+    rng = np.random.default_rng(23)
+    x_off, w_off = 7, -4
+    xq = np.full((2, 5, 6, 3), x_off, np.int8)
+    wq = rng.integers(-128, 128, size=(4, 3, 3, 3), dtype=np.int8)
+    bq = np.array([100, -250, 0, 77], np.int32)
+    sx, sw, sy, y_off = 0.5, 0.25, 1.0, -3          # multiplier 1/8
+    y, acc = oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, (1, 1), (1, 1, 1, 1), 1,
+                            return_acc=True)
+    exp = np.array([math.floor(b / 8 + 0.5) + y_off for b in bq])
+    assert np.all(acc == bq.reshape(1, 1, 1, 4))
+    assert np.all(y == exp.reshape(1, 1, 1, 4))
+    # and a non-constant input: full pipeline against integer numpy + exact rational requantize
+    xq = rng.integers(-128, 128, size=(2, 5, 6, 3), dtype=np.int8)
+    sx, sw, sy = 0.043, 0.0071, 0.09
+    m, sh = oracle.requant_params(sx, sw, sy)
+    xr = xq.astype(np.float64) - x_off
+    wr = wq.astype(np.float64) - w_off
+    acc_ref = im2col_matmul(xr, wr, bq.astype(np.float64), (2, 1), (1, 0, 1, 2), 1).astype(np.int64)
+    y = oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, (2, 1), (1, 0, 1, 2), 1, act=oracle.ACT_RELU)
+    exp = np.vectorize(lambda a: _exact_requant(int(a), m, sh, y_off, y_off))(acc_ref)
+    np.testing.assert_array_equal(y.astype(np.int64), exp)
+    idx = np.arange(0, y.size, 3, dtype=np.int64)
+    pts = oracle.qconv2d_points(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, idx, (2, 1), (1, 0, 1, 2), 1,
+                                act=oracle.ACT_RELU)
+    np.testing.assert_array_equal(pts.astype(np.int64), exp.reshape(-1)[idx])
+
+
+def pin_qfc_full():
+    rng = np.random.default_rng(24)
+    aq = rng.integers(-128, 128, size=(3, 50), dtype=np.int8)
+    wq = rng.integers(-128, 128, size=(50, 9), dtype=np.int8)
+    bq = rng.integers(-3000, 3000, size=(9,), dtype=np.int32)
+    sa, a_off, sw, w_off, sy, y_off = 0.031, -11, 0.0093, 5, 0.27, 9
+    m, sh = oracle.requant_params(sa, sw, sy)
+    acc = (aq.astype(np.int64) - a_off) @ (wq.astype(np.int64) - w_off) + bq
+    for act, lo in ((oracle.ACT_NONE, -128), (oracle.ACT_RELU, y_off)):
+        exp = np.vectorize(lambda a: _exact_requant(int(a), m, sh, y_off, lo))(acc)
+        got = oracle.qfc(aq, sa, a_off, wq, sw, w_off, bq, sy, y_off, act=act)
+        np.testing.assert_array_equal(got.astype(np.int64), exp)
+
+
+def pin_accumulator_overflow_is_reported():
+    aq = np.full((1, 140000), 127, np.int8)
+    wq = np.full((140000, 1), 127, np.int8)
+    try:
+        oracle.qfc(aq, 0.1, 0, wq, 0.1, 0, None, 1.0, 0)     # 140000 * 16129 > 2^31
+    except oracle.OracleError as e:
+        assert e.code == oracle.ACC_OVERFLOW
+    else:
+        raise AssertionError("overflow not reported")
+
+
+ALL_PINS = [
+    pin_shape_examples,
+    pin_conv_vs_im2col,
+    pin_conv_points_match_definition,
+    pin_identity_and_delta_filters,
+    pin_linearity_in_filter,
+    pin_all_ones_closed_form,
+    pin_pointwise_is_matmul,
+    pin_fc,
+    pin_relu_sign_pattern,
+    pin_dequantize_hand_cases,
+    pin_quantize_round_trip,
+    pin_int_accumulator_vs_real_domain,
+    pin_requantize_hand_cases,
+    pin_requant_params,
+    pin_requantize_exact_rational,
+    pin_requantize_vs_real_formula,
+    pin_quantized_relu,
+    pin_zero_point_and_padding,
+    pin_qfc_full,
+    pin_accumulator_overflow_is_reported,
+]

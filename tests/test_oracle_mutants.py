@@ -1,0 +1,90 @@
+"""Sensitivity of the pins: plant one plausible mistake at a time in a copy of the oracle's C source
+(on the CPU, in a temporary directory), rebuild it, and require that at least one pin fails.
+
+This guards the pins, not the oracle: a pin suite that lets a dropped term, a wrong sign, a swapped
+index or a transposed operand through would not be worth trusting.
+"""
+import os
+import subprocess
+
+import pytest
+
+import oracle
+from oracle_pins import ALL_PINS
+
+SRC = os.path.join(os.path.dirname(oracle.__file__), "glow_oracle.c")
+
+# (name, old text, new text, which occurrence: index or None for all)
+MUTANTS = [
+    ("flip_rows_f32", "- cs->pad_t + r;", "- cs->pad_t - r + cs->r - 1;", 0),
+    ("flip_rows_int", "- cs->pad_t + r;", "- cs->pad_t - r + cs->r - 1;", 1),
+    ("pad_sign_w_f32", "- cs->pad_l + s;", "+ cs->pad_l + s;", 0),
+    ("pad_sign_w_int", "- cs->pad_l + s;", "+ cs->pad_l + s;", 1),
+    ("ceil_out_dim", "return span / stride + 1;", "return (span + stride - 1) / stride + 1;", None),
+    ("drop_bias_f32", "if (bias) acc += (double)bias[k];", "", None),
+    ("drop_bias_int", "if (bias) acc += (int64_t)bias[k];", "", None),
+    ("relu_inverted", "if (act == ORACLE_ACT_RELU && acc < 0.0) acc = 0.0;\n  return (float)acc;",
+     "if (act == ORACLE_ACT_RELU && acc > 0.0) acc = 0.0;\n  return (float)acc;", None),
+    ("relu_missing_fc", "if (act == ORACLE_ACT_RELU && acc < 0.0) acc = 0.0;\n      y[m * N + n]",
+     "y[m * N + n]", None),
+    ("filter_rs_swapped_f32", "((k * cs->r + r) * cs->s + s) * cg + cc", "((k * cs->s + s) * cs->r + r) * cg + cc", 0),
+    ("filter_rs_swapped_int", "((k * cs->r + r) * cs->s + s) * cg + cc", "((k * cs->s + s) * cs->r + r) * cg + cc", 1),
+    ("input_hw_swapped_f32", "((n * cs->h + ih) * cs->w + iw) * cs->c + c", "((n * cs->w + iw) * cs->h + ih) * cs->c + c", 0),
+    ("input_hw_swapped_int", "((n * cs->h + ih) * cs->w + iw) * cs->c + c", "((n * cs->w + iw) * cs->h + ih) * cs->c + c", 1),
+    ("stride_axes_swapped", "oh * cs->stride_h - cs->pad_t", "oh * cs->stride_w - cs->pad_t", 0),
+    ("group_channel_base_f32", "const int64_t c = g * cg + cc;", "const int64_t c = cc;", 0),
+    ("group_channel_base_int", "const int64_t c = g * cg + cc;", "const int64_t c = cc;", 1),
+    ("fc_weight_transposed", "(double)w[k * N + n]", "(double)w[n * K + k]", None),
+    ("fc_bias_index", "acc += (double)bias[n];", "acc += (double)bias[m];", None),
+    ("qfc_weight_transposed", "(int64_t)w[k * N + n] - w_off", "(int64_t)w[n * K + k] - w_off", None),
+    ("qfc_offset_sign", "(int64_t)a[m * K + k] - a_off", "(int64_t)a[m * K + k] + a_off", None),
+    ("dequant_offset_sign", "((double)q[i] - (double)offset)", "((double)q[i] + (double)offset)", None),
+    ("dequant_scale_divides", "(double)offset) * (double)scale;", "(double)offset) / (double)scale;", None),
+    ("quantize_floor", "nearbyint(value[i] / (double)scale)", "floor(value[i] / (double)scale)", None),
+    ("x_offset_ignored", "* cs->c + c] - x_off;", "* cs->c + c];", None),
+    ("w_offset_ignored", "* cg + cc] - w_off;", "* cg + cc];", None),
+    ("requant_truncates", "const int64_t half = (int64_t)1 << (shift - 1);", "const int64_t half = 0;", None),
+    ("requant_rounds_to_zero", "if ((t % d) < 0) q -= 1;", "", None),
+    ("requant_half_away", "const int64_t t = prod + half;", "const int64_t t = prod + (prod < 0 ? half - 1 : half);", None),
+    ("requant_no_carry", "if (m == 2147483648LL) { m = 1073741824LL; e += 1; }", "", None),
+    ("requant_shift_off_by_one", "const int sh = 31 - e;", "const int sh = 30 - e;", None),
+    ("requant_mantissa_30_bits", "llround(f * 2147483648.0)", "2 * llround(f * 1073741824.0 / 32768.0) * 16384", None),
+    ("requant_offset_before_scale", "q += y_offset;", "q -= y_offset;", None),
+    ("no_upper_saturation", "if (q > 127) q = 127;", "", None),
+    ("no_lower_saturation", "if (q < lo) q = lo;", "", None),
+    ("relu_floor_is_zero", "if (act == ORACLE_ACT_RELU && y_offset > -128) return y_offset;",
+     "if (act == ORACLE_ACT_RELU) return 0;", None),
+    ("points_decode_swapped", "const int64_t ow = f % cs.ow; f /= cs.ow;\n    const int64_t oh = f % cs.oh; f /= cs.oh;\n    out[i] = conv_f32_one",
+     "const int64_t oh = f % cs.oh; f /= cs.oh;\n    const int64_t ow = f % cs.ow; f /= cs.ow;\n    out[i] = conv_f32_one", None),
+    ("overflow_unchecked", "if (s > INT32_MAX || s < INT32_MIN) { overflow |= 1; continue; }", "", None),
+]
+
+
+def _mutate(text, old, new, which):
+    assert old in text, f"mutation anchor not found: {old!r}"
+    if which is None:
+        return text.replace(old, new)
+    parts = text.split(old)
+    assert len(parts) > which + 1, f"occurrence {which} of {old!r} missing"
+    return old.join(parts[: which + 1]) + new + old.join(parts[which + 1:])
+
+
+@pytest.mark.parametrize("name,old,new,which", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_pins_catch_mutant(tmp_path, name, old, new, which):
+    src = open(SRC).read()
+    mutated = _mutate(src, old, new, which)
+    assert mutated != src
+    c_path = tmp_path / f"{name}.c"
+    so_path = tmp_path / f"lib{name}.so"
+    c_path.write_text(mutated)
+    subprocess.run(["gcc", "-std=c11", "-O1", "-fopenmp", "-fPIC", "-shared", "-w", "-o", str(so_path),
+                    str(c_path), "-lm"], check=True)
+    caught = []
+    with oracle.use_library(str(so_path)):
+        for pin in ALL_PINS:
+            try:
+                pin()
+            except (AssertionError, oracle.OracleError):
+                caught.append(pin.__name__)
+                break
+    assert caught, f"mutant {name} passes every pin"
