@@ -1,0 +1,149 @@
+/*
+ * glowmi -- the lowered Convolution / FullyConnected hot path of the Glow paper (arXiv 1805.00907)
+ * as hand-written HIP kernels for AMD MI355X (gfx950), behind a plain C ABI.
+ *
+ * What the calls compute
+ * ----------------------
+ * After the paper's node-lowering phase (Section 3.4) a network's dense layers are a matrix
+ * multiplication followed by a broadcasted add of the bias, and the element-wise operators that
+ * follow are executed in the same pass over the data (Section 5.2, operator stacking).  Each entry
+ * point below is one such stack: contraction + bias + optional Relu (the max0 instruction of the
+ * Section 3.5 listing), in fp32 and in the quantized int8 form of Section 4.
+ *
+ * Conventions common to every call
+ * --------------------------------
+ *  - Every tensor pointer is a DEVICE pointer to a dense, row-major buffer owned by the caller.
+ *    Inputs are never written.  Outputs must not overlap inputs or the workspace.
+ *  - x, w, y (and a, the FC input) must be 16-byte aligned, bias 4-byte aligned, else
+ *    GLOWMI_ERR_ALIGN.  bias may be NULL (treated as zeros).
+ *  - Calls are asynchronous on `stream`, never synchronise the device and never allocate.
+ *  - `workspace` is optional scratch in device memory (16-byte aligned).  With NULL / 0 bytes the
+ *    call still computes the same result; with at least glowmi_*_workspace_bytes() bytes the
+ *    library may split the reduction dimension over more workgroups (small-M layers).  The
+ *    contents on entry do not matter and are undefined on return.  Two calls that share a
+ *    workspace must be ordered on one stream.
+ *  - Arguments are validated on the host before anything is launched.  On any error nothing is
+ *    launched, y is untouched, the status says why and glowmi_last_error() gives a sentence.
+ *  - Every tensor must hold fewer than 2^31 elements (GLOWMI_ERR_UNSUPPORTED otherwise).
+ *  - Results: fp32 entry points accumulate in fp32 (order unspecified); the int8 entry points are
+ *    exact integer arithmetic and reproducible bit for bit.
+ */
+#ifndef GLOWMI_H
+#define GLOWMI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#include <hip/hip_runtime_api.h> /* hipStream_t */
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum glowmi_status {
+  GLOWMI_OK = 0,
+  GLOWMI_ERR_NULL = 1,        /* a required pointer is NULL                                   */
+  GLOWMI_ERR_SHAPE = 2,       /* non-positive extent, groups not dividing channels, empty output */
+  GLOWMI_ERR_UNSUPPORTED = 3, /* valid request outside what the kernels cover (e.g. >= 2^31 elements) */
+  GLOWMI_ERR_ALIGN = 4,       /* pointer alignment                                             */
+  GLOWMI_ERR_QUANT = 5,       /* scale not finite and positive, offset outside [-128,127], multiplier out of range */
+  GLOWMI_ERR_HIP = 6          /* the HIP runtime refused the launch                            */
+} glowmi_status;
+
+/* The element-wise chain fused behind the contraction. */
+typedef enum glowmi_act {
+  GLOWMI_ACT_NONE = 0,
+  GLOWMI_ACT_RELU = 1 /* max(v, 0); on a quantized tensor: max(q, y.offset) (Section 4.3, same-scale max) */
+} glowmi_act;
+
+/*
+ * Convolution geometry.  Input is <n x h x w x c> (Section 3.5 listing), the filter is
+ * [k][r][s][c/groups] = [depth, filter_x, filter_y, channel] (filter-layout figure of Section 5.2),
+ * the output is <n x oh x ow x k> with
+ *     oh = floor((h + pad_t + pad_b - r) / stride_h) + 1,   ow likewise
+ * (the listing's [kernel stride pad depth] parameters; its 28 -> 28 and 28 -> 9 examples).
+ * Padding is zero padding of the real-valued input.  No filter flip: output (oh, ow) reads input
+ * row oh*stride_h - pad_t + r and column ow*stride_w - pad_l + s.  groups splits input and output
+ * channels into that many contiguous blocks (a reading: the paper has no grouped convolution).
+ */
+typedef struct glowmi_conv_desc {
+  int32_t n, h, w, c;
+  int32_t k, r, s;
+  int32_t stride_h, stride_w;
+  int32_t pad_t, pad_l, pad_b, pad_r;
+  int32_t groups;
+} glowmi_conv_desc;
+
+/* Quantized tensor type of Section 4.1: int8 codes q with value = (q - offset) * scale. */
+typedef struct glowmi_qparam {
+  float scale;    /* finite, > 0 */
+  int32_t offset; /* in [-128, 127] */
+} glowmi_qparam;
+
+/* Output extents for a descriptor; returns GLOWMI_ERR_SHAPE if the descriptor is invalid. Host only. */
+glowmi_status glowmi_conv_out_shape(const glowmi_conv_desc* d, int32_t* oh, int32_t* ow);
+
+/*
+ * fp32 Convolution + bias + activation (Sections 3.1, 3.5, 5.2).
+ *   x [n][h][w][c], w [k][r][s][c/groups], bias [k] or NULL, y [n][oh][ow][k], all float, device.
+ */
+glowmi_status glowmi_conv2d(const float* x, const float* w, const float* bias, float* y,
+                            const glowmi_conv_desc* d, glowmi_act act, void* workspace,
+                            size_t workspace_bytes, hipStream_t stream);
+size_t glowmi_conv2d_workspace_bytes(const glowmi_conv_desc* d);
+
+/*
+ * fp32 FullyConnected as lowered in Section 3.4: y = a * w (MatMul), + bias broadcast over rows
+ * (BatchedAdd), then the activation.
+ *   a [M][K], w [K][N], bias [N] or NULL, y [M][N], all float, device.
+ */
+glowmi_status glowmi_fc(const float* a, const float* w, const float* bias, float* y, int32_t M,
+                        int32_t K, int32_t N, glowmi_act act, void* workspace,
+                        size_t workspace_bytes, hipStream_t stream);
+size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N);
+
+/*
+ * Quantized Convolution (Section 4.1 tensor type; Section 4.3: the rescale to the output range is
+ * folded into the operation, and Relu is a plain integer max because both sides share a scale).
+ *   acc   = sum over taps inside the image of (x - xq.offset) * (w - wq.offset)  + bias     (int32)
+ *   y     = saturate( round(acc * xq.scale * wq.scale / yq.scale) + yq.offset )  to [lo, 127]
+ *   lo    = max(-128, yq.offset) with GLOWMI_ACT_RELU, else -128
+ * bias is int32 with scale xq.scale*wq.scale and offset 0 (or NULL).  The multiplier
+ * Mr = xq.scale*wq.scale/yq.scale is evaluated in double on the host and applied as an integer:
+ * Mr = f * 2^e with f in [0.5, 1); mant = round(f * 2^31) (renormalised if that is 2^31);
+ * shift = 31 - e, which must lie in [1, 62] (GLOWMI_ERR_QUANT otherwise);
+ *   round(acc * Mr) := (acc * mant + 2^(shift-1)) >> shift    (64-bit, arithmetic shift: ties go up).
+ * The int32 accumulator must not overflow (not detected on the device: caller's contract; it holds
+ * whenever r*s*c/groups * 2^15 < 2^31).
+ *   x int8 [n][h][w][c], w int8 [k][r][s][c/groups], bias int32 [k], y int8 [n][oh][ow][k], device.
+ */
+glowmi_status glowmi_qconv2d(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
+                             const int32_t* bias, int8_t* y, glowmi_qparam yq,
+                             const glowmi_conv_desc* d, glowmi_act act, void* workspace,
+                             size_t workspace_bytes, hipStream_t stream);
+size_t glowmi_qconv2d_workspace_bytes(const glowmi_conv_desc* d);
+
+/*
+ * Quantized FullyConnected: the Section 3.4 lowering on Section 4.1 tensors, same arithmetic as
+ * glowmi_qconv2d.   a int8 [M][K], w int8 [K][N], bias int32 [N] or NULL, y int8 [M][N], device.
+ */
+glowmi_status glowmi_qfc(const int8_t* a, glowmi_qparam aq, const int8_t* w, glowmi_qparam wq,
+                         const int32_t* bias, int8_t* y, glowmi_qparam yq, int32_t M, int32_t K,
+                         int32_t N, glowmi_act act, void* workspace, size_t workspace_bytes,
+                         hipStream_t stream);
+size_t glowmi_qfc_workspace_bytes(int32_t M, int32_t K, int32_t N);
+
+/* Host helper: the integer multiplier/shift the quantized entry points derive from three scales. */
+glowmi_status glowmi_requant_params(float x_scale, float w_scale, float y_scale, int32_t* mant,
+                                    int32_t* shift);
+
+const char* glowmi_status_string(glowmi_status s);
+/* Message of the last failing call on the calling thread ("" if none). Valid until the next call. */
+const char* glowmi_last_error(void);
+/* Name of the kernel variant the last successful call on this thread launched (for profiling). */
+const char* glowmi_last_variant(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GLOWMI_H */

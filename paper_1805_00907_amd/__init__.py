@@ -1,0 +1,27 @@
+"""glowmi: the lowered Convolution / FullyConnected hot path of the Glow paper (arXiv 1805.00907)
+as hand-written HIP kernels for AMD MI355X, behind a C ABI (include/glowmi.h).
+
+This package is only the thin Python face of that library: it marshals torch device tensors into
+the C calls.  Every step of the computation runs in the HIP kernels; there is no CPU fallback, and
+loading fails loudly when the library has not been built (python -m paper_1805_00907_amd.build).
+"""
+from .binding import (  # noqa: F401
+    ACT_NONE,
+    ACT_RELU,
+    ConvDesc,
+    GlowmiError,
+    QParam,
+    conv2d,
+    conv2d_workspace_bytes,
+    conv_out_shape,
+    fc,
+    fc_workspace_bytes,
+    last_variant,
+    library,
+    library_path,
+    qconv2d,
+    qconv2d_workspace_bytes,
+    qfc,
+    qfc_workspace_bytes,
+    requant_params,
+)

@@ -1,0 +1,160 @@
+"""ctypes binding of libglowmi.so with the same names as the C ABI (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+ACT_NONE = 0
+ACT_RELU = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libglowmi.so")
+
+STATUS_NAMES = {0: "GLOWMI_OK", 1: "GLOWMI_ERR_NULL", 2: "GLOWMI_ERR_SHAPE", 3: "GLOWMI_ERR_UNSUPPORTED",
+                4: "GLOWMI_ERR_ALIGN", 5: "GLOWMI_ERR_QUANT", 6: "GLOWMI_ERR_HIP"}
+
+
+class ConvDesc(ctypes.Structure):
+    """glowmi_conv_desc: input n,h,w,c; filter k,r,s; strides; pads (top, left, bottom, right); groups."""
+    _fields_ = [(name, ctypes.c_int32) for name in
+                ("n", "h", "w", "c", "k", "r", "s", "stride_h", "stride_w",
+                 "pad_t", "pad_l", "pad_b", "pad_r", "groups")]
+
+
+class QParam(ctypes.Structure):
+    """glowmi_qparam: value = (q - offset) * scale."""
+    _fields_ = [("scale", ctypes.c_float), ("offset", ctypes.c_int32)]
+
+
+class GlowmiError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def library() -> ctypes.CDLL:
+    """Load libglowmi.so.  There is no fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_1805_00907_amd.build` "
+                          "(glowmi has no CPU or PyTorch fallback)")
+    L = ctypes.CDLL(_LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    dp = ctypes.POINTER(ConvDesc)
+    L.glowmi_conv_out_shape.argtypes = [dp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.glowmi_conv2d.argtypes = [vp, vp, vp, vp, dp, ctypes.c_int, vp, sz, vp]
+    L.glowmi_conv2d_workspace_bytes.argtypes = [dp]
+    L.glowmi_conv2d_workspace_bytes.restype = sz
+    L.glowmi_fc.argtypes = [vp, vp, vp, vp, i32, i32, i32, ctypes.c_int, vp, sz, vp]
+    L.glowmi_fc_workspace_bytes.argtypes = [i32, i32, i32]
+    L.glowmi_fc_workspace_bytes.restype = sz
+    L.glowmi_qconv2d.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, dp, ctypes.c_int, vp, sz, vp]
+    L.glowmi_qconv2d_workspace_bytes.argtypes = [dp]
+    L.glowmi_qconv2d_workspace_bytes.restype = sz
+    L.glowmi_qfc.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, i32, i32, i32, ctypes.c_int, vp, sz, vp]
+    L.glowmi_qfc_workspace_bytes.argtypes = [i32, i32, i32]
+    L.glowmi_qfc_workspace_bytes.restype = sz
+    L.glowmi_requant_params.argtypes = [ctypes.c_float] * 3 + [ctypes.POINTER(i32)] * 2
+    L.glowmi_status_string.argtypes = [ctypes.c_int]
+    L.glowmi_status_string.restype = ctypes.c_char_p
+    L.glowmi_last_error.restype = ctypes.c_char_p
+    L.glowmi_last_variant.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        raise GlowmiError(status, library().glowmi_last_error().decode())
+
+
+def last_variant() -> str:
+    return library().glowmi_last_variant().decode()
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (None -> NULL); accepts a raw integer address too."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _ws(workspace) -> Tuple[Optional[int], int]:
+    if workspace is None:
+        return None, 0
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    """hipStream_t handle: a torch stream, a raw handle, or torch's current stream when None."""
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def conv_out_shape(desc: ConvDesc) -> Tuple[int, int]:
+    oh, ow = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(library().glowmi_conv_out_shape(ctypes.byref(desc), ctypes.byref(oh), ctypes.byref(ow)))
+    return oh.value, ow.value
+
+
+def conv2d_workspace_bytes(desc: ConvDesc) -> int:
+    return int(library().glowmi_conv2d_workspace_bytes(ctypes.byref(desc)))
+
+
+def conv2d(x, w, bias, y, desc: ConvDesc, act: int = ACT_NONE, workspace=None, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(library().glowmi_conv2d(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), ctypes.byref(desc), act, wp, wb,
+                                   _stream(stream)))
+
+
+def fc_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(library().glowmi_fc_workspace_bytes(M, K, N))
+
+
+def fc(a, w, bias, y, M: int, K: int, N: int, act: int = ACT_NONE, workspace=None, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(library().glowmi_fc(_ptr(a), _ptr(w), _ptr(bias), _ptr(y), M, K, N, act, wp, wb, _stream(stream)))
+
+
+def qconv2d_workspace_bytes(desc: ConvDesc) -> int:
+    return int(library().glowmi_qconv2d_workspace_bytes(ctypes.byref(desc)))
+
+
+def qconv2d(x, xq: QParam, w, wq: QParam, bias, y, yq: QParam, desc: ConvDesc, act: int = ACT_NONE,
+            workspace=None, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(library().glowmi_qconv2d(_ptr(x), xq, _ptr(w), wq, _ptr(bias), _ptr(y), yq, ctypes.byref(desc),
+                                    act, wp, wb, _stream(stream)))
+
+
+def qfc_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(library().glowmi_qfc_workspace_bytes(M, K, N))
+
+
+def qfc(a, aq: QParam, w, wq: QParam, bias, y, yq: QParam, M: int, K: int, N: int, act: int = ACT_NONE,
+        workspace=None, stream=None) -> None:
+    wp, wb = _ws(workspace)
+    _check(library().glowmi_qfc(_ptr(a), aq, _ptr(w), wq, _ptr(bias), _ptr(y), yq, M, K, N, act, wp, wb,
+                                _stream(stream)))
+
+
+def requant_params(x_scale: float, w_scale: float, y_scale: float) -> Tuple[int, int]:
+    m, s = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(library().glowmi_requant_params(x_scale, w_scale, y_scale, ctypes.byref(m), ctypes.byref(s)))
+    return m.value, s.value

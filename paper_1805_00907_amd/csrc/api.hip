@@ -1,0 +1,305 @@
+// C ABI of glowmi: argument validation, problem set-up and dispatch.  No arithmetic of the
+// operators lives here except the host-side derivation of the integer requantization multiplier.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/glowmi.h"
+#include "igemm.h"
+
+namespace {
+
+thread_local char g_error[256] = "";
+thread_local const char* g_variant = "";
+
+glowmi_status fail(glowmi_status s, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+  return s;
+}
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+constexpr long long kMaxElems = (1LL << 31) - 1;
+constexpr int kMaxExtent = 1 << 20;       // spatial / filter extents; keeps row arithmetic in int32
+constexpr int kMaxQuantDepth = 65535;     // reduction depth for which an int32 accumulator cannot overflow
+
+struct Geometry {
+  int oh, ow;
+  long long x_elems, w_elems, y_elems;
+};
+
+glowmi_status check_desc(const glowmi_conv_desc* d, Geometry* geo) {
+  if (!d) return fail(GLOWMI_ERR_NULL, "descriptor is NULL");
+  if (d->n <= 0 || d->h <= 0 || d->w <= 0 || d->c <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0)
+    return fail(GLOWMI_ERR_SHAPE, "extents must be positive (n=%d h=%d w=%d c=%d k=%d r=%d s=%d)", d->n,
+                d->h, d->w, d->c, d->k, d->r, d->s);
+  if (d->stride_h <= 0 || d->stride_w <= 0)
+    return fail(GLOWMI_ERR_SHAPE, "strides must be positive (%d, %d)", d->stride_h, d->stride_w);
+  if (d->pad_t < 0 || d->pad_l < 0 || d->pad_b < 0 || d->pad_r < 0)
+    return fail(GLOWMI_ERR_SHAPE, "pads must be non-negative");
+  if (d->groups <= 0 || d->c % d->groups != 0 || d->k % d->groups != 0)
+    return fail(GLOWMI_ERR_SHAPE, "groups=%d must divide c=%d and k=%d", d->groups, d->c, d->k);
+  const long long span_h = (long long)d->h + d->pad_t + d->pad_b - d->r;
+  const long long span_w = (long long)d->w + d->pad_l + d->pad_r - d->s;
+  if (span_h < 0 || span_w < 0)
+    return fail(GLOWMI_ERR_SHAPE, "filter %dx%d larger than padded input %lldx%lld", d->r, d->s,
+                (long long)d->h + d->pad_t + d->pad_b, (long long)d->w + d->pad_l + d->pad_r);
+  if (d->h > kMaxExtent || d->w > kMaxExtent || d->r > kMaxExtent || d->s > kMaxExtent ||
+      d->pad_t > kMaxExtent || d->pad_l > kMaxExtent || d->pad_b > kMaxExtent || d->pad_r > kMaxExtent ||
+      d->stride_h > kMaxExtent || d->stride_w > kMaxExtent)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "spatial extents, pads and strides are limited to 2^20");
+  const long long oh = span_h / d->stride_h + 1, ow = span_w / d->stride_w + 1;
+  geo->oh = (int)oh;
+  geo->ow = (int)ow;
+  geo->x_elems = (long long)d->n * d->h * d->w * d->c;
+  geo->w_elems = (long long)d->k * d->r * d->s * (d->c / d->groups);
+  geo->y_elems = (long long)d->n * oh * ow * d->k;
+  if (geo->x_elems > kMaxElems || geo->w_elems > kMaxElems || geo->y_elems > kMaxElems)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "a tensor has 2^31 or more elements");
+  return GLOWMI_OK;
+}
+
+void fill_conv(glowmi::Problem& p, const glowmi_conv_desc* d, const Geometry& geo) {
+  std::memset(&p, 0, sizeof(p));
+  p.n = d->n; p.h = d->h; p.w_ = d->w; p.c = d->c;
+  p.k = d->k; p.r = d->r; p.s = d->s;
+  p.oh = geo.oh; p.ow = geo.ow;
+  p.stride_h = d->stride_h; p.stride_w = d->stride_w;
+  p.pad_t = d->pad_t; p.pad_l = d->pad_l;
+  p.groups = d->groups; p.cg = d->c / d->groups; p.kg = d->k / d->groups;
+  p.M = d->n * geo.oh * geo.ow;
+  p.Kgemm = d->r * d->s * p.cg;
+  p.split_k = 1;
+  p.slabs_per_split = 0;
+  p.b_is_kn = 0;
+}
+
+glowmi_status check_fc(int32_t M, int32_t K, int32_t N) {
+  if (M <= 0 || K <= 0 || N <= 0)
+    return fail(GLOWMI_ERR_SHAPE, "extents must be positive (M=%d K=%d N=%d)", M, K, N);
+  if ((long long)M * K > kMaxElems || (long long)K * N > kMaxElems || (long long)M * N > kMaxElems)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "a tensor has 2^31 or more elements");
+  return GLOWMI_OK;
+}
+
+// FullyConnected as the same contraction: rows are "images" of a 1x1 map with K channels.
+void fill_fc(glowmi::Problem& p, int32_t M, int32_t K, int32_t N) {
+  std::memset(&p, 0, sizeof(p));
+  p.n = M; p.h = 1; p.w_ = 1; p.c = K;
+  p.k = N; p.r = 1; p.s = 1;
+  p.oh = 1; p.ow = 1;
+  p.stride_h = 1; p.stride_w = 1;
+  p.groups = 1; p.cg = K; p.kg = N;
+  p.M = M;
+  p.Kgemm = K;
+  p.split_k = 1;
+  p.b_is_kn = 1;
+}
+
+glowmi_status check_act(glowmi_act act) {
+  if (act != GLOWMI_ACT_NONE && act != GLOWMI_ACT_RELU)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "unknown activation %d", (int)act);
+  return GLOWMI_OK;
+}
+
+glowmi_status check_ptrs(const void* x, const void* w, const void* bias, const void* y) {
+  if (!x || !w || !y) return fail(GLOWMI_ERR_NULL, "input, weight and output pointers must not be NULL");
+  if (!aligned(x, 16) || !aligned(w, 16) || !aligned(y, 16))
+    return fail(GLOWMI_ERR_ALIGN, "input, weight and output pointers must be 16-byte aligned");
+  if (bias && !aligned(bias, 4)) return fail(GLOWMI_ERR_ALIGN, "bias must be 4-byte aligned");
+  return GLOWMI_OK;
+}
+
+bool workspace_usable(const void* ws, size_t have, size_t need) {
+  return ws != nullptr && need > 0 && have >= need && aligned(ws, 16);
+}
+
+glowmi_status quant_setup(glowmi::Problem& p, glowmi_qparam xq, glowmi_qparam wq, glowmi_qparam yq,
+                          glowmi_act act) {
+  if (xq.offset < -128 || xq.offset > 127 || wq.offset < -128 || wq.offset > 127 || yq.offset < -128 ||
+      yq.offset > 127)
+    return fail(GLOWMI_ERR_QUANT, "offsets must lie in [-128, 127] (x %d, w %d, y %d)", xq.offset, wq.offset,
+                yq.offset);
+  int32_t mant = 0, shift = 0;
+  glowmi_status st = glowmi_requant_params(xq.scale, wq.scale, yq.scale, &mant, &shift);
+  if (st != GLOWMI_OK) return st;
+  if (p.Kgemm > kMaxQuantDepth)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "reduction depth %d exceeds %d: int32 accumulator could overflow",
+                p.Kgemm, kMaxQuantDepth);
+  p.x_off = xq.offset; p.w_off = wq.offset; p.y_off = yq.offset;
+  p.mant = mant; p.shift = shift;
+  p.lo = (act == GLOWMI_ACT_RELU && yq.offset > -128) ? yq.offset : -128;
+  return GLOWMI_OK;
+}
+
+glowmi_status finish(hipError_t e, const char* variant) {
+  if (e != hipSuccess) return fail(GLOWMI_ERR_HIP, "launch failed: %s", hipGetErrorString(e));
+  g_variant = variant;
+  g_error[0] = 0;
+  return GLOWMI_OK;
+}
+
+size_t split_bytes(const glowmi::Plan& pl, const glowmi::Problem& p) {
+  return pl.split_k > 1 ? (size_t)pl.split_k * (size_t)p.M * (size_t)p.k * 4u : 0u;
+}
+
+}  // namespace
+
+extern "C" {
+
+glowmi_status glowmi_conv_out_shape(const glowmi_conv_desc* d, int32_t* oh, int32_t* ow) {
+  Geometry geo;
+  glowmi_status st = check_desc(d, &geo);
+  if (st != GLOWMI_OK) return st;
+  if (oh) *oh = geo.oh;
+  if (ow) *ow = geo.ow;
+  return GLOWMI_OK;
+}
+
+size_t glowmi_conv2d_workspace_bytes(const glowmi_conv_desc* d) {
+  Geometry geo;
+  if (check_desc(d, &geo) != GLOWMI_OK) return 0;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  return split_bytes(glowmi::plan_f32(p, true), p);
+}
+
+glowmi_status glowmi_conv2d(const float* x, const float* w, const float* bias, float* y,
+                            const glowmi_conv_desc* d, glowmi_act act, void* workspace,
+                            size_t workspace_bytes, hipStream_t stream) {
+  Geometry geo;
+  glowmi_status st = check_desc(d, &geo);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
+  if ((st = check_act(act)) != GLOWMI_OK) return st;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  const size_t need = split_bytes(glowmi::plan_f32(p, true), p);
+  p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
+  const char* variant = "";
+  return finish(glowmi::launch_f32(p, stream, &variant), variant);
+}
+
+size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N) {
+  if (check_fc(M, K, N) != GLOWMI_OK) return 0;
+  glowmi::Problem p;
+  fill_fc(p, M, K, N);
+  return split_bytes(glowmi::plan_f32(p, true), p);
+}
+
+glowmi_status glowmi_fc(const float* a, const float* w, const float* bias, float* y, int32_t M,
+                        int32_t K, int32_t N, glowmi_act act, void* workspace,
+                        size_t workspace_bytes, hipStream_t stream) {
+  glowmi_status st = check_fc(M, K, N);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_ptrs(a, w, bias, y)) != GLOWMI_OK) return st;
+  if ((st = check_act(act)) != GLOWMI_OK) return st;
+  glowmi::Problem p;
+  fill_fc(p, M, K, N);
+  p.x = a; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  const size_t need = split_bytes(glowmi::plan_f32(p, true), p);
+  p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
+  const char* variant = "";
+  return finish(glowmi::launch_f32(p, stream, &variant), variant);
+}
+
+size_t glowmi_qconv2d_workspace_bytes(const glowmi_conv_desc* d) {
+  Geometry geo;
+  if (check_desc(d, &geo) != GLOWMI_OK) return 0;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  return split_bytes(glowmi::plan_i8(p, true), p);
+}
+
+glowmi_status glowmi_qconv2d(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
+                             const int32_t* bias, int8_t* y, glowmi_qparam yq,
+                             const glowmi_conv_desc* d, glowmi_act act, void* workspace,
+                             size_t workspace_bytes, hipStream_t stream) {
+  Geometry geo;
+  glowmi_status st = check_desc(d, &geo);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
+  if ((st = check_act(act)) != GLOWMI_OK) return st;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  if ((st = quant_setup(p, xq, wq, yq, act)) != GLOWMI_OK) return st;
+  p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  const size_t need = split_bytes(glowmi::plan_i8(p, true), p);
+  p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
+  const char* variant = "";
+  return finish(glowmi::launch_i8(p, stream, &variant), variant);
+}
+
+size_t glowmi_qfc_workspace_bytes(int32_t M, int32_t K, int32_t N) {
+  if (check_fc(M, K, N) != GLOWMI_OK) return 0;
+  glowmi::Problem p;
+  fill_fc(p, M, K, N);
+  return split_bytes(glowmi::plan_i8(p, true), p);
+}
+
+glowmi_status glowmi_qfc(const int8_t* a, glowmi_qparam aq, const int8_t* w, glowmi_qparam wq,
+                         const int32_t* bias, int8_t* y, glowmi_qparam yq, int32_t M, int32_t K,
+                         int32_t N, glowmi_act act, void* workspace, size_t workspace_bytes,
+                         hipStream_t stream) {
+  glowmi_status st = check_fc(M, K, N);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_ptrs(a, w, bias, y)) != GLOWMI_OK) return st;
+  if ((st = check_act(act)) != GLOWMI_OK) return st;
+  glowmi::Problem p;
+  fill_fc(p, M, K, N);
+  if ((st = quant_setup(p, aq, wq, yq, act)) != GLOWMI_OK) return st;
+  p.x = a; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  const size_t need = split_bytes(glowmi::plan_i8(p, true), p);
+  p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
+  const char* variant = "";
+  return finish(glowmi::launch_i8(p, stream, &variant), variant);
+}
+
+// Mr = x_scale * w_scale / y_scale as mant * 2^-shift, mant a 31-bit integer with its top bit set.
+glowmi_status glowmi_requant_params(float x_scale, float w_scale, float y_scale, int32_t* mant,
+                                    int32_t* shift) {
+  if (!mant || !shift) return fail(GLOWMI_ERR_NULL, "mant/shift output pointers are NULL");
+  const float sc[3] = {x_scale, w_scale, y_scale};
+  for (float v : sc)
+    if (!std::isfinite(v) || v <= 0.0f) return fail(GLOWMI_ERR_QUANT, "scale %g is not finite and positive", (double)v);
+  const double mr = (double)x_scale * (double)w_scale / (double)y_scale;
+  if (!std::isfinite(mr) || mr <= 0.0) return fail(GLOWMI_ERR_QUANT, "combined multiplier %g is unusable", mr);
+  int exponent = 0;
+  const double frac = std::frexp(mr, &exponent);               // [0.5, 1)
+  long long q31 = std::llround(std::ldexp(frac, 31));          // [2^30, 2^31]
+  if (q31 == (1LL << 31)) {                                    // rounded up to the next binade
+    q31 >>= 1;
+    exponent += 1;
+  }
+  const int sh = 31 - exponent;
+  if (sh < 1 || sh > 62)
+    return fail(GLOWMI_ERR_QUANT, "combined multiplier %g needs shift %d outside [1, 62]", mr, sh);
+  *mant = (int32_t)q31;
+  *shift = sh;
+  return GLOWMI_OK;
+}
+
+const char* glowmi_status_string(glowmi_status s) {
+  switch (s) {
+    case GLOWMI_OK: return "ok";
+    case GLOWMI_ERR_NULL: return "null pointer";
+    case GLOWMI_ERR_SHAPE: return "invalid shape";
+    case GLOWMI_ERR_UNSUPPORTED: return "unsupported";
+    case GLOWMI_ERR_ALIGN: return "misaligned pointer";
+    case GLOWMI_ERR_QUANT: return "invalid quantization parameters";
+    case GLOWMI_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+const char* glowmi_last_error(void) { return g_error; }
+const char* glowmi_last_variant(void) { return g_variant; }
+
+}  // extern "C"

@@ -1,0 +1,53 @@
+// Internal interface between the host-side C ABI (api.hip) and the kernel translation units.
+// One problem description serves Convolution and FullyConnected: both are the contraction
+//   Y[m][n] = sum_kg A[m][kg] * B[n][kg]
+// with m = (image, oh, ow), n = output channel, kg = (r, s, c).  A is never materialised: the
+// kernel gathers it from the NHWC input (no im2col buffer, the cost the paper's evaluation section
+// attributes to im2col+GEMM).  FullyConnected is the same problem with h = w = r = s = 1 and the
+// weight matrix stored [K][N] (b_is_kn).
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+namespace glowmi {
+
+struct Problem {
+  const void* x;      // input  [n][h][w][c]            (float or int8)
+  const void* w;      // filter [k][r][s][cg]  or FC weight [Kgemm][k] when b_is_kn
+  const void* bias;   // [k] float or int32, may be null
+  void* y;            // output [M][k]
+  void* partial;      // split-K partial sums [split_k][M][k] (float or int32), null when split_k == 1
+  int32_t n, h, w_, c;
+  int32_t k, r, s;
+  int32_t oh, ow;
+  int32_t stride_h, stride_w, pad_t, pad_l;
+  int32_t groups, cg, kg;   // channels per group: input (cg) and output (kg)
+  int32_t M;                // n * oh * ow
+  int32_t Kgemm;            // r * s * cg
+  int32_t split_k;          // >= 1
+  int32_t slabs_per_split;  // reduction slabs each split walks
+  int32_t act;              // 0 none, 1 relu
+  int32_t b_is_kn;          // FC weight layout
+  // quantized form only
+  int32_t x_off, w_off, y_off;
+  int32_t mant, shift;      // requantize multiplier
+  int32_t lo;               // lower clamp bound
+};
+
+// Each launcher validates nothing (the ABI layer did), picks the tile variant, launches on `stream`
+// and reports the variant name.  Returns the hipError_t of the launch.
+hipError_t launch_f32(const Problem& p, hipStream_t stream, const char** variant);
+hipError_t launch_i8(const Problem& p, hipStream_t stream, const char** variant);
+
+// Split-K planning shared by the ABI layer (workspace sizing) and the launchers.
+struct Plan {
+  int bm, bn, bk;
+  int tiles_m, tiles_n;
+  int slabs;            // ceil(Kgemm / bk)
+  int split_k;
+  int slabs_per_split;
+};
+Plan plan_f32(const Problem& p, bool allow_split);
+Plan plan_i8(const Problem& p, bool allow_split);
+
+}  // namespace glowmi

@@ -1,0 +1,430 @@
+// fp32 implicit-GEMM Convolution / FullyConnected for gfx950 (MI355X).
+//
+// The contraction the paper's lowering phase reduces these layers to (Section 3.4: MatMul followed
+// by a broadcasted add; Section 3.1: the convolution loop nest) runs on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32, fp32 accumulate).  The element-wise chain that follows -- bias add and
+// Relu -- is applied to the accumulators in registers before the only store of the output, which
+// is the paper's operator stacking (Section 5.2) in its GPU form.
+//
+// Work decomposition (one workgroup = 256 threads = 4 wavefronts of 64):
+//   - the output matrix [M = n*oh*ow][k] is cut into BM x BN tiles, one per workgroup; workgroup
+//     ids are remapped so that each of the 8 XCDs (own L2 each) walks a contiguous range of tiles
+//     and re-reads of neighbouring input rows hit its L2;
+//   - the reduction axis kg = (r, s, c) is walked in slabs of BK = 32; for each slab the input patch
+//     tile (gathered on the fly from NHWC, 16-byte loads along c) and the filter tile are staged in
+//     LDS, double buffered, with the next slab's global loads in flight during the MFMAs;
+//   - each wavefront owns a (BM/WAVES_M) x (BN/WAVES_N) sub-tile made of 32x32 MFMA blocks and
+//     feeds them with ds_read_b128 from K-contiguous, padded (bank-conflict-free) LDS rows.
+#include <hip/hip_runtime.h>
+
+#include "igemm.h"
+
+namespace glowmi {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int BK = 32;            // reduction slab
+constexpr int LDK = BK + 4;       // K-contiguous LDS row, padded: 36 floats keeps ds_read_b128 conflict free
+constexpr int NTHREADS = 256;
+constexpr int KV = BK / 4;        // float4 chunks per K-contiguous row
+constexpr int ROWS_PER_PASS = NTHREADS / KV;   // 32
+constexpr int INVALID_ROW = -(1 << 24);
+constexpr int FLUSH_SLABS = 16;   // MFMA accumulators are folded into a second set every 512 k
+
+template <int BN>
+struct BkN {                      // FC weight tile [BK][BN] with N contiguous
+  static constexpr int LD = BN + 8;             // +8 puts k and k+4 rows on disjoint bank halves
+  static constexpr int NV = BN / 4;             // float4 chunks per row
+  static constexpr int ROWS = NTHREADS / NV;    // k-rows per pass
+  static constexpr int PASSES = BK / ROWS;
+};
+
+template <int BM, int BN, bool B_KN>
+constexpr int lds_floats() {
+  return 2 * (BM * LDK + (B_KN ? BK * BkN<BN>::LD : BN * LDK));
+}
+
+// Decomposition of a reduction index kg into filter row r, filter column s and channel c.
+struct Tap {
+  int r, s, c;
+  __device__ void init(int kg, int cg, int S) {
+    c = kg % cg;
+    int t = kg / cg;
+    s = t % S;
+    r = t / S;
+  }
+  __device__ void advance(int step, int cg, int S) {
+    c += step;
+    while (c >= cg) {
+      c -= cg;
+      if (++s == S) { s = 0; ++r; }
+    }
+  }
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
+__global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, int tiles_m, int tiles_n,
+                                                             int total_tiles) {
+  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;   // wavefront tile
+  constexpr int TM = WTM / 32, TN = WTN / 32;             // 32x32 MFMA blocks per wavefront
+  static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
+  constexpr int A_PASSES = BM / ROWS_PER_PASS;
+  constexpr int B_PASSES = B_KN ? BkN<BN>::PASSES : BN / ROWS_PER_PASS;
+  constexpr int A_ELEMS = BM * LDK;
+  constexpr int B_ELEMS = B_KN ? BK * BkN<BN>::LD : BN * LDK;
+
+  extern __shared__ __align__(16) float lds[];
+
+  // ---- workgroup -> tile, XCD aware: hardware deals consecutive workgroup ids round-robin over
+  // the 8 XCDs, so id % 8 names the XCD; give each XCD a contiguous run of logical tiles.
+  const int per_xcd = gridDim.x >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= total_tiles) return;
+  const int tn = logical % tiles_n;
+  const int tmg = logical / tiles_n;
+  const int tm = tmg % tiles_m;
+  const int g = tmg / tiles_m;
+  const int split = blockIdx.y;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  const float* __restrict__ X = static_cast<const float*>(p.x);
+  const float* __restrict__ Wt = static_cast<const float*>(p.w);
+
+  // ---- per-thread description of the A (input patch) rows it stages
+  const int kvec = tid % KV;        // which float4 of the slab
+  const int row0 = tid / KV;        // first tile row handled
+  int a_base[A_PASSES], a_ih0[A_PASSES], a_iw0[A_PASSES];
+  {
+    const int ohow = p.oh * p.ow;
+#pragma unroll
+    for (int q = 0; q < A_PASSES; ++q) {
+      const int m = tm * BM + row0 + q * ROWS_PER_PASS;
+      if (m < p.M) {
+        const int img = m / ohow;
+        const int rem = m - img * ohow;
+        const int oh = rem / p.ow;
+        const int ow = rem - oh * p.ow;
+        a_ih0[q] = oh * p.stride_h - p.pad_t;
+        a_iw0[q] = ow * p.stride_w - p.pad_l;
+        a_base[q] = ((img * p.h + a_ih0[q]) * p.w_ + a_iw0[q]) * p.c + g * p.cg;
+      } else {
+        a_ih0[q] = INVALID_ROW;
+        a_iw0[q] = INVALID_ROW;
+        a_base[q] = 0;
+      }
+    }
+  }
+
+  const int slab_begin = split * p.slabs_per_split;
+  const int total_slabs = (p.Kgemm + BK - 1) / BK;
+  int slab_end = slab_begin + p.slabs_per_split;
+  if (slab_end > total_slabs) slab_end = total_slabs;
+
+  Tap tap;
+  tap.init(slab_begin * BK + kvec * 4, p.cg, p.s);
+
+  v4f ra[A_PASSES], rb[B_PASSES];
+
+  auto load_global = [&](int slab) {
+    const int kg0 = slab * BK + kvec * 4;
+    // ---------------- A: gather from NHWC
+    if (VEC) {
+      const bool kok = kg0 < p.Kgemm;                       // Kgemm % 4 == 0 on this path
+      const int tap_off = (tap.r * p.w_ + tap.s) * p.c + tap.c;
+#pragma unroll
+      for (int q = 0; q < A_PASSES; ++q) {
+        const int ih = a_ih0[q] + tap.r, iw = a_iw0[q] + tap.s;
+        const bool ok = kok && (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
+        ra[q] = ok ? *reinterpret_cast<const v4f*>(X + a_base[q] + tap_off) : v4f{0.f, 0.f, 0.f, 0.f};
+      }
+    } else {
+      Tap t = tap;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const bool kok = kg0 + e < p.Kgemm;
+        const int tap_off = (t.r * p.w_ + t.s) * p.c + t.c;
+#pragma unroll
+        for (int q = 0; q < A_PASSES; ++q) {
+          const int ih = a_ih0[q] + t.r, iw = a_iw0[q] + t.s;
+          const bool ok = kok && (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
+          ra[q][e] = ok ? X[a_base[q] + tap_off] : 0.f;
+        }
+        t.advance(1, p.cg, p.s);
+      }
+    }
+    // ---------------- B: filter rows (K contiguous) or FC weight rows (N contiguous)
+    if (!B_KN) {
+#pragma unroll
+      for (int q = 0; q < B_PASSES; ++q) {
+        const int n = tn * BN + row0 + q * ROWS_PER_PASS;
+        const bool nok = n < p.kg;
+        const float* src = Wt + (size_t)(g * p.kg + n) * p.Kgemm + kg0;
+        if (VEC) {
+          rb[q] = (nok && kg0 < p.Kgemm) ? *reinterpret_cast<const v4f*>(src) : v4f{0.f, 0.f, 0.f, 0.f};
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) rb[q][e] = (nok && kg0 + e < p.Kgemm) ? src[e] : 0.f;
+        }
+      }
+    } else {
+      constexpr int NV = BkN<BN>::NV, ROWS = BkN<BN>::ROWS;
+      const int nv = tid % NV, kr0 = tid / NV;
+      const int col = tn * BN + nv * 4;
+#pragma unroll
+      for (int q = 0; q < B_PASSES; ++q) {
+        const int kgr = slab * BK + kr0 + q * ROWS;
+        const bool kok = kgr < p.Kgemm;
+        const float* src = Wt + (size_t)kgr * p.k + col;
+        if (VEC) {
+          rb[q] = (kok && col < p.k) ? *reinterpret_cast<const v4f*>(src) : v4f{0.f, 0.f, 0.f, 0.f};
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) rb[q][e] = (kok && col + e < p.k) ? src[e] : 0.f;
+        }
+      }
+    }
+  };
+
+  auto store_lds = [&](int buf) {
+    float* As = lds + buf * (A_ELEMS + B_ELEMS);
+    float* Bs = As + A_ELEMS;
+#pragma unroll
+    for (int q = 0; q < A_PASSES; ++q)
+      *reinterpret_cast<v4f*>(As + (row0 + q * ROWS_PER_PASS) * LDK + kvec * 4) = ra[q];
+    if (!B_KN) {
+#pragma unroll
+      for (int q = 0; q < B_PASSES; ++q)
+        *reinterpret_cast<v4f*>(Bs + (row0 + q * ROWS_PER_PASS) * LDK + kvec * 4) = rb[q];
+    } else {
+      constexpr int NV = BkN<BN>::NV, ROWS = BkN<BN>::ROWS, LD = BkN<BN>::LD;
+      const int nv = tid % NV, kr0 = tid / NV;
+#pragma unroll
+      for (int q = 0; q < B_PASSES; ++q)
+        *reinterpret_cast<v4f*>(Bs + (kr0 + q * ROWS) * LD + nv * 4) = rb[q];
+    }
+  };
+
+  // Two accumulator sets: the MFMAs add into `acc`; every FLUSH_SLABS slabs it is folded into
+  // `total`.  Long reductions (FC with K in the tens of thousands) then round like a sum of short
+  // chains, which keeps the fp32 result well inside 1e-5 of the exact sum.
+  v16f acc[TM][TN], total[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) { acc[i][j][e] = 0.f; total[i][j][e] = 0.f; }
+  auto flush = [&]() {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        total[i][j] += acc[i][j];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      }
+  };
+
+  const int lrow = lane & 31;       // row (A) / column (B) inside a 32x32 MFMA block
+  const int lhalf = lane >> 5;      // which half of the 8-deep K group this lane feeds
+
+  auto compute = [&](int buf) {
+    const float* As = lds + buf * (A_ELEMS + B_ELEMS);
+    const float* Bs = As + A_ELEMS;
+#pragma unroll
+    for (int k8 = 0; k8 < BK / 8; ++k8) {
+      // A lane holds 4 consecutive k of its row; MFMA step kk consumes element kk of both operands,
+      // i.e. the pair k = {k8*8 + kk, k8*8 + 4 + kk}: any pairing works as long as A and B agree.
+      v4f a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        a[i] = *reinterpret_cast<const v4f*>(As + (wm * WTM + i * 32 + lrow) * LDK + k8 * 8 + lhalf * 4);
+      if (!B_KN) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          b[j] = *reinterpret_cast<const v4f*>(Bs + (wn * WTN + j * 32 + lrow) * LDK + k8 * 8 + lhalf * 4);
+      } else {
+        constexpr int LD = BkN<BN>::LD;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk)
+            b[j][kk] = Bs[(k8 * 8 + lhalf * 4 + kk) * LD + wn * WTN + j * 32 + lrow];
+      }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][kk], b[j][kk], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  // ---- main loop: global loads of slab i+1 in flight while slab i is multiplied
+  if (slab_begin < slab_end) {
+    load_global(slab_begin);
+    store_lds(0);
+    __syncthreads();
+    for (int slab = slab_begin; slab < slab_end; ++slab) {
+      const int buf = (slab - slab_begin) & 1;
+      const bool more = slab + 1 < slab_end;
+      if (more) {
+        tap.advance(BK, p.cg, p.s);
+        load_global(slab + 1);
+      }
+      compute(buf);
+      if (more) store_lds(buf ^ 1);
+      if (((slab - slab_begin) % FLUSH_SLABS) == FLUSH_SLABS - 1) flush();
+      __syncthreads();
+    }
+  }
+  flush();
+
+  // ---- epilogue: bias + activation on the accumulators, one store.
+  // 32x32 MFMA block: register e of a lane is row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
+  float* __restrict__ Y = static_cast<float*>(p.y);
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = tn * BN + wn * WTN + j * 32 + lrow;
+    if (col >= p.kg) continue;
+    const int ch = g * p.kg + col;
+    const float bv = (p.split_k == 1 && bias) ? bias[ch] : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = tm * BM + wm * WTM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+        if (row >= p.M) continue;
+        float v = total[i][j][e];
+        if (p.split_k == 1) {
+          v += bv;
+          if (p.act == 1) v = fmaxf(v, 0.f);
+          Y[(size_t)row * p.k + ch] = v;
+        } else {
+          static_cast<float*>(p.partial)[((size_t)split * p.M + row) * p.k + ch] = v;
+        }
+      }
+    }
+  }
+}
+
+// Finish of a split reduction: sum the partial tiles in split order (deterministic), then the same
+// fused bias + activation, one store.
+__global__ __launch_bounds__(256) void splitk_finish_f32(const float* __restrict__ partial,
+                                                         const float* __restrict__ bias,
+                                                         float* __restrict__ y, int total, int k,
+                                                         int split_k, int act) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    float v = 0.f;
+    for (int s = 0; s < split_k; ++s) v += partial[(size_t)s * total + i];
+    if (bias) v += bias[i % k];
+    if (act == 1) v = fmaxf(v, 0.f);
+    y[i] = v;
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
+hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
+  auto kern = igemm_f32_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN>;
+  constexpr int lds_bytes = lds_floats<BM, BN, B_KN>() * (int)sizeof(float);
+  static bool attr_set = false;   // per instantiation; benign if two threads race to set it
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int total_tiles = plan.tiles_m * plan.tiles_n * p.groups;
+  const int grid_x = ((total_tiles + 7) / 8) * 8;
+  dim3 grid(grid_x, plan.split_k, 1), block(NTHREADS, 1, 1);
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, p, plan.tiles_m, plan.tiles_n, total_tiles);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+Plan plan_f32(const Problem& p, bool allow_split) {
+  Plan pl;
+  pl.bk = BK;
+  pl.slabs = (p.Kgemm + BK - 1) / BK;
+  // Tile choice: narrow N tile when there are few output channels per group, short M tile when
+  // the layer has too few rows to give every compute unit a workgroup otherwise.
+  pl.bn = (p.kg > 64) ? 128 : 64;
+  pl.bm = 128;
+  auto tiles = [&](int bm, int bn) {
+    return (long long)((p.M + bm - 1) / bm) * ((p.kg + bn - 1) / bn) * p.groups;
+  };
+  if (p.M <= 32 && pl.bn == 128) {
+    pl.bm = 32;
+  } else if (tiles(pl.bm, pl.bn) < 512) {
+    pl.bm = 64;
+    pl.bn = 64;
+  }
+  pl.tiles_m = (p.M + pl.bm - 1) / pl.bm;
+  pl.tiles_n = (p.kg + pl.bn - 1) / pl.bn;
+  pl.split_k = 1;
+  pl.slabs_per_split = pl.slabs;
+  const long long t = (long long)pl.tiles_m * pl.tiles_n * p.groups;
+  if (allow_split && t < 256 && pl.slabs >= 8) {
+    int want = (int)((768 + t - 1) / t);            // aim at ~3 workgroups per compute unit
+    int max_split = pl.slabs / 4;                   // at least 4 slabs per split
+    int sk = want < max_split ? want : max_split;
+    if (sk > 64) sk = 64;
+    if (sk > 1) {
+      pl.slabs_per_split = (pl.slabs + sk - 1) / sk;
+      pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
+    }
+  }
+  return pl;
+}
+
+hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
+  Problem p = p_in;
+  const Plan plan = plan_f32(p, p.partial != nullptr);
+  p.split_k = plan.split_k;
+  p.slabs_per_split = plan.slabs_per_split;
+  // 16-byte gathers need channel runs that are multiples of 4 floats
+  const bool fc = p.b_is_kn != 0;
+  const bool vec = fc ? (p.Kgemm % 4 == 0 && p.k % 4 == 0) : (p.cg % 4 == 0 && p.c % 4 == 0);
+  hipError_t e;
+#define GLOWMI_CASE(BM_, BN_, WM_, WN_, NAME)                                                        \
+  if (plan.bm == BM_ && plan.bn == BN_) {                                                            \
+    if (fc) {                                                                                        \
+      e = vec ? launch_variant<BM_, BN_, WM_, WN_, true, true>(p, plan, stream)                      \
+              : launch_variant<BM_, BN_, WM_, WN_, false, true>(p, plan, stream);                    \
+      *variant = vec ? "igemm_f32_" NAME "_fc_vec" : "igemm_f32_" NAME "_fc_scalar";                 \
+    } else {                                                                                         \
+      e = vec ? launch_variant<BM_, BN_, WM_, WN_, true, false>(p, plan, stream)                     \
+              : launch_variant<BM_, BN_, WM_, WN_, false, false>(p, plan, stream);                   \
+      *variant = vec ? "igemm_f32_" NAME "_conv_vec" : "igemm_f32_" NAME "_conv_scalar";             \
+    }                                                                                                \
+  } else
+  GLOWMI_CASE(128, 128, 2, 2, "128x128")
+  GLOWMI_CASE(128, 64, 2, 2, "128x64")
+  GLOWMI_CASE(64, 64, 2, 2, "64x64")
+  GLOWMI_CASE(32, 128, 1, 4, "32x128")
+  { return hipErrorInvalidValue; }
+#undef GLOWMI_CASE
+  if (e != hipSuccess) return e;
+  if (plan.split_k > 1) {
+    const int total = p.M * p.k;
+    int blocks = (total + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(splitk_finish_f32, dim3(blocks), dim3(256), 0, stream,
+                       static_cast<const float*>(p.partial), static_cast<const float*>(p.bias),
+                       static_cast<float*>(p.y), total, p.k, plan.split_k, p.act);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace glowmi

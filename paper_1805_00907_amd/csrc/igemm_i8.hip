@@ -1,0 +1,455 @@
+// int8 implicit-GEMM Convolution / FullyConnected for gfx950 (MI355X), the quantized form of
+// Section 4 of the paper: int8 codes with per-tensor scale/offset (Section 4.1), int32 accumulation,
+// and the rescale to the output range folded into the producing operation (Section 4.3), with Relu
+// as a plain integer max against the output offset (same-scale max, Section 4.3).
+//
+// The matrix cores multiply raw codes (v_mfma_i32_32x32x32_i8).  Offsets are taken out afterwards:
+//   sum (x - xo)(w - wo) = sum x*w - xo * sum_k w - wo * sum_k x + Kcount * xo * wo
+// where padded taps are staged as the code xo (real value 0), so they cancel exactly.  The row sums
+// are collected with dot-product instructions while the tiles are staged.  Everything after the
+// accumulator is integer arithmetic, so results are reproducible bit for bit.
+//
+// Tiling mirrors the fp32 kernel: BM x BN output tile per 256-thread workgroup, reduction slabs of
+// 64 codes staged in double-buffered LDS as K-contiguous rows of 64 + 16 pad bytes (conflict-free
+// ds_read_b128), XCD-aware workgroup order.
+#include <hip/hip_runtime.h>
+
+#include "igemm.h"
+
+namespace glowmi {
+namespace {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int BKQ = 64;                  // codes per reduction slab
+constexpr int LDQ = BKQ + 16;            // LDS row pitch in bytes
+constexpr int NTHREADS = 256;
+constexpr int KV = BKQ / 16;             // 16-byte chunks per K-contiguous row
+constexpr int ROWS_PER_PASS = NTHREADS / KV;   // 64
+constexpr int INVALID_ROW = -(1 << 24);
+
+struct Tap {
+  int r, s, c;
+  __device__ void init(int kg, int cg, int S) {
+    c = kg % cg;
+    int t = kg / cg;
+    s = t % S;
+    r = t / S;
+  }
+  __device__ void advance(int step, int cg, int S) {
+    c += step;
+    while (c >= cg) {
+      c -= cg;
+      if (++s == S) { s = 0; ++r; }
+    }
+  }
+};
+
+__device__ __forceinline__ int sum_bytes(int packed) {   // sum of the four signed bytes
+  return __builtin_amdgcn_sdot4(packed, 0x01010101, 0, false);
+}
+
+__device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_off, int lo) {
+  long long t = (long long)acc * (long long)mant + (1LL << (shift - 1));
+  long long q = (t >> shift) + y_off;     // arithmetic shift: floor, so ties round up
+  q = q < lo ? lo : q;
+  q = q > 127 ? 127 : q;
+  return (int)q;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
+__global__ __launch_bounds__(NTHREADS) void igemm_i8_kernel(const Problem p, int tiles_m, int tiles_n,
+                                                            int total_tiles) {
+  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  static_assert(TM >= 1 && TN >= 1 && BM % 64 == 0 && BN % 64 == 0, "tile shape");
+  constexpr int A_PASSES = BM / ROWS_PER_PASS;
+  constexpr int B_PASSES = BN / ROWS_PER_PASS;          // K-contiguous filter rows
+  constexpr int B_UNITS = (BKQ / 4) * (BN / 4);         // FC weight: 4k x 4n byte blocks per slab
+  constexpr int B_UPT = B_UNITS / NTHREADS;             // blocks per thread
+  constexpr int A_BYTES = BM * LDQ, B_BYTES = BN * LDQ;
+
+  extern __shared__ __align__(16) unsigned char ldsq[];
+
+  const int per_xcd = gridDim.x >> 3;
+  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (logical >= total_tiles) return;
+  const int tn = logical % tiles_n;
+  const int tmg = logical / tiles_n;
+  const int tm = tmg % tiles_m;
+  const int g = tmg / tiles_m;
+  const int split = blockIdx.y;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = tid >> 6;
+  const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+
+  const signed char* __restrict__ X = static_cast<const signed char*>(p.x);
+  const signed char* __restrict__ Wt = static_cast<const signed char*>(p.w);
+
+  const int kvec = tid % KV;
+  const int row0 = tid / KV;
+  int a_base[A_PASSES], a_ih0[A_PASSES], a_iw0[A_PASSES];
+  {
+    const int ohow = p.oh * p.ow;
+#pragma unroll
+    for (int q = 0; q < A_PASSES; ++q) {
+      const int m = tm * BM + row0 + q * ROWS_PER_PASS;
+      if (m < p.M) {
+        const int img = m / ohow;
+        const int rem = m - img * ohow;
+        const int oh = rem / p.ow;
+        const int ow = rem - oh * p.ow;
+        a_ih0[q] = oh * p.stride_h - p.pad_t;
+        a_iw0[q] = ow * p.stride_w - p.pad_l;
+        a_base[q] = ((img * p.h + a_ih0[q]) * p.w_ + a_iw0[q]) * p.c + g * p.cg;
+      } else {
+        a_ih0[q] = INVALID_ROW;
+        a_iw0[q] = INVALID_ROW;
+        a_base[q] = 0;
+      }
+    }
+  }
+
+  const int slab_begin = split * p.slabs_per_split;
+  const int total_slabs = (p.Kgemm + BKQ - 1) / BKQ;
+  int slab_end = slab_begin + p.slabs_per_split;
+  if (slab_end > total_slabs) slab_end = total_slabs;
+  int k_hi = slab_end * BKQ;
+  if (k_hi > p.Kgemm) k_hi = p.Kgemm;
+  const int k_count = k_hi - slab_begin * BKQ;          // codes this split really reduces over
+
+  Tap tap;
+  tap.init(slab_begin * BKQ + kvec * 16, p.cg, p.s);
+
+  const int xo_byte = p.x_off & 0xff;
+  const int xo_fill = xo_byte * 0x01010101;             // padding = the code of real zero
+  const bool need_xsum = p.w_off != 0;
+
+  v4i ra[A_PASSES];
+  v4i rb[B_KN ? B_UPT : B_PASSES];
+  int asum[A_PASSES];                                   // running sum of staged input codes per row
+  int bsum[B_KN ? B_UPT * 4 : B_PASSES];                // running sum of staged filter codes
+#pragma unroll
+  for (int q = 0; q < A_PASSES; ++q) asum[q] = 0;
+#pragma unroll
+  for (int q = 0; q < (B_KN ? B_UPT * 4 : B_PASSES); ++q) bsum[q] = 0;
+
+  auto load_global = [&](int slab) {
+    const int kg0 = slab * BKQ + kvec * 16;
+    if (VEC) {
+      const bool kok = kg0 < p.Kgemm;                   // Kgemm % 16 == 0 on this path
+      const int tap_off = (tap.r * p.w_ + tap.s) * p.c + tap.c;
+#pragma unroll
+      for (int q = 0; q < A_PASSES; ++q) {
+        const int ih = a_ih0[q] + tap.r, iw = a_iw0[q] + tap.s;
+        const bool inside = (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
+        if (!kok) ra[q] = v4i{0, 0, 0, 0};
+        else if (inside) ra[q] = *reinterpret_cast<const v4i*>(X + a_base[q] + tap_off);
+        else ra[q] = v4i{xo_fill, xo_fill, xo_fill, xo_fill};
+      }
+    } else {
+      Tap t = tap;
+#pragma unroll
+      for (int q = 0; q < A_PASSES; ++q) ra[q] = v4i{0, 0, 0, 0};
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const bool kok = kg0 + e < p.Kgemm;
+        const int tap_off = (t.r * p.w_ + t.s) * p.c + t.c;
+#pragma unroll
+        for (int q = 0; q < A_PASSES; ++q) {
+          const int ih = a_ih0[q] + t.r, iw = a_iw0[q] + t.s;
+          const bool inside = (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
+          int v = 0;
+          if (kok) v = inside ? ((int)X[a_base[q] + tap_off] & 0xff) : xo_byte;
+          ra[q][e >> 2] |= v << ((e & 3) * 8);
+        }
+        t.advance(1, p.cg, p.s);
+      }
+    }
+    if (!B_KN) {
+#pragma unroll
+      for (int q = 0; q < B_PASSES; ++q) {
+        const int n = tn * BN + row0 + q * ROWS_PER_PASS;
+        const bool nok = n < p.kg;
+        const signed char* src = Wt + (size_t)(g * p.kg + n) * p.Kgemm + kg0;
+        if (VEC) {
+          rb[q] = (nok && kg0 < p.Kgemm) ? *reinterpret_cast<const v4i*>(src) : v4i{0, 0, 0, 0};
+        } else {
+          rb[q] = v4i{0, 0, 0, 0};
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int v = (nok && kg0 + e < p.Kgemm) ? ((int)src[e] & 0xff) : 0;
+            rb[q][e >> 2] |= v << ((e & 3) * 8);
+          }
+        }
+      }
+    } else {
+      // FC weight [Kgemm][k], N contiguous: each thread takes 4 k-rows x 4 columns and transposes
+      // the 4x4 byte block so that every column becomes one dword of 4 consecutive k.
+#pragma unroll
+      for (int q = 0; q < B_UPT; ++q) {
+        const int u = tid + q * NTHREADS;
+        const int ng = u % (BN / 4), kgp = u / (BN / 4);
+        const int col = tn * BN + ng * 4;
+        int d[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const int kgr = slab * BKQ + kgp * 4 + kk;
+          const signed char* src = Wt + (size_t)kgr * p.k + col;
+          if (kgr >= p.Kgemm) d[kk] = 0;
+          else if (VEC) d[kk] = col < p.k ? *reinterpret_cast<const int*>(src) : 0;
+          else {
+            d[kk] = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (col + e < p.k) d[kk] |= ((int)src[e] & 0xff) << (e * 8);
+          }
+        }
+#pragma unroll
+        for (int nn = 0; nn < 4; ++nn) {
+          int o = 0;
+#pragma unroll
+          for (int kk = 0; kk < 4; ++kk) o |= ((d[kk] >> (nn * 8)) & 0xff) << (kk * 8);
+          rb[q][nn] = o;
+        }
+      }
+    }
+  };
+
+  auto store_lds = [&](int buf) {
+    unsigned char* As = ldsq + buf * (A_BYTES + B_BYTES);
+    unsigned char* Bs = As + A_BYTES;
+#pragma unroll
+    for (int q = 0; q < A_PASSES; ++q) {
+      *reinterpret_cast<v4i*>(As + (row0 + q * ROWS_PER_PASS) * LDQ + kvec * 16) = ra[q];
+      if (need_xsum)
+        asum[q] += sum_bytes(ra[q][0]) + sum_bytes(ra[q][1]) + sum_bytes(ra[q][2]) + sum_bytes(ra[q][3]);
+    }
+    if (!B_KN) {
+#pragma unroll
+      for (int q = 0; q < B_PASSES; ++q) {
+        *reinterpret_cast<v4i*>(Bs + (row0 + q * ROWS_PER_PASS) * LDQ + kvec * 16) = rb[q];
+        bsum[q] += sum_bytes(rb[q][0]) + sum_bytes(rb[q][1]) + sum_bytes(rb[q][2]) + sum_bytes(rb[q][3]);
+      }
+    } else {
+#pragma unroll
+      for (int q = 0; q < B_UPT; ++q) {
+        const int u = tid + q * NTHREADS;
+        const int ng = u % (BN / 4), kgp = u / (BN / 4);
+#pragma unroll
+        for (int nn = 0; nn < 4; ++nn) {
+          *reinterpret_cast<int*>(Bs + (ng * 4 + nn) * LDQ + kgp * 4) = rb[q][nn];
+          bsum[q * 4 + nn] += sum_bytes(rb[q][nn]);
+        }
+      }
+    }
+  };
+
+  v16i acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+  const int lrow = lane & 31;
+  const int lhalf = lane >> 5;
+
+  auto compute = [&](int buf) {
+    const unsigned char* As = ldsq + buf * (A_BYTES + B_BYTES);
+    const unsigned char* Bs = As + A_BYTES;
+#pragma unroll
+    for (int k32 = 0; k32 < BKQ / 32; ++k32) {
+      // each lane feeds 16 consecutive codes of its row; lanes 32..63 take the upper 16 of the 32
+      v4i a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        a[i] = *reinterpret_cast<const v4i*>(As + (wm * WTM + i * 32 + lrow) * LDQ + k32 * 32 + lhalf * 16);
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        b[j] = *reinterpret_cast<const v4i*>(Bs + (wn * WTN + j * 32 + lrow) * LDQ + k32 * 32 + lhalf * 16);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  if (slab_begin < slab_end) {
+    load_global(slab_begin);
+    store_lds(0);
+    __syncthreads();
+    for (int slab = slab_begin; slab < slab_end; ++slab) {
+      const int buf = (slab - slab_begin) & 1;
+      const bool more = slab + 1 < slab_end;
+      if (more) {
+        tap.advance(BKQ, p.cg, p.s);
+        load_global(slab + 1);
+      }
+      compute(buf);
+      if (more) store_lds(buf ^ 1);
+      __syncthreads();
+    }
+  }
+
+  // ---- per-row / per-column code sums into LDS (the staging buffers are free now)
+  int* xsum = reinterpret_cast<int*>(ldsq);            // [BM]
+  int* wsum = xsum + BM;                               // [BN]
+  for (int i = tid; i < BM + BN; i += NTHREADS) xsum[i] = 0;
+  __syncthreads();
+  if (need_xsum) {
+#pragma unroll
+    for (int q = 0; q < A_PASSES; ++q) atomicAdd(&xsum[row0 + q * ROWS_PER_PASS], asum[q]);
+  }
+  if (!B_KN) {
+#pragma unroll
+    for (int q = 0; q < B_PASSES; ++q) atomicAdd(&wsum[row0 + q * ROWS_PER_PASS], bsum[q]);
+  } else {
+#pragma unroll
+    for (int q = 0; q < B_UPT; ++q) {
+      const int u = tid + q * NTHREADS;
+      const int ng = u % (BN / 4);
+#pragma unroll
+      for (int nn = 0; nn < 4; ++nn) atomicAdd(&wsum[ng * 4 + nn], bsum[q * 4 + nn]);
+    }
+  }
+  __syncthreads();
+
+  // ---- epilogue: offsets out, bias, requantize, clamp (Relu = lower bound), one store
+  signed char* __restrict__ Y = static_cast<signed char*>(p.y);
+  const int* __restrict__ bias = static_cast<const int*>(p.bias);
+  // The correction terms are combined modulo 2^32 (unsigned): each may exceed the final value, the
+  // true accumulator fits int32 by contract, so the wrapped sum is exact.
+  const unsigned kxw = (unsigned)k_count * (unsigned)(p.x_off * p.w_off);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int lcol = wn * WTN + j * 32 + lrow;
+    const int col = tn * BN + lcol;
+    if (col >= p.kg) continue;
+    const int ch = g * p.kg + col;
+    unsigned colterm = kxw - (unsigned)p.x_off * (unsigned)wsum[lcol];
+    if (p.split_k == 1 && bias) colterm += (unsigned)bias[ch];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int lr = wm * WTM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+        const int row = tm * BM + lr;
+        if (row >= p.M) continue;
+        unsigned u = (unsigned)acc[i][j][e] + colterm;
+        if (need_xsum) u -= (unsigned)p.w_off * (unsigned)xsum[lr];
+        const int v = (int)u;
+        if (p.split_k == 1) {
+          Y[(size_t)row * p.k + ch] = (signed char)requantize(v, p.mant, p.shift, p.y_off, p.lo);
+        } else {
+          static_cast<int*>(p.partial)[((size_t)split * p.M + row) * p.k + ch] = v;
+        }
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void splitk_finish_i8(const int* __restrict__ partial,
+                                                        const int* __restrict__ bias,
+                                                        signed char* __restrict__ y, int total, int k,
+                                                        int split_k, int mant, int shift, int y_off,
+                                                        int lo) {
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    unsigned v = 0;
+    for (int s = 0; s < split_k; ++s) v += (unsigned)partial[(size_t)s * total + i];
+    if (bias) v += (unsigned)bias[i % k];
+    y[i] = (signed char)requantize((int)v, mant, shift, y_off, lo);
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
+hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
+  auto kern = igemm_i8_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN>;
+  constexpr int lds_bytes = 2 * (BM + BN) * LDQ;
+  static_assert(lds_bytes >= (BM + BN) * 4, "row sums reuse the staging buffers");
+  const int total_tiles = plan.tiles_m * plan.tiles_n * p.groups;
+  const int grid_x = ((total_tiles + 7) / 8) * 8;
+  dim3 grid(grid_x, plan.split_k, 1), block(NTHREADS, 1, 1);
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, p, plan.tiles_m, plan.tiles_n, total_tiles);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+Plan plan_i8(const Problem& p, bool allow_split) {
+  Plan pl;
+  pl.bk = BKQ;
+  pl.slabs = (p.Kgemm + BKQ - 1) / BKQ;
+  pl.bn = (p.kg > 64) ? 128 : 64;
+  pl.bm = 128;
+  auto tiles = [&](int bm, int bn) {
+    return (long long)((p.M + bm - 1) / bm) * ((p.kg + bn - 1) / bn) * p.groups;
+  };
+  if (tiles(pl.bm, pl.bn) < 512) {
+    pl.bm = 64;
+    pl.bn = 64;
+  }
+  pl.tiles_m = (p.M + pl.bm - 1) / pl.bm;
+  pl.tiles_n = (p.kg + pl.bn - 1) / pl.bn;
+  pl.split_k = 1;
+  pl.slabs_per_split = pl.slabs;
+  const long long t = (long long)pl.tiles_m * pl.tiles_n * p.groups;
+  if (allow_split && t < 256 && pl.slabs >= 8) {
+    int want = (int)((768 + t - 1) / t);
+    int max_split = pl.slabs / 4;
+    int sk = want < max_split ? want : max_split;
+    if (sk > 64) sk = 64;
+    if (sk > 1) {
+      pl.slabs_per_split = (pl.slabs + sk - 1) / sk;
+      pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
+    }
+  }
+  return pl;
+}
+
+hipError_t launch_i8(const Problem& p_in, hipStream_t stream, const char** variant) {
+  Problem p = p_in;
+  const Plan plan = plan_i8(p, p.partial != nullptr);
+  p.split_k = plan.split_k;
+  p.slabs_per_split = plan.slabs_per_split;
+  const bool fc = p.b_is_kn != 0;
+  const bool vec = fc ? (p.Kgemm % 16 == 0 && p.k % 4 == 0) : (p.cg % 16 == 0 && p.c % 16 == 0);
+  hipError_t e;
+#define GLOWMI_CASE(BM_, BN_, WM_, WN_, NAME)                                                        \
+  if (plan.bm == BM_ && plan.bn == BN_) {                                                            \
+    if (fc) {                                                                                        \
+      e = vec ? launch_variant<BM_, BN_, WM_, WN_, true, true>(p, plan, stream)                      \
+              : launch_variant<BM_, BN_, WM_, WN_, false, true>(p, plan, stream);                    \
+      *variant = vec ? "igemm_i8_" NAME "_fc_vec" : "igemm_i8_" NAME "_fc_scalar";                   \
+    } else {                                                                                         \
+      e = vec ? launch_variant<BM_, BN_, WM_, WN_, true, false>(p, plan, stream)                     \
+              : launch_variant<BM_, BN_, WM_, WN_, false, false>(p, plan, stream);                   \
+      *variant = vec ? "igemm_i8_" NAME "_conv_vec" : "igemm_i8_" NAME "_conv_scalar";               \
+    }                                                                                                \
+  } else
+  GLOWMI_CASE(128, 128, 2, 2, "128x128")
+  GLOWMI_CASE(128, 64, 2, 2, "128x64")
+  GLOWMI_CASE(64, 64, 2, 2, "64x64")
+  { return hipErrorInvalidValue; }
+#undef GLOWMI_CASE
+  if (e != hipSuccess) return e;
+  if (plan.split_k > 1) {
+    const int total = p.M * p.k;
+    int blocks = (total + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(splitk_finish_i8, dim3(blocks), dim3(256), 0, stream,
+                       static_cast<const int*>(p.partial), static_cast<const int*>(p.bias),
+                       static_cast<signed char*>(p.y), total, p.k, plan.split_k, p.mant, p.shift,
+                       p.y_off, p.lo);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace glowmi

@@ -1,0 +1,178 @@
+"""Element-by-element parity of the HIP path (through the C ABI) against the CPU oracle on seeded
+inputs, at sizes the oracle finishes in seconds and that still span several tiles and ragged tails.
+
+fp32: |gpu - oracle| <= 1e-5 + 1e-4 |oracle|.  int8: bit-exact.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_1805_00907_amd import workloads as wl
+
+
+def _gpu():
+    import gpu_util
+    return gpu_util
+
+
+# n  h  w  c  k  r  s  stride  pads(t,l,b,r)  groups
+CONV_SHAPES = [
+    (1, 32, 32, 16, 16, 3, 3, (1, 1), (1, 1, 1, 1), 1),        # config 1
+    (2, 9, 8, 4, 6, 3, 3, (2, 2), (1, 1, 1, 1), 1),            # tiny, vector path with c = 4
+    (1, 8, 11, 2, 3, 5, 3, (2, 1), (2, 0, 1, 2), 1),           # scalar path, asymmetric pads
+    (3, 6, 6, 4, 6, 3, 3, (1, 2), (1, 2, 0, 1), 2),            # groups 2, scalar (cg = 2)
+    (2, 12, 12, 3, 5, 7, 7, (2, 2), (3, 3, 3, 3), 1),          # stem-like 7x7/2 with c = 3
+    (1, 10, 10, 32, 48, 1, 1, (1, 1), (0, 0, 0, 0), 2),        # 1x1 grouped, vector
+    (2, 30, 30, 3, 64, 7, 7, (2, 2), (3, 3, 3, 3), 1),         # stem shape, small map
+    (3, 19, 17, 24, 40, 3, 3, (1, 1), (1, 1, 1, 1), 1),        # ragged M and K tails (Kgemm = 216)
+    (2, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1, 1, 1), 1),        # several M tiles
+    (1, 28, 28, 64, 256, 1, 1, (1, 1), (0, 0, 0, 0), 1),       # 128-wide N tiles
+    (2, 7, 7, 128, 136, 3, 3, (1, 1), (1, 1, 1, 1), 1),        # deep K, ragged N (136), split-K
+    (5, 16, 16, 32, 160, 3, 3, (2, 2), (0, 1, 1, 0), 1),       # stride 2, mixed pads
+    (1, 40, 36, 16, 8, 3, 3, (1, 1), (2, 2, 2, 2), 1),         # pad larger than needed
+    (4, 5, 5, 16, 32, 5, 5, (1, 1), (0, 0, 0, 0), 1),          # filter covers the whole map
+    (2, 6, 6, 64, 64, 3, 3, (1, 1), (1, 1, 1, 1), 16),         # 16 groups of 4 channels
+]
+
+
+def _conv_case(i, dist="uniform"):
+    n, h, w, c, k, r, s, st, pd, g = CONV_SHAPES[i]
+    rng = np.random.default_rng(1000 + i)
+    lim = 1.0 if dist == "uniform" else None
+    x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
+    wt = (rng.uniform(-1, 1, size=(k, r, s, c // g)) / np.sqrt(r * s * c // g)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(k,)).astype(np.float32)
+    return x, wt, b, st, pd, g
+
+
+@pytest.mark.parametrize("i", range(len(CONV_SHAPES)))
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_NONE])
+def test_conv2d_f32(i, act):
+    G = _gpu()
+    x, wt, b, st, pd, g = _conv_case(i)
+    ref = oracle.conv2d_f32(x, wt, b, st, pd, g, act=act)
+    desc = G.make_desc(x.shape, wt.shape, st, pd, g)
+    for use_ws in (True, False):
+        got, variant = G.gpu_conv2d_f32(x, wt, b, desc, act, use_workspace=use_ws)
+        G.assert_close_f32(got, ref, f"conv case {i} act {act} ws {use_ws} [{variant}]")
+
+
+def test_conv2d_f32_no_bias():
+    G = _gpu()
+    x, wt, b, st, pd, g = _conv_case(7)
+    ref = oracle.conv2d_f32(x, wt, None, st, pd, g, act=wl.ACT_RELU)
+    got, _ = G.gpu_conv2d_f32(x, wt, None, G.make_desc(x.shape, wt.shape, st, pd, g), wl.ACT_RELU)
+    G.assert_close_f32(got, ref, "conv without bias")
+
+
+def test_conv2d_f32_config1():
+    G = _gpu()
+    layer = wl.config1_layer()
+    x, wt, b = wl.conv_inputs_f32(layer, wl.layer_seed(0, 0), dist="uniform")
+    ref = oracle.conv2d_f32(x, wt, b, (1, 1), (1, 1, 1, 1), 1, act=wl.ACT_RELU)
+    got, _ = G.gpu_conv2d_f32(x, wt, b, G.desc_of(layer), wl.ACT_RELU)
+    G.assert_close_f32(got, ref, "config 1")
+
+
+@pytest.mark.parametrize("li", range(5))
+def test_conv2d_f32_resnet_batch1(li):
+    G = _gpu()
+    layer = wl.resnet50_layers(1)[li]
+    x, wt, b = wl.conv_inputs_f32(layer, wl.layer_seed(1, li))
+    pd = (layer.pad,) * 4
+    ref = oracle.conv2d_f32(x, wt, b, (layer.stride,) * 2, pd, 1, act=layer.act)
+    for use_ws in (True, False):
+        got, variant = G.gpu_conv2d_f32(x, wt, b, G.desc_of(layer), layer.act, use_workspace=use_ws)
+        G.assert_close_f32(got, ref, f"{layer.name} ws {use_ws} [{variant}]")
+
+
+FC_SHAPES = [(1, 64, 8), (5, 37, 11), (16, 512, 1000), (3, 1000, 257), (64, 2048, 1000), (1, 2048, 1000),
+             (130, 260, 132), (33, 4096, 64), (256, 300, 520)]
+
+
+@pytest.mark.parametrize("shape", FC_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_NONE])
+def test_fc_f32(shape, act):
+    G = _gpu()
+    M, K, N = shape
+    rng = np.random.default_rng(2000 + M + K + N)
+    a = rng.uniform(-1, 1, size=(M, K)).astype(np.float32)
+    w = (rng.uniform(-1, 1, size=(K, N)) / np.sqrt(K)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(N,)).astype(np.float32)
+    ref = oracle.fc_f32(a, w, b, act=act)
+    for use_ws in (True, False):
+        got, variant = G.gpu_fc_f32(a, w, b, act, use_workspace=use_ws)
+        G.assert_close_f32(got, ref, f"fc {shape} act {act} ws {use_ws} [{variant}]")
+
+
+def _qconv_case(i, dist, w_off):
+    n, h, w, c, k, r, s, st, pd, g = CONV_SHAPES[i]
+    layer = wl.ConvLayer(f"case{i}", n, h, w, c, k, r, s, 1, 0, g)
+    return wl.conv_inputs_q(layer, 3000 + i, dist=dist, w_off=w_off), st, pd, g
+
+
+@pytest.mark.parametrize("i", range(len(CONV_SHAPES)))
+@pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", 0), ("normal", -7)])
+def test_qconv2d(i, dist, w_off):
+    G = _gpu()
+    (xq, wq, bq, qp), st, pd, g = _qconv_case(i, dist, w_off)
+    desc = G.make_desc(xq.shape, wq.shape, st, pd, g)
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                             st, pd, g, act=act)
+        for use_ws in (True, False):
+            got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, act, use_workspace=use_ws)
+            G.assert_equal_i8(got, ref, f"qconv case {i} {dist} w_off {w_off} act {act} ws {use_ws} [{variant}]")
+
+
+def test_qconv2d_zero_point_padding():
+    """Input constantly at its offset: every output, borders included, is requantize(bias)."""
+    G = _gpu()
+    rng = np.random.default_rng(5)
+    xq = np.full((2, 9, 9, 16), 11, np.int8)
+    wq = rng.integers(-127, 128, size=(24, 3, 3, 16), dtype=np.int8)
+    bq = rng.integers(-4000, 4000, size=(24,), dtype=np.int32)
+    qp = wl.QParams(0.05, 11, 0.01, 0, 0.02, -5)
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                         (1, 1), (1, 1, 1, 1), 1)
+    assert np.all(ref == ref[0, 0, 0, :])
+    got, _ = G.gpu_qconv2d(xq, wq, bq, qp, G.make_desc(xq.shape, wq.shape, (1, 1), (1, 1, 1, 1), 1), wl.ACT_NONE)
+    G.assert_equal_i8(got, ref, "zero-point padding")
+
+
+@pytest.mark.parametrize("li", range(5))
+def test_qconv2d_resnet_batch1(li):
+    G = _gpu()
+    layer = wl.resnet50_layers(1)[li]
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, wl.layer_seed(3, li))
+    pd = (layer.pad,) * 4
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                         (layer.stride,) * 2, pd, 1, act=layer.act)
+    for use_ws in (True, False):
+        got, variant = G.gpu_qconv2d(xq, wq, bq, qp, G.desc_of(layer), layer.act, use_workspace=use_ws)
+        G.assert_equal_i8(got, ref, f"{layer.name} ws {use_ws} [{variant}]")
+
+
+@pytest.mark.parametrize("shape", FC_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", 3)])
+def test_qfc(shape, dist, w_off):
+    G = _gpu()
+    M, K, N = shape
+    layer = wl.FcLayer("case", M, K, N)
+    aq, wq, bq, qp = wl.fc_inputs_q(layer, 4000 + M + K + N, dist=dist, w_off=w_off)
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off, act=act)
+        for use_ws in (True, False):
+            got, variant = G.gpu_qfc(aq, wq, bq, qp, act, use_workspace=use_ws)
+            G.assert_equal_i8(got, ref, f"qfc {shape} {dist} act {act} ws {use_ws} [{variant}]")
+
+
+def test_requant_params_match_oracle():
+    """Host helper of the library against the oracle's independent derivation."""
+    import paper_1805_00907_amd as glowmi
+    rng = np.random.default_rng(6)
+    for _ in range(500):
+        sx, sw, sy = (float(np.float32(v)) for v in rng.uniform(0.001, 0.3, size=3))
+        assert glowmi.requant_params(sx, sw, sy) == oracle.requant_params(sx, sw, sy)
