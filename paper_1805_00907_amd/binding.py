@@ -48,6 +48,9 @@ def library() -> ctypes.CDLL:
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: build it with `python -m paper_1805_00907_amd.build` "
                           "(glowmi has no CPU or PyTorch fallback)")
+    # torch ships its own HIP runtime; import it first so that this library binds to the same
+    # runtime instance that owns the device memory and streams handed to it.
+    import torch  # noqa: F401
     L = ctypes.CDLL(_LIB_PATH)
     vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
     dp = ctypes.POINTER(ConvDesc)

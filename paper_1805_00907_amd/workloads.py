@@ -132,14 +132,20 @@ def layer_seed(config_index: int, layer_index: int) -> int:
 
 
 # ---------------------------------------------------------------------------------------------------
-# Random tensors.  dist "uniform": x, w ~ U(-1,1), bias ~ U(-0.1,0.1).
-#                  dist "fan_in" : x ~ N(0,1), w and bias ~ N(0,1)/sqrt(fan_in).
+# Random tensors.  dist "uniform"       : x, w ~ U(-1,1), bias ~ U(-0.1,0.1).
+#                  dist "uniform_fan_in": x ~ U(-1,1), w ~ U(-1,1)/sqrt(fan_in), bias ~ U(-0.1,0.1)
+#                                         (outputs stay O(1) however deep the reduction is, as
+#                                         in a trained network).
+#                  dist "fan_in"        : x ~ N(0,1), w and bias ~ N(0,1)/sqrt(fan_in).
 # ---------------------------------------------------------------------------------------------------
 
 def _draw(rng: np.random.Generator, shape, dist: str, fan_in: int, is_bias=False, is_input=False):
-    if dist == "uniform":
+    if dist in ("uniform", "uniform_fan_in"):
         lim = 0.1 if is_bias else 1.0
-        return rng.uniform(-lim, lim, size=shape).astype(np.float32)
+        t = rng.uniform(-lim, lim, size=shape).astype(np.float32)
+        if dist == "uniform_fan_in" and not is_bias and not is_input:
+            t *= np.float32(1.0 / math.sqrt(fan_in))
+        return t
     if dist == "fan_in":
         t = rng.standard_normal(size=shape, dtype=np.float32)
         if not is_input:

@@ -1,0 +1,121 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, validates arguments before launching anything, and derives the same integer
+requantization multiplier as the oracle's independent implementation."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_1805_00907_amd as glowmi
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000001000   # aligned, never dereferenced: validation fails before any launch
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "glowmi.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(glowmi_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = glowmi.library()
+    names = _declared_symbols()
+    assert {"glowmi_conv2d", "glowmi_fc", "glowmi_qconv2d", "glowmi_qfc"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in include/glowmi.h but not exported"
+
+
+def _desc(**kw):
+    base = dict(n=1, h=8, w=8, c=4, k=4, r=3, s=3, stride_h=1, stride_w=1, pad_t=1, pad_l=1, pad_b=1, pad_r=1, groups=1)
+    base.update(kw)
+    return glowmi.ConvDesc(**base)
+
+
+def test_out_shape_follows_the_paper_examples():
+    d = glowmi.ConvDesc(8, 28, 28, 1, 16, 5, 5, 1, 1, 2, 2, 2, 2, 1)       # Section 3.5 listing
+    assert glowmi.conv_out_shape(d) == (28, 28)
+    d = glowmi.ConvDesc(8, 28, 28, 16, 16, 3, 3, 3, 3, 0, 0, 0, 0, 1)      # its pool geometry: floor
+    assert glowmi.conv_out_shape(d) == (9, 9)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(n=0), 2), (dict(c=-1), 2), (dict(stride_h=0), 2), (dict(pad_l=-1), 2),
+    (dict(groups=3), 2), (dict(groups=0), 2), (dict(r=11, pad_t=0, pad_b=0), 2),
+    (dict(n=1 << 20, h=1 << 10, w=1 << 10), 3),
+])
+def test_conv_descriptor_errors(kw, status):
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.conv2d(FAKE, FAKE, None, FAKE, _desc(**kw), stream=0)
+    assert e.value.status == status
+    assert glowmi.library().glowmi_last_error()
+
+
+def test_pointer_errors():
+    d = _desc()
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.conv2d(None, FAKE, None, FAKE, d, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.conv2d(FAKE, FAKE + 4, None, FAKE, d, stream=0)
+    assert e.value.status == 4
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.conv2d(FAKE, FAKE, FAKE + 2, FAKE, d, stream=0)
+    assert e.value.status == 4
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.fc(FAKE, FAKE, None, None, 4, 4, 4, stream=0)
+    assert e.value.status == 1
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.fc(FAKE, FAKE, None, FAKE, 4, 0, 4, stream=0)
+    assert e.value.status == 2
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.conv2d(FAKE, FAKE, None, FAKE, d, act=7, stream=0)
+    assert e.value.status == 3
+
+
+def test_quant_errors():
+    d = _desc()
+    ok = glowmi.QParam(0.1, 0)
+    for bad in (glowmi.QParam(0.0, 0), glowmi.QParam(-1.0, 0), glowmi.QParam(float("nan"), 0),
+                glowmi.QParam(float("inf"), 0), glowmi.QParam(0.1, 128), glowmi.QParam(0.1, -129)):
+        for pos in range(3):
+            q = [ok, ok, ok]
+            q[pos] = bad
+            with pytest.raises(glowmi.GlowmiError) as e:
+                glowmi.qconv2d(FAKE, q[0], FAKE, q[1], None, FAKE, q[2], d, stream=0)
+            assert e.value.status == 5
+    with pytest.raises(glowmi.GlowmiError) as e:     # multiplier far outside the representable range
+        glowmi.qfc(FAKE, glowmi.QParam(1e30, 0), FAKE, glowmi.QParam(1e30, 0), None, FAKE, glowmi.QParam(1e-30, 0),
+                   4, 4, 4, stream=0)
+    assert e.value.status == 5
+    with pytest.raises(glowmi.GlowmiError) as e:     # reduction too deep for an int32 accumulator
+        glowmi.qfc(FAKE, ok, FAKE, ok, None, FAKE, ok, 4, 70000, 4, stream=0)
+    assert e.value.status == 3
+
+
+def test_requant_params_match_oracle():
+    rng = np.random.default_rng(6)
+    for _ in range(2000):
+        sx, sw, sy = (float(np.float32(v)) for v in rng.uniform(0.001, 0.3, size=3))
+        assert glowmi.requant_params(sx, sw, sy) == oracle.requant_params(sx, sw, sy)
+    assert glowmi.requant_params(1.0 + 2.0 ** -17, 1.0 - 2.0 ** -17, 1.0) == (1 << 30, 30)   # carry case
+    assert glowmi.requant_params(0.5, 0.5, 1.0) == (1 << 30, 32)
+
+
+def test_workspace_queries_are_pure():
+    assert glowmi.fc_workspace_bytes(16, 25088, 4096) > 0
+    assert glowmi.fc_workspace_bytes(0, 1, 1) == 0
+    big = glowmi.ConvDesc(16, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1)
+    assert glowmi.conv2d_workspace_bytes(big) == 0          # plenty of tiles: no split
+
+
+def test_product_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_1805_00907_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "glow_oracle" not in text, f

@@ -167,12 +167,3 @@ def test_qfc(shape, dist, w_off):
         for use_ws in (True, False):
             got, variant = G.gpu_qfc(aq, wq, bq, qp, act, use_workspace=use_ws)
             G.assert_equal_i8(got, ref, f"qfc {shape} {dist} act {act} ws {use_ws} [{variant}]")
-
-
-def test_requant_params_match_oracle():
-    """Host helper of the library against the oracle's independent derivation."""
-    import paper_1805_00907_amd as glowmi
-    rng = np.random.default_rng(6)
-    for _ in range(500):
-        sx, sw, sy = (float(np.float32(v)) for v in rng.uniform(0.001, 0.3, size=3))
-        assert glowmi.requant_params(sx, sw, sy) == oracle.requant_params(sx, sw, sy)
