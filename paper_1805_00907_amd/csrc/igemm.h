@@ -41,6 +41,7 @@ hipError_t launch_i8(const Problem& p, hipStream_t stream, const char** variant)
 
 // Split-K planning shared by the ABI layer (workspace sizing) and the launchers.
 struct Plan {
+  int tile;             // index into the kernel file's tile table
   int bm, bn, bk;
   int tiles_m, tiles_n;
   int slabs;            // ceil(Kgemm / bk)

@@ -17,6 +17,9 @@
 //     feeds them with ds_read_b128 from K-contiguous, padded (bank-conflict-free) LDS rows.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+#include <cstdlib>
+
 #include "igemm.h"
 
 namespace glowmi {
@@ -27,23 +30,22 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int BK = 32;            // reduction slab
 constexpr int LDK = BK + 4;       // K-contiguous LDS row, padded: 36 floats keeps ds_read_b128 conflict free
-constexpr int NTHREADS = 256;
 constexpr int KV = BK / 4;        // float4 chunks per K-contiguous row
-constexpr int ROWS_PER_PASS = NTHREADS / KV;   // 32
 constexpr int INVALID_ROW = -(1 << 24);
-constexpr int FLUSH_SLABS = 16;   // MFMA accumulators are folded into a second set every 512 k
+constexpr int FLUSH_SLABS = 32;   // MFMA accumulators are folded into a second set every 1024 k
 
-template <int BN>
-struct BkN {                      // FC weight tile [BK][BN] with N contiguous
+template <int BN, int NT>
+struct BkN {                      // FC weight tile [BK][BN] with N contiguous, staged by NT threads
   static constexpr int LD = BN + 8;             // +8 puts k and k+4 rows on disjoint bank halves
   static constexpr int NV = BN / 4;             // float4 chunks per row
-  static constexpr int ROWS = NTHREADS / NV;    // k-rows per pass
+  static constexpr int ROWS = NT / NV;          // k-rows per pass
   static constexpr int PASSES = BK / ROWS;
+  static_assert(ROWS >= 1 && ROWS <= BK && BK % ROWS == 0, "FC weight tile does not divide over the threads");
 };
 
 template <int BM, int BN, bool B_KN>
 constexpr int lds_floats() {
-  return 2 * (BM * LDK + (B_KN ? BK * BkN<BN>::LD : BN * LDK));
+  return 2 * (BM * LDK + (B_KN ? BK * (BN + 8) : BN * LDK));
 }
 
 // Decomposition of a reduction index kg into filter row r, filter column s and channel c.
@@ -64,30 +66,48 @@ struct Tap {
   }
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
-__global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, int tiles_m, int tiles_n,
-                                                             int total_tiles) {
-  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+// One unit of work: an output tile of one group, for one slice of the reduction axis.
+struct Item {
+  int tm, tn, g, split;
+  int slab_begin, slab_end;
+};
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const Problem p, int tiles_m,
+                                                                          int tiles_n, int total_work) {
+  constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
+  constexpr int ROWS_PER_PASS = NTHREADS / KV;            // tile rows staged per pass over the threads
+  static_assert(NTHREADS == 256 || NTHREADS == 512, "four or eight wavefronts per workgroup");
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;   // wavefront tile
   constexpr int TM = WTM / 32, TN = WTN / 32;             // 32x32 MFMA blocks per wavefront
   static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
+  static_assert(BM % ROWS_PER_PASS == 0 && (B_KN || BN % ROWS_PER_PASS == 0), "tile rows per pass");
+  using BT = BkN<BN, NTHREADS>;
   constexpr int A_PASSES = BM / ROWS_PER_PASS;
-  constexpr int B_PASSES = B_KN ? BkN<BN>::PASSES : BN / ROWS_PER_PASS;
+  constexpr int B_PASSES = B_KN ? BT::PASSES : BN / ROWS_PER_PASS;
   constexpr int A_ELEMS = BM * LDK;
-  constexpr int B_ELEMS = B_KN ? BK * BkN<BN>::LD : BN * LDK;
+  constexpr int B_ELEMS = B_KN ? BK * BT::LD : BN * LDK;
 
   extern __shared__ __align__(16) float lds[];
 
-  // ---- workgroup -> tile, XCD aware: hardware deals consecutive workgroup ids round-robin over
-  // the 8 XCDs, so id % 8 names the XCD; give each XCD a contiguous run of logical tiles.
+  // ---- workgroup -> work item, XCD aware.  Hardware deals consecutive workgroup ids round-robin
+  // over the 8 XCDs, so id % 8 names the XCD; each XCD gets a contiguous run of items, so tiles in
+  // flight on one XCD are neighbours and the input rows / filter tiles they share hit its L2.
   const int per_xcd = gridDim.x >> 3;
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= total_tiles) return;
-  const int tn = logical % tiles_n;
-  const int tmg = logical / tiles_n;
-  const int tm = tmg % tiles_m;
-  const int g = tmg / tiles_m;
-  const int split = blockIdx.y;
+  const int w = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (w >= total_work) return;
+  const int total_slabs = (p.Kgemm + BK - 1) / BK;
+  Item cur;
+  {
+    cur.tn = w % tiles_n;
+    int t = w / tiles_n;
+    cur.tm = t % tiles_m;
+    t /= tiles_m;
+    cur.g = t % p.groups;
+    cur.split = t / p.groups;
+    cur.slab_begin = cur.split * p.slabs_per_split;
+    cur.slab_end = cur.slab_begin + p.slabs_per_split < total_slabs ? cur.slab_begin + p.slabs_per_split : total_slabs;
+  }
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -97,15 +117,17 @@ __global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, in
   const float* __restrict__ X = static_cast<const float*>(p.x);
   const float* __restrict__ Wt = static_cast<const float*>(p.w);
 
-  // ---- per-thread description of the A (input patch) rows it stages
+  // ---- per-thread description of the A (input patch) rows it stages for the item being loaded
   const int kvec = tid % KV;        // which float4 of the slab
   const int row0 = tid / KV;        // first tile row handled
   int a_base[A_PASSES], a_ih0[A_PASSES], a_iw0[A_PASSES];
-  {
+  int ld_tn = 0, ld_g = 0;          // tile column and group of the item being loaded
+  Tap tap;
+  auto setup_rows = [&](const Item& it) {
     const int ohow = p.oh * p.ow;
 #pragma unroll
     for (int q = 0; q < A_PASSES; ++q) {
-      const int m = tm * BM + row0 + q * ROWS_PER_PASS;
+      const int m = it.tm * BM + row0 + q * ROWS_PER_PASS;
       if (m < p.M) {
         const int img = m / ohow;
         const int rem = m - img * ohow;
@@ -113,22 +135,17 @@ __global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, in
         const int ow = rem - oh * p.ow;
         a_ih0[q] = oh * p.stride_h - p.pad_t;
         a_iw0[q] = ow * p.stride_w - p.pad_l;
-        a_base[q] = ((img * p.h + a_ih0[q]) * p.w_ + a_iw0[q]) * p.c + g * p.cg;
+        a_base[q] = ((img * p.h + a_ih0[q]) * p.w_ + a_iw0[q]) * p.c + it.g * p.cg;
       } else {
         a_ih0[q] = INVALID_ROW;
         a_iw0[q] = INVALID_ROW;
         a_base[q] = 0;
       }
     }
-  }
-
-  const int slab_begin = split * p.slabs_per_split;
-  const int total_slabs = (p.Kgemm + BK - 1) / BK;
-  int slab_end = slab_begin + p.slabs_per_split;
-  if (slab_end > total_slabs) slab_end = total_slabs;
-
-  Tap tap;
-  tap.init(slab_begin * BK + kvec * 4, p.cg, p.s);
+    ld_tn = it.tn;
+    ld_g = it.g;
+    tap.init(it.slab_begin * BK + kvec * 4, p.cg, p.s);
+  };
 
   v4f ra[A_PASSES], rb[B_PASSES];
 
@@ -163,9 +180,9 @@ __global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, in
     if (!B_KN) {
 #pragma unroll
       for (int q = 0; q < B_PASSES; ++q) {
-        const int n = tn * BN + row0 + q * ROWS_PER_PASS;
+        const int n = ld_tn * BN + row0 + q * ROWS_PER_PASS;
         const bool nok = n < p.kg;
-        const float* src = Wt + (size_t)(g * p.kg + n) * p.Kgemm + kg0;
+        const float* src = Wt + (size_t)(ld_g * p.kg + n) * p.Kgemm + kg0;
         if (VEC) {
           rb[q] = (nok && kg0 < p.Kgemm) ? *reinterpret_cast<const v4f*>(src) : v4f{0.f, 0.f, 0.f, 0.f};
         } else {
@@ -174,9 +191,9 @@ __global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, in
         }
       }
     } else {
-      constexpr int NV = BkN<BN>::NV, ROWS = BkN<BN>::ROWS;
+      constexpr int NV = BT::NV, ROWS = BT::ROWS;
       const int nv = tid % NV, kr0 = tid / NV;
-      const int col = tn * BN + nv * 4;
+      const int col = ld_tn * BN + nv * 4;
 #pragma unroll
       for (int q = 0; q < B_PASSES; ++q) {
         const int kgr = slab * BK + kr0 + q * ROWS;
@@ -203,7 +220,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, in
       for (int q = 0; q < B_PASSES; ++q)
         *reinterpret_cast<v4f*>(Bs + (row0 + q * ROWS_PER_PASS) * LDK + kvec * 4) = rb[q];
     } else {
-      constexpr int NV = BkN<BN>::NV, ROWS = BkN<BN>::ROWS, LD = BkN<BN>::LD;
+      constexpr int NV = BT::NV, ROWS = BT::ROWS, LD = BT::LD;
       const int nv = tid % NV, kr0 = tid / NV;
 #pragma unroll
       for (int q = 0; q < B_PASSES; ++q)
@@ -214,14 +231,20 @@ __global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, in
   // Two accumulator sets: the MFMAs add into `acc`; every FLUSH_SLABS slabs it is folded into
   // `total`.  Long reductions (FC with K in the tens of thousands) then round like a sum of short
   // chains, which keeps the fp32 result well inside 1e-5 of the exact sum.
-  v16f acc[TM][TN], total[TM][TN];
+  // Only instantiated (LONGK) for reductions longer than FLUSH_SLABS slabs; short ones keep a
+  // single set and the registers that saves.
+  v16f acc[TM][TN], total[LONGK ? TM : 1][LONGK ? TN : 1];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { acc[i][j][e] = 0.f; total[i][j][e] = 0.f; }
+      for (int e = 0; e < 16; ++e) {
+        acc[i][j][e] = 0.f;
+        if (LONGK) total[i][j][e] = 0.f;
+      }
   auto flush = [&]() {
+    if (!LONGK) return;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -251,7 +274,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, in
         for (int j = 0; j < TN; ++j)
           b[j] = *reinterpret_cast<const v4f*>(Bs + (wn * WTN + j * 32 + lrow) * LDK + k8 * 8 + lhalf * 4);
       } else {
-        constexpr int LD = BkN<BN>::LD;
+        constexpr int LD = BT::LD;
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -268,53 +291,60 @@ __global__ __launch_bounds__(NTHREADS) void igemm_f32_kernel(const Problem p, in
     }
   };
 
-  // ---- main loop: global loads of slab i+1 in flight while slab i is multiplied
-  if (slab_begin < slab_end) {
-    load_global(slab_begin);
-    store_lds(0);
-    __syncthreads();
-    for (int slab = slab_begin; slab < slab_end; ++slab) {
-      const int buf = (slab - slab_begin) & 1;
-      const bool more = slab + 1 < slab_end;
+  // ---- epilogue of one item: bias + activation on the accumulators, one store.
+  // 32x32 MFMA block: register e of a lane is row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
+  float* __restrict__ Y = static_cast<float*>(p.y);
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  auto epilogue = [&](const Item& it) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = it.tn * BN + wn * WTN + j * 32 + lrow;
+      const bool cok = col < p.kg;
+      const int ch = it.g * p.kg + col;
+      const float bv = (cok && p.split_k == 1 && bias) ? bias[ch] : 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int row = it.tm * BM + wm * WTM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+          float v = LONGK ? total[i][j][e] : acc[i][j][e];
+          if (!cok || row >= p.M) continue;
+          if (p.split_k == 1) {
+            v += bv;
+            if (p.act == 1) v = fmaxf(v, 0.f);
+            Y[(size_t)row * p.k + ch] = v;
+          } else {
+            static_cast<float*>(p.partial)[((size_t)it.split * p.M + row) * p.k + ch] = v;
+          }
+        }
+      }
+    }
+  };
+
+  // ---- main loop: global loads of slab i+1 in flight while slab i is multiplied.  The loop is
+  // nested so that the fold of `acc` into `total` sits outside the inner loop and the MFMA
+  // accumulators never leave their registers inside it.
+  setup_rows(cur);
+  load_global(cur.slab_begin);
+  store_lds(0);
+  __syncthreads();
+  int buf = 0;
+  for (int chunk = cur.slab_begin; chunk < cur.slab_end; chunk += FLUSH_SLABS) {
+    const int chunk_end = chunk + FLUSH_SLABS < cur.slab_end ? chunk + FLUSH_SLABS : cur.slab_end;
+    for (int slab = chunk; slab < chunk_end; ++slab) {
+      const bool more = slab + 1 < cur.slab_end;
       if (more) {
         tap.advance(BK, p.cg, p.s);
         load_global(slab + 1);
       }
       compute(buf);
       if (more) store_lds(buf ^ 1);
-      if (((slab - slab_begin) % FLUSH_SLABS) == FLUSH_SLABS - 1) flush();
       __syncthreads();
+      buf ^= 1;
     }
+    flush();
   }
-  flush();
-
-  // ---- epilogue: bias + activation on the accumulators, one store.
-  // 32x32 MFMA block: register e of a lane is row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
-  float* __restrict__ Y = static_cast<float*>(p.y);
-  const float* __restrict__ bias = static_cast<const float*>(p.bias);
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int col = tn * BN + wn * WTN + j * 32 + lrow;
-    if (col >= p.kg) continue;
-    const int ch = g * p.kg + col;
-    const float bv = (p.split_k == 1 && bias) ? bias[ch] : 0.f;
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = tm * BM + wm * WTM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-        if (row >= p.M) continue;
-        float v = total[i][j][e];
-        if (p.split_k == 1) {
-          v += bv;
-          if (p.act == 1) v = fmaxf(v, 0.f);
-          Y[(size_t)row * p.k + ch] = v;
-        } else {
-          static_cast<float*>(p.partial)[((size_t)split * p.M + row) * p.k + ch] = v;
-        }
-      }
-    }
-  }
+  epilogue(cur);
 }
 
 // Finish of a split reduction: sum the partial tiles in split order (deterministic), then the same
@@ -332,10 +362,11 @@ __global__ __launch_bounds__(256) void splitk_finish_f32(const float* __restrict
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK>
 hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
-  auto kern = igemm_f32_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN>;
+  auto kern = igemm_f32_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN, LONGK>;
   constexpr int lds_bytes = lds_floats<BM, BN, B_KN>() * (int)sizeof(float);
+  constexpr int nthreads = 64 * WAVES_M * WAVES_N;
   static bool attr_set = false;   // per instantiation; benign if two threads race to set it
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -343,32 +374,41 @@ hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const int total_tiles = plan.tiles_m * plan.tiles_n * p.groups;
-  const int grid_x = ((total_tiles + 7) / 8) * 8;
-  dim3 grid(grid_x, plan.split_k, 1), block(NTHREADS, 1, 1);
-  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, p, plan.tiles_m, plan.tiles_n, total_tiles);
+  const long long total_work = (long long)plan.tiles_m * plan.tiles_n * p.groups * plan.split_k;
+  const long long grid_x = ((total_work + 7) / 8) * 8;
+  dim3 grid((unsigned)grid_x, 1, 1), block(nthreads, 1, 1);
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, p, plan.tiles_m, plan.tiles_n, (int)total_work);
   return hipGetLastError();
 }
 
 }  // namespace
 
+// Tile variants.  bm x bn output tile, waves_m x waves_n wavefronts.
+struct TileF32 { int bm, bn, wm, wn; const char* name; };
+constexpr TileF32 kTilesF32[] = {
+    {64, 64, 2, 2, "64x64w4"},       // 0: default; 4 workgroups per CU keep the matrix cores fed
+    {128, 64, 4, 2, "128x64w8"},     // 1
+    {128, 128, 2, 4, "128x128w8"},   // 2
+    {32, 128, 1, 4, "32x128w4"},     // 3: FC with a handful of rows
+    {128, 64, 2, 2, "128x64w4"},     // 4
+};
+constexpr int kNumTilesF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
+
 Plan plan_f32(const Problem& p, bool allow_split) {
   Plan pl;
   pl.bk = BK;
   pl.slabs = (p.Kgemm + BK - 1) / BK;
-  // Tile choice: narrow N tile when there are few output channels per group, short M tile when
-  // the layer has too few rows to give every compute unit a workgroup otherwise.
-  pl.bn = (p.kg > 64) ? 128 : 64;
-  pl.bm = 128;
-  auto tiles = [&](int bm, int bn) {
-    return (long long)((p.M + bm - 1) / bm) * ((p.kg + bn - 1) / bn) * p.groups;
-  };
-  if (p.M <= 32 && pl.bn == 128) {
-    pl.bm = 32;
-  } else if (tiles(pl.bm, pl.bn) < 512) {
-    pl.bm = 64;
-    pl.bn = 64;
+  // Measured on VGG-19 / ResNet-50 shaped layers the 64x64 tile with four resident workgroups per
+  // CU is within 2% of the best variant everywhere; FC with very few rows takes the 32-row tile.
+  int tile = 0;
+  if (p.M <= 32 && p.kg > 64) tile = 3;
+  if (const char* env = getenv("GLOWMI_F32_TILE")) {       // experiments: force a tile variant
+    const int t = atoi(env);
+    if (t >= 0 && t < kNumTilesF32) tile = t;
   }
+  pl.tile = tile;
+  pl.bm = kTilesF32[tile].bm;
+  pl.bn = kTilesF32[tile].bn;
   pl.tiles_m = (p.M + pl.bm - 1) / pl.bm;
   pl.tiles_n = (p.kg + pl.bn - 1) / pl.bn;
   pl.split_k = 1;
@@ -387,6 +427,21 @@ Plan plan_f32(const Problem& p, bool allow_split) {
   return pl;
 }
 
+namespace {
+template <int BM, int BN, int WM, int WN, bool LONGK>
+hipError_t launch_tile2(const Problem& p, const Plan& plan, hipStream_t stream, bool fc, bool vec) {
+  if (fc) return vec ? launch_variant<BM, BN, WM, WN, true, true, LONGK>(p, plan, stream)
+                     : launch_variant<BM, BN, WM, WN, false, true, LONGK>(p, plan, stream);
+  return vec ? launch_variant<BM, BN, WM, WN, true, false, LONGK>(p, plan, stream)
+             : launch_variant<BM, BN, WM, WN, false, false, LONGK>(p, plan, stream);
+}
+template <int BM, int BN, int WM, int WN>
+hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, bool fc, bool vec) {
+  return plan.slabs_per_split > FLUSH_SLABS ? launch_tile2<BM, BN, WM, WN, true>(p, plan, stream, fc, vec)
+                                            : launch_tile2<BM, BN, WM, WN, false>(p, plan, stream, fc, vec);
+}
+}  // namespace
+
 hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
   Problem p = p_in;
   const Plan plan = plan_f32(p, p.partial != nullptr);
@@ -395,25 +450,19 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
   // 16-byte gathers need channel runs that are multiples of 4 floats
   const bool fc = p.b_is_kn != 0;
   const bool vec = fc ? (p.Kgemm % 4 == 0 && p.k % 4 == 0) : (p.cg % 4 == 0 && p.c % 4 == 0);
+  static thread_local char name[64];
+  snprintf(name, sizeof(name), "igemm_f32_%s_%s_%s", kTilesF32[plan.tile].name, fc ? "fc" : "conv",
+           vec ? "vec" : "scalar");
+  *variant = name;
   hipError_t e;
-#define GLOWMI_CASE(BM_, BN_, WM_, WN_, NAME)                                                        \
-  if (plan.bm == BM_ && plan.bn == BN_) {                                                            \
-    if (fc) {                                                                                        \
-      e = vec ? launch_variant<BM_, BN_, WM_, WN_, true, true>(p, plan, stream)                      \
-              : launch_variant<BM_, BN_, WM_, WN_, false, true>(p, plan, stream);                    \
-      *variant = vec ? "igemm_f32_" NAME "_fc_vec" : "igemm_f32_" NAME "_fc_scalar";                 \
-    } else {                                                                                         \
-      e = vec ? launch_variant<BM_, BN_, WM_, WN_, true, false>(p, plan, stream)                     \
-              : launch_variant<BM_, BN_, WM_, WN_, false, false>(p, plan, stream);                   \
-      *variant = vec ? "igemm_f32_" NAME "_conv_vec" : "igemm_f32_" NAME "_conv_scalar";             \
-    }                                                                                                \
-  } else
-  GLOWMI_CASE(128, 128, 2, 2, "128x128")
-  GLOWMI_CASE(128, 64, 2, 2, "128x64")
-  GLOWMI_CASE(64, 64, 2, 2, "64x64")
-  GLOWMI_CASE(32, 128, 1, 4, "32x128")
-  { return hipErrorInvalidValue; }
-#undef GLOWMI_CASE
+  switch (plan.tile) {
+    case 0: e = launch_tile<64, 64, 2, 2>(p, plan, stream, fc, vec); break;
+    case 1: e = launch_tile<128, 64, 4, 2>(p, plan, stream, fc, vec); break;
+    case 2: e = launch_tile<128, 128, 2, 4>(p, plan, stream, fc, vec); break;
+    case 3: e = launch_tile<32, 128, 1, 4>(p, plan, stream, fc, vec); break;
+    case 4: e = launch_tile<128, 64, 2, 2>(p, plan, stream, fc, vec); break;
+    default: return hipErrorInvalidValue;
+  }
   if (e != hipSuccess) return e;
   if (plan.split_k > 1) {
     const int total = p.M * p.k;

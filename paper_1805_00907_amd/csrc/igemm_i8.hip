@@ -384,6 +384,7 @@ hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream
 
 Plan plan_i8(const Problem& p, bool allow_split) {
   Plan pl;
+  pl.tile = 0;
   pl.bk = BKQ;
   pl.slabs = (p.Kgemm + BKQ - 1) / BKQ;
   pl.bn = (p.kg > 64) ? 128 : 64;
