@@ -123,12 +123,21 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
   int a_base[A_PASSES], a_ih0[A_PASSES], a_iw0[A_PASSES];
   int ld_tn = 0, ld_g = 0;          // tile column and group of the item being loaded
   Tap tap;
+  // A pointwise layer (1x1 filter, stride 1, no padding; FullyConnected is one) maps output row m
+  // straight to input pixel m: no (image, oh, ow) decomposition and no border test is needed.
+  const bool pointwise = p.r == 1 && p.s == 1 && p.stride_h == 1 && p.stride_w == 1 && p.pad_t == 0 &&
+                         p.pad_l == 0 && p.oh == p.h && p.ow == p.w_;
   auto setup_rows = [&](const Item& it) {
     const int ohow = p.oh * p.ow;
 #pragma unroll
     for (int q = 0; q < A_PASSES; ++q) {
       const int m = it.tm * BM + row0 + q * ROWS_PER_PASS;
-      if (m < p.M) {
+      if (pointwise) {
+        const bool ok = m < p.M;
+        a_ih0[q] = ok ? 0 : INVALID_ROW;
+        a_iw0[q] = ok ? 0 : INVALID_ROW;
+        a_base[q] = ok ? m * p.c + it.g * p.cg : 0;
+      } else if (m < p.M) {
         const int img = m / ohow;
         const int rem = m - img * ohow;
         const int oh = rem / p.ow;
@@ -362,6 +371,131 @@ __global__ __launch_bounds__(256) void splitk_finish_f32(const float* __restrict
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// FullyConnected with at most 16 rows (batch 1..16): the layer is a stream of the weight matrix
+// through the chip, bound by HBM.  No LDS staging and no barriers in the main loop: every lane loads
+// float4 pieces of weight rows straight into registers in the layout the MFMA wants, activations
+// (a few rows, L2 resident) are read as float4 along K, the four wavefronts of a workgroup
+// interleave K steps and are summed through LDS in a fixed order; if the grid also splits K the
+// sums go to the workspace for the finishing kernel.
+//
+// v_mfma_f32_16x16x4_f32 is used because a 32-row MFMA would spend half of the matrix unit on
+// padding rows, and at 64 cycles per 256 bytes of weights the matrix unit, not HBM, would set the
+// pace.  Lane l = (c = l % 16, q = l / 16): loads float4 W[k0 + 4q + t][n0 + 4c..] for t = 0..3
+// (16 lanes cover 256 contiguous bytes of one weight row) and float4 A[c][k0 + 4q..]; MFMA (t, j)
+// multiplies k = k0 + 4q + t into the column group j, i.e. columns n0 + 4c + j, so the four
+// accumulators of a lane hold four consecutive output columns (one float4 store).
+// ---------------------------------------------------------------------------------------------------
+constexpr int SK_WAVES = 4;
+constexpr int SK16_COLS = 64;    // output columns per workgroup
+constexpr int SK16_STEP = 16;    // weight rows per step
+
+typedef float v4f_acc __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(64 * SK_WAVES) void fc_skinny16_f32_kernel(
+    const float* __restrict__ A, const float* __restrict__ Wt, const float* __restrict__ bias,
+    float* __restrict__ Y, float* __restrict__ partial, int M, int K, int N, int act, int split_k,
+    int steps_per_split) {
+  __shared__ float red[(SK_WAVES - 1) * 16 * 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int c16 = lane & 15, q = lane >> 4;
+  const int n0 = blockIdx.x * SK16_COLS;
+  const int split = blockIdx.y;
+  const int total_steps = (K + SK16_STEP - 1) / SK16_STEP;
+  const int step_begin = split * steps_per_split;
+  const int step_end = step_begin + steps_per_split < total_steps ? step_begin + steps_per_split : total_steps;
+
+  const int col = n0 + 4 * c16;
+  const bool col_ok = col < N;                   // N % 4 == 0: all four or none
+  const bool row_ok = c16 < M;                   // as the A operand, lane c16 holds activation row c16
+
+  v4f_acc acc[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) acc[j] = v4f_acc{0.f, 0.f, 0.f, 0.f};
+
+  // Full steps (16 weight rows inside K) are loaded without any predicate, so the compiler keeps
+  // the loads in flight across the MFMAs.  Lanes whose row or column lies outside the problem load
+  // from a clamped address: their products land in result rows / columns that are never stored.
+  // The one partial step a K that is not a multiple of 16 leaves is done separately, masked.
+  const float* a_base = A + (size_t)(row_ok ? c16 : 0) * K + q * 4;
+  const float* w_base = Wt + (col_ok ? col : 0) + (size_t)(q * 4) * N;
+  auto load_step = [&](int step, v4f& a, v4f (&b)[4]) {
+    a = *reinterpret_cast<const v4f*>(a_base + (size_t)step * SK16_STEP);
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      b[t] = *reinterpret_cast<const v4f*>(w_base + ((size_t)step * SK16_STEP + t) * N);
+  };
+  auto mma_step = [&](const v4f& a, const v4f (&b)[4]) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[t], b[t][j], acc[j], 0, 0, 0);
+  };
+
+  const int full_steps = K / SK16_STEP;
+  const int fast_end = step_end < full_steps ? step_end : full_steps;
+  const int stride = SK_WAVES;                   // the four wavefronts interleave steps
+  // Plain loop, one step per trip: with 16 wavefronts resident per CU the hardware overlaps the
+  // loads of some with the MFMAs of others (measured faster than explicit register double buffering).
+  for (int step = step_begin + wave; step < fast_end; step += stride) {
+    v4f a, b[4];
+    load_step(step, a, b);
+    mma_step(a, b);
+  }
+  if (step_end > full_steps && full_steps >= step_begin && (full_steps - step_begin) % stride == wave) {
+    // wave-uniform branch: the partial last step.  K % 4 == 0, so a lane's group of four k is
+    // entirely inside or outside; outside groups read group 0 and are cancelled by a zero operand.
+    const int k0 = full_steps * SK16_STEP + q * 4;
+    const bool kok = k0 < K;
+    const int kc = kok ? k0 : 0;
+    v4f a = *reinterpret_cast<const v4f*>(A + (size_t)(row_ok ? c16 : 0) * K + kc);
+    if (!kok) a = v4f{0.f, 0.f, 0.f, 0.f};
+    v4f b[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+      b[t] = *reinterpret_cast<const v4f*>(Wt + (col_ok ? col : 0) + (size_t)(kc + t) * N);
+    mma_step(a, b);
+  }
+
+  if (wave > 0) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) red[((wave - 1) * 16 + j * 4 + e) * 64 + lane] = acc[j][e];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+#pragma unroll
+  for (int wv = 0; wv < SK_WAVES - 1; ++wv)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[j][e] += red[(wv * 16 + j * 4 + e) * 64 + lane];
+
+  if (!col_ok) return;
+  v4f bv = {0.f, 0.f, 0.f, 0.f};
+  if (split_k == 1 && bias) bv = *reinterpret_cast<const v4f*>(bias + col);
+  // 16x16 result: register e of lane (c, q) is row 4q + e, column c
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int row = q * 4 + e;
+    if (row >= M) continue;
+    v4f v = {acc[0][e], acc[1][e], acc[2][e], acc[3][e]};
+    if (split_k == 1) {
+      v += bv;
+      if (act == 1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = fmaxf(v[j], 0.f);
+      }
+      *reinterpret_cast<v4f*>(Y + (size_t)row * N + col) = v;
+    } else {
+      *reinterpret_cast<v4f*>(partial + ((size_t)split * M + row) * N + col) = v;
+    }
+  }
+}
+
+constexpr int kTileSkinny16 = 101;   // Plan::tile value of the skinny FC kernel
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK>
 hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
   auto kern = igemm_f32_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN, LONGK>;
@@ -391,11 +525,39 @@ constexpr TileF32 kTilesF32[] = {
     {128, 128, 2, 4, "128x128w8"},   // 2
     {32, 128, 1, 4, "32x128w4"},     // 3: FC with a handful of rows
     {128, 64, 2, 2, "128x64w4"},     // 4
+    {128, 128, 2, 2, "128x128w4"},   // 5
 };
 constexpr int kNumTilesF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 
 Plan plan_f32(const Problem& p, bool allow_split) {
   Plan pl;
+  if (p.b_is_kn && p.M <= 16 && p.groups == 1 && p.k % 4 == 0 && p.Kgemm % 4 == 0 &&
+      !getenv("GLOWMI_F32_TILE")) {
+    // FC with a handful of rows: stream the weights (fc_skinny16_f32_kernel).  "slabs" are steps of
+    // SK16_STEP weight rows; K is split over the grid until ~4 workgroups per CU exist, each
+    // wavefront keeping at least two steps.
+    const int cols = SK16_COLS, stepk = SK16_STEP;
+    pl.tile = kTileSkinny16;
+    pl.bm = 16;
+    pl.bn = cols;
+    pl.bk = stepk;
+    pl.tiles_m = 1;
+    pl.tiles_n = (p.k + cols - 1) / cols;
+    pl.slabs = (p.Kgemm + stepk - 1) / stepk;
+    pl.split_k = 1;
+    pl.slabs_per_split = pl.slabs;
+    if (allow_split) {
+      int want = (1024 + pl.tiles_n - 1) / pl.tiles_n;
+      int max_split = pl.slabs / (2 * SK_WAVES);
+      int sk = want < max_split ? want : max_split;
+      if (sk > 128) sk = 128;
+      if (sk > 1) {
+        pl.slabs_per_split = (pl.slabs + sk - 1) / sk;
+        pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
+      }
+    }
+    return pl;
+  }
   pl.bk = BK;
   pl.slabs = (p.Kgemm + BK - 1) / BK;
   // Measured on VGG-19 / ResNet-50 shaped layers the 64x64 tile with four resident workgroups per
@@ -451,17 +613,28 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
   const bool fc = p.b_is_kn != 0;
   const bool vec = fc ? (p.Kgemm % 4 == 0 && p.k % 4 == 0) : (p.cg % 4 == 0 && p.c % 4 == 0);
   static thread_local char name[64];
+  hipError_t e;
+  if (plan.tile == kTileSkinny16) {
+    *variant = "fc_skinny16_f32";
+    dim3 grid(plan.tiles_n, plan.split_k, 1), block(64 * SK_WAVES, 1, 1);
+    hipLaunchKernelGGL(fc_skinny16_f32_kernel, grid, block, 0, stream, static_cast<const float*>(p.x),
+                       static_cast<const float*>(p.w), static_cast<const float*>(p.bias),
+                       static_cast<float*>(p.y), static_cast<float*>(p.partial), p.M, p.Kgemm, p.k, p.act,
+                       plan.split_k, plan.slabs_per_split);
+    e = hipGetLastError();
+  } else {
   snprintf(name, sizeof(name), "igemm_f32_%s_%s_%s", kTilesF32[plan.tile].name, fc ? "fc" : "conv",
            vec ? "vec" : "scalar");
   *variant = name;
-  hipError_t e;
   switch (plan.tile) {
     case 0: e = launch_tile<64, 64, 2, 2>(p, plan, stream, fc, vec); break;
     case 1: e = launch_tile<128, 64, 4, 2>(p, plan, stream, fc, vec); break;
     case 2: e = launch_tile<128, 128, 2, 4>(p, plan, stream, fc, vec); break;
     case 3: e = launch_tile<32, 128, 1, 4>(p, plan, stream, fc, vec); break;
     case 4: e = launch_tile<128, 64, 2, 2>(p, plan, stream, fc, vec); break;
+    case 5: e = launch_tile<128, 128, 2, 2>(p, plan, stream, fc, vec); break;
     default: return hipErrorInvalidValue;
+  }
   }
   if (e != hipSuccess) return e;
   if (plan.split_k > 1) {

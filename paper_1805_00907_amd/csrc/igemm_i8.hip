@@ -9,10 +9,16 @@
 // are collected with dot-product instructions while the tiles are staged.  Everything after the
 // accumulator is integer arithmetic, so results are reproducible bit for bit.
 //
-// Tiling mirrors the fp32 kernel: BM x BN output tile per 256-thread workgroup, reduction slabs of
-// 64 codes staged in double-buffered LDS as K-contiguous rows of 64 + 16 pad bytes (conflict-free
-// ds_read_b128), XCD-aware workgroup order.
+// Tiling mirrors the fp32 kernel: BM x BN output tile per workgroup of 4 or 8 wavefronts, reduction
+// slabs of 128 codes staged in double-buffered LDS as K-contiguous rows of 128 + 16 pad bytes
+// (conflict-free ds_read_b128), XCD-aware workgroup order.  The MFMA is issued with the filter
+// fragment as its row operand, so a lane ends up with four consecutive output channels of one
+// pixel: they are requantized, packed into one dword, transposed through LDS and leave the chip as
+// 16-byte stores along the channel axis.
 #include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
 
 #include "igemm.h"
 
@@ -22,11 +28,9 @@ namespace {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int BKQ = 64;                  // codes per reduction slab
-constexpr int LDQ = BKQ + 16;            // LDS row pitch in bytes
-constexpr int NTHREADS = 256;
+constexpr int BKQ = 128;                 // codes per reduction slab
+constexpr int LDQ = BKQ + 16;            // LDS row pitch in bytes (36 dwords: conflict-free b128 reads)
 constexpr int KV = BKQ / 16;             // 16-byte chunks per K-contiguous row
-constexpr int ROWS_PER_PASS = NTHREADS / KV;   // 64
 constexpr int INVALID_ROW = -(1 << 24);
 
 struct Tap {
@@ -50,37 +54,57 @@ __device__ __forceinline__ int sum_bytes(int packed) {   // sum of the four sign
   return __builtin_amdgcn_sdot4(packed, 0x01010101, 0, false);
 }
 
+// round_half_up(acc * mant / 2^shift) + y_off, clamped to [lo, 127].
+// With P = acc * mant = hi * 2^32 + lo32 and shift >= 33 the rounding constant 2^(shift-1) is a
+// multiple of 2^32, so (P + 2^(shift-1)) >> shift == (hi + 2^(shift-33)) >> (shift-32) exactly:
+// one 32-bit multiply-high instead of 64-bit arithmetic.  That covers every multiplier below 1/4
+// (the usual case); larger multipliers take the 64-bit form.  The branch is uniform.
 __device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_off, int lo) {
-  long long t = (long long)acc * (long long)mant + (1LL << (shift - 1));
-  long long q = (t >> shift) + y_off;     // arithmetic shift: floor, so ties round up
+  int q;
+  if (shift >= 33) {
+    q = (__mulhi(acc, mant) + (1 << (shift - 33))) >> (shift - 32);
+  } else {
+    long long t = (long long)acc * (long long)mant + (1LL << (shift - 1));
+    t >>= shift;                            // arithmetic shift: floor, so ties round up
+    t = t < -4096 ? -4096 : t;              // far outside the int8 range either way
+    t = t > 4096 ? 4096 : t;
+    q = (int)t;
+  }
+  q += y_off;
   q = q < lo ? lo : q;
   q = q > 127 ? 127 : q;
-  return (int)q;
+  return q;
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
-__global__ __launch_bounds__(NTHREADS) void igemm_i8_kernel(const Problem p, int tiles_m, int tiles_n,
-                                                            int total_tiles) {
-  static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const Problem p, int tiles_m,
+                                                                         int tiles_n, int total_work) {
+  constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
+  constexpr int ROWS_PER_PASS = NTHREADS / KV;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int TM = WTM / 32, TN = WTN / 32;
-  static_assert(TM >= 1 && TN >= 1 && BM % 64 == 0 && BN % 64 == 0, "tile shape");
+  static_assert(TM >= 1 && TN >= 1 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
+  static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile rows per pass");
   constexpr int A_PASSES = BM / ROWS_PER_PASS;
   constexpr int B_PASSES = BN / ROWS_PER_PASS;          // K-contiguous filter rows
   constexpr int B_UNITS = (BKQ / 4) * (BN / 4);         // FC weight: 4k x 4n byte blocks per slab
   constexpr int B_UPT = B_UNITS / NTHREADS;             // blocks per thread
+  static_assert(B_UNITS % NTHREADS == 0, "FC weight tile does not divide over the threads");
   constexpr int A_BYTES = BM * LDQ, B_BYTES = BN * LDQ;
+  constexpr int OUT_PITCH = BN + 16;                    // output tile staged in LDS, bytes per pixel row
+  static_assert(2 * (A_BYTES + B_BYTES) >= BM * OUT_PITCH + (BM + 2 * BN) * 4, "epilogue reuses the staging LDS");
 
   extern __shared__ __align__(16) unsigned char ldsq[];
 
   const int per_xcd = gridDim.x >> 3;
-  const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (logical >= total_tiles) return;
-  const int tn = logical % tiles_n;
-  const int tmg = logical / tiles_n;
-  const int tm = tmg % tiles_m;
-  const int g = tmg / tiles_m;
-  const int split = blockIdx.y;
+  const int w = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (w >= total_work) return;
+  const int tn = w % tiles_n;
+  int t_ = w / tiles_n;
+  const int tm = t_ % tiles_m;
+  t_ /= tiles_m;
+  const int g = t_ % p.groups;
+  const int split = t_ / p.groups;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -249,6 +273,7 @@ __global__ __launch_bounds__(NTHREADS) void igemm_i8_kernel(const Problem p, int
     }
   };
 
+  // acc[i][j]: 32 output channels (rows of the MFMA result) x 32 pixels (columns)
   v16i acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -276,8 +301,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_i8_kernel(const Problem p, int
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i], b[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j)   // filter fragment as the row operand: result rows = channels
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[j], a[i], acc[i][j], 0, 0, 0);
     }
   };
 
@@ -285,8 +310,8 @@ __global__ __launch_bounds__(NTHREADS) void igemm_i8_kernel(const Problem p, int
     load_global(slab_begin);
     store_lds(0);
     __syncthreads();
+    int buf = 0;
     for (int slab = slab_begin; slab < slab_end; ++slab) {
-      const int buf = (slab - slab_begin) & 1;
       const bool more = slab + 1 < slab_end;
       if (more) {
         tap.advance(BKQ, p.cg, p.s);
@@ -295,12 +320,17 @@ __global__ __launch_bounds__(NTHREADS) void igemm_i8_kernel(const Problem p, int
       compute(buf);
       if (more) store_lds(buf ^ 1);
       __syncthreads();
+      buf ^= 1;
     }
   }
 
-  // ---- per-row / per-column code sums into LDS (the staging buffers are free now)
-  int* xsum = reinterpret_cast<int*>(ldsq);            // [BM]
-  int* wsum = xsum + BM;                               // [BN]
+  // ---- epilogue.  LDS (staging buffers are free now):
+  //   out   [BM][OUT_PITCH] bytes : requantized tile, pixel-major
+  //   xsum  [BM] int, wsum [BN] int : code sums;  cterm [BN] int : per-channel additive term
+  unsigned char* out = ldsq;
+  int* xsum = reinterpret_cast<int*>(ldsq + BM * OUT_PITCH);
+  int* wsum = xsum + BM;
+  int* cterm = wsum + BN;
   for (int i = tid; i < BM + BN; i += NTHREADS) xsum[i] = 0;
   __syncthreads();
   if (need_xsum) {
@@ -320,35 +350,71 @@ __global__ __launch_bounds__(NTHREADS) void igemm_i8_kernel(const Problem p, int
     }
   }
   __syncthreads();
-
-  // ---- epilogue: offsets out, bias, requantize, clamp (Relu = lower bound), one store
-  signed char* __restrict__ Y = static_cast<signed char*>(p.y);
-  const int* __restrict__ bias = static_cast<const int*>(p.bias);
   // The correction terms are combined modulo 2^32 (unsigned): each may exceed the final value, the
   // true accumulator fits int32 by contract, so the wrapped sum is exact.
-  const unsigned kxw = (unsigned)k_count * (unsigned)(p.x_off * p.w_off);
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int lcol = wn * WTN + j * 32 + lrow;
-    const int col = tn * BN + lcol;
-    if (col >= p.kg) continue;
-    const int ch = g * p.kg + col;
-    unsigned colterm = kxw - (unsigned)p.x_off * (unsigned)wsum[lcol];
-    if (p.split_k == 1 && bias) colterm += (unsigned)bias[ch];
+  const int* __restrict__ bias = static_cast<const int*>(p.bias);
+  for (int i = tid; i < BN; i += NTHREADS) {
+    const int col = tn * BN + i;
+    unsigned ct = (unsigned)k_count * (unsigned)(p.x_off * p.w_off) - (unsigned)p.x_off * (unsigned)wsum[i];
+    if (p.split_k == 1 && bias && col < p.kg) ct += (unsigned)bias[g * p.kg + col];
+    cterm[i] = (int)ct;
+  }
+  __syncthreads();
+
+  if (p.split_k == 1) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
+      const int lr = wm * WTM + i * 32 + lrow;                        // pixel row inside the tile
+      const unsigned rowterm = need_xsum ? (unsigned)p.w_off * (unsigned)xsum[lr] : 0u;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int lr = wm * WTM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-        const int row = tm * BM + lr;
-        if (row >= p.M) continue;
-        unsigned u = (unsigned)acc[i][j][e] + colterm;
-        if (need_xsum) u -= (unsigned)p.w_off * (unsigned)xsum[lr];
-        const int v = (int)u;
-        if (p.split_k == 1) {
-          Y[(size_t)row * p.k + ch] = (signed char)requantize(v, p.mant, p.shift, p.y_off, p.lo);
-        } else {
-          static_cast<int*>(p.partial)[((size_t)split * p.M + row) * p.k + ch] = v;
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const int lc = wn * WTN + j * 32 + q4 * 8 + lhalf * 4;      // first of 4 consecutive channels
+          const v4i ct = *reinterpret_cast<const v4i*>(cterm + lc);
+          unsigned packed = 0;
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const int v = (int)((unsigned)acc[i][j][q4 * 4 + t] + (unsigned)ct[t] - rowterm);
+            packed |= ((unsigned)requantize(v, p.mant, p.shift, p.y_off, p.lo) & 0xffu) << (t * 8);
+          }
+          *reinterpret_cast<unsigned*>(out + lr * OUT_PITCH + lc) = packed;
+        }
+      }
+    }
+    __syncthreads();
+    // copy out: 16 bytes of one pixel row per thread and pass
+    signed char* __restrict__ Y = static_cast<signed char*>(p.y);
+    constexpr int CHUNKS = BN / 16;
+    const bool wide = (p.kg % 16 == 0) && (p.k % 16 == 0);
+    for (int u = tid; u < BM * CHUNKS; u += NTHREADS) {
+      const int lr = u / CHUNKS, ch = u % CHUNKS;
+      const int row = tm * BM + lr, col = tn * BN + ch * 16;
+      if (row >= p.M || col >= p.kg) continue;
+      signed char* dst = Y + (size_t)row * p.k + g * p.kg + col;
+      const unsigned char* src = out + lr * OUT_PITCH + ch * 16;
+      if (wide) {
+        *reinterpret_cast<v4i*>(dst) = *reinterpret_cast<const v4i*>(src);
+      } else {
+        for (int e = 0; e < 16 && col + e < p.kg; ++e) dst[e] = (signed char)src[e];
+      }
+    }
+  } else {
+    int* __restrict__ part = static_cast<int*>(p.partial);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int lr = wm * WTM + i * 32 + lrow;
+      const int row = tm * BM + lr;
+      const unsigned rowterm = need_xsum ? (unsigned)p.w_off * (unsigned)xsum[lr] : 0u;
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int lc = wn * WTN + j * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+          const int col = tn * BN + lc;
+          if (row >= p.M || col >= p.kg) continue;
+          part[((size_t)split * p.M + row) * p.k + g * p.kg + col] =
+              (int)((unsigned)acc[i][j][e] + (unsigned)cterm[lc] - rowterm);
         }
       }
     }
@@ -372,30 +438,52 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
 hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
   auto kern = igemm_i8_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN>;
   constexpr int lds_bytes = 2 * (BM + BN) * LDQ;
-  static_assert(lds_bytes >= (BM + BN) * 4, "row sums reuse the staging buffers");
-  const int total_tiles = plan.tiles_m * plan.tiles_n * p.groups;
-  const int grid_x = ((total_tiles + 7) / 8) * 8;
-  dim3 grid(grid_x, plan.split_k, 1), block(NTHREADS, 1, 1);
-  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, p, plan.tiles_m, plan.tiles_n, total_tiles);
+  constexpr int nthreads = 64 * WAVES_M * WAVES_N;
+  static bool attr_set = false;   // per instantiation; benign if two threads race to set it
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const long long total_work = (long long)plan.tiles_m * plan.tiles_n * p.groups * plan.split_k;
+  const long long grid_x = ((total_work + 7) / 8) * 8;
+  dim3 grid((unsigned)grid_x, 1, 1), block(nthreads, 1, 1);
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, p, plan.tiles_m, plan.tiles_n, (int)total_work);
   return hipGetLastError();
+}
+
+struct TileI8 { int bm, bn, wm, wn; const char* name; };
+constexpr TileI8 kTilesI8[] = {
+    {64, 64, 2, 2, "64x64w4"},       // 0: default
+    {128, 64, 4, 2, "128x64w8"},     // 1
+    {128, 128, 2, 4, "128x128w8"},   // 2
+    {128, 128, 2, 2, "128x128w4"},   // 3
+};
+constexpr int kNumTilesI8 = sizeof(kTilesI8) / sizeof(kTilesI8[0]);
+
+template <int BM, int BN, int WM, int WN>
+hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, bool fc, bool vec) {
+  if (fc) return vec ? launch_variant<BM, BN, WM, WN, true, true>(p, plan, stream)
+                     : launch_variant<BM, BN, WM, WN, false, true>(p, plan, stream);
+  return vec ? launch_variant<BM, BN, WM, WN, true, false>(p, plan, stream)
+             : launch_variant<BM, BN, WM, WN, false, false>(p, plan, stream);
 }
 
 }  // namespace
 
 Plan plan_i8(const Problem& p, bool allow_split) {
   Plan pl;
-  pl.tile = 0;
   pl.bk = BKQ;
   pl.slabs = (p.Kgemm + BKQ - 1) / BKQ;
-  pl.bn = (p.kg > 64) ? 128 : 64;
-  pl.bm = 128;
-  auto tiles = [&](int bm, int bn) {
-    return (long long)((p.M + bm - 1) / bm) * ((p.kg + bn - 1) / bn) * p.groups;
-  };
-  if (tiles(pl.bm, pl.bn) < 512) {
-    pl.bm = 64;
-    pl.bn = 64;
+  int tile = 0;
+  if (const char* env = getenv("GLOWMI_I8_TILE")) {        // experiments: force a tile variant
+    const int t = atoi(env);
+    if (t >= 0 && t < kNumTilesI8) tile = t;
   }
+  pl.tile = tile;
+  pl.bm = kTilesI8[tile].bm;
+  pl.bn = kTilesI8[tile].bn;
   pl.tiles_m = (p.M + pl.bm - 1) / pl.bm;
   pl.tiles_n = (p.kg + pl.bn - 1) / pl.bn;
   pl.split_k = 1;
@@ -421,24 +509,18 @@ hipError_t launch_i8(const Problem& p_in, hipStream_t stream, const char** varia
   p.slabs_per_split = plan.slabs_per_split;
   const bool fc = p.b_is_kn != 0;
   const bool vec = fc ? (p.Kgemm % 16 == 0 && p.k % 4 == 0) : (p.cg % 16 == 0 && p.c % 16 == 0);
+  static thread_local char name[64];
+  snprintf(name, sizeof(name), "igemm_i8_%s_%s_%s", kTilesI8[plan.tile].name, fc ? "fc" : "conv",
+           vec ? "vec" : "scalar");
+  *variant = name;
   hipError_t e;
-#define GLOWMI_CASE(BM_, BN_, WM_, WN_, NAME)                                                        \
-  if (plan.bm == BM_ && plan.bn == BN_) {                                                            \
-    if (fc) {                                                                                        \
-      e = vec ? launch_variant<BM_, BN_, WM_, WN_, true, true>(p, plan, stream)                      \
-              : launch_variant<BM_, BN_, WM_, WN_, false, true>(p, plan, stream);                    \
-      *variant = vec ? "igemm_i8_" NAME "_fc_vec" : "igemm_i8_" NAME "_fc_scalar";                   \
-    } else {                                                                                         \
-      e = vec ? launch_variant<BM_, BN_, WM_, WN_, true, false>(p, plan, stream)                     \
-              : launch_variant<BM_, BN_, WM_, WN_, false, false>(p, plan, stream);                   \
-      *variant = vec ? "igemm_i8_" NAME "_conv_vec" : "igemm_i8_" NAME "_conv_scalar";               \
-    }                                                                                                \
-  } else
-  GLOWMI_CASE(128, 128, 2, 2, "128x128")
-  GLOWMI_CASE(128, 64, 2, 2, "128x64")
-  GLOWMI_CASE(64, 64, 2, 2, "64x64")
-  { return hipErrorInvalidValue; }
-#undef GLOWMI_CASE
+  switch (plan.tile) {
+    case 0: e = launch_tile<64, 64, 2, 2>(p, plan, stream, fc, vec); break;
+    case 1: e = launch_tile<128, 64, 4, 2>(p, plan, stream, fc, vec); break;
+    case 2: e = launch_tile<128, 128, 2, 4>(p, plan, stream, fc, vec); break;
+    case 3: e = launch_tile<128, 128, 2, 2>(p, plan, stream, fc, vec); break;
+    default: return hipErrorInvalidValue;
+  }
   if (e != hipSuccess) return e;
   if (plan.split_k > 1) {
     const int total = p.M * p.k;

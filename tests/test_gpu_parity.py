@@ -167,3 +167,27 @@ def test_qfc(shape, dist, w_off):
         for use_ws in (True, False):
             got, variant = G.gpu_qfc(aq, wq, bq, qp, act, use_workspace=use_ws)
             G.assert_equal_i8(got, ref, f"qfc {shape} {dist} act {act} ws {use_ws} [{variant}]")
+
+
+@pytest.mark.parametrize("mr_exp", [-1, 0, 1, 2, -2, -3, -8])
+def test_quantized_large_and_small_multipliers(mr_exp):
+    """Combined multipliers around and above 1/4 take the kernel's 64-bit requantize form, smaller
+    ones its multiply-high form; both must agree with the oracle bit for bit."""
+    G = _gpu()
+    rng = np.random.default_rng(70 + mr_exp)
+    xq = rng.integers(-6, 7, size=(2, 9, 9, 16), dtype=np.int8)
+    wq = rng.integers(-5, 6, size=(40, 3, 3, 16), dtype=np.int8)
+    bq = rng.integers(-50, 50, size=(40,), dtype=np.int32)
+    # sx*sw/sy = 0.8 * 2^mr_exp (not a power of two, so the mantissa is a full 31-bit number)
+    qp = wl.QParams(0.8, 1, float(2.0 ** mr_exp), 0, 1.0, -3)
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                         (1, 1), (1, 1, 1, 1), 1, act=wl.ACT_RELU)
+    assert (ref > -3).any()
+    got, _ = G.gpu_qconv2d(xq, wq, bq, qp, G.make_desc(xq.shape, wq.shape, (1, 1), (1, 1, 1, 1), 1), wl.ACT_RELU)
+    G.assert_equal_i8(got, ref, f"qconv multiplier 0.8*2^{mr_exp}")
+    aq = rng.integers(-4, 5, size=(5, 64), dtype=np.int8)
+    wf = rng.integers(-4, 5, size=(64, 48), dtype=np.int8)
+    bf = rng.integers(-20, 20, size=(48,), dtype=np.int32)
+    ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wf, qp.w_scale, qp.w_off, bf, qp.y_scale, qp.y_off, act=wl.ACT_NONE)
+    got, _ = G.gpu_qfc(aq, wf, bf, qp, wl.ACT_NONE)
+    G.assert_equal_i8(got, ref, f"qfc multiplier 0.8*2^{mr_exp}")
