@@ -1,0 +1,215 @@
+// fp32 Convolution for layers with very few input channels (a network's first layer: 7x7 stride 2 on
+// 3 channels).  The paper's CPU backend singles out "convolutions with a small number of channels"
+// as one of three kinds that get their own strategy (Section 5.4); this is that kind on gfx950.
+//
+// With 3 channels the generic implicit-GEMM gather degenerates into scalar loads with per-element
+// index arithmetic and the vector ALUs, not the matrix cores, set the pace.  Here instead:
+//   - a workgroup owns a tile of 8 x 16 output pixels and 64 output channels and keeps the raw
+//     input patch it needs ((8-1)*stride + R rows of (16-1)*stride + S pixels, all channels) in LDS,
+//     fetched with fully coalesced row loads and zero-filled outside the image (double buffered:
+//     the next tile's patch is in flight during the MFMAs);
+//   - the reduction index v = (r, s, c) is walked two at a time (v_mfma_f32_32x32x2_f32).  Within a
+//     filter row r the (s, c) run is contiguous both in the patch and in the filter, so the A
+//     operand of a lane is one ds_read_b32 at a compile-time offset from a per-lane base;
+//   - the filter fragment of the wavefront's 32 output channels (ceil(R*S*C/2) registers per lane)
+//     is loaded once and stays in registers while the persistent workgroup walks over its tiles.
+// Epilogue as everywhere: bias + Relu on the accumulators, one store.
+#include <hip/hip_runtime.h>
+
+#include "igemm.h"
+
+namespace glowmi {
+namespace {
+
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int TH = 8, TW = 16;          // output tile (pixels); 4 wavefronts = 2 pixel halves x 2 channel halves
+constexpr int SC_THREADS = 256;
+
+template <int R, int S, int C, int STRIDE>
+struct SmallC {
+  static constexpr int K = R * S * C;                    // reduction length
+  static constexpr int STEPS = (K + 1) / 2;              // MFMA steps (two k each)
+  static constexpr int RUN = S * C;                      // contiguous (s, c) run per filter row
+  static constexpr int PH = (TH - 1) * STRIDE + R;       // patch rows
+  static constexpr int PWC = ((TW - 1) * STRIDE + S) * C;   // patch row length in floats
+  static constexpr int PITCH = ((PWC + 15) / 16) * 16;   // multiple of 16 floats: see bank note below
+  static constexpr int PATCH = (PH + 1) * PITCH;         // +1 row: the k = K padding step reads it
+  static constexpr int LOADS = (PH * PWC + SC_THREADS - 1) / SC_THREADS;
+  static constexpr int lds_bytes = 2 * PATCH * (int)sizeof(float);
+  // patch offset of reduction index v relative to a pixel's patch origin
+  static constexpr int off(int v) { return (v / RUN) * PITCH + (v % RUN); }
+};
+
+template <int R, int S, int C, int STRIDE>
+__global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Problem p, int tiles_y, int tiles_x,
+                                                                    int total_tiles) {
+  using G = SmallC<R, S, C, STRIDE>;
+  extern __shared__ __align__(16) float patch[];          // [2][PH + 1][PITCH]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lrow = lane & 31, lhalf = lane >> 5;
+  const int wpix = wave >> 1;            // which half of the tile's pixels (rows 4*wpix .. 4*wpix+3)
+  const int wch = wave & 1;              // which 32 of the 64 output channels
+  const int n_tile = blockIdx.y;
+
+  const float* __restrict__ X = static_cast<const float*>(p.x);
+  const float* __restrict__ Wt = static_cast<const float*>(p.w);
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  float* __restrict__ Y = static_cast<float*>(p.y);
+
+  // ---- filter fragment: lane (channel, half) keeps W[channel][2t + half] for every step t
+  const int ch = n_tile * 64 + wch * 32 + lrow;
+  const bool ch_ok = ch < p.k;
+  float wfrag[G::STEPS];
+#pragma unroll
+  for (int t = 0; t < G::STEPS; ++t) {
+    const int v = 2 * t + lhalf;
+    wfrag[t] = (ch_ok && v < G::K) ? Wt[(size_t)ch * G::K + v] : 0.f;
+  }
+  const float bv = (ch_ok && bias) ? bias[ch] : 0.f;
+
+  // ---- per-lane patch bases.  Lane = pixel (prow, pcol) of a 32-pixel MFMA block (2 rows x 16)
+  // and half h; step t reads patch[origin + off(2t + h)].  off(2t+1) - off(2t) is 1 except where the
+  // pair straddles two filter rows; a second base register covers those steps, so every read uses a
+  // compile-time immediate.  Bank note: pixels of a row are 6 floats apart and PITCH is a multiple
+  // of 16, so the 64 lanes of one read hit 64 different banks.
+  const int pix_origin = ((wpix * 4 + (lrow >> 4)) * STRIDE) * G::PITCH + (lrow & 15) * STRIDE * C;
+  const int base_norm = pix_origin + lhalf;                          // off(2t+1) = off(2t) + 1
+  const int base_cross = pix_origin + lhalf * (G::PITCH - (G::RUN - 1));   // 2t is the last index of a run
+
+  // zero the padding row of both buffers once (never overwritten by patch loads)
+  for (int i = tid; i < G::PITCH; i += SC_THREADS) {
+    patch[G::PH * G::PITCH + i] = 0.f;
+    patch[G::PATCH + G::PH * G::PITCH + i] = 0.f;
+  }
+
+  float stage[G::LOADS];
+  auto load_patch = [&](int tile) {
+    const int tx = tile % tiles_x;
+    const int t2 = tile / tiles_x;
+    const int ty = t2 % tiles_y;
+    const int img = t2 / tiles_y;
+    const int ih0 = ty * TH * STRIDE - p.pad_t;
+    const int fx0 = (tx * TW * STRIDE - p.pad_l) * C;                // float offset inside an image row
+    const int row_floats = p.w_ * C;
+#pragma unroll
+    for (int i = 0; i < G::LOADS; ++i) {
+      const int idx = tid + i * SC_THREADS;
+      const int pr = idx / G::PWC, pc = idx % G::PWC;               // compile-time divisor
+      const int ih = ih0 + pr, fx = fx0 + pc;
+      const bool ok = idx < G::PH * G::PWC && (unsigned)ih < (unsigned)p.h && (unsigned)fx < (unsigned)row_floats;
+      stage[i] = ok ? X[((size_t)img * p.h + ih) * row_floats + fx] : 0.f;
+    }
+  };
+  auto store_patch = [&](int buf) {
+    float* dst = patch + buf * G::PATCH;
+#pragma unroll
+    for (int i = 0; i < G::LOADS; ++i) {
+      const int idx = tid + i * SC_THREADS;
+      if (idx < G::PH * G::PWC) dst[(idx / G::PWC) * G::PITCH + idx % G::PWC] = stage[i];
+    }
+  };
+
+  // persistent walk over tiles: blockIdx.x, + gridDim.x, ...
+  int tile = blockIdx.x;
+  if (tile >= total_tiles) return;
+  load_patch(tile);
+  store_patch(0);
+  __syncthreads();
+  int buf = 0;
+  for (;;) {
+    const int next = tile + gridDim.x;
+    const bool has_next = next < total_tiles;
+    if (has_next) load_patch(next);
+
+    v16f acc[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { acc[0][e] = 0.f; acc[1][e] = 0.f; }
+    const float* src = patch + buf * G::PATCH;
+    const float* pn = src + base_norm;
+    const float* pc_ = src + base_cross;
+#pragma unroll
+    for (int t = 0; t < G::STEPS; ++t) {
+      constexpr int blk = 2 * STRIDE * G::PITCH;                     // second 32-pixel block: two rows down
+      const bool cross = (2 * t) % G::RUN == G::RUN - 1;             // compile-time after unrolling
+      const float* b = cross ? pc_ : pn;
+      const int o = G::off(2 * t);
+      const float a0 = b[o], a1 = b[o + blk];
+      acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, wfrag[t], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, wfrag[t], acc[1], 0, 0, 0);
+    }
+
+    if (has_next) store_patch(buf ^ 1);
+
+    // ---- epilogue of this tile.  32x32 result: register e of a lane is pixel (e/4)*8 + 4*half + e%4
+    // of the block, channel = lane % 32.
+    {
+      const int tx = tile % tiles_x;
+      const int t2 = tile / tiles_x;
+      const int ty = t2 % tiles_y;
+      const int img = t2 / tiles_y;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int pix = (e >> 2) * 8 + lhalf * 4 + (e & 3);        // 0..31 inside the block
+          const int oh = ty * TH + wpix * 4 + i * 2 + (pix >> 4);
+          const int ow = tx * TW + (pix & 15);
+          if (!ch_ok || oh >= p.oh || ow >= p.ow) continue;
+          float v = acc[i][e] + bv;
+          if (p.act == 1) v = fmaxf(v, 0.f);
+          Y[(((size_t)img * p.oh + oh) * p.ow + ow) * p.k + ch] = v;
+        }
+      }
+    }
+    if (!has_next) break;
+    __syncthreads();
+    buf ^= 1;
+    tile = next;
+  }
+}
+
+template <int R, int S, int C, int STRIDE>
+hipError_t launch_smallc(const Problem& p, hipStream_t stream) {
+  using G = SmallC<R, S, C, STRIDE>;
+  auto kern = conv_smallc_f32_kernel<R, S, C, STRIDE>;
+  static int wg_per_cu = 0, num_cu = 0;     // benign if two threads race: both compute the same values
+  if (wg_per_cu == 0) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes);
+    if (e != hipSuccess) return e;
+    int occ = 0, dev = 0, n = 0;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void*>(kern), SC_THREADS,
+                                                     G::lds_bytes);
+    if (e == hipSuccess) e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    num_cu = n < 1 ? 1 : n;
+    wg_per_cu = occ < 1 ? 1 : occ;
+  }
+  const int tiles_y = (p.oh + TH - 1) / TH, tiles_x = (p.ow + TW - 1) / TW;
+  const long long total = (long long)p.n * tiles_y * tiles_x;
+  const int n_tiles = (p.k + 63) / 64;
+  long long gx = (long long)num_cu * wg_per_cu / n_tiles;
+  if (gx < 1) gx = 1;
+  if (gx > total) gx = total;
+  dim3 grid((unsigned)gx, n_tiles, 1), block(SC_THREADS, 1, 1);
+  hipLaunchKernelGGL(kern, grid, block, G::lds_bytes, stream, p, tiles_y, tiles_x, (int)total);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool smallc_f32_applicable(const Problem& p) {
+  return !p.b_is_kn && p.groups == 1 && p.r == 7 && p.s == 7 && p.c == 3 && p.stride_h == 2 && p.stride_w == 2 &&
+         (long long)p.n * ((p.oh + TH - 1) / TH) * ((p.ow + TW - 1) / TW) < (1LL << 31);
+}
+
+hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** variant) {
+  *variant = "conv_smallc_f32_7x7s2c3";
+  return launch_smallc<7, 7, 3, 2>(p, stream);
+}
+
+}  // namespace glowmi

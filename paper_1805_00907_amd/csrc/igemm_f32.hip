@@ -48,7 +48,8 @@ constexpr int lds_floats() {
   return 2 * (BM * LDK + (B_KN ? BK * (BN + 8) : BN * LDK));
 }
 
-// Decomposition of a reduction index kg into filter row r, filter column s and channel c.
+// Decomposition of a reduction index kg into filter row r, filter column s and channel c, with
+// branch-free stepping (a data-dependent loop here would serialise the wavefront).
 struct Tap {
   int r, s, c;
   __device__ void init(int kg, int cg, int S) {
@@ -57,12 +58,33 @@ struct Tap {
     s = t % S;
     r = t / S;
   }
-  __device__ void advance(int step, int cg, int S) {
-    c += step;
-    while (c >= cg) {
-      c -= cg;
-      if (++s == S) { s = 0; ++r; }
-    }
+  __device__ void advance1(int cg, int S) {
+    c += 1;
+    const bool wc = c == cg;
+    c = wc ? 0 : c;
+    s += wc ? 1 : 0;
+    const bool ws = s == S;
+    s = ws ? 0 : s;
+    r += ws ? 1 : 0;
+  }
+};
+// The same step for a whole slab of BK indices: BK = (dr * S + ds) * cg + dc, one carry per digit.
+struct SlabStep {
+  int dr, ds, dc;
+  __device__ void init(int step, int cg, int S) {
+    dc = step % cg;
+    const int t = step / cg;
+    ds = t % S;
+    dr = t / S;
+  }
+  __device__ void apply(Tap& t, int cg, int S) const {
+    t.c += dc;
+    const bool wc = t.c >= cg;
+    t.c -= wc ? cg : 0;
+    t.s += ds + (wc ? 1 : 0);
+    const bool ws = t.s >= S;
+    t.s -= ws ? S : 0;
+    t.r += dr + (ws ? 1 : 0);
   }
 };
 
@@ -123,6 +145,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
   int a_base[A_PASSES], a_ih0[A_PASSES], a_iw0[A_PASSES];
   int ld_tn = 0, ld_g = 0;          // tile column and group of the item being loaded
   Tap tap;
+  SlabStep slab_step;
+  slab_step.init(BK, p.cg, p.s);
   // A pointwise layer (1x1 filter, stride 1, no padding; FullyConnected is one) maps output row m
   // straight to input pixel m: no (image, oh, ow) decomposition and no border test is needed.
   const bool pointwise = p.r == 1 && p.s == 1 && p.stride_h == 1 && p.stride_w == 1 && p.pad_t == 0 &&
@@ -182,7 +206,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
           const bool ok = kok && (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
           ra[q][e] = ok ? X[a_base[q] + tap_off] : 0.f;
         }
-        t.advance(1, p.cg, p.s);
+        t.advance1(p.cg, p.s);
       }
     }
     // ---------------- B: filter rows (K contiguous) or FC weight rows (N contiguous)
@@ -343,7 +367,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
     for (int slab = chunk; slab < chunk_end; ++slab) {
       const bool more = slab + 1 < cur.slab_end;
       if (more) {
-        tap.advance(BK, p.cg, p.s);
+        slab_step.apply(tap, p.cg, p.s);
         load_global(slab + 1);
       }
       compute(buf);
@@ -531,6 +555,7 @@ constexpr int kNumTilesF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 
 Plan plan_f32(const Problem& p, bool allow_split) {
   Plan pl;
+  if (smallc_f32_applicable(p) && !getenv("GLOWMI_F32_TILE")) allow_split = false;   // own kernel, no workspace
   if (p.b_is_kn && p.M <= 16 && p.groups == 1 && p.k % 4 == 0 && p.Kgemm % 4 == 0 &&
       !getenv("GLOWMI_F32_TILE")) {
     // FC with a handful of rows: stream the weights (fc_skinny16_f32_kernel).  "slabs" are steps of
@@ -605,6 +630,7 @@ hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, b
 }  // namespace
 
 hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
+  if (smallc_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE")) return launch_smallc_f32(p_in, stream, variant);
   Problem p = p_in;
   const Plan plan = plan_f32(p, p.partial != nullptr);
   p.split_k = plan.split_k;
