@@ -172,6 +172,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet50_fp32", choices=WORKLOADS)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of 256 MiB (a kernel of known traffic, used to "
+                         "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build is single-GPU (one MI355X per box); run with --gpus 1. "
@@ -195,6 +198,13 @@ def main():
     def step():
         for l in layers:
             l.launch(stream)
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                    # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
 
     for l in layers:                      # first touch + variant names
         l.launch(stream)

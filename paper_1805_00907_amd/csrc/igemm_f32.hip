@@ -649,8 +649,8 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
                        plan.split_k, plan.slabs_per_split);
     e = hipGetLastError();
   } else {
-  snprintf(name, sizeof(name), "igemm_f32_%s_%s_%s", kTilesF32[plan.tile].name, fc ? "fc" : "conv",
-           vec ? "vec" : "scalar");
+  snprintf(name, sizeof(name), "igemm_f32_%s_%s_%s%s", kTilesF32[plan.tile].name, fc ? "fc" : "conv",
+           vec ? "vec" : "scalar", plan.slabs_per_split > FLUSH_SLABS ? "_longk" : "");
   *variant = name;
   switch (plan.tile) {
     case 0: e = launch_tile<64, 64, 2, 2>(p, plan, stream, fc, vec); break;
