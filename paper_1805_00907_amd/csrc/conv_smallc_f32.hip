@@ -1,6 +1,6 @@
 // fp32 Convolution for layers with very few input channels (a network's first layer: 7x7 stride 2 on
 // 3 channels).  The paper's CPU backend singles out "convolutions with a small number of channels"
-// as one of three kinds that get their own strategy (Section 5.4); this is that kind on gfx950.
+// as one of three kinds that get their own strategy (Section 5.3); this is that kind on gfx950.
 //
 // With 3 channels the generic implicit-GEMM gather degenerates into scalar loads with per-element
 // index arithmetic and the vector ALUs, not the matrix cores, set the pace.  Here instead:

@@ -329,26 +329,29 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
   float* __restrict__ Y = static_cast<float*>(p.y);
   const float* __restrict__ bias = static_cast<const float*>(p.bias);
   auto epilogue = [&](const Item& it) {
+    // One base pointer per lane; every element is then base + a wave-uniform row offset, so the
+    // per-element cost is the arithmetic of the chain itself.  Tiles that lie completely inside the
+    // output skip the bounds tests (uniform branch).
+    float* dst_base = p.split_k == 1 ? Y : static_cast<float*>(p.partial) + (size_t)it.split * p.M * p.k;
+    const int row_base = it.tm * BM + wm * WTM + lhalf * 4;
+    const bool full = (it.tm + 1) * BM <= p.M && (it.tn + 1) * BN <= p.kg;
+    const bool finish = p.split_k == 1;
+    const bool relu = finish && p.act == 1;
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = it.tn * BN + wn * WTN + j * 32 + lrow;
       const bool cok = col < p.kg;
       const int ch = it.g * p.kg + col;
-      const float bv = (cok && p.split_k == 1 && bias) ? bias[ch] : 0.f;
+      const float bv = (cok && finish && bias) ? bias[ch] : 0.f;
+      float* dst = dst_base + (size_t)row_base * p.k + ch;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int row = it.tm * BM + wm * WTM + i * 32 + (e >> 2) * 8 + lhalf * 4 + (e & 3);
-          float v = LONGK ? total[i][j][e] : acc[i][j][e];
-          if (!cok || row >= p.M) continue;
-          if (p.split_k == 1) {
-            v += bv;
-            if (p.act == 1) v = fmaxf(v, 0.f);
-            Y[(size_t)row * p.k + ch] = v;
-          } else {
-            static_cast<float*>(p.partial)[((size_t)it.split * p.M + row) * p.k + ch] = v;
-          }
+          const int r = i * 32 + (e >> 2) * 8 + (e & 3);          // compile-time row inside the wave tile
+          float v = (LONGK ? total[i][j][e] : acc[i][j][e]) + bv;
+          if (relu) v = fmaxf(v, 0.f);
+          if (full || (cok && row_base + r < p.M)) dst[(size_t)r * p.k] = v;
         }
       }
     }
