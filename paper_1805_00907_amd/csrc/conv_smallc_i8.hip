@@ -1,0 +1,254 @@
+// int8 Convolution for the few-input-channel first layer (7x7 stride 2 on 3 channels), quantized form
+// of Section 4 of the paper; the same "small number of channels" kind of convolution that the
+// paper's CPU backend gives its own strategy (Section 5.3).
+//
+// The generic int8 kernel would gather this layer byte by byte.  Here a workgroup keeps the input
+// patch of an 8 x 16 pixel output tile in LDS with every pixel widened from 3 to 4 codes (one
+// dword), so that for one filter row r the codes a pixel needs -- 8 pixels x 4 codes = 32 bytes,
+// the 8th pixel and the 4th code being padding that meets a zero filter code -- are contiguous and
+// 8-byte aligned: one v_mfma_i32_32x32x32_i8 per filter row, its operand two ds_read_b64.
+// Out-of-image pixels are staged as the code x_off (real zero).  The filter fragment (7 rows x 16
+// bytes per lane) lives in registers.  Offsets are removed after the MFMAs with
+//   sum (x - xo) * w = sum x*w - xo * sum w          (this kernel requires a filter offset of 0)
+// then bias, requantize, clamp (Relu = lower bound), pack four channels per dword (the MFMA takes
+// the filter fragment as its row operand), transpose through LDS, 16-byte stores.
+#include <hip/hip_runtime.h>
+
+#include "igemm.h"
+
+namespace glowmi {
+namespace {
+
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int TH = 8, TW = 16;            // output tile in pixels
+constexpr int QS_THREADS = 256;
+constexpr int R = 7, S = 7, C = 3, STRIDE = 2;
+constexpr int PH = (TH - 1) * STRIDE + R;                 // 21 patch rows
+constexpr int PW = (TW - 1) * STRIDE + S + 1;             // 38 pixels: one more than needed, read by the padding tap
+constexpr int PITCH = 40;                                 // dwords per patch row
+constexpr int PATCH = PH * PITCH;                         // dwords
+constexpr int PIX_LOADS = (PH * PW + QS_THREADS - 1) / QS_THREADS;
+constexpr int OUT_PITCH = 64 + 16;                        // bytes per pixel row of the staged output tile
+constexpr int LDS_DWORDS = 2 * PATCH + (TH * TW * OUT_PITCH) / 4 + 64;   // patches, output tile, per-channel term
+
+__device__ __forceinline__ int sum_bytes(int packed) {
+  return __builtin_amdgcn_sdot4(packed, 0x01010101, 0, false);
+}
+
+// Same arithmetic as the generic int8 kernel: round_half_up(acc * mant / 2^shift) + y_off, clamped.
+__device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_off, int lo) {
+  int q;
+  if (shift >= 33) {
+    q = (__mulhi(acc, mant) + (1 << (shift - 33))) >> (shift - 32);
+  } else {
+    long long t = (long long)acc * (long long)mant + (1LL << (shift - 1));
+    t >>= shift;
+    t = t < -4096 ? -4096 : t;
+    t = t > 4096 ? 4096 : t;
+    q = (int)t;
+  }
+  q += y_off;
+  q = q < lo ? lo : q;
+  q = q > 127 ? 127 : q;
+  return q;
+}
+
+__global__ __launch_bounds__(QS_THREADS) void conv_smallc_i8_kernel(const Problem p, int tiles_y, int tiles_x,
+                                                                   int total_tiles) {
+  __shared__ __align__(16) int lds[LDS_DWORDS];
+  int* patch = lds;                                        // [2][PH][PITCH] dwords, one pixel each
+  unsigned char* out = reinterpret_cast<unsigned char*>(lds + 2 * PATCH);   // [128][OUT_PITCH]
+  int* cterm = lds + 2 * PATCH + (TH * TW * OUT_PITCH) / 4;                 // [64]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lrow = lane & 31, lhalf = lane >> 5;
+  const int wpix = wave >> 1;              // pixel rows 4*wpix .. 4*wpix+3 of the tile
+  const int wch = wave & 1;                // channels 32*wch .. +31 of the block's 64
+  const int n_tile = blockIdx.y;
+
+  const signed char* __restrict__ X = static_cast<const signed char*>(p.x);
+  const signed char* __restrict__ Wt = static_cast<const signed char*>(p.w);
+  const int* __restrict__ bias = static_cast<const int*>(p.bias);
+  signed char* __restrict__ Y = static_cast<signed char*>(p.y);
+
+  // ---- filter fragment: lane (channel, half) holds, for each filter row r, the 16 codes
+  // W[ch][r][s = 4*half + 0..3][c = 0..3]; s = 7 and c = 3 do not exist and are zero codes.
+  const int ch = n_tile * 64 + wch * 32 + lrow;
+  const bool ch_ok = ch < p.k;
+  v4i wfrag[R];
+  int wsum = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+#pragma unroll
+    for (int si = 0; si < 4; ++si) {
+      const int s = 4 * lhalf + si;
+      int d = 0;
+#pragma unroll
+      for (int c = 0; c < C; ++c) {
+        const int v = (ch_ok && s < S) ? (int)Wt[((size_t)ch * R + r) * (S * C) + s * C + c] : 0;
+        d |= (v & 0xff) << (8 * c);
+      }
+      wfrag[r][si] = d;
+      wsum += sum_bytes(d);
+    }
+  }
+  wsum += __shfl_xor(wsum, 32);            // both halves of the channel's filter
+  // per-channel additive term: bias - x_off * sum(w)   (modulo 2^32, exact because the true value fits)
+  if (wpix == 0 && lhalf == 0) {
+    unsigned ct = 0u - (unsigned)p.x_off * (unsigned)wsum;
+    if (ch_ok && bias) ct += (unsigned)bias[ch];
+    cterm[wch * 32 + lrow] = (int)ct;
+  }
+
+  const int xo_byte = p.x_off & 0xff;
+  const int xo_pix = (int)((unsigned)xo_byte * 0x01010101u);
+
+  int stage[PIX_LOADS];
+  auto load_patch = [&](int tile) {
+    const int tx = tile % tiles_x;
+    const int t2 = tile / tiles_x;
+    const int ty = t2 % tiles_y;
+    const int img = t2 / tiles_y;
+    const int ih0 = ty * TH * STRIDE - p.pad_t;
+    const int iw0 = tx * TW * STRIDE - p.pad_l;
+#pragma unroll
+    for (int i = 0; i < PIX_LOADS; ++i) {
+      const int idx = tid + i * QS_THREADS;
+      const int pr = idx / PW, pc = idx % PW;
+      const int ih = ih0 + pr, iw = iw0 + pc;
+      const bool ok = idx < PH * PW && (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
+      unsigned d = (unsigned)xo_pix;
+      if (ok) {
+        const signed char* src = X + (((size_t)img * p.h + ih) * p.w_ + iw) * C;
+        d = ((unsigned)src[0] & 0xffu) | (((unsigned)src[1] & 0xffu) << 8) | (((unsigned)src[2] & 0xffu) << 16) |
+            ((unsigned)xo_byte << 24);
+      }
+      stage[i] = (int)d;
+    }
+  };
+  auto store_patch = [&](int buf) {
+    int* dst = patch + buf * PATCH;
+#pragma unroll
+    for (int i = 0; i < PIX_LOADS; ++i) {
+      const int idx = tid + i * QS_THREADS;
+      if (idx < PH * PW) dst[(idx / PW) * PITCH + idx % PW] = stage[i];
+    }
+  };
+
+  // lane = pixel (prow, pcol) of a 32-pixel block (2 rows x 16) as the MFMA column operand
+  const int pix_origin = ((wpix * 4 + (lrow >> 4)) * STRIDE) * PITCH + (lrow & 15) * STRIDE + 4 * lhalf;
+
+  int tile = blockIdx.x;
+  if (tile >= total_tiles) return;
+  load_patch(tile);
+  store_patch(0);
+  __syncthreads();
+  int buf = 0;
+  for (;;) {
+    const int next = tile + gridDim.x;
+    const bool has_next = next < total_tiles;
+    if (has_next) load_patch(next);
+
+    v16i acc[2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { acc[0][e] = 0; acc[1][e] = 0; }
+    const int* src = patch + buf * PATCH + pix_origin;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int* a = src + (r + i * 2 * STRIDE) * PITCH;          // block i: two pixel rows further down
+        const v2i lo2 = *reinterpret_cast<const v2i*>(a);
+        const v2i hi2 = *reinterpret_cast<const v2i*>(a + 2);
+        const v4i av = {lo2[0], lo2[1], hi2[0], hi2[1]};
+        // filter fragment as the row operand: result rows = channels, columns = pixels
+        acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wfrag[r], av, acc[i], 0, 0, 0);
+      }
+    }
+
+    if (has_next) store_patch(buf ^ 1);
+
+    // ---- epilogue: register e of a lane = channel (e/4)*8 + 4*half + e%4 of the wave's 32, pixel lane%32
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int lp = wpix * 64 + i * 32 + lrow;                      // pixel index inside the tile (row-major 8 x 16)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int lc = wch * 32 + q4 * 8 + lhalf * 4;
+        const v4i ct = *reinterpret_cast<const v4i*>(cterm + lc);
+        unsigned packed = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int v = (int)((unsigned)acc[i][q4 * 4 + t] + (unsigned)ct[t]);
+          packed |= ((unsigned)requantize(v, p.mant, p.shift, p.y_off, p.lo) & 0xffu) << (t * 8);
+        }
+        *reinterpret_cast<unsigned*>(out + lp * OUT_PITCH + lc) = packed;
+      }
+    }
+    __syncthreads();
+    {
+      const int tx = tile % tiles_x;
+      const int t2 = tile / tiles_x;
+      const int ty = t2 % tiles_y;
+      const int img = t2 / tiles_y;
+      const bool wide = p.k % 16 == 0;
+      for (int u = tid; u < TH * TW * 4; u += QS_THREADS) {          // 16 bytes of one pixel per thread and pass
+        const int lp = u >> 2, chunk = u & 3;
+        const int oh = ty * TH + (lp >> 4), ow = tx * TW + (lp & 15);
+        const int col = n_tile * 64 + chunk * 16;
+        if (oh >= p.oh || ow >= p.ow || col >= p.k) continue;
+        signed char* dst = Y + (((size_t)img * p.oh + oh) * p.ow + ow) * p.k + col;
+        const unsigned char* s8 = out + lp * OUT_PITCH + chunk * 16;
+        if (wide) {
+          *reinterpret_cast<v4i*>(dst) = *reinterpret_cast<const v4i*>(s8);
+        } else {
+          for (int e = 0; e < 16 && col + e < p.k; ++e) dst[e] = (signed char)s8[e];
+        }
+      }
+    }
+    if (!has_next) break;
+    __syncthreads();
+    buf ^= 1;
+    tile = next;
+  }
+}
+
+}  // namespace
+
+bool smallc_i8_applicable(const Problem& p) {
+  return !p.b_is_kn && p.groups == 1 && p.r == R && p.s == S && p.c == C && p.stride_h == STRIDE &&
+         p.stride_w == STRIDE && p.w_off == 0 &&
+         (long long)p.n * ((p.oh + TH - 1) / TH) * ((p.ow + TW - 1) / TW) < (1LL << 31);
+}
+
+hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant) {
+  *variant = "conv_smallc_i8_7x7s2c3";
+  auto kern = conv_smallc_i8_kernel;
+  static int wg_per_cu = 0, num_cu = 0;     // benign if two threads race: both compute the same values
+  if (wg_per_cu == 0) {
+    int occ = 0, dev = 0, n = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void*>(kern),
+                                                                QS_THREADS, 0);
+    if (e == hipSuccess) e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    num_cu = n < 1 ? 1 : n;
+    wg_per_cu = occ < 1 ? 1 : occ;
+  }
+  const int tiles_y = (p.oh + TH - 1) / TH, tiles_x = (p.ow + TW - 1) / TW;
+  const long long total = (long long)p.n * tiles_y * tiles_x;
+  const int n_tiles = (p.k + 63) / 64;
+  const int per_cu = wg_per_cu < 3 ? wg_per_cu : 3;   // measured: 3 persistent workgroups per CU is the sweet spot
+  long long gx = (long long)num_cu * per_cu / n_tiles;
+  if (gx < 1) gx = 1;
+  if (gx > total) gx = total;
+  dim3 grid((unsigned)gx, n_tiles, 1), block(QS_THREADS, 1, 1);
+  hipLaunchKernelGGL(kern, grid, block, 0, stream, p, tiles_y, tiles_x, (int)total);
+  return hipGetLastError();
+}
+
+}  // namespace glowmi

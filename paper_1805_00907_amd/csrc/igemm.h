@@ -42,6 +42,8 @@ hipError_t launch_i8(const Problem& p, hipStream_t stream, const char** variant)
 // Few-input-channel first-layer convolution (conv_smallc_f32.hip); used by launch_f32 when applicable.
 bool smallc_f32_applicable(const Problem& p);
 hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** variant);
+bool smallc_i8_applicable(const Problem& p);
+hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant);
 
 // Split-K planning shared by the ABI layer (workspace sizing) and the launchers.
 struct Plan {
