@@ -26,6 +26,7 @@ glowmi_status fail(glowmi_status s, const char* fmt, ...) {
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
+constexpr long long kMaxOperandBytes = (1LL << 32) - 64;   // inputs are read through 32-bit buffer offsets
 constexpr int kMaxExtent = 1 << 20;       // spatial / filter extents; keeps row arithmetic in int32
 constexpr int kMaxQuantDepth = 65535;     // reduction depth for which an int32 accumulator cannot overflow
 
@@ -100,6 +101,15 @@ void fill_fc(glowmi::Problem& p, int32_t M, int32_t K, int32_t N) {
   p.Kgemm = K;
   p.split_k = 1;
   p.b_is_kn = 1;
+}
+
+// Input and weight tensors are read with buffer loads whose range check covers 4 GiB.
+glowmi_status set_operand_bytes(glowmi::Problem& p, long long x_elems, long long w_elems, int elem) {
+  if (x_elems * elem > kMaxOperandBytes || w_elems * elem > kMaxOperandBytes)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "input or weight tensor larger than 4 GiB");
+  p.x_bytes = (uint32_t)(x_elems * elem);
+  p.w_bytes = (uint32_t)(w_elems * elem);
+  return GLOWMI_OK;
 }
 
 glowmi_status check_act(glowmi_act act) {
@@ -180,6 +190,7 @@ glowmi_status glowmi_conv2d(const float* x, const float* w, const float* bias, f
   if ((st = check_act(act)) != GLOWMI_OK) return st;
   glowmi::Problem p;
   fill_conv(p, d, geo);
+  if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 4)) != GLOWMI_OK) return st;
   p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
   const size_t need = split_bytes(glowmi::plan_f32(p, true), p);
   p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
@@ -203,6 +214,7 @@ glowmi_status glowmi_fc(const float* a, const float* w, const float* bias, float
   if ((st = check_act(act)) != GLOWMI_OK) return st;
   glowmi::Problem p;
   fill_fc(p, M, K, N);
+  if ((st = set_operand_bytes(p, (long long)M * K, (long long)K * N, 4)) != GLOWMI_OK) return st;
   p.x = a; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
   const size_t need = split_bytes(glowmi::plan_f32(p, true), p);
   p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
@@ -229,6 +241,7 @@ glowmi_status glowmi_qconv2d(const int8_t* x, glowmi_qparam xq, const int8_t* w,
   if ((st = check_act(act)) != GLOWMI_OK) return st;
   glowmi::Problem p;
   fill_conv(p, d, geo);
+  if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 1)) != GLOWMI_OK) return st;
   if ((st = quant_setup(p, xq, wq, yq, act)) != GLOWMI_OK) return st;
   p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
   const size_t need = split_bytes(glowmi::plan_i8(p, true), p);
@@ -254,6 +267,7 @@ glowmi_status glowmi_qfc(const int8_t* a, glowmi_qparam aq, const int8_t* w, glo
   if ((st = check_act(act)) != GLOWMI_OK) return st;
   glowmi::Problem p;
   fill_fc(p, M, K, N);
+  if ((st = set_operand_bytes(p, (long long)M * K, (long long)K * N, 1)) != GLOWMI_OK) return st;
   if ((st = quant_setup(p, aq, wq, yq, act)) != GLOWMI_OK) return st;
   p.x = a; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
   const size_t need = split_bytes(glowmi::plan_i8(p, true), p);

@@ -26,6 +26,7 @@ struct Problem {
   int32_t Kgemm;            // r * s * cg
   int32_t split_k;          // >= 1
   int32_t slabs_per_split;  // reduction slabs each split walks
+  uint32_t x_bytes, w_bytes; // sizes of the input and weight tensors (hardware-checked buffer loads)
   int32_t act;              // 0 none, 1 relu
   int32_t b_is_kn;          // FC weight layout
   // quantized form only

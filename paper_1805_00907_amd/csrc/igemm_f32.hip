@@ -181,9 +181,18 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
   };
 
   v4f ra[A_PASSES], rb[B_PASSES];
+  // raw buffer descriptors (stride 0, range = tensor bytes); 0x00020000 = 32-bit data format word of gfx9
+  const __amdgpu_buffer_rsrc_t rsrc_x =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X), 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_w =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Wt), 0, (int)p.w_bytes, 0x00020000);
+  constexpr unsigned OOB = 0xFFFFFF00u;   // beyond any tensor this library accepts (< 4 GiB - 64)
 
   auto load_global = [&](int slab) {
     const int kg0 = slab * BK + kvec * 4;
+    // Loads go through buffer resources: the hardware range check returns zeros for an offset beyond
+    // the tensor, so an element that must read as zero (padding tap, reduction tail, row or column
+    // outside the problem) simply gets the offset OOB -- no branch, no pre-zeroed registers.
     // ---------------- A: gather from NHWC
     if (VEC) {
       const bool kok = kg0 < p.Kgemm;                       // Kgemm % 4 == 0 on this path
@@ -192,7 +201,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
       for (int q = 0; q < A_PASSES; ++q) {
         const int ih = a_ih0[q] + tap.r, iw = a_iw0[q] + tap.s;
         const bool ok = kok && (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
-        ra[q] = ok ? *reinterpret_cast<const v4f*>(X + a_base[q] + tap_off) : v4f{0.f, 0.f, 0.f, 0.f};
+        const unsigned off = ok ? (unsigned)(a_base[q] + tap_off) * 4u : OOB;
+        ra[q] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0));
       }
     } else {
       Tap t = tap;
@@ -204,7 +214,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
         for (int q = 0; q < A_PASSES; ++q) {
           const int ih = a_ih0[q] + t.r, iw = a_iw0[q] + t.s;
           const bool ok = kok && (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
-          ra[q][e] = ok ? X[a_base[q] + tap_off] : 0.f;
+          const unsigned off = ok ? (unsigned)(a_base[q] + tap_off) * 4u : OOB;
+          ra[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_x, off, 0, 0));
         }
         t.advance1(p.cg, p.s);
       }
@@ -215,12 +226,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
       for (int q = 0; q < B_PASSES; ++q) {
         const int n = ld_tn * BN + row0 + q * ROWS_PER_PASS;
         const bool nok = n < p.kg;
-        const float* src = Wt + (size_t)(ld_g * p.kg + n) * p.Kgemm + kg0;
+        const unsigned row_off = ((unsigned)(ld_g * p.kg + n) * (unsigned)p.Kgemm + (unsigned)kg0) * 4u;
         if (VEC) {
-          rb[q] = (nok && kg0 < p.Kgemm) ? *reinterpret_cast<const v4f*>(src) : v4f{0.f, 0.f, 0.f, 0.f};
+          const unsigned off = (nok && kg0 < p.Kgemm) ? row_off : OOB;
+          rb[q] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, off, 0, 0));
         } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) rb[q][e] = (nok && kg0 + e < p.Kgemm) ? src[e] : 0.f;
+          for (int e = 0; e < 4; ++e) {
+            const unsigned off = (nok && kg0 + e < p.Kgemm) ? row_off + 4u * e : OOB;
+            rb[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_w, off, 0, 0));
+          }
         }
       }
     } else {
@@ -231,12 +246,16 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
       for (int q = 0; q < B_PASSES; ++q) {
         const int kgr = slab * BK + kr0 + q * ROWS;
         const bool kok = kgr < p.Kgemm;
-        const float* src = Wt + (size_t)kgr * p.k + col;
+        const unsigned row_off = ((unsigned)kgr * (unsigned)p.k + (unsigned)col) * 4u;
         if (VEC) {
-          rb[q] = (kok && col < p.k) ? *reinterpret_cast<const v4f*>(src) : v4f{0.f, 0.f, 0.f, 0.f};
+          const unsigned off = (kok && col < p.k) ? row_off : OOB;
+          rb[q] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, off, 0, 0));
         } else {
 #pragma unroll
-          for (int e = 0; e < 4; ++e) rb[q][e] = (kok && col + e < p.k) ? src[e] : 0.f;
+          for (int e = 0; e < 4; ++e) {
+            const unsigned off = (kok && col + e < p.k) ? row_off + 4u * e : OOB;
+            rb[q][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_w, off, 0, 0));
+          }
         }
       }
     }
@@ -604,13 +623,26 @@ Plan plan_f32(const Problem& p, bool allow_split) {
   pl.split_k = 1;
   pl.slabs_per_split = pl.slabs;
   const long long t = (long long)pl.tiles_m * pl.tiles_n * p.groups;
-  if (allow_split && t < 256 && pl.slabs >= 8) {
-    int want = (int)((768 + t - 1) / t);            // aim at ~3 workgroups per compute unit
-    int max_split = pl.slabs / 4;                   // at least 4 slabs per split
-    int sk = want < max_split ? want : max_split;
-    if (sk > 64) sk = 64;
-    if (sk > 1) {
-      pl.slabs_per_split = (pl.slabs + sk - 1) / sk;
+  // Split the reduction when the tiles alone cannot fill the chip.  `slots` = workgroups resident
+  // at once (256 CUs x 4 for the default tile).  Among the split factors that keep at least four
+  // slabs per workgroup, take the smallest one that fills >= 90 % of the slots of its last round,
+  // else the one that fills them best.
+  constexpr long long slots = 1024;
+  if (allow_split && t < slots && pl.slabs >= 8) {
+    const int max_split = pl.slabs / 4 < 64 ? pl.slabs / 4 : 64;
+    int best = 1;
+    double best_u = 0.0;
+    for (int sk = 1; sk <= max_split; ++sk) {
+      const int sps = (pl.slabs + sk - 1) / sk;
+      const int real = (pl.slabs + sps - 1) / sps;          // splits that actually get work
+      if (real != sk) continue;
+      const long long blocks = t * sk;
+      const double u = (double)blocks / (double)(((blocks + slots - 1) / slots) * slots);
+      if (u > best_u + 1e-9) { best_u = u; best = sk; }
+      if (u >= 0.9) { best = sk; break; }
+    }
+    if (best > 1) {
+      pl.slabs_per_split = (pl.slabs + best - 1) / best;
       pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
     }
   }

@@ -490,13 +490,25 @@ Plan plan_i8(const Problem& p, bool allow_split) {
   pl.split_k = 1;
   pl.slabs_per_split = pl.slabs;
   const long long t = (long long)pl.tiles_m * pl.tiles_n * p.groups;
-  if (allow_split && t < 256 && pl.slabs >= 8) {
-    int want = (int)((768 + t - 1) / t);
-    int max_split = pl.slabs / 4;
-    int sk = want < max_split ? want : max_split;
-    if (sk > 64) sk = 64;
-    if (sk > 1) {
-      pl.slabs_per_split = (pl.slabs + sk - 1) / sk;
+  // Split the reduction when the tiles alone cannot fill the chip: among the split factors that keep
+  // at least four slabs per workgroup, the smallest that fills >= 90 % of the resident-workgroup
+  // slots of its last round, else the one that fills them best.
+  constexpr long long slots = 1024;
+  if (allow_split && t < slots && pl.slabs >= 8) {
+    const int max_split = pl.slabs / 4 < 64 ? pl.slabs / 4 : 64;
+    int best = 1;
+    double best_u = 0.0;
+    for (int sk = 1; sk <= max_split; ++sk) {
+      const int sps = (pl.slabs + sk - 1) / sk;
+      const int real = (pl.slabs + sps - 1) / sps;
+      if (real != sk) continue;
+      const long long blocks = t * sk;
+      const double u = (double)blocks / (double)(((blocks + slots - 1) / slots) * slots);
+      if (u > best_u + 1e-9) { best_u = u; best = sk; }
+      if (u >= 0.9) { best = sk; break; }
+    }
+    if (best > 1) {
+      pl.slabs_per_split = (pl.slabs + best - 1) / best;
       pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
     }
   }
