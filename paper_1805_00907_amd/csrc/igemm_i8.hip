@@ -495,7 +495,8 @@ Plan plan_i8(const Problem& p, bool allow_split) {
   // slots of its last round, else the one that fills them best.
   constexpr long long slots = 1024;
   if (allow_split && t < slots && pl.slabs >= 8) {
-    const int max_split = pl.slabs / 4 < 64 ? pl.slabs / 4 : 64;
+    int max_split = pl.slabs / 4 < 64 ? pl.slabs / 4 : 64;
+    if (t >= 256 && max_split > p.Kgemm / 3072) max_split = p.Kgemm / 3072;   // int32 partials are 4x the output
     int best = 1;
     double best_u = 0.0;
     for (int sk = 1; sk <= max_split; ++sk) {
