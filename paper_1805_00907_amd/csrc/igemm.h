@@ -11,6 +11,19 @@
 
 namespace glowmi {
 
+// Division of an index below 2^31 by a fixed divisor d as one multiply-high and one shift:
+// with s = ceil(log2 d) and mul = ceil(2^(31+s) / d), n / d == (n * mul) >> (31 + s) exactly.
+// The host fills it once per call; the kernels use it wherever they take a tile or reduction index
+// apart (output pixel -> image/row/column, reduction index -> filter tap/channel).
+struct FastDiv {
+  uint32_t mul, shift, d;
+#if defined(__HIPCC__)
+  __device__ __forceinline__ int div(int n) const {
+    return d == 1 ? n : (int)(__umulhi((unsigned)n, mul) >> shift);
+  }
+#endif
+};
+
 struct Problem {
   const void* x;      // input  [n][h][w][c]            (float or int8)
   const void* w;      // filter [k][r][s][cg]  or FC weight [Kgemm][k] when b_is_kn
@@ -26,6 +39,7 @@ struct Problem {
   int32_t Kgemm;            // r * s * cg
   int32_t split_k;          // >= 1
   int32_t slabs_per_split;  // reduction slabs each split walks
+  FastDiv div_ohow, div_ow, div_cg, div_s;   // divisors oh*ow, ow, cg, s
   uint32_t x_bytes, w_bytes; // sizes of the input and weight tensors (hardware-checked buffer loads)
   int32_t act;              // 0 none, 1 relu
   int32_t b_is_kn;          // FC weight layout

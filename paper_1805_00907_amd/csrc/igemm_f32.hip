@@ -52,11 +52,11 @@ constexpr int lds_floats() {
 // branch-free stepping (a data-dependent loop here would serialise the wavefront).
 struct Tap {
   int r, s, c;
-  __device__ void init(int kg, int cg, int S) {
-    c = kg % cg;
-    int t = kg / cg;
-    s = t % S;
-    r = t / S;
+  __device__ void init(int kg, int cg, int S, const FastDiv& dcg, const FastDiv& ds) {
+    const int t = dcg.div(kg);
+    c = kg - t * cg;
+    r = ds.div(t);
+    s = t - r * S;
   }
   __device__ void advance1(int cg, int S) {
     c += 1;
@@ -162,9 +162,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
         a_iw0[q] = ok ? 0 : INVALID_ROW;
         a_base[q] = ok ? m * p.c + it.g * p.cg : 0;
       } else if (m < p.M) {
-        const int img = m / ohow;
+        const int img = p.div_ohow.div(m);
         const int rem = m - img * ohow;
-        const int oh = rem / p.ow;
+        const int oh = p.div_ow.div(rem);
         const int ow = rem - oh * p.ow;
         a_ih0[q] = oh * p.stride_h - p.pad_t;
         a_iw0[q] = ow * p.stride_w - p.pad_l;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
     }
     ld_tn = it.tn;
     ld_g = it.g;
-    tap.init(it.slab_begin * BK + kvec * 4, p.cg, p.s);
+    tap.init(it.slab_begin * BK + kvec * 4, p.cg, p.s, p.div_cg, p.div_s);
   };
 
   v4f ra[A_PASSES], rb[B_PASSES];
@@ -594,7 +594,7 @@ Plan plan_f32(const Problem& p, bool allow_split) {
     pl.split_k = 1;
     pl.slabs_per_split = pl.slabs;
     if (allow_split) {
-      int want = (1024 + pl.tiles_n - 1) / pl.tiles_n;
+      int want = (1024 + pl.tiles_n - 1) / pl.tiles_n;   // 1024 workgroups measured best (2048+ is slower)
       int max_split = pl.slabs / (2 * SK_WAVES);
       int sk = want < max_split ? want : max_split;
       if (sk > 128) sk = 128;

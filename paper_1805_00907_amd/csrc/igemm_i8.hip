@@ -35,11 +35,11 @@ constexpr int INVALID_ROW = -(1 << 24);
 
 struct Tap {
   int r, s, c;
-  __device__ void init(int kg, int cg, int S) {
-    c = kg % cg;
-    int t = kg / cg;
-    s = t % S;
-    r = t / S;
+  __device__ void init(int kg, int cg, int S, const FastDiv& dcg, const FastDiv& ds) {
+    const int t = dcg.div(kg);
+    c = kg - t * cg;
+    r = ds.div(t);
+    s = t - r * S;
   }
   __device__ void advance(int step, int cg, int S) {
     c += step;
@@ -123,9 +123,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const 
     for (int q = 0; q < A_PASSES; ++q) {
       const int m = tm * BM + row0 + q * ROWS_PER_PASS;
       if (m < p.M) {
-        const int img = m / ohow;
+        const int img = p.div_ohow.div(m);
         const int rem = m - img * ohow;
-        const int oh = rem / p.ow;
+        const int oh = p.div_ow.div(rem);
         const int ow = rem - oh * p.ow;
         a_ih0[q] = oh * p.stride_h - p.pad_t;
         a_iw0[q] = ow * p.stride_w - p.pad_l;
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const 
   const int k_count = k_hi - slab_begin * BKQ;          // codes this split really reduces over
 
   Tap tap;
-  tap.init(slab_begin * BKQ + kvec * 16, p.cg, p.s);
+  tap.init(slab_begin * BKQ + kvec * 16, p.cg, p.s, p.div_cg, p.div_s);
 
   const int xo_byte = p.x_off & 0xff;
   const int xo_fill = xo_byte * 0x01010101;             // padding = the code of real zero
