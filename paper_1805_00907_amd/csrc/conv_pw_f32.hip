@@ -1,0 +1,259 @@
+// fp32 pointwise (1x1, unpadded) Convolution with a short reduction: the "1x1 on many pixels" kind of
+// layer that makes up two thirds of a residual network's convolutions.  The paper's CPU backend
+// gives each kind of convolution its own strategy (Section 5.3); this is the one for this kind on
+// gfx950.
+//
+// With C = 64..256 input channels the reduction is only a few MFMA steps long, so a tile-per-workgroup
+// GEMM spends most of its time in set-up, barriers and the epilogue.  Here instead
+//   - the filter slice of a workgroup (BN output channels x C, 64 KB) is staged into LDS once and
+//     stays there: one persistent workgroup of eight wavefronts per CU, all reading their B
+//     fragments from it;
+//   - a wavefront owns blocks of 32 output pixels and walks their reduction in chunks of 64
+//     channels.  A chunk (32 pixels x 256 bytes) is fetched with fully coalesced 16-byte loads - every
+//     load instruction covers whole cache lines exactly once - and goes through a private 8.5 KB LDS
+//     region of the wavefront, from which the A fragments are read in MFMA layout.  The region is
+//     private, so no barrier is involved: a wavefront's LDS operations execute in order;
+//   - after the one barrier that publishes the filter slice the wavefronts run independently, two
+//     per SIMD overlapping each other's loads and MFMAs; the next chunk's global loads are in flight
+//     during the MFMAs of the current one;
+//   - work items are (pixel block, 64-channel group); a wavefront takes a contiguous range of them
+//     (with C = 64 consecutive items of one pixel block reuse the staged chunk), so the last round of
+//     the grid is short.
+// Epilogue as everywhere (operator stacking, Section 5.2): bias + Relu on the accumulators, one store.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+
+#include "igemm.h"
+
+namespace glowmi {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int PW_THREADS = 512;
+constexpr int PW_WAVES = PW_THREADS / 64;
+constexpr int PW_CHUNK = 64;                  // channels per staged A chunk
+constexpr int PW_APITCH = PW_CHUNK + 4;       // floats; conflict-free ds_read_b128 / ds_write_b128
+constexpr int PW_AREGION = 32 * PW_APITCH;    // floats per wavefront
+
+template <int K>
+struct Pw {
+  static constexpr int BN = 16384 / K;        // output channels per workgroup: BN * K * 4 = 64 KB
+  static constexpr int NG = BN / 64;          // 64-channel groups per slice (power of two)
+  static constexpr int PITCH = K + 4;         // LDS row pitch of the filter slice in floats
+  static constexpr int KC = K / PW_CHUNK;     // chunks per reduction
+  static constexpr int lds_bytes = (BN * PITCH + PW_WAVES * PW_AREGION + BN) * (int)sizeof(float);
+  static_assert(BN >= 64 && (NG & (NG - 1)) == 0 && K % PW_CHUNK == 0, "slice shape");
+};
+
+// CONTIGUOUS: the input pixel of output pixel m is m itself (unit strides); otherwise it is derived
+// from (image, row, column).
+template <int K, bool CONTIGUOUS>
+__global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Problem p, int row_blocks,
+                                                                   int items_div, int items_rem) {
+  using G = Pw<K>;
+  extern __shared__ __align__(16) float smem[];            // filter slice [BN][PITCH], A regions, bias [BN]
+  float* wlds = smem;
+  float* blds = smem + G::BN * G::PITCH + PW_WAVES * PW_AREGION;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int slice = blockIdx.y;
+  float* alds = smem + G::BN * G::PITCH + wave * PW_AREGION;
+
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  const __amdgpu_buffer_rsrc_t rsrc_x =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.x), 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_w =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w), 0, (int)p.w_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_y =
+      __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
+
+  // ---- filter slice -> LDS.  The slice is one contiguous run of the [k][C] filter; rows past the
+  // last output channel lie past the end of the tensor and the range-checked loads return zeros.
+  {
+    constexpr int V4_PER_ROW = K / 4;
+    constexpr int PASSES = G::BN * V4_PER_ROW / PW_THREADS;
+    const unsigned base = (unsigned)slice * (unsigned)(G::BN * K * 4);
+    v4f stage[PASSES];
+#pragma unroll
+    for (int q = 0; q < PASSES; ++q) {
+      const int i = tid + q * PW_THREADS;
+      stage[q] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, base + (unsigned)i * 16u, 0, 0));
+    }
+#pragma unroll
+    for (int q = 0; q < PASSES; ++q) {
+      const int i = tid + q * PW_THREADS;
+      const int ch = i / V4_PER_ROW, kq = i % V4_PER_ROW;
+      *reinterpret_cast<v4f*>(wlds + ch * G::PITCH + kq * 4) = stage[q];
+    }
+    // the slice's bias values too: read in the epilogue from LDS, so that no global load (whose
+    // wait would also wait for the stores before it) sits between one item's stores and the next
+    if (tid < G::BN) {
+      const int ch = slice * G::BN + tid;
+      blds[tid] = (bias && ch < p.k) ? bias[ch] : 0.f;
+    }
+  }
+  __syncthreads();
+
+  // ---- this wavefront's contiguous range of items (pixel block major, channel group minor)
+  const int wv = blockIdx.x * PW_WAVES + wave;
+  int it = wv * items_div + (wv < items_rem ? wv : items_rem);
+  const int it_end = it + items_div + (wv < items_rem ? 1 : 0);
+  if (it >= it_end) return;
+
+  const int ohow = p.oh * p.ow;
+  const unsigned row_bytes = (unsigned)p.k * 4u;           // output pixel pitch
+  const float floor_value = p.act == 1 ? 0.f : -__builtin_inff();   // Relu as a lower bound
+
+  // Staging of one chunk: load i of a lane covers pixel 4i + lane/16 of the block, 16 bytes at
+  // channel chunk*64 + 4*(lane%16): four whole 256-byte runs per instruction.
+  const int srow = lane >> 4, sq = lane & 15;
+  v4f st[8];
+  auto fetch_chunk = [&](int rb, int chunk) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int m = rb * 32 + 4 * i + srow;
+      if (m >= p.M) m = p.M - 1;                           // results of such rows are never stored
+      int pix = m;
+      if (!CONTIGUOUS) {
+        const int img = p.div_ohow.div(m);
+        const int rem = m - img * ohow;
+        const int oh = p.div_ow.div(rem);
+        const int ow = rem - oh * p.ow;
+        pix = (img * p.h + oh * p.stride_h) * p.w_ + ow * p.stride_w;
+      }
+      const unsigned off = ((unsigned)pix * (unsigned)K + (unsigned)(chunk * PW_CHUNK + 4 * sq)) * 4u;
+      st[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0));
+    }
+  };
+  auto commit_chunk = [&]() {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) *reinterpret_cast<v4f*>(alds + (4 * i + srow) * PW_APITCH + 4 * sq) = st[i];
+  };
+
+  const float* a_lane = alds + l32 * PW_APITCH + 4 * lh;
+  const float* w_lane = wlds + l32 * G::PITCH + 4 * lh;
+
+  fetch_chunk(it / G::NG, 0);
+  commit_chunk();
+  for (; it < it_end; ++it) {
+    const int rb = it / G::NG, ng = it % G::NG;
+    const bool more = it + 1 < it_end;
+    const int rb_next = (it + 1) / G::NG;
+
+    v16f acc0, acc1;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) { acc0[e] = 0.f; acc1[e] = 0.f; }
+    const float* wl = w_lane + ng * 64 * G::PITCH;
+#pragma unroll
+    for (int c = 0; c < G::KC; ++c) {
+      // the chunk after this one: the next of this item, or the first of the next item (with a
+      // single chunk per reduction the staged one is reused while the pixel block stays the same)
+      const bool stage_next = c + 1 < G::KC || (more && (G::KC > 1 || rb_next != rb));
+      if (stage_next) fetch_chunk(c + 1 < G::KC ? rb : rb_next, c + 1 < G::KC ? c + 1 : 0);
+#pragma unroll
+      for (int j = 0; j < PW_CHUNK / 8; ++j) {
+        // all three operands hold channels {8j+t, 8j+4+t} in component t of the two half-waves
+        const v4f a4 = *reinterpret_cast<const v4f*>(a_lane + 8 * j);
+        const v4f b0 = *reinterpret_cast<const v4f*>(wl + c * PW_CHUNK + 8 * j);
+        const v4f b1 = *reinterpret_cast<const v4f*>(wl + 32 * G::PITCH + c * PW_CHUNK + 8 * j);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[t], b0[t], acc0, 0, 0, 0);
+          acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[t], b1[t], acc1, 0, 0, 0);
+        }
+      }
+      // in program order after this chunk's fragment reads: the wavefront's LDS operations execute
+      // in order, so the region is overwritten only once it has been read
+      if (stage_next) commit_chunk();
+    }
+
+    // ---- epilogue: register e of a lane is pixel (e/4)*8 + 4*lh + e%4 of the block, channel l32.
+    // Rows past M fall outside the output buffer's range and the checked stores drop them.
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      const v16f& acc = nb == 0 ? acc0 : acc1;
+      const int ch = slice * G::BN + ng * 64 + nb * 32 + l32;
+      if (ch < p.k) {
+        const float bv = blds[ng * 64 + nb * 32 + l32];
+        unsigned lane_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes + (unsigned)ch * 4u;
+        asm volatile("" : "+v"(lane_off));                 // keep the per-register row offsets scalar
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float v = fmaxf(acc[e] + bv, floor_value);
+          const unsigned off = lane_off + (unsigned)((e >> 2) * 8 + (e & 3)) * row_bytes;
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, off, 0, 0);
+        }
+      }
+    }
+  }
+}
+
+template <int K, bool CONTIGUOUS>
+hipError_t launch_pw(const Problem& p, hipStream_t stream) {
+  using G = Pw<K>;
+  auto kern = conv_pw_f32_kernel<K, CONTIGUOUS>;
+  static int num_cu = 0;          // benign if two threads race: both compute the same value
+  if (num_cu == 0) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes);
+    if (e != hipSuccess) return e;
+    int dev = 0, n = 0;
+    e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    num_cu = n < 1 ? 1 : n;
+  }
+  const int slices = (p.k + G::BN - 1) / G::BN;
+  const int row_blocks = (p.M + 31) / 32;
+  const long long items = (long long)row_blocks * G::NG;          // per slice
+  long long wgs = (long long)num_cu / slices;             // one persistent workgroup per CU
+  if (wgs < 1) wgs = 1;
+  if (wgs > (items + PW_WAVES - 1) / PW_WAVES) wgs = (items + PW_WAVES - 1) / PW_WAVES;
+  const long long waves = wgs * PW_WAVES;
+  dim3 grid((unsigned)wgs, (unsigned)slices, 1), block(PW_THREADS, 1, 1);
+  hipLaunchKernelGGL(kern, grid, block, G::lds_bytes, stream, p, row_blocks, (int)(items / waves),
+                     (int)(items % waves));
+  return hipGetLastError();
+}
+
+int pw_min_items() {
+  if (const char* env = getenv("GLOWMI_F32_PW_MIN_ITEMS")) return atoi(env);   // experiments
+  return 1024;
+}
+
+}  // namespace
+
+bool pw_f32_applicable(const Problem& p) {
+  if (p.b_is_kn || p.groups != 1 || p.r != 1 || p.s != 1 || p.pad_t != 0 || p.pad_l != 0) return false;
+  if (p.c != 64 && p.c != 128 && p.c != 256) return false;
+  // bottom/right padding would make output pixels read outside the image
+  if ((long long)(p.oh - 1) * p.stride_h >= p.h || (long long)(p.ow - 1) * p.stride_w >= p.w_) return false;
+  if ((unsigned long long)p.M * (unsigned long long)p.k * 4ull > 0xF0000000ull || p.k > 65536) return false;
+  if (p.w_bytes > 0x7FFFFFFFu) return false;
+  const long long items = (long long)((p.M + 31) / 32) * (16384 / p.c / 64);
+  return items >= pw_min_items() && items < (1LL << 30);
+}
+
+hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** variant) {
+  const bool contiguous = p.stride_h == 1 && p.stride_w == 1;
+  switch (p.c) {
+    case 64:
+      *variant = contiguous ? "conv_pw_f32_c64" : "conv_pw_f32_c64_strided";
+      return contiguous ? launch_pw<64, true>(p, stream) : launch_pw<64, false>(p, stream);
+    case 128:
+      *variant = contiguous ? "conv_pw_f32_c128" : "conv_pw_f32_c128_strided";
+      return contiguous ? launch_pw<128, true>(p, stream) : launch_pw<128, false>(p, stream);
+    case 256:
+      *variant = contiguous ? "conv_pw_f32_c256" : "conv_pw_f32_c256_strided";
+      return contiguous ? launch_pw<256, true>(p, stream) : launch_pw<256, false>(p, stream);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+}  // namespace glowmi

@@ -57,6 +57,9 @@ hipError_t launch_i8(const Problem& p, hipStream_t stream, const char** variant)
 // Few-input-channel first-layer convolution (conv_smallc_f32.hip); used by launch_f32 when applicable.
 bool smallc_f32_applicable(const Problem& p);
 hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** variant);
+// Pointwise convolution with a short reduction and many pixels (conv_pw_f32.hip).
+bool pw_f32_applicable(const Problem& p);
+hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** variant);
 bool smallc_i8_applicable(const Problem& p);
 hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant);
 

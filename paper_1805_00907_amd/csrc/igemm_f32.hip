@@ -577,7 +577,8 @@ constexpr int kNumTilesF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 
 Plan plan_f32(const Problem& p, bool allow_split) {
   Plan pl;
-  if (smallc_f32_applicable(p) && !getenv("GLOWMI_F32_TILE")) allow_split = false;   // own kernel, no workspace
+  if ((smallc_f32_applicable(p) || pw_f32_applicable(p)) && !getenv("GLOWMI_F32_TILE"))
+    allow_split = false;   // kernels of their own, no workspace
   if (p.b_is_kn && p.M <= 16 && p.groups == 1 && p.k % 4 == 0 && p.Kgemm % 4 == 0 &&
       !getenv("GLOWMI_F32_TILE")) {
     // FC with a handful of rows: stream the weights (fc_skinny16_f32_kernel).  "slabs" are steps of
@@ -676,6 +677,7 @@ hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, b
 
 hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
   if (smallc_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE")) return launch_smallc_f32(p_in, stream, variant);
+  if (pw_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE")) return launch_pw_f32(p_in, stream, variant);
   Problem p = p_in;
   const Plan plan = plan_f32(p, p.partial != nullptr);
   p.split_k = plan.split_k;

@@ -40,13 +40,31 @@ def poison(shape, dtype):
     return torch.full(shape, 77, dtype=dtype, device=DEV)
 
 
+GUARD = 4096   # elements of untouched poison kept on either side of a guarded output
+
+
+def guarded(shape, dtype):
+    """A poisoned output inside a larger poisoned allocation: (whole buffer, view of the output)."""
+    count = int(np.prod(shape))
+    whole = poison((count + 2 * GUARD,), dtype)
+    return whole, whole[GUARD:GUARD + count].view(shape)
+
+
+def guards_intact(whole, dtype):
+    lo, hi = whole[:GUARD], whole[-GUARD:]
+    if dtype == torch.float32:
+        return bool(torch.isnan(lo).all() and torch.isnan(hi).all())
+    return bool((lo == 77).all() and (hi == 77).all())
+
+
 def gpu_conv2d_f32(x, w, b, desc, act, use_workspace=True):
     oh, ow = glowmi.conv_out_shape(desc)
     xd, wd, bd = dev(x), dev(w), dev(b)
-    y = poison((desc.n, oh, ow, desc.k), torch.float32)
+    whole, y = guarded((desc.n, oh, ow, desc.k), torch.float32)
     ws = workspace(glowmi.conv2d_workspace_bytes(desc)) if use_workspace else None
     glowmi.conv2d(xd, wd, bd, y, desc, act, ws)
     torch.cuda.synchronize()
+    assert guards_intact(whole, torch.float32), "write outside the output tensor"
     return y.cpu().numpy(), glowmi.last_variant()
 
 

@@ -88,6 +88,53 @@ def test_conv2d_f32_resnet_batch1(li):
         G.assert_close_f32(got, ref, f"{layer.name} ws {use_ws} [{variant}]")
 
 
+# Pointwise-convolution kernel (LDS-resident filter slice, A fragments straight from global memory).
+# n  h  w  c  k  stride
+PW_SHAPES = [
+    (2, 20, 21, 64, 256, 1),      # M = 840: ragged last pixel block, all four channel groups
+    (1, 33, 31, 64, 72, 1),       # ragged N: one full 64-channel group + 8 channels
+    (3, 17, 19, 128, 200, 2),     # stride 2, C = 128, two filter slices, ragged N
+    (2, 15, 15, 256, 64, 1),      # C = 256, one channel group
+    (1, 13, 29, 256, 130, 2),     # C = 256, three slices, ragged N, stride 2
+    (1, 1, 5, 64, 64, 1),         # fewer pixels than one block
+]
+
+
+@pytest.mark.parametrize("shape", PW_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_NONE])
+def test_conv2d_f32_pointwise(shape, act, monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_F32_PW_MIN_ITEMS", "1")     # take the pointwise kernel at any size
+    n, h, w, c, k, st = shape
+    rng = np.random.default_rng(4000 + 7 * c + k)
+    x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
+    wt = (rng.uniform(-1, 1, size=(k, 1, 1, c)) / np.sqrt(c)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(k,)).astype(np.float32)
+    ref = oracle.conv2d_f32(x, wt, b, (st, st), (0, 0, 0, 0), 1, act=act)
+    desc = G.make_desc(x.shape, wt.shape, (st, st), (0, 0, 0, 0), 1)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, act)
+    assert variant.startswith("conv_pw_f32"), variant
+    G.assert_close_f32(got, ref, f"pointwise {shape} act {act} [{variant}]")
+    got, variant = G.gpu_conv2d_f32(x, wt, None, desc, act)
+    G.assert_close_f32(got, oracle.conv2d_f32(x, wt, None, (st, st), (0, 0, 0, 0), 1, act=act),
+                       f"pointwise {shape} without bias")
+
+
+def test_conv2d_f32_pointwise_not_taken_with_bottom_padding(monkeypatch):
+    """A 1x1 convolution padded at the bottom/right reads outside the image: generic kernel."""
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_F32_PW_MIN_ITEMS", "1")
+    rng = np.random.default_rng(4100)
+    x = rng.uniform(-1, 1, size=(1, 9, 9, 64)).astype(np.float32)
+    wt = (rng.uniform(-1, 1, size=(64, 1, 1, 64)) / 8).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(64,)).astype(np.float32)
+    pads = (0, 0, 1, 2)
+    ref = oracle.conv2d_f32(x, wt, b, (1, 1), pads, 1, act=wl.ACT_NONE)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, G.make_desc(x.shape, wt.shape, (1, 1), pads, 1), wl.ACT_NONE)
+    assert not variant.startswith("conv_pw_f32"), variant
+    G.assert_close_f32(got, ref, "1x1 with bottom/right padding")
+
+
 FC_SHAPES = [(1, 64, 8), (5, 37, 11), (16, 512, 1000), (3, 1000, 257), (64, 2048, 1000), (1, 2048, 1000),
              (130, 260, 132), (33, 4096, 64), (256, 300, 520)]
 
