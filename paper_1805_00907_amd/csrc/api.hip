@@ -66,23 +66,11 @@ glowmi_status check_desc(const glowmi_conv_desc* d, Geometry* geo) {
   return GLOWMI_OK;
 }
 
-glowmi::FastDiv make_fastdiv(uint32_t d) {
-  glowmi::FastDiv f;
-  f.d = d;
-  uint32_t s = 0;
-  while ((1ull << s) < d) ++s;                        // ceil(log2 d)
-  if (d <= 1) { f.mul = 0; f.shift = 0; return f; }   // the device side short-cuts d == 1
-  const unsigned long long num = 1ull << (31 + s);
-  f.mul = (uint32_t)((num + d - 1) / d);              // < 2^32 because d > 2^(s-1)
-  f.shift = s - 1;
-  return f;
-}
-
 void fill_divs(glowmi::Problem& p) {
-  p.div_ohow = make_fastdiv((uint32_t)p.oh * (uint32_t)p.ow);
-  p.div_ow = make_fastdiv((uint32_t)p.ow);
-  p.div_cg = make_fastdiv((uint32_t)p.cg);
-  p.div_s = make_fastdiv((uint32_t)p.s);
+  p.div_ohow = glowmi::make_fastdiv((uint32_t)p.oh * (uint32_t)p.ow);
+  p.div_ow = glowmi::make_fastdiv((uint32_t)p.ow);
+  p.div_cg = glowmi::make_fastdiv((uint32_t)p.cg);
+  p.div_s = glowmi::make_fastdiv((uint32_t)p.s);
 }
 
 void fill_conv(glowmi::Problem& p, const glowmi_conv_desc* d, const Geometry& geo) {

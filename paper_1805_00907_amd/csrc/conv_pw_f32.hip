@@ -3,7 +3,7 @@
 // gives each kind of convolution its own strategy (Section 5.3); this is the one for this kind on
 // gfx950.
 //
-// With C = 64..256 input channels the reduction is only a few MFMA steps long, so a tile-per-workgroup
+// With C = 64 or 128 input channels the reduction is only a few MFMA steps long, so a tile-per-workgroup
 // GEMM spends most of its time in set-up, barriers and the epilogue.  Here instead
 //   - the filter slice of a workgroup (BN output channels x C, 64 KB) is staged into LDS once and
 //     stays there: one persistent workgroup of eight wavefronts per CU, all reading their B
@@ -48,11 +48,19 @@ struct Pw {
   static_assert(BN >= 64 && (NG & (NG - 1)) == 0 && K % PW_CHUNK == 0, "slice shape");
 };
 
+// How the items of one filter slice are dealt to the wavefronts of its workgroups: ngc 64-channel
+// groups per pixel block that really exist in the slice, items = pixel blocks * ngc, wavefront wv
+// takes items_div (+1 for the first items_rem wavefronts) consecutive ones.
+struct PwRange {
+  int ngc, items_div, items_rem;
+  FastDiv div_ngc;
+};
+
 // CONTIGUOUS: the input pixel of output pixel m is m itself (unit strides); otherwise it is derived
 // from (image, row, column).
 template <int K, bool CONTIGUOUS>
-__global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Problem p, int row_blocks,
-                                                                   int items_div, int items_rem) {
+__global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Problem p, const PwRange full,
+                                                                   const PwRange last) {
   using G = Pw<K>;
   extern __shared__ __align__(16) float smem[];            // filter slice [BN][PITCH], A regions, bias [BN]
   float* wlds = smem;
@@ -73,38 +81,12 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
   const __amdgpu_buffer_rsrc_t rsrc_y =
       __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
 
-  // ---- filter slice -> LDS.  The slice is one contiguous run of the [k][C] filter; rows past the
-  // last output channel lie past the end of the tensor and the range-checked loads return zeros.
-  {
-    constexpr int V4_PER_ROW = K / 4;
-    constexpr int PASSES = G::BN * V4_PER_ROW / PW_THREADS;
-    const unsigned base = (unsigned)slice * (unsigned)(G::BN * K * 4);
-    v4f stage[PASSES];
-#pragma unroll
-    for (int q = 0; q < PASSES; ++q) {
-      const int i = tid + q * PW_THREADS;
-      stage[q] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, base + (unsigned)i * 16u, 0, 0));
-    }
-#pragma unroll
-    for (int q = 0; q < PASSES; ++q) {
-      const int i = tid + q * PW_THREADS;
-      const int ch = i / V4_PER_ROW, kq = i % V4_PER_ROW;
-      *reinterpret_cast<v4f*>(wlds + ch * G::PITCH + kq * 4) = stage[q];
-    }
-    // the slice's bias values too: read in the epilogue from LDS, so that no global load (whose
-    // wait would also wait for the stores before it) sits between one item's stores and the next
-    if (tid < G::BN) {
-      const int ch = slice * G::BN + tid;
-      blds[tid] = (bias && ch < p.k) ? bias[ch] : 0.f;
-    }
-  }
-  __syncthreads();
-
   // ---- this wavefront's contiguous range of items (pixel block major, channel group minor)
+  const PwRange& range = slice == (int)gridDim.y - 1 ? last : full;    // the last slice may be narrower
   const int wv = blockIdx.x * PW_WAVES + wave;
-  int it = wv * items_div + (wv < items_rem ? wv : items_rem);
-  const int it_end = it + items_div + (wv < items_rem ? 1 : 0);
-  if (it >= it_end) return;
+  int it = wv * range.items_div + (wv < range.items_rem ? wv : range.items_rem);
+  const int it_end = it + range.items_div + (wv < range.items_rem ? 1 : 0);
+  auto block_of = [&](int item) { return range.div_ngc.div(item); };
 
   const int ohow = p.oh * p.ow;
   const unsigned row_bytes = (unsigned)p.k * 4u;           // output pixel pitch
@@ -136,15 +118,46 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
     for (int i = 0; i < 8; ++i) *reinterpret_cast<v4f*>(alds + (4 * i + srow) * PW_APITCH + 4 * sq) = st[i];
   };
 
+  // the first chunk's loads go out before the filter slice's, so both latencies overlap
+  const bool has_work = it < it_end;
+  if (has_work) fetch_chunk(block_of(it), 0);
+
+  // ---- filter slice -> LDS.  The slice is one contiguous run of the [k][C] filter; rows past the
+  // last output channel lie past the end of the tensor and the range-checked loads return zeros.
+  {
+    constexpr int V4_PER_ROW = K / 4;
+    constexpr int PASSES = G::BN * V4_PER_ROW / PW_THREADS;
+    const unsigned base = (unsigned)slice * (unsigned)(G::BN * K * 4);
+    v4f stage[PASSES];
+#pragma unroll
+    for (int q = 0; q < PASSES; ++q) {
+      const int i = tid + q * PW_THREADS;
+      stage[q] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, base + (unsigned)i * 16u, 0, 0));
+    }
+#pragma unroll
+    for (int q = 0; q < PASSES; ++q) {
+      const int i = tid + q * PW_THREADS;
+      const int ch = i / V4_PER_ROW, kq = i % V4_PER_ROW;
+      *reinterpret_cast<v4f*>(wlds + ch * G::PITCH + kq * 4) = stage[q];
+    }
+    // the slice's bias values too: read in the epilogue from LDS, so that no global load (whose
+    // wait would also wait for the stores before it) sits between one item's stores and the next
+    if (tid < G::BN) {
+      const int ch = slice * G::BN + tid;
+      blds[tid] = (bias && ch < p.k) ? bias[ch] : 0.f;
+    }
+  }
+  __syncthreads();
+
   const float* a_lane = alds + l32 * PW_APITCH + 4 * lh;
   const float* w_lane = wlds + l32 * G::PITCH + 4 * lh;
 
-  fetch_chunk(it / G::NG, 0);
+  if (!has_work) return;
   commit_chunk();
   for (; it < it_end; ++it) {
-    const int rb = it / G::NG, ng = it % G::NG;
+    const int rb = block_of(it), ng = it - rb * range.ngc;
     const bool more = it + 1 < it_end;
-    const int rb_next = (it + 1) / G::NG;
+    const int rb_next = block_of(it + 1);
 
     v16f acc0, acc1;
 #pragma unroll
@@ -211,14 +224,24 @@ hipError_t launch_pw(const Problem& p, hipStream_t stream) {
   }
   const int slices = (p.k + G::BN - 1) / G::BN;
   const int row_blocks = (p.M + 31) / 32;
-  const long long items = (long long)row_blocks * G::NG;          // per slice
+  const int groups_last = (p.k - (slices - 1) * G::BN + 63) / 64;      // 64-channel groups of the last slice
+  const int groups_full = slices > 1 ? G::NG : groups_last;
   long long wgs = (long long)num_cu / slices;             // one persistent workgroup per CU
   if (wgs < 1) wgs = 1;
-  if (wgs > (items + PW_WAVES - 1) / PW_WAVES) wgs = (items + PW_WAVES - 1) / PW_WAVES;
+  const long long items_max = (long long)row_blocks * groups_full;
+  if (wgs > (items_max + PW_WAVES - 1) / PW_WAVES) wgs = (items_max + PW_WAVES - 1) / PW_WAVES;
   const long long waves = wgs * PW_WAVES;
+  auto range_of = [&](int ngc) {
+    PwRange r;
+    const long long items = (long long)row_blocks * ngc;
+    r.ngc = ngc;
+    r.items_div = (int)(items / waves);
+    r.items_rem = (int)(items % waves);
+    r.div_ngc = make_fastdiv((uint32_t)ngc);
+    return r;
+  };
   dim3 grid((unsigned)wgs, (unsigned)slices, 1), block(PW_THREADS, 1, 1);
-  hipLaunchKernelGGL(kern, grid, block, G::lds_bytes, stream, p, row_blocks, (int)(items / waves),
-                     (int)(items % waves));
+  hipLaunchKernelGGL(kern, grid, block, G::lds_bytes, stream, p, range_of(groups_full), range_of(groups_last));
   return hipGetLastError();
 }
 
@@ -231,12 +254,13 @@ int pw_min_items() {
 
 bool pw_f32_applicable(const Problem& p) {
   if (p.b_is_kn || p.groups != 1 || p.r != 1 || p.s != 1 || p.pad_t != 0 || p.pad_l != 0) return false;
-  if (p.c != 64 && p.c != 128 && p.c != 256) return false;
+  if (p.c != 64 && p.c != 128) return false;   // longer reductions amortise the generic kernel's set-up
   // bottom/right padding would make output pixels read outside the image
   if ((long long)(p.oh - 1) * p.stride_h >= p.h || (long long)(p.ow - 1) * p.stride_w >= p.w_) return false;
   if ((unsigned long long)p.M * (unsigned long long)p.k * 4ull > 0xF0000000ull || p.k > 65536) return false;
   if (p.w_bytes > 0x7FFFFFFFu) return false;
-  const long long items = (long long)((p.M + 31) / 32) * (16384 / p.c / 64);
+  const int bn = 16384 / p.c;
+  const long long items = (long long)((p.M + 31) / 32) * ((p.k < bn ? p.k : bn) + 63) / 64;
   return items >= pw_min_items() && items < (1LL << 30);
 }
 
@@ -249,9 +273,6 @@ hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** vari
     case 128:
       *variant = contiguous ? "conv_pw_f32_c128" : "conv_pw_f32_c128_strided";
       return contiguous ? launch_pw<128, true>(p, stream) : launch_pw<128, false>(p, stream);
-    case 256:
-      *variant = contiguous ? "conv_pw_f32_c256" : "conv_pw_f32_c256_strided";
-      return contiguous ? launch_pw<256, true>(p, stream) : launch_pw<256, false>(p, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -24,6 +24,19 @@ struct FastDiv {
 #endif
 };
 
+inline FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  f.mul = 0;
+  f.shift = 0;
+  if (d <= 1) return f;                                // the device side short-cuts d == 1
+  uint32_t s = 0;
+  while ((1ull << s) < d) ++s;                         // ceil(log2 d)
+  f.mul = (uint32_t)(((1ull << (31 + s)) + d - 1) / d);   // < 2^32 because d > 2^(s-1)
+  f.shift = s - 1;
+  return f;
+}
+
 struct Problem {
   const void* x;      // input  [n][h][w][c]            (float or int8)
   const void* w;      // filter [k][r][s][cg]  or FC weight [Kgemm][k] when b_is_kn

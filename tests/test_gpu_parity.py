@@ -94,8 +94,10 @@ PW_SHAPES = [
     (2, 20, 21, 64, 256, 1),      # M = 840: ragged last pixel block, all four channel groups
     (1, 33, 31, 64, 72, 1),       # ragged N: one full 64-channel group + 8 channels
     (3, 17, 19, 128, 200, 2),     # stride 2, C = 128, two filter slices, ragged N
-    (2, 15, 15, 256, 64, 1),      # C = 256, one channel group
-    (1, 13, 29, 256, 130, 2),     # C = 256, three slices, ragged N, stride 2
+    (2, 15, 15, 128, 64, 1),      # C = 128, one channel group
+    (1, 13, 29, 128, 330, 2),     # C = 128, three slices, ragged N, stride 2
+    (1, 9, 9, 64, 520, 1),        # three slices, the last with a single channel group of 8
+    (2, 12, 12, 64, 64, 1),       # one channel group out of the slice's four
     (1, 1, 5, 64, 64, 1),         # fewer pixels than one block
 ]
 
