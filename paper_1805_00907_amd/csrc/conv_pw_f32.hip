@@ -25,6 +25,7 @@
 #include <cstdlib>
 
 #include "igemm.h"
+#include "pw_common.h"
 
 namespace glowmi {
 namespace {
@@ -46,14 +47,6 @@ struct Pw {
   static constexpr int KC = K / PW_CHUNK;     // chunks per reduction
   static constexpr int lds_bytes = (BN * PITCH + PW_WAVES * PW_AREGION + BN) * (int)sizeof(float);
   static_assert(BN >= 64 && (NG & (NG - 1)) == 0 && K % PW_CHUNK == 0, "slice shape");
-};
-
-// How the items of one filter slice are dealt to the wavefronts of its workgroups: ngc 64-channel
-// groups per pixel block that really exist in the slice, items = pixel blocks * ngc, wavefront wv
-// takes items_div (+1 for the first items_rem wavefronts) consecutive ones.
-struct PwRange {
-  int ngc, items_div, items_rem;
-  FastDiv div_ngc;
 };
 
 // CONTIGUOUS: the input pixel of output pixel m is m itself (unit strides); otherwise it is derived
@@ -231,17 +224,9 @@ hipError_t launch_pw(const Problem& p, hipStream_t stream) {
   const long long items_max = (long long)row_blocks * groups_full;
   if (wgs > (items_max + PW_WAVES - 1) / PW_WAVES) wgs = (items_max + PW_WAVES - 1) / PW_WAVES;
   const long long waves = wgs * PW_WAVES;
-  auto range_of = [&](int ngc) {
-    PwRange r;
-    const long long items = (long long)row_blocks * ngc;
-    r.ngc = ngc;
-    r.items_div = (int)(items / waves);
-    r.items_rem = (int)(items % waves);
-    r.div_ngc = make_fastdiv((uint32_t)ngc);
-    return r;
-  };
   dim3 grid((unsigned)wgs, (unsigned)slices, 1), block(PW_THREADS, 1, 1);
-  hipLaunchKernelGGL(kern, grid, block, G::lds_bytes, stream, p, range_of(groups_full), range_of(groups_last));
+  hipLaunchKernelGGL(kern, grid, block, G::lds_bytes, stream, p,
+                     make_pw_range(row_blocks, groups_full, waves), make_pw_range(row_blocks, groups_last, waves));
   return hipGetLastError();
 }
 

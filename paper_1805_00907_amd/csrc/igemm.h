@@ -73,6 +73,8 @@ hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** 
 // Pointwise convolution with a short reduction and many pixels (conv_pw_f32.hip).
 bool pw_f32_applicable(const Problem& p);
 hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** variant);
+bool pw_i8_applicable(const Problem& p);
+hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** variant);
 bool smallc_i8_applicable(const Problem& p);
 hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant);
 

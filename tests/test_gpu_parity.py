@@ -176,6 +176,71 @@ def test_qconv2d(i, dist, w_off):
             G.assert_equal_i8(got, ref, f"qconv case {i} {dist} w_off {w_off} act {act} ws {use_ws} [{variant}]")
 
 
+# int8 pointwise kernel: output channels in multiples of 16, filter offset 0.
+# n  h  w  c  k  stride
+PWQ_SHAPES = [
+    (2, 20, 21, 64, 256, 1),      # ragged last pixel block, four channel groups
+    (1, 33, 31, 64, 80, 1),       # ragged N: one full group + 16 channels
+    (3, 17, 19, 128, 208, 2),     # stride 2, C = 128
+    (2, 15, 15, 256, 64, 1),      # C = 256, one channel group
+    (1, 13, 29, 256, 336, 2),     # C = 256, three slices of 128, ragged, stride 2
+    (1, 9, 9, 64, 528, 1),        # three slices, the last with a single run of 16 channels
+    (1, 1, 5, 128, 48, 1),        # fewer pixels than one block
+]
+
+
+@pytest.mark.parametrize("shape", PWQ_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dist", ["normal", "uniform"])
+def test_qconv2d_pointwise(shape, dist, monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")      # take the pointwise kernel at any size
+    n, h, w, c, k, st = shape
+    layer = wl.ConvLayer("pw", n, h, w, c, k, 1, 1, st, 0, 1)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 5000 + 3 * c + k, dist=dist, w_off=0)
+    desc = G.make_desc(xq.shape, wq.shape, (st, st), (0, 0, 0, 0), 1)
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                             (st, st), (0, 0, 0, 0), 1, act=act)
+        got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, act)
+        assert variant.startswith("conv_pw_i8"), variant
+        G.assert_equal_i8(got, ref, f"pointwise int8 {shape} {dist} act {act} [{variant}]")
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, None, qp.y_scale, qp.y_off,
+                         (st, st), (0, 0, 0, 0), 1, act=wl.ACT_NONE)
+    got, _ = G.gpu_qconv2d(xq, wq, None, qp, desc, wl.ACT_NONE)
+    G.assert_equal_i8(got, ref, f"pointwise int8 {shape} without bias")
+
+
+@pytest.mark.parametrize("mr_exp", [-1, 1, -3, -8])
+def test_qconv2d_pointwise_multipliers(mr_exp, monkeypatch):
+    """Both requantize forms of the pointwise kernel (64-bit for multipliers from 1/4 up)."""
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")
+    rng = np.random.default_rng(170 + mr_exp)
+    xq = rng.integers(-6, 7, size=(2, 9, 9, 64), dtype=np.int8)
+    wq = rng.integers(-5, 6, size=(48, 1, 1, 64), dtype=np.int8)
+    bq = rng.integers(-50, 50, size=(48,), dtype=np.int32)
+    qp = wl.QParams(0.8, 1, float(2.0 ** mr_exp), 0, 1.0, -3)
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                         (1, 1), (0, 0, 0, 0), 1, act=wl.ACT_RELU)
+    got, variant = G.gpu_qconv2d(xq, wq, bq, qp, G.make_desc(xq.shape, wq.shape, (1, 1), (0, 0, 0, 0), 1),
+                                 wl.ACT_RELU)
+    assert variant.startswith("conv_pw_i8"), variant
+    G.assert_equal_i8(got, ref, f"pointwise int8 multiplier 0.8*2^{mr_exp}")
+
+
+def test_qconv2d_pointwise_not_taken_with_filter_offset(monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")
+    layer = wl.ConvLayer("pw", 1, 9, 9, 64, 64, 1, 1, 1, 0, 1)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 5999, dist="normal", w_off=5)
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                         (1, 1), (0, 0, 0, 0), 1, act=wl.ACT_RELU)
+    got, variant = G.gpu_qconv2d(xq, wq, bq, qp, G.make_desc(xq.shape, wq.shape, (1, 1), (0, 0, 0, 0), 1),
+                                 wl.ACT_RELU)
+    assert not variant.startswith("conv_pw_i8"), variant
+    G.assert_equal_i8(got, ref, "1x1 int8 with a filter offset")
+
+
 def test_qconv2d_zero_point_padding():
     """Input constantly at its offset: every output, borders included, is requantize(bias)."""
     G = _gpu()
