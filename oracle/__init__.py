@@ -54,6 +54,15 @@ def _bind(path: str) -> ctypes.CDLL:
     L.oracle_out_dim.argtypes = [i64] * 5
     L.oracle_conv2d_f32.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int]
     L.oracle_conv2d_f32_points.argtypes = [vp, vp, vp, vp, ctypes.c_int, vp, i64, vp]
+    L.oracle_conv2d_f32_add.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int]
+    L.oracle_conv2d_f32_add_points.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, i64, vp]
+    L.oracle_rescale_params.argtypes = [f32, f32, f32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+    L.oracle_rescale_term.argtypes = [i32, i32, i32]
+    L.oracle_rescale_term.restype = i64
+    L.oracle_qconv2d_add.argtypes = [vp, f32, i32, vp, f32, i32, vp, vp, f32, i32, vp, f32, i32, vp,
+                                     ctypes.c_int, vp]
+    L.oracle_qconv2d_add_points.argtypes = [vp, f32, i32, vp, f32, i32, vp, vp, f32, i32, f32, i32, vp,
+                                            ctypes.c_int, vp, i64, vp]
     L.oracle_fc_f32.argtypes = [vp, vp, vp, vp, i64, i64, i64, ctypes.c_int]
     L.oracle_dequantize.argtypes = [vp, i64, f32, i32, vp]
     L.oracle_dequantize.restype = None
@@ -157,6 +166,36 @@ def conv2d_f32_points(x, w, bias, flat_idx, stride=(1, 1), pads=(0, 0, 0, 0), gr
     return out
 
 
+def conv2d_f32_add(x, w, bias, addend, stride=(1, 1), pads=(0, 0, 0, 0), groups=1, act=ACT_NONE) -> np.ndarray:
+    """act(conv + bias + addend): the contraction with a tensor add stacked before the activation."""
+    x = _arr(x, np.float32); w = _arr(w, np.float32)
+    p, yshape = _conv_params(x.shape, w.shape, stride, pads, groups)
+    b = None if bias is None else _arr(bias, np.float32, (w.shape[0],))
+    if min(yshape) <= 0:
+        raise OracleError(BAD_SHAPE, "conv2d_f32_add")
+    r = None if addend is None else _arr(addend, np.float32, yshape)
+    y = np.empty(yshape, dtype=np.float32)
+    rc = lib().oracle_conv2d_f32_add(_ptr(x), _ptr(w), _ptr(b), _ptr(r), _ptr(y), _ptr(p), act)
+    if rc:
+        raise OracleError(rc, "conv2d_f32_add")
+    return y
+
+
+def conv2d_f32_add_points(x, w, bias, addend, flat_idx, stride=(1, 1), pads=(0, 0, 0, 0), groups=1,
+                          act=ACT_NONE) -> np.ndarray:
+    x = _arr(x, np.float32); w = _arr(w, np.float32)
+    p, yshape = _conv_params(x.shape, w.shape, stride, pads, groups)
+    b = None if bias is None else _arr(bias, np.float32, (w.shape[0],))
+    r = None if addend is None else _arr(addend, np.float32, yshape)
+    idx = _arr(flat_idx, np.int64)
+    out = np.empty(idx.shape, dtype=np.float32)
+    rc = lib().oracle_conv2d_f32_add_points(_ptr(x), _ptr(w), _ptr(b), _ptr(r), _ptr(p), act, _ptr(idx),
+                                            idx.size, _ptr(out))
+    if rc:
+        raise OracleError(rc, "conv2d_f32_add_points")
+    return out
+
+
 def fc_f32(a, w, bias=None, act=ACT_NONE) -> np.ndarray:
     a = _arr(a, np.float32); w = _arr(w, np.float32)
     M, K = a.shape
@@ -195,6 +234,52 @@ def requant_params(sx: float, sw: float, sy: float) -> Tuple[int, int]:
 
 def requantize(acc: int, mant: int, shift: int, y_offset: int, lo: int = -128) -> int:
     return int(lib().oracle_requantize(int(acc), int(mant), int(shift), int(y_offset), int(lo)))
+
+
+def rescale_params(sr: float, sx: float, sw: float) -> Tuple[int, int]:
+    """(mant, shift) of the multiplier sr / (sx*sw) that brings an addend to the accumulator's scale."""
+    m, s = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib().oracle_rescale_params(sr, sx, sw, ctypes.byref(m), ctypes.byref(s))
+    if rc:
+        raise OracleError(rc, "rescale_params")
+    return int(m.value), int(s.value)
+
+
+def rescale_term(d: int, mant: int, shift: int) -> int:
+    return int(lib().oracle_rescale_term(int(d), int(mant), int(shift)))
+
+
+def qconv2d_add(xq, x_scale, x_off, wq, w_scale, w_off, bias_q, addend_q, r_scale, r_off, y_scale, y_off,
+                stride=(1, 1), pads=(0, 0, 0, 0), groups=1, act=ACT_NONE, return_acc=False):
+    xq = _arr(xq, np.int8); wq = _arr(wq, np.int8)
+    p, yshape = _conv_params(xq.shape, wq.shape, stride, pads, groups)
+    b = None if bias_q is None else _arr(bias_q, np.int32, (wq.shape[0],))
+    if min(yshape) <= 0:
+        raise OracleError(BAD_SHAPE, "qconv2d_add")
+    r = None if addend_q is None else _arr(addend_q, np.int8, yshape)
+    y = np.empty(yshape, dtype=np.int8)
+    acc = np.empty(yshape, dtype=np.int32) if return_acc else None
+    rc = lib().oracle_qconv2d_add(_ptr(xq), x_scale, x_off, _ptr(wq), w_scale, w_off, _ptr(b), _ptr(r),
+                                  r_scale, r_off, _ptr(y), y_scale, y_off, _ptr(p), act, _ptr(acc))
+    if rc:
+        raise OracleError(rc, "qconv2d_add")
+    return (y, acc) if return_acc else y
+
+
+def qconv2d_add_points(xq, x_scale, x_off, wq, w_scale, w_off, bias_q, addend_q, r_scale, r_off, y_scale,
+                       y_off, flat_idx, stride=(1, 1), pads=(0, 0, 0, 0), groups=1, act=ACT_NONE) -> np.ndarray:
+    xq = _arr(xq, np.int8); wq = _arr(wq, np.int8)
+    p, yshape = _conv_params(xq.shape, wq.shape, stride, pads, groups)
+    b = None if bias_q is None else _arr(bias_q, np.int32, (wq.shape[0],))
+    r = None if addend_q is None else _arr(addend_q, np.int8, yshape)
+    idx = _arr(flat_idx, np.int64)
+    out = np.empty(idx.shape, dtype=np.int8)
+    rc = lib().oracle_qconv2d_add_points(_ptr(xq), x_scale, x_off, _ptr(wq), w_scale, w_off, _ptr(b),
+                                         _ptr(r), r_scale, r_off, y_scale, y_off, _ptr(p), act, _ptr(idx),
+                                         idx.size, _ptr(out))
+    if rc:
+        raise OracleError(rc, "qconv2d_add_points")
+    return out
 
 
 def qconv2d(xq, x_scale, x_off, wq, w_scale, w_off, bias_q, y_scale, y_off, stride=(1, 1),

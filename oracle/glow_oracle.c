@@ -18,12 +18,19 @@
  *   - quantized tensors      : Section 4.1, value = (input - offset) * scale, int8 range [-128, 127].
  *   - requantize             : Section 4.3 (rescale folded into the numeric-producing operation) and the
  *                              same-scale max of Section 4.3 for the quantized Relu.
+ *   - chain with a tensor add: Section 5.2 (stacked data-parallel operators work on one memory
+ *                              location one after the other; the fused Add + max loop of the
+ *                              code-generation figure of Section 5.3): Y = act(conv + bias + addend).
+ *                              Quantized: the addend is rescaled (Section 4.3 rescale node) to the
+ *                              accumulator's scale sx*sw and added before the one requantize.
  *
  * Readings taken where the paper is silent (all listed in the design notes of the repository):
  *   cross-correlation (no filter flip); zero padding in the real domain; floor in the output-size
  *   formula; contiguous channel groups; FC weight is [K][N] row-major; int32 bias with scale sx*sw
  *   and offset 0; requantization multiplier sx*sw/sy represented as m * 2^-sh with a 31-bit
- *   mantissa, rounding half up; saturation to [-128, 127].
+ *   mantissa, rounding half up; saturation to [-128, 127]; a quantized addend (scale sr, offset
+   r_off) enters the int32 accumulator as round_half_up((r - r_off) * sr / (sx*sw)) with the same
+   mantissa/shift representation of sr/(sx*sw).
  *
  * Floating point: every sum is accumulated in double in the loop order written here and rounded
  * once to float.  Integer: sums are accumulated in 64-bit and must fit 32-bit (checked).
@@ -89,8 +96,8 @@ static int conv_shape_init(conv_shape *cs, const int64_t *p) {
  * fp32 convolution: one output element.  The three inner loops (r, s, c) of the seven.
  * Taps that fall into the padding contribute nothing (zero padding).
  * ---------------------------------------------------------------------------------------------- */
-static float conv_f32_one(const float *x, const float *w, const float *bias, const conv_shape *cs,
-                          int act, int64_t n, int64_t oh, int64_t ow, int64_t k) {
+static float conv_f32_one(const float *x, const float *w, const float *bias, const float *addend,
+                          const conv_shape *cs, int act, int64_t n, int64_t oh, int64_t ow, int64_t k) {
   const int64_t cg = cs->c / cs->groups;   /* input channels per group  */
   const int64_t kg = cs->k / cs->groups;   /* output channels per group */
   const int64_t g = k / kg;
@@ -110,13 +117,24 @@ static float conv_f32_one(const float *x, const float *w, const float *bias, con
     }
   }
   if (bias) acc += (double)bias[k];
+  /* the next link of the element-wise chain: a tensor of the output's shape */
+  if (addend) acc += (double)addend[((n * cs->oh + oh) * cs->ow + ow) * cs->k + k];
   if (act == ORACLE_ACT_RELU && acc < 0.0) acc = 0.0;
   return (float)acc;
 }
 
 /* p = {n,h,w,c, k,r,s, stride_h,stride_w, pad_t,pad_l,pad_b,pad_r, groups}.  y is [n][oh][ow][k]. */
+int oracle_conv2d_f32_add(const float *x, const float *w, const float *bias, const float *addend, float *y,
+                          const int64_t *p, int act);
+
 int oracle_conv2d_f32(const float *x, const float *w, const float *bias, float *y, const int64_t *p,
                       int act) {
+  return oracle_conv2d_f32_add(x, w, bias, NULL, y, p, act);
+}
+
+/* Y = act(conv(X, W) + bias + addend); addend is [n][oh][ow][k] like y, or NULL. */
+int oracle_conv2d_f32_add(const float *x, const float *w, const float *bias, const float *addend, float *y,
+                          const int64_t *p, int act) {
   conv_shape cs;
   int rc = conv_shape_init(&cs, p);
   if (rc) return rc;
@@ -125,13 +143,24 @@ int oracle_conv2d_f32(const float *x, const float *w, const float *bias, float *
     for (int64_t oh = 0; oh < cs.oh; ++oh)
       for (int64_t ow = 0; ow < cs.ow; ++ow)
         for (int64_t k = 0; k < cs.k; ++k)
-          y[((n * cs.oh + oh) * cs.ow + ow) * cs.k + k] = conv_f32_one(x, w, bias, &cs, act, n, oh, ow, k);
+          y[((n * cs.oh + oh) * cs.ow + ow) * cs.k + k] =
+              conv_f32_one(x, w, bias, addend, &cs, act, n, oh, ow, k);
   return ORACLE_OK;
 }
 
 /* The same definition evaluated only at the given flat output indices (into [n][oh][ow][k]). */
+int oracle_conv2d_f32_add_points(const float *x, const float *w, const float *bias, const float *addend,
+                                 const int64_t *p, int act, const int64_t *flat_idx, int64_t n_idx,
+                                 float *out);
+
 int oracle_conv2d_f32_points(const float *x, const float *w, const float *bias, const int64_t *p, int act,
                              const int64_t *flat_idx, int64_t n_idx, float *out) {
+  return oracle_conv2d_f32_add_points(x, w, bias, NULL, p, act, flat_idx, n_idx, out);
+}
+
+int oracle_conv2d_f32_add_points(const float *x, const float *w, const float *bias, const float *addend,
+                                 const int64_t *p, int act, const int64_t *flat_idx, int64_t n_idx,
+                                 float *out) {
   conv_shape cs;
   int rc = conv_shape_init(&cs, p);
   if (rc) return rc;
@@ -144,7 +173,7 @@ int oracle_conv2d_f32_points(const float *x, const float *w, const float *bias, 
     const int64_t k = f % cs.k; f /= cs.k;
     const int64_t ow = f % cs.ow; f /= cs.ow;
     const int64_t oh = f % cs.oh; f /= cs.oh;
-    out[i] = conv_f32_one(x, w, bias, &cs, act, f, oh, ow, k);
+    out[i] = conv_f32_one(x, w, bias, addend, &cs, act, f, oh, ow, k);
   }
   return ORACLE_OK;
 }
@@ -228,8 +257,8 @@ static int32_t relu_floor(int act, int32_t y_offset) {
 }
 
 static int qconv_acc_one(const int8_t *x, int32_t x_off, const int8_t *w, int32_t w_off,
-                         const int32_t *bias, const conv_shape *cs, int64_t n, int64_t oh, int64_t ow,
-                         int64_t k, int32_t *acc_out) {
+                         const int32_t *bias, int64_t extra, const conv_shape *cs, int64_t n, int64_t oh,
+                         int64_t ow, int64_t k, int32_t *acc_out) {
   const int64_t cg = cs->c / cs->groups;
   const int64_t kg = cs->k / cs->groups;
   const int64_t g = k / kg;
@@ -249,6 +278,7 @@ static int qconv_acc_one(const int8_t *x, int32_t x_off, const int8_t *w, int32_
     }
   }
   if (bias) acc += (int64_t)bias[k];
+  acc += extra;                                    /* rescaled addend of the chain, 0 without one */
   if (acc > INT32_MAX || acc < INT32_MIN) return ORACLE_ACC_OVERFLOW;
   *acc_out = (int32_t)acc;
   return ORACLE_OK;
@@ -258,10 +288,49 @@ static int offsets_ok(int32_t a, int32_t b, int32_t c) {
   return a >= -128 && a <= 127 && b >= -128 && b <= 127 && c >= -128 && c <= 127;
 }
 
+/* Rescale of a quantized addend (scale sr) to the accumulator's scale sx*sw: the multiplier
+ * sr / (sx*sw) as mant * 2^-shift, mant in [2^30, 2^31), shift in [1, 62]. */
+int oracle_rescale_params(float sr, float sx, float sw, int32_t *mant, int32_t *shift) {
+  if (!(sr > 0.0f) || !(sx > 0.0f) || !(sw > 0.0f) || isinf(sr) || isinf(sx) || isinf(sw))
+    return ORACLE_BAD_QUANT;
+  const double mr = (double)sr / ((double)sx * (double)sw);
+  if (!(mr > 0.0) || isinf(mr)) return ORACLE_BAD_QUANT;
+  int e = 0;
+  const double f = frexp(mr, &e);
+  int64_t m = llround(f * 2147483648.0);
+  if (m == 2147483648LL) { m = 1073741824LL; e += 1; }
+  const int sh = 31 - e;
+  if (sh < 1 || sh > 62) return ORACLE_BAD_QUANT;
+  *mant = (int32_t)m;
+  *shift = (int32_t)sh;
+  return ORACLE_OK;
+}
+
+/* round_half_up(d * mant / 2^shift) for a code difference d = r - r_off (|d| <= 255). */
+int64_t oracle_rescale_term(int32_t d, int32_t mant, int32_t shift) {
+  const int64_t t = (int64_t)d * (int64_t)mant + ((int64_t)1 << (shift - 1));
+  const int64_t den = (int64_t)1 << shift;
+  int64_t q = t / den;
+  if ((t % den) < 0) q -= 1;                       /* floor */
+  return q;
+}
+
+int oracle_qconv2d_add(const int8_t *x, float sx, int32_t x_off, const int8_t *w, float sw, int32_t w_off,
+                       const int32_t *bias, const int8_t *addend, float sr, int32_t r_off, int8_t *y,
+                       float sy, int32_t y_off, const int64_t *p, int act, int32_t *acc);
+
 /* Quantized convolution.  y (int8) may be NULL, acc (int32 accumulators incl. bias) may be NULL. */
 int oracle_qconv2d(const int8_t *x, float sx, int32_t x_off, const int8_t *w, float sw, int32_t w_off,
                    const int32_t *bias, int8_t *y, float sy, int32_t y_off, const int64_t *p, int act,
                    int32_t *acc) {
+  return oracle_qconv2d_add(x, sx, x_off, w, sw, w_off, bias, NULL, 1.0f, 0, y, sy, y_off, p, act, acc);
+}
+
+/* Quantized convolution with a quantized addend [n][oh][ow][k] (scale sr, offset r_off; NULL: none):
+ * acc = sum + bias + rescale(addend - r_off), y = clamp(requantize(acc)).  acc out includes the term. */
+int oracle_qconv2d_add(const int8_t *x, float sx, int32_t x_off, const int8_t *w, float sw, int32_t w_off,
+                       const int32_t *bias, const int8_t *addend, float sr, int32_t r_off, int8_t *y,
+                       float sy, int32_t y_off, const int64_t *p, int act, int32_t *acc) {
   conv_shape cs;
   int rc = conv_shape_init(&cs, p);
   if (rc) return rc;
@@ -269,6 +338,12 @@ int oracle_qconv2d(const int8_t *x, float sx, int32_t x_off, const int8_t *w, fl
   int32_t mant = 0, shift = 0;
   rc = oracle_requant_params(sx, sw, sy, &mant, &shift);
   if (rc) return rc;
+  int32_t r_mant = 0, r_shift = 1;
+  if (addend) {
+    if (r_off < -128 || r_off > 127) return ORACLE_BAD_QUANT;
+    rc = oracle_rescale_params(sr, sx, sw, &r_mant, &r_shift);
+    if (rc) return rc;
+  }
   const int32_t lo = relu_floor(act, y_off);
   int overflow = 0;
 #pragma omp parallel for collapse(2) schedule(static) reduction(| : overflow)
@@ -277,17 +352,31 @@ int oracle_qconv2d(const int8_t *x, float sx, int32_t x_off, const int8_t *w, fl
       for (int64_t ow = 0; ow < cs.ow; ++ow)
         for (int64_t k = 0; k < cs.k; ++k) {
           int32_t a = 0;
-          if (qconv_acc_one(x, x_off, w, w_off, bias, &cs, n, oh, ow, k, &a)) { overflow |= 1; continue; }
           const int64_t o = ((n * cs.oh + oh) * cs.ow + ow) * cs.k + k;
+          const int64_t extra = addend ? oracle_rescale_term((int32_t)addend[o] - r_off, r_mant, r_shift) : 0;
+          if (qconv_acc_one(x, x_off, w, w_off, bias, extra, &cs, n, oh, ow, k, &a)) { overflow |= 1; continue; }
           if (acc) acc[o] = a;
           if (y) y[o] = (int8_t)oracle_requantize(a, mant, shift, y_off, lo);
         }
   return overflow ? ORACLE_ACC_OVERFLOW : ORACLE_OK;
 }
 
+int oracle_qconv2d_add_points(const int8_t *x, float sx, int32_t x_off, const int8_t *w, float sw,
+                              int32_t w_off, const int32_t *bias, const int8_t *addend, float sr,
+                              int32_t r_off, float sy, int32_t y_off, const int64_t *p, int act,
+                              const int64_t *flat_idx, int64_t n_idx, int8_t *out);
+
 int oracle_qconv2d_points(const int8_t *x, float sx, int32_t x_off, const int8_t *w, float sw,
                           int32_t w_off, const int32_t *bias, float sy, int32_t y_off, const int64_t *p,
                           int act, const int64_t *flat_idx, int64_t n_idx, int8_t *out) {
+  return oracle_qconv2d_add_points(x, sx, x_off, w, sw, w_off, bias, NULL, 1.0f, 0, sy, y_off, p, act,
+                                   flat_idx, n_idx, out);
+}
+
+int oracle_qconv2d_add_points(const int8_t *x, float sx, int32_t x_off, const int8_t *w, float sw,
+                              int32_t w_off, const int32_t *bias, const int8_t *addend, float sr,
+                              int32_t r_off, float sy, int32_t y_off, const int64_t *p, int act,
+                              const int64_t *flat_idx, int64_t n_idx, int8_t *out) {
   conv_shape cs;
   int rc = conv_shape_init(&cs, p);
   if (rc) return rc;
@@ -295,6 +384,12 @@ int oracle_qconv2d_points(const int8_t *x, float sx, int32_t x_off, const int8_t
   int32_t mant = 0, shift = 0;
   rc = oracle_requant_params(sx, sw, sy, &mant, &shift);
   if (rc) return rc;
+  int32_t r_mant = 0, r_shift = 1;
+  if (addend) {
+    if (r_off < -128 || r_off > 127) return ORACLE_BAD_QUANT;
+    rc = oracle_rescale_params(sr, sx, sw, &r_mant, &r_shift);
+    if (rc) return rc;
+  }
   const int32_t lo = relu_floor(act, y_off);
   const int64_t total = cs.n * cs.oh * cs.ow * cs.k;
   for (int64_t i = 0; i < n_idx; ++i)
@@ -307,7 +402,9 @@ int oracle_qconv2d_points(const int8_t *x, float sx, int32_t x_off, const int8_t
     const int64_t ow = f % cs.ow; f /= cs.ow;
     const int64_t oh = f % cs.oh; f /= cs.oh;
     int32_t a = 0;
-    if (qconv_acc_one(x, x_off, w, w_off, bias, &cs, f, oh, ow, k, &a)) { overflow |= 1; continue; }
+    const int64_t extra =
+        addend ? oracle_rescale_term((int32_t)addend[flat_idx[i]] - r_off, r_mant, r_shift) : 0;
+    if (qconv_acc_one(x, x_off, w, w_off, bias, extra, &cs, f, oh, ow, k, &a)) { overflow |= 1; continue; }
     out[i] = (int8_t)oracle_requantize(a, mant, shift, y_off, lo);
   }
   return overflow ? ORACLE_ACC_OVERFLOW : ORACLE_OK;

@@ -417,6 +417,115 @@ def pin_accumulator_overflow_is_reported():
         raise AssertionError("overflow not reported")
 
 
+# ---------------------------------------------------------------------------------------------------
+# the element-wise chain with a tensor add (Section 5.2 stacking; fused Add + max of Section 5.3)
+# ---------------------------------------------------------------------------------------------------
+
+def pin_conv_add_f32():
+    """act(conv + bias + addend) against the im2col reference plus the addend, in float64; the addend
+    enters before the activation (cases where it flips the sign in both directions exist)."""
+    rng = np.random.default_rng(31)
+    for (n, h, w, c, k, r, s, st, pd, g) in TINY_SHAPES:
+        x = _rand(rng, (n, h, w, c)); wt = _rand(rng, (k, r, s, c // g)); b = _rand(rng, (k,))
+        pre = im2col_matmul(x, wt, b, st, pd, g)
+        add = (2.0 * _rand(rng, pre.shape)).astype(np.float32)
+        ref = pre + add.astype(np.float64)
+        got = oracle.conv2d_f32_add(x, wt, b, add, st, pd, g)
+        np.testing.assert_allclose(got.astype(np.float64), ref, rtol=1e-6, atol=1e-6)
+        got_relu = oracle.conv2d_f32_add(x, wt, b, add, st, pd, g, act=oracle.ACT_RELU)
+        np.testing.assert_allclose(got_relu.astype(np.float64), np.maximum(ref, 0.0), rtol=1e-6, atol=1e-6)
+        if pre.size > 50:
+            assert ((pre < -1e-3) & (ref > 1e-3)).any() and ((pre > 1e-3) & (ref < -1e-3)).any()
+        assert np.all(got_relu[ref < -1e-6] == 0.0)
+        # without an addend it is the plain operator, bit for bit
+        np.testing.assert_array_equal(oracle.conv2d_f32_add(x, wt, b, None, st, pd, g),
+                                      oracle.conv2d_f32(x, wt, b, st, pd, g))
+        idx = rng.permutation(ref.size)[: max(1, ref.size // 3)].astype(np.int64)
+        pts = oracle.conv2d_f32_add_points(x, wt, b, add, idx, st, pd, g, act=oracle.ACT_RELU)
+        np.testing.assert_allclose(pts.astype(np.float64), np.maximum(ref, 0.0).reshape(-1)[idx],
+                                   rtol=1e-6, atol=1e-6)
+    # closed form: 1x1 identity filter -> Y = X + b + addend
+    x = _rand(rng, (2, 5, 4, 6)); b = _rand(rng, (6,)); add = _rand(rng, (2, 5, 4, 6))
+    eye = np.eye(6, dtype=np.float32).reshape(6, 1, 1, 6)
+    got = oracle.conv2d_f32_add(x, eye, b, add)
+    np.testing.assert_allclose(got.astype(np.float64),
+                               x.astype(np.float64) + b.astype(np.float64) + add.astype(np.float64),
+                               rtol=1e-7, atol=1e-7)
+
+
+def _exact_rescale(d, mant, shift):
+    return math.floor(Fraction(d * mant, 1 << shift) + Fraction(1, 2))
+
+
+def pin_rescale_params_and_term():
+    # ratio 2^k: mantissa 2^30, shift 30 - k
+    for k in range(-10, 12):
+        m, sh = oracle.rescale_params(2.0 ** k, 1.0, 1.0)
+        assert (m, sh) == (1 << 30, 30 - k), (k, m, sh)
+        m, sh = oracle.rescale_params(1.0, 2.0 ** -k, 1.0)
+        assert (m, sh) == (1 << 30, 30 - k), (k, m, sh)
+    rng = np.random.default_rng(32)
+    for _ in range(500):
+        sr, sx, sw = (float(np.float32(v)) for v in rng.uniform(0.002, 0.3, size=3))
+        m, sh = oracle.rescale_params(sr, sx, sw)
+        ratio = Fraction(sr) / (Fraction(sx) * Fraction(sw))
+        assert (1 << 30) <= m < (1 << 31)
+        # the double product sx*sw is rounded once before the division: 2^-52 on top of the mantissa's 2^-31
+        assert abs(Fraction(m, 1 << sh) - ratio) <= ratio / (1 << 30)
+        for d in list(range(-255, 256, 7)) + [-255, -1, 0, 1, 255]:
+            assert oracle.rescale_term(d, m, sh) == _exact_rescale(d, m, sh), (d, m, sh)
+    # ratio 1: the term is the code difference itself; ratio 1/2: ties go up, both signs
+    m, sh = oracle.rescale_params(0.25, 0.5, 0.5)
+    assert [oracle.rescale_term(d, m, sh) for d in (-255, -3, 0, 4, 255)] == [-255, -3, 0, 4, 255]
+    m, sh = oracle.rescale_params(0.125, 0.5, 0.5)
+    assert [oracle.rescale_term(d, m, sh) for d in (-3, -2, -1, 0, 1, 2, 3)] == [-1, -1, 0, 0, 1, 1, 2]
+    for bad in [(0.0, 1.0, 1.0), (1.0, -1.0, 1.0), (float("nan"), 1.0, 1.0), (1e30, 1e-30, 1e-30)]:
+        try:
+            oracle.rescale_params(*bad)
+        except oracle.OracleError as e:
+            assert e.code == oracle.BAD_QUANT
+        else:
+            raise AssertionError(f"accepted {bad}")
+
+
+def pin_qconv_add():
+    """Composition from parts pinned elsewhere: plain accumulator (integer/real-domain pin) + exact
+    rational rescale of the addend, then the exact rational requantize; and the real-valued rule."""
+    rng = np.random.default_rng(33)
+    for (n, h, w, c, k, r, s, st, pd, g) in TINY_SHAPES[1:7]:
+        xq = rng.integers(-128, 128, size=(n, h, w, c), dtype=np.int8)
+        wq = rng.integers(-40, 41, size=(k, r, s, c // g), dtype=np.int8)
+        bq = rng.integers(-3000, 3000, size=(k,), dtype=np.int32)
+        sx, sw, sy, sr = (float(np.float32(v)) for v in (0.05, 0.01, 0.9 * r * s, rng.uniform(0.02, 0.2)))
+        x_off, w_off, y_off, r_off = (int(v) for v in rng.integers(-20, 21, size=4))
+        _, acc = oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, st, pd, g, return_acc=True)
+        rq = rng.integers(-128, 128, size=acc.shape, dtype=np.int8)
+        m, sh = oracle.requant_params(sx, sw, sy)
+        rm, rsh = oracle.rescale_params(sr, sx, sw)
+        for act in (oracle.ACT_NONE, oracle.ACT_RELU):
+            lo = max(-128, y_off) if act == oracle.ACT_RELU else -128
+            got, acc_add = oracle.qconv2d_add(xq, sx, x_off, wq, sw, w_off, bq, rq, sr, r_off, sy, y_off,
+                                              st, pd, g, act=act, return_acc=True)
+            exp_acc = np.array([int(a) + _exact_rescale(int(q) - r_off, rm, rsh)
+                                for a, q in zip(acc.reshape(-1), rq.reshape(-1))], dtype=np.int64)
+            np.testing.assert_array_equal(acc_add.reshape(-1).astype(np.int64), exp_acc)
+            exp = np.array([_exact_requant(int(a), m, sh, y_off, lo) for a in exp_acc], dtype=np.int64)
+            np.testing.assert_array_equal(got.reshape(-1).astype(np.int64), exp)
+            # real-valued rule of Section 4.1: (conv + addend) / sy + y_off, within one code
+            real = (acc.astype(np.float64) * sx * sw + (rq.astype(np.float64) - r_off) * sr) / sy + y_off
+            inside = (real > lo + 1) & (real < 126)
+            assert inside.any()
+            assert np.all(np.abs(got.astype(np.float64) - real)[inside] <= 1.0 + 1e-6)
+            idx = rng.permutation(got.size)[: max(1, got.size // 3)].astype(np.int64)
+            pts = oracle.qconv2d_add_points(xq, sx, x_off, wq, sw, w_off, bq, rq, sr, r_off, sy, y_off, idx,
+                                            st, pd, g, act=act)
+            np.testing.assert_array_equal(pts, got.reshape(-1)[idx])
+        # an addend constantly at its offset is the real value 0: the plain operator
+        same = oracle.qconv2d_add(xq, sx, x_off, wq, sw, w_off, bq, np.full(acc.shape, r_off, np.int8), sr,
+                                  r_off, sy, y_off, st, pd, g)
+        np.testing.assert_array_equal(same, oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, st, pd, g))
+
+
 ALL_PINS = [
     pin_shape_examples,
     pin_conv_vs_im2col,
@@ -438,4 +547,7 @@ ALL_PINS = [
     pin_zero_point_and_padding,
     pin_qfc_full,
     pin_accumulator_overflow_is_reported,
+    pin_conv_add_f32,
+    pin_rescale_params_and_term,
+    pin_qconv_add,
 ]

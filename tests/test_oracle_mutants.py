@@ -56,6 +56,21 @@ MUTANTS = [
      "if (act == ORACLE_ACT_RELU) return 0;", None),
     ("points_decode_swapped", "const int64_t ow = f % cs.ow; f /= cs.ow;\n    const int64_t oh = f % cs.oh; f /= cs.oh;\n    out[i] = conv_f32_one",
      "const int64_t oh = f % cs.oh; f /= cs.oh;\n    const int64_t ow = f % cs.ow; f /= cs.ow;\n    out[i] = conv_f32_one", None),
+    ("addend_after_relu", "  if (addend) acc += (double)addend[((n * cs->oh + oh) * cs->ow + ow) * cs->k + k];\n"
+     "  if (act == ORACLE_ACT_RELU && acc < 0.0) acc = 0.0;",
+     "  if (act == ORACLE_ACT_RELU && acc < 0.0) acc = 0.0;\n"
+     "  if (addend) acc += (double)addend[((n * cs->oh + oh) * cs->ow + ow) * cs->k + k];", None),
+    ("addend_sign", "if (addend) acc += (double)addend[", "if (addend) acc -= (double)addend[", None),
+    ("addend_index_transposed", "acc += (double)addend[((n * cs->oh + oh) * cs->ow + ow) * cs->k + k];",
+     "acc += (double)addend[((n * cs->ow + ow) * cs->oh + oh) * cs->k + k];", None),
+    ("rescale_inverted", "(double)sr / ((double)sx * (double)sw)", "((double)sx * (double)sw) / (double)sr", None),
+    ("rescale_ignores_sw", "(double)sr / ((double)sx * (double)sw)", "(double)sr / (double)sx", None),
+    ("rescale_offset_sign", "(int32_t)addend[o] - r_off", "(int32_t)addend[o] + r_off", None),
+    ("rescale_truncates", "(int64_t)d * (int64_t)mant + ((int64_t)1 << (shift - 1));",
+     "(int64_t)d * (int64_t)mant;", None),
+    ("rescale_rounds_to_zero", "if ((t % den) < 0) q -= 1;", "", None),
+    ("rescale_after_requantize", "acc += extra;", "", None),
+    ("points_addend_index", "(int32_t)addend[flat_idx[i]] - r_off", "(int32_t)addend[i] - r_off", None),
     ("overflow_unchecked", "if (s > INT32_MAX || s < INT32_MIN) { overflow |= 1; continue; }", "", None),
 ]
 
