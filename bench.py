@@ -28,7 +28,8 @@ PEAK_FP32_MFMA = 157.3e12      # FLOP/s, fp32 matrix
 PEAK_INT8_MFMA = 5.0e15        # OP/s
 PEAK_HBM = 8.0e12              # B/s
 
-WORKLOADS = ["resnet50_fp32", "vgg19_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8"]
+WORKLOADS = ["resnet50_fp32", "vgg19_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8",
+             "resnet50_tail_fp32", "resnet50_tail_int8"]
 
 
 def _build_workload(name):
@@ -43,6 +44,10 @@ def _build_workload(name):
         return "f32", 4, wl.fc_sweep_layers()
     if name == "fc_sweep_int8":
         return "i8", 4, wl.fc_sweep_layers()
+    if name == "resnet50_tail_fp32":   # block tails: 1x1 expand + residual add + Relu in one kernel
+        return "f32", 5, wl.resnet50_block_tails(32)
+    if name == "resnet50_tail_int8":
+        return "i8", 5, wl.resnet50_block_tails(32)
     raise SystemExit(f"unknown workload {name}; choose from {WORKLOADS}")
 
 
@@ -74,6 +79,7 @@ class Layer:
             x, w, b = gen(spec, seed)          # timing does not depend on the value distribution
             self.x, self.w, self.b = to(x), to(w), to(b)
             self.y = torch.empty(yshape, dtype=torch.float32, device=dev)
+            self.add = to(wl.addend_f32(spec, seed)) if getattr(spec, "add", False) else None
             if self.is_conv:
                 nws = glowmi.conv2d_workspace_bytes(self.desc)
             else:
@@ -85,6 +91,10 @@ class Layer:
             self.qp = (glowmi.QParam(qp.x_scale, qp.x_off), glowmi.QParam(qp.w_scale, qp.w_off),
                        glowmi.QParam(qp.y_scale, qp.y_off))
             self.y = torch.empty(yshape, dtype=torch.int8, device=dev)
+            self.add = None
+            if getattr(spec, "add", False):
+                codes, r_scale, r_off = wl.addend_q(spec, seed, qp.y_scale)
+                self.add, self.add_q = to(codes), glowmi.QParam(r_scale, r_off)
             if self.is_conv:
                 nws = glowmi.qconv2d_workspace_bytes(self.desc)
             else:
@@ -96,13 +106,18 @@ class Layer:
     def launch(self, stream):
         g, s = self.glowmi, self.spec
         if self.dtype == "f32":
-            if self.is_conv:
+            if self.is_conv and self.add is not None:
+                g.conv2d_chain(self.x, self.w, self.b, self.y, self.desc, self.add, s.act, self.ws, stream)
+            elif self.is_conv:
                 g.conv2d(self.x, self.w, self.b, self.y, self.desc, s.act, self.ws, stream)
             else:
                 g.fc(self.x, self.w, self.b, self.y, s.M, s.K, s.N, s.act, self.ws, stream)
         else:
             xq, wq, yq = self.qp
-            if self.is_conv:
+            if self.is_conv and self.add is not None:
+                g.qconv2d_chain(self.x, xq, self.w, wq, self.b, self.y, yq, self.desc, self.add, self.add_q,
+                                s.act, self.ws, stream)
+            elif self.is_conv:
                 g.qconv2d(self.x, xq, self.w, wq, self.b, self.y, yq, self.desc, s.act, self.ws, stream)
             else:
                 g.qfc(self.x, xq, self.w, wq, self.b, self.y, yq, s.M, s.K, s.N, s.act, self.ws, stream)
@@ -132,12 +147,14 @@ def _cpu_baseline(workload, dtype, cfg_index, unit_scale, budget_s=15.0):
                 st, pd = (s.stride, s.stride), (s.pad,) * 4
                 if dtype == "f32":
                     x, w, b = wl.conv_inputs_f32(s, seed)
-                    t0 = time.perf_counter(); oracle.conv2d_f32(x, w, b, st, pd, s.groups, act=s.act)
+                    r = wl.addend_f32(s, seed) if s.add else None
+                    t0 = time.perf_counter(); oracle.conv2d_f32_add(x, w, b, r, st, pd, s.groups, act=s.act)
                 else:
                     x, w, b, qp = wl.conv_inputs_q(s, seed)
+                    r, r_scale, r_off = wl.addend_q(s, seed, qp.y_scale) if s.add else (None, 1.0, 0)
                     t0 = time.perf_counter()
-                    oracle.qconv2d(x, qp.x_scale, qp.x_off, w, qp.w_scale, qp.w_off, b, qp.y_scale, qp.y_off,
-                                   st, pd, s.groups, act=s.act)
+                    oracle.qconv2d_add(x, qp.x_scale, qp.x_off, w, qp.w_scale, qp.w_off, b, r, r_scale, r_off,
+                                       qp.y_scale, qp.y_off, st, pd, s.groups, act=s.act)
             else:
                 if dtype == "f32":
                     a, w, b = wl.fc_inputs_f32(s, seed)

@@ -133,8 +133,47 @@ glowmi_status glowmi_qfc(const int8_t* a, glowmi_qparam aq, const int8_t* w, glo
                          hipStream_t stream);
 size_t glowmi_qfc_workspace_bytes(int32_t M, int32_t K, int32_t N);
 
+/*
+ * The element-wise chain behind the contraction when one of its links has a tensor operand.
+ * Section 5.2 (operator stacking): consecutive data-parallel operators work on one memory location one
+ * after the other instead of each making its own pass; the code-generation figure of Section 5.3 shows
+ * an element-wise Add fused with a max.  Here the chain is
+ *     bias add  ->  + addend (optional)  ->  act
+ * i.e. y = act(contraction + bias + addend): the tail of a residual block in one pass.
+ *   addend    device tensor with the shape, layout and element type of y (float for glowmi_conv2d_chain,
+ *             int8 for glowmi_qconv2d_chain), 16-byte aligned; NULL removes the link (the call is then
+ *             glowmi_conv2d / glowmi_qconv2d).  addend may be y itself (in-place accumulate into the
+ *             residual); any other overlap with y is not allowed.
+ *   addend_q  quantized form only: the addend's scale/offset.  Following Section 4.3 (a rescale node in
+ *             front of the add, folded into the producer) the addend is brought to the accumulator's
+ *             scale x.scale*w.scale before the single requantize:
+ *                 acc += round((addend - addend_q.offset) * Mres),  Mres = addend_q.scale / (x.scale*w.scale)
+ *             with Mres evaluated in double and applied as mant * 2^-shift exactly like the output
+ *             multiplier (31-bit mantissa, shift in [1, 62] else GLOWMI_ERR_QUANT, ties go up).
+ *             The sum must still fit int32 (caller's contract).
+ */
+typedef struct glowmi_chain {
+  const void* addend;
+  glowmi_qparam addend_q;
+  glowmi_act act;
+} glowmi_chain;
+
+/* glowmi_conv2d with the chain above.  chain must not be NULL.  Workspace as for glowmi_conv2d. */
+glowmi_status glowmi_conv2d_chain(const float* x, const float* w, const float* bias, float* y,
+                                  const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
+                                  size_t workspace_bytes, hipStream_t stream);
+/* glowmi_qconv2d with the chain above.  chain must not be NULL.  Workspace as for glowmi_qconv2d. */
+glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
+                                   const int32_t* bias, int8_t* y, glowmi_qparam yq,
+                                   const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
+                                   size_t workspace_bytes, hipStream_t stream);
+
 /* Host helper: the integer multiplier/shift the quantized entry points derive from three scales. */
 glowmi_status glowmi_requant_params(float x_scale, float w_scale, float y_scale, int32_t* mant,
+                                    int32_t* shift);
+
+/* Host helper: mant/shift of Mres = r_scale / (x_scale * w_scale), the addend rescale of glowmi_chain. */
+glowmi_status glowmi_rescale_params(float r_scale, float x_scale, float w_scale, int32_t* mant,
                                     int32_t* shift);
 
 const char* glowmi_status_string(glowmi_status s);

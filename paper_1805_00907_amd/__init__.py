@@ -8,10 +8,12 @@ loading fails loudly when the library has not been built (python -m paper_1805_0
 from .binding import (  # noqa: F401
     ACT_NONE,
     ACT_RELU,
+    Chain,
     ConvDesc,
     GlowmiError,
     QParam,
     conv2d,
+    conv2d_chain,
     conv2d_workspace_bytes,
     conv_out_shape,
     fc,
@@ -20,8 +22,10 @@ from .binding import (  # noqa: F401
     library,
     library_path,
     qconv2d,
+    qconv2d_chain,
     qconv2d_workspace_bytes,
     qfc,
     qfc_workspace_bytes,
     requant_params,
+    rescale_params,
 )

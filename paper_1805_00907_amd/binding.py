@@ -27,6 +27,11 @@ class QParam(ctypes.Structure):
     _fields_ = [("scale", ctypes.c_float), ("offset", ctypes.c_int32)]
 
 
+class Chain(ctypes.Structure):
+    """glowmi_chain: bias add -> + addend (optional tensor of y's shape) -> act."""
+    _fields_ = [("addend", ctypes.c_void_p), ("addend_q", QParam), ("act", ctypes.c_int)]
+
+
 class GlowmiError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
@@ -67,7 +72,11 @@ def library() -> ctypes.CDLL:
     L.glowmi_qfc.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, i32, i32, i32, ctypes.c_int, vp, sz, vp]
     L.glowmi_qfc_workspace_bytes.argtypes = [i32, i32, i32]
     L.glowmi_qfc_workspace_bytes.restype = sz
+    cp = ctypes.POINTER(Chain)
+    L.glowmi_conv2d_chain.argtypes = [vp, vp, vp, vp, dp, cp, vp, sz, vp]
+    L.glowmi_qconv2d_chain.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, dp, cp, vp, sz, vp]
     L.glowmi_requant_params.argtypes = [ctypes.c_float] * 3 + [ctypes.POINTER(i32)] * 2
+    L.glowmi_rescale_params.argtypes = [ctypes.c_float] * 3 + [ctypes.POINTER(i32)] * 2
     L.glowmi_status_string.argtypes = [ctypes.c_int]
     L.glowmi_status_string.restype = ctypes.c_char_p
     L.glowmi_last_error.restype = ctypes.c_char_p
@@ -146,6 +155,28 @@ def qconv2d(x, xq: QParam, w, wq: QParam, bias, y, yq: QParam, desc: ConvDesc, a
                                     act, wp, wb, _stream(stream)))
 
 
+def _chain(addend, addend_q: Optional[QParam], act: int) -> Chain:
+    return Chain(_ptr(addend), addend_q if addend_q is not None else QParam(1.0, 0), act)
+
+
+def conv2d_chain(x, w, bias, y, desc: ConvDesc, addend=None, act: int = ACT_NONE, workspace=None,
+                 stream=None) -> None:
+    """y = act(conv + bias + addend); addend is a float tensor of y's shape (may be y) or None."""
+    wp, wb = _ws(workspace)
+    chain = _chain(addend, None, act)
+    _check(library().glowmi_conv2d_chain(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), ctypes.byref(desc),
+                                         ctypes.byref(chain), wp, wb, _stream(stream)))
+
+
+def qconv2d_chain(x, xq: QParam, w, wq: QParam, bias, y, yq: QParam, desc: ConvDesc, addend=None,
+                  addend_q: Optional[QParam] = None, act: int = ACT_NONE, workspace=None, stream=None) -> None:
+    """Quantized form: addend is an int8 tensor of y's shape with scale/offset addend_q."""
+    wp, wb = _ws(workspace)
+    chain = _chain(addend, addend_q, act)
+    _check(library().glowmi_qconv2d_chain(_ptr(x), xq, _ptr(w), wq, _ptr(bias), _ptr(y), yq,
+                                          ctypes.byref(desc), ctypes.byref(chain), wp, wb, _stream(stream)))
+
+
 def qfc_workspace_bytes(M: int, K: int, N: int) -> int:
     return int(library().glowmi_qfc_workspace_bytes(M, K, N))
 
@@ -160,4 +191,10 @@ def qfc(a, aq: QParam, w, wq: QParam, bias, y, yq: QParam, M: int, K: int, N: in
 def requant_params(x_scale: float, w_scale: float, y_scale: float) -> Tuple[int, int]:
     m, s = ctypes.c_int32(0), ctypes.c_int32(0)
     _check(library().glowmi_requant_params(x_scale, w_scale, y_scale, ctypes.byref(m), ctypes.byref(s)))
+    return m.value, s.value
+
+
+def rescale_params(r_scale: float, x_scale: float, w_scale: float) -> Tuple[int, int]:
+    m, s = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(library().glowmi_rescale_params(r_scale, x_scale, w_scale, ctypes.byref(m), ctypes.byref(s)))
     return m.value, s.value

@@ -67,6 +67,8 @@ glowmi_status check_desc(const glowmi_conv_desc* d, Geometry* geo) {
 }
 
 void fill_divs(glowmi::Problem& p) {
+  p.addend = nullptr;
+  p.r_off = 0; p.r_mant = 0; p.r_shift = 1;
   p.div_ohow = glowmi::make_fastdiv((uint32_t)p.oh * (uint32_t)p.ow);
   p.div_ow = glowmi::make_fastdiv((uint32_t)p.ow);
   p.div_cg = glowmi::make_fastdiv((uint32_t)p.cg);
@@ -135,6 +137,16 @@ glowmi_status check_ptrs(const void* x, const void* w, const void* bias, const v
   return GLOWMI_OK;
 }
 
+// The tensor operand of a chain: aligned, and either the output itself or disjoint from it.
+glowmi_status check_addend(const void* addend, const void* y, size_t bytes) {
+  if (!addend) return GLOWMI_OK;
+  if (!aligned(addend, 16)) return fail(GLOWMI_ERR_ALIGN, "addend must be 16-byte aligned");
+  const uintptr_t a = reinterpret_cast<uintptr_t>(addend), o = reinterpret_cast<uintptr_t>(y);
+  if (a != o && a < o + bytes && o < a + bytes)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "addend overlaps the output without being the output itself");
+  return GLOWMI_OK;
+}
+
 bool workspace_usable(const void* ws, size_t have, size_t need) {
   return ws != nullptr && need > 0 && have >= need && aligned(ws, 16);
 }
@@ -192,15 +204,30 @@ size_t glowmi_conv2d_workspace_bytes(const glowmi_conv_desc* d) {
 glowmi_status glowmi_conv2d(const float* x, const float* w, const float* bias, float* y,
                             const glowmi_conv_desc* d, glowmi_act act, void* workspace,
                             size_t workspace_bytes, hipStream_t stream) {
+  glowmi_chain chain;
+  chain.addend = nullptr;
+  chain.addend_q.scale = 1.0f;
+  chain.addend_q.offset = 0;
+  chain.act = act;
+  return glowmi_conv2d_chain(x, w, bias, y, d, &chain, workspace, workspace_bytes, stream);
+}
+
+glowmi_status glowmi_conv2d_chain(const float* x, const float* w, const float* bias, float* y,
+                                  const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
+                                  size_t workspace_bytes, hipStream_t stream) {
+  if (!chain) return fail(GLOWMI_ERR_NULL, "chain must not be NULL");
+  const glowmi_act act = chain->act;
   Geometry geo;
   glowmi_status st = check_desc(d, &geo);
   if (st != GLOWMI_OK) return st;
   if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
   if ((st = check_act(act)) != GLOWMI_OK) return st;
+  if ((st = check_addend(chain->addend, y, (size_t)geo.y_elems * 4u)) != GLOWMI_OK) return st;
   glowmi::Problem p;
   fill_conv(p, d, geo);
   if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 4)) != GLOWMI_OK) return st;
   p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  p.addend = chain->addend;
   const size_t need = split_bytes(glowmi::plan_f32(p, true), p);
   p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
   const char* variant = "";
@@ -243,16 +270,40 @@ glowmi_status glowmi_qconv2d(const int8_t* x, glowmi_qparam xq, const int8_t* w,
                              const int32_t* bias, int8_t* y, glowmi_qparam yq,
                              const glowmi_conv_desc* d, glowmi_act act, void* workspace,
                              size_t workspace_bytes, hipStream_t stream) {
+  glowmi_chain chain;
+  chain.addend = nullptr;
+  chain.addend_q.scale = 1.0f;
+  chain.addend_q.offset = 0;
+  chain.act = act;
+  return glowmi_qconv2d_chain(x, xq, w, wq, bias, y, yq, d, &chain, workspace, workspace_bytes, stream);
+}
+
+glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
+                                   const int32_t* bias, int8_t* y, glowmi_qparam yq,
+                                   const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
+                                   size_t workspace_bytes, hipStream_t stream) {
+  if (!chain) return fail(GLOWMI_ERR_NULL, "chain must not be NULL");
+  const glowmi_act act = chain->act;
   Geometry geo;
   glowmi_status st = check_desc(d, &geo);
   if (st != GLOWMI_OK) return st;
   if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
   if ((st = check_act(act)) != GLOWMI_OK) return st;
+  if ((st = check_addend(chain->addend, y, (size_t)geo.y_elems)) != GLOWMI_OK) return st;
   glowmi::Problem p;
   fill_conv(p, d, geo);
   if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 1)) != GLOWMI_OK) return st;
   if ((st = quant_setup(p, xq, wq, yq, act)) != GLOWMI_OK) return st;
   p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  if (chain->addend) {
+    if (chain->addend_q.offset < -128 || chain->addend_q.offset > 127)
+      return fail(GLOWMI_ERR_QUANT, "addend offset %d outside [-128, 127]", chain->addend_q.offset);
+    int32_t r_mant = 0, r_shift = 0;
+    if ((st = glowmi_rescale_params(chain->addend_q.scale, xq.scale, wq.scale, &r_mant, &r_shift)) != GLOWMI_OK)
+      return st;
+    p.addend = chain->addend;
+    p.r_off = chain->addend_q.offset; p.r_mant = r_mant; p.r_shift = r_shift;
+  }
   const size_t need = split_bytes(glowmi::plan_i8(p, true), p);
   p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
   const char* variant = "";
@@ -285,14 +336,30 @@ glowmi_status glowmi_qfc(const int8_t* a, glowmi_qparam aq, const int8_t* w, glo
   return finish(glowmi::launch_i8(p, stream, &variant), variant);
 }
 
-// Mr = x_scale * w_scale / y_scale as mant * 2^-shift, mant a 31-bit integer with its top bit set.
+// A positive multiplier as mant * 2^-shift, mant a 31-bit integer with its top bit set.
+static glowmi_status multiplier_params(double mr, int32_t* mant, int32_t* shift);
+
+// Mr = x_scale * w_scale / y_scale
 glowmi_status glowmi_requant_params(float x_scale, float w_scale, float y_scale, int32_t* mant,
                                     int32_t* shift) {
   if (!mant || !shift) return fail(GLOWMI_ERR_NULL, "mant/shift output pointers are NULL");
   const float sc[3] = {x_scale, w_scale, y_scale};
   for (float v : sc)
     if (!std::isfinite(v) || v <= 0.0f) return fail(GLOWMI_ERR_QUANT, "scale %g is not finite and positive", (double)v);
-  const double mr = (double)x_scale * (double)w_scale / (double)y_scale;
+  return multiplier_params((double)x_scale * (double)w_scale / (double)y_scale, mant, shift);
+}
+
+// Mres = r_scale / (x_scale * w_scale)
+glowmi_status glowmi_rescale_params(float r_scale, float x_scale, float w_scale, int32_t* mant,
+                                    int32_t* shift) {
+  if (!mant || !shift) return fail(GLOWMI_ERR_NULL, "mant/shift output pointers are NULL");
+  const float sc[3] = {r_scale, x_scale, w_scale};
+  for (float v : sc)
+    if (!std::isfinite(v) || v <= 0.0f) return fail(GLOWMI_ERR_QUANT, "scale %g is not finite and positive", (double)v);
+  return multiplier_params((double)r_scale / ((double)x_scale * (double)w_scale), mant, shift);
+}
+
+static glowmi_status multiplier_params(double mr, int32_t* mant, int32_t* shift) {
   if (!std::isfinite(mr) || mr <= 0.0) return fail(GLOWMI_ERR_QUANT, "combined multiplier %g is unusable", mr);
   int exponent = 0;
   const double frac = std::frexp(mr, &exponent);               // [0.5, 1)

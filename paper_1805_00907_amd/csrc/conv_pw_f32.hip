@@ -22,6 +22,7 @@
 // Epilogue as everywhere (operator stacking, Section 5.2): bias + Relu on the accumulators, one store.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
 
 #include "igemm.h"
@@ -51,7 +52,8 @@ struct Pw {
 
 // CONTIGUOUS: the input pixel of output pixel m is m itself (unit strides); otherwise it is derived
 // from (image, row, column).
-template <int K, bool CONTIGUOUS>
+// ADD: the element-wise chain has a tensor-add link (p.addend, of the output's shape).
+template <int K, bool CONTIGUOUS, bool ADD>
 __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Problem p, const PwRange full,
                                                                    const PwRange last) {
   using G = Pw<K>;
@@ -73,6 +75,8 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w), 0, (int)p.w_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_y =
       __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_add = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(ADD ? p.addend : p.y), 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
 
   // ---- this wavefront's contiguous range of items (pixel block major, channel group minor)
   const PwRange& range = slice == (int)gridDim.y - 1 ? last : full;    // the last slice may be narrower
@@ -152,6 +156,20 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
     const bool more = it + 1 < it_end;
     const int rb_next = block_of(it + 1);
 
+    // The addend values of this item are fetched before the MFMAs: a load issued in the epilogue
+    // would wait for its own latency and, the memory counter being in order, for the stores before it.
+    const unsigned item_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes +
+                              (unsigned)(slice * G::BN + ng * 64 + l32) * 4u;
+    float addv[2][16];
+    if (ADD) {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          addv[nb][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+              rsrc_add, item_off + 128u * nb + (unsigned)((e >> 2) * 8 + (e & 3)) * row_bytes, 0, 0));
+    }
+
     v16f acc0, acc1;
 #pragma unroll
     for (int e = 0; e < 16; ++e) { acc0[e] = 0.f; acc1[e] = 0.f; }
@@ -191,7 +209,7 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
         asm volatile("" : "+v"(lane_off));                 // keep the per-register row offsets scalar
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float v = fmaxf(acc[e] + bv, floor_value);
+          const float v = fmaxf(acc[e] + bv + (ADD ? addv[nb][e] : 0.f), floor_value);
           const unsigned off = lane_off + (unsigned)((e >> 2) * 8 + (e & 3)) * row_bytes;
           __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, off, 0, 0);
         }
@@ -200,10 +218,10 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
   }
 }
 
-template <int K, bool CONTIGUOUS>
+template <int K, bool CONTIGUOUS, bool ADD>
 hipError_t launch_pw(const Problem& p, hipStream_t stream) {
   using G = Pw<K>;
-  auto kern = conv_pw_f32_kernel<K, CONTIGUOUS>;
+  auto kern = conv_pw_f32_kernel<K, CONTIGUOUS, ADD>;
   static int num_cu = 0;          // benign if two threads race: both compute the same value
   if (num_cu == 0) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -249,15 +267,21 @@ bool pw_f32_applicable(const Problem& p) {
   return items >= pw_min_items() && items < (1LL << 30);
 }
 
+template <int K>
+hipError_t launch_pw_k(const Problem& p, hipStream_t stream) {
+  const bool contiguous = p.stride_h == 1 && p.stride_w == 1;
+  if (p.addend) return contiguous ? launch_pw<K, true, true>(p, stream) : launch_pw<K, false, true>(p, stream);
+  return contiguous ? launch_pw<K, true, false>(p, stream) : launch_pw<K, false, false>(p, stream);
+}
+
 hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** variant) {
   const bool contiguous = p.stride_h == 1 && p.stride_w == 1;
+  static thread_local char name[48];
+  snprintf(name, sizeof(name), "conv_pw_f32_c%d%s%s", p.c, contiguous ? "" : "_strided", p.addend ? "_add" : "");
+  *variant = name;
   switch (p.c) {
-    case 64:
-      *variant = contiguous ? "conv_pw_f32_c64" : "conv_pw_f32_c64_strided";
-      return contiguous ? launch_pw<64, true>(p, stream) : launch_pw<64, false>(p, stream);
-    case 128:
-      *variant = contiguous ? "conv_pw_f32_c128" : "conv_pw_f32_c128_strided";
-      return contiguous ? launch_pw<128, true>(p, stream) : launch_pw<128, false>(p, stream);
+    case 64: return launch_pw_k<64>(p, stream);
+    case 128: return launch_pw_k<128>(p, stream);
     default: return hipErrorInvalidValue;
   }
 }

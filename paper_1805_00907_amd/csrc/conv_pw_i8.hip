@@ -17,7 +17,9 @@
 //     channels of one pixel: add the channel term, requantize, clamp, pack, two 16-byte stores.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "igemm.h"
 #include "pw_common.h"
@@ -55,7 +57,9 @@ __host__ __device__ constexpr int staged_row(int c) {
   return ((c >> 4) & 1) * 32 + ((c >> 2) & 3) * 8 + (c >> 5) * 4 + (c & 3);
 }
 
-template <int K, bool CONTIGUOUS>
+// ADD: the element-wise chain has a tensor-add link (p.addend, int8 of the output's shape, rescaled
+// to the accumulator's scale before it is added).
+template <int K, bool CONTIGUOUS, bool ADD>
 __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_kernel(const Problem p,
                                                                                   const PwRange full,
                                                                                   const PwRange last) {
@@ -78,6 +82,8 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w), 0, (int)p.w_bytes, 0x00020000);
   const __amdgpu_buffer_rsrc_t rsrc_y =
       __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)((unsigned)p.M * (unsigned)p.k), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_add = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(ADD ? p.addend : p.y), 0, (int)((unsigned)p.M * (unsigned)p.k), 0x00020000);
 
   // ---- this wavefront's contiguous range of items (pixel block major, channel group minor)
   const PwRange& range = slice == (int)gridDim.y - 1 ? last : full;    // the last slice may be narrower
@@ -168,6 +174,15 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
 
     for (; it < rb_items_end; ++it) {
       const int ng = it - rb * range.ngc;
+      // the lane's 32 addend codes, fetched ahead of the MFMAs (a load in the epilogue would wait for
+      // its own latency and, the memory counter being in order, for the stores before it)
+      const int ch0 = slice * G::BN + ng * 64 + 32 * lh;   // first of the lane's 32 channels
+      const unsigned off = (unsigned)(rb * 32 + l32) * (unsigned)p.k + (unsigned)ch0;
+      v4i addq[2];
+      if (ADD) {
+        addq[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_add, off, 0, 0);
+        addq[1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_add, off + 16u, 0, 0);
+      }
       v16i acc0, acc1;
 #pragma unroll
       for (int e = 0; e < 16; ++e) { acc0[e] = 0; acc1[e] = 0; }
@@ -183,8 +198,6 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
       }
 
       // ---- epilogue: lane (l32, lh) holds pixel l32, channels 32*lh + 16*nb + e of the group
-      const int ch0 = slice * G::BN + ng * 64 + 32 * lh;   // first of the lane's 32 channels
-      const unsigned off = (unsigned)(rb * 32 + l32) * (unsigned)p.k + (unsigned)ch0;
       auto finish = [&](auto fast_tag) {
         constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
@@ -196,9 +209,14 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
             const v4i ct = *reinterpret_cast<const v4i*>(cterm + ng * 64 + 32 * lh + 16 * nb + 4 * q4);
             int q[4];
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
-              q[t] = requantize_as<FAST>((int)((unsigned)acc[4 * q4 + t] + (unsigned)ct[t]), p.mant, p.shift,
-                                         p.y_off, p.lo);
+            for (int t = 0; t < 4; ++t) {
+              unsigned v = (unsigned)acc[4 * q4 + t] + (unsigned)ct[t];
+              if (ADD) {
+                const int code = (int)(signed char)((unsigned)addq[nb][q4] >> (8 * t));
+                v += (unsigned)rescale_term(code - p.r_off, p.r_mant, p.r_shift);
+              }
+              q[t] = requantize_as<FAST>((int)v, p.mant, p.shift, p.y_off, p.lo);
+            }
             out[q4] = (int)pack_codes(q[0], q[1], q[2], q[3]);
           }
           // channels are stored in runs of 16 (k % 16 == 0): a run is wholly inside or outside;
@@ -212,10 +230,10 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
   }
 }
 
-template <int K, bool CONTIGUOUS>
+template <int K, bool CONTIGUOUS, bool ADD>
 hipError_t launch_pwq(const Problem& p, hipStream_t stream) {
   using G = PwQ<K>;
-  auto kern = conv_pw_i8_kernel<K, CONTIGUOUS>;
+  auto kern = conv_pw_i8_kernel<K, CONTIGUOUS, ADD>;
   static int num_cu = 0;          // benign if two threads race: both compute the same value
   if (num_cu == 0) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -262,18 +280,22 @@ bool pw_i8_applicable(const Problem& p) {
   return items >= pwq_min_items() && items < (1LL << 30);
 }
 
+template <int K>
+hipError_t launch_pwq_k(const Problem& p, hipStream_t stream) {
+  const bool contiguous = p.stride_h == 1 && p.stride_w == 1;
+  if (p.addend) return contiguous ? launch_pwq<K, true, true>(p, stream) : launch_pwq<K, false, true>(p, stream);
+  return contiguous ? launch_pwq<K, true, false>(p, stream) : launch_pwq<K, false, false>(p, stream);
+}
+
 hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** variant) {
   const bool contiguous = p.stride_h == 1 && p.stride_w == 1;
+  static thread_local char name[48];
+  snprintf(name, sizeof(name), "conv_pw_i8_c%d%s%s", p.c, contiguous ? "" : "_strided", p.addend ? "_add" : "");
+  *variant = name;
   switch (p.c) {
-    case 64:
-      *variant = contiguous ? "conv_pw_i8_c64" : "conv_pw_i8_c64_strided";
-      return contiguous ? launch_pwq<64, true>(p, stream) : launch_pwq<64, false>(p, stream);
-    case 128:
-      *variant = contiguous ? "conv_pw_i8_c128" : "conv_pw_i8_c128_strided";
-      return contiguous ? launch_pwq<128, true>(p, stream) : launch_pwq<128, false>(p, stream);
-    case 256:
-      *variant = contiguous ? "conv_pw_i8_c256" : "conv_pw_i8_c256_strided";
-      return contiguous ? launch_pwq<256, true>(p, stream) : launch_pwq<256, false>(p, stream);
+    case 64: return launch_pwq_k<64>(p, stream);
+    case 128: return launch_pwq_k<128>(p, stream);
+    case 256: return launch_pwq_k<256>(p, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -15,6 +15,7 @@
 #include <hip/hip_runtime.h>
 
 #include "igemm.h"
+#include "quant_epilogue.h"
 
 namespace glowmi {
 namespace {
@@ -38,22 +39,9 @@ __device__ __forceinline__ int sum_bytes(int packed) {
   return __builtin_amdgcn_sdot4(packed, 0x01010101, 0, false);
 }
 
-// Same arithmetic as the generic int8 kernel: round_half_up(acc * mant / 2^shift) + y_off, clamped.
 __device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_off, int lo) {
-  int q;
-  if (shift >= 33) {
-    q = (__mulhi(acc, mant) + (1 << (shift - 33))) >> (shift - 32);
-  } else {
-    long long t = (long long)acc * (long long)mant + (1LL << (shift - 1));
-    t >>= shift;
-    t = t < -4096 ? -4096 : t;
-    t = t > 4096 ? 4096 : t;
-    q = (int)t;
-  }
-  q += y_off;
-  q = q < lo ? lo : q;
-  q = q > 127 ? 127 : q;
-  return q;
+  return shift >= 33 ? requantize_as<true>(acc, mant, shift, y_off, lo)
+                     : requantize_as<false>(acc, mant, shift, y_off, lo);   // uniform branch
 }
 
 __global__ __launch_bounds__(QS_THREADS) void conv_smallc_i8_kernel(const Problem p, int tiles_y, int tiles_x,

@@ -43,6 +43,8 @@ struct Problem {
   const void* bias;   // [k] float or int32, may be null
   void* y;            // output [M][k]
   void* partial;      // split-K partial sums [split_k][M][k] (float or int32), null when split_k == 1
+  const void* addend; // tensor operand of the element-wise chain [M][k] (float or int8), may be null:
+                      // added to the accumulator after the bias and before the activation
   int32_t n, h, w_, c;
   int32_t k, r, s;
   int32_t oh, ow;
@@ -60,6 +62,8 @@ struct Problem {
   int32_t x_off, w_off, y_off;
   int32_t mant, shift;      // requantize multiplier
   int32_t lo;               // lower clamp bound
+  int32_t r_off, r_mant, r_shift;   // quantized addend: its offset and the multiplier that brings a
+                                    // code difference to the accumulator's scale, mant * 2^-shift
 };
 
 // Each launcher validates nothing (the ABI layer did), picks the tile variant, launches on `stream`

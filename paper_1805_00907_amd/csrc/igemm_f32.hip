@@ -19,6 +19,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "igemm.h"
 
@@ -347,7 +348,9 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
   // 32x32 MFMA block: register e of a lane is row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
   float* __restrict__ Y = static_cast<float*>(p.y);
   const float* __restrict__ bias = static_cast<const float*>(p.bias);
-  auto epilogue = [&](const Item& it) {
+  const float* addend = static_cast<const float*>(p.addend);   // may be the output itself
+  auto epilogue_as = [&](const Item& it, auto add_tag) {
+    constexpr bool ADD = decltype(add_tag)::value;   // the chain has a tensor-add link
     // One base pointer per lane; every element is then base + a wave-uniform row offset, so the
     // per-element cost is the arithmetic of the chain itself.  Tiles that lie completely inside the
     // output skip the bounds tests (uniform branch).
@@ -363,17 +366,24 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
       const int ch = it.g * p.kg + col;
       const float bv = (cok && finish && bias) ? bias[ch] : 0.f;
       float* dst = dst_base + (size_t)row_base * p.k + ch;
+      const float* add = ADD ? addend + (size_t)row_base * p.k + ch : nullptr;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int r = i * 32 + (e >> 2) * 8 + (e & 3);          // compile-time row inside the wave tile
           float v = (LONGK ? total[i][j][e] : acc[i][j][e]) + bv;
+          const bool inside = full || (cok && row_base + r < p.M);
+          if (ADD && inside) v += add[(size_t)r * p.k];
           if (relu) v = fmaxf(v, 0.f);
-          if (full || (cok && row_base + r < p.M)) dst[(size_t)r * p.k] = v;
+          if (inside) dst[(size_t)r * p.k] = v;
         }
       }
     }
+  };
+  auto epilogue = [&](const Item& it) {
+    if (addend && p.split_k == 1) epilogue_as(it, std::true_type{});
+    else epilogue_as(it, std::false_type{});
   };
 
   // ---- main loop: global loads of slab i+1 in flight while slab i is multiplied.  The loop is
@@ -406,12 +416,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
 // fused bias + activation, one store.
 __global__ __launch_bounds__(256) void splitk_finish_f32(const float* __restrict__ partial,
                                                          const float* __restrict__ bias,
-                                                         float* __restrict__ y, int total, int k,
+                                                         const float* addend, float* y, int total, int k,
                                                          int split_k, int act) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
     float v = 0.f;
     for (int s = 0; s < split_k; ++s) v += partial[(size_t)s * total + i];
     if (bias) v += bias[i % k];
+    if (addend) v += addend[i];
     if (act == 1) v = fmaxf(v, 0.f);
     y[i] = v;
   }
@@ -577,9 +588,9 @@ constexpr int kNumTilesF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 
 Plan plan_f32(const Problem& p, bool allow_split) {
   Plan pl;
-  if ((smallc_f32_applicable(p) || pw_f32_applicable(p)) && !getenv("GLOWMI_F32_TILE"))
+  if (((smallc_f32_applicable(p) && !p.addend) || pw_f32_applicable(p)) && !getenv("GLOWMI_F32_TILE"))
     allow_split = false;   // kernels of their own, no workspace
-  if (p.b_is_kn && p.M <= 16 && p.groups == 1 && p.k % 4 == 0 && p.Kgemm % 4 == 0 &&
+  if (p.b_is_kn && p.M <= 16 && p.groups == 1 && p.k % 4 == 0 && p.Kgemm % 4 == 0 && !p.addend &&
       !getenv("GLOWMI_F32_TILE")) {
     // FC with a handful of rows: stream the weights (fc_skinny16_f32_kernel).  "slabs" are steps of
     // SK16_STEP weight rows; K is split over the grid until ~4 workgroups per CU exist, each
@@ -676,7 +687,8 @@ hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, b
 }  // namespace
 
 hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
-  if (smallc_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE")) return launch_smallc_f32(p_in, stream, variant);
+  if (smallc_f32_applicable(p_in) && !p_in.addend && !getenv("GLOWMI_F32_TILE"))
+    return launch_smallc_f32(p_in, stream, variant);   // (that kernel has no tensor-add link)
   if (pw_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE")) return launch_pw_f32(p_in, stream, variant);
   Problem p = p_in;
   const Plan plan = plan_f32(p, p.partial != nullptr);
@@ -716,6 +728,7 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(splitk_finish_f32, dim3(blocks), dim3(256), 0, stream,
                        static_cast<const float*>(p.partial), static_cast<const float*>(p.bias),
+                       static_cast<const float*>(p.addend),
                        static_cast<float*>(p.y), total, p.k, plan.split_k, p.act);
     e = hipGetLastError();
   }

@@ -21,6 +21,7 @@
 #include <cstdlib>
 
 #include "igemm.h"
+#include "quant_epilogue.h"
 
 namespace glowmi {
 namespace {
@@ -54,26 +55,9 @@ __device__ __forceinline__ int sum_bytes(int packed) {   // sum of the four sign
   return __builtin_amdgcn_sdot4(packed, 0x01010101, 0, false);
 }
 
-// round_half_up(acc * mant / 2^shift) + y_off, clamped to [lo, 127].
-// With P = acc * mant = hi * 2^32 + lo32 and shift >= 33 the rounding constant 2^(shift-1) is a
-// multiple of 2^32, so (P + 2^(shift-1)) >> shift == (hi + 2^(shift-33)) >> (shift-32) exactly:
-// one 32-bit multiply-high instead of 64-bit arithmetic.  That covers every multiplier below 1/4
-// (the usual case); larger multipliers take the 64-bit form.  The branch is uniform.
 __device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_off, int lo) {
-  int q;
-  if (shift >= 33) {
-    q = (__mulhi(acc, mant) + (1 << (shift - 33))) >> (shift - 32);
-  } else {
-    long long t = (long long)acc * (long long)mant + (1LL << (shift - 1));
-    t >>= shift;                            // arithmetic shift: floor, so ties round up
-    t = t < -4096 ? -4096 : t;              // far outside the int8 range either way
-    t = t > 4096 ? 4096 : t;
-    q = (int)t;
-  }
-  q += y_off;
-  q = q < lo ? lo : q;
-  q = q > 127 ? 127 : q;
-  return q;
+  return shift >= 33 ? requantize_as<true>(acc, mant, shift, y_off, lo)
+                     : requantize_as<false>(acc, mant, shift, y_off, lo);   // uniform branch
 }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
@@ -361,11 +345,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const 
   }
   __syncthreads();
 
+  const signed char* addend = static_cast<const signed char*>(p.addend);   // may be the output itself
   if (p.split_k == 1) {
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
       const int lr = wm * WTM + i * 32 + lrow;                        // pixel row inside the tile
       const unsigned rowterm = need_xsum ? (unsigned)p.w_off * (unsigned)xsum[lr] : 0u;
+      const int row = tm * BM + lr;
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -375,7 +361,12 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const 
           unsigned packed = 0;
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
-            const int v = (int)((unsigned)acc[i][j][q4 * 4 + t] + (unsigned)ct[t] - rowterm);
+            int v = (int)((unsigned)acc[i][j][q4 * 4 + t] + (unsigned)ct[t] - rowterm);
+            if (addend) {                                             // uniform: tensor-add link of the chain
+              const int col = tn * BN + lc + t;
+              const int code = (row < p.M && col < p.kg) ? (int)addend[(size_t)row * p.k + g * p.kg + col] : p.r_off;
+              v += rescale_term(code - p.r_off, p.r_mant, p.r_shift);
+            }
             packed |= ((unsigned)requantize(v, p.mant, p.shift, p.y_off, p.lo) & 0xffu) << (t * 8);
           }
           *reinterpret_cast<unsigned*>(out + lr * OUT_PITCH + lc) = packed;
@@ -423,13 +414,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const 
 
 __global__ __launch_bounds__(256) void splitk_finish_i8(const int* __restrict__ partial,
                                                         const int* __restrict__ bias,
-                                                        signed char* __restrict__ y, int total, int k,
+                                                        const signed char* addend, int r_off, int r_mant,
+                                                        int r_shift, signed char* y, int total, int k,
                                                         int split_k, int mant, int shift, int y_off,
                                                         int lo) {
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
     unsigned v = 0;
     for (int s = 0; s < split_k; ++s) v += (unsigned)partial[(size_t)s * total + i];
     if (bias) v += (unsigned)bias[i % k];
+    if (addend) v += (unsigned)rescale_term((int)addend[i] - r_off, r_mant, r_shift);
     y[i] = (signed char)requantize((int)v, mant, shift, y_off, lo);
   }
 }
@@ -474,7 +467,7 @@ hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, b
 
 Plan plan_i8(const Problem& p, bool allow_split) {
   Plan pl;
-  if ((smallc_i8_applicable(p) || pw_i8_applicable(p)) && !getenv("GLOWMI_I8_TILE"))
+  if (((smallc_i8_applicable(p) && !p.addend) || pw_i8_applicable(p)) && !getenv("GLOWMI_I8_TILE"))
     allow_split = false;   // kernels of their own, no workspace
   pl.bk = BKQ;
   pl.slabs = (p.Kgemm + BKQ - 1) / BKQ;
@@ -518,7 +511,8 @@ Plan plan_i8(const Problem& p, bool allow_split) {
 }
 
 hipError_t launch_i8(const Problem& p_in, hipStream_t stream, const char** variant) {
-  if (smallc_i8_applicable(p_in) && !getenv("GLOWMI_I8_TILE")) return launch_smallc_i8(p_in, stream, variant);
+  if (smallc_i8_applicable(p_in) && !p_in.addend && !getenv("GLOWMI_I8_TILE"))
+    return launch_smallc_i8(p_in, stream, variant);   // (that kernel has no tensor-add link)
   if (pw_i8_applicable(p_in) && !getenv("GLOWMI_I8_TILE")) return launch_pw_i8(p_in, stream, variant);
   Problem p = p_in;
   const Plan plan = plan_i8(p, p.partial != nullptr);
@@ -545,6 +539,7 @@ hipError_t launch_i8(const Problem& p_in, hipStream_t stream, const char** varia
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(splitk_finish_i8, dim3(blocks), dim3(256), 0, stream,
                        static_cast<const int*>(p.partial), static_cast<const int*>(p.bias),
+                       static_cast<const signed char*>(p.addend), p.r_off, p.r_mant, p.r_shift,
                        static_cast<signed char*>(p.y), total, p.k, plan.split_k, p.mant, p.shift,
                        p.y_off, p.lo);
     e = hipGetLastError();

@@ -29,6 +29,13 @@ __device__ __forceinline__ int requantize_as(int acc, int mant, int shift, int y
   return q;
 }
 
+// round_half_up(d * mant / 2^shift): a quantized addend's code difference d = r - r_offset brought
+// to the accumulator's scale (the rescale node of Section 4.3 in front of the add), shift in [1, 62].
+__device__ __forceinline__ int rescale_term(int d, int mant, int shift) {
+  const long long t = (long long)d * (long long)mant + (1LL << (shift - 1));
+  return (int)(t >> shift);                 // arithmetic shift: floor, so ties round up
+}
+
 // the low bytes of four ints as one dword, a in the lowest byte
 __device__ __forceinline__ unsigned pack_codes(int a, int b, int c, int d) {
   const unsigned ab = __builtin_amdgcn_perm((unsigned)b, (unsigned)a, 0x0c0c0400u);

@@ -36,6 +36,7 @@ class ConvLayer:
     pad: int = 0
     groups: int = 1
     act: int = ACT_RELU
+    add: bool = False      # the element-wise chain has a tensor-add link (residual add) before the activation
 
     @property
     def oh(self) -> int:
@@ -56,11 +57,11 @@ class ConvLayer:
         return 2 * m * n * k
 
     def alg_bytes(self, elem: int, bias_elem: int = 4) -> int:
-        """Each tensor once: input + filter + bias + output."""
+        """Each tensor once: input + filter + bias + output (+ the addend of the chain)."""
         x = self.n * self.h * self.w * self.c
         wt = self.k * self.r * self.s * (self.c // self.groups)
         y = self.n * self.oh * self.ow * self.k
-        return (x + wt + y) * elem + self.k * bias_elem
+        return (x + wt + y * (2 if self.add else 1)) * elem + self.k * bias_elem
 
     def with_batch(self, n: int) -> "ConvLayer":
         return dataclasses.replace(self, n=n, name=f"{self.name.split('@b')[0]}@b{n}")
@@ -101,6 +102,34 @@ def resnet50_layers(batch: int) -> List[ConvLayer]:
         ConvLayer(f"rn_1x1_c64_k256_56@b{b}", b, 56, 56, 64, 256, 1, 1, 1, 0),
         ConvLayer(f"rn_3x3_c512_k512_7@b{b}", b, 7, 7, 512, 512, 3, 3, 1, 1),
     ]
+
+
+def resnet50_block_tails(batch: int) -> List[ConvLayer]:
+    """The last convolution of a bottleneck block in each of the four stages, with the block's
+    residual add and Relu stacked on it (Section 5.2): 1x1 expand, + shortcut, max."""
+    b = batch
+    return [
+        ConvLayer(f"rn_tail_1x1_c64_k256_56@b{b}", b, 56, 56, 64, 256, 1, 1, 1, 0, add=True),
+        ConvLayer(f"rn_tail_1x1_c128_k512_28@b{b}", b, 28, 28, 128, 512, 1, 1, 1, 0, add=True),
+        ConvLayer(f"rn_tail_1x1_c256_k1024_14@b{b}", b, 14, 14, 256, 1024, 1, 1, 1, 0, add=True),
+        ConvLayer(f"rn_tail_1x1_c512_k2048_7@b{b}", b, 7, 7, 512, 2048, 1, 1, 1, 0, add=True),
+    ]
+
+
+def addend_f32(layer: ConvLayer, seed: int) -> np.ndarray:
+    """Shortcut tensor of a block tail: unit-variance activations of the output's shape."""
+    rng = np.random.default_rng(seed + 500)
+    return rng.standard_normal(size=(layer.n, layer.oh, layer.ow, layer.k), dtype=np.float32)
+
+
+def addend_q(layer: ConvLayer, seed: int, y_scale: float):
+    """-> int8 shortcut codes, scale, offset: a post-Relu tensor on roughly the output's scale."""
+    rng = np.random.default_rng(seed + 500)
+    r_scale = float(np.float32(y_scale * rng.uniform(0.5, 1.5)))
+    r_off = -128
+    codes = np.clip(np.rint(np.abs(rng.standard_normal(size=(layer.n, layer.oh, layer.ow, layer.k))) / r_scale)
+                    + r_off, -128, 127).astype(np.int8)
+    return codes, r_scale, r_off
 
 
 def vgg19_conv_layers(batch: int = 16) -> List[ConvLayer]:

@@ -68,6 +68,41 @@ def gpu_conv2d_f32(x, w, b, desc, act, use_workspace=True):
     return y.cpu().numpy(), glowmi.last_variant()
 
 
+def gpu_conv2d_f32_chain(x, w, b, addend, desc, act, use_workspace=True, in_place=False):
+    """conv + bias + addend + act through glowmi_conv2d_chain; in_place: the output buffer holds the addend."""
+    oh, ow = glowmi.conv_out_shape(desc)
+    xd, wd, bd = dev(x), dev(w), dev(b)
+    whole, y = guarded((desc.n, oh, ow, desc.k), torch.float32)
+    if in_place:
+        y.copy_(torch.from_numpy(np.ascontiguousarray(addend)))
+        ad = y
+    else:
+        ad = dev(addend)
+    ws = workspace(glowmi.conv2d_workspace_bytes(desc)) if use_workspace else None
+    glowmi.conv2d_chain(xd, wd, bd, y, desc, addend=ad, act=act, workspace=ws)
+    torch.cuda.synchronize()
+    assert guards_intact(whole, torch.float32), "write outside the output tensor"
+    return y.cpu().numpy(), glowmi.last_variant()
+
+
+def gpu_qconv2d_chain(xq, wq, bq, qp, addend_q, r_scale, r_off, desc, act, use_workspace=True, in_place=False):
+    oh, ow = glowmi.conv_out_shape(desc)
+    xd, wd, bd = dev(xq), dev(wq), dev(bq)
+    whole, y = guarded((desc.n, oh, ow, desc.k), torch.int8)
+    if in_place:
+        y.copy_(torch.from_numpy(np.ascontiguousarray(addend_q)))
+        ad = y
+    else:
+        ad = dev(addend_q)
+    ws = workspace(glowmi.qconv2d_workspace_bytes(desc)) if use_workspace else None
+    xp, wp, yp = qparams(qp)
+    glowmi.qconv2d_chain(xd, xp, wd, wp, bd, y, yp, desc, addend=ad, addend_q=glowmi.QParam(r_scale, r_off),
+                         act=act, workspace=ws)
+    torch.cuda.synchronize()
+    assert guards_intact(whole, torch.int8), "write outside the output tensor"
+    return y.cpu().numpy(), glowmi.last_variant()
+
+
 def gpu_fc_f32(a, w, b, act, use_workspace=True):
     M, K = a.shape
     N = w.shape[1]

@@ -105,6 +105,41 @@ def test_requant_params_match_oracle():
     assert glowmi.requant_params(0.5, 0.5, 1.0) == (1 << 30, 32)
 
 
+def test_rescale_params_match_oracle():
+    rng = np.random.default_rng(7)
+    for _ in range(2000):
+        sr, sx, sw = (float(np.float32(v)) for v in rng.uniform(0.001, 0.3, size=3))
+        assert glowmi.rescale_params(sr, sx, sw) == oracle.rescale_params(sr, sx, sw)
+    assert glowmi.rescale_params(0.25, 0.5, 0.5) == (1 << 30, 30)
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.rescale_params(1e30, 1e-30, 1e-30)
+    assert e.value.status == 5
+
+
+def test_chain_errors():
+    d = _desc()
+    ok = glowmi.QParam(0.1, 0)
+    oh, ow = glowmi.conv_out_shape(d)
+    y_bytes = d.n * oh * ow * d.k * 4
+    with pytest.raises(glowmi.GlowmiError) as e:      # misaligned addend
+        glowmi.conv2d_chain(FAKE, FAKE, None, FAKE, d, addend=FAKE + 4, stream=0)
+    assert e.value.status == 4
+    with pytest.raises(glowmi.GlowmiError) as e:      # overlaps the output without being it
+        glowmi.conv2d_chain(FAKE, FAKE, None, FAKE + 4096, d, addend=FAKE + 4096 + 16, stream=0)
+    assert e.value.status == 3 and y_bytes > 16
+    with pytest.raises(glowmi.GlowmiError) as e:      # addend offset out of range
+        glowmi.qconv2d_chain(FAKE, ok, FAKE, ok, None, FAKE, ok, d, addend=FAKE + (1 << 20),
+                             addend_q=glowmi.QParam(0.1, 200), stream=0)
+    assert e.value.status == 5
+    with pytest.raises(glowmi.GlowmiError) as e:      # addend scale unusable
+        glowmi.qconv2d_chain(FAKE, ok, FAKE, ok, None, FAKE, ok, d, addend=FAKE + (1 << 20),
+                             addend_q=glowmi.QParam(0.0, 0), stream=0)
+    assert e.value.status == 5
+    import ctypes
+    status = glowmi.library().glowmi_conv2d_chain(FAKE, FAKE, None, FAKE, ctypes.byref(d), None, None, 0, 0)
+    assert status == 1                                # NULL chain
+
+
 def test_workspace_queries_are_pure():
     assert glowmi.fc_workspace_bytes(16, 25088, 4096) > 0
     assert glowmi.fc_workspace_bytes(0, 1, 1) == 0

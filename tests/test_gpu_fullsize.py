@@ -99,3 +99,34 @@ def test_fc_sweep_int8(li):
     ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off, act=layer.act)
     got, variant = G.gpu_qfc(aq, wq, bq, qp, layer.act)
     G.assert_equal_i8(got, ref, f"{layer.name} [{variant}]")
+
+
+@pytest.mark.parametrize("li", range(4))
+def test_resnet50_block_tails_fp32(li):
+    """1x1 expand convolution + residual add + Relu in one kernel, at batch 32."""
+    G = _gpu()
+    layer = wl.resnet50_block_tails(32)[li]
+    seed = wl.layer_seed(5, li)
+    x, w, b = wl.conv_inputs_f32(layer, seed)
+    add = wl.addend_f32(layer, seed)
+    got, variant = G.gpu_conv2d_f32_chain(x, w, b, add, G.desc_of(layer), layer.act)
+    idx = wl.sample_output_indices(layer, seed)
+    ref = oracle.conv2d_f32_add_points(x, w, b, add, idx, (1, 1), (0, 0, 0, 0), 1, act=layer.act)
+    assert np.all(np.isfinite(got)), f"{layer.name}: unwritten or non-finite outputs"
+    G.assert_close_f32(got.reshape(-1)[idx], ref, f"{layer.name} [{variant}]")
+    assert 0.2 < np.mean(ref > 0) < 0.8        # the add and the Relu both matter on these inputs
+
+
+@pytest.mark.parametrize("li", range(4))
+def test_resnet50_block_tails_int8(li):
+    G = _gpu()
+    layer = wl.resnet50_block_tails(32)[li]
+    seed = wl.layer_seed(5, li)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, seed)
+    rq, r_scale, r_off = wl.addend_q(layer, seed, qp.y_scale)
+    got, variant = G.gpu_qconv2d_chain(xq, wq, bq, qp, rq, r_scale, r_off, G.desc_of(layer), layer.act)
+    idx = wl.sample_output_indices(layer, seed)
+    ref = oracle.qconv2d_add_points(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, rq, r_scale, r_off,
+                                    qp.y_scale, qp.y_off, idx, (1, 1), (0, 0, 0, 0), 1, act=layer.act)
+    G.assert_equal_i8(got.reshape(-1)[idx], ref, f"{layer.name} [{variant}]")
+    assert 0.02 < np.mean((ref > -128) & (ref < 127)), "almost everything saturates"

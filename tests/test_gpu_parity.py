@@ -305,3 +305,88 @@ def test_quantized_large_and_small_multipliers(mr_exp):
     ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wf, qp.w_scale, qp.w_off, bf, qp.y_scale, qp.y_off, act=wl.ACT_NONE)
     got, _ = G.gpu_qfc(aq, wf, bf, qp, wl.ACT_NONE)
     G.assert_equal_i8(got, ref, f"qfc multiplier 0.8*2^{mr_exp}")
+
+
+# ---------------------------------------------------------------------------------------------------
+# element-wise chain with a tensor add (residual add + Relu in the producing kernel)
+# ---------------------------------------------------------------------------------------------------
+CHAIN_CASES = [0, 3, 4, 7, 8, 9, 10, 11]     # generic tiles, groups, stem shape, split-K, ragged tails
+
+
+@pytest.mark.parametrize("i", CHAIN_CASES)
+@pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_NONE])
+def test_conv2d_chain_f32(i, act):
+    G = _gpu()
+    x, wt, b, st, pd, g = _conv_case(i)
+    desc = G.make_desc(x.shape, wt.shape, st, pd, g)
+    oh, ow = oracle.out_dim(x.shape[1], wt.shape[1], st[0], pd[0], pd[2]), oracle.out_dim(x.shape[2], wt.shape[2], st[1], pd[1], pd[3])
+    add = np.random.default_rng(6000 + i).uniform(-1, 1, size=(x.shape[0], oh, ow, wt.shape[0])).astype(np.float32)
+    ref = oracle.conv2d_f32_add(x, wt, b, add, st, pd, g, act=act)
+    for use_ws in (True, False):
+        for in_place in (False, True):
+            got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, desc, act, use_workspace=use_ws, in_place=in_place)
+            G.assert_close_f32(got, ref, f"chain case {i} act {act} ws {use_ws} in-place {in_place} [{variant}]")
+    # a chain without the add link is the plain operator
+    got, _ = G.gpu_conv2d_f32_chain(x, wt, b, None, desc, act)
+    G.assert_close_f32(got, oracle.conv2d_f32(x, wt, b, st, pd, g, act=act), f"chain case {i} without addend")
+
+
+@pytest.mark.parametrize("shape", PW_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_conv2d_chain_f32_pointwise(shape, monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_F32_PW_MIN_ITEMS", "1")
+    n, h, w, c, k, st = shape
+    rng = np.random.default_rng(6100 + 7 * c + k)
+    x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
+    wt = (rng.uniform(-1, 1, size=(k, 1, 1, c)) / np.sqrt(c)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(k,)).astype(np.float32)
+    desc = G.make_desc(x.shape, wt.shape, (st, st), (0, 0, 0, 0), 1)
+    oh, ow = (h - 1) // st + 1, (w - 1) // st + 1
+    add = rng.uniform(-1, 1, size=(n, oh, ow, k)).astype(np.float32)
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.conv2d_f32_add(x, wt, b, add, (st, st), (0, 0, 0, 0), 1, act=act)
+        for in_place in (False, True):
+            got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, desc, act, in_place=in_place)
+            assert variant.startswith("conv_pw_f32") and variant.endswith("_add"), variant
+            G.assert_close_f32(got, ref, f"pointwise chain {shape} act {act} in-place {in_place} [{variant}]")
+
+
+@pytest.mark.parametrize("i", CHAIN_CASES)
+@pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", 0), ("normal", -7)])
+def test_qconv2d_chain(i, dist, w_off):
+    G = _gpu()
+    (xq, wq, bq, qp), st, pd, g = _qconv_case(i, dist, w_off)
+    desc = G.make_desc(xq.shape, wq.shape, st, pd, g)
+    oh, ow = oracle.out_dim(xq.shape[1], wq.shape[1], st[0], pd[0], pd[2]), oracle.out_dim(xq.shape[2], wq.shape[2], st[1], pd[1], pd[3])
+    rng = np.random.default_rng(6200 + i)
+    rq = rng.integers(-128, 128, size=(xq.shape[0], oh, ow, wq.shape[0]), dtype=np.int8)
+    # addend scales on both sides of the accumulator's: multipliers well above and below one
+    for r_scale, r_off in ((float(np.float32(qp.y_scale * 0.7)), 9), (float(np.float32(qp.x_scale * qp.w_scale * 0.3)), -4)):
+        for act in (wl.ACT_RELU, wl.ACT_NONE):
+            ref = oracle.qconv2d_add(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, rq, r_scale, r_off,
+                                     qp.y_scale, qp.y_off, st, pd, g, act=act)
+            for use_ws, in_place in ((True, False), (False, True)):
+                got, variant = G.gpu_qconv2d_chain(xq, wq, bq, qp, rq, r_scale, r_off, desc, act,
+                                                   use_workspace=use_ws, in_place=in_place)
+                G.assert_equal_i8(got, ref, f"qchain case {i} {dist} w_off {w_off} r_scale {r_scale} act {act} "
+                                            f"ws {use_ws} in-place {in_place} [{variant}]")
+
+
+@pytest.mark.parametrize("shape", PWQ_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_qconv2d_chain_pointwise(shape, monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")
+    n, h, w, c, k, st = shape
+    layer = wl.ConvLayer("pw", n, h, w, c, k, 1, 1, st, 0, 1)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 6300 + 3 * c + k, dist="normal", w_off=0)
+    desc = G.make_desc(xq.shape, wq.shape, (st, st), (0, 0, 0, 0), 1)
+    oh, ow = (h - 1) // st + 1, (w - 1) // st + 1
+    rq = np.random.default_rng(6300 + k).integers(-128, 128, size=(n, oh, ow, k), dtype=np.int8)
+    r_scale, r_off = float(np.float32(qp.y_scale * 0.6)), -11
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.qconv2d_add(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, rq, r_scale, r_off,
+                                 qp.y_scale, qp.y_off, (st, st), (0, 0, 0, 0), 1, act=act)
+        for in_place in (False, True):
+            got, variant = G.gpu_qconv2d_chain(xq, wq, bq, qp, rq, r_scale, r_off, desc, act, in_place=in_place)
+            assert variant.startswith("conv_pw_i8") and variant.endswith("_add"), variant
+            G.assert_equal_i8(got, ref, f"pointwise qchain {shape} act {act} in-place {in_place} [{variant}]")
