@@ -168,6 +168,36 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
                                    const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
                                    size_t workspace_bytes, hipStream_t stream);
 
+/*
+ * Conversions at the borders of the integer islands of Section 4.2, on the device, so that quantized
+ * layers can be chained without the host.  count elements, device pointers, 16-byte aligned, the
+ * output must not overlap the input (except glowmi_rescale, which may run in place: out == in).
+ *   glowmi_quantize    q = saturate(round(v / scale) + offset), the inverse of the Section 4.1 formula;
+ *                      the quotient is formed in double and rounded to nearest, ties to even.
+ *   glowmi_dequantize  v = (q - offset) * scale                                   (Section 4.1).
+ *   glowmi_rescale     the rescale node of Section 4.3: the same real values on another scale/offset,
+ *                      out = saturate(round((in - from.offset) * from.scale / to.scale) + to.offset), the
+ *                      multiplier applied in the integer form of glowmi_qconv2d (ties go up).
+ */
+glowmi_status glowmi_quantize(const float* x, int8_t* q, size_t count, glowmi_qparam qp, hipStream_t stream);
+glowmi_status glowmi_dequantize(const int8_t* q, float* x, size_t count, glowmi_qparam qp, hipStream_t stream);
+glowmi_status glowmi_rescale(const int8_t* in, glowmi_qparam from, int8_t* out, glowmi_qparam to, size_t count,
+                             hipStream_t stream);
+
+/*
+ * Host-side, compile-time transformation (the paper merges batch normalization into the preceding
+ * convolution before code generation, Section 5.3): fold y = gamma * (conv - mean) / sqrt(var + eps)
+ * + beta into the filter and bias,
+ *     w_out[k][...] = w[k][...] * gamma[k] / sqrt(var[k] + eps)
+ *     bias_out[k]   = (bias[k] - mean[k]) * gamma[k] / sqrt(var[k] + eps) + beta[k]
+ * so that glowmi_conv2d on (w_out, bias_out) computes convolution + batch normalization.
+ * ALL POINTERS ARE HOST POINTERS.  w, w_out: k filters of elems_per_filter floats (r*s*c/groups);
+ * bias may be NULL (zeros); w_out may be w and bias_out may be bias.  Evaluated in double, rounded once.
+ */
+glowmi_status glowmi_fold_batchnorm(const float* w, const float* bias, const float* gamma, const float* beta,
+                                    const float* mean, const float* var, float eps, int32_t k,
+                                    int64_t elems_per_filter, float* w_out, float* bias_out);
+
 /* Host helper: the integer multiplier/shift the quantized entry points derive from three scales. */
 glowmi_status glowmi_requant_params(float x_scale, float w_scale, float y_scale, int32_t* mant,
                                     int32_t* shift);

@@ -56,6 +56,7 @@ def _bind(path: str) -> ctypes.CDLL:
     L.oracle_conv2d_f32_points.argtypes = [vp, vp, vp, vp, ctypes.c_int, vp, i64, vp]
     L.oracle_conv2d_f32_add.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int]
     L.oracle_conv2d_f32_add_points.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int, vp, i64, vp]
+    L.oracle_rescale.argtypes = [vp, i64, f32, i32, f32, i32, vp]
     L.oracle_rescale_params.argtypes = [f32, f32, f32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
     L.oracle_rescale_term.argtypes = [i32, i32, i32]
     L.oracle_rescale_term.restype = i64
@@ -236,6 +237,25 @@ def requantize(acc: int, mant: int, shift: int, y_offset: int, lo: int = -128) -
     return int(lib().oracle_requantize(int(acc), int(mant), int(shift), int(y_offset), int(lo)))
 
 
+def quantize_f32(x, scale: float, offset: int) -> np.ndarray:
+    """Codes of a float32 tensor: the float values are exact in double, then `quantize`."""
+    return quantize(np.asarray(x, dtype=np.float32).astype(np.float64), scale, offset)
+
+
+def dequantize_f32(q, scale: float, offset: int) -> np.ndarray:
+    """Values of a quantized tensor rounded once to float32 ((q - offset) * scale is exact in double)."""
+    return dequantize(q, scale, offset).astype(np.float32)
+
+
+def rescale(q, s_in: float, in_offset: int, s_out: float, out_offset: int) -> np.ndarray:
+    q = _arr(q, np.int8)
+    out = np.empty(q.shape, dtype=np.int8)
+    rc = lib().oracle_rescale(_ptr(q), q.size, s_in, in_offset, s_out, out_offset, _ptr(out))
+    if rc:
+        raise OracleError(rc, "rescale")
+    return out
+
+
 def rescale_params(sr: float, sx: float, sw: float) -> Tuple[int, int]:
     """(mant, shift) of the multiplier sr / (sx*sw) that brings an addend to the accumulator's scale."""
     m, s = ctypes.c_int32(0), ctypes.c_int32(0)
@@ -326,3 +346,18 @@ def qfc(aq, a_scale, a_off, wq, w_scale, w_off, bias_q, y_scale, y_off, act=ACT_
     if rc:
         raise OracleError(rc, "qfc")
     return (y, acc) if return_acc else y
+
+
+def fold_batchnorm(w, bias, gamma, beta, mean, var, eps: float):
+    """Batch normalization merged into the preceding convolution (the paper does this before code
+    generation, Section 5.3): y = gamma * (conv - mean) / sqrt(var + eps) + beta becomes a
+    convolution with w' = w * gamma / sqrt(var + eps), b' = (b - mean) * gamma / sqrt(var + eps) + beta.
+    float64 arithmetic, one rounding to float32 at the end.  -> (w', b')"""
+    w64 = np.asarray(w, dtype=np.float32).astype(np.float64)
+    k = w64.shape[0]
+    g, bt, mu, vr = (np.asarray(a, dtype=np.float32).astype(np.float64).reshape(k) for a in (gamma, beta, mean, var))
+    b64 = np.zeros(k) if bias is None else np.asarray(bias, dtype=np.float32).astype(np.float64).reshape(k)
+    scale = g / np.sqrt(vr + np.float64(np.float32(eps)))
+    w_f = w64 * scale.reshape((k,) + (1,) * (w64.ndim - 1))
+    b_f = (b64 - mu) * scale + bt
+    return w_f.astype(np.float32), b_f.astype(np.float32)

@@ -18,6 +18,7 @@
  *   - quantized tensors      : Section 4.1, value = (input - offset) * scale, int8 range [-128, 127].
  *   - requantize             : Section 4.3 (rescale folded into the numeric-producing operation) and the
  *                              same-scale max of Section 4.3 for the quantized Relu.
+ *   - rescale                : Section 4.3 (rescale nodes change the range of the integers).
  *   - chain with a tensor add: Section 5.2 (stacked data-parallel operators work on one memory
  *                              location one after the other; the fused Add + max loop of the
  *                              code-generation figure of Section 5.3): Y = act(conv + bias + addend).
@@ -286,6 +287,20 @@ static int qconv_acc_one(const int8_t *x, int32_t x_off, const int8_t *w, int32_
 
 static int offsets_ok(int32_t a, int32_t b, int32_t c) {
   return a >= -128 && a <= 127 && b >= -128 && b <= 127 && c >= -128 && c <= 127;
+}
+
+/* The rescale node of Section 4.3 on its own: the same real values on another scale/offset,
+ * out = sat(round_half_up((in - in_offset) * s_in / s_out) + out_offset), with the multiplier s_in / s_out
+ * in the mantissa/shift form of oracle_requant_params. */
+int oracle_rescale(const int8_t *in, int64_t count, float s_in, int32_t in_offset, float s_out,
+                   int32_t out_offset, int8_t *out) {
+  if (in_offset < -128 || in_offset > 127 || out_offset < -128 || out_offset > 127) return ORACLE_BAD_QUANT;
+  int32_t mant = 0, shift = 0;
+  const int rc = oracle_requant_params(s_in, 1.0f, s_out, &mant, &shift);
+  if (rc) return rc;
+  for (int64_t i = 0; i < count; ++i)
+    out[i] = (int8_t)oracle_requantize((int32_t)in[i] - in_offset, mant, shift, out_offset, -128);
+  return ORACLE_OK;
 }
 
 /* Rescale of a quantized addend (scale sr) to the accumulator's scale sx*sw: the multiplier

@@ -16,8 +16,10 @@ from .binding import (  # noqa: F401
     conv2d_chain,
     conv2d_workspace_bytes,
     conv_out_shape,
+    dequantize,
     fc,
     fc_workspace_bytes,
+    fold_batchnorm,
     last_variant,
     library,
     library_path,
@@ -26,6 +28,8 @@ from .binding import (  # noqa: F401
     qconv2d_workspace_bytes,
     qfc,
     qfc_workspace_bytes,
+    quantize,
     requant_params,
+    rescale,
     rescale_params,
 )

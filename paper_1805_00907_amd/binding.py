@@ -75,6 +75,10 @@ def library() -> ctypes.CDLL:
     cp = ctypes.POINTER(Chain)
     L.glowmi_conv2d_chain.argtypes = [vp, vp, vp, vp, dp, cp, vp, sz, vp]
     L.glowmi_qconv2d_chain.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, dp, cp, vp, sz, vp]
+    L.glowmi_quantize.argtypes = [vp, vp, sz, QParam, vp]
+    L.glowmi_dequantize.argtypes = [vp, vp, sz, QParam, vp]
+    L.glowmi_rescale.argtypes = [vp, QParam, vp, QParam, sz, vp]
+    L.glowmi_fold_batchnorm.argtypes = [vp] * 6 + [ctypes.c_float, i32, ctypes.c_int64, vp, vp]
     L.glowmi_requant_params.argtypes = [ctypes.c_float] * 3 + [ctypes.POINTER(i32)] * 2
     L.glowmi_rescale_params.argtypes = [ctypes.c_float] * 3 + [ctypes.POINTER(i32)] * 2
     L.glowmi_status_string.argtypes = [ctypes.c_int]
@@ -198,3 +202,34 @@ def rescale_params(r_scale: float, x_scale: float, w_scale: float) -> Tuple[int,
     m, s = ctypes.c_int32(0), ctypes.c_int32(0)
     _check(library().glowmi_rescale_params(r_scale, x_scale, w_scale, ctypes.byref(m), ctypes.byref(s)))
     return m.value, s.value
+
+
+def quantize(x, q, qp: QParam, count: Optional[int] = None, stream=None) -> None:
+    """float32 device tensor x -> int8 device tensor q with scale/offset qp."""
+    n = x.numel() if count is None else count
+    _check(library().glowmi_quantize(_ptr(x), _ptr(q), n, qp, _stream(stream)))
+
+
+def dequantize(q, x, qp: QParam, count: Optional[int] = None, stream=None) -> None:
+    n = q.numel() if count is None else count
+    _check(library().glowmi_dequantize(_ptr(q), _ptr(x), n, qp, _stream(stream)))
+
+
+def rescale(q_in, from_q: QParam, q_out, to_q: QParam, count: Optional[int] = None, stream=None) -> None:
+    """The same real values on another scale/offset; q_out may be q_in."""
+    n = q_in.numel() if count is None else count
+    _check(library().glowmi_rescale(_ptr(q_in), from_q, _ptr(q_out), to_q, n, _stream(stream)))
+
+
+def fold_batchnorm(w, bias, gamma, beta, mean, var, eps: float):
+    """Host arrays (numpy float32): -> (w_folded, bias_folded) with batch normalization merged in."""
+    import numpy as np
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    k = w.shape[0]
+    per = w.size // k
+    arrs = [None if a is None else np.ascontiguousarray(a, dtype=np.float32) for a in (bias, gamma, beta, mean, var)]
+    w_out, b_out = np.empty_like(w), np.empty((k,), dtype=np.float32)
+    hp = lambda a: None if a is None else a.ctypes.data
+    _check(library().glowmi_fold_batchnorm(hp(w), hp(arrs[0]), hp(arrs[1]), hp(arrs[2]), hp(arrs[3]), hp(arrs[4]),
+                                           eps, k, per, hp(w_out), hp(b_out)))
+    return w_out, b_out

@@ -336,6 +336,84 @@ glowmi_status glowmi_qfc(const int8_t* a, glowmi_qparam aq, const int8_t* w, glo
   return finish(glowmi::launch_i8(p, stream, &variant), variant);
 }
 
+static glowmi_status check_elementwise(const void* in, const void* out, size_t count, size_t in_elem,
+                                       size_t out_elem, bool in_place_ok) {
+  if (!in || !out) return fail(GLOWMI_ERR_NULL, "input and output pointers must not be NULL");
+  if (count == 0) return fail(GLOWMI_ERR_SHAPE, "count must be positive");
+  if (count > (size_t)kMaxElems) return fail(GLOWMI_ERR_UNSUPPORTED, "a tensor has 2^31 or more elements");
+  if (!aligned(in, 16) || !aligned(out, 16)) return fail(GLOWMI_ERR_ALIGN, "pointers must be 16-byte aligned");
+  const uintptr_t a = reinterpret_cast<uintptr_t>(in), o = reinterpret_cast<uintptr_t>(out);
+  if (!(in_place_ok && a == o) && a < o + count * out_elem && o < a + count * in_elem)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "output overlaps the input");
+  return GLOWMI_OK;
+}
+
+static glowmi_status check_qparam(glowmi_qparam q, const char* what) {
+  if (!std::isfinite(q.scale) || q.scale <= 0.0f)
+    return fail(GLOWMI_ERR_QUANT, "%s scale %g is not finite and positive", what, (double)q.scale);
+  if (q.offset < -128 || q.offset > 127) return fail(GLOWMI_ERR_QUANT, "%s offset %d outside [-128, 127]", what, q.offset);
+  return GLOWMI_OK;
+}
+
+glowmi_status glowmi_quantize(const float* x, int8_t* q, size_t count, glowmi_qparam qp, hipStream_t stream) {
+  glowmi_status st = check_elementwise(x, q, count, 4, 1, false);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_qparam(qp, "tensor")) != GLOWMI_OK) return st;
+  return finish(glowmi::launch_quantize(x, reinterpret_cast<signed char*>(q), (long long)count, qp.scale, qp.offset, stream),
+                "quantize");
+}
+
+glowmi_status glowmi_dequantize(const int8_t* q, float* x, size_t count, glowmi_qparam qp, hipStream_t stream) {
+  glowmi_status st = check_elementwise(q, x, count, 1, 4, false);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_qparam(qp, "tensor")) != GLOWMI_OK) return st;
+  return finish(glowmi::launch_dequantize(reinterpret_cast<const signed char*>(q), x, (long long)count, qp.scale,
+                                          qp.offset, stream),
+                "dequantize");
+}
+
+glowmi_status glowmi_rescale(const int8_t* in, glowmi_qparam from, int8_t* out, glowmi_qparam to, size_t count,
+                             hipStream_t stream) {
+  glowmi_status st = check_elementwise(in, out, count, 1, 1, true);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_qparam(from, "input")) != GLOWMI_OK) return st;
+  if ((st = check_qparam(to, "output")) != GLOWMI_OK) return st;
+  int32_t mant = 0, shift = 0;
+  if ((st = glowmi_requant_params(from.scale, 1.0f, to.scale, &mant, &shift)) != GLOWMI_OK) return st;
+  return finish(glowmi::launch_rescale(reinterpret_cast<const signed char*>(in), reinterpret_cast<signed char*>(out),
+                                       (long long)count, from.offset, mant, shift, to.offset, stream),
+                "rescale");
+}
+
+#pragma clang fp contract(off)   // every product and sum below is rounded on its own, as written
+glowmi_status glowmi_fold_batchnorm(const float* w, const float* bias, const float* gamma, const float* beta,
+                                    const float* mean, const float* var, float eps, int32_t k,
+                                    int64_t elems_per_filter, float* w_out, float* bias_out) {
+  if (!w || !gamma || !beta || !mean || !var || !w_out || !bias_out)
+    return fail(GLOWMI_ERR_NULL, "filter, statistics and output pointers must not be NULL");
+  if (k <= 0 || elems_per_filter <= 0) return fail(GLOWMI_ERR_SHAPE, "k and elems_per_filter must be positive");
+  if (!std::isfinite(eps) || eps < 0.0f) return fail(GLOWMI_ERR_SHAPE, "eps must be finite and non-negative");
+  for (int32_t i = 0; i < k; ++i) {
+    const double denom = (double)var[i] + (double)eps;
+    if (!(denom > 0.0) || !std::isfinite(denom))
+      return fail(GLOWMI_ERR_SHAPE, "var[%d] + eps = %g is not positive and finite", i, denom);
+  }
+  for (int32_t i = 0; i < k; ++i) {
+    const double root = std::sqrt((double)var[i] + (double)eps);
+    const double scale = (double)gamma[i] / root;
+    for (int64_t e = 0; e < elems_per_filter; ++e) {
+      const double prod = (double)w[(int64_t)i * elems_per_filter + e] * scale;
+      w_out[(int64_t)i * elems_per_filter + e] = (float)prod;
+    }
+    const double centred = (bias ? (double)bias[i] : 0.0) - (double)mean[i];
+    const double scaled = centred * scale;
+    const double shifted = scaled + (double)beta[i];
+    bias_out[i] = (float)shifted;
+  }
+  g_error[0] = 0;
+  return GLOWMI_OK;
+}
+
 // A positive multiplier as mant * 2^-shift, mant a 31-bit integer with its top bit set.
 static glowmi_status multiplier_params(double mr, int32_t* mant, int32_t* shift);
 

@@ -82,6 +82,14 @@ hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** varia
 bool smallc_i8_applicable(const Problem& p);
 hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant);
 
+// Element-wise conversions between float and quantized tensors (elementwise.hip).
+hipError_t launch_quantize(const float* x, signed char* q, long long count, float scale, int offset,
+                           hipStream_t stream);
+hipError_t launch_dequantize(const signed char* q, float* x, long long count, float scale, int offset,
+                             hipStream_t stream);
+hipError_t launch_rescale(const signed char* in, signed char* out, long long count, int in_offset, int mant,
+                          int shift, int out_offset, hipStream_t stream);
+
 // Split-K planning shared by the ABI layer (workspace sizing) and the launchers.
 struct Plan {
   int tile;             // index into the kernel file's tile table

@@ -453,6 +453,54 @@ def pin_conv_add_f32():
                                rtol=1e-7, atol=1e-7)
 
 
+def pin_rescale_node():
+    """The stand-alone rescale: exact rationals for every code, identity on equal types, and the
+    real-valued rule (same real value on the new scale) within one code."""
+    rng = np.random.default_rng(34)
+    codes = np.arange(-128, 128, dtype=np.int8)
+    for _ in range(200):
+        s_in, s_out = (float(np.float32(v)) for v in rng.uniform(0.01, 0.3, size=2))
+        o_in, o_out = (int(v) for v in rng.integers(-128, 128, size=2))
+        got = oracle.rescale(codes, s_in, o_in, s_out, o_out)
+        m, sh = oracle.requant_params(s_in, 1.0, s_out)
+        exp = np.array([_exact_requant(int(c) - o_in, m, sh, o_out, -128) for c in codes], dtype=np.int64)
+        np.testing.assert_array_equal(got.astype(np.int64), exp)
+        real = (codes.astype(np.float64) - o_in) * s_in / s_out + o_out
+        inside = (real > -127) & (real < 126)
+        assert np.all(np.abs(got.astype(np.float64) - real)[inside] <= 0.5 + 1e-6)
+    np.testing.assert_array_equal(oracle.rescale(codes, 0.125, 7, 0.125, 7), codes)
+    # halving the scale doubles the distance from the offset (until saturation)
+    got = oracle.rescale(codes, 0.25, 0, 0.125, 0).astype(np.int64)
+    np.testing.assert_array_equal(got, np.clip(2 * codes.astype(np.int64), -128, 127))
+    # float tensors: quantize(dequantize(q)) == q through the float32 wrappers as well
+    for scale, off in ((0.5, -3), (0.0123, 17)):
+        np.testing.assert_array_equal(oracle.quantize_f32(oracle.dequantize_f32(codes, scale, off), scale, off), codes)
+    assert oracle.dequantize_f32(np.array([-128, -3, 127], np.int8), 0.5, -3).tolist() == [-62.5, 0.0, 65.0]
+
+
+def pin_fold_batchnorm():
+    """Convolution with the folded filter equals batch normalization applied to the convolution,
+    the latter written out from the definition on the float64 im2col reference."""
+    rng = np.random.default_rng(35)
+    for (n, h, w, c, k, r, s, st, pd, g) in TINY_SHAPES[1:6]:
+        x = _rand(rng, (n, h, w, c)); wt = _rand(rng, (k, r, s, c // g)); b = _rand(rng, (k,))
+        gamma = rng.uniform(0.5, 1.5, size=k).astype(np.float32); beta = _rand(rng, (k,))
+        mean = _rand(rng, (k,)); var = rng.uniform(0.1, 2.0, size=k).astype(np.float32)
+        eps = 1e-3
+        conv = im2col_matmul(x, wt, b, st, pd, g)
+        ref = gamma.astype(np.float64) * (conv - mean.astype(np.float64)) / np.sqrt(var.astype(np.float64) + eps) \
+            + beta.astype(np.float64)
+        wf, bf = oracle.fold_batchnorm(wt, b, gamma, beta, mean, var, eps)
+        got = oracle.conv2d_f32(x, wf, bf, st, pd, g)
+        np.testing.assert_allclose(got.astype(np.float64), ref, rtol=2e-5, atol=2e-5)
+    # identity statistics leave the layer alone
+    wf, bf = oracle.fold_batchnorm(wt, b, np.ones(k), np.zeros(k), np.zeros(k), np.ones(k), 0.0)
+    np.testing.assert_array_equal(wf, wt); np.testing.assert_array_equal(bf, b)
+    # no bias: b' = -mean * scale + beta
+    wf, bf = oracle.fold_batchnorm(wt, None, gamma, beta, mean, var, 0.0)
+    np.testing.assert_allclose(bf, -mean / np.sqrt(var) * gamma + beta, rtol=1e-6, atol=1e-6)
+
+
 def _exact_rescale(d, mant, shift):
     return math.floor(Fraction(d * mant, 1 << shift) + Fraction(1, 2))
 
@@ -550,4 +598,6 @@ ALL_PINS = [
     pin_conv_add_f32,
     pin_rescale_params_and_term,
     pin_qconv_add,
+    pin_rescale_node,
+    pin_fold_batchnorm,
 ]

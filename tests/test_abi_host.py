@@ -140,6 +140,37 @@ def test_chain_errors():
     assert status == 1                                # NULL chain
 
 
+def test_fold_batchnorm_matches_oracle():
+    """Host-only entry point: runs without a GPU.  Same double arithmetic, so bit-identical."""
+    rng = np.random.default_rng(8)
+    for k, shape in ((5, (5, 3, 3, 4)), (64, (64, 7, 7, 3)), (1, (1, 1, 1, 9))):
+        w = rng.standard_normal(size=shape).astype(np.float32)
+        b = rng.standard_normal(size=k).astype(np.float32)
+        gamma = rng.uniform(0.5, 1.5, size=k).astype(np.float32)
+        beta, mean = (rng.standard_normal(size=k).astype(np.float32) for _ in range(2))
+        var = rng.uniform(0.05, 3.0, size=k).astype(np.float32)
+        for bias in (b, None):
+            got_w, got_b = glowmi.fold_batchnorm(w, bias, gamma, beta, mean, var, 1e-5)
+            ref_w, ref_b = oracle.fold_batchnorm(w, bias, gamma, beta, mean, var, 1e-5)
+            np.testing.assert_array_equal(got_w, ref_w)
+            np.testing.assert_array_equal(got_b, ref_b)
+    with pytest.raises(glowmi.GlowmiError) as e:      # variance + eps not positive
+        glowmi.fold_batchnorm(w, b, gamma, beta, mean, np.zeros(1, np.float32), 0.0)
+    assert e.value.status == 2
+
+
+def test_elementwise_errors():
+    ok = glowmi.QParam(0.1, 0)
+    lib = glowmi.library()
+    assert lib.glowmi_quantize(None, FAKE, 16, ok, 0) == 1
+    assert lib.glowmi_quantize(FAKE, FAKE + (1 << 20), 0, ok, 0) == 2
+    assert lib.glowmi_quantize(FAKE, FAKE + 4, 16, ok, 0) == 4
+    assert lib.glowmi_quantize(FAKE, FAKE + 32, 16, ok, 0) == 3                      # overlap
+    assert lib.glowmi_dequantize(FAKE, FAKE + (1 << 20), 16, glowmi.QParam(0.0, 0), 0) == 5
+    assert lib.glowmi_rescale(FAKE, ok, FAKE + 16, ok, 64, 0) == 3                   # partial overlap
+    assert lib.glowmi_rescale(FAKE, ok, FAKE + (1 << 20), glowmi.QParam(0.1, 300), 64, 0) == 5
+
+
 def test_workspace_queries_are_pure():
     assert glowmi.fc_workspace_bytes(16, 25088, 4096) > 0
     assert glowmi.fc_workspace_bytes(0, 1, 1) == 0

@@ -390,3 +390,44 @@ def test_qconv2d_chain_pointwise(shape, monkeypatch):
             got, variant = G.gpu_qconv2d_chain(xq, wq, bq, qp, rq, r_scale, r_off, desc, act, in_place=in_place)
             assert variant.startswith("conv_pw_i8") and variant.endswith("_add"), variant
             G.assert_equal_i8(got, ref, f"pointwise qchain {shape} act {act} in-place {in_place} [{variant}]")
+
+
+# ---------------------------------------------------------------------------------------------------
+# conversions at the borders of the integer islands: quantize / dequantize / rescale on the device
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("count", [1, 15, 16, 17, 4096, 100003, 1 << 21])
+def test_quantize_dequantize_rescale(count):
+    import torch
+    import paper_1805_00907_amd as glowmi
+    rng = np.random.default_rng(7000 + count % 97)
+    scale, off = float(np.float32(rng.uniform(0.01, 0.1))), int(rng.integers(-30, 31))
+    x = (rng.standard_normal(size=count) * 3.0).astype(np.float32)
+    # exact ties and values far outside the range exercise rounding to even and saturation
+    x[: min(count, 8)] = (np.array([0.5, 1.5, 2.5, -0.5, -1.5, 1e6, -1e6, 0.0], np.float32) * np.float32(scale))[: min(count, 8)]
+    xd = torch.from_numpy(x).to("cuda:0")
+    qd = torch.full((count + 64,), 77, dtype=torch.int8, device="cuda:0")
+    glowmi.quantize(xd, qd, glowmi.QParam(scale, off), count=count)
+    torch.cuda.synchronize()
+    q = qd.cpu().numpy()
+    np.testing.assert_array_equal(q[:count], oracle.quantize_f32(x, scale, off))
+    assert np.all(q[count:] == 77), "write past the end"
+
+    vd = torch.full((count + 64,), float("nan"), dtype=torch.float32, device="cuda:0")
+    glowmi.dequantize(qd, vd, glowmi.QParam(scale, off), count=count)
+    torch.cuda.synchronize()
+    v = vd.cpu().numpy()
+    np.testing.assert_array_equal(v[:count], oracle.dequantize_f32(q[:count], scale, off))
+    assert np.all(np.isnan(v[count:])), "write past the end"
+
+    for s_out, o_out in ((float(np.float32(scale * 2.3)), -7), (float(np.float32(scale * 0.11)), 12), (scale, off)):
+        rd = torch.full((count + 64,), 55, dtype=torch.int8, device="cuda:0")
+        glowmi.rescale(qd, glowmi.QParam(scale, off), rd, glowmi.QParam(s_out, o_out), count=count)
+        torch.cuda.synchronize()
+        r = rd.cpu().numpy()
+        np.testing.assert_array_equal(r[:count], oracle.rescale(q[:count], scale, off, s_out, o_out))
+        assert np.all(r[count:] == 55), "write past the end"
+    # in place
+    rd = qd.clone()
+    glowmi.rescale(rd, glowmi.QParam(scale, off), rd, glowmi.QParam(0.05, 3), count=count)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(rd.cpu().numpy()[:count], oracle.rescale(q[:count], scale, off, 0.05, 3))

@@ -71,6 +71,10 @@ MUTANTS = [
     ("rescale_rounds_to_zero", "if ((t % den) < 0) q -= 1;", "", None),
     ("rescale_after_requantize", "acc += extra;", "", None),
     ("points_addend_index", "(int32_t)addend[flat_idx[i]] - r_off", "(int32_t)addend[i] - r_off", None),
+    ("rescale_node_inverted", "oracle_requant_params(s_in, 1.0f, s_out, &mant, &shift);",
+     "oracle_requant_params(s_out, 1.0f, s_in, &mant, &shift);", None),
+    ("rescale_node_offset_sign", "(int32_t)in[i] - in_offset", "(int32_t)in[i] + in_offset", None),
+    ("rescale_node_wrong_out_offset", "mant, shift, out_offset, -128);", "mant, shift, in_offset, -128);", None),
     ("overflow_unchecked", "if (s > INT32_MAX || s < INT32_MIN) { overflow |= 1; continue; }", "", None),
 ]
 
