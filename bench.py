@@ -29,7 +29,8 @@ PEAK_INT8_MFMA = 5.0e15        # OP/s
 PEAK_HBM = 8.0e12              # B/s
 
 WORKLOADS = ["resnet50_fp32", "vgg19_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8",
-             "resnet50_tail_fp32", "resnet50_tail_int8"]
+             "resnet50_tail_fp32", "resnet50_tail_int8", "resnet50_block_fp32", "resnet50_block_int8"]
+CHAINED = {"resnet50_block_fp32", "resnet50_block_int8"}   # layers feed each other: run as one sequence
 
 
 def _build_workload(name):
@@ -48,6 +49,10 @@ def _build_workload(name):
         return "f32", 5, wl.resnet50_block_tails(32)
     if name == "resnet50_tail_int8":
         return "i8", 5, wl.resnet50_block_tails(32)
+    if name == "resnet50_block_fp32":  # a whole bottleneck block back to back out of one planned arena
+        return "f32", 6, wl.resnet50_bottleneck(32)
+    if name == "resnet50_block_int8":
+        return "i8", 6, wl.resnet50_bottleneck(32)
     raise SystemExit(f"unknown workload {name}; choose from {WORKLOADS}")
 
 
@@ -123,6 +128,47 @@ class Layer:
                 g.qfc(self.x, xq, self.w, wq, self.b, self.y, yq, s.M, s.K, s.N, s.act, self.ws, stream)
 
 
+class Sequence:
+    """A chain of layers launched with ONE glowmi_seq_* call: activations live in a single arena whose
+    regions are planned up front; presented to the timing code as one layer."""
+
+    class _Spec:
+        def __init__(self, name, gemm):
+            self.name, self.gemm = name, gemm
+
+    def __init__(self, layers, dtype, torch, glowmi, name):
+        self.parts, self.dtype, self.glowmi = layers, dtype, glowmi
+        self.spec = Sequence._Spec(name, (0, 0, 0))
+        self.ops = sum(l.ops for l in layers)
+        # algorithmic bytes of the block: its input, filters and biases, its output; intermediates
+        # are the block's own business
+        elem = 4 if dtype == "f32" else 1
+        first, last = layers[0].spec, layers[-1].spec
+        self.bytes = (first.n * first.h * first.w * first.c + last.n * last.oh * last.ow * last.k) * elem + \
+            sum(l.spec.k * l.spec.r * l.spec.s * (l.spec.c // l.spec.groups) * elem + 4 * l.spec.k for l in layers)
+        peak = PEAK_FP32_MFMA if dtype == "f32" else PEAK_INT8_MFMA
+        t_mfma, t_hbm = self.ops / peak, self.bytes / PEAK_HBM
+        self.bound = "mfma" if t_mfma >= t_hbm else "hbm"
+        self.t_roof = max(t_mfma, t_hbm)
+        self.x = layers[0].x
+        self.y = layers[-1].y
+        if dtype == "f32":
+            tuples = [(l.desc, l.w, l.b, l.spec.act, l.spec.add) for l in layers]
+        else:
+            tuples = [(l.desc, l.w, l.b, l.spec.act, l.spec.add, l.qp[1], l.qp[2]) for l in layers]
+            self.xq = layers[0].qp[0]
+        self.arr = glowmi.seq_layers(tuples)
+        nbytes = glowmi.seq_arena_bytes(self.arr, dtype != "f32")
+        self.arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+        self.variant = "sequence"
+
+    def launch(self, stream):
+        if self.dtype == "f32":
+            self.glowmi.seq_conv2d(self.x, self.arr, self.y, self.arena, stream)
+        else:
+            self.glowmi.seq_qconv2d(self.x, self.xq, self.arr, self.y, self.arena, stream)
+
+
 def _cpu_baseline(workload, dtype, cfg_index, unit_scale, budget_s=15.0):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample."""
     import oracle
@@ -189,6 +235,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="resnet50_fp32", choices=WORKLOADS)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time replays of it (launch-overhead "
+                         "amortisation); the roofline figure then comes from the eager calibration pass")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a kernel of known traffic, used to "
                          "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -209,6 +258,8 @@ def main():
 
     dtype, cfg_index, specs = _build_workload(args.workload)
     layers = [Layer(s, dtype, wl.layer_seed(cfg_index, i), torch, glowmi) for i, s in enumerate(specs)]
+    if args.workload in CHAINED:
+        layers = [Sequence(layers, dtype, torch, glowmi, f"{args.workload}@b{specs[0].n} ({len(specs)} launches)")]
     unit = "TFLOP/s" if dtype == "f32" else "TOP/s"
     total_ops = sum(l.ops for l in layers)
 
@@ -225,7 +276,7 @@ def main():
 
     for l in layers:                      # first touch + variant names
         l.launch(stream)
-        l.variant = glowmi.last_variant()
+        l.variant = ("sequence:" if isinstance(l, Sequence) else "") + glowmi.last_variant()
     torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
@@ -253,23 +304,44 @@ def main():
     dom_ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in dom_idx]
               for _ in range(args.steps)]
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(args.steps):
-        j = 0
-        for i, l in enumerate(layers):
-            if j < len(dom_idx) and dom_idx[j] == i:
-                dom_ev[s][j][0].record(stream)
-                l.launch(stream)
-                dom_ev[s][j][1].record(stream)
-                j += 1
-            else:
-                l.launch(stream)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    if args.graph:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step_on = lambda st: [l.launch(st) for l in layers]
+            step_on(side)
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step_on(side)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    else:
+        t0 = time.perf_counter()
+        for s in range(args.steps):
+            j = 0
+            for i, l in enumerate(layers):
+                if j < len(dom_idx) and dom_idx[j] == i:
+                    dom_ev[s][j][0].record(stream)
+                    l.launch(stream)
+                    dom_ev[s][j][1].record(stream)
+                    j += 1
+                else:
+                    l.launch(stream)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = total_ops / (ms_per_step * 1e-3) / 1e12
 
-    dom_ms = [dom_ev[s][j][0].elapsed_time(dom_ev[s][j][1]) for s in range(args.steps) for j in range(len(dom_idx))]
+    if args.graph:   # no events inside a captured graph: the dominant kernel's figure is the calibration pass's
+        dom_ms = [per_layer_ms[i] for i in dom_idx]
+    else:
+        dom_ms = [dom_ev[s][j][0].elapsed_time(dom_ev[s][j][1]) for s in range(args.steps) for j in range(len(dom_idx))]
     avg_launch_s = sum(dom_ms) / len(dom_ms) * 1e-3
     dom_layers = [layers[i] for i in dom_idx]
     dom_ops = sum(l.ops for l in dom_layers) / len(dom_layers)          # algorithmic ops per launch
@@ -302,7 +374,7 @@ def main():
         "value": round(value, 3), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if dtype == "f32" else "int8", "data": "synthetic",
-        "config": {"workload": args.workload, "layers": len(layers),
+        "config": {"workload": args.workload, "layers": len(layers), "launch": "hip graph replay" if args.graph else "eager",
                    "note": "ResNet-50/VGG-19 layer shapes, seeded synthetic values; no trained weights"},
         "roofline": roofline,
     }

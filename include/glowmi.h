@@ -169,6 +169,39 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
                                    size_t workspace_bytes, hipStream_t stream);
 
 /*
+ * A straight sequence of convolution layers (with their stacked chains) run back to back on one
+ * stream out of ONE caller-provided arena.  The paper's low-level IR marks the lifetime of every
+ * activation (alloc/dealloc, Section 3.5) and all of them are then allocated statically in a single
+ * buffer (Section 5.3); in a straight sequence two alternately used regions hold every intermediate.
+ * The arena also carries the split-reduction workspace.  Layer i reads layer i-1's output (layer 0
+ * reads x); the last layer writes y.  add_input != 0 adds the sequence input x (an identity shortcut;
+ * shapes must match) in that layer's chain before its activation: 1x1 -> 3x3 -> 1x1 with add_input on
+ * the last layer is a residual bottleneck block in three launches.  Nothing is synchronised or
+ * allocated, so the whole sequence can be captured in a HIP graph (fewer launches is the other gain
+ * the paper names for stacking on GPUs, Section 5.2).
+ *   w, bias: device pointers, float / float for glowmi_seq_conv2d, int8 / int32 for glowmi_seq_qconv2d.
+ *   wq, yq:  quantized form only: the filter's and the layer output's scale/offset; a layer's input
+ *            type is the previous layer's yq (xq for layer 0); the shortcut is x with xq.
+ *   arena:   device memory, 16-byte aligned, at least glowmi_seq_arena_bytes(); contents undefined after.
+ * Errors: GLOWMI_ERR_SHAPE when consecutive layers (or the shortcut) do not fit, GLOWMI_ERR_ALIGN when
+ * the arena is too small or misaligned, otherwise the status of the failing layer call.
+ */
+typedef struct glowmi_seq_layer {
+  glowmi_conv_desc desc;
+  const void* w;
+  const void* bias;
+  glowmi_qparam wq, yq;
+  glowmi_act act;
+  int32_t add_input;
+} glowmi_seq_layer;
+
+size_t glowmi_seq_arena_bytes(const glowmi_seq_layer* layers, int32_t n, int32_t quantized);
+glowmi_status glowmi_seq_conv2d(const float* x, const glowmi_seq_layer* layers, int32_t n, float* y, void* arena,
+                                size_t arena_bytes, hipStream_t stream);
+glowmi_status glowmi_seq_qconv2d(const int8_t* x, glowmi_qparam xq, const glowmi_seq_layer* layers, int32_t n,
+                                 int8_t* y, void* arena, size_t arena_bytes, hipStream_t stream);
+
+/*
  * Conversions at the borders of the integer islands of Section 4.2, on the device, so that quantized
  * layers can be chained without the host.  count elements, device pointers, 16-byte aligned, the
  * output must not overlap the input (except glowmi_rescale, which may run in place: out == in).

@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     ConvDesc,
     GlowmiError,
     QParam,
+    SeqLayer,
     conv2d,
     conv2d_chain,
     conv2d_workspace_bytes,
@@ -32,4 +33,8 @@ from .binding import (  # noqa: F401
     requant_params,
     rescale,
     rescale_params,
+    seq_arena_bytes,
+    seq_conv2d,
+    seq_layers,
+    seq_qconv2d,
 )

@@ -32,6 +32,12 @@ class Chain(ctypes.Structure):
     _fields_ = [("addend", ctypes.c_void_p), ("addend_q", QParam), ("act", ctypes.c_int)]
 
 
+class SeqLayer(ctypes.Structure):
+    """glowmi_seq_layer: one layer of a back-to-back sequence."""
+    _fields_ = [("desc", ConvDesc), ("w", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("wq", QParam),
+                ("yq", QParam), ("act", ctypes.c_int), ("add_input", ctypes.c_int32)]
+
+
 class GlowmiError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
@@ -75,6 +81,11 @@ def library() -> ctypes.CDLL:
     cp = ctypes.POINTER(Chain)
     L.glowmi_conv2d_chain.argtypes = [vp, vp, vp, vp, dp, cp, vp, sz, vp]
     L.glowmi_qconv2d_chain.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, dp, cp, vp, sz, vp]
+    sp = ctypes.POINTER(SeqLayer)
+    L.glowmi_seq_arena_bytes.argtypes = [sp, i32, i32]
+    L.glowmi_seq_arena_bytes.restype = sz
+    L.glowmi_seq_conv2d.argtypes = [vp, sp, i32, vp, vp, sz, vp]
+    L.glowmi_seq_qconv2d.argtypes = [vp, QParam, sp, i32, vp, vp, sz, vp]
     L.glowmi_quantize.argtypes = [vp, vp, sz, QParam, vp]
     L.glowmi_dequantize.argtypes = [vp, vp, sz, QParam, vp]
     L.glowmi_rescale.argtypes = [vp, QParam, vp, QParam, sz, vp]
@@ -233,3 +244,31 @@ def fold_batchnorm(w, bias, gamma, beta, mean, var, eps: float):
     _check(library().glowmi_fold_batchnorm(hp(w), hp(arrs[0]), hp(arrs[1]), hp(arrs[2]), hp(arrs[3]), hp(arrs[4]),
                                            eps, k, per, hp(w_out), hp(b_out)))
     return w_out, b_out
+
+
+def seq_layers(layers) -> "ctypes.Array":
+    """ctypes array of SeqLayer from (desc, w, bias, act, add_input[, wq, yq]) tuples of device tensors."""
+    arr = (SeqLayer * len(layers))()
+    for i, l in enumerate(layers):
+        desc, w, bias, act, add_input = l[:5]
+        wq, yq = (l[5], l[6]) if len(l) > 5 else (QParam(1.0, 0), QParam(1.0, 0))
+        arr[i] = SeqLayer(desc, _ptr(w), _ptr(bias), wq, yq, act, 1 if add_input else 0)
+    return arr
+
+
+def seq_arena_bytes(arr, quantized: bool) -> int:
+    return int(library().glowmi_seq_arena_bytes(arr, len(arr), 1 if quantized else 0))
+
+
+def seq_conv2d(x, arr, y, arena, stream=None) -> None:
+    ap, ab = _ws(arena)
+    st = library().glowmi_seq_conv2d(_ptr(x), arr, len(arr), _ptr(y), ap, ab, _stream(stream))
+    if st != 0:
+        raise GlowmiError(st, library().glowmi_last_error().decode() or "sequence rejected")
+
+
+def seq_qconv2d(x, xq: QParam, arr, y, arena, stream=None) -> None:
+    ap, ab = _ws(arena)
+    st = library().glowmi_seq_qconv2d(_ptr(x), xq, arr, len(arr), _ptr(y), ap, ab, _stream(stream))
+    if st != 0:
+        raise GlowmiError(st, library().glowmi_last_error().decode() or "sequence rejected")

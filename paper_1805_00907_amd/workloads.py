@@ -116,6 +116,17 @@ def resnet50_block_tails(batch: int) -> List[ConvLayer]:
     ]
 
 
+def resnet50_bottleneck(batch: int) -> List[ConvLayer]:
+    """One identity-shortcut bottleneck block of the 56x56 stage as a chain: 1x1 reduce, 3x3, 1x1
+    expand whose chain adds the block input and applies Relu.  Each layer reads its predecessor."""
+    b = batch
+    return [
+        ConvLayer(f"rn_block_1x1_c256_k64_56@b{b}", b, 56, 56, 256, 64, 1, 1, 1, 0),
+        ConvLayer(f"rn_block_3x3_c64_k64_56@b{b}", b, 56, 56, 64, 64, 3, 3, 1, 1),
+        ConvLayer(f"rn_block_1x1_c64_k256_56@b{b}", b, 56, 56, 64, 256, 1, 1, 1, 0, add=True),
+    ]
+
+
 def addend_f32(layer: ConvLayer, seed: int) -> np.ndarray:
     """Shortcut tensor of a block tail: unit-variance activations of the output's shape."""
     rng = np.random.default_rng(seed + 500)

@@ -171,6 +171,26 @@ def test_elementwise_errors():
     assert lib.glowmi_rescale(FAKE, ok, FAKE + (1 << 20), glowmi.QParam(0.1, 300), 64, 0) == 5
 
 
+def test_sequence_planning_and_errors():
+    """Arena planning is host code: two alternating activation regions + the largest workspace."""
+    d1 = glowmi.ConvDesc(2, 8, 8, 16, 8, 1, 1, 1, 1, 0, 0, 0, 0, 1)      # -> 2x8x8x8
+    d2 = glowmi.ConvDesc(2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1, 1, 1)       # -> 2x8x8x8
+    d3 = glowmi.ConvDesc(2, 8, 8, 8, 16, 1, 1, 1, 1, 0, 0, 0, 0, 1)      # -> 2x8x8x16 (+ shortcut)
+    arr = glowmi.seq_layers([(d1, FAKE, None, 1, False), (d2, FAKE, None, 1, False), (d3, FAKE, None, 1, True)])
+    act_bytes = 2 * 8 * 8 * 8 * 4
+    need = glowmi.seq_arena_bytes(arr, False)
+    assert need >= 2 * act_bytes and need % 256 == 0
+    assert glowmi.seq_arena_bytes(arr, True) >= 2 * (act_bytes // 4)
+    lib = glowmi.library()
+    assert lib.glowmi_seq_conv2d(FAKE, arr, 3, FAKE, FAKE, need - 256, 0) == 4          # arena too small
+    bad = glowmi.seq_layers([(d1, FAKE, None, 1, False), (d3, FAKE, None, 1, False), (d2, FAKE, None, 1, False)])
+    assert glowmi.seq_arena_bytes(bad, False) == 0
+    assert lib.glowmi_seq_conv2d(FAKE, bad, 3, FAKE, FAKE, 1 << 20, 0) == 2             # shapes do not chain
+    short = glowmi.seq_layers([(d1, FAKE, None, 1, True)])                              # shortcut shape mismatch
+    assert lib.glowmi_seq_conv2d(FAKE, short, 1, FAKE, FAKE, 1 << 20, 0) == 2
+    assert lib.glowmi_seq_conv2d(None, arr, 3, FAKE, FAKE, need, 0) == 1
+
+
 def test_workspace_queries_are_pure():
     assert glowmi.fc_workspace_bytes(16, 25088, 4096) > 0
     assert glowmi.fc_workspace_bytes(0, 1, 1) == 0

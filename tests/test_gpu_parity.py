@@ -431,3 +431,103 @@ def test_quantize_dequantize_rescale(count):
     glowmi.rescale(rd, glowmi.QParam(scale, off), rd, glowmi.QParam(0.05, 3), count=count)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(rd.cpu().numpy()[:count], oracle.rescale(q[:count], scale, off, 0.05, 3))
+
+
+# ---------------------------------------------------------------------------------------------------
+# a bottleneck block as one sequence out of one arena (1x1 reduce -> 3x3 -> 1x1 expand + shortcut + Relu)
+# ---------------------------------------------------------------------------------------------------
+def _block_layers(n, hw, c, mid):
+    return [wl.ConvLayer("b1", n, hw, hw, c, mid, 1, 1, 1, 0), wl.ConvLayer("b2", n, hw, hw, mid, mid, 3, 3, 1, 1),
+            wl.ConvLayer("b3", n, hw, hw, mid, c, 1, 1, 1, 0, add=True)]
+
+
+@pytest.mark.parametrize("n,hw,c,mid", [(2, 9, 32, 8), (3, 14, 256, 64), (1, 28, 128, 64)])
+def test_sequence_f32_bottleneck(n, hw, c, mid, monkeypatch):
+    """Every layer of the sequence against the oracle fed with the GPU's own previous activation
+    (prefix sequences are deterministic), to the single-operator tolerance; plus replays of the
+    captured graph against the eager result."""
+    import torch
+    import paper_1805_00907_amd as glowmi
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_F32_PW_MIN_ITEMS", "1")
+    specs = _block_layers(n, hw, c, mid)
+    data = [wl.conv_inputs_f32(s, 8000 + i) for i, s in enumerate(specs)]
+    x = data[0][0]
+    xd = G.dev(x)
+    dev_w = [(G.dev(w), G.dev(b)) for (_, w, b) in data]
+    tuples = [(G.desc_of(s), w, b, s.act, s.add) for s, (w, b) in zip(specs, dev_w)]
+    outs = []
+    for upto in (1, 2, 3):
+        arr = glowmi.seq_layers(tuples[:upto])
+        arena = torch.empty(glowmi.seq_arena_bytes(arr, False), dtype=torch.uint8, device="cuda:0")
+        s = specs[upto - 1]
+        y = G.poison((n, s.oh, s.ow, s.k), torch.float32)
+        if upto == 1 or upto == 2:
+            glowmi.seq_conv2d(xd, arr, y, arena)
+        else:
+            glowmi.seq_conv2d(xd, arr, y, arena)
+        torch.cuda.synchronize()
+        outs.append(y.cpu().numpy())
+    prev = x
+    for i, s in enumerate(specs):
+        _, w, b = data[i]
+        ref = oracle.conv2d_f32_add(prev, w, b, x if s.add else None, (1, 1), (s.pad,) * 4, 1, act=s.act)
+        G.assert_close_f32(outs[i], ref, f"sequence layer {i}")
+        prev = outs[i]
+    # graph replays, with eager work and synchronisation in between, each checked against eager
+    arr = glowmi.seq_layers(tuples)
+    arena = torch.empty(glowmi.seq_arena_bytes(arr, False), dtype=torch.uint8, device="cuda:0")
+    y = G.poison(outs[2].shape, torch.float32)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        glowmi.seq_conv2d(xd, arr, y, arena, side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            glowmi.seq_conv2d(xd, arr, y, arena, side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y.cpu().numpy(), outs[2], err_msg=f"graph replay {rep}")
+        scratch = torch.empty(1 << 16, device="cuda:0").normal_()      # the program's own eager work
+        float(scratch.sum())
+
+
+@pytest.mark.parametrize("n,hw,c,mid", [(2, 9, 32, 16), (3, 14, 256, 64), (1, 28, 128, 64)])
+def test_sequence_int8_bottleneck(n, hw, c, mid, monkeypatch):
+    """Integer arithmetic end to end: the whole block must match the oracle's chain bit for bit."""
+    import torch
+    import paper_1805_00907_amd as glowmi
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")
+    specs = _block_layers(n, hw, c, mid)
+    data = [wl.conv_inputs_q(s, 8100 + i) for i, s in enumerate(specs)]
+    xq = data[0][0]
+    qps = [d[3] for d in data]
+    # a layer's input type is the previous layer's output type
+    in_q = [(qps[0].x_scale, qps[0].x_off)] + [(qps[i].y_scale, qps[i].y_off) for i in range(2)]
+    xd = G.dev(xq)
+    tuples, keep = [], []
+    for i, s in enumerate(specs):
+        _, w, b, qp = data[i]
+        wd, bd = G.dev(w), G.dev(b)
+        keep.append((wd, bd))
+        tuples.append((G.desc_of(s), wd, bd, s.act, s.add, glowmi.QParam(qp.w_scale, qp.w_off),
+                       glowmi.QParam(qp.y_scale, qp.y_off)))
+    arr = glowmi.seq_layers(tuples)
+    arena = torch.empty(glowmi.seq_arena_bytes(arr, True), dtype=torch.uint8, device="cuda:0")
+    last = specs[-1]
+    y = G.poison((n, last.oh, last.ow, last.k), torch.int8)
+    glowmi.seq_qconv2d(xd, glowmi.QParam(*in_q[0]), arr, y, arena)
+    torch.cuda.synchronize()
+    prev = xq
+    for i, s in enumerate(specs):
+        _, w, b, qp = data[i]
+        prev = oracle.qconv2d_add(prev, in_q[i][0], in_q[i][1], w, qp.w_scale, qp.w_off, b,
+                                  xq if s.add else None, in_q[0][0], in_q[0][1], qp.y_scale, qp.y_off,
+                                  (1, 1), (s.pad,) * 4, 1, act=s.act)
+    G.assert_equal_i8(y.cpu().numpy(), prev, "int8 bottleneck sequence")
+    assert 0.02 < np.mean((prev > -128) & (prev < 127)), "almost everything saturates"
