@@ -413,18 +413,37 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
 }
 
 // Finish of a split reduction: sum the partial tiles in split order (deterministic), then the same
-// fused bias + activation, one store.
+// fused bias (+ addend) + activation, one store.  A thread owns W consecutive outputs (W = 4 when the
+// row length allows 16-byte accesses) and walks the splits eight at a time: the eight loads are
+// independent and in flight together, the additions stay in split order.
+template <int W>
 __global__ __launch_bounds__(256) void splitk_finish_f32(const float* __restrict__ partial,
                                                          const float* __restrict__ bias,
                                                          const float* addend, float* y, int total, int k,
                                                          int split_k, int act) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
-    float v = 0.f;
-    for (int s = 0; s < split_k; ++s) v += partial[(size_t)s * total + i];
-    if (bias) v += bias[i % k];
-    if (addend) v += addend[i];
-    if (act == 1) v = fmaxf(v, 0.f);
-    y[i] = v;
+  typedef float vec __attribute__((ext_vector_type(W)));
+  const int groups = total / W;                      // W divides total (the launcher checks)
+  for (int gi = blockIdx.x * blockDim.x + threadIdx.x; gi < groups; gi += gridDim.x * blockDim.x) {
+    const size_t i = (size_t)gi * W;
+    vec v = {};
+    for (int s = 0; s < split_k; s += 8) {
+      vec t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int su = s + u < split_k ? s + u : s;  // a repeated row stands in past the end and is not added
+        t[u] = *reinterpret_cast<const vec*>(partial + (size_t)su * total + i);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (s + u < split_k) v += t[u];
+    }
+    if (bias) v += *reinterpret_cast<const vec*>(bias + i % k);      // W divides k: no wrap inside the vector
+    if (addend) v += *reinterpret_cast<const vec*>(addend + i);
+    if (act == 1) {
+#pragma unroll
+      for (int e = 0; e < W; ++e) v[e] = fmaxf(v[e], 0.f);
+    }
+    *reinterpret_cast<vec*>(y + i) = v;
   }
 }
 
@@ -724,9 +743,11 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
   if (e != hipSuccess) return e;
   if (plan.split_k > 1) {
     const int total = p.M * p.k;
-    int blocks = (total + 255) / 256;
+    const bool wide = p.k % 4 == 0 && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;   // y, partial, addend are 16-byte aligned
+    int blocks = (total / (wide ? 4 : 1) + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(splitk_finish_f32, dim3(blocks), dim3(256), 0, stream,
+    auto kern = wide ? splitk_finish_f32<4> : splitk_finish_f32<1>;
+    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, stream,
                        static_cast<const float*>(p.partial), static_cast<const float*>(p.bias),
                        static_cast<const float*>(p.addend),
                        static_cast<float*>(p.y), total, p.k, plan.split_k, p.act);

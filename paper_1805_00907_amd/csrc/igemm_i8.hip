@@ -412,18 +412,46 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const 
   }
 }
 
+// A thread owns W consecutive outputs (W = 4 when the row length allows: 16-byte loads of the int32
+// partials, one dword of codes stored) and walks the splits eight at a time with the loads in flight
+// together.  Integer sums: any order gives the same result.
+template <int W>
 __global__ __launch_bounds__(256) void splitk_finish_i8(const int* __restrict__ partial,
                                                         const int* __restrict__ bias,
                                                         const signed char* addend, int r_off, int r_mant,
                                                         int r_shift, signed char* y, int total, int k,
                                                         int split_k, int mant, int shift, int y_off,
                                                         int lo) {
-  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
-    unsigned v = 0;
-    for (int s = 0; s < split_k; ++s) v += (unsigned)partial[(size_t)s * total + i];
-    if (bias) v += (unsigned)bias[i % k];
-    if (addend) v += (unsigned)rescale_term((int)addend[i] - r_off, r_mant, r_shift);
-    y[i] = (signed char)requantize((int)v, mant, shift, y_off, lo);
+  typedef unsigned vec __attribute__((ext_vector_type(W)));
+  const int groups = total / W;                      // W divides total (the launcher checks)
+  for (int gi = blockIdx.x * blockDim.x + threadIdx.x; gi < groups; gi += gridDim.x * blockDim.x) {
+    const size_t i = (size_t)gi * W;
+    vec v = {};
+    for (int s = 0; s < split_k; s += 8) {
+      vec t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int su = s + u < split_k ? s + u : s;
+        t[u] = *reinterpret_cast<const vec*>(partial + (size_t)su * total + i);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (s + u < split_k) v += t[u];
+    }
+    if (bias) v += *reinterpret_cast<const vec*>(bias + i % k);      // W divides k: no wrap inside the vector
+    int q[W];
+#pragma unroll
+    for (int e = 0; e < W; ++e) {
+      unsigned a = v[e];
+      if (addend) a += (unsigned)rescale_term((int)addend[i + e] - r_off, r_mant, r_shift);
+      q[e] = requantize((int)a, mant, shift, y_off, lo);
+    }
+    if (W == 4) {
+      *reinterpret_cast<unsigned*>(y + i) = pack_codes(q[0], q[1], q[2], q[3]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < W; ++e) y[i + e] = (signed char)q[e];
+    }
   }
 }
 
@@ -535,9 +563,11 @@ hipError_t launch_i8(const Problem& p_in, hipStream_t stream, const char** varia
   if (e != hipSuccess) return e;
   if (plan.split_k > 1) {
     const int total = p.M * p.k;
-    int blocks = (total + 255) / 256;
+    const bool wide = p.k % 4 == 0 && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;   // y, partial are 16-byte aligned
+    int blocks = (total / (wide ? 4 : 1) + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(splitk_finish_i8, dim3(blocks), dim3(256), 0, stream,
+    auto finish_kernel = wide ? splitk_finish_i8<4> : splitk_finish_i8<1>;
+    hipLaunchKernelGGL(finish_kernel, dim3(blocks), dim3(256), 0, stream,
                        static_cast<const int*>(p.partial), static_cast<const int*>(p.bias),
                        static_cast<const signed char*>(p.addend), p.r_off, p.r_mant, p.r_shift,
                        static_cast<signed char*>(p.y), total, p.k, plan.split_k, p.mant, p.shift,
