@@ -102,4 +102,10 @@ struct Plan {
 Plan plan_f32(const Problem& p, bool allow_split);
 Plan plan_i8(const Problem& p, bool allow_split);
 
+// int8 kernel for large contractions (igemm_i8_wide.hip): 128 x 128 or 128 x 64 output tiles, tile
+// indices 4 and 5 of the int8 plan.
+bool wide_i8_applicable(const Problem& p);
+Plan plan_wide_i8(const Problem& p, int bn, bool allow_split);
+hipError_t launch_wide_i8(const Problem& p, const Plan& plan, hipStream_t stream, const char** variant);
+
 }  // namespace glowmi

@@ -500,9 +500,14 @@ Plan plan_i8(const Problem& p, bool allow_split) {
   pl.bk = BKQ;
   pl.slabs = (p.Kgemm + BKQ - 1) / BKQ;
   int tile = 0;
-  if (const char* env = getenv("GLOWMI_I8_TILE")) {        // experiments: force a tile variant
-    const int t = atoi(env);
-    if (t >= 0 && t < kNumTilesI8) tile = t;
+  int forced = -1;
+  if (const char* env = getenv("GLOWMI_I8_TILE")) forced = atoi(env);   // experiments and tests: force a tile variant
+  if (forced >= 0 && forced < kNumTilesI8) tile = forced;
+  // Large contractions (deep reduction, enough pixels and channels for 128-wide tiles) take the
+  // kernel built for them.
+  if (wide_i8_applicable(p)) {
+    if (forced == 4 || forced == 5) return plan_wide_i8(p, (forced == 4 || p.b_is_kn) ? 128 : 64, allow_split);
+    if (forced < 0 && p.Kgemm >= 1024 && p.M >= 96 && p.kg >= 96) return plan_wide_i8(p, 128, allow_split);
   }
   pl.tile = tile;
   pl.bm = kTilesI8[tile].bm;
@@ -548,17 +553,21 @@ hipError_t launch_i8(const Problem& p_in, hipStream_t stream, const char** varia
   p.slabs_per_split = plan.slabs_per_split;
   const bool fc = p.b_is_kn != 0;
   const bool vec = fc ? (p.Kgemm % 16 == 0 && p.k % 4 == 0) : (p.cg % 16 == 0 && p.c % 16 == 0);
-  static thread_local char name[64];
-  snprintf(name, sizeof(name), "igemm_i8_%s_%s_%s", kTilesI8[plan.tile].name, fc ? "fc" : "conv",
-           vec ? "vec" : "scalar");
-  *variant = name;
   hipError_t e;
-  switch (plan.tile) {
-    case 0: e = launch_tile<64, 64, 2, 2>(p, plan, stream, fc, vec); break;
-    case 1: e = launch_tile<128, 64, 4, 2>(p, plan, stream, fc, vec); break;
-    case 2: e = launch_tile<128, 128, 2, 4>(p, plan, stream, fc, vec); break;
-    case 3: e = launch_tile<128, 128, 2, 2>(p, plan, stream, fc, vec); break;
-    default: return hipErrorInvalidValue;
+  if (plan.tile >= 4) {
+    e = launch_wide_i8(p, plan, stream, variant);
+  } else {
+    static thread_local char name[64];
+    snprintf(name, sizeof(name), "igemm_i8_%s_%s_%s", kTilesI8[plan.tile].name, fc ? "fc" : "conv",
+             vec ? "vec" : "scalar");
+    *variant = name;
+    switch (plan.tile) {
+      case 0: e = launch_tile<64, 64, 2, 2>(p, plan, stream, fc, vec); break;
+      case 1: e = launch_tile<128, 64, 4, 2>(p, plan, stream, fc, vec); break;
+      case 2: e = launch_tile<128, 128, 2, 4>(p, plan, stream, fc, vec); break;
+      case 3: e = launch_tile<128, 128, 2, 2>(p, plan, stream, fc, vec); break;
+      default: return hipErrorInvalidValue;
+    }
   }
   if (e != hipSuccess) return e;
   if (plan.split_k > 1) {

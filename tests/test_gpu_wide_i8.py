@@ -1,0 +1,130 @@
+"""Parity of the int8 kernel for large contractions (128-pixel tiles, reduction slabs split between two
+sets of wavefronts, optional split over workgroups) against the CPU oracle, bit for bit.  The kernel
+is forced through the tile override so that small shapes with ragged tails in every dimension reach
+it; the planner's own choice is covered by the last tests.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_1805_00907_amd import workloads as wl
+
+
+def _gpu():
+    import gpu_util
+    return gpu_util
+
+
+# n  h  w  c  k  r  s  stride  pads(t,l,b,r)  groups
+WIDE_CONV = [
+    (2, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1, 1, 1), 1),        # several M tiles, Kgemm 576 (tail of 64)
+    (2, 7, 7, 128, 136, 3, 3, (1, 1), (1, 1, 1, 1), 1),        # ragged N (136), M = 98 < one tile
+    (3, 19, 17, 48, 40, 3, 3, (1, 1), (1, 1, 1, 1), 1),        # Kgemm 432: chunk tail inside a slab
+    (5, 16, 16, 32, 160, 3, 3, (2, 2), (0, 1, 1, 0), 1),       # stride 2, mixed pads
+    (1, 10, 10, 32, 48, 1, 1, (1, 1), (0, 0, 0, 0), 2),        # groups 2, one 16-byte chunk per tap
+    (1, 12, 9, 16, 8, 5, 3, (2, 1), (2, 0, 1, 2), 1),          # 5x3 filter, asymmetric pads, 8 channels out
+    (4, 5, 5, 16, 32, 5, 5, (1, 1), (0, 0, 0, 0), 1),          # filter covers the whole map
+    (1, 40, 36, 16, 12, 3, 3, (1, 1), (2, 2, 2, 2), 1),        # pad larger than needed, many pixels
+    (2, 9, 9, 256, 260, 3, 3, (1, 1), (1, 1, 1, 1), 1),        # deep reduction (2304), three N tiles, split-K
+    (2, 6, 6, 64, 64, 3, 3, (1, 1), (1, 1, 1, 1), 4),          # 4 groups of 16 channels
+]
+
+
+@pytest.mark.parametrize("i", range(len(WIDE_CONV)))
+@pytest.mark.parametrize("tile", ["4", "5"])
+@pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", -7)])
+def test_qconv2d_wide(i, tile, dist, w_off, monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_TILE", tile)
+    n, h, w, c, k, r, s, st, pd, g = WIDE_CONV[i]
+    layer = wl.ConvLayer(f"wide{i}", n, h, w, c, k, r, s, 1, 0, g)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 8000 + i, dist=dist, w_off=w_off)
+    desc = G.make_desc(xq.shape, wq.shape, st, pd, g)
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                             st, pd, g, act=act)
+        for use_ws in (True, False):
+            got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, act, use_workspace=use_ws)
+            assert variant.startswith("igemm_i8_wide"), variant
+            G.assert_equal_i8(got, ref, f"wide conv {i} tile {tile} {dist} w_off {w_off} act {act} ws {use_ws} [{variant}]")
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, None, qp.y_scale, qp.y_off,
+                         st, pd, g, act=wl.ACT_NONE)
+    got, _ = G.gpu_qconv2d(xq, wq, None, qp, desc, wl.ACT_NONE)
+    G.assert_equal_i8(got, ref, f"wide conv {i} without bias")
+
+
+WIDE_FC = [(130, 272, 132), (5, 64, 8), (256, 1040, 520), (33, 4096, 64), (300, 2048, 1000), (128, 128, 128),
+           (1, 2048, 1000), (97, 6400, 260)]
+
+
+@pytest.mark.parametrize("shape", WIDE_FC, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", 3)])
+def test_qfc_wide(shape, dist, w_off, monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_TILE", "4")
+    M, K, N = shape
+    layer = wl.FcLayer("wide", M, K, N)
+    aq, wq, bq, qp = wl.fc_inputs_q(layer, 8100 + M + K + N, dist=dist, w_off=w_off)
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off, act=act)
+        for use_ws in (True, False):
+            got, variant = G.gpu_qfc(aq, wq, bq, qp, act, use_workspace=use_ws)
+            assert variant.startswith("igemm_i8_wide"), variant
+            G.assert_equal_i8(got, ref, f"wide qfc {shape} {dist} act {act} ws {use_ws} [{variant}]")
+
+
+@pytest.mark.parametrize("i", [0, 1, 3, 8])
+def test_qconv2d_chain_wide(i, monkeypatch):
+    """Tensor-add link of the element-wise chain behind the wide kernel, out of place and in place."""
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_TILE", "4")
+    n, h, w, c, k, r, s, st, pd, g = WIDE_CONV[i]
+    layer = wl.ConvLayer(f"wide{i}", n, h, w, c, k, r, s, 1, 0, g)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 8200 + i, dist="normal", w_off=0)
+    desc = G.make_desc(xq.shape, wq.shape, st, pd, g)
+    oh, ow = oracle.out_dim(h, r, st[0], pd[0], pd[2]), oracle.out_dim(w, s, st[1], pd[1], pd[3])
+    rq = np.random.default_rng(8200 + i).integers(-128, 128, size=(n, oh, ow, k), dtype=np.int8)
+    r_scale, r_off = float(np.float32(qp.y_scale * 0.7)), 9
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.qconv2d_add(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, rq, r_scale, r_off,
+                                 qp.y_scale, qp.y_off, st, pd, g, act=act)
+        for use_ws, in_place in ((True, False), (False, True)):
+            got, variant = G.gpu_qconv2d_chain(xq, wq, bq, qp, rq, r_scale, r_off, desc, act,
+                                               use_workspace=use_ws, in_place=in_place)
+            assert variant.startswith("igemm_i8_wide"), variant
+            G.assert_equal_i8(got, ref, f"wide qchain {i} act {act} ws {use_ws} in-place {in_place} [{variant}]")
+
+
+@pytest.mark.parametrize("mr_exp", [-1, 1, -3, -8])
+def test_qfc_wide_multipliers(mr_exp, monkeypatch):
+    """Both requantize forms (64-bit for multipliers from 1/4 up, multiply-high below)."""
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_TILE", "4")
+    rng = np.random.default_rng(8300 + mr_exp)
+    aq = rng.integers(-4, 5, size=(70, 192), dtype=np.int8)
+    wf = rng.integers(-4, 5, size=(192, 144), dtype=np.int8)
+    bf = rng.integers(-20, 20, size=(144,), dtype=np.int32)
+    qp = wl.QParams(0.8, 1, float(2.0 ** mr_exp), 0, 1.0, -3)
+    ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wf, qp.w_scale, qp.w_off, bf, qp.y_scale, qp.y_off, act=wl.ACT_RELU)
+    got, variant = G.gpu_qfc(aq, wf, bf, qp, wl.ACT_RELU)
+    assert variant.startswith("igemm_i8_wide"), variant
+    G.assert_equal_i8(got, ref, f"wide qfc multiplier 0.8*2^{mr_exp}")
+
+
+def test_wide_kernel_is_the_planner_choice_for_large_contractions():
+    """Without any override a deep, wide layer goes to the wide kernel and a shallow one does not."""
+    G = _gpu()
+    layer = wl.FcLayer("big", 200, 1536, 384)
+    aq, wq, bq, qp = wl.fc_inputs_q(layer, 8400)
+    ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off, act=wl.ACT_RELU)
+    got, variant = G.gpu_qfc(aq, wq, bq, qp, wl.ACT_RELU)
+    assert variant.startswith("igemm_i8_wide"), variant
+    G.assert_equal_i8(got, ref, "planner-chosen wide qfc")
+    small = wl.FcLayer("small", 8, 64, 32)
+    aq, wq, bq, qp = wl.fc_inputs_q(small, 8401)
+    ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off, act=wl.ACT_NONE)
+    got, variant = G.gpu_qfc(aq, wq, bq, qp, wl.ACT_NONE)
+    assert not variant.startswith("igemm_i8_wide"), variant
+    G.assert_equal_i8(got, ref, "small qfc")
