@@ -3,23 +3,28 @@
 // accumulation, the rescale folded into the producer, Relu as an integer lower bound) for layers
 // whose cost is the contraction itself rather than moving bytes.
 //
-// For v_mfma_i32_32x32x32_i8 a wavefront must reuse every operand fragment it reads from LDS at
-// least twice, and the vector ALU gets about seven issue slots per MFMA, so this kernel is built
-// around what is spent per reduction slab besides the MFMAs:
+// For v_mfma_i32_32x32x32_i8 a wavefront gets about seven vector-ALU issue slots per MFMA and must
+// reuse every operand fragment it reads from LDS at least twice, so the kernel spends as little as
+// possible per reduction slab besides the MFMAs:
 //   - one workgroup = 128 pixels x BN channels, eight wavefronts: 2 x 2 wavefronts tile the output
 //     (64 x BN/2 each, 2 x BN/64 MFMA tiles) and two such sets split every 128-code slab between them
-//     (codes 0..63 and 64..127), so each SIMD always has two wavefronts to interleave, however small
-//     the grid is; the two partial tiles are exchanged through LDS at the end and each wavefront
-//     finishes half of them;
-//   - staging is specialised by wavefront: four stage the filter slab, four the input slab; the
-//     gathers are 16-byte loads held in registers for three slabs (three slabs in flight) before
-//     they are written to double-buffered LDS;
+//     (codes 0..63 and 64..127); the two partial tiles are exchanged through LDS at the end and each
+//     wavefront finishes half of them;
+//   - both operands go from global memory straight into LDS (buffer loads with the LDS bit, 16 bytes
+//     per lane, no staging registers, no LDS store instructions) into a ring of NBUF slab buffers,
+//     NBUF-1 slabs in flight; out-of-range lanes (rows past the tensor, reduction tail, taps on
+//     padding) make the hardware write zeros, and a padding chunk is then overwritten with the code
+//     of real zero by the lane that issued it;
+//   - a lane's LDS destination is fixed (base + 16 * lane), its global source is not: lane l of a
+//     load fetches chunk (l % 8) ^ (l / 8) of row l / 8, which XOR-swizzles the 16-byte chunks of the
+//     128-byte rows so that fragment reads are spread over the banks;
+//   - the FullyConnected weight ([K][N], N contiguous) is staged as it lies in memory and the MFMA
+//     fragments (16 consecutive reduction codes per lane) are read with the transposing LDS load
+//     (ds_read_b64_tr_b8: within 16 lanes, result byte e of lane i comes from byte i % 8 of the 8
+//     bytes addressed by lane 2e + i / 8);
 //   - whether a filter tap falls on padding is one bit test against a per-pixel mask computed once;
-//   - the FullyConnected weight ([K][N], N contiguous) is turned K-contiguous with byte permutes
-//     (16 x 4 bytes per thread, eight permutes per 16 bytes) on its way to LDS;
-//   - LDS rows are 128 bytes, 16-byte chunks XOR-swizzled by the row so that fragment reads, the
-//     row-wise writes of the gathers and the column-wise writes of the transposed weight are all
-//     spread over the banks.
+//   - the code sums needed to remove the offsets are taken with dot-product instructions from the
+//     fragments the wavefronts read anyway.
 // Offsets are removed after the contraction exactly as in the generic kernel:
 //   sum (x - xo)(w - wo) = sum x*w - xo * sum_k w - wo * sum_k x + Kcount * xo * wo,
 // padded taps staged as the code xo.  Everything after the accumulator is integer arithmetic.
@@ -27,7 +32,6 @@
 
 #include <cstdio>
 #include <cstdlib>
-#include <type_traits>
 
 #include "igemm.h"
 #include "quant_epilogue.h"
@@ -35,17 +39,40 @@
 namespace glowmi {
 namespace {
 
+typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WBM = 128;                 // pixels per workgroup tile
 constexpr int WBK = 128;                 // codes per reduction slab
 constexpr int WTHREADS = 512;
-constexpr int WSTAGES = 3;               // slabs held in registers between the gather and LDS
 
-// Byte offset of 16-byte chunk c (0..7) of row `row` inside a staged operand.
-__device__ __forceinline__ int chunk_at(int row, int c) {
-  return row * WBK + ((c ^ (row & 7) ^ ((row >> 3) & 3)) << 4);
+#define GLOWMI_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+// 16 bytes per lane from a range-checked buffer straight into LDS at lds_addr + 16 * lane (lanes whose
+// offset is out of range write zeros).  Issued as inline assembly on purpose: for the intrinsic form
+// the compiler cannot tell which later LDS reads depend on which load and waits for all outstanding
+// loads before every LDS read, which would serialise the ring of slab buffers; here the kernel
+// places the vmcnt waits itself.  lds_addr is wave-uniform.
+__device__ __forceinline__ void load16_to_lds(v4i rsrc, unsigned lds_addr, unsigned voffset) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc)
+               : "memory");
+}
+
+__device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
+  const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+  v4i r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+  r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((a >> 32) & 0xffffu));   // stride 0: raw buffer
+  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);                              // num_records in bytes
+  r[3] = 0x00020000;
+  return r;
+}
+
+__device__ __forceinline__ unsigned lds_offset_of(const void* p) {
+  return (unsigned)(unsigned long long)GLOWMI_LDS_PTR(p);
 }
 
 __device__ __forceinline__ int sum4(int packed, int acc) {   // acc + the four signed bytes
@@ -57,22 +84,29 @@ __device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_of
                      : requantize_as<false>(acc, mant, shift, y_off, lo);   // uniform branch
 }
 
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and
+// leaves the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
+
 // PADDED: some filter tap of some pixel may fall on padding (otherwise the per-tap tests are dropped).
 // XSUM: the filter offset is not zero, so the input code sums per pixel are needed as well.
-template <int BN, bool B_KN, bool PADDED, bool XSUM>
-__global__ __launch_bounds__(WTHREADS) void igemm_i8_wide_kernel(const Problem p, int tiles_m, int tiles_n,
-                                                                int band_n, int total_work) {
+// NBUF: slab buffers in the LDS ring (2: two workgroups per CU, 4: one workgroup with three slabs in flight).
+template <int BN, bool B_KN, bool PADDED, bool XSUM, int NBUF>
+__global__ __launch_bounds__(WTHREADS, NBUF <= 2 ? 2 : 1) void igemm_i8_wide_kernel(const Problem p, int tiles_m,
+                                                                                   int tiles_n, int band_n,
+                                                                                   int total_work) {
   static_assert(BN == 64 || BN == 128, "channel tile");
-  static_assert(!B_KN || BN == 128, "the transposing weight path stages 128 columns");
+  static_assert(!B_KN || BN == 128, "the [K][N] weight path stages 128 columns");
   constexpr int TN = BN / 64;                           // MFMA tiles along the channels per wavefront
+  constexpr int BT = BN / 64;                           // filter loads per wavefront and slab ([k][r][s][c] layout)
+  constexpr int LPI = 2 + (B_KN ? 2 : BT);              // loads one wavefront issues per slab
   constexpr int A_BYTES = WBM * WBK, B_BYTES = BN * WBK, BUF = A_BYTES + B_BYTES;
-  constexpr int BQ = BN / 32;                           // 16-byte chunks a filter-staging thread moves per slab
   constexpr int OUT_PITCH = BN + 16;
-  static_assert(2 * BUF >= WBM * OUT_PITCH, "output staging fits the slab buffers");
-  static_assert(2 * BUF >= 8 * TN * 16 * 64 * 4, "exchange of the partial tiles fits the slab buffers");
+  static_assert(NBUF * BUF >= WBM * OUT_PITCH, "output staging fits the slab buffers");
+  static_assert(NBUF * BUF >= 8 * TN * 16 * 64 * 4, "exchange of the partial tiles fits the slab buffers");
 
   extern __shared__ __align__(16) unsigned char lds[];
-  int* xsum = reinterpret_cast<int*>(lds + 2 * BUF);    // [128] input code sums per pixel row
+  int* xsum = reinterpret_cast<int*>(lds + NBUF * BUF); // [128] input code sums per pixel row
   int* wsum = xsum + WBM;                               // [BN]  filter code sums per channel
   int* cterm = wsum + BN;                               // [BN]  per-channel additive term
 
@@ -98,14 +132,10 @@ __global__ __launch_bounds__(WTHREADS) void igemm_i8_wide_kernel(const Problem p
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int kgrp = wave >> 2;                           // which half of every slab this wavefront multiplies
   const int wm = (wave >> 1) & 1, wn = wave & 1;
-  const bool stage_a = wave >= 4;                       // wavefronts 4..7 gather the input, 0..3 the filter
-  const int st = tid & 255;                             // index among the 256 threads of one staging role
   const int lrow = lane & 31, lhalf = lane >> 5;
 
-  const __amdgpu_buffer_rsrc_t rsrc_x =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.x), 0, (int)p.x_bytes, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rsrc_w =
-      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w), 0, (int)p.w_bytes, 0x00020000);
+  const v4i rsrc_x = make_rsrc(p.x, p.x_bytes);
+  const v4i rsrc_w = make_rsrc(p.w, p.w_bytes);
   constexpr unsigned OOB = 0x80000000u;                 // beyond any tensor this kernel accepts: loads give 0
 
   for (int i = tid; i < WBM + BN; i += WTHREADS) xsum[i] = 0;   // xsum and wsum (visible after the first barrier)
@@ -118,146 +148,111 @@ __global__ __launch_bounds__(WTHREADS) void igemm_i8_wide_kernel(const Problem p
   if (k_hi > p.Kgemm) k_hi = p.Kgemm;
   const int k_count = k_hi - slab_begin * WBK;          // codes this split really reduces over
 
-  // ---- staging state
-  // input role: thread = (chunk kvec of the slab, pixel rows st/8 + 32q)
-  // filter role, [k][r][s][c] layout: thread = (chunk kvec, channel rows st/8 + 32q)
-  // filter role, [K][N] layout: thread = (4 columns ng, 16 reduction rows kblk)
-  const int kvec = st & 7, row0 = st >> 3;
-  unsigned a_base[4];                                   // byte offset of the pixel's window origin
-  unsigned a_mask[4];                                   // bits 0..15: filter rows inside, 16..31: filter columns inside
-  unsigned b_off[4];                                    // filter role: byte offset of each channel row / of the thread's column
-  int tap_r = 0, tap_s = 0, tap_c = 0;                  // filter tap and channel of this thread's chunk in the next slab
+  // ---- staging state.  Load t (0, 1) of wavefront w covers tile rows 8w + 64t .. + 7, lane l the row
+  // 8w + 64t + l/8 and, of that row's eight 16-byte chunks, chunk cch = (l%8) ^ (l/8); it lands at
+  // chunk position l%8 of the row.
+  const int srow = 8 * wave + (lane >> 3);              // tile row of load 0 (load 1: + 64)
+  const int cch = (lane & 7) ^ (lane >> 3);
+  unsigned a_base[2];                                   // byte offset of the pixel's window origin, OOB past M
+  unsigned a_mask[2];                                   // bits 0..15: filter rows inside, 16..31: filter columns inside
+  unsigned b_off[2];                                    // filter rows ([k][r][s][c]) or the lane's column offset ([K][N])
+  int tap_r, tap_s, tap_c;                              // filter tap and channel of this lane's chunk in the next slab to issue
   const int xo_fill = (p.x_off & 0xff) * 0x01010101;    // padding = the code of real zero
-  constexpr bool need_xsum = XSUM;
-  if (stage_a) {
+  {
     const int ohow = p.oh * p.ow;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int m = tm * WBM + row0 + q * 32;
-      a_base[q] = OOB;                                  // rows past M: every load out of range
-      a_mask[q] = 0;
+    for (int t = 0; t < 2; ++t) {
+      const int m = tm * WBM + srow + 64 * t;
+      a_base[t] = OOB;
+      a_mask[t] = 0;
       if (m < p.M) {
         const int img = p.div_ohow.div(m);
         const int rem = m - img * ohow;
         const int oh = p.div_ow.div(rem);
         const int ow = rem - oh * p.ow;
         const int ih0 = oh * p.stride_h - p.pad_t, iw0 = ow * p.stride_w - p.pad_l;
-        a_base[q] = (unsigned)(((img * p.h + ih0) * p.w_ + iw0) * p.c + g * p.cg);   // may wrap below 0: only used with an inside tap
+        a_base[t] = (unsigned)(((img * p.h + ih0) * p.w_ + iw0) * p.c + g * p.cg);   // may wrap below 0: only used with an inside tap
         const int rlo = ih0 < 0 ? -ih0 : 0, rhi = p.h - ih0 < p.r ? p.h - ih0 : p.r;
         const int slo = iw0 < 0 ? -iw0 : 0, shi = p.w_ - iw0 < p.s ? p.w_ - iw0 : p.s;
         const unsigned rm = rhi > rlo ? (1u << rhi) - (1u << rlo) : 0u;
         const unsigned sm = shi > slo ? (1u << shi) - (1u << slo) : 0u;
-        a_mask[q] = rm | (sm << 16);
+        a_mask[t] = rm | (sm << 16);
       }
     }
-    const int kg0 = slab_begin * WBK + kvec * 16;
-    const int t = p.div_cg.div(kg0);
-    tap_c = kg0 - t * p.cg;
-    tap_r = p.div_s.div(t);
-    tap_s = t - tap_r * p.s;
-  } else if (!B_KN) {
+    const int kg0 = slab_begin * WBK + cch * 16;
+    const int tp = p.div_cg.div(kg0);
+    tap_c = kg0 - tp * p.cg;
+    tap_r = p.div_s.div(tp);
+    tap_s = tp - tap_r * p.s;
+    if (!B_KN) {
 #pragma unroll
-    for (int q = 0; q < BQ; ++q) {
-      const int n = tn * BN + row0 + q * 32;
-      b_off[q] = n < p.kg ? (unsigned)((g * p.kg + n) * p.Kgemm + kvec * 16) : OOB;
+      for (int t = 0; t < BT; ++t) {
+        const int n = tn * BN + srow + 64 * t;
+        b_off[t] = n < p.kg ? (unsigned)((g * p.kg + n) * p.Kgemm + cch * 16) : OOB;
+      }
+    } else {
+      const int col = tn * BN + cch * 16;               // k % 16 == 0 on this path: a chunk is whole or absent
+      b_off[0] = col < p.k ? (unsigned)col : OOB;
     }
-  } else {
-    const int col = tn * BN + (st & 31) * 4;
-    b_off[0] = col < p.k ? (unsigned)((st >> 5) * 16 * p.k + col) : OOB;
   }
+  unsigned padq = 0;                                    // 2 bits per slab in flight: which of the lane's input chunks are padding
 
-  v4i stage[WSTAGES][4];
-  unsigned fill[WSTAGES] = {0, 0, 0};                   // input role: which of a stage's 4 chunks are padding
-  int asum[4] = {0, 0, 0, 0};                           // input role: running code sums of its 4 pixel rows
-  int bsum[4] = {0, 0, 0, 0};                           // filter role: running code sums of its rows / columns
-
-  // Issue the gathers of slab `slab` into one register stage.
-  // The staging role is a compile-time argument: the main loop exists once per role, so each copy
-  // has a fixed number of loads per slab and waits exactly for the slab it is about to write to LDS
-  // while the younger gathers stay in flight.
-  using RoleInput = std::integral_constant<int, 0>;
-  using RoleFilter = std::integral_constant<int, 1>;
-  auto gather = [&](auto role, int slab, v4i (&r)[4], unsigned& pad) {
-    constexpr bool INPUT = decltype(role)::value == 0;
-    if constexpr (INPUT) {
-      const int kg0 = slab * WBK + kvec * 16;
-      const bool kok = kg0 < p.Kgemm;                   // reduction tail: zeros (the filter side is zero there too)
+  // Issue the loads of slab `slab` into ring buffer `buf`; `slot` = how many slabs are already in flight.
+  auto issue = [&](int slab, int buf, int slot) {
+    const unsigned As = __builtin_amdgcn_readfirstlane(lds_offset_of(lds) + buf * BUF + (8 * wave) * WBK);
+    const unsigned Bs = As + A_BYTES;
+    {
       const unsigned tap_off = (unsigned)((tap_r * p.w_ + tap_s) * p.c + tap_c);
-      pad = 0;
       if constexpr (PADDED || XSUM) {
+        const bool kok = slab * WBK + cch * 16 < p.Kgemm;   // reduction tail: zeros
+        unsigned bits = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const bool inside = (a_mask[q] >> tap_r) & (a_mask[q] >> (16 + tap_s)) & 1u;
-          r[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, (inside && kok) ? a_base[q] + tap_off : OOB, 0, 0);
-          if (!inside && kok) pad |= 1u << q;
+        for (int t = 0; t < 2; ++t) {
+          const bool inside = (a_mask[t] >> tap_r) & (a_mask[t] >> (16 + tap_s)) & 1u;
+          load16_to_lds(rsrc_x, As + t * 64 * WBK, (inside && kok) ? a_base[t] + tap_off : OOB);
+          if (!inside && kok && a_base[t] != OOB) bits |= 1u << t;
         }
+        padq |= bits << (2 * slot);
       } else {
         // no tap can fall on padding and no code sums are taken: in the reduction tail the filter
         // side is zero, so whatever an in-range address holds there does not matter
 #pragma unroll
-        for (int q = 0; q < 4; ++q) r[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, a_base[q] + tap_off, 0, 0);
+        for (int t = 0; t < 2; ++t)
+          load16_to_lds(rsrc_x, As + t * 64 * WBK, a_base[t] + tap_off);
       }
-      tap_c += WBK;                                     // this thread's chunk one slab further
+      tap_c += WBK;                                     // this lane's chunk one slab further
       while (tap_c >= p.cg) {
         tap_c -= p.cg;
         if (++tap_s == p.s) { tap_s = 0; ++tap_r; }
       }
-    } else if constexpr (!B_KN) {
+    }
+    if constexpr (!B_KN) {
+      const bool kok = slab * WBK + cch * 16 < p.Kgemm;
       const unsigned koff = (unsigned)(slab * WBK);
-      const bool kok = slab * WBK + kvec * 16 < p.Kgemm;
 #pragma unroll
-      for (int q = 0; q < BQ; ++q)
-        r[q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, kok ? b_off[q] + koff : OOB, 0, 0);
+      for (int t = 0; t < BT; ++t)
+        load16_to_lds(rsrc_w, Bs + t * 64 * WBK, kok ? b_off[t] + koff : OOB);
     } else {
-      // 16 reduction rows x 4 columns; rows at or beyond Kgemm lie past the end of the tensor: zeros
-      const unsigned base = b_off[0] + (unsigned)(slab * WBK) * (unsigned)p.k;
+      // weight rows slab*128 + 8w + 64t + l/8 as they lie in memory; rows at or beyond Kgemm lie past
+      // the end of the tensor: zeros
+      const unsigned base = b_off[0] + (unsigned)(slab * WBK + srow) * (unsigned)p.k;
 #pragma unroll
-      for (int j = 0; j < 16; ++j)
-        r[j >> 2][j & 3] = __builtin_amdgcn_raw_buffer_load_b32(rsrc_w, base + (unsigned)j * (unsigned)p.k, 0, 0);
+      for (int t = 0; t < 2; ++t)
+        load16_to_lds(rsrc_w, Bs + t * 64 * WBK, base + (unsigned)(64 * t) * (unsigned)p.k);
     }
   };
 
-  // Write one register stage to LDS buffer `buf` (padding filled in, weight transposed, sums taken).
-  auto commit = [&](auto role, int buf, v4i (&r)[4], unsigned pad) {
-    constexpr bool INPUT = decltype(role)::value == 0;
-    unsigned char* As = lds + buf * BUF;
-    unsigned char* Bs = As + A_BYTES;
-    if constexpr (INPUT) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        v4i v = r[q];
-        if constexpr (PADDED || XSUM) {
-          if ((pad >> q) & 1u) v = v4i{xo_fill, xo_fill, xo_fill, xo_fill};
-        }
-        *reinterpret_cast<v4i*>(As + chunk_at(row0 + q * 32, kvec)) = v;
-        if (need_xsum) asum[q] = sum4(v[0], sum4(v[1], sum4(v[2], sum4(v[3], asum[q]))));
+  // After the loads of the oldest slab in flight have landed: chunks that are padding get the code of
+  // real zero (the hardware wrote zeros there), by the lane that issued them.
+  auto fix_padding = [&](int buf) {
+    if constexpr (PADDED || XSUM) {
+      if (padq & 3u) {
+        unsigned char* As = lds + buf * BUF + (8 * wave) * WBK + lane * 16;
+        const v4i fill = v4i{xo_fill, xo_fill, xo_fill, xo_fill};
+        if (padq & 1u) *reinterpret_cast<v4i*>(As) = fill;
+        if (padq & 2u) *reinterpret_cast<v4i*>(As + 64 * WBK) = fill;
       }
-    } else if constexpr (!B_KN) {
-#pragma unroll
-      for (int q = 0; q < BQ; ++q) {
-        *reinterpret_cast<v4i*>(Bs + chunk_at(row0 + q * 32, kvec)) = r[q];
-        bsum[q] = sum4(r[q][0], sum4(r[q][1], sum4(r[q][2], sum4(r[q][3], bsum[q]))));
-      }
-    } else {
-      // r[t][i] holds row 4t+i of 16 reduction rows, 4 columns per dword: transpose 4x4 byte blocks
-      // so that column nn becomes 16 consecutive reduction codes
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const unsigned d0 = r[t][0], d1 = r[t][1], d2 = r[t][2], d3 = r[t][3];
-        const unsigned p01l = __builtin_amdgcn_perm(d1, d0, 0x05010400u), p01h = __builtin_amdgcn_perm(d1, d0, 0x07030602u);
-        const unsigned p23l = __builtin_amdgcn_perm(d3, d2, 0x05010400u), p23h = __builtin_amdgcn_perm(d3, d2, 0x07030602u);
-        r[t][0] = (int)__builtin_amdgcn_perm(p23l, p01l, 0x05040100u);   // column 0, reduction rows 4t..4t+3
-        r[t][1] = (int)__builtin_amdgcn_perm(p23l, p01l, 0x07060302u);   // column 1
-        r[t][2] = (int)__builtin_amdgcn_perm(p23h, p01h, 0x05040100u);   // column 2
-        r[t][3] = (int)__builtin_amdgcn_perm(p23h, p01h, 0x07060302u);   // column 3
-      }
-      const int ng = st & 31, kblk = st >> 5;
-#pragma unroll
-      for (int nn = 0; nn < 4; ++nn) {
-        const v4i v = v4i{r[0][nn], r[1][nn], r[2][nn], r[3][nn]};
-        *reinterpret_cast<v4i*>(Bs + chunk_at(ng * 4 + nn, kblk)) = v;
-        bsum[nn] = sum4(v[0], sum4(v[1], sum4(v[2], sum4(v[3], bsum[nn]))));
-      }
+      padq >>= 2;
     }
   };
 
@@ -269,16 +264,26 @@ __global__ __launch_bounds__(WTHREADS) void igemm_i8_wide_kernel(const Problem p
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+  int wacc = 0, xacc = 0;                               // this lane's share of a filter-row / pixel-row code sum
 
-  // Fragment addresses: lane (lrow, lhalf) reads chunk 2*k32 + lhalf of its row; the row's swizzle
-  // only depends on lrow because fragment row blocks start at multiples of 32.
-  const int swz = (lrow & 7) ^ ((lrow >> 3) & 3);
+  // Fragment addresses inside a slab buffer.  K-contiguous rows: lane (lrow, lhalf) reads chunk
+  // 2*k32 + lhalf of its row, stored at position chunk ^ (row % 8).  [K][N] weight: lane i of a
+  // 16-lane block addresses 8 bytes of reduction row 32*k32 + 16*lhalf + 8u + i/2 (u = 0, 1) at
+  // columns (block's 16 columns) + 8*(i%2); that row's chunks are stored at position chunk ^ (row % 8).
   int frag_a[2], frag_b[2];
 #pragma unroll
   for (int kk = 0; kk < 2; ++kk) {
-    const int c = ((kgrp * 2 + kk) * 2 + lhalf) ^ swz;
+    const int k32 = kgrp * 2 + kk;
+    const int c = (k32 * 2 + lhalf) ^ (lrow & 7);
     frag_a[kk] = (wm * 64 + lrow) * WBK + (c << 4);
-    frag_b[kk] = A_BYTES + (wn * (BN / 2) + lrow) * WBK + (c << 4);
+    if (!B_KN) {
+      frag_b[kk] = A_BYTES + (wn * (BN / 2) + lrow) * WBK + (c << 4);
+    } else {
+      const int i16 = lane & 15, blk = (lane >> 4) & 1;
+      const int krow = k32 * 32 + lhalf * 16 + (i16 >> 1);           // + 8u
+      const int nchunk = wn * 4 + blk;                                // + 2j
+      frag_b[kk] = A_BYTES + krow * WBK + ((nchunk ^ (i16 >> 1)) << 4) + 8 * (i16 & 1);
+    }
   }
 
   auto compute = [&](int buf) {
@@ -289,7 +294,21 @@ __global__ __launch_bounds__(WTHREADS) void igemm_i8_wide_kernel(const Problem p
 #pragma unroll
       for (int i = 0; i < 2; ++i) a[kk][i] = *reinterpret_cast<const v4i*>(base + frag_a[kk] + i * 32 * WBK);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[kk][j] = *reinterpret_cast<const v4i*>(base + frag_b[kk] + j * 32 * WBK);
+      for (int j = 0; j < TN; ++j) {
+        if constexpr (!B_KN) {
+          b[kk][j] = *reinterpret_cast<const v4i*>(base + frag_b[kk] + j * 32 * WBK);
+        } else {
+          // chunk index + 2j: XOR with a value below 8 commutes with adding 2j only when done on the
+          // chunk number, so the position is recomputed from the parts
+          const int i16 = lane & 15;
+          const int pos = (((wn * 4 + ((lane >> 4) & 1) + 2 * j) ^ (i16 >> 1)) << 4);
+          const int rowpart = frag_b[kk] & ~0x70;                     // row base + 8*(i%2), chunk bits cleared
+          const unsigned char* q = base + rowpart + pos;
+          const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(q));
+          const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(q + 8 * WBK));
+          b[kk][j] = v4i{lo[0], lo[1], hi[0], hi[1]};
+        }
+      }
     }
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
@@ -298,56 +317,63 @@ __global__ __launch_bounds__(WTHREADS) void igemm_i8_wide_kernel(const Problem p
 #pragma unroll
         for (int j = 0; j < TN; ++j)   // filter fragment as the row operand: result rows = channels
           acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(b[kk][j], a[kk][i], acc[i][j], 0, 0, 0);
-  };
-
-  // ---- main loop: slab s is multiplied out of LDS buffer s%2 while slab s+1 waits in registers and
-  // slab s+2 is being fetched.  Unrolled six times so that buffer and register-stage indices are
-  // compile-time constants; the steady-state trips issue every gather unconditionally.  Both roles
-  // execute the same number of barriers.
-  auto run = [&](auto role) {
-    gather(role, slab_begin, stage[0], fill[0]);
-    if (slab_begin + 1 < slab_end) gather(role, slab_begin + 1, stage[1], fill[1]);
-    commit(role, 0, stage[0], fill[0]);
-    __syncthreads();
-    int s0 = slab_begin;
-    for (; s0 + 8 <= slab_end; s0 += 6) {
+    // code sums from the fragments: of the two wavefronts that read the same filter fragments
+    // (wm = 0, 1) each sums half of them, likewise for the input fragments (wn = 0, 1)
 #pragma unroll
-      for (int u = 0; u < 6; ++u) {
-        gather(role, s0 + u + 2, stage[(u + 2) % 3], fill[(u + 2) % 3]);
-        compute(u & 1);
-        commit(role, (u & 1) ^ 1, stage[(u + 1) % 3], fill[(u + 1) % 3]);
-        __syncthreads();
+    for (int kk = 0; kk < 2; ++kk) {
+      if (TN == 2) {
+        const v4i v = wm ? b[kk][TN - 1] : b[kk][0];
+        wacc = sum4(v[0], sum4(v[1], sum4(v[2], sum4(v[3], wacc))));
+      } else if (kk == 0) {
+        const v4i v = wm ? b[1][0] : b[0][0];
+        wacc = sum4(v[0], sum4(v[1], sum4(v[2], sum4(v[3], wacc))));
+      }
+      if constexpr (XSUM) {
+        const v4i v = wn ? a[kk][1] : a[kk][0];
+        xacc = sum4(v[0], sum4(v[1], sum4(v[2], sum4(v[3], xacc))));
       }
     }
-    for (; s0 < slab_end; s0 += 6) {
+  };
+
+  // ---- main loop.  Iteration s: wait for slab s (the younger slabs stay in flight), patch padding,
+  // barrier, refill the buffer that was multiplied last iteration with slab s + NBUF - 1, multiply
+  // slab s.  Unrolled NBUF times so that buffer indices are compile-time constants; the steady-state
+  // trips issue and wait unconditionally.
+  {
 #pragma unroll
-      for (int u = 0; u < 6; ++u) {
+    for (int d = 0; d < NBUF - 1; ++d)
+      if (slab_begin + d < slab_end) issue(slab_begin + d, d, d);
+    int s0 = slab_begin;
+    for (; s0 + 2 * NBUF - 1 <= slab_end; s0 += NBUF) {
+#pragma unroll
+      for (int u = 0; u < NBUF; ++u) {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NBUF - 2) * LPI));
+        fix_padding(u);
+        __syncthreads();
+        issue(s0 + u + NBUF - 1, (u + NBUF - 1) % NBUF, NBUF - 2);
+        compute(u);
+      }
+    }
+    for (; s0 < slab_end; s0 += NBUF) {
+#pragma unroll
+      for (int u = 0; u < NBUF; ++u) {
         const int s = s0 + u;
         if (s < slab_end) {
-          if (s + 2 < slab_end) gather(role, s + 2, stage[(u + 2) % 3], fill[(u + 2) % 3]);
-          compute(u & 1);
-          if (s + 1 < slab_end) commit(role, (u & 1) ^ 1, stage[(u + 1) % 3], fill[(u + 1) % 3]);
+          __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+          fix_padding(u);
           __syncthreads();
+          if (s + NBUF - 1 < slab_end) issue(s + NBUF - 1, (u + NBUF - 1) % NBUF, NBUF - 2);
+          compute(u);
         }
       }
     }
-  };
-  if (stage_a) run(RoleInput{});
-  else run(RoleFilter{});
-
-  // ---- code sums: every staging thread adds what it saw (LDS atomics; integer, so order is free)
-  if (stage_a) {
-    if (need_xsum) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) atomicAdd(&xsum[row0 + q * 32], asum[q]);
-    }
-  } else if (!B_KN) {
-#pragma unroll
-    for (int q = 0; q < BQ; ++q) atomicAdd(&wsum[row0 + q * 32], bsum[q]);
-  } else {
-#pragma unroll
-    for (int nn = 0; nn < 4; ++nn) atomicAdd(&wsum[(st & 31) * 4 + nn], bsum[nn]);
+    __syncthreads();                                    // every wavefront is done with the slab buffers
   }
+
+  // ---- code sums (LDS atomics; integer, so order is free)
+  if (TN == 2) atomicAdd(&wsum[wn * (BN / 2) + wm * 32 + lrow], wacc);
+  else atomicAdd(&wsum[wn * (BN / 2) + lrow], wacc);
+  if constexpr (XSUM) atomicAdd(&xsum[wm * 64 + wn * 32 + lrow], xacc);
 
   // ---- exchange: the two wavefronts that hold partial sums of the same 64 x BN/2 sub-tile swap
   // halves; the kgrp-0 wavefront finishes pixel rows 0..31 of the sub-tile, the other rows 32..63.
@@ -394,7 +420,7 @@ __global__ __launch_bounds__(WTHREADS) void igemm_i8_wide_kernel(const Problem p
 
   const int lr = wm * 64 + kgrp * 32 + lrow;            // pixel row inside the tile
   const int row = tm * WBM + lr;
-  const unsigned rowterm = need_xsum ? (unsigned)p.w_off * (unsigned)xsum[lr] : 0u;
+  const unsigned rowterm = XSUM ? (unsigned)p.w_off * (unsigned)xsum[lr] : 0u;
 
   if (p.split_k == 1) {
     unsigned char* out = lds;                           // [128][OUT_PITCH] requantized tile, pixel-major
@@ -462,10 +488,10 @@ __global__ __launch_bounds__(WTHREADS) void igemm_i8_wide_kernel(const Problem p
   }
 }
 
-template <int BN, bool B_KN, bool PADDED, bool XSUM>
+template <int BN, bool B_KN, bool PADDED, bool XSUM, int NBUF>
 hipError_t launch_wide_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
-  auto kern = igemm_i8_wide_kernel<BN, B_KN, PADDED, XSUM>;
-  constexpr int lds_bytes = 2 * (WBM + BN) * WBK + (WBM + 2 * BN) * 4;
+  auto kern = igemm_i8_wide_kernel<BN, B_KN, PADDED, XSUM, NBUF>;
+  constexpr int lds_bytes = NBUF * (WBM + BN) * WBK + (WBM + 2 * BN) * 4;
   static bool attr_set = false;   // per instantiation; benign if two threads race to set it
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -484,13 +510,25 @@ hipError_t launch_wide_variant(const Problem& p, const Plan& plan, hipStream_t s
   return hipGetLastError();
 }
 
+template <int BN, bool B_KN, int NBUF>
+hipError_t launch_wide_flags(const Problem& p, const Plan& plan, hipStream_t stream) {
+  // the general instantiation (tap tests and input code sums) serves every case; the common ones
+  // (filter offset 0, with or without padding) have leaner copies
+  const bool xsum = p.w_off != 0;
+  const bool padded = p.pad_t != 0 || p.pad_l != 0 || (p.oh - 1) * p.stride_h - p.pad_t + p.r > p.h ||
+                      (p.ow - 1) * p.stride_w - p.pad_l + p.s > p.w_;
+  if (xsum) return launch_wide_variant<BN, B_KN, true, true, NBUF>(p, plan, stream);
+  if (padded) return launch_wide_variant<BN, B_KN, true, false, NBUF>(p, plan, stream);
+  return launch_wide_variant<BN, B_KN, false, false, NBUF>(p, plan, stream);
+}
+
 }  // namespace
 
 bool wide_i8_applicable(const Problem& p) {
   if (p.r > 16 || p.s > 16) return false;                       // tap masks are 16 bits per axis
   if (p.x_bytes >= 0x80000000u || p.w_bytes >= 0x80000000u) return false;
   if (p.k % 4 != 0 || p.kg % 4 != 0) return false;              // dword-granular channel handling
-  if (p.b_is_kn) return p.Kgemm % 16 == 0 && p.groups == 1;
+  if (p.b_is_kn) return p.Kgemm % 16 == 0 && p.k % 16 == 0 && p.groups == 1;   // 16-byte chunks of weight rows
   return p.cg % 16 == 0 && p.c % 16 == 0;
 }
 
@@ -529,24 +567,18 @@ Plan plan_wide_i8(const Problem& p, int bn, bool allow_split) {
 }
 
 hipError_t launch_wide_i8(const Problem& p, const Plan& plan, hipStream_t stream, const char** variant) {
+  // ring depth: one workgroup per CU with three slabs in flight, or (experiments) two per CU with one each
+  int nbuf = 4;
+  if (const char* env = getenv("GLOWMI_I8_WIDE_NBUF")) nbuf = atoi(env) == 2 ? 2 : 4;
   static thread_local char name[64];
-  snprintf(name, sizeof(name), "igemm_i8_wide_128x%dk2w8_%s", plan.bn, p.b_is_kn ? "fc" : "conv");
+  snprintf(name, sizeof(name), "igemm_i8_wide_128x%dk2w8r%d_%s", plan.bn, nbuf, p.b_is_kn ? "fc" : "conv");
   *variant = name;
-  // the general instantiation (tap tests and input code sums) serves every case; the common ones
-  // (filter offset 0, with or without padding) have leaner copies
-  const bool xsum = p.w_off != 0;
-  const bool padded = p.pad_t != 0 || p.pad_l != 0 || (p.oh - 1) * p.stride_h - p.pad_t + p.r > p.h ||
-                      (p.ow - 1) * p.stride_w - p.pad_l + p.s > p.w_;
-  if (p.b_is_kn) return xsum ? launch_wide_variant<128, true, true, true>(p, plan, stream)
-                             : launch_wide_variant<128, true, false, false>(p, plan, stream);
-  if (plan.bn == 128) {
-    if (xsum) return launch_wide_variant<128, false, true, true>(p, plan, stream);
-    return padded ? launch_wide_variant<128, false, true, false>(p, plan, stream)
-                  : launch_wide_variant<128, false, false, false>(p, plan, stream);
-  }
-  if (xsum) return launch_wide_variant<64, false, true, true>(p, plan, stream);
-  return padded ? launch_wide_variant<64, false, true, false>(p, plan, stream)
-                : launch_wide_variant<64, false, false, false>(p, plan, stream);
+  if (p.b_is_kn) return nbuf == 2 ? launch_wide_flags<128, true, 2>(p, plan, stream)
+                                  : launch_wide_flags<128, true, 4>(p, plan, stream);
+  if (plan.bn == 128) return nbuf == 2 ? launch_wide_flags<128, false, 2>(p, plan, stream)
+                                       : launch_wide_flags<128, false, 4>(p, plan, stream);
+  return nbuf == 2 ? launch_wide_flags<64, false, 2>(p, plan, stream)
+                   : launch_wide_flags<64, false, 4>(p, plan, stream);
 }
 
 }  // namespace glowmi

@@ -55,8 +55,10 @@ def test_qconv2d_wide(i, tile, dist, w_off, monkeypatch):
     G.assert_equal_i8(got, ref, f"wide conv {i} without bias")
 
 
-WIDE_FC = [(130, 272, 132), (5, 64, 8), (256, 1040, 520), (33, 4096, 64), (300, 2048, 1000), (128, 128, 128),
-           (1, 2048, 1000), (97, 6400, 260)]
+# (M, K, N); the kernel stages 16-byte chunks of weight rows, so N must be a multiple of 16 (other
+# widths fall back to the generic kernel and are checked all the same)
+WIDE_FC = [(130, 272, 144), (5, 64, 16), (256, 1040, 528), (33, 4096, 64), (300, 2048, 1008), (128, 128, 128),
+           (1, 2048, 1024), (97, 6400, 272), (130, 272, 132), (300, 2048, 1000)]
 
 
 @pytest.mark.parametrize("shape", WIDE_FC, ids=lambda s: "x".join(map(str, s)))
@@ -71,7 +73,7 @@ def test_qfc_wide(shape, dist, w_off, monkeypatch):
         ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off, act=act)
         for use_ws in (True, False):
             got, variant = G.gpu_qfc(aq, wq, bq, qp, act, use_workspace=use_ws)
-            assert variant.startswith("igemm_i8_wide"), variant
+            assert variant.startswith("igemm_i8_wide") == (N % 16 == 0), variant
             G.assert_equal_i8(got, ref, f"wide qfc {shape} {dist} act {act} ws {use_ws} [{variant}]")
 
 
