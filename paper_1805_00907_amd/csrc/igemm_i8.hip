@@ -507,7 +507,8 @@ Plan plan_i8(const Problem& p, bool allow_split) {
   // kernel built for them.
   if (wide_i8_applicable(p)) {
     if (forced == 4 || forced == 5) return plan_wide_i8(p, (forced == 4 || p.b_is_kn) ? 128 : 64, allow_split);
-    if (forced < 0 && p.Kgemm >= 1024 && p.M >= 96 && p.kg >= 96) return plan_wide_i8(p, 128, allow_split);
+    if (forced < 0 && p.Kgemm >= 256 && p.M >= 96 && p.kg >= 128 && !pw_i8_applicable(p))
+      return plan_wide_i8(p, 128, allow_split);
   }
   pl.tile = tile;
   pl.bm = kTilesI8[tile].bm;

@@ -149,10 +149,11 @@ __global__ __launch_bounds__(WTHREADS, NBUF <= 2 ? 2 : 1) void igemm_i8_wide_ker
   const int k_count = k_hi - slab_begin * WBK;          // codes this split really reduces over
 
   // ---- staging state.  Load t (0, 1) of wavefront w covers tile rows 8w + 64t .. + 7, lane l the row
-  // 8w + 64t + l/8 and, of that row's eight 16-byte chunks, chunk cch = (l%8) ^ (l/8); it lands at
+  // 8w + 64t + l/8 and, of that row's eight 16-byte chunks, chunk cch = (l%8) ^ swz(row) with swz(row) =
+  // (row % 8) ^ ((row / 8) % 4) = (l/8) ^ (w % 4); it lands at
   // chunk position l%8 of the row.
   const int srow = 8 * wave + (lane >> 3);              // tile row of load 0 (load 1: + 64)
-  const int cch = (lane & 7) ^ (lane >> 3);
+  const int cch = (lane & 7) ^ (lane >> 3) ^ (wave & 3);
   unsigned a_base[2];                                   // byte offset of the pixel's window origin, OOB past M
   unsigned a_mask[2];                                   // bits 0..15: filter rows inside, 16..31: filter columns inside
   unsigned b_off[2];                                    // filter rows ([k][r][s][c]) or the lane's column offset ([K][N])
@@ -267,14 +268,14 @@ __global__ __launch_bounds__(WTHREADS, NBUF <= 2 ? 2 : 1) void igemm_i8_wide_ker
   int wacc = 0, xacc = 0;                               // this lane's share of a filter-row / pixel-row code sum
 
   // Fragment addresses inside a slab buffer.  K-contiguous rows: lane (lrow, lhalf) reads chunk
-  // 2*k32 + lhalf of its row, stored at position chunk ^ (row % 8).  [K][N] weight: lane i of a
+  // 2*k32 + lhalf of its row, stored at position chunk ^ swz(row).  [K][N] weight: lane i of a
   // 16-lane block addresses 8 bytes of reduction row 32*k32 + 16*lhalf + 8u + i/2 (u = 0, 1) at
-  // columns (block's 16 columns) + 8*(i%2); that row's chunks are stored at position chunk ^ (row % 8).
+  // columns (block's 16 columns) + 8*(i%2); that row's chunks are stored at position chunk ^ swz(row).
   int frag_a[2], frag_b[2];
 #pragma unroll
   for (int kk = 0; kk < 2; ++kk) {
     const int k32 = kgrp * 2 + kk;
-    const int c = (k32 * 2 + lhalf) ^ (lrow & 7);
+    const int c = (k32 * 2 + lhalf) ^ (lrow & 7) ^ ((lrow >> 3) & 3);
     frag_a[kk] = (wm * 64 + lrow) * WBK + (c << 4);
     if (!B_KN) {
       frag_b[kk] = A_BYTES + (wn * (BN / 2) + lrow) * WBK + (c << 4);
@@ -301,11 +302,13 @@ __global__ __launch_bounds__(WTHREADS, NBUF <= 2 ? 2 : 1) void igemm_i8_wide_ker
           // chunk index + 2j: XOR with a value below 8 commutes with adding 2j only when done on the
           // chunk number, so the position is recomputed from the parts
           const int i16 = lane & 15;
-          const int pos = (((wn * 4 + ((lane >> 4) & 1) + 2 * j) ^ (i16 >> 1)) << 4);
+          const int chunk = (wn * 4 + ((lane >> 4) & 1) + 2 * j) ^ (i16 >> 1);   // ^ (row / 8) % 4 per read
           const int rowpart = frag_b[kk] & ~0x70;                     // row base + 8*(i%2), chunk bits cleared
-          const unsigned char* q = base + rowpart + pos;
-          const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(q));
-          const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(q + 8 * WBK));
+          const unsigned char* q = base + rowpart;
+          const v2i lo = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+              (v2i __attribute__((address_space(3)))*)(q + ((chunk ^ (lhalf * 2)) << 4)));
+          const v2i hi = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
+              (v2i __attribute__((address_space(3)))*)(q + 8 * WBK + ((chunk ^ (lhalf * 2 + 1)) << 4)));
           b[kk][j] = v4i{lo[0], lo[1], hi[0], hi[1]};
         }
       }
@@ -567,9 +570,12 @@ Plan plan_wide_i8(const Problem& p, int bn, bool allow_split) {
 }
 
 hipError_t launch_wide_i8(const Problem& p, const Plan& plan, hipStream_t stream, const char** variant) {
-  // ring depth: one workgroup per CU with three slabs in flight, or (experiments) two per CU with one each
-  int nbuf = 4;
-  if (const char* env = getenv("GLOWMI_I8_WIDE_NBUF")) nbuf = atoi(env) == 2 ? 2 : 4;
+  // ring depth: a grid of at most one workgroup per CU runs one round, so each workgroup gets the
+  // whole LDS (four buffers, three slabs in flight); larger grids run two workgroups per CU with two
+  // buffers each, which hides one workgroup's prologue and epilogue behind the other's main loop
+  const long long work = (long long)plan.tiles_m * plan.tiles_n * p.groups * plan.split_k;
+  int nbuf = work <= 256 ? 4 : 2;
+  if (const char* env = getenv("GLOWMI_I8_WIDE_NBUF")) nbuf = atoi(env) == 2 ? 2 : 4;   // experiments
   static thread_local char name[64];
   snprintf(name, sizeof(name), "igemm_i8_wide_128x%dk2w8r%d_%s", plan.bn, nbuf, p.b_is_kn ? "fc" : "conv");
   *variant = name;
