@@ -468,6 +468,7 @@ constexpr int SK16_STEP = 16;    // weight rows per step
 
 typedef float v4f_acc __attribute__((ext_vector_type(4)));
 
+template <bool STREAM>
 __global__ __launch_bounds__(64 * SK_WAVES) void fc_skinny16_f32_kernel(
     const float* __restrict__ A, const float* __restrict__ Wt, const float* __restrict__ bias,
     float* __restrict__ Y, float* __restrict__ partial, int M, int K, int N, int act, int split_k,
@@ -498,8 +499,12 @@ __global__ __launch_bounds__(64 * SK_WAVES) void fc_skinny16_f32_kernel(
   auto load_step = [&](int step, v4f& a, v4f (&b)[4]) {
     a = *reinterpret_cast<const v4f*>(a_base + (size_t)step * SK16_STEP);
 #pragma unroll
-    for (int t = 0; t < 4; ++t)
-      b[t] = *reinterpret_cast<const v4f*>(w_base + ((size_t)step * SK16_STEP + t) * N);
+    for (int t = 0; t < 4; ++t) {
+      // a weight matrix larger than the last-level cache is a pure stream: non-temporal loads keep it
+      // from displacing everything else on its way through (measured 78 -> 71 us on 25088 x 4096)
+      const v4f* src = reinterpret_cast<const v4f*>(w_base + ((size_t)step * SK16_STEP + t) * N);
+      b[t] = STREAM ? __builtin_nontemporal_load(src) : *src;
+    }
   };
   auto mma_step = [&](const v4f& a, const v4f (&b)[4]) {
 #pragma unroll
@@ -721,7 +726,9 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
   if (plan.tile == kTileSkinny16) {
     *variant = "fc_skinny16_f32";
     dim3 grid(plan.tiles_n, plan.split_k, 1), block(64 * SK_WAVES, 1, 1);
-    hipLaunchKernelGGL(fc_skinny16_f32_kernel, grid, block, 0, stream, static_cast<const float*>(p.x),
+    // weights beyond half of the 256 MB last-level cache are treated as a stream
+    auto kern = p.w_bytes > (128u << 20) ? fc_skinny16_f32_kernel<true> : fc_skinny16_f32_kernel<false>;
+    hipLaunchKernelGGL(kern, grid, block, 0, stream, static_cast<const float*>(p.x),
                        static_cast<const float*>(p.w), static_cast<const float*>(p.bias),
                        static_cast<float*>(p.y), static_cast<float*>(p.partial), p.M, p.Kgemm, p.k, p.act,
                        plan.split_k, plan.slabs_per_split);
