@@ -257,7 +257,7 @@ int pw_min_items() {
 
 bool pw_f32_applicable(const Problem& p) {
   if (p.b_is_kn || p.groups != 1 || p.r != 1 || p.s != 1 || p.pad_t != 0 || p.pad_l != 0) return false;
-  if (p.c != 64 && p.c != 128) return false;   // longer reductions amortise the generic kernel's set-up
+  if (p.c != 64 && p.c != 128 && p.c != 256) return false;   // longer reductions amortise the generic kernel's set-up
   // bottom/right padding would make output pixels read outside the image
   if ((long long)(p.oh - 1) * p.stride_h >= p.h || (long long)(p.ow - 1) * p.stride_w >= p.w_) return false;
   if ((unsigned long long)p.M * (unsigned long long)p.k * 4ull > 0xF0000000ull || p.k > 65536) return false;
@@ -282,6 +282,7 @@ hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** vari
   switch (p.c) {
     case 64: return launch_pw_k<64>(p, stream);
     case 128: return launch_pw_k<128>(p, stream);
+    case 256: return launch_pw_k<256>(p, stream);
     default: return hipErrorInvalidValue;
   }
 }

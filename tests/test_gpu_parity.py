@@ -99,6 +99,8 @@ PW_SHAPES = [
     (1, 9, 9, 64, 520, 1),        # three slices, the last with a single channel group of 8
     (2, 12, 12, 64, 64, 1),       # one channel group out of the slice's four
     (1, 1, 5, 64, 64, 1),         # fewer pixels than one block
+    (2, 15, 17, 256, 64, 1),      # C = 256: four chunks per reduction, one channel group per slice
+    (1, 11, 13, 256, 136, 2),     # C = 256, three slices, ragged N, stride 2
 ]
 
 
