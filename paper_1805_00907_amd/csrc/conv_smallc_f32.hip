@@ -16,6 +16,8 @@
 // Epilogue as everywhere: bias + Relu on the accumulators, one store.
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "igemm.h"
 
 namespace glowmi {
@@ -23,10 +25,13 @@ namespace {
 
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int TH = 8, TW = 16;          // output tile (pixels); 4 wavefronts = 2 pixel halves x 2 channel halves
+constexpr int TW = 16;                  // output tile width (pixels); 4 wavefronts = 2 pixel halves x 2 channel halves
+// Tile height TH = 8 (each wavefront two 32-pixel MFMA blocks) or 4 (one block): the persistent grid
+// walks total_tiles / workgroups tiles each, and with few tiles per workgroup the taller tile loses a
+// fifth of the chip to the uneven last round (3136 tiles on 768 workgroups: 5 rounds for 4.08).
 constexpr int SC_THREADS = 256;
 
-template <int R, int S, int C, int STRIDE>
+template <int R, int S, int C, int STRIDE, int TH>
 struct SmallC {
   static constexpr int K = R * S * C;                    // reduction length
   static constexpr int STEPS = (K + 1) / 2;              // MFMA steps (two k each)
@@ -41,16 +46,18 @@ struct SmallC {
   static constexpr int off(int v) { return (v / RUN) * PITCH + (v % RUN); }
 };
 
-template <int R, int S, int C, int STRIDE>
+template <int R, int S, int C, int STRIDE, int TH>
 __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Problem p, int tiles_y, int tiles_x,
                                                                     int total_tiles) {
-  using G = SmallC<R, S, C, STRIDE>;
+  using G = SmallC<R, S, C, STRIDE, TH>;
+  static_assert(TH == 4 || TH == 8, "tile height");
+  constexpr int NB = TH / 4;             // 32-pixel blocks (2 rows x 16) per wavefront
   extern __shared__ __align__(16) float patch[];          // [2][PH + 1][PITCH]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int lrow = lane & 31, lhalf = lane >> 5;
-  const int wpix = wave >> 1;            // which half of the tile's pixels (rows 4*wpix .. 4*wpix+3)
+  const int wpix = wave >> 1;            // which half of the tile's pixels (rows 2*NB*wpix .. + 2*NB - 1)
   const int wch = wave & 1;              // which 32 of the 64 output channels
   const int n_tile = blockIdx.y;
 
@@ -75,7 +82,7 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
   // pair straddles two filter rows; a second base register covers those steps, so every read uses a
   // compile-time immediate.  Bank note: pixels of a row are 6 floats apart and PITCH is a multiple
   // of 16, so the 64 lanes of one read hit 64 different banks.
-  const int pix_origin = ((wpix * 4 + (lrow >> 4)) * STRIDE) * G::PITCH + (lrow & 15) * STRIDE * C;
+  const int pix_origin = ((wpix * 2 * NB + (lrow >> 4)) * STRIDE) * G::PITCH + (lrow & 15) * STRIDE * C;
   const int base_norm = pix_origin + lhalf;                          // off(2t+1) = off(2t) + 1
   const int base_cross = pix_origin + lhalf * (G::PITCH - (G::RUN - 1));   // 2t is the last index of a run
 
@@ -124,9 +131,11 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
     const bool has_next = next < total_tiles;
     if (has_next) load_patch(next);
 
-    v16f acc[2];
+    v16f acc[NB];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { acc[0][e] = 0.f; acc[1][e] = 0.f; }
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
     const float* src = patch + buf * G::PATCH;
     const float* pn = src + base_norm;
     const float* pc_ = src + base_cross;
@@ -136,9 +145,9 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
       const bool cross = (2 * t) % G::RUN == G::RUN - 1;             // compile-time after unrolling
       const float* b = cross ? pc_ : pn;
       const int o = G::off(2 * t);
-      const float a0 = b[o], a1 = b[o + blk];
-      acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, wfrag[t], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, wfrag[t], acc[1], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[o + i * blk], wfrag[t], acc[i], 0, 0, 0);
     }
 
     if (has_next) store_patch(buf ^ 1);
@@ -151,11 +160,11 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
       const int ty = t2 % tiles_y;
       const int img = t2 / tiles_y;
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < NB; ++i) {
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int pix = (e >> 2) * 8 + lhalf * 4 + (e & 3);        // 0..31 inside the block
-          const int oh = ty * TH + wpix * 4 + i * 2 + (pix >> 4);
+          const int oh = ty * TH + wpix * 2 * NB + i * 2 + (pix >> 4);
           const int ow = tx * TW + (pix & 15);
           if (!ch_ok || oh >= p.oh || ow >= p.ow) continue;
           float v = acc[i][e] + bv;
@@ -171,10 +180,10 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
   }
 }
 
-template <int R, int S, int C, int STRIDE>
+template <int R, int S, int C, int STRIDE, int TH>
 hipError_t launch_smallc(const Problem& p, hipStream_t stream) {
-  using G = SmallC<R, S, C, STRIDE>;
-  auto kern = conv_smallc_f32_kernel<R, S, C, STRIDE>;
+  using G = SmallC<R, S, C, STRIDE, TH>;
+  auto kern = conv_smallc_f32_kernel<R, S, C, STRIDE, TH>;
   static int wg_per_cu = 0, num_cu = 0;     // benign if two threads race: both compute the same values
   if (wg_per_cu == 0) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -204,12 +213,18 @@ hipError_t launch_smallc(const Problem& p, hipStream_t stream) {
 
 bool smallc_f32_applicable(const Problem& p) {
   return !p.b_is_kn && p.groups == 1 && p.r == 7 && p.s == 7 && p.c == 3 && p.stride_h == 2 && p.stride_w == 2 &&
-         (long long)p.n * ((p.oh + TH - 1) / TH) * ((p.ow + TW - 1) / TW) < (1LL << 31);
+         (long long)p.n * ((p.oh + 3) / 4) * ((p.ow + TW - 1) / TW) < (1LL << 31);
 }
 
 hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** variant) {
   *variant = "conv_smallc_f32_7x7s2c3";
-  return launch_smallc<7, 7, 3, 2>(p, stream);
+  // the taller tile is the faster one per tile (two independent MFMA chains per wavefront); the
+  // shorter one doubles the number of tiles, which pays while there are fewer than about two per
+  // resident workgroup (batch 1: 13.8 -> 11.1 us; batch 32: 97.8 vs 100.5 us)
+  const long long tiles8 = (long long)p.n * ((p.oh + 7) / 8) * ((p.ow + TW - 1) / TW);
+  int th = tiles8 < 1536 ? 4 : 8;
+  if (const char* env = getenv("GLOWMI_SMALLC_TH")) th = atoi(env) == 8 ? 8 : 4;   // experiments
+  return th == 8 ? launch_smallc<7, 7, 3, 2, 8>(p, stream) : launch_smallc<7, 7, 3, 2, 4>(p, stream);
 }
 
 }  // namespace glowmi

@@ -58,7 +58,9 @@ __device__ __forceinline__ void load16_to_lds(v4i rsrc, unsigned lds_addr, unsig
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                :
                : "s"(lds_addr), "v"(voffset), "s"(rsrc)
-               : "memory");
+               : "memory");   // m0 is written here and nowhere else in this file (it is a reserved
+                              // register: the compiler warns about it on a clobber list and keeps
+                              // nothing live in it in a kernel without LDS-direct intrinsics)
 }
 
 __device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
