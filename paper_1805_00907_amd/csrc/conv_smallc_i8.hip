@@ -65,23 +65,39 @@ __global__ __launch_bounds__(QS_THREADS) void conv_smallc_i8_kernel(const Proble
 
   // ---- filter fragment: lane (channel, half) holds, for each filter row r, the 16 codes
   // W[ch][r][s = 4*half + 0..3][c = 0..3]; s = 7 and c = 3 do not exist and are zero codes.
+  // The filter of the workgroup's 64 channels (64 x 147 bytes, contiguous in memory) is first copied to
+  // LDS with consecutive lanes reading consecutive bytes; picking a lane's fragment straight from
+  // global memory would put every lane on a different cache line (channels are 147 bytes apart) and,
+  // with 84 such loads per lane, cost more than the convolution itself.
   const int ch = n_tile * 64 + wch * 32 + lrow;
   const bool ch_ok = ch < p.k;
+  {
+    constexpr int FB = R * S * C;                            // filter bytes per channel
+    static_assert(64 * FB <= TH * TW * OUT_PITCH, "the filter staging fits the output staging area");
+    const int ch0 = n_tile * 64;
+    const int nbytes = (p.k - ch0 < 64 ? p.k - ch0 : 64) * FB;
+    const signed char* src = Wt + (size_t)ch0 * FB;
+    for (int i = tid; i < 64 * FB; i += QS_THREADS) out[i] = i < nbytes ? (unsigned char)src[i] : 0;
+  }
+  __syncthreads();
   v4i wfrag[R];
   int wsum = 0;
+  {
+    const unsigned char* wrow = out + (wch * 32 + lrow) * (R * S * C);   // zeros for channels past k
 #pragma unroll
-  for (int r = 0; r < R; ++r) {
+    for (int r = 0; r < R; ++r) {
 #pragma unroll
-    for (int si = 0; si < 4; ++si) {
-      const int s = 4 * lhalf + si;
-      int d = 0;
+      for (int si = 0; si < 4; ++si) {
+        const int s = 4 * lhalf + si;
+        int d = 0;
 #pragma unroll
-      for (int c = 0; c < C; ++c) {
-        const int v = (ch_ok && s < S) ? (int)Wt[((size_t)ch * R + r) * (S * C) + s * C + c] : 0;
-        d |= (v & 0xff) << (8 * c);
+        for (int c = 0; c < C; ++c) {
+          const int v = s < S ? (int)wrow[r * (S * C) + s * C + c] : 0;
+          d |= v << (8 * c);
+        }
+        wfrag[r][si] = d;
+        wsum += sum_bytes(d);
       }
-      wfrag[r][si] = d;
-      wsum += sum_bytes(d);
     }
   }
   wsum += __shfl_xor(wsum, 32);            // both halves of the channel's filter
