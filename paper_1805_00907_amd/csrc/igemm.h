@@ -79,6 +79,9 @@ bool pw_f32_applicable(const Problem& p);
 hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** variant);
 bool pw_i8_applicable(const Problem& p);
 hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** variant);
+// int8 3x3 convolution over 64 input channels on many pixels (conv_k3c64_i8.hip).
+bool k3c64_i8_applicable(const Problem& p);
+hipError_t launch_k3c64_i8(const Problem& p, hipStream_t stream, const char** variant);
 bool smallc_i8_applicable(const Problem& p);
 hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant);
 
