@@ -2,19 +2,25 @@
 // of Section 4 of the paper; the same "small number of channels" kind of convolution that the
 // paper's CPU backend gives its own strategy (Section 5.3).
 //
-// The generic int8 kernel would gather this layer byte by byte.  Here a workgroup keeps the input
-// patch of an 8 x 16 pixel output tile in LDS with every pixel widened from 3 to 4 codes (one
-// dword), so that for one filter row r the codes a pixel needs -- 8 pixels x 4 codes = 32 bytes,
-// the 8th pixel and the 4th code being padding that meets a zero filter code -- are contiguous and
-// 8-byte aligned: one v_mfma_i32_32x32x32_i8 per filter row, its operand two ds_read_b64.
-// Out-of-image pixels are staged as the code x_off (real zero).  The filter fragment (7 rows x 16
-// bytes per lane) lives in registers.  Offsets are removed after the MFMAs with
+// The generic int8 kernel would gather this layer byte by byte.  Here a wavefront keeps the input
+// patch of a 2 x 16 pixel block of outputs in a private LDS region with every pixel widened from 3 to
+// 4 codes (one dword), so that for one filter row r the codes a pixel needs -- 8 pixels x 4 codes =
+// 32 bytes, the 8th pixel and the 4th code being padding that meets a zero filter code -- are
+// contiguous and 8-byte aligned: one v_mfma_i32_32x32x32_i8 per filter row and half of the 64
+// channels, its pixel operand two ds_read_b64.  Out-of-image pixels are staged as the code x_off
+// (real zero).  The next block's patch is fetched into registers while the current one is
+// multiplied and written to the region afterwards (a wavefront's LDS operations execute in order),
+// so after the prologue there is no workgroup barrier and blocks are dealt to wavefronts, not to
+// workgroups.  The filter fragments (2 x 7 rows x 16 bytes per lane, the same for every wavefront)
+// are built once per persistent workgroup and kept in LDS, with the channels dealt to MFMA rows so
+// that a lane ends with 32 consecutive channels of its pixel.  Offsets are removed after the MFMAs:
 //   sum (x - xo) * w = sum x*w - xo * sum w          (this kernel requires a filter offset of 0)
-// then bias, requantize, clamp (Relu = lower bound), pack four channels per dword (the MFMA takes
-// the filter fragment as its row operand), transpose through LDS, 16-byte stores.
+// then bias, requantize, clamp (Relu = lower bound), pack, two 16-byte stores per lane.  The layer
+// is bound by that per-output arithmetic and by the 64 bytes written per pixel, not by the MFMAs.
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <type_traits>
 
 #include "igemm.h"
 #include "quant_epilogue.h"
@@ -26,200 +32,236 @@ typedef int v2i __attribute__((ext_vector_type(2)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-constexpr int TH = 8, TW = 16;            // output tile in pixels
+constexpr int BH = 2, BW = 16;            // block of output pixels of one wavefront
 constexpr int QS_THREADS = 256;
+constexpr int QS_WAVES = QS_THREADS / 64;
 constexpr int R = 7, S = 7, C = 3, STRIDE = 2;
-constexpr int PH = (TH - 1) * STRIDE + R;                 // 21 patch rows
-constexpr int PW = (TW - 1) * STRIDE + S + 1;             // 38 pixels: one more than needed, read by the padding tap
+constexpr int FB = R * S * C;                             // filter bytes per channel
+constexpr int PH = (BH - 1) * STRIDE + R;                 // 9 patch rows
+constexpr int PW = (BW - 1) * STRIDE + S + 1;             // 38 pixels: one more than needed, read by the padding tap
 constexpr int PITCH = 40;                                 // dwords per patch row
-constexpr int PATCH = PH * PITCH;                         // dwords
-constexpr int PIX_LOADS = (PH * PW + QS_THREADS - 1) / QS_THREADS;
-constexpr int OUT_PITCH = 64 + 16;                        // bytes per pixel row of the staged output tile
-constexpr int LDS_DWORDS = 2 * PATCH + (TH * TW * OUT_PITCH) / 4 + 64;   // patches, output tile, per-channel term
+constexpr int PATCH = PH * PITCH;                         // dwords per wavefront
+constexpr int PIX_LOADS = (PH * PW + 63) / 64;            // loads per lane and block
+constexpr int W_DWORDS = 64 * FB / 4;                     // filter of 64 channels
+constexpr int W_LOADS = (W_DWORDS + QS_THREADS - 1) / QS_THREADS;
+constexpr int LDS_DWORDS = QS_WAVES * PATCH + W_DWORDS + 2 * R * 64 * 4 + 64;   // patches, filter, its fragments, per-channel term
+static_assert(PATCH % 4 == 0 && (64 * FB) % 16 == 0, "16-byte alignment of the LDS areas");
 
-__device__ __forceinline__ int sum_bytes(int packed) {
-  return __builtin_amdgcn_sdot4(packed, 0x01010101, 0, false);
+// Channel (0..63) whose filter is MFMA row j (0..31) of channel block nb (0/1).  Result register e of
+// a lane with half h is MFMA row (e/4)*8 + 4h + e%4; this assignment makes that row channel
+// 32h + 16nb + e, so a lane's 16 registers of a block are 16 consecutive channels.
+__device__ __forceinline__ int channel_of_row(int nb, int j) {
+  return 32 * ((j >> 2) & 1) + 16 * nb + (j >> 3) * 4 + (j & 3);
 }
 
-__device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_off, int lo) {
-  return shift >= 33 ? requantize_as<true>(acc, mant, shift, y_off, lo)
-                     : requantize_as<false>(acc, mant, shift, y_off, lo);   // uniform branch
+// The 4 bytes at byte offset `off` of a buffer of `bytes` bytes (>= 4), any alignment, with bytes past
+// the end reading as zero, in two steps so that a lane's loads are all in flight before the first
+// result is touched: load4_issue fetches the dword (from the last whole dword of the buffer when the
+// wanted one would straddle or pass the end: a range-checked load would drop a straddling dword as a
+// whole) and load4_over says by how many bytes (at most 4) the result must be shifted down.
+__device__ __forceinline__ unsigned load4_over(unsigned off, unsigned bytes) {
+  const unsigned last = bytes - 4u;
+  const unsigned over = off < last ? 0u : off - last;
+  return over < 4u ? over : 4u;
+}
+__device__ __forceinline__ unsigned load4_issue(__amdgpu_buffer_rsrc_t rsrc, unsigned off, unsigned bytes) {
+  const unsigned last = bytes - 4u;
+  return (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rsrc, off < last ? off : last, 0, 0);
+}
+__device__ __forceinline__ unsigned load4_shift(unsigned d, unsigned over) {
+  return (unsigned)((unsigned long long)d >> (8u * over));
 }
 
-__global__ __launch_bounds__(QS_THREADS) void conv_smallc_i8_kernel(const Problem p, int tiles_y, int tiles_x,
-                                                                   int total_tiles) {
+__global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Problem p, int blocks_y, int blocks_x,
+                                                                      int items_div, int items_rem) {
   __shared__ __align__(16) int lds[LDS_DWORDS];
-  int* patch = lds;                                        // [2][PH][PITCH] dwords, one pixel each
-  unsigned char* out = reinterpret_cast<unsigned char*>(lds + 2 * PATCH);   // [128][OUT_PITCH]
-  int* cterm = lds + 2 * PATCH + (TH * TW * OUT_PITCH) / 4;                 // [64]
+  unsigned* wstage = reinterpret_cast<unsigned*>(lds + QS_WAVES * PATCH);            // [64][FB] bytes
+  v4i* wfrag = reinterpret_cast<v4i*>(lds + QS_WAVES * PATCH + W_DWORDS);            // [2][R][64 lanes]
+  int* cterm = lds + QS_WAVES * PATCH + W_DWORDS + 2 * R * 64 * 4;                   // [64]
 
   const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lrow = lane & 31, lhalf = lane >> 5;
-  const int wpix = wave >> 1;              // pixel rows 4*wpix .. 4*wpix+3 of the tile
-  const int wch = wave & 1;                // channels 32*wch .. +31 of the block's 64
   const int n_tile = blockIdx.y;
+  int* patch = lds + wave * PATCH;                         // [PH][PITCH] dwords, one pixel each
 
-  const signed char* __restrict__ X = static_cast<const signed char*>(p.x);
-  const signed char* __restrict__ Wt = static_cast<const signed char*>(p.w);
   const int* __restrict__ bias = static_cast<const int*>(p.bias);
   signed char* __restrict__ Y = static_cast<signed char*>(p.y);
-
-  // ---- filter fragment: lane (channel, half) holds, for each filter row r, the 16 codes
-  // W[ch][r][s = 4*half + 0..3][c = 0..3]; s = 7 and c = 3 do not exist and are zero codes.
-  // The filter of the workgroup's 64 channels (64 x 147 bytes, contiguous in memory) is first copied to
-  // LDS with consecutive lanes reading consecutive bytes; picking a lane's fragment straight from
-  // global memory would put every lane on a different cache line (channels are 147 bytes apart) and,
-  // with 84 such loads per lane, cost more than the convolution itself.
-  const int ch = n_tile * 64 + wch * 32 + lrow;
-  const bool ch_ok = ch < p.k;
-  {
-    constexpr int FB = R * S * C;                            // filter bytes per channel
-    static_assert(64 * FB <= TH * TW * OUT_PITCH, "the filter staging fits the output staging area");
-    const int ch0 = n_tile * 64;
-    const int nbytes = (p.k - ch0 < 64 ? p.k - ch0 : 64) * FB;
-    const signed char* src = Wt + (size_t)ch0 * FB;
-    for (int i = tid; i < 64 * FB; i += QS_THREADS) out[i] = i < nbytes ? (unsigned char)src[i] : 0;
-  }
-  __syncthreads();
-  v4i wfrag[R];
-  int wsum = 0;
-  {
-    const unsigned char* wrow = out + (wch * 32 + lrow) * (R * S * C);   // zeros for channels past k
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-#pragma unroll
-      for (int si = 0; si < 4; ++si) {
-        const int s = 4 * lhalf + si;
-        int d = 0;
-#pragma unroll
-        for (int c = 0; c < C; ++c) {
-          const int v = s < S ? (int)wrow[r * (S * C) + s * C + c] : 0;
-          d |= v << (8 * c);
-        }
-        wfrag[r][si] = d;
-        wsum += sum_bytes(d);
-      }
-    }
-  }
-  wsum += __shfl_xor(wsum, 32);            // both halves of the channel's filter
-  // per-channel additive term: bias - x_off * sum(w)   (modulo 2^32, exact because the true value fits)
-  if (wpix == 0 && lhalf == 0) {
-    unsigned ct = 0u - (unsigned)p.x_off * (unsigned)wsum;
-    if (ch_ok && bias) ct += (unsigned)bias[ch];
-    cterm[wch * 32 + lrow] = (int)ct;
-  }
+  const __amdgpu_buffer_rsrc_t rsrc_x =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.x), 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_w =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w), 0, (int)p.w_bytes, 0x00020000);
 
   const int xo_byte = p.x_off & 0xff;
   const int xo_pix = (int)((unsigned)xo_byte * 0x01010101u);
 
-  int stage[PIX_LOADS];
-  auto load_patch = [&](int tile) {
-    const int tx = tile % tiles_x;
-    const int t2 = tile / tiles_x;
-    const int ty = t2 % tiles_y;
-    const int img = t2 / tiles_y;
-    const int ih0 = ty * TH * STRIDE - p.pad_t;
-    const int iw0 = tx * TW * STRIDE - p.pad_l;
+  // ---- this wavefront's contiguous range of pixel blocks (image major, then block row, then column)
+  const int wv = blockIdx.x * QS_WAVES + wave;
+  int it = wv * items_div + (wv < items_rem ? wv : items_rem);
+  const int it_end = it + items_div + (wv < items_rem ? 1 : 0);
+
+  // ---- input patch: one pixel (3 codes) per load, as the 4 bytes that start at the pixel; the 4th
+  // byte (the next pixel's first code, or nothing at the end of the tensor) is replaced by x_off.
+  // Loading only issues the loads and notes, 4 bits per load, whether the pixel is inside the image
+  // and the shift; the values are touched when they are written to LDS, a block later.
+  unsigned stage[PIX_LOADS];
+  unsigned stage_meta = 0;
+  auto load_patch = [&](int item) {
+    const int bx = item % blocks_x;
+    const int t2 = item / blocks_x;
+    const int by = t2 % blocks_y;
+    const int img = t2 / blocks_y;
+    const int ih0 = by * BH * STRIDE - p.pad_t;
+    const int iw0 = bx * BW * STRIDE - p.pad_l;
+    stage_meta = 0;
 #pragma unroll
     for (int i = 0; i < PIX_LOADS; ++i) {
-      const int idx = tid + i * QS_THREADS;
+      const int idx = lane + i * 64;
       const int pr = idx / PW, pc = idx % PW;
       const int ih = ih0 + pr, iw = iw0 + pc;
       const bool ok = idx < PH * PW && (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
-      unsigned d = (unsigned)xo_pix;
-      if (ok) {
-        const signed char* src = X + (((size_t)img * p.h + ih) * p.w_ + iw) * C;
-        d = ((unsigned)src[0] & 0xffu) | (((unsigned)src[1] & 0xffu) << 8) | (((unsigned)src[2] & 0xffu) << 16) |
-            ((unsigned)xo_byte << 24);
-      }
-      stage[i] = (int)d;
+      const unsigned off = ok ? (unsigned)((img * p.h + ih) * p.w_ + iw) * (unsigned)C : 0u;
+      stage[i] = load4_issue(rsrc_x, off, p.x_bytes);      // unconditional: no branch around a load
+      stage_meta |= (load4_over(off, p.x_bytes) | (ok ? 8u : 0u)) << (4 * i);
     }
   };
-  auto store_patch = [&](int buf) {
-    int* dst = patch + buf * PATCH;
+  auto store_patch = [&]() {
 #pragma unroll
     for (int i = 0; i < PIX_LOADS; ++i) {
-      const int idx = tid + i * QS_THREADS;
-      if (idx < PH * PW) dst[(idx / PW) * PITCH + idx % PW] = stage[i];
+      const int idx = lane + i * 64;
+      const unsigned meta = stage_meta >> (4 * i);
+      const bool ok = (meta & 8u) != 0;
+      const unsigned px = load4_shift(stage[i], meta & 7u);
+      const unsigned keep = ok ? 0x00ffffffu : 0u;
+      const unsigned fillv = ok ? (unsigned)xo_byte << 24 : (unsigned)xo_pix;
+      if (idx < PH * PW) patch[(idx / PW) * PITCH + idx % PW] = (int)((px & keep) | fillv);
     }
   };
 
-  // lane = pixel (prow, pcol) of a 32-pixel block (2 rows x 16) as the MFMA column operand
-  const int pix_origin = ((wpix * 4 + (lrow >> 4)) * STRIDE) * PITCH + (lrow & 15) * STRIDE + 4 * lhalf;
+  const bool has_work = it < it_end;
+  if (has_work) load_patch(it);            // in flight while the filter is fetched
 
-  int tile = blockIdx.x;
-  if (tile >= total_tiles) return;
-  load_patch(tile);
-  store_patch(0);
+  // ---- filter fragments: for channel block nb and filter row r, lane (MFMA row j, half) feeds the 16
+  // codes W[channel_of_row(nb, j)][r][s = 4*half + 0..3][c = 0..3]; s = 7 and c = 3 do not exist and
+  // are zero codes.  The filter of the workgroup's 64 channels (64 x 147 bytes, contiguous in memory;
+  // channels past the last read as zero) is first copied to LDS with coalesced loads (picking
+  // fragments straight from global memory would put every lane on a different cache line, channels
+  // being 147 bytes apart), then the 14 fragments are built once, dealt over the wavefronts, and
+  // kept in LDS in lane order: one conflict-free 16-byte read per MFMA.
+  {
+    const unsigned base = (unsigned)n_tile * (unsigned)(64 * FB);
+    unsigned wd[W_LOADS];
+#pragma unroll
+    for (int q = 0; q < W_LOADS; ++q)
+      wd[q] = load4_issue(rsrc_w, base + 4u * (unsigned)(tid + q * QS_THREADS), p.w_bytes);
+#pragma unroll
+    for (int q = 0; q < W_LOADS; ++q) {
+      const int i = tid + q * QS_THREADS;
+      if (i < W_DWORDS) wstage[i] = load4_shift(wd[q], load4_over(base + 4u * (unsigned)i, p.w_bytes));
+    }
+  }
   __syncthreads();
-  int buf = 0;
-  for (;;) {
-    const int next = tile + gridDim.x;
-    const bool has_next = next < total_tiles;
-    if (has_next) load_patch(next);
+  const unsigned char* wbytes = reinterpret_cast<const unsigned char*>(wstage);
+  for (int f = wave; f < 2 * R; f += QS_WAVES) {
+    const int nb = f / R, r = f % R;
+    const unsigned char* wrow = wbytes + channel_of_row(nb, lrow) * FB + r * (S * C);
+    v4i frag;
+#pragma unroll
+    for (int si = 0; si < 4; ++si) {
+      const int s = 4 * lhalf + si;
+      int d = 0;
+#pragma unroll
+      for (int c = 0; c < C; ++c) {
+        const int v = s < S ? (int)wrow[s * C + c] : 0;
+        d |= v << (8 * c);
+      }
+      frag[si] = d;
+    }
+    wfrag[f * 64 + lane] = frag;
+  }
+  // per-channel additive term: bias - x_off * sum(w)   (modulo 2^32, exact because the true value fits);
+  // four threads per channel sum a quarter of its filter each
+  {
+    constexpr int QUARTER = (FB + 3) / 4;
+    const int lc = tid >> 2, q = tid & 3;
+    const unsigned char* wrow = wbytes + lc * FB;
+    int wsum = 0;
+    for (int i = q * QUARTER; i < (q + 1) * QUARTER && i < FB; ++i) wsum += (int)(signed char)wrow[i];
+    wsum += __shfl_xor(wsum, 1);
+    wsum += __shfl_xor(wsum, 2);
+    if (q == 0) {
+      const int ch = n_tile * 64 + lc;
+      unsigned ct = 0u - (unsigned)p.x_off * (unsigned)wsum;
+      if (ch < p.k && bias) ct += (unsigned)bias[ch];
+      cterm[lc] = (int)ct;
+    }
+  }
+  __syncthreads();                           // fragments and channel terms; the only barriers of the kernel
+  if (!has_work) return;
+
+  // lane = pixel (row lrow / 16 of the block's two, column lrow % 16) as the MFMA column operand
+  const int* src = patch + ((lrow >> 4) * STRIDE) * PITCH + (lrow & 15) * STRIDE + 4 * lhalf;
+  const bool fast = p.shift >= 33;           // uniform
+  const bool wide = p.k % 16 == 0;           // uniform: runs of 16 channels are wholly inside or outside
+  const int col0 = n_tile * 64 + 32 * lhalf; // first of the lane's 32 channels
+
+  store_patch();
+  for (; it < it_end; ++it) {
+    const bool has_next = it + 1 < it_end;
+    if (has_next) load_patch(it + 1);
 
     v16i acc[2];
 #pragma unroll
     for (int e = 0; e < 16; ++e) { acc[0][e] = 0; acc[1][e] = 0; }
-    const int* src = patch + buf * PATCH + pix_origin;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int* a = src + (r + i * 2 * STRIDE) * PITCH;          // block i: two pixel rows further down
-        const v2i lo2 = *reinterpret_cast<const v2i*>(a);
-        const v2i hi2 = *reinterpret_cast<const v2i*>(a + 2);
-        const v4i av = {lo2[0], lo2[1], hi2[0], hi2[1]};
-        // filter fragment as the row operand: result rows = channels, columns = pixels
-        acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wfrag[r], av, acc[i], 0, 0, 0);
-      }
+      const int* a = src + r * PITCH;
+      const v2i lo2 = *reinterpret_cast<const v2i*>(a);
+      const v2i hi2 = *reinterpret_cast<const v2i*>(a + 2);
+      const v4i av = {lo2[0], lo2[1], hi2[0], hi2[1]};
+      // filter fragment as the row operand: result rows = channels, columns = pixels
+      acc[0] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wfrag[r * 64 + lane], av, acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wfrag[(R + r) * 64 + lane], av, acc[1], 0, 0, 0);
     }
 
-    if (has_next) store_patch(buf ^ 1);
+    if (has_next) store_patch();             // after this block's reads, in order
 
-    // ---- epilogue: register e of a lane = channel (e/4)*8 + 4*half + e%4 of the wave's 32, pixel lane%32
+    // ---- epilogue: register e of block nb = channel 32*half + 16*nb + e of pixel lane % 32
+    const int bx = it % blocks_x;
+    const int t2 = it / blocks_x;
+    const int by = t2 % blocks_y;
+    const int img = t2 / blocks_y;
+    const int oh = by * BH + (lrow >> 4), ow = bx * BW + (lrow & 15);
+    const bool pix_ok = oh < p.oh && ow < p.ow;
+    signed char* dst = Y + (((size_t)img * p.oh + oh) * p.ow + ow) * p.k + col0;
+    auto finish = [&](auto fast_tag) {
+      constexpr bool FAST = decltype(fast_tag)::value;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int lp = wpix * 64 + i * 32 + lrow;                      // pixel index inside the tile (row-major 8 x 16)
+      for (int nb = 0; nb < 2; ++nb) {
+        v4i out;
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int lc = wch * 32 + q4 * 8 + lhalf * 4;
-        const v4i ct = *reinterpret_cast<const v4i*>(cterm + lc);
-        unsigned packed = 0;
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const v4i ct = *reinterpret_cast<const v4i*>(cterm + 32 * lhalf + 16 * nb + 4 * q4);
+          int q[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int v = (int)((unsigned)acc[i][q4 * 4 + t] + (unsigned)ct[t]);
-          packed |= ((unsigned)requantize(v, p.mant, p.shift, p.y_off, p.lo) & 0xffu) << (t * 8);
+          for (int t = 0; t < 4; ++t)
+            q[t] = requantize_as<FAST>((int)((unsigned)acc[nb][4 * q4 + t] + (unsigned)ct[t]), p.mant, p.shift,
+                                       p.y_off, p.lo);
+          out[q4] = (int)pack_codes(q[0], q[1], q[2], q[3]);
         }
-        *reinterpret_cast<unsigned*>(out + lp * OUT_PITCH + lc) = packed;
-      }
-    }
-    __syncthreads();
-    {
-      const int tx = tile % tiles_x;
-      const int t2 = tile / tiles_x;
-      const int ty = t2 % tiles_y;
-      const int img = t2 / tiles_y;
-      const bool wide = p.k % 16 == 0;
-      for (int u = tid; u < TH * TW * 4; u += QS_THREADS) {          // 16 bytes of one pixel per thread and pass
-        const int lp = u >> 2, chunk = u & 3;
-        const int oh = ty * TH + (lp >> 4), ow = tx * TW + (lp & 15);
-        const int col = n_tile * 64 + chunk * 16;
-        if (oh >= p.oh || ow >= p.ow || col >= p.k) continue;
-        signed char* dst = Y + (((size_t)img * p.oh + oh) * p.ow + ow) * p.k + col;
-        const unsigned char* s8 = out + lp * OUT_PITCH + chunk * 16;
+        const int col = col0 + 16 * nb;
+        if (!pix_ok || col >= p.k) continue;
         if (wide) {
-          *reinterpret_cast<v4i*>(dst) = *reinterpret_cast<const v4i*>(s8);
+          *reinterpret_cast<v4i*>(dst + 16 * nb) = out;
         } else {
-          for (int e = 0; e < 16 && col + e < p.k; ++e) dst[e] = (signed char)s8[e];
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (col + e < p.k) dst[16 * nb + e] = (signed char)((unsigned)out[e >> 2] >> (8 * (e & 3)));
         }
       }
-    }
-    if (!has_next) break;
-    __syncthreads();
-    buf ^= 1;
-    tile = next;
+    };
+    if (fast) finish(std::true_type{}); else finish(std::false_type{});
   }
 }
 
@@ -227,35 +269,35 @@ __global__ __launch_bounds__(QS_THREADS) void conv_smallc_i8_kernel(const Proble
 
 bool smallc_i8_applicable(const Problem& p) {
   return !p.b_is_kn && p.groups == 1 && p.r == R && p.s == S && p.c == C && p.stride_h == STRIDE &&
-         p.stride_w == STRIDE && p.w_off == 0 &&
-         (long long)p.n * ((p.oh + TH - 1) / TH) * ((p.ow + TW - 1) / TW) < (1LL << 31);
+         p.stride_w == STRIDE && p.w_off == 0 && p.x_bytes >= 4u && p.x_bytes <= 0x7FFFFFFFu &&
+         p.w_bytes <= 0x7FFFFFFFu &&
+         (long long)p.n * ((p.oh + BH - 1) / BH) * ((p.ow + BW - 1) / BW) < (1LL << 30);
 }
 
 hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant) {
   *variant = "conv_smallc_i8_7x7s2c3";
   auto kern = conv_smallc_i8_kernel;
-  static int wg_per_cu = 0, num_cu = 0;     // benign if two threads race: both compute the same values
-  if (wg_per_cu == 0) {
-    int occ = 0, dev = 0, n = 0;
-    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void*>(kern),
-                                                                QS_THREADS, 0);
-    if (e == hipSuccess) e = hipGetDevice(&dev);
+  static int num_cu = 0;     // benign if two threads race: both compute the same value
+  if (num_cu == 0) {
+    int dev = 0, n = 0;
+    hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
     num_cu = n < 1 ? 1 : n;
-    wg_per_cu = occ < 1 ? 1 : occ;
   }
-  const int tiles_y = (p.oh + TH - 1) / TH, tiles_x = (p.ow + TW - 1) / TW;
-  const long long total = (long long)p.n * tiles_y * tiles_x;
+  const int blocks_y = (p.oh + BH - 1) / BH, blocks_x = (p.ow + BW - 1) / BW;
+  const long long items = (long long)p.n * blocks_y * blocks_x;
   const int n_tiles = (p.k + 63) / 64;
-  int want = 4;   // measured: 4 persistent workgroups per CU (all the registers allow) is best: 40.9 / 34.7 / 32.9 us for 2 / 3 / 4
-  if (const char* env = getenv("GLOWMI_SMALLC_I8_WGS")) want = atoi(env);
-  const int per_cu = wg_per_cu < want ? wg_per_cu : want;
+  int per_cu = 3;            // persistent workgroups per CU (measured at batch 32: 24.2 / 25.5 / 28.0 us for 3 / 4 / 5)
+  if (const char* env = getenv("GLOWMI_SMALLC_I8_WGS")) per_cu = atoi(env);   // experiments
+  if (per_cu < 1) per_cu = 1;
+  if (per_cu > 8) per_cu = 8;
   long long gx = (long long)num_cu * per_cu / n_tiles;
   if (gx < 1) gx = 1;
-  if (gx > total) gx = total;
+  if (gx > (items + QS_WAVES - 1) / QS_WAVES) gx = (items + QS_WAVES - 1) / QS_WAVES;
+  const long long waves = gx * QS_WAVES;
   dim3 grid((unsigned)gx, n_tiles, 1), block(QS_THREADS, 1, 1);
-  hipLaunchKernelGGL(kern, grid, block, 0, stream, p, tiles_y, tiles_x, (int)total);
+  hipLaunchKernelGGL(kern, grid, block, 0, stream, p, blocks_y, blocks_x, (int)(items / waves), (int)(items % waves));
   return hipGetLastError();
 }
 
