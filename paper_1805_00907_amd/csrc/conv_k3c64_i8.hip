@@ -15,7 +15,8 @@
 //     is multiplied: no workgroup barrier after the prologue;
 //   - per chunk 6 MFMA steps (v_mfma_i32_32x32x32_i8) x 2 halves of the 64 channels, the filter as
 //     the row operand and the channels permuted so that a lane ends with 32 consecutive channels of
-//     one pixel: add the channel term, requantize, clamp, pack, two 16-byte stores.
+//     one pixel (the accumulators start at the channel term): requantize, clamp, pack, two 16-byte
+//     stores.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -184,6 +185,8 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_kernel(const Prob
   const unsigned char* a_lane = alds + l32 * K3_APITCH + 16 * lh;
   const unsigned char* w_lane = wlds + l32 * K3_WPITCH + 16 * lh;
   const bool fast = p.shift >= 33;                         // uniform
+  const FoldedRequant fold = make_folded_requant(p.shift, p.y_off);   // uniform
+  const int lo_v = p.lo;
   const int ch0 = slice * K3_BN + 32 * lh;                 // first of the lane's 32 channels
 
   commit();
@@ -195,9 +198,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_kernel(const Prob
       addq[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_add, off, 0, 0);
       addq[1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_add, off + 16u, 0, 0);
     }
+    // the accumulators start at the channel terms: register e of acc<nb> = channel 32*lh + 16*nb + e
     v16i acc0, acc1;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { acc0[e] = 0; acc1[e] = 0; }
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const v4i c0 = *reinterpret_cast<const v4i*>(cterm + 32 * lh + 4 * q4);
+      const v4i c1 = *reinterpret_cast<const v4i*>(cterm + 32 * lh + 16 + 4 * q4);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) { acc0[4 * q4 + t] = c0[t]; acc1[4 * q4 + t] = c1[t]; }
+    }
     const bool more = rb + 1 < rb_end;                     // uniform: this wavefront owns block rb + 1 too
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
@@ -219,24 +228,24 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_kernel(const Prob
     }
 
     // ---- epilogue: lane (l32, lh) holds pixel l32, channels 32*lh + 16*nb + e of the slice
-    auto finish = [&](auto fast_tag) {
-      constexpr bool FAST = decltype(fast_tag)::value;
+    auto finish = [&](auto mode_tag) {
+      constexpr int MODE = decltype(mode_tag)::value;      // 2 folded, 1 multiply-high, 0 64-bit
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
         const v16i& acc = nb == 0 ? acc0 : acc1;
         v4i out;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          const v4i ct = *reinterpret_cast<const v4i*>(cterm + 32 * lh + 16 * nb + 4 * q4);
           int q[4];
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
-            unsigned v = (unsigned)acc[4 * q4 + t] + (unsigned)ct[t];
+            unsigned v = (unsigned)acc[4 * q4 + t];
             if (ADD) {
               const int code = (int)(signed char)((unsigned)addq[nb][q4] >> (8 * t));
               v += (unsigned)rescale_term(code - p.r_off, p.r_mant, p.r_shift);
             }
-            q[t] = requantize_as<FAST>((int)v, p.mant, p.shift, p.y_off, p.lo);
+            q[t] = MODE == 2 ? requantize_folded((int)v, p.mant, fold, lo_v)
+                             : requantize_as<MODE == 1>((int)v, p.mant, p.shift, p.y_off, p.lo);
           }
           out[q4] = (int)pack_codes(q[0], q[1], q[2], q[3]);
         }
@@ -245,7 +254,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_kernel(const Prob
         if (ch0 + 16 * nb < p.k) __builtin_amdgcn_raw_buffer_store_b128(out, rsrc_y, off + 16u * nb, 0, 0);
       }
     };
-    if (fast) finish(std::true_type{}); else finish(std::false_type{});
+    if (fold.ok) finish(std::integral_constant<int, 2>{});
+    else if (fast) finish(std::integral_constant<int, 1>{});
+    else finish(std::integral_constant<int, 0>{});
   }
 }
 

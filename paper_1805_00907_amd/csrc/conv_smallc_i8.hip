@@ -12,7 +12,7 @@
 // multiplied and written to the region afterwards (a wavefront's LDS operations execute in order),
 // so after the prologue there is no workgroup barrier and blocks are dealt to wavefronts, not to
 // workgroups.  The filter fragments (2 x 7 rows x 16 bytes per lane, the same for every wavefront)
-// are built once per persistent workgroup and kept in LDS, with the channels dealt to MFMA rows so
+// are built once per persistent workgroup, straight from global memory, and kept in LDS, with the channels dealt to MFMA rows so
 // that a lane ends with 32 consecutive channels of its pixel.  Offsets are removed after the MFMAs:
 //   sum (x - xo) * w = sum x*w - xo * sum w          (this kernel requires a filter offset of 0)
 // then bias, requantize, clamp (Relu = lower bound), pack, two 16-byte stores per lane.  The layer
@@ -41,11 +41,8 @@ constexpr int PH = (BH - 1) * STRIDE + R;                 // 9 patch rows
 constexpr int PW = (BW - 1) * STRIDE + S + 1;             // 38 pixels: one more than needed, read by the padding tap
 constexpr int PITCH = 40;                                 // dwords per patch row
 constexpr int PATCH = PH * PITCH;                         // dwords per wavefront
-constexpr int PIX_LOADS = (PH * PW + 63) / 64;            // loads per lane and block
-constexpr int W_DWORDS = 64 * FB / 4;                     // filter of 64 channels
-constexpr int W_LOADS = (W_DWORDS + QS_THREADS - 1) / QS_THREADS;
-constexpr int LDS_DWORDS = QS_WAVES * PATCH + W_DWORDS + 2 * R * 64 * 4 + 64;   // patches, filter, its fragments, per-channel term
-static_assert(PATCH % 4 == 0 && (64 * FB) % 16 == 0, "16-byte alignment of the LDS areas");
+constexpr int LDS_DWORDS = QS_WAVES * PATCH + 2 * R * 64 * 4 + 64;   // patches, filter fragments, per-channel term
+static_assert(PATCH % 4 == 0 && PW <= 64, "16-byte alignment of the LDS areas; one lane per patch column");
 
 // Channel (0..63) whose filter is MFMA row j (0..31) of channel block nb (0/1).  Result register e of
 // a lane with half h is MFMA row (e/4)*8 + 4h + e%4; this assignment makes that row channel
@@ -75,9 +72,8 @@ __device__ __forceinline__ unsigned load4_shift(unsigned d, unsigned over) {
 __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Problem p, int blocks_y, int blocks_x,
                                                                       int items_div, int items_rem) {
   __shared__ __align__(16) int lds[LDS_DWORDS];
-  unsigned* wstage = reinterpret_cast<unsigned*>(lds + QS_WAVES * PATCH);            // [64][FB] bytes
-  v4i* wfrag = reinterpret_cast<v4i*>(lds + QS_WAVES * PATCH + W_DWORDS);            // [2][R][64 lanes]
-  int* cterm = lds + QS_WAVES * PATCH + W_DWORDS + 2 * R * 64 * 4;                   // [64]
+  v4i* wfrag = reinterpret_cast<v4i*>(lds + QS_WAVES * PATCH);            // [2][R][64 lanes]
+  int* cterm = lds + QS_WAVES * PATCH + 2 * R * 64 * 4;                   // [64]
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -93,20 +89,26 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
   const __amdgpu_buffer_rsrc_t rsrc_w =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w), 0, (int)p.w_bytes, 0x00020000);
 
-  const int xo_byte = p.x_off & 0xff;
-  const int xo_pix = (int)((unsigned)xo_byte * 0x01010101u);
+  const unsigned xo_byte = (unsigned)p.x_off & 0xffu;
+  const unsigned xo_pix = xo_byte * 0x01010101u;
 
   // ---- this wavefront's contiguous range of pixel blocks (image major, then block row, then column)
   const int wv = blockIdx.x * QS_WAVES + wave;
   int it = wv * items_div + (wv < items_rem ? wv : items_rem);
   const int it_end = it + items_div + (wv < items_rem ? 1 : 0);
 
-  // ---- input patch: one pixel (3 codes) per load, as the 4 bytes that start at the pixel; the 4th
-  // byte (the next pixel's first code, or nothing at the end of the tensor) is replaced by x_off.
-  // Loading only issues the loads and notes, 4 bits per load, whether the pixel is inside the image
-  // and the shift; the values are touched when they are written to LDS, a block later.
-  unsigned stage[PIX_LOADS];
-  unsigned stage_meta = 0;
+  // ---- input patch: lane l < PW fetches column l of each of the PH patch rows, one pixel (3 codes)
+  // per load as the 4 bytes that start at the pixel; the 4th byte (the next pixel's first code) is
+  // replaced by x_off when the pixel is written to LDS, a block later.  Every load is issued
+  // unconditionally at an address inside the tensor: a branch around a load, which is what the
+  // compiler makes of a conditional on a loaded value, would put a wait behind each of them.  Rows
+  // are uniform over the wavefront, so their part of the address and their validity are scalar.
+  // The dword of the very last pixel of the tensor would end one byte outside: that one load starts
+  // a byte earlier and is shifted before use (tail_row >= 0 only in the block that holds the pixel).
+  unsigned stage[PH];
+  bool col_ok = false;        // the lane's patch column lies inside the image
+  unsigned row_mask = 0;      // bit i: patch row i lies inside the image (uniform)
+  int tail_row = -1, tail_lane = -1;
   auto load_patch = [&](int item) {
     const int bx = item % blocks_x;
     const int t2 = item / blocks_x;
@@ -114,28 +116,35 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
     const int img = t2 / blocks_y;
     const int ih0 = by * BH * STRIDE - p.pad_t;
     const int iw0 = bx * BW * STRIDE - p.pad_l;
-    stage_meta = 0;
+    const int iw = iw0 + lane;
+    col_ok = lane < PW && (unsigned)iw < (unsigned)p.w_;
+    tail_lane = p.w_ - 1 - iw0;
+    tail_row = img == p.n - 1 && tail_lane < PW ? p.h - 1 - ih0 : -1;
+    if (tail_row >= PH) tail_row = -1;
+    unsigned voff = col_ok ? (unsigned)iw * (unsigned)C : 0u;
+    row_mask = 0;
 #pragma unroll
-    for (int i = 0; i < PIX_LOADS; ++i) {
-      const int idx = lane + i * 64;
-      const int pr = idx / PW, pc = idx % PW;
-      const int ih = ih0 + pr, iw = iw0 + pc;
-      const bool ok = idx < PH * PW && (unsigned)ih < (unsigned)p.h && (unsigned)iw < (unsigned)p.w_;
-      const unsigned off = ok ? (unsigned)((img * p.h + ih) * p.w_ + iw) * (unsigned)C : 0u;
-      stage[i] = load4_issue(rsrc_x, off, p.x_bytes);      // unconditional: no branch around a load
-      stage_meta |= (load4_over(off, p.x_bytes) | (ok ? 8u : 0u)) << (4 * i);
+    for (int i = 0; i < PH; ++i) {
+      const int ih = ih0 + i;
+      const bool rok = (unsigned)ih < (unsigned)p.h;
+      row_mask |= (rok ? 1u : 0u) << i;
+      const unsigned soff = rok ? (unsigned)((img * p.h + ih) * p.w_) * (unsigned)C : 0u;
+      unsigned vo = voff;
+      if (i == tail_row && lane == tail_lane) vo -= 1u;     // (uniform test first: false almost always)
+      stage[i] = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rsrc_x, vo, soff, 0);
     }
   };
   auto store_patch = [&]() {
+    if (tail_row >= 0) {
 #pragma unroll
-    for (int i = 0; i < PIX_LOADS; ++i) {
-      const int idx = lane + i * 64;
-      const unsigned meta = stage_meta >> (4 * i);
-      const bool ok = (meta & 8u) != 0;
-      const unsigned px = load4_shift(stage[i], meta & 7u);
-      const unsigned keep = ok ? 0x00ffffffu : 0u;
-      const unsigned fillv = ok ? (unsigned)xo_byte << 24 : (unsigned)xo_pix;
-      if (idx < PH * PW) patch[(idx / PW) * PITCH + idx % PW] = (int)((px & keep) | fillv);
+      for (int i = 0; i < PH; ++i)
+        if (i == tail_row && lane == tail_lane) stage[i] >>= 8;
+    }
+#pragma unroll
+    for (int i = 0; i < PH; ++i) {
+      const bool ok = col_ok && ((row_mask >> i) & 1u);
+      const unsigned v = ok ? (stage[i] & 0x00ffffffu) | (xo_byte << 24) : xo_pix;
+      if (lane < PW) patch[i * PITCH + lane] = (int)v;
     }
   };
 
@@ -144,76 +153,71 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
 
   // ---- filter fragments: for channel block nb and filter row r, lane (MFMA row j, half) feeds the 16
   // codes W[channel_of_row(nb, j)][r][s = 4*half + 0..3][c = 0..3]; s = 7 and c = 3 do not exist and
-  // are zero codes.  The filter of the workgroup's 64 channels (64 x 147 bytes, contiguous in memory;
-  // channels past the last read as zero) is first copied to LDS with coalesced loads (picking
-  // fragments straight from global memory would put every lane on a different cache line, channels
-  // being 147 bytes apart), then the 14 fragments are built once, dealt over the wavefronts, and
-  // kept in LDS in lane order: one conflict-free 16-byte read per MFMA.
-  {
-    const unsigned base = (unsigned)n_tile * (unsigned)(64 * FB);
-    unsigned wd[W_LOADS];
+  // are zero codes.  The 12 bytes a lane needs for one fragment are contiguous in the [k][7][7][3]
+  // filter: three dword loads at any alignment, all 21 of a lane in flight together, repacked 3 -> 4
+  // bytes per tap.  Wavefront nb (0/1) builds the seven fragments of its channel block, which are the
+  // same for every wavefront and stay in LDS in lane order (one conflict-free 16-byte read per
+  // MFMA), and from them the per-channel term  bias - x_off * sum(w)  (modulo 2^32, exact because the
+  // true value fits).  Channels past the last one read as zeros.
+  if (wave < 2) {
+    const int nb = wave;
+    const int lc = channel_of_row(nb, lrow);
+    const int ch = n_tile * 64 + lc;
+    const unsigned base = (unsigned)ch * (unsigned)FB + 12u * lhalf;
+    unsigned wd[R][3];
 #pragma unroll
-    for (int q = 0; q < W_LOADS; ++q)
-      wd[q] = load4_issue(rsrc_w, base + 4u * (unsigned)(tid + q * QS_THREADS), p.w_bytes);
+    for (int r = 0; r < R; ++r)
 #pragma unroll
-    for (int q = 0; q < W_LOADS; ++q) {
-      const int i = tid + q * QS_THREADS;
-      if (i < W_DWORDS) wstage[i] = load4_shift(wd[q], load4_over(base + 4u * (unsigned)i, p.w_bytes));
-    }
-  }
-  __syncthreads();
-  const unsigned char* wbytes = reinterpret_cast<const unsigned char*>(wstage);
-  for (int f = wave; f < 2 * R; f += QS_WAVES) {
-    const int nb = f / R, r = f % R;
-    const unsigned char* wrow = wbytes + channel_of_row(nb, lrow) * FB + r * (S * C);
-    v4i frag;
-#pragma unroll
-    for (int si = 0; si < 4; ++si) {
-      const int s = 4 * lhalf + si;
-      int d = 0;
-#pragma unroll
-      for (int c = 0; c < C; ++c) {
-        const int v = s < S ? (int)wrow[s * C + c] : 0;
-        d |= v << (8 * c);
-      }
-      frag[si] = d;
-    }
-    wfrag[f * 64 + lane] = frag;
-  }
-  // per-channel additive term: bias - x_off * sum(w)   (modulo 2^32, exact because the true value fits);
-  // four threads per channel sum a quarter of its filter each
-  {
-    constexpr int QUARTER = (FB + 3) / 4;
-    const int lc = tid >> 2, q = tid & 3;
-    const unsigned char* wrow = wbytes + lc * FB;
+      for (int j = 0; j < 3; ++j) wd[r][j] = load4_issue(rsrc_w, base + (unsigned)(r * S * C + 4 * j), p.w_bytes);
     int wsum = 0;
-    for (int i = q * QUARTER; i < (q + 1) * QUARTER && i < FB; ++i) wsum += (int)(signed char)wrow[i];
-    wsum += __shfl_xor(wsum, 1);
-    wsum += __shfl_xor(wsum, 2);
-    if (q == 0) {
-      const int ch = n_tile * 64 + lc;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      unsigned w[3];
+#pragma unroll
+      for (int j = 0; j < 3; ++j)
+        w[j] = load4_shift(wd[r][j], load4_over(base + (unsigned)(r * S * C + 4 * j), p.w_bytes));
+      v4i frag;
+      frag[0] = (int)(w[0] & 0x00ffffffu);
+      frag[1] = (int)(((w[0] >> 24) | (w[1] << 8)) & 0x00ffffffu);
+      frag[2] = (int)(((w[1] >> 16) | (w[2] << 16)) & 0x00ffffffu);
+      frag[3] = lhalf ? 0 : (int)(w[2] >> 8);               // tap 7 does not exist
+#pragma unroll
+      for (int si = 0; si < 4; ++si) wsum = __builtin_amdgcn_sdot4(frag[si], 0x01010101, wsum, false);
+      wfrag[(nb * R + r) * 64 + lane] = frag;
+    }
+    wsum += __shfl_xor(wsum, 32);            // both halves of the channel's filter
+    if (lhalf == 0) {
       unsigned ct = 0u - (unsigned)p.x_off * (unsigned)wsum;
       if (ch < p.k && bias) ct += (unsigned)bias[ch];
       cterm[lc] = (int)ct;
     }
   }
-  __syncthreads();                           // fragments and channel terms; the only barriers of the kernel
+  __syncthreads();                           // fragments and channel terms; the only barrier of the kernel
   if (!has_work) return;
 
   // lane = pixel (row lrow / 16 of the block's two, column lrow % 16) as the MFMA column operand
   const int* src = patch + ((lrow >> 4) * STRIDE) * PITCH + (lrow & 15) * STRIDE + 4 * lhalf;
+  const FoldedRequant fold = make_folded_requant(p.shift, p.y_off);   // uniform
   const bool fast = p.shift >= 33;           // uniform
   const bool wide = p.k % 16 == 0;           // uniform: runs of 16 channels are wholly inside or outside
   const int col0 = n_tile * 64 + 32 * lhalf; // first of the lane's 32 channels
+  const int lo_v = p.lo;
 
   store_patch();
   for (; it < it_end; ++it) {
     const bool has_next = it + 1 < it_end;
     if (has_next) load_patch(it + 1);
 
+    // the accumulators start at the channel terms: register e of block nb = channel 32*half + 16*nb + e
     v16i acc[2];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { acc[0][e] = 0; acc[1][e] = 0; }
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const v4i ct = *reinterpret_cast<const v4i*>(cterm + 32 * lhalf + 16 * nb + 4 * q4);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) acc[nb][4 * q4 + t] = ct[t];
+      }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const int* a = src + r * PITCH;
@@ -227,7 +231,7 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
 
     if (has_next) store_patch();             // after this block's reads, in order
 
-    // ---- epilogue: register e of block nb = channel 32*half + 16*nb + e of pixel lane % 32
+    // ---- epilogue: requantize, clamp, pack, store the lane's 32 channels of pixel lane % 32
     const int bx = it % blocks_x;
     const int t2 = it / blocks_x;
     const int by = t2 % blocks_y;
@@ -235,19 +239,20 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
     const int oh = by * BH + (lrow >> 4), ow = bx * BW + (lrow & 15);
     const bool pix_ok = oh < p.oh && ow < p.ow;
     signed char* dst = Y + (((size_t)img * p.oh + oh) * p.ow + ow) * p.k + col0;
-    auto finish = [&](auto fast_tag) {
-      constexpr bool FAST = decltype(fast_tag)::value;
+    auto finish = [&](auto mode_tag) {
+      constexpr int MODE = decltype(mode_tag)::value;      // 2 folded, 1 multiply-high, 0 64-bit
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
         v4i out;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-          const v4i ct = *reinterpret_cast<const v4i*>(cterm + 32 * lhalf + 16 * nb + 4 * q4);
           int q[4];
 #pragma unroll
-          for (int t = 0; t < 4; ++t)
-            q[t] = requantize_as<FAST>((int)((unsigned)acc[nb][4 * q4 + t] + (unsigned)ct[t]), p.mant, p.shift,
-                                       p.y_off, p.lo);
+          for (int t = 0; t < 4; ++t) {
+            const int v = acc[nb][4 * q4 + t];
+            q[t] = MODE == 2 ? requantize_folded(v, p.mant, fold, lo_v)
+                             : requantize_as<MODE == 1>(v, p.mant, p.shift, p.y_off, p.lo);
+          }
           out[q4] = (int)pack_codes(q[0], q[1], q[2], q[3]);
         }
         const int col = col0 + 16 * nb;
@@ -261,7 +266,9 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
         }
       }
     };
-    if (fast) finish(std::true_type{}); else finish(std::false_type{});
+    if (fold.ok) finish(std::integral_constant<int, 2>{});
+    else if (fast) finish(std::integral_constant<int, 1>{});
+    else finish(std::integral_constant<int, 0>{});
   }
 }
 
@@ -288,7 +295,7 @@ hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** v
   const int blocks_y = (p.oh + BH - 1) / BH, blocks_x = (p.ow + BW - 1) / BW;
   const long long items = (long long)p.n * blocks_y * blocks_x;
   const int n_tiles = (p.k + 63) / 64;
-  int per_cu = 3;            // persistent workgroups per CU (measured at batch 32: 24.2 / 25.5 / 28.0 us for 3 / 4 / 5)
+  int per_cu = 4;            // persistent workgroups per CU (measured: 3, 4 and 5 are within 1 % at batch 32; 4 is best at batch 1)
   if (const char* env = getenv("GLOWMI_SMALLC_I8_WGS")) per_cu = atoi(env);   // experiments
   if (per_cu < 1) per_cu = 1;
   if (per_cu > 8) per_cu = 8;

@@ -29,6 +29,31 @@ __device__ __forceinline__ int requantize_as(int acc, int mant, int shift, int y
   return q;
 }
 
+// The same for shift in [33, 54] with the rounding constant and the output offset folded into one
+// addend  K = 2^(shift-33) + y_off * 2^(shift-32):
+//   ((hi + 2^(shift-33)) >> (shift-32)) + y_off == (hi + K) >> (shift-32)
+// exactly (a multiple of 2^(shift-32) added before an arithmetic shift adds that multiple of one
+// after it), and |hi| < 2^30, |K| < 2^30, so the sum cannot overflow.  The clamp to [lo, 127] is one
+// median-of-three; the compiler does not form it from a variable lower bound, hence the asm (VOP3
+// reads at most one scalar register here, so `lo` comes in a vector register).
+struct FoldedRequant {
+  int s, K;           // shift - 32, folded addend
+  bool ok;            // shift in [33, 54]
+};
+__device__ __forceinline__ FoldedRequant make_folded_requant(int shift, int y_off) {
+  FoldedRequant f;
+  f.ok = shift >= 33 && shift <= 54;
+  f.s = f.ok ? shift - 32 : 1;
+  f.K = (1 << (f.s - 1)) + y_off * (1 << f.s);
+  return f;
+}
+__device__ __forceinline__ int requantize_folded(int acc, int mant, const FoldedRequant& f, int lo_vgpr) {
+  const int q = (__mulhi(acc, mant) + f.K) >> f.s;
+  int r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(q), "v"(lo_vgpr), "s"(127));
+  return r;
+}
+
 // round_half_up(d * mant / 2^shift): a quantized addend's code difference d = r - r_offset brought
 // to the accumulator's scale (the rescale node of Section 4.3 in front of the add), shift in [1, 62].
 __device__ __forceinline__ int rescale_term(int d, int mant, int shift) {
