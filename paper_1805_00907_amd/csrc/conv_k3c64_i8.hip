@@ -42,7 +42,7 @@ constexpr int K3_AREGION = 32 * K3_APITCH;     // bytes per wavefront
 constexpr int K3_LOADS = K3_ROW / 2 / 16;      // 16-byte loads per lane and chunk (two lanes per pixel)
 
 template <int WAVES>
-constexpr int k3_lds_bytes() { return K3_BN * K3_WPITCH + WAVES * K3_AREGION + K3_BN * 4; }
+constexpr int k3_lds_bytes() { return K3_BN * K3_WPITCH + WAVES * K3_AREGION + K3_BN * 4 + 256 * 4; }   // + addend table
 
 // Row of the staged filter slice that holds output channel `c` (0..63).  MFMA nb (0/1) multiplies
 // rows nb*32 .. nb*32+31; result register e of a lane with half h is MFMA row (e/4)*8 + 4h + e%4,
@@ -60,6 +60,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_kernel(const Prob
   extern __shared__ __align__(16) unsigned char smem[];   // filter slice, chunk regions, channel terms
   unsigned char* wlds = smem;
   int* cterm = reinterpret_cast<int*>(smem + K3_BN * K3_WPITCH + WAVES * K3_AREGION);
+  int* addlut = cterm + K3_BN;   // [256] the addend's code (as an unsigned byte) -> its term at the accumulator's scale
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -164,6 +165,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_kernel(const Prob
     }
   }
   __syncthreads();
+  // every value a quantized addend can contribute: 256 codes, so the 64-bit rescale is done once per
+  // code here instead of once per output in the epilogue
+  if (ADD && tid < 256) addlut[tid] = rescale_term((int)(signed char)tid - p.r_off, p.r_mant, p.r_shift);
   // per-channel additive term, combined modulo 2^32 (the true accumulator fits int32 by contract)
   if (tid < K3_BN) {
     const int ch = slice * K3_BN + tid;
@@ -241,8 +245,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_kernel(const Prob
           for (int t = 0; t < 4; ++t) {
             unsigned v = (unsigned)acc[4 * q4 + t];
             if (ADD) {
-              const int code = (int)(signed char)((unsigned)addq[nb][q4] >> (8 * t));
-              v += (unsigned)rescale_term(code - p.r_off, p.r_mant, p.r_shift);
+              v += (unsigned)addlut[((unsigned)addq[nb][q4] >> (8 * t)) & 0xffu];
             }
             q[t] = MODE == 2 ? requantize_folded((int)v, p.mant, fold, lo_v)
                              : requantize_as<MODE == 1>((int)v, p.mant, p.shift, p.y_off, p.lo);

@@ -14,7 +14,8 @@
 //     operations execute in order) while the previous block is being worked on;
 //   - per (block, 64-channel group) item: C/32 MFMA steps (v_mfma_i32_32x32x32_i8) with the filter
 //     as the row operand and the channels permuted so that a lane ends up with 32 consecutive
-//     channels of one pixel: add the channel term, requantize, clamp, pack, two 16-byte stores.
+//     channels of one pixel (the accumulators start at the channel term): requantize, clamp, pack,
+//     two 16-byte stores.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -45,7 +46,7 @@ struct PwQ {
   static constexpr int NI = 32 / RPI;               // staging instructions per block
   static constexpr int AREGION = 32 * PITCH;        // bytes per wavefront
   static constexpr int WG_PER_CU = K <= 128 ? 2 : 1;
-  static constexpr int lds_bytes = BN * PITCH + PWQ_WAVES * AREGION + BN * 4;
+  static constexpr int lds_bytes = BN * PITCH + PWQ_WAVES * AREGION + BN * 4 + 256 * 4;   // + addend table
   static_assert(K % 64 == 0 && K <= 256, "reduction length");
 };
 
@@ -67,6 +68,7 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
   extern __shared__ __align__(16) unsigned char smem[];   // filter slice, A regions, channel terms
   unsigned char* wlds = smem;
   int* cterm = reinterpret_cast<int*>(smem + G::BN * G::PITCH + PWQ_WAVES * G::AREGION);
+  int* addlut = cterm + G::BN;   // [256] the addend's code (as an unsigned byte) -> its term at the accumulator's scale
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -118,9 +120,22 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
       *reinterpret_cast<v4i*>(alds + (i * G::RPI + srow) * G::PITCH + 16 * sq) = st[i];
   };
 
+  // The lane's 32 addend codes of an item are fetched one item ahead: a load issued in the item that
+  // uses it would expose its whole latency (the MFMAs of a short reduction hide none of it), and a
+  // load in the epilogue would, the memory counter being in order, also wait for the stores before it.
+  v4i addn[2];
+  auto fetch_addend = [&](int item) {
+    const int rbx = range.div_ngc.div(item);
+    const int ngx = item - rbx * range.ngc;
+    const unsigned offx = (unsigned)(rbx * 32 + l32) * (unsigned)p.k + (unsigned)(slice * G::BN + ngx * 64 + 32 * lh);
+    addn[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_add, offx, 0, 0);
+    addn[1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_add, offx + 16u, 0, 0);
+  };
+
   // the first block's loads go out before the filter slice's, so both latencies overlap
   const bool has_work = it < it_end;
   if (has_work) fetch_block(range.div_ngc.div(it));
+  if (ADD && has_work) fetch_addend(it);
 
   // ---- filter slice -> LDS in MFMA row order.  The slice is one contiguous run of the [k][C]
   // filter; rows past the last output channel lie past the end of the tensor and the range-checked
@@ -142,6 +157,9 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
     }
   }
   __syncthreads();
+  // every value a quantized addend can contribute: 256 codes, so the 64-bit rescale is done once per
+  // code here instead of once per output in the epilogue
+  if (ADD && tid < 256) addlut[tid] = rescale_term((int)(signed char)tid - p.r_off, p.r_mant, p.r_shift);
   // per-channel additive term, combined modulo 2^32 (the true accumulator fits int32 by contract)
   if (tid < G::BN) {
     const int ch = slice * G::BN + tid;
@@ -163,6 +181,8 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
   const unsigned char* a_lane = alds + l32 * G::PITCH + 16 * lh;
   const unsigned char* w_lane = wlds + l32 * G::PITCH + 16 * lh;
   const bool fast = p.shift >= 33;                         // uniform
+  const FoldedRequant fold = make_folded_requant(p.shift, p.y_off);   // uniform
+  const int lo_v = p.lo;
 
   commit_block();
   while (it < it_end) {
@@ -174,18 +194,23 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
 
     for (; it < rb_items_end; ++it) {
       const int ng = it - rb * range.ngc;
-      // the lane's 32 addend codes, fetched ahead of the MFMAs (a load in the epilogue would wait for
-      // its own latency and, the memory counter being in order, for the stores before it)
       const int ch0 = slice * G::BN + ng * 64 + 32 * lh;   // first of the lane's 32 channels
       const unsigned off = (unsigned)(rb * 32 + l32) * (unsigned)p.k + (unsigned)ch0;
       v4i addq[2];
       if (ADD) {
-        addq[0] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_add, off, 0, 0);
-        addq[1] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_add, off + 16u, 0, 0);
+        addq[0] = addn[0];
+        addq[1] = addn[1];
+        if (it + 1 < it_end) fetch_addend(it + 1);
       }
+      // the accumulators start at the channel terms: register e of acc<nb> = channel 32*lh + 16*nb + e
       v16i acc0, acc1;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) { acc0[e] = 0; acc1[e] = 0; }
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const v4i c0 = *reinterpret_cast<const v4i*>(cterm + ng * 64 + 32 * lh + 4 * q4);
+        const v4i c1 = *reinterpret_cast<const v4i*>(cterm + ng * 64 + 32 * lh + 16 + 4 * q4);
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { acc0[4 * q4 + t] = c0[t]; acc1[4 * q4 + t] = c1[t]; }
+      }
       const unsigned char* wl = w_lane + ng * 64 * G::PITCH;
 #pragma unroll
       for (int s = 0; s < G::STEPS; ++s) {
@@ -198,24 +223,23 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
       }
 
       // ---- epilogue: lane (l32, lh) holds pixel l32, channels 32*lh + 16*nb + e of the group
-      auto finish = [&](auto fast_tag) {
-        constexpr bool FAST = decltype(fast_tag)::value;
+      auto finish = [&](auto mode_tag) {
+        constexpr int MODE = decltype(mode_tag)::value;    // 2 folded, 1 multiply-high, 0 64-bit
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
           const v16i& acc = nb == 0 ? acc0 : acc1;
           v4i out;
 #pragma unroll
           for (int q4 = 0; q4 < 4; ++q4) {
-            const v4i ct = *reinterpret_cast<const v4i*>(cterm + ng * 64 + 32 * lh + 16 * nb + 4 * q4);
             int q[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-              unsigned v = (unsigned)acc[4 * q4 + t] + (unsigned)ct[t];
+              unsigned v = (unsigned)acc[4 * q4 + t];
               if (ADD) {
-                const int code = (int)(signed char)((unsigned)addq[nb][q4] >> (8 * t));
-                v += (unsigned)rescale_term(code - p.r_off, p.r_mant, p.r_shift);
+                v += (unsigned)addlut[((unsigned)addq[nb][q4] >> (8 * t)) & 0xffu];
               }
-              q[t] = requantize_as<FAST>((int)v, p.mant, p.shift, p.y_off, p.lo);
+              q[t] = MODE == 2 ? requantize_folded((int)v, p.mant, fold, lo_v)
+                               : requantize_as<MODE == 1>((int)v, p.mant, p.shift, p.y_off, p.lo);
             }
             out[q4] = (int)pack_codes(q[0], q[1], q[2], q[3]);
           }
@@ -224,7 +248,9 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
           if (ch0 + 16 * nb < p.k) __builtin_amdgcn_raw_buffer_store_b128(out, rsrc_y, off + 16u * nb, 0, 0);
         }
       };
-      if (fast) finish(std::true_type{}); else finish(std::false_type{});
+      if (fold.ok) finish(std::integral_constant<int, 2>{});
+      else if (fast) finish(std::integral_constant<int, 1>{});
+      else finish(std::integral_constant<int, 0>{});
     }
     if (has_next) commit_block();                          // after this block's fragment reads, in order
   }
