@@ -508,8 +508,13 @@ Plan plan_i8(const Problem& p, bool allow_split) {
   // kernel built for them.
   if (wide_i8_applicable(p)) {
     if (forced == 4 || forced == 5) return plan_wide_i8(p, (forced == 4 || p.b_is_kn) ? 128 : 64, allow_split);
-    if (forced < 0 && p.Kgemm >= 256 && p.M >= 96 && p.kg >= 128 && !pw_i8_applicable(p))
-      return plan_wide_i8(p, 128, allow_split);
+    if (forced < 0 && p.Kgemm >= 256 && p.M >= 96 && p.kg >= 128 && !pw_i8_applicable(p)) {
+      // convolutions with at most one 128 x 128 tile per CU take 128 x 64 tiles: twice the workgroups
+      // for the same bytes per workgroup (measured: 3x3 512->512 on 7x7 at batch 32 21.8 -> 19.6 us,
+      // 1x1 512->2048 on 7x7 9.1 -> 8.5 us; 1x1 256->1024 on 14x14 with 392 tiles stays at 128 x 128)
+      const long long t128 = (long long)((p.M + 127) / 128) * ((p.kg + 127) / 128) * p.groups;
+      return plan_wide_i8(p, (!p.b_is_kn && t128 <= 256) ? 64 : 128, allow_split);
+    }
   }
   pl.tile = tile;
   pl.bm = kTilesI8[tile].bm;
