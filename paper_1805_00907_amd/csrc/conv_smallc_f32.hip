@@ -41,7 +41,9 @@ struct SmallC {
   static constexpr int PITCH = ((PWC + 15) / 16) * 16;   // multiple of 16 floats: see bank note below
   static constexpr int PATCH = (PH + 1) * PITCH;         // +1 row: the k = K padding step reads it
   static constexpr int LOADS = (PH * PWC + SC_THREADS - 1) / SC_THREADS;
-  static constexpr int lds_bytes = 2 * PATCH * (int)sizeof(float);
+  // two patch buffers; the same space first holds half a filter slice (32 channels) while the
+  // filter fragments are picked
+  static constexpr int lds_bytes = (2 * PATCH > 32 * K ? 2 * PATCH : 32 * K) * (int)sizeof(float);
   // patch offset of reduction index v relative to a pixel's patch origin
   static constexpr int off(int v) { return (v / RUN) * PITCH + (v % RUN); }
 };
@@ -64,17 +66,11 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
   const float* __restrict__ X = static_cast<const float*>(p.x);
   const float* __restrict__ Wt = static_cast<const float*>(p.w);
   const float* __restrict__ bias = static_cast<const float*>(p.bias);
-  float* __restrict__ Y = static_cast<float*>(p.y);
+  const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
+      p.y, 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
 
-  // ---- filter fragment: lane (channel, half) keeps W[channel][2t + half] for every step t
   const int ch = n_tile * 64 + wch * 32 + lrow;
   const bool ch_ok = ch < p.k;
-  float wfrag[G::STEPS];
-#pragma unroll
-  for (int t = 0; t < G::STEPS; ++t) {
-    const int v = 2 * t + lhalf;
-    wfrag[t] = (ch_ok && v < G::K) ? Wt[(size_t)ch * G::K + v] : 0.f;
-  }
   const float bv = (ch_ok && bias) ? bias[ch] : 0.f;
 
   // ---- per-lane patch bases.  Lane = pixel (prow, pcol) of a 32-pixel MFMA block (2 rows x 16)
@@ -86,11 +82,6 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
   const int base_norm = pix_origin + lhalf;                          // off(2t+1) = off(2t) + 1
   const int base_cross = pix_origin + lhalf * (G::PITCH - (G::RUN - 1));   // 2t is the last index of a run
 
-  // zero the padding row of both buffers once (never overwritten by patch loads)
-  for (int i = tid; i < G::PITCH; i += SC_THREADS) {
-    patch[G::PH * G::PITCH + i] = 0.f;
-    patch[G::PATCH + G::PH * G::PITCH + i] = 0.f;
-  }
 
   float stage[G::LOADS];
   auto load_patch = [&](int tile) {
@@ -122,7 +113,52 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
   // persistent walk over tiles: blockIdx.x, + gridDim.x, ...
   int tile = blockIdx.x;
   if (tile >= total_tiles) return;
-  load_patch(tile);
+  load_patch(tile);                        // in flight while the filter is fetched
+
+  // ---- filter fragment: lane (channel, half) keeps W[channel][2t + half] for every step t.  Picked
+  // straight from global memory every lane of a load sits on its own cache line (channels are K
+  // floats apart) and the 74 loads of a wavefront keep the CU's address unit busy for ~5000 cycles,
+  // times the wavefronts resident on the CU: a quarter of the whole layer at batch 32.  Instead the
+  // 32 channels of each channel half (32 x K floats, contiguous in memory) are copied into LDS
+  // with coalesced loads, in the space of the patch buffers, and the lanes pick from there; rows past
+  // the last output channel lie past the end of the tensor and the range-checked loads return zeros.
+  float wfrag[G::STEPS];
+  {
+    const __amdgpu_buffer_rsrc_t rsrc_w =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Wt), 0, (int)p.w_bytes, 0x00020000);
+    constexpr int HALF_FLOATS = 32 * G::K;
+    constexpr int W_LOADS = (HALF_FLOATS + SC_THREADS - 1) / SC_THREADS;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const unsigned base = (unsigned)((n_tile * 64 + half * 32) * G::K) * 4u;
+      float wst[W_LOADS];
+#pragma unroll
+      for (int i = 0; i < W_LOADS; ++i) {
+        const int e = tid + i * SC_THREADS;
+        wst[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                               rsrc_w, e < HALF_FLOATS ? base + 4u * e : 0xFFFFFFFCu, 0, 0));
+      }
+#pragma unroll
+      for (int i = 0; i < W_LOADS; ++i) {
+        const int e = tid + i * SC_THREADS;
+        if (e < HALF_FLOATS) patch[e] = wst[i];
+      }
+      __syncthreads();
+      if (wch == half) {
+#pragma unroll
+        for (int t = 0; t < G::STEPS; ++t) {
+          const int v = 2 * t + lhalf;
+          wfrag[t] = v < G::K ? patch[lrow * G::K + v] : 0.f;
+        }
+      }
+      __syncthreads();
+    }
+  }
+  // zero the padding row of both buffers once (never overwritten by patch loads)
+  for (int i = tid; i < G::PITCH; i += SC_THREADS) {
+    patch[G::PH * G::PITCH + i] = 0.f;
+    patch[G::PATCH + G::PH * G::PITCH + i] = 0.f;
+  }
   store_patch(0);
   __syncthreads();
   int buf = 0;
@@ -153,23 +189,33 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
     if (has_next) store_patch(buf ^ 1);
 
     // ---- epilogue of this tile.  32x32 result: register e of a lane is pixel (e/4)*8 + 4*half + e%4
-    // of the block, channel = lane % 32.
+    // of the block (2 rows x 16 columns), channel = lane % 32: relative to the lane's first pixel
+    // (row 0, column 4*half) register e lies drow = e/8 rows down and dcol = e%4 + 8*((e/4)%2) columns
+    // right.  The stores go through a range-checked buffer with the (uniform) pixel step in the scalar
+    // offset, so a store costs a compare against the lane's remaining rows / columns instead of a
+    // 64-bit address computation; a pixel outside the image gets an offset past the buffer (outputs are
+    // below 2 GiB here, so 2^31 plus any pixel step is past the end without wrapping) and is dropped by
+    // the hardware.
     {
       const int tx = tile % tiles_x;
       const int t2 = tile / tiles_x;
       const int ty = t2 % tiles_y;
       const int img = t2 / tiles_y;
+      const int ow0 = tx * TW + 4 * lhalf;
+      const int cols_left = ch_ok ? p.ow - ow0 : 0;                  // dcol is stored iff dcol < cols_left
 #pragma unroll
       for (int i = 0; i < NB; ++i) {
+        const int oh0 = ty * TH + wpix * 2 * NB + i * 2;
+        const int rows_left = p.oh - oh0;                            // uniform
+        const unsigned base = (unsigned)(((img * p.oh + oh0) * p.ow + ow0) * p.k + ch) * 4u;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int pix = (e >> 2) * 8 + lhalf * 4 + (e & 3);        // 0..31 inside the block
-          const int oh = ty * TH + wpix * 2 * NB + i * 2 + (pix >> 4);
-          const int ow = tx * TW + (pix & 15);
-          if (!ch_ok || oh >= p.oh || ow >= p.ow) continue;
+          const int drow = e >> 3, dcol = (e & 3) + 8 * ((e >> 2) & 1);
           float v = acc[i][e] + bv;
           if (p.act == 1) v = fmaxf(v, 0.f);
-          Y[(((size_t)img * p.oh + oh) * p.ow + ow) * p.k + ch] = v;
+          const bool ok = dcol < cols_left && drow < rows_left;
+          const unsigned soff = (unsigned)((drow * p.ow + dcol) * p.k) * 4u;   // uniform
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, ok ? base : 0x80000000u, soff, 0);
         }
       }
     }
@@ -213,6 +259,7 @@ hipError_t launch_smallc(const Problem& p, hipStream_t stream) {
 
 bool smallc_f32_applicable(const Problem& p) {
   return !p.b_is_kn && p.groups == 1 && p.r == 7 && p.s == 7 && p.c == 3 && p.stride_h == 2 && p.stride_w == 2 &&
+         (long long)p.M * p.k * 4 < (1LL << 31) && p.w_bytes <= 0x7FFFFFFFu &&
          (long long)p.n * ((p.oh + 3) / 4) * ((p.ow + TW - 1) / TW) < (1LL << 31);
 }
 
