@@ -24,6 +24,7 @@
 #include <type_traits>
 
 #include "igemm.h"
+#include "pw_common.h"
 #include "quant_epilogue.h"
 
 namespace glowmi {
@@ -81,8 +82,9 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_kernel(const Prob
 
   // ---- this wavefront's contiguous range of pixel blocks
   const int wv = blockIdx.x * WAVES + wave;
-  int rb = wv * blocks_div + (wv < blocks_rem ? wv : blocks_rem);
-  const int rb_end = rb + blocks_div + (wv < blocks_rem ? 1 : 0);
+  int rb, rb_end_;
+  deal_range(wv, (int)gridDim.x * WAVES, blocks_div, blocks_rem, rb, rb_end_);
+  const int rb_end = rb_end_;
   const int ohow = p.oh * p.ow;
 
   // ---- gathering a chunk: lane l fetches the half `l & 1` (96 bytes) of filter row r of pixel l / 2.

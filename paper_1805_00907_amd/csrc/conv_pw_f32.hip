@@ -81,8 +81,9 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
   // ---- this wavefront's contiguous range of items (pixel block major, channel group minor)
   const PwRange& range = slice == (int)gridDim.y - 1 ? last : full;    // the last slice may be narrower
   const int wv = blockIdx.x * PW_WAVES + wave;
-  int it = wv * range.items_div + (wv < range.items_rem ? wv : range.items_rem);
-  const int it_end = it + range.items_div + (wv < range.items_rem ? 1 : 0);
+  int it, it_end_;
+  deal_range(wv, (int)gridDim.x * PW_WAVES, range.items_div, range.items_rem, it, it_end_);
+  const int it_end = it_end_;
   auto block_of = [&](int item) { return range.div_ngc.div(item); };
 
   const int ohow = p.oh * p.ow;

@@ -90,8 +90,9 @@ __global__ __launch_bounds__(PWQ_THREADS, PwQ<K>::WG_PER_CU) void conv_pw_i8_ker
   // ---- this wavefront's contiguous range of items (pixel block major, channel group minor)
   const PwRange& range = slice == (int)gridDim.y - 1 ? last : full;    // the last slice may be narrower
   const int wv = blockIdx.x * PWQ_WAVES + wave;
-  int it = wv * range.items_div + (wv < range.items_rem ? wv : range.items_rem);
-  const int it_end = it + range.items_div + (wv < range.items_rem ? 1 : 0);
+  int it, it_end_;
+  deal_range(wv, (int)gridDim.x * PWQ_WAVES, range.items_div, range.items_rem, it, it_end_);
+  const int it_end = it_end_;
   const int ohow = p.oh * p.ow;
 
   // Staging of a pixel block: load i of a lane covers pixel i*RPI + lane/LPR, 16 bytes at channel

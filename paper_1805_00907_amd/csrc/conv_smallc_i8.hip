@@ -23,6 +23,7 @@
 #include <type_traits>
 
 #include "igemm.h"
+#include "pw_common.h"
 #include "quant_epilogue.h"
 
 namespace glowmi {
@@ -94,8 +95,9 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
 
   // ---- this wavefront's contiguous range of pixel blocks (image major, then block row, then column)
   const int wv = blockIdx.x * QS_WAVES + wave;
-  int it = wv * items_div + (wv < items_rem ? wv : items_rem);
-  const int it_end = it + items_div + (wv < items_rem ? 1 : 0);
+  int it, it_end_;
+  deal_range(wv, (int)gridDim.x * QS_WAVES, items_div, items_rem, it, it_end_);
+  const int it_end = it_end_;
 
   // ---- input patch: lane l < PW fetches column l of each of the PH patch rows, one pixel (3 codes)
   // per load as the 4 bytes that start at the pixel; the 4th byte (the next pixel's first code) is
