@@ -83,6 +83,9 @@ hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** varia
 bool k3c64_i8_applicable(const Problem& p);
 hipError_t launch_k3c64_i8(const Problem& p, hipStream_t stream, const char** variant);
 bool smallc_i8_applicable(const Problem& p);
+// int8 FullyConnected with at most 64 rows in one launch (fc_small_i8.hip).
+bool fc_small_i8_applicable(const Problem& p);
+hipError_t launch_fc_small_i8(const Problem& p, hipStream_t stream, const char** variant);
 hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant);
 
 // Element-wise conversions between float and quantized tensors (elementwise.hip).

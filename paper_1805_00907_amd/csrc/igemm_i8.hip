@@ -495,7 +495,8 @@ hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, b
 
 Plan plan_i8(const Problem& p, bool allow_split) {
   Plan pl;
-  if (((smallc_i8_applicable(p) && !p.addend) || pw_i8_applicable(p) || k3c64_i8_applicable(p)) &&
+  if (((smallc_i8_applicable(p) && !p.addend) || pw_i8_applicable(p) || k3c64_i8_applicable(p) ||
+       fc_small_i8_applicable(p)) &&
       !getenv("GLOWMI_I8_TILE"))
     allow_split = false;   // kernels of their own, no workspace
   pl.bk = BKQ;
@@ -555,6 +556,7 @@ hipError_t launch_i8(const Problem& p_in, hipStream_t stream, const char** varia
     return launch_smallc_i8(p_in, stream, variant);   // (that kernel has no tensor-add link)
   if (pw_i8_applicable(p_in) && !getenv("GLOWMI_I8_TILE")) return launch_pw_i8(p_in, stream, variant);
   if (k3c64_i8_applicable(p_in) && !getenv("GLOWMI_I8_TILE")) return launch_k3c64_i8(p_in, stream, variant);
+  if (fc_small_i8_applicable(p_in) && !getenv("GLOWMI_I8_TILE")) return launch_fc_small_i8(p_in, stream, variant);
   Problem p = p_in;
   const Plan plan = plan_i8(p, p.partial != nullptr);
   p.split_k = plan.split_k;
