@@ -77,6 +77,9 @@ hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** 
 // Pointwise convolution with a short reduction and many pixels (conv_pw_f32.hip).
 bool pw_f32_applicable(const Problem& p);
 hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** variant);
+// fp32 convolution on few pixels with a short reduction, in one launch (conv_small_f32.hip).
+bool conv_small_f32_applicable(const Problem& p);
+hipError_t launch_conv_small_f32(const Problem& p, hipStream_t stream, const char** variant);
 bool pw_i8_applicable(const Problem& p);
 hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** variant);
 // int8 3x3 convolution over 64 input channels on many pixels (conv_k3c64_i8.hip).

@@ -612,7 +612,8 @@ constexpr int kNumTilesF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 
 Plan plan_f32(const Problem& p, bool allow_split) {
   Plan pl;
-  if (((smallc_f32_applicable(p) && !p.addend) || pw_f32_applicable(p)) && !getenv("GLOWMI_F32_TILE"))
+  if (((smallc_f32_applicable(p) && !p.addend) || pw_f32_applicable(p) || conv_small_f32_applicable(p)) &&
+      !getenv("GLOWMI_F32_TILE"))
     allow_split = false;   // kernels of their own, no workspace
   if (p.b_is_kn && p.M <= 16 && p.groups == 1 && p.k % 4 == 0 && p.Kgemm % 4 == 0 && !p.addend &&
       !getenv("GLOWMI_F32_TILE")) {
@@ -714,6 +715,8 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
   if (smallc_f32_applicable(p_in) && !p_in.addend && !getenv("GLOWMI_F32_TILE"))
     return launch_smallc_f32(p_in, stream, variant);   // (that kernel has no tensor-add link)
   if (pw_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE")) return launch_pw_f32(p_in, stream, variant);
+  if (conv_small_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE"))
+    return launch_conv_small_f32(p_in, stream, variant);
   Problem p = p_in;
   const Plan plan = plan_f32(p, p.partial != nullptr);
   p.split_k = plan.split_k;
