@@ -36,7 +36,8 @@ constexpr int CS_THREADS = 64 * CS_WAVES;
 constexpr int CS_MAXG = 10;                     // groups of 8 reduction indices per wavefront
 
 template <int G>
-__global__ __launch_bounds__(CS_THREADS, 1) void conv_small_f32_kernel(const Problem p, int groups_total) {
+__global__ __launch_bounds__(CS_THREADS, 1) void conv_small_f32_kernel(const Problem p, int groups_total,
+                                                                       int groups_per_split) {
   __shared__ float part[CS_WAVES * 16 * 64];    // partial accumulators [wave][register][lane]
 
   const int tid = threadIdx.x;
@@ -69,7 +70,9 @@ __global__ __launch_bounds__(CS_THREADS, 1) void conv_small_f32_kernel(const Pro
   const unsigned w_base = ch < p.k ? (unsigned)ch * (unsigned)p.Kgemm * 4u : OOB;
 
   // ---- all loads of this wavefront's groups
-  const int g_begin = wave * G;
+  // blockIdx.z: which slice of the reduction this workgroup takes when it is split over the grid
+  const int g_split_end = (blockIdx.z + 1) * groups_per_split < groups_total ? (blockIdx.z + 1) * groups_per_split : groups_total;
+  const int g_begin = blockIdx.z * groups_per_split + wave * G;
   v4f a[G], b[G];
 #pragma unroll
   for (int i = 0; i < G; ++i) {
@@ -79,13 +82,13 @@ __global__ __launch_bounds__(CS_THREADS, 1) void conv_small_f32_kernel(const Pro
     const int c0 = kk - tap * p.c;
     const int r = p.div_s.div(tap);
     const int s = tap - r * p.s;
-    const bool inside = g < groups_total && m_ok && (unsigned)(ih0 + r) < (unsigned)p.h &&
+    const bool inside = g < g_split_end && m_ok && (unsigned)(ih0 + r) < (unsigned)p.h &&
                         (unsigned)(iw0 + s) < (unsigned)p.w_;
     const unsigned xoff = pix_base + (unsigned)(((r * p.w_ + s) * p.c + c0 + 4 * lh) * 4);
     a[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, inside ? xoff : OOB, 0, 0));
     const unsigned woff = w_base + (unsigned)((kk + 4 * lh) * 4);
     b[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(
-                                       rsrc_w, (g < groups_total && w_base != OOB) ? woff : OOB, 0, 0));
+                                       rsrc_w, (g < g_split_end && w_base != OOB) ? woff : OOB, 0, 0));
   }
 
   v16f acc;
@@ -111,11 +114,17 @@ __global__ __launch_bounds__(CS_THREADS, 1) void conv_small_f32_kernel(const Pro
   if (m >= p.M) return;
   const float* __restrict__ bias = static_cast<const float*>(p.bias);
   float* __restrict__ Y = static_cast<float*>(p.y);
+  const bool split = gridDim.z > 1;              // partial sums go to the workspace, the finishing kernel does the rest
+  float* __restrict__ P = static_cast<float*>(p.partial) + (size_t)blockIdx.z * p.M * p.k;
 #pragma unroll
   for (int g4 = 0; g4 < 4; ++g4) {
     const int c0 = n0 + 8 * g4 + 4 * lh;
     if (c0 >= p.k) continue;                     // k % 4 == 0: a group of four channels is whole or absent
     v4f v = {acc[4 * g4], acc[4 * g4 + 1], acc[4 * g4 + 2], acc[4 * g4 + 3]};
+    if (split) {
+      *reinterpret_cast<v4f*>(P + (size_t)m * p.k + c0) = v;
+      continue;
+    }
     if (bias) v += *reinterpret_cast<const v4f*>(bias + c0);
     if (p.act == 1) {
 #pragma unroll
@@ -131,36 +140,66 @@ int cs_max_tiles() {
 }
 
 template <int G>
-hipError_t launch_cs(const Problem& p, hipStream_t stream, int groups_total) {
-  dim3 grid((unsigned)((p.M + 31) / 32), (unsigned)((p.k + 31) / 32), 1), block(CS_THREADS, 1, 1);
-  hipLaunchKernelGGL(conv_small_f32_kernel<G>, grid, block, 0, stream, p, groups_total);
+hipError_t launch_cs(const Problem& p, hipStream_t stream, int groups_total, int groups_per_split, int splits) {
+  dim3 grid((unsigned)((p.M + 31) / 32), (unsigned)((p.k + 31) / 32), (unsigned)splits), block(CS_THREADS, 1, 1);
+  hipLaunchKernelGGL(conv_small_f32_kernel<G>, grid, block, 0, stream, p, groups_total, groups_per_split);
   return hipGetLastError();
+}
+
+bool shape_ok(const Problem& p) {
+  if (p.b_is_kn || p.groups != 1) return false;
+  if (p.c % 8 != 0 || p.k % 4 != 0) return false;
+  return p.x_bytes <= 0x7FFFFFFFu && p.w_bytes <= 0x7FFFFFFFu;
 }
 
 }  // namespace
 
 bool conv_small_f32_applicable(const Problem& p) {
-  if (p.b_is_kn || p.groups != 1 || p.addend) return false;
-  if (p.c % 8 != 0 || p.k % 4 != 0) return false;
+  if (!shape_ok(p) || p.addend) return false;
   // eight wavefronts x up to CS_MAXG groups of 8; with fewer than two groups per wavefront the generic
   // kernel is as fast (measured: 1x1 64->256 on 56x56, one group each, 7.8 vs 7.2 us)
   if (p.Kgemm > 8 * CS_WAVES * CS_MAXG || p.Kgemm < 8 * CS_WAVES * 2) return false;
-  if (p.x_bytes > 0x7FFFFFFFu || p.w_bytes > 0x7FFFFFFFu) return false;
   const long long tiles = (long long)((p.M + 31) / 32) * ((p.k + 31) / 32);
   return tiles <= cs_max_tiles();
 }
 
-hipError_t launch_conv_small_f32(const Problem& p, hipStream_t stream, const char** variant) {
-  *variant = "conv_small_f32";
+// The same kernel with the reduction also split over the grid, for the deep reductions on very few
+// pixels (3x3 512->512 on a 7x7 map at batch 1): slices of at most 8 x CS_WAVES x 9 reduction indices,
+// partial sums to the workspace, the generic finishing kernel sums them in split order.  Returns the
+// number of slices, 0 if the layer is not of that kind.
+int conv_small_f32_splits(const Problem& p) {
+  if (!shape_ok(p) || p.Kgemm <= 8 * CS_WAVES * CS_MAXG) return 0;
+  if (getenv("GLOWMI_F32_SMALL_NO_SPLIT")) return 0;          // experiments
+  const long long tiles = (long long)((p.M + 31) / 32) * ((p.k + 31) / 32);
   const int groups_total = p.Kgemm / 8;
+  const int per_split = CS_WAVES * 9;
+  const int splits = (groups_total + per_split - 1) / per_split;
+  // enough workgroups to pull the filter through many CUs at once, few enough that the partial sums
+  // (splits x M x k floats, written and read once) stay small next to the filter itself
+  int min_wgs = 64, max_tiles = 128;
+  if (const char* env = getenv("GLOWMI_F32_SMALL_SPLIT_MAX_TILES")) max_tiles = atoi(env);   // experiments
+  if (const char* env = getenv("GLOWMI_F32_SMALL_MIN_WGS")) min_wgs = atoi(env);   // experiments and tests
+  // (measured: 3x3 512->512 on 7x7 at batch 1, 256 workgroups: 16.2 -> 10.6 us; 3x3 128->128 on 28x28, 200:
+  // 13.6 -> 10.4 us; 1x1 1024->256 on 14x14, 112: 11.1 -> 10.1 us; 3x3 512->512 on 7x7 at batch 4, 896: 27.7 -> 29.3 us)
+  if (tiles > max_tiles || tiles * splits < min_wgs || tiles * splits > 512 || splits > 64) return 0;
+  return splits;
+}
+
+hipError_t launch_conv_small_f32(const Problem& p, hipStream_t stream, const char** variant) {
+  const int groups_total = p.Kgemm / 8;
+  if (p.split_k > 1) {
+    *variant = "conv_small_f32_splitk";
+    return launch_cs<9>(p, stream, groups_total, CS_WAVES * 9, p.split_k);
+  }
+  *variant = "conv_small_f32";
   const int per_wave = (groups_total + CS_WAVES - 1) / CS_WAVES;
   switch (per_wave) {
-    case 1: return launch_cs<1>(p, stream, groups_total);
-    case 2: return launch_cs<2>(p, stream, groups_total);
-    case 3: case 4: return launch_cs<4>(p, stream, groups_total);
-    case 5: case 6: return launch_cs<6>(p, stream, groups_total);
-    case 7: case 8: return launch_cs<8>(p, stream, groups_total);
-    default: return launch_cs<CS_MAXG>(p, stream, groups_total);
+    case 1: return launch_cs<1>(p, stream, groups_total, groups_total, 1);
+    case 2: return launch_cs<2>(p, stream, groups_total, groups_total, 1);
+    case 3: case 4: return launch_cs<4>(p, stream, groups_total, groups_total, 1);
+    case 5: case 6: return launch_cs<6>(p, stream, groups_total, groups_total, 1);
+    case 7: case 8: return launch_cs<8>(p, stream, groups_total, groups_total, 1);
+    default: return launch_cs<CS_MAXG>(p, stream, groups_total, groups_total, 1);
   }
 }
 

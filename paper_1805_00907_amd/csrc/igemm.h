@@ -80,6 +80,7 @@ hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** vari
 // fp32 convolution on few pixels with a short reduction, in one launch (conv_small_f32.hip).
 bool conv_small_f32_applicable(const Problem& p);
 hipError_t launch_conv_small_f32(const Problem& p, hipStream_t stream, const char** variant);
+int conv_small_f32_splits(const Problem& p);   // > 1: the split form of that kernel applies, with this many reduction slices
 bool pw_i8_applicable(const Problem& p);
 hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** variant);
 // int8 3x3 convolution over 64 input channels on many pixels (conv_k3c64_i8.hip).

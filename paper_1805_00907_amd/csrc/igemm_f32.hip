@@ -577,6 +577,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void fc_skinny16_f32_kernel(
 }
 
 constexpr int kTileSkinny16 = 101;   // Plan::tile value of the skinny FC kernel
+constexpr int kTileSmallSplit = 102; // Plan::tile value of the small-convolution kernel with a split reduction
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK>
 hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
   auto kern = igemm_f32_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN, LONGK>;
@@ -641,6 +642,22 @@ Plan plan_f32(const Problem& p, bool allow_split) {
       }
     }
     return pl;
+  }
+  if (allow_split && !getenv("GLOWMI_F32_TILE")) {
+    // deep reduction on very few pixels: the single-round-trip kernel, reduction sliced over the grid
+    const int slices = conv_small_f32_splits(p);
+    if (slices > 1) {
+      pl.tile = kTileSmallSplit;
+      pl.bm = 32;
+      pl.bn = 32;
+      pl.bk = 576;
+      pl.tiles_m = (p.M + 31) / 32;
+      pl.tiles_n = (p.k + 31) / 32;
+      pl.slabs = slices;
+      pl.split_k = slices;
+      pl.slabs_per_split = 1;
+      return pl;
+    }
   }
   pl.bk = BK;
   pl.slabs = (p.Kgemm + BK - 1) / BK;
@@ -726,7 +743,9 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
   const bool vec = fc ? (p.Kgemm % 4 == 0 && p.k % 4 == 0) : (p.cg % 4 == 0 && p.c % 4 == 0);
   static thread_local char name[64];
   hipError_t e;
-  if (plan.tile == kTileSkinny16) {
+  if (plan.tile == kTileSmallSplit) {
+    e = launch_conv_small_f32(p, stream, variant);
+  } else if (plan.tile == kTileSkinny16) {
     *variant = "fc_skinny16_f32";
     dim3 grid(plan.tiles_n, plan.split_k, 1), block(64 * SK_WAVES, 1, 1);
     // weights beyond half of the 256 MB last-level cache are treated as a stream

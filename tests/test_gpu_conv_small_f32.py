@@ -67,3 +67,56 @@ def test_conv2d_small_f32_not_taken_with_many_tiles_or_odd_channels():
         got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)
         assert variant != "conv_small_f32", (shape, variant)
         G.assert_close_f32(got, ref, f"conv {shape} [{variant}]")
+
+
+# The same kernel with the reduction also sliced over the grid (partial sums to the workspace, the
+# finishing kernel sums them in split order): deep reductions on very few pixels.
+# n  h  w  c  k  r  s  stride  pads
+SPLIT_CONV = [
+    (1, 7, 7, 512, 512, 3, 3, (1, 1), (1, 1, 1, 1)),       # the batch-1 3x3 of the last stage: 8 slices x 32 tiles
+    (1, 14, 14, 256, 256, 3, 3, (1, 1), (1, 1, 1, 1)),     # 4 slices x 56 tiles
+    (2, 5, 6, 96, 36, 3, 3, (1, 1), (1, 1, 1, 1)),         # 864 indices: a full slice and a half one; ragged pixels and channels
+    (1, 4, 9, 648, 8, 1, 1, (1, 1), (0, 0, 0, 0)),         # 648 indices, 8 more than one workgroup takes: second slice of one group
+    (3, 3, 3, 40, 20, 5, 5, (2, 2), (2, 2, 2, 2)),         # 5x5 stride 2 on a 3x3 map: most taps are padding
+]
+
+
+@pytest.mark.parametrize("i", range(len(SPLIT_CONV)))
+def test_conv2d_small_f32_split(i, monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_F32_SMALL_MIN_WGS", "1")     # take the sliced form at any size
+    n, h, w, c, k, r, s, st, pd = SPLIT_CONV[i]
+    rng = np.random.default_rng(9750 + i)
+    x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
+    wt = (rng.uniform(-1, 1, size=(k, r, s, c)) / np.sqrt(r * s * c)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(k,)).astype(np.float32)
+    desc = G.make_desc(x.shape, wt.shape, st, pd, 1)
+    oh, ow = oracle.out_dim(h, r, st[0], pd[0], pd[2]), oracle.out_dim(w, s, st[1], pd[1], pd[3])
+    add = rng.uniform(-1, 1, size=(n, oh, ow, k)).astype(np.float32)
+    for act in (wl.ACT_RELU, wl.ACT_NONE):
+        ref = oracle.conv2d_f32(x, wt, b, st, pd, 1, act=act)
+        got, variant = G.gpu_conv2d_f32(x, wt, b, desc, act)
+        assert variant == "conv_small_f32_splitk", variant
+        G.assert_close_f32(got, ref, f"sliced small conv {SPLIT_CONV[i]} act {act} [{variant}]")
+        # without a workspace the reduction cannot be sliced over the grid: another kernel, same result
+        got, variant = G.gpu_conv2d_f32(x, wt, b, desc, act, use_workspace=False)
+        assert variant != "conv_small_f32_splitk", variant
+        G.assert_close_f32(got, ref, f"sliced small conv {SPLIT_CONV[i]} act {act} no workspace [{variant}]")
+        # the add link is applied by the finishing kernel
+        ref = oracle.conv2d_f32_add(x, wt, b, add, st, pd, 1, act=act)
+        got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, desc, act)
+        assert variant == "conv_small_f32_splitk", variant
+        G.assert_close_f32(got, ref, f"sliced small conv + add {SPLIT_CONV[i]} act {act} [{variant}]")
+
+
+def test_conv2d_small_f32_split_is_the_planner_choice():
+    """Without any override the batch-1 3x3 512->512 on a 7x7 map takes the sliced form."""
+    G = _gpu()
+    n, h, w, c, k, r, s, st, pd = SPLIT_CONV[0]
+    rng = np.random.default_rng(9760)
+    x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
+    wt = (rng.uniform(-1, 1, size=(k, r, s, c)) / np.sqrt(r * s * c)).astype(np.float32)
+    desc = G.make_desc(x.shape, wt.shape, st, pd, 1)
+    got, variant = G.gpu_conv2d_f32(x, wt, None, desc, wl.ACT_RELU)
+    assert variant == "conv_small_f32_splitk", variant
+    G.assert_close_f32(got, oracle.conv2d_f32(x, wt, None, st, pd, 1, act=wl.ACT_RELU), "planner-chosen sliced small conv")
