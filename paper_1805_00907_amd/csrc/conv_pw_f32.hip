@@ -16,7 +16,9 @@
 //   - after the one barrier that publishes the filter slice the wavefronts run independently, two
 //     per SIMD overlapping each other's loads and MFMAs; the next chunk's global loads are in flight
 //     during the MFMAs of the current one;
-//   - work items are (pixel block, 64-channel group); a wavefront takes a contiguous range of them
+//   - work items are (pixel block, 64-channel group), or their 32-channel halves when there are few
+//     per wavefront; a wavefront takes a contiguous range of them and computes the two halves of a
+//     group together where it holds both
 //     (with C = 64 consecutive items of one pixel block reuse the staged chunk), so the last round of
 //     the grid is short.
 // Epilogue as everywhere (operator stacking, Section 5.2): bias + Relu on the accumulators, one store.
@@ -24,6 +26,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "igemm.h"
 #include "pw_common.h"
@@ -55,7 +58,7 @@ struct Pw {
 // ADD: the element-wise chain has a tensor-add link (p.addend, of the output's shape).
 template <int K, bool CONTIGUOUS, bool ADD>
 __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Problem p, const PwRange full,
-                                                                   const PwRange last) {
+                                                                   const PwRange last, int halves) {
   using G = Pw<K>;
   extern __shared__ __align__(16) float smem[];            // filter slice [BN][PITCH], A regions, bias [BN]
   float* wlds = smem;
@@ -152,29 +155,30 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
 
   if (!has_work) return;
   commit_chunk();
-  for (; it < it_end; ++it) {
-    const int rb = block_of(it), ng = it - rb * range.ngc;
-    const bool more = it + 1 < it_end;
-    const int rb_next = block_of(it + 1);
-
+  // One item: NB = 2 (both 32-channel halves of a 64-channel group, sharing the pixel fragments) or
+  // NB = 1 (the half `hsel` alone, where a wavefront's range begins or ends inside a group).
+  auto process = [&](auto nb_tag, int rb, int ng, int hsel, bool more, int rb_next) {
+    constexpr int NB = decltype(nb_tag)::value;
     // The addend values of this item are fetched before the MFMAs: a load issued in the epilogue
     // would wait for its own latency and, the memory counter being in order, for the stores before it.
     const unsigned item_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes +
-                              (unsigned)(slice * G::BN + ng * 64 + l32) * 4u;
-    float addv[2][16];
+                              (unsigned)(slice * G::BN + ng * 64 + hsel * 32 + l32) * 4u;
+    float addv[NB][16];
     if (ADD) {
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb)
+      for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int e = 0; e < 16; ++e)
           addv[nb][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
               rsrc_add, item_off + 128u * nb + (unsigned)((e >> 2) * 8 + (e & 3)) * row_bytes, 0, 0));
     }
 
-    v16f acc0, acc1;
+    v16f acc[NB];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) { acc0[e] = 0.f; acc1[e] = 0.f; }
-    const float* wl = w_lane + ng * 64 * G::PITCH;
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[nb][e] = 0.f;
+    const float* wl = w_lane + (ng * 64 + hsel * 32) * G::PITCH;
 #pragma unroll
     for (int c = 0; c < G::KC; ++c) {
       // the chunk after this one: the next of this item, or the first of the next item (with a
@@ -183,15 +187,17 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
       if (stage_next) fetch_chunk(c + 1 < G::KC ? rb : rb_next, c + 1 < G::KC ? c + 1 : 0);
 #pragma unroll
       for (int j = 0; j < PW_CHUNK / 8; ++j) {
-        // all three operands hold channels {8j+t, 8j+4+t} in component t of the two half-waves
+        // all operands hold channels {8j+t, 8j+4+t} in component t of the two half-waves
         const v4f a4 = *reinterpret_cast<const v4f*>(a_lane + 8 * j);
-        const v4f b0 = *reinterpret_cast<const v4f*>(wl + c * PW_CHUNK + 8 * j);
-        const v4f b1 = *reinterpret_cast<const v4f*>(wl + 32 * G::PITCH + c * PW_CHUNK + 8 * j);
+        v4f b[NB];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[t], b0[t], acc0, 0, 0, 0);
-          acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[t], b1[t], acc1, 0, 0, 0);
-        }
+        for (int nb = 0; nb < NB; ++nb)
+          b[nb] = *reinterpret_cast<const v4f*>(wl + nb * 32 * G::PITCH + c * PW_CHUNK + 8 * j);
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(a4[t], b[nb][t], acc[nb], 0, 0, 0);
       }
       // in program order after this chunk's fragment reads: the wavefront's LDS operations execute
       // in order, so the region is overwritten only once it has been read
@@ -201,21 +207,41 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
     // ---- epilogue: register e of a lane is pixel (e/4)*8 + 4*lh + e%4 of the block, channel l32.
     // Rows past M fall outside the output buffer's range and the checked stores drop them.
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const v16f& acc = nb == 0 ? acc0 : acc1;
-      const int ch = slice * G::BN + ng * 64 + nb * 32 + l32;
+    for (int nb = 0; nb < NB; ++nb) {
+      const int ch = slice * G::BN + ng * 64 + (hsel + nb) * 32 + l32;
       if (ch < p.k) {
-        const float bv = blds[ng * 64 + nb * 32 + l32];
+        const float bv = blds[ng * 64 + (hsel + nb) * 32 + l32];
         unsigned lane_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes + (unsigned)ch * 4u;
         asm volatile("" : "+v"(lane_off));                 // keep the per-register row offsets scalar
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const float v = fmaxf(acc[e] + bv + (ADD ? addv[nb][e] : 0.f), floor_value);
+          const float v = fmaxf(acc[nb][e] + bv + (ADD ? addv[nb][e] : 0.f), floor_value);
           const unsigned off = lane_off + (unsigned)((e >> 2) * 8 + (e & 3)) * row_bytes;
           __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, off, 0, 0);
         }
       }
     }
+  };
+
+  if (!halves) {
+    // items are whole 64-channel groups
+    for (; it < it_end; ++it) {
+      const int rb = block_of(it);
+      process(std::integral_constant<int, 2>{}, rb, it - rb * range.ngc, 0, it + 1 < it_end, block_of(it + 1));
+    }
+    return;
+  }
+  // Items are 32-channel halves (range.ngc of them per pixel block, an even number); a wavefront takes
+  // the two halves of a group together wherever its range holds both.
+  while (it < it_end) {
+    const int rb = block_of(it), hh = it - rb * range.ngc;
+    const bool pair = (hh & 1) == 0 && it + 1 < it_end;    // uniform
+    const int step = pair ? 2 : 1;
+    const bool more = it + step < it_end;
+    const int rb_next = block_of(it + step);
+    if (pair) process(std::integral_constant<int, 2>{}, rb, hh >> 1, 0, more, rb_next);
+    else process(std::integral_constant<int, 1>{}, rb, hh >> 1, hh & 1, more, rb_next);
+    it += step;
   }
 }
 
@@ -244,8 +270,14 @@ hipError_t launch_pw(const Problem& p, hipStream_t stream) {
   if (wgs > (items_max + PW_WAVES - 1) / PW_WAVES) wgs = (items_max + PW_WAVES - 1) / PW_WAVES;
   const long long waves = wgs * PW_WAVES;
   dim3 grid((unsigned)wgs, (unsigned)slices, 1), block(PW_THREADS, 1, 1);
-  hipLaunchKernelGGL(kern, grid, block, G::lds_bytes, stream, p,
-                     make_pw_range(row_blocks, groups_full, waves), make_pw_range(row_blocks, groups_last, waves));
+  // With few groups per wavefront (1.5 each on 256->64 at batch 32) whole groups leave a third of the
+  // SIMDs a quarter longer than the rest: the work is then dealt in 32-channel halves (measured 44.4 ->
+  // 41.3 us).  With many groups per wavefront halves only cost shared fragment reads (64->256: 6 groups
+  // each, 44 -> 47 us inside the step), so whole groups stay.
+  const int halves = items_max < 4 * waves ? 1 : 0;
+  const int unit = halves ? 2 : 1;
+  hipLaunchKernelGGL(kern, grid, block, G::lds_bytes, stream, p, make_pw_range(row_blocks, unit * groups_full, waves),
+                     make_pw_range(row_blocks, unit * groups_last, waves), halves);
   return hipGetLastError();
 }
 
