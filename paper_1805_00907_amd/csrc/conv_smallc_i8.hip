@@ -111,26 +111,57 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
   bool col_ok = false;        // the lane's patch column lies inside the image
   unsigned row_mask = 0;      // bit i: patch row i lies inside the image (uniform)
   int tail_row = -1, tail_lane = -1;
-  auto load_patch = [&](int item) {
-    const int bx = item % blocks_x;
+  // Position of an item as (block column, block row, image), stepped instead of divided out per item:
+  // the scalar unit is shared by the whole CU and a block is only a few hundred vector instructions.
+  struct Pos {
+    int bx, by, img;
+  };
+  auto pos_of = [&](int item) {
+    Pos q;
+    q.bx = item % blocks_x;
     const int t2 = item / blocks_x;
-    const int by = t2 % blocks_y;
-    const int img = t2 / blocks_y;
-    const int ih0 = by * BH * STRIDE - p.pad_t;
-    const int iw0 = bx * BW * STRIDE - p.pad_l;
+    q.by = t2 % blocks_y;
+    q.img = t2 / blocks_y;
+    return q;
+  };
+  auto advance = [&](Pos& q) {
+    q.bx += 1;
+    const bool wx = q.bx == blocks_x;
+    q.bx = wx ? 0 : q.bx;
+    q.by += wx ? 1 : 0;
+    const bool wy = q.by == blocks_y;
+    q.by = wy ? 0 : q.by;
+    q.img += wy ? 1 : 0;
+  };
+  auto load_patch = [&](const Pos& q) {
+    const int ih0 = q.by * BH * STRIDE - p.pad_t;
+    const int iw0 = q.bx * BW * STRIDE - p.pad_l;
     const int iw = iw0 + lane;
     col_ok = lane < PW && (unsigned)iw < (unsigned)p.w_;
     tail_lane = p.w_ - 1 - iw0;
-    tail_row = img == p.n - 1 && tail_lane < PW ? p.h - 1 - ih0 : -1;
+    tail_row = q.img == p.n - 1 && tail_lane < PW ? p.h - 1 - ih0 : -1;
     if (tail_row >= PH) tail_row = -1;
-    unsigned voff = col_ok ? (unsigned)iw * (unsigned)C : 0u;
+    const unsigned voff = col_ok ? (unsigned)iw * (unsigned)C : 0u;
+    const unsigned row_bytes = (unsigned)p.w_ * (unsigned)C;
+    if (ih0 >= 0 && ih0 + PH <= p.h && tail_row < 0) {
+      // all patch rows inside the image, and not the block with the tensor's last pixel (almost every
+      // block): one scalar add per row
+      row_mask = (1u << PH) - 1u;
+      unsigned soff = (unsigned)(q.img * p.h + ih0) * row_bytes;
+#pragma unroll
+      for (int i = 0; i < PH; ++i) {
+        stage[i] = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rsrc_x, voff, soff, 0);
+        soff += row_bytes;
+      }
+      return;
+    }
     row_mask = 0;
 #pragma unroll
     for (int i = 0; i < PH; ++i) {
       const int ih = ih0 + i;
       const bool rok = (unsigned)ih < (unsigned)p.h;
       row_mask |= (rok ? 1u : 0u) << i;
-      const unsigned soff = rok ? (unsigned)((img * p.h + ih) * p.w_) * (unsigned)C : 0u;
+      const unsigned soff = rok ? (unsigned)(q.img * p.h + ih) * row_bytes : 0u;
       unsigned vo = voff;
       if (i == tail_row && lane == tail_lane) vo -= 1u;     // (uniform test first: false almost always)
       stage[i] = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(rsrc_x, vo, soff, 0);
@@ -151,7 +182,8 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
   };
 
   const bool has_work = it < it_end;
-  if (has_work) load_patch(it);            // in flight while the filter is fetched
+  Pos cur = pos_of(has_work ? it : 0), nxt = cur;
+  if (has_work) load_patch(cur);           // in flight while the filter is fetched
 
   // ---- filter fragments: for channel block nb and filter row r, lane (MFMA row j, half) feeds the 16
   // codes W[channel_of_row(nb, j)][r][s = 4*half + 0..3][c = 0..3]; s = 7 and c = 3 do not exist and
@@ -204,11 +236,17 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
   const bool wide = p.k % 16 == 0;           // uniform: runs of 16 channels are wholly inside or outside
   const int col0 = n_tile * 64 + 32 * lhalf; // first of the lane's 32 channels
   const int lo_v = p.lo;
+  // the lane's part of the output address, the same for every block
+  const int prow = lrow >> 4, pcol = lrow & 15;
+  const size_t lane_off = ((size_t)prow * p.ow + pcol) * p.k + col0;
 
   store_patch();
   for (; it < it_end; ++it) {
     const bool has_next = it + 1 < it_end;
-    if (has_next) load_patch(it + 1);
+    if (has_next) {
+      advance(nxt);
+      load_patch(nxt);
+    }
 
     // the accumulators start at the channel terms: register e of block nb = channel 32*half + 16*nb + e
     v16i acc[2];
@@ -234,13 +272,10 @@ __global__ __launch_bounds__(QS_THREADS, 4) void conv_smallc_i8_kernel(const Pro
     if (has_next) store_patch();             // after this block's reads, in order
 
     // ---- epilogue: requantize, clamp, pack, store the lane's 32 channels of pixel lane % 32
-    const int bx = it % blocks_x;
-    const int t2 = it / blocks_x;
-    const int by = t2 % blocks_y;
-    const int img = t2 / blocks_y;
-    const int oh = by * BH + (lrow >> 4), ow = bx * BW + (lrow & 15);
-    const bool pix_ok = oh < p.oh && ow < p.ow;
-    signed char* dst = Y + (((size_t)img * p.oh + oh) * p.ow + ow) * p.k + col0;
+    const int oh0 = cur.by * BH, ow0 = cur.bx * BW;         // uniform
+    const bool pix_ok = prow < p.oh - oh0 && pcol < p.ow - ow0;
+    signed char* dst = Y + (((size_t)cur.img * p.oh + oh0) * p.ow + ow0) * p.k + lane_off;
+    cur = nxt;
     auto finish = [&](auto mode_tag) {
       constexpr int MODE = decltype(mode_tag)::value;      // 2 folded, 1 multiply-high, 0 64-bit
 #pragma unroll

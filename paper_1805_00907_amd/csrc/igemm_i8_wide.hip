@@ -563,6 +563,7 @@ Plan plan_wide_i8(const Problem& p, int bn, bool allow_split) {
       if (sk > 1) cost += (double)(sk + 1) * p.M * p.k * 4.0 / 4e12 / 0.25e-6;
       if (cost < best_cost - 1e-9) { best_cost = cost; best = sk; }
     }
+    if (const char* env = getenv("GLOWMI_I8_WIDE_SPLIT")) best = atoi(env);   // experiments
     if (best > 1) {
       pl.slabs_per_split = (pl.slabs + best - 1) / best;
       pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
