@@ -94,7 +94,10 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >>
 // XSUM: the filter offset is not zero, so the input code sums per pixel are needed as well.
 // NBUF: slab buffers in the LDS ring (2: two workgroups per CU, 4: one workgroup with three slabs in flight).
 template <int BN, bool B_KN, bool PADDED, bool XSUM, int NBUF>
-__global__ __launch_bounds__(WTHREADS, NBUF <= 2 ? 2 : 1) void igemm_i8_wide_kernel(const Problem p, int tiles_m,
+// (second launch bound = wavefronts per SIMD: two workgroups of eight per CU need four, i.e. at most 128
+// registers -- with a bound of two the padded 128-channel form took 130 and ran one workgroup per CU;
+// the forms that also take input code sums do not fit 128 without spilling and stay at one per CU)
+__global__ __launch_bounds__(WTHREADS, (NBUF <= 2 && !XSUM) ? 4 : 2) void igemm_i8_wide_kernel(const Problem p, int tiles_m,
                                                                                    int tiles_n, int band_n,
                                                                                    int total_work) {
   static_assert(BN == 64 || BN == 128, "channel tile");
