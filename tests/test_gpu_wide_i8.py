@@ -130,3 +130,56 @@ def test_wide_kernel_is_the_planner_choice_for_large_contractions():
     got, variant = G.gpu_qfc(aq, wq, bq, qp, wl.ACT_NONE)
     assert not variant.startswith("igemm_i8_wide"), variant
     G.assert_equal_i8(got, ref, "small qfc")
+
+
+@pytest.mark.parametrize("i", [0, 1, 3, 5, 8])
+@pytest.mark.parametrize("tile", ["4", "5"])
+@pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", -7)])
+def test_qconv2d_wide_two_buffers(i, tile, dist, w_off, monkeypatch):
+    """The two-buffer form (built for two workgroups per CU, at most 128 registers) on the same shapes:
+    the launcher takes it by itself only for grids larger than the chip, here it is forced."""
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_TILE", tile)
+    monkeypatch.setenv("GLOWMI_I8_WIDE_NBUF", "2")
+    n, h, w, c, k, r, s, st, pd, g = WIDE_CONV[i]
+    layer = wl.ConvLayer(f"wide{i}", n, h, w, c, k, r, s, 1, 0, g)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 8500 + i, dist=dist, w_off=w_off)
+    desc = G.make_desc(xq.shape, wq.shape, st, pd, g)
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                         st, pd, g, act=wl.ACT_RELU)
+    for use_ws in (True, False):
+        got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, wl.ACT_RELU, use_workspace=use_ws)
+        assert variant.startswith("igemm_i8_wide") and "r2_" in variant, variant
+        G.assert_equal_i8(got, ref, f"wide conv {i} tile {tile} {dist} w_off {w_off} ws {use_ws} [{variant}]")
+
+
+@pytest.mark.parametrize("shape", [(130, 272, 144), (256, 1040, 528), (300, 2048, 1008)], ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", 3)])
+def test_qfc_wide_two_buffers(shape, dist, w_off, monkeypatch):
+    G = _gpu()
+    monkeypatch.setenv("GLOWMI_I8_TILE", "4")
+    monkeypatch.setenv("GLOWMI_I8_WIDE_NBUF", "2")
+    M, K, N = shape
+    layer = wl.FcLayer("wide", M, K, N)
+    aq, wq, bq, qp = wl.fc_inputs_q(layer, 8600 + M + K + N, dist=dist, w_off=w_off)
+    ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off, act=wl.ACT_RELU)
+    for use_ws in (True, False):
+        got, variant = G.gpu_qfc(aq, wq, bq, qp, wl.ACT_RELU, use_workspace=use_ws)
+        assert variant.startswith("igemm_i8_wide") and "r2_" in variant, variant
+        G.assert_equal_i8(got, ref, f"wide qfc {shape} {dist} ws {use_ws} [{variant}]")
+
+
+def test_qconv2d_wide_more_tiles_than_cus():
+    """A padded 3x3 layer with 128-channel tiles and more tiles than CUs (the planner's own choice of the
+    two-buffer form, two workgroups resident per CU): sampled outputs against the oracle, which computes
+    them one by one from the definition."""
+    G = _gpu()
+    layer = wl.ConvLayer("many_tiles", 12, 56, 56, 128, 256, 3, 3, 1, 1, 1)   # M = 37632: 294 x 2 tiles
+    for dist in ("normal", "uniform"):
+        xq, wq, bq, qp = wl.conv_inputs_q(layer, 8700, dist=dist, w_off=0)
+        got, variant = G.gpu_qconv2d(xq, wq, bq, qp, G.desc_of(layer), wl.ACT_RELU)
+        assert variant == "igemm_i8_wide_128x128k2w8r2_conv", variant
+        idx = wl.sample_output_indices(layer, 8701)
+        ref = oracle.qconv2d_points(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                                    idx, (1, 1), (1, 1, 1, 1), 1, act=wl.ACT_RELU)
+        G.assert_equal_i8(got.reshape(-1)[idx], ref, f"many tiles {dist} [{variant}]")
