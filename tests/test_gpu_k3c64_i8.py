@@ -1,5 +1,6 @@
-"""The int8 kernel for 3x3 filters over 64 input channels (filter resident in LDS, one chunk per
-filter row, wavefront-private gathering) through the C ABI against the CPU oracle, bit-exact: strides,
+"""The int8 kernel for 3x3 filters over 64 input channels (filter resident in LDS; at stride 1 a block's
+input patch staged once per wavefront, at other strides one gathered chunk per filter row) through the C
+ABI against the CPU oracle, bit-exact: strides,
 every kind of padding, ragged pixel counts and channel counts, several filter slices, both requantize
 forms, the tensor-add link, and the planner's own choice at a size where it takes this kernel.
 """
@@ -31,17 +32,28 @@ K3_SHAPES = [
     (1, 1, 1, 64, (1, 1), (1, 1, 1, 1)),          # one pixel: only the centre tap inside
     (5, 3, 40, 128, (1, 2), (1, 0, 1, 1)),        # wide short images
     (1, 70, 70, 64, (1, 1), (1, 1, 1, 1)),        # more blocks than one workgroup's wavefronts: several per wavefront on few CUs
+    (2, 5, 9, 64, (1, 1), (1, 1, 1, 1)),          # 5 x 9 outputs: a 4 x 8 block grid ragged by one row and one column
+    (3, 4, 8, 32, (1, 1), (1, 1, 1, 1)),          # exactly one block per image
+    (1, 11, 30, 64, (1, 1), (0, 2, 2, 0)),        # one-sided padding at stride 1, 11 x 30 outputs
 ]
 
 
 @pytest.mark.parametrize("i", range(len(K3_SHAPES)))
 @pytest.mark.parametrize("dist,x_off", [("normal", None), ("uniform", -9)])
 @pytest.mark.parametrize("waves", ["8", "16"])
-def test_qconv2d_k3c64(i, dist, x_off, waves, monkeypatch):
+@pytest.mark.parametrize("form", ["2d", "gather"])
+def test_qconv2d_k3c64(i, dist, x_off, waves, form, monkeypatch):
+    """form "2d": the planner's own choice (at stride 1 the form that stages a block's input patch once);
+    "gather": the form that gathers per filter row, which the planner takes for other strides only."""
     G = _gpu()
     monkeypatch.setenv("GLOWMI_I8_K3_MIN_BLOCKS", "1")     # take this kernel at any size
     monkeypatch.setenv("GLOWMI_I8_K3_WAVES", waves)
     n, h, w, k, st, pd = K3_SHAPES[i]
+    if form == "gather":
+        if st != (1, 1):
+            pytest.skip("other strides take the gathering form anyway")
+        monkeypatch.setenv("GLOWMI_I8_K3_GATHER", "1")
+    want_2d = form == "2d" and st == (1, 1)
     layer = wl.ConvLayer(f"k3_{i}", n, h, w, 64, k, 3, 3, 1, 0, 1)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 9500 + i, dist=dist, w_off=0)
     if x_off is not None:
@@ -51,7 +63,7 @@ def test_qconv2d_k3c64(i, dist, x_off, waves, monkeypatch):
         ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
                              st, pd, 1, act=act)
         got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, act)
-        assert variant.startswith("conv_k3c64_i8_w" + waves), variant
+        assert variant.startswith("conv_k3c64_i8_w" + waves) and ("_2d" in variant) == want_2d, variant
         G.assert_equal_i8(got, ref, f"k3c64 {K3_SHAPES[i]} {dist} act {act} [{variant}]")
     ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, None, qp.y_scale, qp.y_off,
                          st, pd, 1, act=wl.ACT_NONE)
@@ -59,11 +71,14 @@ def test_qconv2d_k3c64(i, dist, x_off, waves, monkeypatch):
     G.assert_equal_i8(got, ref, f"k3c64 {K3_SHAPES[i]} without bias")
 
 
-@pytest.mark.parametrize("i", [1, 3, 7])
-def test_qconv2d_chain_k3c64(i, monkeypatch):
-    """Tensor-add link of the element-wise chain behind this kernel, out of place and in place."""
+@pytest.mark.parametrize("i", [1, 3, 7, 12])
+@pytest.mark.parametrize("gather", [False, True])
+def test_qconv2d_chain_k3c64(i, gather, monkeypatch):
+    """Tensor-add link of the element-wise chain behind this kernel (both forms), out of place and in place."""
     G = _gpu()
     monkeypatch.setenv("GLOWMI_I8_K3_MIN_BLOCKS", "1")
+    if gather:
+        monkeypatch.setenv("GLOWMI_I8_K3_GATHER", "1")
     n, h, w, k, st, pd = K3_SHAPES[i]
     layer = wl.ConvLayer(f"k3_{i}", n, h, w, 64, k, 3, 3, 1, 0, 1)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 9600 + i, dist="normal", w_off=0)
