@@ -705,6 +705,7 @@ Plan plan_f32(const Problem& p, bool allow_split) {
       if (u > best_u + 1e-9) { best_u = u; best = sk; }
       if (u >= 0.9) { best = sk; break; }
     }
+    if (const char* env = getenv("GLOWMI_F32_SPLIT")) best = atoi(env);   // experiments
     if (best > 1) {
       pl.slabs_per_split = (pl.slabs + best - 1) / best;
       pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
