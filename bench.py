@@ -2,18 +2,29 @@
 """Benchmark of the glowmi hot path on one MI355X.
 
 A step is one pass of the whole hot path -- contraction + bias + Relu (+ requantize), one fused
-kernel per layer -- over every layer of the selected workload, inputs resident in HBM.  The default
-workload is the ResNet-50-shaped fp32 convolution layer set at batch 1 and 32.
+kernel per layer -- over every layer of a workload, inputs resident in HBM.
 
-Prints ONE JSON line: whole-job throughput (`value`), the live roofline figure of the dominant
-kernel (`roofline`), the CPU oracle timed on the host cores on a bounded sample (`cpu_baseline`) and
-a per-layer table (`layers`: TFLOP/s or TOP/s and fraction of the layer's MFMA/HBM roofline).
+The default run times EVERY baseline configuration: the headline (`value`, `ms_per_step`, `roofline`,
+`cpu_baseline`, `layers`) is the largest single-GPU one, the VGG-19-shaped fp32 stack at batch 16 plus
+its FC layers; the ResNet-50 fp32 set (batch 1 and 32), the ResNet-50 int8 set (batch 32) and the FC
+sweep in fp32 and int8 follow under the extra key `workloads`, each with the same block.  Every
+workload is timed with the same --steps / --warmup.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+Prints ONE JSON line.  Per layer: eager time per launch (events on the launch stream), TFLOP/s or
+TOP/s, GB/s of algorithmic bytes, fraction of the layer's MFMA/HBM roofline, and
+  * `llc`: "warm" when the layer reruns on the same buffers and those fit the 256 MB last-level cache
+    (its HBM figure is then a cache figure), "cold" when the tensors exceed it; for every HBM-bound
+    layer `us_cold` is the time per launch when the launches rotate over copies of the tensors that
+    together exceed 512 MB, so that every launch streams from HBM;
+  * `us_graph`: for layers under 10 us, the time per launch of 100 back-to-back launches replayed as
+    one HIP graph (launch-amortised figure).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--only] [--no-cpu-baseline]
 """
 from __future__ import annotations
 
 import argparse
+import copy
 import json
 import os
 import sys
@@ -27,9 +38,15 @@ if ROOT not in sys.path:
 PEAK_FP32_MFMA = 157.3e12      # FLOP/s, fp32 matrix
 PEAK_INT8_MFMA = 5.0e15        # OP/s
 PEAK_HBM = 8.0e12              # B/s
+LLC_BYTES = 256 << 20          # last-level (Infinity) cache
+COLD_ROTATION_BYTES = 512 << 20
+GRAPH_LAUNCHES = 100
+SMALL_LAYER_US = 10.0
 
-WORKLOADS = ["resnet50_fp32", "vgg19_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8",
+WORKLOADS = ["vgg19_fp32", "resnet50_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8",
              "resnet50_tail_fp32", "resnet50_tail_int8", "resnet50_block_fp32", "resnet50_block_int8"]
+HEADLINE = "vgg19_fp32"        # largest single-GPU baseline configuration
+ALSO = ["resnet50_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8"]   # the other baseline configurations
 CHAINED = {"resnet50_block_fp32", "resnet50_block_int8"}   # layers feed each other: run as one sequence
 
 
@@ -58,6 +75,8 @@ def _build_workload(name):
 
 class Layer:
     """One layer resident on the device plus the closure that launches it."""
+
+    TENSORS = ("x", "w", "b", "y", "add", "ws")
 
     def __init__(self, spec, dtype, seed, torch, glowmi):
         from paper_1805_00907_amd import workloads as wl
@@ -107,6 +126,17 @@ class Layer:
         self.ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
         self.glowmi = glowmi
         self.variant = ""
+
+    def device_bytes(self):
+        return sum(t.numel() * t.element_size() for t in (getattr(self, n) for n in self.TENSORS) if t is not None)
+
+    def clone(self):
+        """The same layer on its own copies of every tensor (for the cold-cache rotation)."""
+        other = copy.copy(self)
+        for n in self.TENSORS:
+            t = getattr(self, n)
+            setattr(other, n, None if t is None else t.clone())
+        return other
 
     def launch(self, stream):
         g, s = self.glowmi, self.spec
@@ -162,6 +192,9 @@ class Sequence:
         self.arena = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
         self.variant = "sequence"
 
+    def device_bytes(self):
+        return LLC_BYTES * 4          # never rotated
+
     def launch(self, stream):
         if self.dtype == "f32":
             self.glowmi.seq_conv2d(self.x, self.arr, self.y, self.arena, stream)
@@ -169,7 +202,7 @@ class Sequence:
             self.glowmi.seq_qconv2d(self.x, self.xq, self.arr, self.y, self.arena, stream)
 
 
-def _cpu_baseline(workload, dtype, cfg_index, unit_scale, budget_s=15.0):
+def _cpu_baseline(workload, dtype, cfg_index, unit_scale, budget_s):
     """The oracle as it stands, timed on this machine's host cores on a bounded sample."""
     import oracle
     from paper_1805_00907_amd import workloads as wl
@@ -228,51 +261,70 @@ def _cpu_baseline(workload, dtype, cfg_index, unit_scale, budget_s=15.0):
             "cores": oracle.num_threads(), "kind": "oracle", "sample": desc, "seconds": round(t, 2)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="resnet50_fp32", choices=WORKLOADS)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--graph", action="store_true",
-                    help="capture one step in a HIP graph and time replays of it (launch-overhead "
-                         "amortisation); the roofline figure then comes from the eager calibration pass")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one plain device copy of 256 MiB (a kernel of known traffic, used to "
-                         "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        raise SystemExit("bench.py: this build is single-GPU (one MI355X per box); run with --gpus 1. "
-                         "Sharding is a design note only (batch/row split needs no exchange).")
+def _median(v):
+    v = sorted(v)
+    return v[len(v) // 2]
 
-    import torch
-    import paper_1805_00907_amd as glowmi
+
+def _time_graph_amortised(layer, torch):
+    """us per launch of GRAPH_LAUNCHES back-to-back launches of one layer replayed as one HIP graph."""
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        layer.launch(side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(GRAPH_LAUNCHES):
+                layer.launch(side)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    times = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+    return _median(times) * 1e3 / GRAPH_LAUNCHES
+
+
+def _time_cold(layer, stream, torch):
+    """us per launch when consecutive launches rotate over copies of the layer's tensors that together
+    exceed COLD_ROTATION_BYTES: nothing a launch reads is left in the last-level cache by the previous one."""
+    per = max(layer.device_bytes(), 1)
+    copies = min(96, max(2, -(-COLD_ROTATION_BYTES // per)))
+    ring = [layer] + [layer.clone() for _ in range(copies - 1)]
+    for l in ring:
+        l.launch(stream)
+    torch.cuda.synchronize()
+    rounds = 3 if copies >= 8 else 8
+    ev = []
+    for _ in range(rounds):
+        for l in ring:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            l.launch(stream)
+            e1.record(stream)
+            ev.append((e0, e1))
+    torch.cuda.synchronize()
+    return _median([a.elapsed_time(b) for a, b in ev]) * 1e3, copies
+
+
+def run_workload(name, args, torch, glowmi, cpu_budget_s):
     from paper_1805_00907_amd import workloads as wl
-
-    if not torch.cuda.is_available():
-        raise SystemExit("bench.py needs a GPU (no CPU fallback exists)")
-    glowmi.library()
-    torch.cuda.set_device(0)
     stream = torch.cuda.current_stream()
-
-    dtype, cfg_index, specs = _build_workload(args.workload)
+    dtype, cfg_index, specs = _build_workload(name)
     layers = [Layer(s, dtype, wl.layer_seed(cfg_index, i), torch, glowmi) for i, s in enumerate(specs)]
-    if args.workload in CHAINED:
-        layers = [Sequence(layers, dtype, torch, glowmi, f"{args.workload}@b{specs[0].n} ({len(specs)} launches)")]
+    if name in CHAINED:
+        layers = [Sequence(layers, dtype, torch, glowmi, f"{name}@b{specs[0].n} ({len(specs)} launches)")]
     unit = "TFLOP/s" if dtype == "f32" else "TOP/s"
     total_ops = sum(l.ops for l in layers)
 
     def step():
         for l in layers:
             l.launch(stream)
-
-    if args.calibrate_copy:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
-        dst = torch.empty_like(src)
-        dst.copy_(src)                    # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
 
     for l in layers:                      # first touch + variant names
         l.launch(stream)
@@ -283,7 +335,7 @@ def main():
     torch.cuda.synchronize()
 
     # ---- per-layer calibration (untimed part of the report): events around every launch
-    cal_steps = max(3, min(10, args.steps))
+    cal_steps = max(5, min(20, args.steps))
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
           for _ in range(cal_steps)]
     for s in range(cal_steps):
@@ -292,7 +344,7 @@ def main():
             l.launch(stream)
             ev[s][i][1].record(stream)
     torch.cuda.synchronize()
-    per_layer_ms = [sorted(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(cal_steps))[cal_steps // 2]
+    per_layer_ms = [_median([ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(cal_steps)])
                     for i in range(len(layers))]
     by_variant = {}
     for l, ms in zip(layers, per_layer_ms):
@@ -356,7 +408,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get(f"{args.workload}:{dominant}")
+            traffic = json.load(f).get(f"{name}:{dominant}")
     roofline = {"bound": dom_bound, "achieved": round(achieved, 3), "peak": peak, "unit": runit,
                 "frac": round(achieved / peak, 4), "traffic": traffic, "kernel": dominant,
                 "launches_per_step": len(dom_idx), "avg_launch_us": round(avg_launch_s * 1e6, 2)}
@@ -364,23 +416,90 @@ def main():
     layer_rows = []
     for l, ms in zip(layers, per_layer_ms):
         t = ms * 1e-3
-        layer_rows.append({"layer": l.spec.name, "gemm_mnk": list(l.spec.gemm), "kernel": l.variant,
-                           "us": round(ms * 1e3, 2), unit: round(l.ops / t / 1e12, 3),
-                           "GB/s": round(l.bytes / t / 1e9, 1), "bound": l.bound,
-                           "roofline_frac": round(l.t_roof / t, 4)})
+        row = {"layer": l.spec.name, "gemm_mnk": list(l.spec.gemm), "kernel": l.variant,
+               "us": round(ms * 1e3, 2), unit: round(l.ops / t / 1e12, 3),
+               "GB/s": round(l.bytes / t / 1e9, 1), "bound": l.bound,
+               "roofline_frac": round(l.t_roof / t, 4),
+               "llc": "warm" if l.device_bytes() <= LLC_BYTES else "cold"}
+        if not args.quick:
+            if l.bound == "hbm" and row["llc"] == "warm":
+                us_cold, copies = _time_cold(l, stream, torch)
+                row["us_cold"] = round(us_cold, 2)
+                row["GB/s_cold"] = round(l.bytes / (us_cold * 1e-6) / 1e9, 1)
+                row["roofline_frac_cold"] = round(l.t_roof / (us_cold * 1e-6), 4)
+                row["cold_copies"] = copies
+            if ms * 1e3 < SMALL_LAYER_US:
+                us_graph = _time_graph_amortised(l, torch)
+                row["us_graph"] = round(us_graph, 2)
+                row["roofline_frac_graph"] = round(l.t_roof / (us_graph * 1e-6), 4)
+        layer_rows.append(row)
 
-    out = {
-        "metric": f"{unit} per conv/FC layer set ({args.workload}), with per-layer % of MFMA/HBM roofline",
-        "value": round(value, 3), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32" if dtype == "f32" else "int8", "data": "synthetic",
-        "config": {"workload": args.workload, "layers": len(layers), "launch": "hip graph replay" if args.graph else "eager",
-                   "note": "ResNet-50/VGG-19 layer shapes, seeded synthetic values; no trained weights"},
-        "roofline": roofline,
-    }
+    block = {"value": round(value, 3), "unit": unit, "steps": args.steps, "warmup": args.warmup,
+             "ms_per_step": round(ms_per_step, 4), "dtype": "f32" if dtype == "f32" else "int8",
+             "config": {"workload": name, "layers": len(layers),
+                        "launch": "hip graph replay" if args.graph else "eager",
+                        "note": "ResNet-50/VGG-19 layer shapes, seeded synthetic values; no trained weights"},
+             "roofline": roofline}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = _cpu_baseline(args.workload, dtype, cfg_index, 1e12)
-    out["layers"] = layer_rows
+        block["cpu_baseline"] = _cpu_baseline(name, dtype, cfg_index, 1e12, cpu_budget_s)
+    block["layers"] = layer_rows
+    del layers
+    torch.cuda.empty_cache()
+    return block
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=HEADLINE, choices=WORKLOADS, help="the headline workload")
+    ap.add_argument("--only", action="store_true",
+                    help="time the headline workload only (default: the other baseline configurations follow "
+                         "under the key `workloads`)")
+    ap.add_argument("--quick", action="store_true",
+                    help="skip the per-layer cold-cache rotation and graph-amortised measurements")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step in a HIP graph and time replays of it (launch-overhead "
+                         "amortisation); the roofline figure then comes from the eager calibration pass")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain device copy of 256 MiB (a kernel of known traffic, used to "
+                         "scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build is single-GPU (one MI355X per box); run with --gpus 1. "
+                         "Sharding is a design note only (batch/row split needs no exchange).")
+
+    import torch
+    import paper_1805_00907_amd as glowmi
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (no CPU fallback exists)")
+    glowmi.library()
+    torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                    # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
+    head = run_workload(args.workload, args, torch, glowmi, cpu_budget_s=15.0)
+    out = {
+        "metric": f"{head['unit']} per conv/FC layer set ({args.workload}), with per-layer % of MFMA/HBM roofline",
+        "value": head["value"], "unit": head["unit"], "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": head["config"], "roofline": head["roofline"],
+    }
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    out["layers"] = head["layers"]
+    if not args.only:
+        out["workloads"] = {name: run_workload(name, args, torch, glowmi, cpu_budget_s=4.0)
+                            for name in ALSO if name != args.workload}
     print(json.dumps(out))
 
 

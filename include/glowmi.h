@@ -14,8 +14,8 @@
  * --------------------------------
  *  - Every tensor pointer is a DEVICE pointer to a dense, row-major buffer owned by the caller.
  *    Inputs are never written.  Outputs must not overlap inputs or the workspace.
- *  - x, w, y (and a, the FC input) must be 16-byte aligned, bias 4-byte aligned, else
- *    GLOWMI_ERR_ALIGN.  bias may be NULL (treated as zeros).
+ *  - x, w, y (and a, the FC input) must be 16-byte aligned, bias 4-byte aligned (any 4-byte
+ *    boundary will do), else GLOWMI_ERR_ALIGN.  bias may be NULL (treated as zeros).
  *  - Calls are asynchronous on `stream`, never synchronise the device and never allocate.
  *  - `workspace` is optional scratch in device memory (16-byte aligned).  With NULL / 0 bytes the
  *    call still computes the same result; with at least glowmi_*_workspace_bytes() bytes the
@@ -113,8 +113,12 @@ size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N);
  * Mr = f * 2^e with f in [0.5, 1); mant = round(f * 2^31) (renormalised if that is 2^31);
  * shift = 31 - e, which must lie in [1, 62] (GLOWMI_ERR_QUANT otherwise);
  *   round(acc * Mr) := (acc * mant + 2^(shift-1)) >> shift    (64-bit, arithmetic shift: ties go up).
- * The int32 accumulator must not overflow (not detected on the device: caller's contract; it holds
- * whenever r*s*c/groups * 2^15 < 2^31).
+ * The int32 accumulator must not overflow.  A code minus its offset reaches 128 + |offset| in magnitude
+ * (255 at the extreme offsets), so the sum of products of a reduction of depth D = r*s*c/groups is
+ * bounded by D * (128 + |x.offset|) * (128 + |w.offset|); the call is rejected with
+ * GLOWMI_ERR_UNSUPPORTED when that bound exceeds 2^31 - 2^27 or when D > 65535.  The 2^27 left over is
+ * room for |bias| plus the rescaled addend of a chain: contents of device memory the host cannot see,
+ * so keeping them inside it is the caller's contract (an overflow is not detected on the device).
  *   x int8 [n][h][w][c], w int8 [k][r][s][c/groups], bias int32 [k], y int8 [n][oh][ow][k], device.
  */
 glowmi_status glowmi_qconv2d(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
@@ -149,8 +153,9 @@ size_t glowmi_qfc_workspace_bytes(int32_t M, int32_t K, int32_t N);
  *             scale x.scale*w.scale before the single requantize:
  *                 acc += round((addend - addend_q.offset) * Mres),  Mres = addend_q.scale / (x.scale*w.scale)
  *             with Mres evaluated in double and applied as mant * 2^-shift exactly like the output
- *             multiplier (31-bit mantissa, shift in [1, 62] else GLOWMI_ERR_QUANT, ties go up).
- *             The sum must still fit int32 (caller's contract).
+ *             multiplier (31-bit mantissa, ties go up); the shift must lie in [12, 62], i.e. Mres < 2^19,
+ *             so that the term of the largest code difference (255) stays below 2^27
+ *             (GLOWMI_ERR_QUANT otherwise).  The sum must still fit int32 (caller's contract).
  */
 typedef struct glowmi_chain {
   const void* addend;
@@ -238,6 +243,18 @@ glowmi_status glowmi_requant_params(float x_scale, float w_scale, float y_scale,
 /* Host helper: mant/shift of Mres = r_scale / (x_scale * w_scale), the addend rescale of glowmi_chain. */
 glowmi_status glowmi_rescale_params(float r_scale, float x_scale, float w_scale, int32_t* mant,
                                     int32_t* shift);
+
+/*
+ * Tuning knobs for experiments and tests: force a tile variant, or lower the size threshold of a
+ * specialised kernel so that a small test shape reaches it.  name is the knob's name without prefix
+ * (e.g. "F32_TILE", "I8_K3_MIN_BLOCKS"); the same knobs are seeded ONCE, at the library's first use,
+ * from environment variables GLOWMI_<name>.  Every setting computes the same results; only the choice
+ * of kernel changes.  glowmi_tuning_reset() returns every knob to "the planner's own choice" (it does
+ * not re-read the environment).  Not thread-safe against concurrent launches that should see a
+ * consistent setting.  GLOWMI_ERR_UNSUPPORTED for an unknown name.
+ */
+glowmi_status glowmi_tuning_set(const char* name, int32_t value);
+void glowmi_tuning_reset(void);
 
 const char* glowmi_status_string(glowmi_status s);
 /* Message of the last failing call on the calling thread ("" if none). Valid until the next call. */

@@ -205,10 +205,13 @@ void oracle_dequantize(const int8_t *q, int64_t count, float scale, int32_t offs
   for (int64_t i = 0; i < count; ++i) value[i] = ((double)q[i] - (double)offset) * (double)scale;
 }
 
-/* Inverse of the above for test data: nearest code (ties to even), saturated. */
+/* Inverse of the above for test data: nearest code (ties to even), saturated.  A NaN has no code;
+ * it is given the code of the real value zero (a reading: the paper does not define it, and a cast
+ * of NaN to an integer is undefined in C). */
 void oracle_quantize(const double *value, int64_t count, float scale, int32_t offset, int8_t *q) {
   for (int64_t i = 0; i < count; ++i) {
     double t = nearbyint(value[i] / (double)scale) + (double)offset;
+    if (t != t) t = (double)offset;
     if (t < -128.0) t = -128.0;
     if (t > 127.0) t = 127.0;
     q[i] = (int8_t)t;

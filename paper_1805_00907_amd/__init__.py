@@ -37,4 +37,6 @@ from .binding import (  # noqa: F401
     seq_conv2d,
     seq_layers,
     seq_qconv2d,
+    tuning_reset,
+    tuning_set,
 )

@@ -72,6 +72,9 @@ def library() -> ctypes.CDLL:
     L.glowmi_fc.argtypes = [vp, vp, vp, vp, i32, i32, i32, ctypes.c_int, vp, sz, vp]
     L.glowmi_fc_workspace_bytes.argtypes = [i32, i32, i32]
     L.glowmi_fc_workspace_bytes.restype = sz
+    L.glowmi_tuning_set.argtypes = [ctypes.c_char_p, i32]
+    L.glowmi_tuning_reset.argtypes = []
+    L.glowmi_tuning_reset.restype = None
     L.glowmi_qconv2d.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, dp, ctypes.c_int, vp, sz, vp]
     L.glowmi_qconv2d_workspace_bytes.argtypes = [dp]
     L.glowmi_qconv2d_workspace_bytes.restype = sz
@@ -109,18 +112,41 @@ def last_variant() -> str:
     return library().glowmi_last_variant().decode()
 
 
-def _ptr(t) -> Optional[int]:
-    """Device address of a torch tensor (None -> NULL); accepts a raw integer address too."""
+def _ptr(t, dtype: Optional[str] = None, count: Optional[int] = None, what: str = "tensor") -> Optional[int]:
+    """Device address of a torch tensor (None -> NULL); a raw integer address is passed through.
+
+    For a tensor, the facts the C side cannot see are checked here, because a mismatch would become
+    an out-of-bounds access on the device: it must live on a GPU, be contiguous, have the element
+    type `dtype` ("float32", "int8", "int32") and hold at least `count` elements."""
     if t is None:
         return None
     if isinstance(t, int):
         return t
+    if not t.is_cuda:
+        raise ValueError(f"{what}: expected a device tensor, got one on {t.device}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: tensor is not contiguous")
+    if dtype is not None and str(t.dtype) != "torch." + dtype:
+        raise ValueError(f"{what}: expected {dtype}, got {t.dtype}")
+    if count is not None and t.numel() < count:
+        raise ValueError(f"{what}: {t.numel()} elements, the call needs {count}")
     return t.data_ptr()
+
+
+def _conv_counts(desc: ConvDesc) -> Tuple[int, int, int]:
+    """(input, filter, output) element counts of a descriptor; zeros when the library will reject it."""
+    oh, ow = ctypes.c_int32(0), ctypes.c_int32(0)
+    if library().glowmi_conv_out_shape(ctypes.byref(desc), ctypes.byref(oh), ctypes.byref(ow)) != 0:
+        return 0, 0, 0
+    return (desc.n * desc.h * desc.w * desc.c, desc.k * desc.r * desc.s * (desc.c // desc.groups),
+            desc.n * oh.value * ow.value * desc.k)
 
 
 def _ws(workspace) -> Tuple[Optional[int], int]:
     if workspace is None:
         return None, 0
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace: expected a contiguous device tensor")
     return workspace.data_ptr(), workspace.numel() * workspace.element_size()
 
 
@@ -146,8 +172,10 @@ def conv2d_workspace_bytes(desc: ConvDesc) -> int:
 
 def conv2d(x, w, bias, y, desc: ConvDesc, act: int = ACT_NONE, workspace=None, stream=None) -> None:
     wp, wb = _ws(workspace)
-    _check(library().glowmi_conv2d(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), ctypes.byref(desc), act, wp, wb,
-                                   _stream(stream)))
+    nx, nw, ny = _conv_counts(desc)
+    _check(library().glowmi_conv2d(_ptr(x, "float32", nx, "x"), _ptr(w, "float32", nw, "w"),
+                                   _ptr(bias, "float32", desc.k, "bias"), _ptr(y, "float32", ny, "y"),
+                                   ctypes.byref(desc), act, wp, wb, _stream(stream)))
 
 
 def fc_workspace_bytes(M: int, K: int, N: int) -> int:
@@ -156,7 +184,19 @@ def fc_workspace_bytes(M: int, K: int, N: int) -> int:
 
 def fc(a, w, bias, y, M: int, K: int, N: int, act: int = ACT_NONE, workspace=None, stream=None) -> None:
     wp, wb = _ws(workspace)
-    _check(library().glowmi_fc(_ptr(a), _ptr(w), _ptr(bias), _ptr(y), M, K, N, act, wp, wb, _stream(stream)))
+    _check(library().glowmi_fc(_ptr(a, "float32", M * K, "a"), _ptr(w, "float32", K * N, "w"),
+                               _ptr(bias, "float32", N, "bias"), _ptr(y, "float32", M * N, "y"), M, K, N, act, wp,
+                               wb, _stream(stream)))
+
+
+def tuning_set(name: str, value: int) -> None:
+    """Set a tuning knob (experiments and tests), e.g. tuning_set("F32_TILE", 2)."""
+    _check(library().glowmi_tuning_set(name.encode(), int(value)))
+
+
+def tuning_reset() -> None:
+    """Every knob back to the planner's own choice."""
+    library().glowmi_tuning_reset()
 
 
 def qconv2d_workspace_bytes(desc: ConvDesc) -> int:
@@ -166,29 +206,31 @@ def qconv2d_workspace_bytes(desc: ConvDesc) -> int:
 def qconv2d(x, xq: QParam, w, wq: QParam, bias, y, yq: QParam, desc: ConvDesc, act: int = ACT_NONE,
             workspace=None, stream=None) -> None:
     wp, wb = _ws(workspace)
-    _check(library().glowmi_qconv2d(_ptr(x), xq, _ptr(w), wq, _ptr(bias), _ptr(y), yq, ctypes.byref(desc),
-                                    act, wp, wb, _stream(stream)))
-
-
-def _chain(addend, addend_q: Optional[QParam], act: int) -> Chain:
-    return Chain(_ptr(addend), addend_q if addend_q is not None else QParam(1.0, 0), act)
+    nx, nw, ny = _conv_counts(desc)
+    _check(library().glowmi_qconv2d(_ptr(x, "int8", nx, "x"), xq, _ptr(w, "int8", nw, "w"), wq,
+                                    _ptr(bias, "int32", desc.k, "bias"), _ptr(y, "int8", ny, "y"), yq,
+                                    ctypes.byref(desc), act, wp, wb, _stream(stream)))
 
 
 def conv2d_chain(x, w, bias, y, desc: ConvDesc, addend=None, act: int = ACT_NONE, workspace=None,
                  stream=None) -> None:
     """y = act(conv + bias + addend); addend is a float tensor of y's shape (may be y) or None."""
     wp, wb = _ws(workspace)
-    chain = _chain(addend, None, act)
-    _check(library().glowmi_conv2d_chain(_ptr(x), _ptr(w), _ptr(bias), _ptr(y), ctypes.byref(desc),
-                                         ctypes.byref(chain), wp, wb, _stream(stream)))
+    nx, nw, ny = _conv_counts(desc)
+    chain = Chain(_ptr(addend, "float32", ny, "addend"), QParam(1.0, 0), act)
+    _check(library().glowmi_conv2d_chain(_ptr(x, "float32", nx, "x"), _ptr(w, "float32", nw, "w"),
+                                         _ptr(bias, "float32", desc.k, "bias"), _ptr(y, "float32", ny, "y"),
+                                         ctypes.byref(desc), ctypes.byref(chain), wp, wb, _stream(stream)))
 
 
 def qconv2d_chain(x, xq: QParam, w, wq: QParam, bias, y, yq: QParam, desc: ConvDesc, addend=None,
                   addend_q: Optional[QParam] = None, act: int = ACT_NONE, workspace=None, stream=None) -> None:
     """Quantized form: addend is an int8 tensor of y's shape with scale/offset addend_q."""
     wp, wb = _ws(workspace)
-    chain = _chain(addend, addend_q, act)
-    _check(library().glowmi_qconv2d_chain(_ptr(x), xq, _ptr(w), wq, _ptr(bias), _ptr(y), yq,
+    nx, nw, ny = _conv_counts(desc)
+    chain = Chain(_ptr(addend, "int8", ny, "addend"), addend_q if addend_q is not None else QParam(1.0, 0), act)
+    _check(library().glowmi_qconv2d_chain(_ptr(x, "int8", nx, "x"), xq, _ptr(w, "int8", nw, "w"), wq,
+                                          _ptr(bias, "int32", desc.k, "bias"), _ptr(y, "int8", ny, "y"), yq,
                                           ctypes.byref(desc), ctypes.byref(chain), wp, wb, _stream(stream)))
 
 
@@ -199,8 +241,9 @@ def qfc_workspace_bytes(M: int, K: int, N: int) -> int:
 def qfc(a, aq: QParam, w, wq: QParam, bias, y, yq: QParam, M: int, K: int, N: int, act: int = ACT_NONE,
         workspace=None, stream=None) -> None:
     wp, wb = _ws(workspace)
-    _check(library().glowmi_qfc(_ptr(a), aq, _ptr(w), wq, _ptr(bias), _ptr(y), yq, M, K, N, act, wp, wb,
-                                _stream(stream)))
+    _check(library().glowmi_qfc(_ptr(a, "int8", M * K, "a"), aq, _ptr(w, "int8", K * N, "w"), wq,
+                                _ptr(bias, "int32", N, "bias"), _ptr(y, "int8", M * N, "y"), yq, M, K, N, act, wp,
+                                wb, _stream(stream)))
 
 
 def requant_params(x_scale: float, w_scale: float, y_scale: float) -> Tuple[int, int]:
@@ -218,18 +261,19 @@ def rescale_params(r_scale: float, x_scale: float, w_scale: float) -> Tuple[int,
 def quantize(x, q, qp: QParam, count: Optional[int] = None, stream=None) -> None:
     """float32 device tensor x -> int8 device tensor q with scale/offset qp."""
     n = x.numel() if count is None else count
-    _check(library().glowmi_quantize(_ptr(x), _ptr(q), n, qp, _stream(stream)))
+    _check(library().glowmi_quantize(_ptr(x, "float32", n, "x"), _ptr(q, "int8", n, "q"), n, qp, _stream(stream)))
 
 
 def dequantize(q, x, qp: QParam, count: Optional[int] = None, stream=None) -> None:
     n = q.numel() if count is None else count
-    _check(library().glowmi_dequantize(_ptr(q), _ptr(x), n, qp, _stream(stream)))
+    _check(library().glowmi_dequantize(_ptr(q, "int8", n, "q"), _ptr(x, "float32", n, "x"), n, qp, _stream(stream)))
 
 
 def rescale(q_in, from_q: QParam, q_out, to_q: QParam, count: Optional[int] = None, stream=None) -> None:
     """The same real values on another scale/offset; q_out may be q_in."""
     n = q_in.numel() if count is None else count
-    _check(library().glowmi_rescale(_ptr(q_in), from_q, _ptr(q_out), to_q, n, _stream(stream)))
+    _check(library().glowmi_rescale(_ptr(q_in, "int8", n, "q_in"), from_q, _ptr(q_out, "int8", n, "q_out"), to_q, n,
+                                    _stream(stream)))
 
 
 def fold_batchnorm(w, bias, gamma, beta, mean, var, eps: float):
@@ -251,8 +295,12 @@ def seq_layers(layers) -> "ctypes.Array":
     arr = (SeqLayer * len(layers))()
     for i, l in enumerate(layers):
         desc, w, bias, act, add_input = l[:5]
-        wq, yq = (l[5], l[6]) if len(l) > 5 else (QParam(1.0, 0), QParam(1.0, 0))
-        arr[i] = SeqLayer(desc, _ptr(w), _ptr(bias), wq, yq, act, 1 if add_input else 0)
+        quantized = len(l) > 5
+        wq, yq = (l[5], l[6]) if quantized else (QParam(1.0, 0), QParam(1.0, 0))
+        _, nw, _ = _conv_counts(desc)
+        arr[i] = SeqLayer(desc, _ptr(w, "int8" if quantized else "float32", nw, f"layer {i} w"),
+                          _ptr(bias, "int32" if quantized else "float32", desc.k, f"layer {i} bias"), wq, yq, act,
+                          1 if add_input else 0)
     return arr
 
 
@@ -262,13 +310,19 @@ def seq_arena_bytes(arr, quantized: bool) -> int:
 
 def seq_conv2d(x, arr, y, arena, stream=None) -> None:
     ap, ab = _ws(arena)
-    st = library().glowmi_seq_conv2d(_ptr(x), arr, len(arr), _ptr(y), ap, ab, _stream(stream))
+    nx, _, _ = _conv_counts(arr[0].desc)
+    _, _, ny = _conv_counts(arr[len(arr) - 1].desc)
+    st = library().glowmi_seq_conv2d(_ptr(x, "float32", nx, "x"), arr, len(arr), _ptr(y, "float32", ny, "y"), ap, ab,
+                                     _stream(stream))
     if st != 0:
         raise GlowmiError(st, library().glowmi_last_error().decode() or "sequence rejected")
 
 
 def seq_qconv2d(x, xq: QParam, arr, y, arena, stream=None) -> None:
     ap, ab = _ws(arena)
-    st = library().glowmi_seq_qconv2d(_ptr(x), xq, arr, len(arr), _ptr(y), ap, ab, _stream(stream))
+    nx, _, _ = _conv_counts(arr[0].desc)
+    _, _, ny = _conv_counts(arr[len(arr) - 1].desc)
+    st = library().glowmi_seq_qconv2d(_ptr(x, "int8", nx, "x"), xq, arr, len(arr), _ptr(y, "int8", ny, "y"), ap, ab,
+                                      _stream(stream))
     if st != 0:
         raise GlowmiError(st, library().glowmi_last_error().decode() or "sequence rejected")

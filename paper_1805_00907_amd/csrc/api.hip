@@ -2,18 +2,26 @@
 // operators lives here except the host-side derivation of the integer requantization multiplier.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/glowmi.h"
+#include "api_internal.h"
 #include "igemm.h"
 
 namespace {
 
 thread_local char g_error[256] = "";
 thread_local const char* g_variant = "";
+
+}  // namespace
+
+namespace glowmi {
 
 glowmi_status fail(glowmi_status s, const char* fmt, ...) {
   va_list ap;
@@ -23,12 +31,59 @@ glowmi_status fail(glowmi_status s, const char* fmt, ...) {
   return s;
 }
 
+// ---- tuning knobs: seeded once from the environment, changed only through glowmi_tuning_set ----
+namespace {
+const char* const kKnobNames[KNOB_COUNT] = {
+    "F32_TILE", "F32_SPLIT", "F32_PW_MIN_ITEMS", "F32_SMALL_MAX_TILES", "F32_SMALL_NO_SPLIT",
+    "F32_SMALL_SPLIT_MAX_TILES", "F32_SMALL_MIN_WGS", "F32_FC_SMALL_OFF", "SMALLC_TH",
+    "I8_TILE", "I8_WIDE_SPLIT", "I8_WIDE_NBUF", "SMALLC_I8_WGS", "I8_PW_MIN_ITEMS",
+    "I8_FC_SMALL_MAX_M", "I8_K3_MIN_BLOCKS", "I8_K3_WAVES", "I8_K3_GATHER", "I8_DEEP_OFF",
+};
+std::atomic<int> g_knobs[KNOB_COUNT];
+std::once_flag g_knobs_once;
+
+void seed_knobs_from_environment() {
+  for (int i = 0; i < KNOB_COUNT; ++i) {
+    char name[64];
+    snprintf(name, sizeof(name), "GLOWMI_%s", kKnobNames[i]);
+    const char* env = getenv(name);
+    int v = kKnobUnset;
+    if (env && *env) {
+      char* end = nullptr;
+      const long parsed = strtol(env, &end, 10);
+      if (end != env && parsed > -(1L << 30) && parsed < (1L << 30)) v = (int)parsed;
+    }
+    g_knobs[i].store(v, std::memory_order_relaxed);
+  }
+}
+}  // namespace
+
+int knob(Knob k) {
+  std::call_once(g_knobs_once, seed_knobs_from_environment);
+  return g_knobs[k].load(std::memory_order_relaxed);
+}
+
+int num_compute_units() {
+  static const int n = []() {
+    int dev = 0, cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return cu;
+  }();
+  return n;
+}
+
+}  // namespace glowmi
+
+namespace {
+using glowmi::fail;
+
 bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 constexpr long long kMaxElems = (1LL << 31) - 1;
 constexpr long long kMaxOperandBytes = (1LL << 32) - 64;   // inputs are read through 32-bit buffer offsets
 constexpr int kMaxExtent = 1 << 20;       // spatial / filter extents; keeps row arithmetic in int32
-constexpr int kMaxQuantDepth = 65535;     // reduction depth for which an int32 accumulator cannot overflow
+constexpr int kMaxQuantDepth = 65535;     // deepest reduction the quantized kernels are built and tested for
 
 struct Geometry {
   int oh, ow;
@@ -151,6 +206,15 @@ bool workspace_usable(const void* ws, size_t have, size_t need) {
   return ws != nullptr && need > 0 && have >= need && aligned(ws, 16);
 }
 
+// Largest magnitude the sum of products of a reduction of depth Kgemm can reach: a code minus its
+// offset lies in [-128 - off, 127 - off], so |x - x_off| <= 128 + |x_off| and likewise for the filter
+// (Section 4.1 tensor type: codes and offsets in [-128, 127]).  The call is accepted only when that
+// bound leaves kAccHeadroom below 2^31 for the bias and the rescaled addend.
+constexpr long long kAccHeadroom = 1LL << 27;
+// Smallest shift accepted for the multiplier of a quantized addend: a code difference reaches 255 and
+// mant < 2^31, so 255 * mant * 2^-shift < 2^27 needs shift >= 12.
+constexpr int kMinAddendShift = 12;
+
 glowmi_status quant_setup(glowmi::Problem& p, glowmi_qparam xq, glowmi_qparam wq, glowmi_qparam yq,
                           glowmi_act act) {
   if (xq.offset < -128 || xq.offset > 127 || wq.offset < -128 || wq.offset > 127 || yq.offset < -128 ||
@@ -161,8 +225,14 @@ glowmi_status quant_setup(glowmi::Problem& p, glowmi_qparam xq, glowmi_qparam wq
   glowmi_status st = glowmi_requant_params(xq.scale, wq.scale, yq.scale, &mant, &shift);
   if (st != GLOWMI_OK) return st;
   if (p.Kgemm > kMaxQuantDepth)
-    return fail(GLOWMI_ERR_UNSUPPORTED, "reduction depth %d exceeds %d: int32 accumulator could overflow",
-                p.Kgemm, kMaxQuantDepth);
+    return fail(GLOWMI_ERR_UNSUPPORTED, "reduction depth %d exceeds %d", p.Kgemm, kMaxQuantDepth);
+  const long long xmax = 128 + (xq.offset < 0 ? -xq.offset : xq.offset);
+  const long long wmax = 128 + (wq.offset < 0 ? -wq.offset : wq.offset);
+  const long long bound = (long long)p.Kgemm * xmax * wmax;
+  if (bound > (1LL << 31) - kAccHeadroom)
+    return fail(GLOWMI_ERR_UNSUPPORTED,
+                "reduction depth %d with offsets x %d, w %d: the sum of products can reach %lld, too close to 2^31 "
+                "for an int32 accumulator", p.Kgemm, xq.offset, wq.offset, bound);
   p.x_off = xq.offset; p.w_off = wq.offset; p.y_off = yq.offset;
   p.mant = mant; p.shift = shift;
   p.lo = (act == GLOWMI_ACT_RELU && yq.offset > -128) ? yq.offset : -128;
@@ -180,7 +250,102 @@ size_t split_bytes(const glowmi::Plan& pl, const glowmi::Problem& p) {
   return pl.split_k > 1 ? (size_t)pl.split_k * (size_t)p.M * (size_t)p.k * 4u : 0u;
 }
 
+// Plan once per call: with the split the planner wants when the workspace can hold its partial sums,
+// without a split otherwise.  Sets p.partial accordingly.
+template <typename PlanFn>
+glowmi::Plan plan_with_workspace(glowmi::Problem& p, PlanFn plan_fn, void* workspace, size_t workspace_bytes) {
+  glowmi::Plan plan = plan_fn(p, true);
+  const size_t need = split_bytes(plan, p);
+  p.partial = nullptr;
+  if (need > 0) {
+    if (workspace_usable(workspace, workspace_bytes, need)) p.partial = workspace;
+    else plan = plan_fn(p, false);
+  }
+  return plan;
+}
+
+glowmi_status setup_fc_f32(const float* a, const float* w, const float* bias, float* y, int32_t M, int32_t K,
+                           int32_t N, glowmi_act act, glowmi::Problem& p) {
+  glowmi_status st = check_fc(M, K, N);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_ptrs(a, w, bias, y)) != GLOWMI_OK) return st;
+  if ((st = check_act(act)) != GLOWMI_OK) return st;
+  fill_fc(p, M, K, N);
+  if ((st = set_operand_bytes(p, (long long)M * K, (long long)K * N, 4)) != GLOWMI_OK) return st;
+  p.x = a; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  return GLOWMI_OK;
+}
+
 }  // namespace
+
+namespace glowmi {
+
+glowmi_status prepare_conv2d_chain(const float* x, const float* w, const float* bias, float* y,
+                                   const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
+                                   size_t workspace_bytes, PreparedCall* out) {
+  if (!chain) return fail(GLOWMI_ERR_NULL, "chain must not be NULL");
+  const glowmi_act act = chain->act;
+  Geometry geo;
+  glowmi_status st = check_desc(d, &geo);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
+  if ((st = check_act(act)) != GLOWMI_OK) return st;
+  if ((st = check_addend(chain->addend, y, (size_t)geo.y_elems * 4u)) != GLOWMI_OK) return st;
+  Problem& p = out->p;
+  fill_conv(p, d, geo);
+  if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 4)) != GLOWMI_OK) return st;
+  p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  p.addend = chain->addend;
+  out->plan = plan_with_workspace(p, plan_f32, workspace, workspace_bytes);
+  out->quantized = false;
+  return GLOWMI_OK;
+}
+
+glowmi_status prepare_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
+                                    const int32_t* bias, int8_t* y, glowmi_qparam yq, const glowmi_conv_desc* d,
+                                    const glowmi_chain* chain, void* workspace, size_t workspace_bytes,
+                                    PreparedCall* out) {
+  if (!chain) return fail(GLOWMI_ERR_NULL, "chain must not be NULL");
+  const glowmi_act act = chain->act;
+  Geometry geo;
+  glowmi_status st = check_desc(d, &geo);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
+  if ((st = check_act(act)) != GLOWMI_OK) return st;
+  if ((st = check_addend(chain->addend, y, (size_t)geo.y_elems)) != GLOWMI_OK) return st;
+  Problem& p = out->p;
+  fill_conv(p, d, geo);
+  if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 1)) != GLOWMI_OK) return st;
+  if ((st = quant_setup(p, xq, wq, yq, act)) != GLOWMI_OK) return st;
+  p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  if (chain->addend) {
+    if (chain->addend_q.offset < -128 || chain->addend_q.offset > 127)
+      return fail(GLOWMI_ERR_QUANT, "addend offset %d outside [-128, 127]", chain->addend_q.offset);
+    int32_t r_mant = 0, r_shift = 0;
+    if ((st = glowmi_rescale_params(chain->addend_q.scale, xq.scale, wq.scale, &r_mant, &r_shift)) != GLOWMI_OK)
+      return st;
+    // the rescaled term must fit the int32 accumulator with room to spare
+    if (r_shift < kMinAddendShift)
+      return fail(GLOWMI_ERR_QUANT,
+                  "addend scale %g is more than 2^%d times the accumulator's scale %g: the rescaled addend "
+                  "would not fit the int32 accumulator", (double)chain->addend_q.scale, 31 - kMinAddendShift,
+                  (double)xq.scale * (double)wq.scale);
+    p.addend = chain->addend;
+    p.r_off = chain->addend_q.offset; p.r_mant = r_mant; p.r_shift = r_shift;
+  }
+  out->plan = plan_with_workspace(p, plan_i8, workspace, workspace_bytes);
+  out->quantized = true;
+  return GLOWMI_OK;
+}
+
+glowmi_status run_prepared(const PreparedCall& call, hipStream_t stream) {
+  const char* variant = "";
+  const hipError_t e = call.quantized ? launch_i8(call.p, call.plan, stream, &variant)
+                                      : launch_f32(call.p, call.plan, stream, &variant);
+  return finish(e, variant);
+}
+
+}  // namespace glowmi
 
 extern "C" {
 
@@ -215,23 +380,10 @@ glowmi_status glowmi_conv2d(const float* x, const float* w, const float* bias, f
 glowmi_status glowmi_conv2d_chain(const float* x, const float* w, const float* bias, float* y,
                                   const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
                                   size_t workspace_bytes, hipStream_t stream) {
-  if (!chain) return fail(GLOWMI_ERR_NULL, "chain must not be NULL");
-  const glowmi_act act = chain->act;
-  Geometry geo;
-  glowmi_status st = check_desc(d, &geo);
+  glowmi::PreparedCall call;
+  glowmi_status st = glowmi::prepare_conv2d_chain(x, w, bias, y, d, chain, workspace, workspace_bytes, &call);
   if (st != GLOWMI_OK) return st;
-  if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
-  if ((st = check_act(act)) != GLOWMI_OK) return st;
-  if ((st = check_addend(chain->addend, y, (size_t)geo.y_elems * 4u)) != GLOWMI_OK) return st;
-  glowmi::Problem p;
-  fill_conv(p, d, geo);
-  if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 4)) != GLOWMI_OK) return st;
-  p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
-  p.addend = chain->addend;
-  const size_t need = split_bytes(glowmi::plan_f32(p, true), p);
-  p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
-  const char* variant = "";
-  return finish(glowmi::launch_f32(p, stream, &variant), variant);
+  return glowmi::run_prepared(call, stream);
 }
 
 size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N) {
@@ -244,18 +396,12 @@ size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N) {
 glowmi_status glowmi_fc(const float* a, const float* w, const float* bias, float* y, int32_t M,
                         int32_t K, int32_t N, glowmi_act act, void* workspace,
                         size_t workspace_bytes, hipStream_t stream) {
-  glowmi_status st = check_fc(M, K, N);
-  if (st != GLOWMI_OK) return st;
-  if ((st = check_ptrs(a, w, bias, y)) != GLOWMI_OK) return st;
-  if ((st = check_act(act)) != GLOWMI_OK) return st;
   glowmi::Problem p;
-  fill_fc(p, M, K, N);
-  if ((st = set_operand_bytes(p, (long long)M * K, (long long)K * N, 4)) != GLOWMI_OK) return st;
-  p.x = a; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
-  const size_t need = split_bytes(glowmi::plan_f32(p, true), p);
-  p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
+  glowmi_status st = setup_fc_f32(a, w, bias, y, M, K, N, act, p);
+  if (st != GLOWMI_OK) return st;
+  const glowmi::Plan plan = plan_with_workspace(p, glowmi::plan_f32, workspace, workspace_bytes);
   const char* variant = "";
-  return finish(glowmi::launch_f32(p, stream, &variant), variant);
+  return finish(glowmi::launch_f32(p, plan, stream, &variant), variant);
 }
 
 size_t glowmi_qconv2d_workspace_bytes(const glowmi_conv_desc* d) {
@@ -282,32 +428,11 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
                                    const int32_t* bias, int8_t* y, glowmi_qparam yq,
                                    const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
                                    size_t workspace_bytes, hipStream_t stream) {
-  if (!chain) return fail(GLOWMI_ERR_NULL, "chain must not be NULL");
-  const glowmi_act act = chain->act;
-  Geometry geo;
-  glowmi_status st = check_desc(d, &geo);
+  glowmi::PreparedCall call;
+  glowmi_status st =
+      glowmi::prepare_qconv2d_chain(x, xq, w, wq, bias, y, yq, d, chain, workspace, workspace_bytes, &call);
   if (st != GLOWMI_OK) return st;
-  if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
-  if ((st = check_act(act)) != GLOWMI_OK) return st;
-  if ((st = check_addend(chain->addend, y, (size_t)geo.y_elems)) != GLOWMI_OK) return st;
-  glowmi::Problem p;
-  fill_conv(p, d, geo);
-  if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 1)) != GLOWMI_OK) return st;
-  if ((st = quant_setup(p, xq, wq, yq, act)) != GLOWMI_OK) return st;
-  p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
-  if (chain->addend) {
-    if (chain->addend_q.offset < -128 || chain->addend_q.offset > 127)
-      return fail(GLOWMI_ERR_QUANT, "addend offset %d outside [-128, 127]", chain->addend_q.offset);
-    int32_t r_mant = 0, r_shift = 0;
-    if ((st = glowmi_rescale_params(chain->addend_q.scale, xq.scale, wq.scale, &r_mant, &r_shift)) != GLOWMI_OK)
-      return st;
-    p.addend = chain->addend;
-    p.r_off = chain->addend_q.offset; p.r_mant = r_mant; p.r_shift = r_shift;
-  }
-  const size_t need = split_bytes(glowmi::plan_i8(p, true), p);
-  p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
-  const char* variant = "";
-  return finish(glowmi::launch_i8(p, stream, &variant), variant);
+  return glowmi::run_prepared(call, stream);
 }
 
 size_t glowmi_qfc_workspace_bytes(int32_t M, int32_t K, int32_t N) {
@@ -330,10 +455,25 @@ glowmi_status glowmi_qfc(const int8_t* a, glowmi_qparam aq, const int8_t* w, glo
   if ((st = set_operand_bytes(p, (long long)M * K, (long long)K * N, 1)) != GLOWMI_OK) return st;
   if ((st = quant_setup(p, aq, wq, yq, act)) != GLOWMI_OK) return st;
   p.x = a; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
-  const size_t need = split_bytes(glowmi::plan_i8(p, true), p);
-  p.partial = workspace_usable(workspace, workspace_bytes, need) ? workspace : nullptr;
+  const glowmi::Plan plan = plan_with_workspace(p, glowmi::plan_i8, workspace, workspace_bytes);
   const char* variant = "";
-  return finish(glowmi::launch_i8(p, stream, &variant), variant);
+  return finish(glowmi::launch_i8(p, plan, stream, &variant), variant);
+}
+
+glowmi_status glowmi_tuning_set(const char* name, int32_t value) {
+  if (!name) return fail(GLOWMI_ERR_NULL, "knob name is NULL");
+  glowmi::knob(glowmi::KNOB_F32_TILE);                    // make sure the environment has been read first
+  for (int i = 0; i < glowmi::KNOB_COUNT; ++i)
+    if (std::strcmp(name, glowmi::kKnobNames[i]) == 0) {
+      glowmi::g_knobs[i].store(value, std::memory_order_relaxed);
+      return GLOWMI_OK;
+    }
+  return fail(GLOWMI_ERR_UNSUPPORTED, "unknown tuning knob \"%s\"", name);
+}
+
+void glowmi_tuning_reset(void) {
+  glowmi::knob(glowmi::KNOB_F32_TILE);
+  for (int i = 0; i < glowmi::KNOB_COUNT; ++i) glowmi::g_knobs[i].store(glowmi::kKnobUnset, std::memory_order_relaxed);
 }
 
 static glowmi_status check_elementwise(const void* in, const void* out, size_t count, size_t in_elem,

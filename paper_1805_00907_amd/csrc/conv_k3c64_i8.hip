@@ -508,25 +508,19 @@ __global__ __launch_bounds__(WAVES * 64, 1) void conv_k3c64_i8_tile_kernel(const
 }
 
 int k3_min_blocks() {
-  if (const char* env = getenv("GLOWMI_I8_K3_MIN_BLOCKS")) return atoi(env);   // experiments and tests
-  return 768;   // measured on 56 x 56 maps: batch 8 (784 blocks) 8.0 -> 7.5 us, batch 4 and below no faster than the tiled kernel
+  return knob_or(KNOB_I8_K3_MIN_BLOCKS, 768);   // measured on 56 x 56 maps: batch 8 (784 blocks) 8.0 -> 7.5 us, batch 4 and below no faster than the tiled kernel
 }
 
 template <int WAVES, bool ADD>
 hipError_t launch_k3(const Problem& p, hipStream_t stream) {
   auto kern = conv_k3c64_i8_kernel<WAVES, ADD>;
   constexpr int lds = k3_lds_bytes<WAVES>();
-  static int num_cu = 0;          // benign if two threads race: both compute the same value
-  if (num_cu == 0) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    int dev = 0, n = 0;
-    e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
-    num_cu = n < 1 ? 1 : n;
-  }
+  // once per instantiation; initialisation of a function-local static is thread-safe
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (attr_status != hipSuccess) return attr_status;
+  const int num_cu = num_compute_units();
+  if (num_cu < 1) return hipErrorInvalidDevice;
   const int slices = (p.k + K3_BN - 1) / K3_BN;
   const int row_blocks = (p.M + 31) / 32;
   long long wgs = num_cu / slices;                                    // persistent workgroups per slice
@@ -542,17 +536,12 @@ template <int WAVES, bool ADD>
 hipError_t launch_t2(const Problem& p, hipStream_t stream) {
   auto kern = conv_k3c64_i8_tile_kernel<WAVES, ADD>;
   constexpr int lds = t2_lds_bytes<WAVES>();
-  static int num_cu = 0;          // benign if two threads race: both compute the same value
-  if (num_cu == 0) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    int dev = 0, n = 0;
-    e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
-    num_cu = n < 1 ? 1 : n;
-  }
+  // once per instantiation; initialisation of a function-local static is thread-safe
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (attr_status != hipSuccess) return attr_status;
+  const int num_cu = num_compute_units();
+  if (num_cu < 1) return hipErrorInvalidDevice;
   const int slices = (p.k + K3_BN - 1) / K3_BN;
   const int blocks_y = (p.oh + T2_BH - 1) / T2_BH, blocks_x = (p.ow + T2_BW - 1) / T2_BW;
   const long long items = (long long)p.n * blocks_y * blocks_x;
@@ -578,11 +567,11 @@ bool k3c64_i8_applicable(const Problem& p) {
 
 hipError_t launch_k3c64_i8(const Problem& p, hipStream_t stream, const char** variant) {
   int waves = 16;     // four wavefronts per SIMD hide the chunk hand-over better than two (measured)
-  if (const char* env = getenv("GLOWMI_I8_K3_WAVES")) waves = atoi(env);   // experiments and tests
+  waves = knob_or(KNOB_I8_K3_WAVES, waves);                                // experiments and tests
   // stride 1: the form that stages each block's input patch once; other strides gather per filter row
   const long long t2_items = (long long)p.n * ((p.oh + T2_BH - 1) / T2_BH) * ((p.ow + T2_BW - 1) / T2_BW);
   bool tiled = p.stride_h == 1 && p.stride_w == 1 && t2_items < (1LL << 30);
-  if (getenv("GLOWMI_I8_K3_GATHER")) tiled = false;                        // experiments and tests
+  if (knob_or(KNOB_I8_K3_GATHER, 0) != 0) tiled = false;                   // experiments and tests
   static thread_local char name[48];
   snprintf(name, sizeof(name), "conv_k3c64_i8_w%d%s%s", waves == 8 ? 8 : 16, tiled ? "_2d" : "", p.addend ? "_add" : "");
   *variant = name;

@@ -261,17 +261,12 @@ template <int K, bool CONTIGUOUS, bool ADD>
 hipError_t launch_pwq(const Problem& p, hipStream_t stream) {
   using G = PwQ<K>;
   auto kern = conv_pw_i8_kernel<K, CONTIGUOUS, ADD>;
-  static int num_cu = 0;          // benign if two threads race: both compute the same value
-  if (num_cu == 0) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes);
-    if (e != hipSuccess) return e;
-    int dev = 0, n = 0;
-    e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
-    num_cu = n < 1 ? 1 : n;
-  }
+  // once per instantiation; initialisation of a function-local static is thread-safe
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes);
+  if (attr_status != hipSuccess) return attr_status;
+  const int num_cu = num_compute_units();
+  if (num_cu < 1) return hipErrorInvalidDevice;
   const int slices = (p.k + G::BN - 1) / G::BN;
   const int row_blocks = (p.M + 31) / 32;
   const int groups_last = (p.k - (slices - 1) * G::BN + 63) / 64;      // 64-channel groups of the last slice
@@ -288,8 +283,7 @@ hipError_t launch_pwq(const Problem& p, hipStream_t stream) {
 }
 
 int pwq_min_items() {
-  if (const char* env = getenv("GLOWMI_I8_PW_MIN_ITEMS")) return atoi(env);   // experiments
-  return 1024;
+  return knob_or(KNOB_I8_PW_MIN_ITEMS, 1024);   // the knob: experiments and tests
 }
 
 }  // namespace

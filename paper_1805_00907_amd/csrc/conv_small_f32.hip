@@ -125,7 +125,7 @@ __global__ __launch_bounds__(CS_THREADS, 1) void conv_small_f32_kernel(const Pro
       *reinterpret_cast<v4f*>(P + (size_t)m * p.k + c0) = v;
       continue;
     }
-    if (bias) v += *reinterpret_cast<const v4f*>(bias + c0);
+    if (bias) v += v4f{bias[c0], bias[c0 + 1], bias[c0 + 2], bias[c0 + 3]};   // bias is only 4-byte aligned
     if (p.act == 1) {
 #pragma unroll
       for (int t = 0; t < 4; ++t) v[t] = fmaxf(v[t], 0.f);
@@ -135,8 +135,9 @@ __global__ __launch_bounds__(CS_THREADS, 1) void conv_small_f32_kernel(const Pro
 }
 
 int cs_max_tiles() {
-  if (const char* env = getenv("GLOWMI_F32_SMALL_MAX_TILES")) return atoi(env);   // experiments and tests
-  return 512;     // measured: 196 tiles 11.0 -> 5.5 us and 12.9 -> 8.3 us, 392 tiles 12.4 -> 8.2 us, 784 tiles 27.0 -> 26.2 us
+  // the knob: experiments and tests
+  return knob_or(KNOB_F32_SMALL_MAX_TILES, 512);
+  // measured: 196 tiles 11.0 -> 5.5 us and 12.9 -> 8.3 us, 392 tiles 12.4 -> 8.2 us, 784 tiles 27.0 -> 26.2 us
 }
 
 template <int G>
@@ -169,7 +170,7 @@ bool conv_small_f32_applicable(const Problem& p) {
 // number of slices, 0 if the layer is not of that kind.
 int conv_small_f32_splits(const Problem& p) {
   if (!shape_ok(p) || p.Kgemm <= 8 * CS_WAVES * CS_MAXG) return 0;
-  if (getenv("GLOWMI_F32_SMALL_NO_SPLIT")) return 0;          // experiments
+  if (knob_or(KNOB_F32_SMALL_NO_SPLIT, 0) != 0) return 0;     // experiments
   const long long tiles = (long long)((p.M + 31) / 32) * ((p.k + 31) / 32);
   const int groups_total = p.Kgemm / 8;
   const int per_split = CS_WAVES * 9;
@@ -177,8 +178,8 @@ int conv_small_f32_splits(const Problem& p) {
   // enough workgroups to pull the filter through many CUs at once, few enough that the partial sums
   // (splits x M x k floats, written and read once) stay small next to the filter itself
   int min_wgs = 64, max_tiles = 128;
-  if (const char* env = getenv("GLOWMI_F32_SMALL_SPLIT_MAX_TILES")) max_tiles = atoi(env);   // experiments
-  if (const char* env = getenv("GLOWMI_F32_SMALL_MIN_WGS")) min_wgs = atoi(env);   // experiments and tests
+  max_tiles = knob_or(KNOB_F32_SMALL_SPLIT_MAX_TILES, max_tiles);   // experiments
+  min_wgs = knob_or(KNOB_F32_SMALL_MIN_WGS, min_wgs);               // experiments and tests
   // (measured: 3x3 512->512 on 7x7 at batch 1, 256 workgroups: 16.2 -> 10.6 us; 3x3 128->128 on 28x28, 200:
   // 13.6 -> 10.4 us; 1x1 1024->256 on 14x14, 112: 11.1 -> 10.1 us; 3x3 512->512 on 7x7 at batch 4, 896: 27.7 -> 29.3 us)
   if (tiles > max_tiles || tiles * splits < min_wgs || tiles * splits > 512 || splits > 64) return 0;

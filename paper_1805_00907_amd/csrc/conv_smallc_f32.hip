@@ -230,20 +230,23 @@ template <int R, int S, int C, int STRIDE, int TH>
 hipError_t launch_smallc(const Problem& p, hipStream_t stream) {
   using G = SmallC<R, S, C, STRIDE, TH>;
   auto kern = conv_smallc_f32_kernel<R, S, C, STRIDE, TH>;
-  static int wg_per_cu = 0, num_cu = 0;     // benign if two threads race: both compute the same values
-  if (wg_per_cu == 0) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes);
-    if (e != hipSuccess) return e;
-    int occ = 0, dev = 0, n = 0;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void*>(kern), SC_THREADS,
-                                                     G::lds_bytes);
-    if (e == hipSuccess) e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
-    num_cu = n < 1 ? 1 : n;
-    wg_per_cu = occ < 1 ? 1 : occ;
-  }
+  // once per instantiation; initialisation of a function-local static is thread-safe
+  struct Setup { hipError_t status; int wg_per_cu; };
+  static const Setup setup = [&]() {
+    Setup s{hipSuccess, 1};
+    s.status = hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   G::lds_bytes);
+    int occ = 0;
+    if (s.status == hipSuccess)
+      s.status = hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, reinterpret_cast<const void*>(kern), SC_THREADS,
+                                                              G::lds_bytes);
+    s.wg_per_cu = occ < 1 ? 1 : occ;
+    return s;
+  }();
+  if (setup.status != hipSuccess) return setup.status;
+  const int wg_per_cu = setup.wg_per_cu;
+  const int num_cu = num_compute_units();
+  if (num_cu < 1) return hipErrorInvalidDevice;
   const int tiles_y = (p.oh + TH - 1) / TH, tiles_x = (p.ow + TW - 1) / TW;
   const long long total = (long long)p.n * tiles_y * tiles_x;
   const int n_tiles = (p.k + 63) / 64;
@@ -270,7 +273,7 @@ hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** 
   // resident workgroup (batch 1: 13.8 -> 11.1 us; batch 32: 97.8 vs 100.5 us)
   const long long tiles8 = (long long)p.n * ((p.oh + 7) / 8) * ((p.ow + TW - 1) / TW);
   int th = tiles8 < 1536 ? 4 : 8;
-  if (const char* env = getenv("GLOWMI_SMALLC_TH")) th = atoi(env) == 8 ? 8 : 4;   // experiments
+  if (knob_is_set(KNOB_SMALLC_TH)) th = knob(KNOB_SMALLC_TH) == 8 ? 8 : 4;   // experiments
   return th == 8 ? launch_smallc<7, 7, 3, 2, 8>(p, stream) : launch_smallc<7, 7, 3, 2, 4>(p, stream);
 }
 

@@ -321,19 +321,13 @@ bool smallc_i8_applicable(const Problem& p) {
 hipError_t launch_smallc_i8(const Problem& p, hipStream_t stream, const char** variant) {
   *variant = "conv_smallc_i8_7x7s2c3";
   auto kern = conv_smallc_i8_kernel;
-  static int num_cu = 0;     // benign if two threads race: both compute the same value
-  if (num_cu == 0) {
-    int dev = 0, n = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e == hipSuccess) e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
-    if (e != hipSuccess) return e;
-    num_cu = n < 1 ? 1 : n;
-  }
+  const int num_cu = num_compute_units();
+  if (num_cu < 1) return hipErrorInvalidDevice;
   const int blocks_y = (p.oh + BH - 1) / BH, blocks_x = (p.ow + BW - 1) / BW;
   const long long items = (long long)p.n * blocks_y * blocks_x;
   const int n_tiles = (p.k + 63) / 64;
   int per_cu = 4;            // persistent workgroups per CU (measured: 3, 4 and 5 are within 1 % at batch 32; 4 is best at batch 1)
-  if (const char* env = getenv("GLOWMI_SMALLC_I8_WGS")) per_cu = atoi(env);   // experiments
+  per_cu = knob_or(KNOB_SMALLC_I8_WGS, per_cu);                               // experiments
   if (per_cu < 1) per_cu = 1;
   if (per_cu > 8) per_cu = 8;
   long long gx = (long long)num_cu * per_cu / n_tiles;

@@ -25,6 +25,7 @@ constexpr int EW_PER_THREAD = 16;
 // rounded), so the rounding decision is the same wherever it is evaluated.
 __device__ __forceinline__ int quantize_one(float v, double scale, int offset) {
   double t = __builtin_rint((double)v / scale) + (double)offset;   // ties to even
+  t = t != t ? (double)offset : t;                                 // NaN has no code: it takes the code of real zero
   t = t < -128.0 ? -128.0 : t;
   t = t > 127.0 ? 127.0 : t;
   return (int)t;

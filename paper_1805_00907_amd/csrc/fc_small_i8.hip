@@ -188,8 +188,7 @@ __global__ __launch_bounds__(FS_THREADS, 1) void fc_small_i8_kernel(const Proble
 }
 
 int fs_max_rows() {
-  if (const char* env = getenv("GLOWMI_I8_FC_SMALL_MAX_M")) return atoi(env);   // experiments and tests
-  return 64;
+  return knob_or(KNOB_I8_FC_SMALL_MAX_M, 64);   // the knob: experiments and tests
 }
 
 }  // namespace
@@ -211,13 +210,10 @@ bool fc_small_i8_applicable(const Problem& p) {
 hipError_t launch_fc_small_i8(const Problem& p, hipStream_t stream, const char** variant) {
   *variant = "fc_small_i8";
   constexpr int lds_bytes = FS_WAVES * FS_REGION + (FS_COLS + 64) * (int)sizeof(int);
-  static bool attr_set = false;   // benign if two threads race to set it
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(fc_small_i8_kernel<1>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once; initialisation of a function-local static is thread-safe
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(fc_small_i8_kernel<1>), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (attr_status != hipSuccess) return attr_status;
   // one workgroup per strip of 32 columns and block of 32 rows (measured with 64 rows: both row blocks
   // in one workgroup 10.5 us, in two workgroups 8.8 us: twice the workgroups in flight, half the loads
   // per lane)

@@ -7,9 +7,29 @@
 // weight matrix stored [K][N] (b_is_kn).
 #pragma once
 #include <hip/hip_runtime_api.h>
+#include <limits.h>
 #include <stdint.h>
 
 namespace glowmi {
+
+// Tuning knobs for experiments and tests (force a tile variant, lower a kernel's size threshold so a
+// small test shape reaches it).  Each is read ONCE from the environment variable GLOWMI_<name> when the
+// library is first used and can be changed afterwards only through glowmi_tuning_set(): nothing on the
+// dispatch path calls getenv.  kKnobUnset means "the planner's own choice".
+enum Knob {
+  KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
+  KNOB_F32_SMALL_SPLIT_MAX_TILES, KNOB_F32_SMALL_MIN_WGS, KNOB_F32_FC_SMALL_OFF, KNOB_SMALLC_TH,
+  KNOB_I8_TILE, KNOB_I8_WIDE_SPLIT, KNOB_I8_WIDE_NBUF, KNOB_SMALLC_I8_WGS, KNOB_I8_PW_MIN_ITEMS,
+  KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER, KNOB_I8_DEEP_OFF,
+  KNOB_COUNT
+};
+constexpr int kKnobUnset = INT_MIN;
+int knob(Knob k);                                     // current value or kKnobUnset
+inline bool knob_is_set(Knob k) { return knob(k) != kKnobUnset; }
+inline int knob_or(Knob k, int dflt) { const int v = knob(k); return v == kKnobUnset ? dflt : v; }
+
+// Compute units of the current device, queried once (0 if the query fails).
+int num_compute_units();
 
 // Division of an index below 2^31 by a fixed divisor d as one multiply-high and one shift:
 // with s = ceil(log2 d) and mul = ceil(2^(31+s) / d), n / d == (n * mul) >> (31 + s) exactly.
@@ -66,10 +86,37 @@ struct Problem {
                                     // code difference to the accumulator's scale, mant * 2^-shift
 };
 
-// Each launcher validates nothing (the ABI layer did), picks the tile variant, launches on `stream`
-// and reports the variant name.  Returns the hipError_t of the launch.
-hipError_t launch_f32(const Problem& p, hipStream_t stream, const char** variant);
-hipError_t launch_i8(const Problem& p, hipStream_t stream, const char** variant);
+// Which kernel family a call takes, and how the reduction is split over workgroups.  The ABI layer
+// plans ONCE per call (with the workspace the caller gave in mind) and hands the plan to the launcher.
+enum KernelKind {
+  KERNEL_TILED = 0,     // generic implicit-GEMM tiles (igemm_f32.hip / igemm_i8.hip)
+  KERNEL_SKINNY16,      // fp32 FullyConnected with at most 16 rows: weight stream
+  KERNEL_SMALL,         // fp32 convolution on few pixels, one launch (conv_small_f32.hip)
+  KERNEL_SMALL_SPLIT,   // the same with the reduction sliced over the grid
+  KERNEL_SMALLC,        // 3-channel 7x7/2 first layer
+  KERNEL_PW,            // pointwise convolution, persistent workgroups
+  KERNEL_K3C64,         // int8 3x3 over 64 channels
+  KERNEL_FC_SMALL,      // FullyConnected with few rows in one launch (fp32: fc_small_f32.hip, int8: fc_small_i8.hip)
+  KERNEL_WIDE,          // int8 large contractions (igemm_i8_wide.hip)
+  KERNEL_DEEP           // int8 deep reduction on few pixels in one launch (conv_deep_i8.hip)
+};
+struct Plan {
+  int kernel;           // KernelKind
+  int tile;             // index into the kernel file's tile table (KERNEL_TILED, KERNEL_WIDE)
+  int bm, bn, bk;
+  int tiles_m, tiles_n;
+  int slabs;            // ceil(Kgemm / bk)
+  int split_k;
+  int slabs_per_split;
+};
+Plan plan_f32(const Problem& p, bool allow_split);
+Plan plan_i8(const Problem& p, bool allow_split);
+
+// Each launcher validates nothing (the ABI layer did), launches what the plan says on `stream` and
+// reports the variant name.  p.partial must be the workspace when plan.split_k > 1.  Returns the
+// hipError_t of the launch.
+hipError_t launch_f32(const Problem& p, const Plan& plan, hipStream_t stream, const char** variant);
+hipError_t launch_i8(const Problem& p, const Plan& plan, hipStream_t stream, const char** variant);
 
 // Few-input-channel first-layer convolution (conv_smallc_f32.hip); used by launch_f32 when applicable.
 bool smallc_f32_applicable(const Problem& p);
@@ -81,6 +128,12 @@ hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** vari
 bool conv_small_f32_applicable(const Problem& p);
 hipError_t launch_conv_small_f32(const Problem& p, hipStream_t stream, const char** variant);
 int conv_small_f32_splits(const Problem& p);   // > 1: the split form of that kernel applies, with this many reduction slices
+// fp32 FullyConnected with few rows and a small weight matrix, in one launch (fc_small_f32.hip).
+bool fc_small_f32_applicable(const Problem& p);
+hipError_t launch_fc_small_f32(const Problem& p, hipStream_t stream, const char** variant);
+// int8 convolution with a deep reduction on few pixels, in one launch (conv_deep_i8.hip).
+bool deep_i8_applicable(const Problem& p);
+hipError_t launch_deep_i8(const Problem& p, hipStream_t stream, const char** variant);
 bool pw_i8_applicable(const Problem& p);
 hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** variant);
 // int8 3x3 convolution over 64 input channels on many pixels (conv_k3c64_i8.hip).
@@ -99,18 +152,6 @@ hipError_t launch_dequantize(const signed char* q, float* x, long long count, fl
                              hipStream_t stream);
 hipError_t launch_rescale(const signed char* in, signed char* out, long long count, int in_offset, int mant,
                           int shift, int out_offset, hipStream_t stream);
-
-// Split-K planning shared by the ABI layer (workspace sizing) and the launchers.
-struct Plan {
-  int tile;             // index into the kernel file's tile table
-  int bm, bn, bk;
-  int tiles_m, tiles_n;
-  int slabs;            // ceil(Kgemm / bk)
-  int split_k;
-  int slabs_per_split;
-};
-Plan plan_f32(const Problem& p, bool allow_split);
-Plan plan_i8(const Problem& p, bool allow_split);
 
 // int8 kernel for large contractions (igemm_i8_wide.hip): 128 x 128 or 128 x 64 output tiles, tile
 // indices 4 and 5 of the int8 plan.

@@ -556,7 +556,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void fc_skinny16_f32_kernel(
 
   if (!col_ok) return;
   v4f bv = {0.f, 0.f, 0.f, 0.f};
-  if (split_k == 1 && bias) bv = *reinterpret_cast<const v4f*>(bias + col);
+  if (split_k == 1 && bias) bv = v4f{bias[col], bias[col + 1], bias[col + 2], bias[col + 3]};   // bias is only 4-byte aligned
   // 16x16 result: register e of lane (c, q) is row 4q + e, column c
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
@@ -576,20 +576,15 @@ __global__ __launch_bounds__(64 * SK_WAVES) void fc_skinny16_f32_kernel(
   }
 }
 
-constexpr int kTileSkinny16 = 101;   // Plan::tile value of the skinny FC kernel
-constexpr int kTileSmallSplit = 102; // Plan::tile value of the small-convolution kernel with a split reduction
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK>
 hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
   auto kern = igemm_f32_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN, LONGK>;
   constexpr int lds_bytes = lds_floats<BM, BN, B_KN>() * (int)sizeof(float);
   constexpr int nthreads = 64 * WAVES_M * WAVES_N;
-  static bool attr_set = false;   // per instantiation; benign if two threads race to set it
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per instantiation; initialisation of a function-local static is thread-safe
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (attr_status != hipSuccess) return attr_status;
   const long long total_work = (long long)plan.tiles_m * plan.tiles_n * p.groups * plan.split_k;
   const long long grid_x = ((total_work + 7) / 8) * 8;
   dim3 grid((unsigned)grid_x, 1, 1), block(nthreads, 1, 1);
@@ -613,16 +608,28 @@ constexpr int kNumTilesF32 = sizeof(kTilesF32) / sizeof(kTilesF32[0]);
 
 Plan plan_f32(const Problem& p, bool allow_split) {
   Plan pl;
-  if (((smallc_f32_applicable(p) && !p.addend) || pw_f32_applicable(p) || conv_small_f32_applicable(p)) &&
-      !getenv("GLOWMI_F32_TILE"))
-    allow_split = false;   // kernels of their own, no workspace
-  if (p.b_is_kn && p.M <= 16 && p.groups == 1 && p.k % 4 == 0 && p.Kgemm % 4 == 0 && !p.addend &&
-      !getenv("GLOWMI_F32_TILE")) {
+  pl.kernel = KERNEL_TILED;
+  pl.tile = 0;
+  pl.bm = pl.bn = pl.bk = 0;
+  pl.tiles_m = pl.tiles_n = 1;
+  pl.slabs = 1;
+  pl.split_k = 1;
+  pl.slabs_per_split = 1;
+  const int forced_tile = knob(KNOB_F32_TILE);           // experiments and tests: force a generic tile variant
+  const bool forced = forced_tile != kKnobUnset;
+  if (!forced) {
+    // kernels of their own, no workspace
+    if (smallc_f32_applicable(p) && !p.addend) { pl.kernel = KERNEL_SMALLC; return pl; }
+    if (pw_f32_applicable(p)) { pl.kernel = KERNEL_PW; return pl; }
+    if (conv_small_f32_applicable(p)) { pl.kernel = KERNEL_SMALL; return pl; }
+    if (fc_small_f32_applicable(p)) { pl.kernel = KERNEL_FC_SMALL; return pl; }
+  }
+  if (p.b_is_kn && p.M <= 16 && p.groups == 1 && p.k % 4 == 0 && p.Kgemm % 4 == 0 && !p.addend && !forced) {
     // FC with a handful of rows: stream the weights (fc_skinny16_f32_kernel).  "slabs" are steps of
     // SK16_STEP weight rows; K is split over the grid until ~4 workgroups per CU exist, each
     // wavefront keeping at least two steps.
     const int cols = SK16_COLS, stepk = SK16_STEP;
-    pl.tile = kTileSkinny16;
+    pl.kernel = KERNEL_SKINNY16;
     pl.bm = 16;
     pl.bn = cols;
     pl.bk = stepk;
@@ -643,11 +650,11 @@ Plan plan_f32(const Problem& p, bool allow_split) {
     }
     return pl;
   }
-  if (allow_split && !getenv("GLOWMI_F32_TILE")) {
+  if (allow_split && !forced) {
     // deep reduction on very few pixels: the single-round-trip kernel, reduction sliced over the grid
     const int slices = conv_small_f32_splits(p);
     if (slices > 1) {
-      pl.tile = kTileSmallSplit;
+      pl.kernel = KERNEL_SMALL_SPLIT;
       pl.bm = 32;
       pl.bn = 32;
       pl.bk = 576;
@@ -672,10 +679,7 @@ Plan plan_f32(const Problem& p, bool allow_split) {
     const long long t128 = (long long)((p.M + 127) / 128) * ((p.kg + 127) / 128) * p.groups;
     if (allow_split && p.kg >= 128 && t128 >= 256 && t128 < 1024 && p.Kgemm >= 4096) tile = 2;
   }
-  if (const char* env = getenv("GLOWMI_F32_TILE")) {       // experiments: force a tile variant
-    const int t = atoi(env);
-    if (t >= 0 && t < kNumTilesF32) tile = t;
-  }
+  if (forced && forced_tile >= 0 && forced_tile < kNumTilesF32) tile = forced_tile;
   pl.tile = tile;
   pl.bm = kTilesF32[tile].bm;
   pl.bn = kTilesF32[tile].bn;
@@ -705,7 +709,12 @@ Plan plan_f32(const Problem& p, bool allow_split) {
       if (u > best_u + 1e-9) { best_u = u; best = sk; }
       if (u >= 0.9) { best = sk; break; }
     }
-    if (const char* env = getenv("GLOWMI_F32_SPLIT")) best = atoi(env);   // experiments
+    if (knob_is_set(KNOB_F32_SPLIT)) {                     // experiments: clamped to what the slabs allow
+      best = knob(KNOB_F32_SPLIT);
+      if (best < 1) best = 1;
+      if (best > pl.slabs) best = pl.slabs;
+      if (best > 256) best = 256;
+    }
     if (best > 1) {
       pl.slabs_per_split = (pl.slabs + best - 1) / best;
       pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
@@ -729,14 +738,16 @@ hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, b
 }
 }  // namespace
 
-hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
-  if (smallc_f32_applicable(p_in) && !p_in.addend && !getenv("GLOWMI_F32_TILE"))
-    return launch_smallc_f32(p_in, stream, variant);   // (that kernel has no tensor-add link)
-  if (pw_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE")) return launch_pw_f32(p_in, stream, variant);
-  if (conv_small_f32_applicable(p_in) && !getenv("GLOWMI_F32_TILE"))
-    return launch_conv_small_f32(p_in, stream, variant);
+hipError_t launch_f32(const Problem& p_in, const Plan& plan, hipStream_t stream, const char** variant) {
+  switch (plan.kernel) {
+    case KERNEL_SMALLC: return launch_smallc_f32(p_in, stream, variant);
+    case KERNEL_PW: return launch_pw_f32(p_in, stream, variant);
+    case KERNEL_SMALL: return launch_conv_small_f32(p_in, stream, variant);
+    case KERNEL_FC_SMALL: return launch_fc_small_f32(p_in, stream, variant);
+    default: break;
+  }
+  if (plan.split_k > 1 && !p_in.partial) return hipErrorInvalidValue;   // the ABI layer never plans a split without a workspace
   Problem p = p_in;
-  const Plan plan = plan_f32(p, p.partial != nullptr);
   p.split_k = plan.split_k;
   p.slabs_per_split = plan.slabs_per_split;
   // 16-byte gathers need channel runs that are multiples of 4 floats
@@ -744,9 +755,9 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
   const bool vec = fc ? (p.Kgemm % 4 == 0 && p.k % 4 == 0) : (p.cg % 4 == 0 && p.c % 4 == 0);
   static thread_local char name[64];
   hipError_t e;
-  if (plan.tile == kTileSmallSplit) {
+  if (plan.kernel == KERNEL_SMALL_SPLIT) {
     e = launch_conv_small_f32(p, stream, variant);
-  } else if (plan.tile == kTileSkinny16) {
+  } else if (plan.kernel == KERNEL_SKINNY16) {
     *variant = "fc_skinny16_f32";
     dim3 grid(plan.tiles_n, plan.split_k, 1), block(64 * SK_WAVES, 1, 1);
     // weights beyond half of the 256 MB last-level cache are treated as a stream
@@ -757,18 +768,18 @@ hipError_t launch_f32(const Problem& p_in, hipStream_t stream, const char** vari
                        plan.split_k, plan.slabs_per_split);
     e = hipGetLastError();
   } else {
-  snprintf(name, sizeof(name), "igemm_f32_%s_%s_%s%s", kTilesF32[plan.tile].name, fc ? "fc" : "conv",
-           vec ? "vec" : "scalar", plan.slabs_per_split > FLUSH_SLABS ? "_longk" : "");
-  *variant = name;
-  switch (plan.tile) {
-    case 0: e = launch_tile<64, 64, 2, 2>(p, plan, stream, fc, vec); break;
-    case 1: e = launch_tile<128, 64, 4, 2>(p, plan, stream, fc, vec); break;
-    case 2: e = launch_tile<128, 128, 2, 4>(p, plan, stream, fc, vec); break;
-    case 3: e = launch_tile<32, 128, 1, 4>(p, plan, stream, fc, vec); break;
-    case 4: e = launch_tile<128, 64, 2, 2>(p, plan, stream, fc, vec); break;
-    case 5: e = launch_tile<128, 128, 2, 2>(p, plan, stream, fc, vec); break;
-    default: return hipErrorInvalidValue;
-  }
+    snprintf(name, sizeof(name), "igemm_f32_%s_%s_%s%s", kTilesF32[plan.tile].name, fc ? "fc" : "conv",
+             vec ? "vec" : "scalar", plan.slabs_per_split > FLUSH_SLABS ? "_longk" : "");
+    *variant = name;
+    switch (plan.tile) {
+      case 0: e = launch_tile<64, 64, 2, 2>(p, plan, stream, fc, vec); break;
+      case 1: e = launch_tile<128, 64, 4, 2>(p, plan, stream, fc, vec); break;
+      case 2: e = launch_tile<128, 128, 2, 4>(p, plan, stream, fc, vec); break;
+      case 3: e = launch_tile<32, 128, 1, 4>(p, plan, stream, fc, vec); break;
+      case 4: e = launch_tile<128, 64, 2, 2>(p, plan, stream, fc, vec); break;
+      case 5: e = launch_tile<128, 128, 2, 2>(p, plan, stream, fc, vec); break;
+      default: return hipErrorInvalidValue;
+    }
   }
   if (e != hipSuccess) return e;
   if (plan.split_k > 1) {

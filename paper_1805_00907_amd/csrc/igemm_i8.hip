@@ -460,13 +460,10 @@ hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream
   auto kern = igemm_i8_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN>;
   constexpr int lds_bytes = 2 * (BM + BN) * LDQ;
   constexpr int nthreads = 64 * WAVES_M * WAVES_N;
-  static bool attr_set = false;   // per instantiation; benign if two threads race to set it
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per instantiation; initialisation of a function-local static is thread-safe
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (attr_status != hipSuccess) return attr_status;
   const long long total_work = (long long)plan.tiles_m * plan.tiles_n * p.groups * plan.split_k;
   const long long grid_x = ((total_work + 7) / 8) * 8;
   dim3 grid((unsigned)grid_x, 1, 1), block(nthreads, 1, 1);
@@ -495,15 +492,25 @@ hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, b
 
 Plan plan_i8(const Problem& p, bool allow_split) {
   Plan pl;
-  if (((smallc_i8_applicable(p) && !p.addend) || pw_i8_applicable(p) || k3c64_i8_applicable(p) ||
-       fc_small_i8_applicable(p)) &&
-      !getenv("GLOWMI_I8_TILE"))
-    allow_split = false;   // kernels of their own, no workspace
+  pl.kernel = KERNEL_TILED;
+  pl.tile = 0;
+  pl.bm = pl.bn = pl.bk = 0;
+  pl.tiles_m = pl.tiles_n = 1;
+  pl.slabs = 1;
+  pl.split_k = 1;
+  pl.slabs_per_split = 1;
+  const int forced = knob_or(KNOB_I8_TILE, -1);   // experiments and tests: force a tile variant
+  if (forced < 0) {
+    // kernels of their own, no workspace
+    if (smallc_i8_applicable(p) && !p.addend) { pl.kernel = KERNEL_SMALLC; return pl; }
+    if (pw_i8_applicable(p)) { pl.kernel = KERNEL_PW; return pl; }
+    if (k3c64_i8_applicable(p)) { pl.kernel = KERNEL_K3C64; return pl; }
+    if (fc_small_i8_applicable(p)) { pl.kernel = KERNEL_FC_SMALL; return pl; }
+    if (deep_i8_applicable(p)) { pl.kernel = KERNEL_DEEP; return pl; }
+  }
   pl.bk = BKQ;
   pl.slabs = (p.Kgemm + BKQ - 1) / BKQ;
   int tile = 0;
-  int forced = -1;
-  if (const char* env = getenv("GLOWMI_I8_TILE")) forced = atoi(env);   // experiments and tests: force a tile variant
   if (forced >= 0 && forced < kNumTilesI8) tile = forced;
   // Large contractions (deep reduction, enough pixels and channels for 128-wide tiles) take the
   // kernel built for them.
@@ -551,20 +558,23 @@ Plan plan_i8(const Problem& p, bool allow_split) {
   return pl;
 }
 
-hipError_t launch_i8(const Problem& p_in, hipStream_t stream, const char** variant) {
-  if (smallc_i8_applicable(p_in) && !p_in.addend && !getenv("GLOWMI_I8_TILE"))
-    return launch_smallc_i8(p_in, stream, variant);   // (that kernel has no tensor-add link)
-  if (pw_i8_applicable(p_in) && !getenv("GLOWMI_I8_TILE")) return launch_pw_i8(p_in, stream, variant);
-  if (k3c64_i8_applicable(p_in) && !getenv("GLOWMI_I8_TILE")) return launch_k3c64_i8(p_in, stream, variant);
-  if (fc_small_i8_applicable(p_in) && !getenv("GLOWMI_I8_TILE")) return launch_fc_small_i8(p_in, stream, variant);
+hipError_t launch_i8(const Problem& p_in, const Plan& plan, hipStream_t stream, const char** variant) {
+  switch (plan.kernel) {
+    case KERNEL_SMALLC: return launch_smallc_i8(p_in, stream, variant);
+    case KERNEL_PW: return launch_pw_i8(p_in, stream, variant);
+    case KERNEL_K3C64: return launch_k3c64_i8(p_in, stream, variant);
+    case KERNEL_FC_SMALL: return launch_fc_small_i8(p_in, stream, variant);
+    case KERNEL_DEEP: return launch_deep_i8(p_in, stream, variant);
+    default: break;
+  }
+  if (plan.split_k > 1 && !p_in.partial) return hipErrorInvalidValue;   // the ABI layer never plans a split without a workspace
   Problem p = p_in;
-  const Plan plan = plan_i8(p, p.partial != nullptr);
   p.split_k = plan.split_k;
   p.slabs_per_split = plan.slabs_per_split;
   const bool fc = p.b_is_kn != 0;
   const bool vec = fc ? (p.Kgemm % 16 == 0 && p.k % 4 == 0) : (p.cg % 16 == 0 && p.c % 16 == 0);
   hipError_t e;
-  if (plan.tile >= 4) {
+  if (plan.kernel == KERNEL_WIDE) {
     e = launch_wide_i8(p, plan, stream, variant);
   } else {
     static thread_local char name[64];

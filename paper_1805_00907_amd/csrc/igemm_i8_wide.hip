@@ -500,13 +500,10 @@ template <int BN, bool B_KN, bool PADDED, bool XSUM, int NBUF>
 hipError_t launch_wide_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
   auto kern = igemm_i8_wide_kernel<BN, B_KN, PADDED, XSUM, NBUF>;
   constexpr int lds_bytes = NBUF * (WBM + BN) * WBK + (WBM + 2 * BN) * 4;
-  static bool attr_set = false;   // per instantiation; benign if two threads race to set it
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  // once per instantiation; initialisation of a function-local static is thread-safe
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (attr_status != hipSuccess) return attr_status;
   const long long total_work = (long long)plan.tiles_m * plan.tiles_n * p.groups * plan.split_k;
   const long long grid_x = ((total_work + 7) / 8) * 8;
   // band width: the run of tiles one XCD gets should be roughly square in (pixel tiles, channel tiles)
@@ -545,6 +542,7 @@ bool wide_i8_applicable(const Problem& p) {
 // its slabs plus a fixed overhead, plus the traffic of the int32 partial sums.
 Plan plan_wide_i8(const Problem& p, int bn, bool allow_split) {
   Plan pl;
+  pl.kernel = KERNEL_WIDE;
   pl.tile = bn == 128 ? 4 : 5;
   pl.bm = WBM;
   pl.bn = bn;
@@ -566,7 +564,12 @@ Plan plan_wide_i8(const Problem& p, int bn, bool allow_split) {
       if (sk > 1) cost += (double)(sk + 1) * p.M * p.k * 4.0 / 4e12 / 0.25e-6;
       if (cost < best_cost - 1e-9) { best_cost = cost; best = sk; }
     }
-    if (const char* env = getenv("GLOWMI_I8_WIDE_SPLIT")) best = atoi(env);   // experiments
+    if (knob_is_set(KNOB_I8_WIDE_SPLIT)) {                 // experiments: clamped to what the slabs allow
+      best = knob(KNOB_I8_WIDE_SPLIT);
+      if (best < 1) best = 1;
+      if (best > pl.slabs) best = pl.slabs;
+      if (best > 32) best = 32;
+    }
     if (best > 1) {
       pl.slabs_per_split = (pl.slabs + best - 1) / best;
       pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
@@ -581,7 +584,7 @@ hipError_t launch_wide_i8(const Problem& p, const Plan& plan, hipStream_t stream
   // buffers each, which hides one workgroup's prologue and epilogue behind the other's main loop
   const long long work = (long long)plan.tiles_m * plan.tiles_n * p.groups * plan.split_k;
   int nbuf = work <= 256 ? 4 : 2;
-  if (const char* env = getenv("GLOWMI_I8_WIDE_NBUF")) nbuf = atoi(env) == 2 ? 2 : 4;   // experiments
+  if (knob_is_set(KNOB_I8_WIDE_NBUF)) nbuf = knob(KNOB_I8_WIDE_NBUF) == 2 ? 2 : 4;   // experiments
   static thread_local char name[64];
   snprintf(name, sizeof(name), "igemm_i8_wide_128x%dk2w8r%d_%s", plan.bn, nbuf, p.b_is_kn ? "fc" : "conv");
   *variant = name;

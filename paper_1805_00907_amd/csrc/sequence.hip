@@ -7,16 +7,21 @@
 //
 // Host code only: it validates, plans offsets and calls the layer entry points; it launches nothing
 // of its own and never synchronises, so a caller can capture the whole sequence in a HIP graph.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdint>
+#include <vector>
 
 #include "../../include/glowmi.h"
+#include "api_internal.h"
 
 namespace {
 
+using glowmi::fail;
+
 constexpr size_t kAlign = 256;
+constexpr int32_t kMaxLayers = 4096;
 size_t round_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct SeqPlan {
@@ -27,7 +32,8 @@ struct SeqPlan {
 
 // Shapes must chain: layer i's input is layer i-1's output.  Returns GLOWMI_OK and the plan.
 glowmi_status plan_sequence(const glowmi_seq_layer* layers, int32_t n, size_t elem, bool quantized, SeqPlan* plan) {
-  if (!layers || n <= 0) return GLOWMI_ERR_NULL;
+  if (!layers) return fail(GLOWMI_ERR_NULL, "layer array is NULL");
+  if (n <= 0 || n > kMaxLayers) return fail(GLOWMI_ERR_SHAPE, "a sequence has 1 to %d layers (got %d)", kMaxLayers, n);
   plan->region[0] = plan->region[1] = plan->workspace = 0;
   for (int32_t i = 0; i < n; ++i) {
     const glowmi_conv_desc& d = layers[i].desc;
@@ -36,18 +42,62 @@ glowmi_status plan_sequence(const glowmi_seq_layer* layers, int32_t n, size_t el
     if (st != GLOWMI_OK) return st;
     if (i + 1 < n) {
       const glowmi_conv_desc& nx = layers[i + 1].desc;
-      if (nx.n != d.n || nx.h != oh || nx.w != ow || nx.c != d.k) return GLOWMI_ERR_SHAPE;
+      if (nx.n != d.n || nx.h != oh || nx.w != ow || nx.c != d.k)
+        return fail(GLOWMI_ERR_SHAPE, "layer %d reads %dx%dx%dx%d but layer %d writes %dx%dx%dx%d", i + 1, nx.n, nx.h,
+                    nx.w, nx.c, i, d.n, oh, ow, d.k);
       const size_t bytes = round_up((size_t)d.n * oh * ow * d.k * elem);
       plan->region[i & 1] = std::max(plan->region[i & 1], bytes);
     }
     if (layers[i].add_input) {      // identity shortcut: the sequence input has the layer's output shape
       const glowmi_conv_desc& first = layers[0].desc;
-      if (first.n != d.n || first.h != oh || first.w != ow || first.c != d.k) return GLOWMI_ERR_SHAPE;
+      if (first.n != d.n || first.h != oh || first.w != ow || first.c != d.k)
+        return fail(GLOWMI_ERR_SHAPE, "layer %d adds the sequence input, whose shape differs from the layer's output", i);
     }
     const size_t ws = quantized ? glowmi_qconv2d_workspace_bytes(&d) : glowmi_conv2d_workspace_bytes(&d);
     plan->workspace = std::max(plan->workspace, round_up(ws));
   }
   plan->total = plan->region[0] + plan->region[1] + plan->workspace;
+  return GLOWMI_OK;
+}
+
+// Validate and plan EVERY layer before anything is launched, then launch them in order: a bad filter
+// pointer or quantization parameter in layer 3 is reported with layers 0-2 still unlaunched.
+glowmi_status run_sequence(const void* x, glowmi_qparam xq, const glowmi_seq_layer* layers, int32_t n, void* y,
+                           void* arena, size_t arena_bytes, bool quantized, hipStream_t stream) {
+  SeqPlan plan;
+  glowmi_status st = plan_sequence(layers, n, quantized ? 1 : 4, quantized, &plan);
+  if (st != GLOWMI_OK) return st;
+  if (!x || !y) return fail(GLOWMI_ERR_NULL, "sequence input and output must not be NULL");
+  if (plan.total && !arena) return fail(GLOWMI_ERR_NULL, "the sequence needs an arena of %zu bytes", plan.total);
+  if (arena_bytes < plan.total) return fail(GLOWMI_ERR_ALIGN, "arena of %zu bytes, %zu needed", arena_bytes, plan.total);
+  if (reinterpret_cast<uintptr_t>(arena) & 15) return fail(GLOWMI_ERR_ALIGN, "arena must be 16-byte aligned");
+  char* base = static_cast<char*>(arena);
+  char* region[2] = {base, base + plan.region[0]};
+  void* ws = plan.workspace ? base + plan.region[0] + plan.region[1] : nullptr;
+  std::vector<glowmi::PreparedCall> calls((size_t)n);
+  const void* in = x;
+  glowmi_qparam in_q = xq;
+  for (int32_t i = 0; i < n; ++i) {
+    void* out = i + 1 < n ? static_cast<void*>(region[i & 1]) : y;
+    glowmi_chain chain;
+    chain.addend = layers[i].add_input ? x : nullptr;
+    chain.addend_q = xq;
+    chain.act = layers[i].act;
+    if (quantized)
+      st = glowmi::prepare_qconv2d_chain(static_cast<const int8_t*>(in), in_q, static_cast<const int8_t*>(layers[i].w),
+                                         layers[i].wq, static_cast<const int32_t*>(layers[i].bias),
+                                         static_cast<int8_t*>(out), layers[i].yq, &layers[i].desc, &chain, ws,
+                                         plan.workspace, &calls[(size_t)i]);
+    else
+      st = glowmi::prepare_conv2d_chain(static_cast<const float*>(in), static_cast<const float*>(layers[i].w),
+                                        static_cast<const float*>(layers[i].bias), static_cast<float*>(out),
+                                        &layers[i].desc, &chain, ws, plan.workspace, &calls[(size_t)i]);
+    if (st != GLOWMI_OK) return st;          // nothing has been launched
+    in = out;
+    in_q = layers[i].yq;
+  }
+  for (int32_t i = 0; i < n; ++i)
+    if ((st = glowmi::run_prepared(calls[(size_t)i], stream)) != GLOWMI_OK) return st;   // only a HIP launch failure
   return GLOWMI_OK;
 }
 
@@ -63,56 +113,15 @@ size_t glowmi_seq_arena_bytes(const glowmi_seq_layer* layers, int32_t n, int32_t
 
 glowmi_status glowmi_seq_conv2d(const float* x, const glowmi_seq_layer* layers, int32_t n, float* y, void* arena,
                                 size_t arena_bytes, hipStream_t stream) {
-  SeqPlan plan;
-  glowmi_status st = plan_sequence(layers, n, 4, false, &plan);
-  if (st != GLOWMI_OK) return st;
-  if (!x || !y || (plan.total && !arena)) return GLOWMI_ERR_NULL;
-  if (arena_bytes < plan.total || (reinterpret_cast<uintptr_t>(arena) & 15)) return GLOWMI_ERR_ALIGN;
-  char* base = static_cast<char*>(arena);
-  char* region[2] = {base, base + plan.region[0]};
-  void* ws = plan.workspace ? base + plan.region[0] + plan.region[1] : nullptr;
-  const float* in = x;
-  for (int32_t i = 0; i < n; ++i) {
-    float* out = i + 1 < n ? reinterpret_cast<float*>(region[i & 1]) : y;
-    glowmi_chain chain;
-    chain.addend = layers[i].add_input ? x : nullptr;
-    chain.addend_q.scale = 1.0f;
-    chain.addend_q.offset = 0;
-    chain.act = layers[i].act;
-    st = glowmi_conv2d_chain(in, static_cast<const float*>(layers[i].w), static_cast<const float*>(layers[i].bias),
-                             out, &layers[i].desc, &chain, ws, plan.workspace, stream);
-    if (st != GLOWMI_OK) return st;
-    in = out;
-  }
-  return GLOWMI_OK;
+  glowmi_qparam none;
+  none.scale = 1.0f;
+  none.offset = 0;
+  return run_sequence(x, none, layers, n, y, arena, arena_bytes, false, stream);
 }
 
 glowmi_status glowmi_seq_qconv2d(const int8_t* x, glowmi_qparam xq, const glowmi_seq_layer* layers, int32_t n,
                                  int8_t* y, void* arena, size_t arena_bytes, hipStream_t stream) {
-  SeqPlan plan;
-  glowmi_status st = plan_sequence(layers, n, 1, true, &plan);
-  if (st != GLOWMI_OK) return st;
-  if (!x || !y || (plan.total && !arena)) return GLOWMI_ERR_NULL;
-  if (arena_bytes < plan.total || (reinterpret_cast<uintptr_t>(arena) & 15)) return GLOWMI_ERR_ALIGN;
-  char* base = static_cast<char*>(arena);
-  char* region[2] = {base, base + plan.region[0]};
-  void* ws = plan.workspace ? base + plan.region[0] + plan.region[1] : nullptr;
-  const int8_t* in = x;
-  glowmi_qparam in_q = xq;
-  for (int32_t i = 0; i < n; ++i) {
-    int8_t* out = i + 1 < n ? reinterpret_cast<int8_t*>(region[i & 1]) : y;
-    glowmi_chain chain;
-    chain.addend = layers[i].add_input ? x : nullptr;
-    chain.addend_q = xq;
-    chain.act = layers[i].act;
-    st = glowmi_qconv2d_chain(in, in_q, static_cast<const int8_t*>(layers[i].w), layers[i].wq,
-                              static_cast<const int32_t*>(layers[i].bias), out, layers[i].yq, &layers[i].desc,
-                              &chain, ws, plan.workspace, stream);
-    if (st != GLOWMI_OK) return st;
-    in = out;
-    in_q = layers[i].yq;
-  }
-  return GLOWMI_OK;
+  return run_sequence(x, xq, layers, n, y, arena, arena_bytes, true, stream);
 }
 
 }  // extern "C"

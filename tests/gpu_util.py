@@ -33,28 +33,29 @@ def workspace(nbytes: int):
     return torch.empty(max(nbytes, 16), dtype=torch.uint8, device=DEV) if nbytes else None
 
 
-def poison(shape, dtype):
-    """Output buffer pre-filled with a value no test expects, so unwritten elements are caught."""
+def poison(shape, dtype, fill=77):
+    """Output buffer pre-filled with a value no test expects (NaN for float, the code `fill` for
+    int8), so unwritten elements are caught."""
     if dtype == torch.float32:
         return torch.full(shape, float("nan"), dtype=dtype, device=DEV)
-    return torch.full(shape, 77, dtype=dtype, device=DEV)
+    return torch.full(shape, fill, dtype=dtype, device=DEV)
 
 
 GUARD = 4096   # elements of untouched poison kept on either side of a guarded output
 
 
-def guarded(shape, dtype):
+def guarded(shape, dtype, fill=77):
     """A poisoned output inside a larger poisoned allocation: (whole buffer, view of the output)."""
     count = int(np.prod(shape))
-    whole = poison((count + 2 * GUARD,), dtype)
+    whole = poison((count + 2 * GUARD,), dtype, fill)
     return whole, whole[GUARD:GUARD + count].view(shape)
 
 
-def guards_intact(whole, dtype):
+def guards_intact(whole, dtype, fill=77):
     lo, hi = whole[:GUARD], whole[-GUARD:]
     if dtype == torch.float32:
         return bool(torch.isnan(lo).all() and torch.isnan(hi).all())
-    return bool((lo == 77).all() and (hi == 77).all())
+    return bool((lo == fill).all() and (hi == fill).all())
 
 
 def gpu_conv2d_f32(x, w, b, desc, act, use_workspace=True):
@@ -85,10 +86,11 @@ def gpu_conv2d_f32_chain(x, w, b, addend, desc, act, use_workspace=True, in_plac
     return y.cpu().numpy(), glowmi.last_variant()
 
 
-def gpu_qconv2d_chain(xq, wq, bq, qp, addend_q, r_scale, r_off, desc, act, use_workspace=True, in_place=False):
+def gpu_qconv2d_chain(xq, wq, bq, qp, addend_q, r_scale, r_off, desc, act, use_workspace=True, in_place=False,
+                      fill=77):
     oh, ow = glowmi.conv_out_shape(desc)
     xd, wd, bd = dev(xq), dev(wq), dev(bq)
-    whole, y = guarded((desc.n, oh, ow, desc.k), torch.int8)
+    whole, y = guarded((desc.n, oh, ow, desc.k), torch.int8, fill)
     if in_place:
         y.copy_(torch.from_numpy(np.ascontiguousarray(addend_q)))
         ad = y
@@ -99,7 +101,7 @@ def gpu_qconv2d_chain(xq, wq, bq, qp, addend_q, r_scale, r_off, desc, act, use_w
     glowmi.qconv2d_chain(xd, xp, wd, wp, bd, y, yp, desc, addend=ad, addend_q=glowmi.QParam(r_scale, r_off),
                          act=act, workspace=ws)
     torch.cuda.synchronize()
-    assert guards_intact(whole, torch.int8), "write outside the output tensor"
+    assert guards_intact(whole, torch.int8, fill), "write outside the output tensor"
     return y.cpu().numpy(), glowmi.last_variant()
 
 
@@ -119,23 +121,23 @@ def qparams(qp):
             glowmi.QParam(qp.y_scale, qp.y_off))
 
 
-def gpu_qconv2d(xq, wq, bq, qp, desc, act, use_workspace=True):
+def gpu_qconv2d(xq, wq, bq, qp, desc, act, use_workspace=True, fill=77):
     oh, ow = glowmi.conv_out_shape(desc)
     xd, wd, bd = dev(xq), dev(wq), dev(bq)
-    whole, y = guarded((desc.n, oh, ow, desc.k), torch.int8)
+    whole, y = guarded((desc.n, oh, ow, desc.k), torch.int8, fill)
     ws = workspace(glowmi.qconv2d_workspace_bytes(desc)) if use_workspace else None
     xp, wp, yp = qparams(qp)
     glowmi.qconv2d(xd, xp, wd, wp, bd, y, yp, desc, act, ws)
     torch.cuda.synchronize()
-    assert guards_intact(whole, torch.int8), "write outside the output tensor"
+    assert guards_intact(whole, torch.int8, fill), "write outside the output tensor"
     return y.cpu().numpy(), glowmi.last_variant()
 
 
-def gpu_qfc(aq, wq, bq, qp, act, use_workspace=True):
+def gpu_qfc(aq, wq, bq, qp, act, use_workspace=True, fill=77):
     M, K = aq.shape
     N = wq.shape[1]
     ad, wd, bd = dev(aq), dev(wq), dev(bq)
-    y = poison((M, N), torch.int8)
+    y = poison((M, N), torch.int8, fill)
     ws = workspace(glowmi.qfc_workspace_bytes(M, K, N)) if use_workspace else None
     xp, wp, yp = qparams(qp)
     glowmi.qfc(ad, xp, wd, wp, bd, y, yp, M, K, N, act, ws)

@@ -226,6 +226,9 @@ def pin_quantize_round_trip():
     # saturation and ties-to-even of the helper
     q = oracle.quantize(np.array([1000.0, -1000.0, 0.25, 0.75, 1.25]), 0.5, 0)
     np.testing.assert_array_equal(q, np.array([127, -128, 0, 2, 2], np.int8))
+    # a NaN takes the code of the real value zero (reading), infinities saturate
+    q = oracle.quantize(np.array([float("nan"), float("inf"), float("-inf")]), 0.5, -7)
+    np.testing.assert_array_equal(q, np.array([-7, 127, -128], np.int8))
 
 
 def pin_int_accumulator_vs_real_domain():

@@ -96,6 +96,74 @@ def test_quant_errors():
     assert e.value.status == 3
 
 
+def test_accumulator_bound_counts_the_offsets():
+    """|x - x_off| reaches 128 + |x_off| and |w - w_off| reaches 128 + |w_off| (Section 4.1: codes and offsets
+    in [-128, 127]), so the depth an int32 accumulator can take depends on both offsets."""
+    ok = glowmi.QParam(0.1, 0)
+
+    def status(K, x_off, w_off):
+        try:
+            glowmi.qfc(FAKE, glowmi.QParam(0.1, x_off), FAKE, glowmi.QParam(0.1, w_off), None, FAKE, ok, 4, K, 4, stream=0)
+        except glowmi.GlowmiError as e:
+            return e.status, str(e)
+        return 0, ""
+
+    # symmetric filter, small activation offset: the deepest supported reduction is accepted (the call
+    # then fails at the launch, there is no GPU behind the fake pointers, or succeeds in validation)
+    assert status(65535, 20, 0)[0] in (0, 6)
+    # extreme offsets: 255 * 255 * K must stay below 2^31 - 2^27
+    limit = ((1 << 31) - (1 << 27)) // (255 * 255)
+    assert status(limit, 127, 127)[0] in (0, 6)
+    st, msg = status(limit + 1, 127, 127)
+    assert st == 3 and "int32 accumulator" in msg
+    st, msg = status(33026, -127, 127)              # the depth from which 255 * 255 * K can pass 2^31
+    assert st == 3
+    st, msg = status(40000, 0, -128)                # 128 * 256 * 40000 = 1.3e9: fine
+    assert st in (0, 6)
+    st, msg = status(65535, 127, 0)                 # 255 * 128 * 65535 = 2.139e9 > 2^31 - 2^27
+    assert st == 3
+
+
+def test_addend_multiplier_is_bounded():
+    """A rescaled addend term must fit the accumulator: multipliers of 2^19 and above are rejected."""
+    d = _desc()
+    x, w = glowmi.QParam(2.0 ** -10, 0), glowmi.QParam(2.0 ** -10, 0)        # accumulator scale 2^-20
+    y = glowmi.QParam(0.1, 0)
+    for r_scale, want in ((2.0 ** -2, (0, 6)), (0.9, (5,))):                 # multipliers 2^18 and 0.9 * 2^20
+        try:
+            glowmi.qconv2d_chain(FAKE, x, FAKE, w, None, FAKE, y, d, addend=FAKE + (1 << 20),
+                                 addend_q=glowmi.QParam(r_scale, 0), stream=0)
+            st = 0
+        except glowmi.GlowmiError as e:
+            st = e.status
+        assert st in want, (r_scale, st)
+
+
+def test_tuning_knobs():
+    glowmi.tuning_reset()
+    base = glowmi.fc_workspace_bytes(64, 4096, 4096)
+    glowmi.tuning_set("F32_TILE", 2)
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.tuning_set("NO_SUCH_KNOB", 1)
+    assert e.value.status == 3
+    # a forced split beyond what the slabs allow is clamped, and the workspace query follows the knob
+    glowmi.tuning_set("F32_TILE", 0)
+    glowmi.tuning_set("F32_SPLIT", 1000000)
+    forced = glowmi.fc_workspace_bytes(64, 4096, 4096)
+    assert forced > 0 and forced <= 256 * 64 * 4096 * 4
+    glowmi.tuning_reset()
+    assert glowmi.fc_workspace_bytes(64, 4096, 4096) == base
+
+
+def test_binding_checks_tensors_before_the_call():
+    """A tensor on the wrong device, of the wrong type, non-contiguous or too small never reaches the library."""
+    import torch
+    d = _desc()
+    x = torch.zeros(1 * 8 * 8 * 4)
+    with pytest.raises(ValueError, match="device tensor"):
+        glowmi.conv2d(x, FAKE, None, FAKE, d, stream=0)
+
+
 def test_requant_params_match_oracle():
     rng = np.random.default_rng(6)
     for _ in range(2000):
@@ -189,6 +257,17 @@ def test_sequence_planning_and_errors():
     short = glowmi.seq_layers([(d1, FAKE, None, 1, True)])                              # shortcut shape mismatch
     assert lib.glowmi_seq_conv2d(FAKE, short, 1, FAKE, FAKE, 1 << 20, 0) == 2
     assert lib.glowmi_seq_conv2d(None, arr, 3, FAKE, FAKE, need, 0) == 1
+    assert lib.glowmi_last_error()                                                      # planning errors leave a message
+    # a bad layer in the middle is found before anything is launched: the status is the validation
+    # error (5), not a launch failure on the fake pointers (6)
+    okq, badq = glowmi.QParam(0.1, 0), glowmi.QParam(-1.0, 0)
+    arrq = glowmi.seq_layers([(d1, FAKE, None, 1, False, okq, okq), (d2, FAKE, None, 1, False, badq, okq),
+                              (d3, FAKE, None, 1, True, okq, okq)])
+    needq = glowmi.seq_arena_bytes(arrq, True)
+    assert lib.glowmi_seq_qconv2d(FAKE, okq, arrq, 3, FAKE, FAKE, needq, 0) == 5
+    assert b"scale" in lib.glowmi_last_error()
+    misaligned = glowmi.seq_layers([(d1, FAKE, None, 1, False), (d2, FAKE + 4, None, 1, False), (d3, FAKE, None, 1, True)])
+    assert lib.glowmi_seq_conv2d(FAKE, misaligned, 3, FAKE, FAKE, need, 0) == 4
 
 
 def test_workspace_queries_are_pure():

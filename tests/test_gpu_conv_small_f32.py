@@ -82,9 +82,9 @@ SPLIT_CONV = [
 
 
 @pytest.mark.parametrize("i", range(len(SPLIT_CONV)))
-def test_conv2d_small_f32_split(i, monkeypatch):
+def test_conv2d_small_f32_split(i, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_F32_SMALL_MIN_WGS", "1")     # take the sliced form at any size
+    knobs.set("F32_SMALL_MIN_WGS", "1")     # take the sliced form at any size
     n, h, w, c, k, r, s, st, pd = SPLIT_CONV[i]
     rng = np.random.default_rng(9750 + i)
     x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)

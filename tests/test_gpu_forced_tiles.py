@@ -31,9 +31,9 @@ FC = [(130, 272, 144), (5, 64, 16), (33, 4096, 64), (70, 100, 36)]
 
 @pytest.mark.parametrize("i", range(len(CONV)))
 @pytest.mark.parametrize("tile", ["0", "1", "2", "3", "4", "5"])
-def test_conv2d_f32_forced_tile(i, tile, monkeypatch):
+def test_conv2d_f32_forced_tile(i, tile, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_F32_TILE", tile)
+    knobs.set("F32_TILE", tile)
     n, h, w, c, k, r, s, st, pd, g = CONV[i]
     layer = wl.ConvLayer(f"forced{i}", n, h, w, c, k, r, s, 1, 0, g)
     x, wt, b = wl.conv_inputs_f32(layer, 9100 + i, dist="uniform")
@@ -47,9 +47,9 @@ def test_conv2d_f32_forced_tile(i, tile, monkeypatch):
 
 @pytest.mark.parametrize("shape", FC, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("tile", ["0", "1", "2", "3", "4", "5"])
-def test_fc_f32_forced_tile(shape, tile, monkeypatch):
+def test_fc_f32_forced_tile(shape, tile, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_F32_TILE", tile)
+    knobs.set("F32_TILE", tile)
     M, K, N = shape
     a, w, b = wl.fc_inputs_f32(wl.FcLayer("forced", M, K, N), 9200 + M + K + N, dist="uniform_fan_in")
     ref = oracle.fc_f32(a, w, b, act=wl.ACT_NONE)
@@ -62,9 +62,9 @@ def test_fc_f32_forced_tile(shape, tile, monkeypatch):
 @pytest.mark.parametrize("i", range(len(CONV)))
 @pytest.mark.parametrize("tile", ["0", "1", "2", "3"])
 @pytest.mark.parametrize("w_off", [0, -7])
-def test_qconv2d_forced_tile(i, tile, w_off, monkeypatch):
+def test_qconv2d_forced_tile(i, tile, w_off, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_TILE", tile)
+    knobs.set("I8_TILE", tile)
     n, h, w, c, k, r, s, st, pd, g = CONV[i]
     layer = wl.ConvLayer(f"forced{i}", n, h, w, c, k, r, s, 1, 0, g)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 9300 + i, dist="uniform", w_off=w_off)
@@ -79,9 +79,9 @@ def test_qconv2d_forced_tile(i, tile, w_off, monkeypatch):
 
 @pytest.mark.parametrize("shape", FC, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("tile", ["0", "1", "2", "3"])
-def test_qfc_forced_tile(shape, tile, monkeypatch):
+def test_qfc_forced_tile(shape, tile, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_TILE", tile)
+    knobs.set("I8_TILE", tile)
     M, K, N = shape
     aq, wq, bq, qp = wl.fc_inputs_q(wl.FcLayer("forced", M, K, N), 9400 + M + K + N, dist="normal", w_off=2)
     ref = oracle.qfc(aq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off, act=wl.ACT_NONE)

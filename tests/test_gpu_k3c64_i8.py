@@ -38,21 +38,23 @@ K3_SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("i", range(len(K3_SHAPES)))
+# "gather" forced only where the planner would not take it anyway (stride 1)
+K3_CASES = [(i, form) for i in range(len(K3_SHAPES)) for form in ("2d", "gather")
+            if form == "2d" or K3_SHAPES[i][4] == (1, 1)]
+
+
+@pytest.mark.parametrize("i,form", K3_CASES)
 @pytest.mark.parametrize("dist,x_off", [("normal", None), ("uniform", -9)])
 @pytest.mark.parametrize("waves", ["8", "16"])
-@pytest.mark.parametrize("form", ["2d", "gather"])
-def test_qconv2d_k3c64(i, dist, x_off, waves, form, monkeypatch):
+def test_qconv2d_k3c64(i, form, dist, x_off, waves, knobs):
     """form "2d": the planner's own choice (at stride 1 the form that stages a block's input patch once);
     "gather": the form that gathers per filter row, which the planner takes for other strides only."""
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_K3_MIN_BLOCKS", "1")     # take this kernel at any size
-    monkeypatch.setenv("GLOWMI_I8_K3_WAVES", waves)
+    knobs.set("I8_K3_MIN_BLOCKS", "1")     # take this kernel at any size
+    knobs.set("I8_K3_WAVES", waves)
     n, h, w, k, st, pd = K3_SHAPES[i]
     if form == "gather":
-        if st != (1, 1):
-            pytest.skip("other strides take the gathering form anyway")
-        monkeypatch.setenv("GLOWMI_I8_K3_GATHER", "1")
+        knobs.set("I8_K3_GATHER", "1")
     want_2d = form == "2d" and st == (1, 1)
     layer = wl.ConvLayer(f"k3_{i}", n, h, w, 64, k, 3, 3, 1, 0, 1)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 9500 + i, dist=dist, w_off=0)
@@ -73,12 +75,12 @@ def test_qconv2d_k3c64(i, dist, x_off, waves, form, monkeypatch):
 
 @pytest.mark.parametrize("i", [1, 3, 7, 12])
 @pytest.mark.parametrize("gather", [False, True])
-def test_qconv2d_chain_k3c64(i, gather, monkeypatch):
+def test_qconv2d_chain_k3c64(i, gather, knobs):
     """Tensor-add link of the element-wise chain behind this kernel (both forms), out of place and in place."""
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_K3_MIN_BLOCKS", "1")
+    knobs.set("I8_K3_MIN_BLOCKS", "1")
     if gather:
-        monkeypatch.setenv("GLOWMI_I8_K3_GATHER", "1")
+        knobs.set("I8_K3_GATHER", "1")
     n, h, w, k, st, pd = K3_SHAPES[i]
     layer = wl.ConvLayer(f"k3_{i}", n, h, w, 64, k, 3, 3, 1, 0, 1)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 9600 + i, dist="normal", w_off=0)
@@ -96,10 +98,10 @@ def test_qconv2d_chain_k3c64(i, gather, monkeypatch):
 
 
 @pytest.mark.parametrize("mr_exp", [-1, 1, -3, -8])
-def test_qconv2d_k3c64_multipliers(mr_exp, monkeypatch):
+def test_qconv2d_k3c64_multipliers(mr_exp, knobs):
     """Both requantize forms (64-bit for multipliers from 1/4 up, multiply-high below)."""
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_K3_MIN_BLOCKS", "1")
+    knobs.set("I8_K3_MIN_BLOCKS", "1")
     rng = np.random.default_rng(9700 + mr_exp)
     xq = rng.integers(-4, 5, size=(2, 9, 9, 64), dtype=np.int8)
     wq = rng.integers(-4, 5, size=(48, 3, 3, 64), dtype=np.int8)
@@ -113,7 +115,7 @@ def test_qconv2d_k3c64_multipliers(mr_exp, monkeypatch):
     G.assert_equal_i8(got, ref, f"k3c64 multiplier 0.8*2^{mr_exp}")
 
 
-def test_k3c64_not_taken_with_filter_offset_and_taken_by_the_planner(monkeypatch):
+def test_k3c64_not_taken_with_filter_offset_and_taken_by_the_planner(knobs):
     G = _gpu()
     pd = (1, 1, 1, 1)
     # planner's own choice: 2 x 128 x 128 pixels = 1024 blocks of 32
@@ -126,7 +128,7 @@ def test_k3c64_not_taken_with_filter_offset_and_taken_by_the_planner(monkeypatch
     assert variant.startswith("conv_k3c64_i8"), variant
     G.assert_equal_i8(got, ref, "planner-chosen k3c64")
     # a filter offset other than 0 takes the generic kernels
-    monkeypatch.setenv("GLOWMI_I8_K3_MIN_BLOCKS", "1")
+    knobs.set("I8_K3_MIN_BLOCKS", "1")
     layer = wl.ConvLayer("k3_off", 1, 9, 9, 64, 64, 3, 3, 1, 1, 1)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 9801, dist="normal", w_off=5)
     desc = G.make_desc(xq.shape, wq.shape, (1, 1), pd, 1)

@@ -106,9 +106,9 @@ PW_SHAPES = [
 
 @pytest.mark.parametrize("shape", PW_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_NONE])
-def test_conv2d_f32_pointwise(shape, act, monkeypatch):
+def test_conv2d_f32_pointwise(shape, act, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_F32_PW_MIN_ITEMS", "1")     # take the pointwise kernel at any size
+    knobs.set("F32_PW_MIN_ITEMS", "1")     # take the pointwise kernel at any size
     n, h, w, c, k, st = shape
     rng = np.random.default_rng(4000 + 7 * c + k)
     x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
@@ -124,10 +124,10 @@ def test_conv2d_f32_pointwise(shape, act, monkeypatch):
                        f"pointwise {shape} without bias")
 
 
-def test_conv2d_f32_pointwise_not_taken_with_bottom_padding(monkeypatch):
+def test_conv2d_f32_pointwise_not_taken_with_bottom_padding(knobs):
     """A 1x1 convolution padded at the bottom/right reads outside the image: generic kernel."""
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_F32_PW_MIN_ITEMS", "1")
+    knobs.set("F32_PW_MIN_ITEMS", "1")
     rng = np.random.default_rng(4100)
     x = rng.uniform(-1, 1, size=(1, 9, 9, 64)).astype(np.float32)
     wt = (rng.uniform(-1, 1, size=(64, 1, 1, 64)) / 8).astype(np.float32)
@@ -193,9 +193,9 @@ PWQ_SHAPES = [
 
 @pytest.mark.parametrize("shape", PWQ_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("dist", ["normal", "uniform"])
-def test_qconv2d_pointwise(shape, dist, monkeypatch):
+def test_qconv2d_pointwise(shape, dist, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")      # take the pointwise kernel at any size
+    knobs.set("I8_PW_MIN_ITEMS", "1")      # take the pointwise kernel at any size
     n, h, w, c, k, st = shape
     layer = wl.ConvLayer("pw", n, h, w, c, k, 1, 1, st, 0, 1)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 5000 + 3 * c + k, dist=dist, w_off=0)
@@ -213,10 +213,10 @@ def test_qconv2d_pointwise(shape, dist, monkeypatch):
 
 
 @pytest.mark.parametrize("mr_exp", [-1, 1, -3, -8])
-def test_qconv2d_pointwise_multipliers(mr_exp, monkeypatch):
+def test_qconv2d_pointwise_multipliers(mr_exp, knobs):
     """Both requantize forms of the pointwise kernel (64-bit for multipliers from 1/4 up)."""
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")
+    knobs.set("I8_PW_MIN_ITEMS", "1")
     rng = np.random.default_rng(170 + mr_exp)
     xq = rng.integers(-6, 7, size=(2, 9, 9, 64), dtype=np.int8)
     wq = rng.integers(-5, 6, size=(48, 1, 1, 64), dtype=np.int8)
@@ -230,9 +230,9 @@ def test_qconv2d_pointwise_multipliers(mr_exp, monkeypatch):
     G.assert_equal_i8(got, ref, f"pointwise int8 multiplier 0.8*2^{mr_exp}")
 
 
-def test_qconv2d_pointwise_not_taken_with_filter_offset(monkeypatch):
+def test_qconv2d_pointwise_not_taken_with_filter_offset(knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")
+    knobs.set("I8_PW_MIN_ITEMS", "1")
     layer = wl.ConvLayer("pw", 1, 9, 9, 64, 64, 1, 1, 1, 0, 1)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 5999, dist="normal", w_off=5)
     ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
@@ -334,9 +334,9 @@ def test_conv2d_chain_f32(i, act):
 
 
 @pytest.mark.parametrize("shape", PW_SHAPES, ids=lambda s: "x".join(map(str, s)))
-def test_conv2d_chain_f32_pointwise(shape, monkeypatch):
+def test_conv2d_chain_f32_pointwise(shape, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_F32_PW_MIN_ITEMS", "1")
+    knobs.set("F32_PW_MIN_ITEMS", "1")
     n, h, w, c, k, st = shape
     rng = np.random.default_rng(6100 + 7 * c + k)
     x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
@@ -375,9 +375,9 @@ def test_qconv2d_chain(i, dist, w_off):
 
 
 @pytest.mark.parametrize("shape", PWQ_SHAPES, ids=lambda s: "x".join(map(str, s)))
-def test_qconv2d_chain_pointwise(shape, monkeypatch):
+def test_qconv2d_chain_pointwise(shape, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")
+    knobs.set("I8_PW_MIN_ITEMS", "1")
     n, h, w, c, k, st = shape
     layer = wl.ConvLayer("pw", n, h, w, c, k, 1, 1, st, 0, 1)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 6300 + 3 * c + k, dist="normal", w_off=0)
@@ -444,14 +444,14 @@ def _block_layers(n, hw, c, mid):
 
 
 @pytest.mark.parametrize("n,hw,c,mid", [(2, 9, 32, 8), (3, 14, 256, 64), (1, 28, 128, 64)])
-def test_sequence_f32_bottleneck(n, hw, c, mid, monkeypatch):
+def test_sequence_f32_bottleneck(n, hw, c, mid, knobs):
     """Every layer of the sequence against the oracle fed with the GPU's own previous activation
     (prefix sequences are deterministic), to the single-operator tolerance; plus replays of the
     captured graph against the eager result."""
     import torch
     import paper_1805_00907_amd as glowmi
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_F32_PW_MIN_ITEMS", "1")
+    knobs.set("F32_PW_MIN_ITEMS", "1")
     specs = _block_layers(n, hw, c, mid)
     data = [wl.conv_inputs_f32(s, 8000 + i) for i, s in enumerate(specs)]
     x = data[0][0]
@@ -499,12 +499,12 @@ def test_sequence_f32_bottleneck(n, hw, c, mid, monkeypatch):
 
 
 @pytest.mark.parametrize("n,hw,c,mid", [(2, 9, 32, 16), (3, 14, 256, 64), (1, 28, 128, 64)])
-def test_sequence_int8_bottleneck(n, hw, c, mid, monkeypatch):
+def test_sequence_int8_bottleneck(n, hw, c, mid, knobs):
     """Integer arithmetic end to end: the whole block must match the oracle's chain bit for bit."""
     import torch
     import paper_1805_00907_amd as glowmi
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_PW_MIN_ITEMS", "1")
+    knobs.set("I8_PW_MIN_ITEMS", "1")
     specs = _block_layers(n, hw, c, mid)
     data = [wl.conv_inputs_q(s, 8100 + i) for i, s in enumerate(specs)]
     xq = data[0][0]

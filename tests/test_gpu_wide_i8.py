@@ -35,9 +35,9 @@ WIDE_CONV = [
 @pytest.mark.parametrize("i", range(len(WIDE_CONV)))
 @pytest.mark.parametrize("tile", ["4", "5"])
 @pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", -7)])
-def test_qconv2d_wide(i, tile, dist, w_off, monkeypatch):
+def test_qconv2d_wide(i, tile, dist, w_off, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_TILE", tile)
+    knobs.set("I8_TILE", tile)
     n, h, w, c, k, r, s, st, pd, g = WIDE_CONV[i]
     layer = wl.ConvLayer(f"wide{i}", n, h, w, c, k, r, s, 1, 0, g)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 8000 + i, dist=dist, w_off=w_off)
@@ -63,9 +63,9 @@ WIDE_FC = [(130, 272, 144), (5, 64, 16), (256, 1040, 528), (33, 4096, 64), (300,
 
 @pytest.mark.parametrize("shape", WIDE_FC, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", 3)])
-def test_qfc_wide(shape, dist, w_off, monkeypatch):
+def test_qfc_wide(shape, dist, w_off, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_TILE", "4")
+    knobs.set("I8_TILE", "4")
     M, K, N = shape
     layer = wl.FcLayer("wide", M, K, N)
     aq, wq, bq, qp = wl.fc_inputs_q(layer, 8100 + M + K + N, dist=dist, w_off=w_off)
@@ -78,10 +78,10 @@ def test_qfc_wide(shape, dist, w_off, monkeypatch):
 
 
 @pytest.mark.parametrize("i", [0, 1, 3, 8])
-def test_qconv2d_chain_wide(i, monkeypatch):
+def test_qconv2d_chain_wide(i, knobs):
     """Tensor-add link of the element-wise chain behind the wide kernel, out of place and in place."""
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_TILE", "4")
+    knobs.set("I8_TILE", "4")
     n, h, w, c, k, r, s, st, pd, g = WIDE_CONV[i]
     layer = wl.ConvLayer(f"wide{i}", n, h, w, c, k, r, s, 1, 0, g)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 8200 + i, dist="normal", w_off=0)
@@ -100,10 +100,10 @@ def test_qconv2d_chain_wide(i, monkeypatch):
 
 
 @pytest.mark.parametrize("mr_exp", [-1, 1, -3, -8])
-def test_qfc_wide_multipliers(mr_exp, monkeypatch):
+def test_qfc_wide_multipliers(mr_exp, knobs):
     """Both requantize forms (64-bit for multipliers from 1/4 up, multiply-high below)."""
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_TILE", "4")
+    knobs.set("I8_TILE", "4")
     rng = np.random.default_rng(8300 + mr_exp)
     aq = rng.integers(-4, 5, size=(70, 192), dtype=np.int8)
     wf = rng.integers(-4, 5, size=(192, 144), dtype=np.int8)
@@ -135,12 +135,12 @@ def test_wide_kernel_is_the_planner_choice_for_large_contractions():
 @pytest.mark.parametrize("i", [0, 1, 3, 5, 8])
 @pytest.mark.parametrize("tile", ["4", "5"])
 @pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", -7)])
-def test_qconv2d_wide_two_buffers(i, tile, dist, w_off, monkeypatch):
+def test_qconv2d_wide_two_buffers(i, tile, dist, w_off, knobs):
     """The two-buffer form (built for two workgroups per CU, at most 128 registers) on the same shapes:
     the launcher takes it by itself only for grids larger than the chip, here it is forced."""
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_TILE", tile)
-    monkeypatch.setenv("GLOWMI_I8_WIDE_NBUF", "2")
+    knobs.set("I8_TILE", tile)
+    knobs.set("I8_WIDE_NBUF", "2")
     n, h, w, c, k, r, s, st, pd, g = WIDE_CONV[i]
     layer = wl.ConvLayer(f"wide{i}", n, h, w, c, k, r, s, 1, 0, g)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 8500 + i, dist=dist, w_off=w_off)
@@ -155,10 +155,10 @@ def test_qconv2d_wide_two_buffers(i, tile, dist, w_off, monkeypatch):
 
 @pytest.mark.parametrize("shape", [(130, 272, 144), (256, 1040, 528), (300, 2048, 1008)], ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", 3)])
-def test_qfc_wide_two_buffers(shape, dist, w_off, monkeypatch):
+def test_qfc_wide_two_buffers(shape, dist, w_off, knobs):
     G = _gpu()
-    monkeypatch.setenv("GLOWMI_I8_TILE", "4")
-    monkeypatch.setenv("GLOWMI_I8_WIDE_NBUF", "2")
+    knobs.set("I8_TILE", "4")
+    knobs.set("I8_WIDE_NBUF", "2")
     M, K, N = shape
     layer = wl.FcLayer("wide", M, K, N)
     aq, wq, bq, qp = wl.fc_inputs_q(layer, 8600 + M + K + N, dist=dist, w_off=w_off)
