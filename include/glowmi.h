@@ -103,6 +103,23 @@ glowmi_status glowmi_fc(const float* a, const float* w, const float* bias, float
 size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N);
 
 /*
+ * glowmi_fc for callers that cannot allocate and have no workspace to hand over: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels and
+ * results as glowmi_fc called with a workspace of glowmi_fc_workspace_bytes(); the split-reduction
+ * partial sums go to a buffer that is part of the library image (a static array in device memory of
+ * glowmi_fc_noalloc_max_scratch_bytes() = 8 MiB, one copy per GPU the library is used on, held until
+ * the process ends).  The call allocates nothing and calls no allocating routine.
+ *   - A shape whose partial sums need more than that (glowmi_fc_workspace_bytes(M, K, N) above the
+ *     maximum) is rejected with GLOWMI_ERR_UNSUPPORTED and a message; nothing is launched.
+ *   - Every call on one GPU shares that GPU's buffer: calls must be ordered on one stream (or otherwise
+ *     serialised); calls that overlap on one GPU race.  Nothing in the buffer needs to start at zero
+ *     (every partial sum is written before it is read), so its stale contents are harmless.
+ */
+glowmi_status glowmi_fc_noalloc(const float* a, const float* w, const float* bias, float* y, int32_t M,
+                                int32_t K, int32_t N, glowmi_act act, hipStream_t stream);
+size_t glowmi_fc_noalloc_max_scratch_bytes(void);
+
+/*
  * Quantized Convolution (Section 4.1 tensor type; Section 4.3: the rescale to the output range is
  * folded into the operation, and Relu is a plain integer max because both sides share a scale).
  *   acc   = sum over taps inside the image of (x - xq.offset) * (w - wq.offset)  + bias     (int32)

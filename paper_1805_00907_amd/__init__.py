@@ -19,6 +19,8 @@ from .binding import (  # noqa: F401
     conv_out_shape,
     dequantize,
     fc,
+    fc_noalloc,
+    fc_noalloc_max_scratch_bytes,
     fc_workspace_bytes,
     fold_batchnorm,
     last_variant,

@@ -72,6 +72,9 @@ def library() -> ctypes.CDLL:
     L.glowmi_fc.argtypes = [vp, vp, vp, vp, i32, i32, i32, ctypes.c_int, vp, sz, vp]
     L.glowmi_fc_workspace_bytes.argtypes = [i32, i32, i32]
     L.glowmi_fc_workspace_bytes.restype = sz
+    L.glowmi_fc_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, i32, ctypes.c_int, vp]
+    L.glowmi_fc_noalloc_max_scratch_bytes.argtypes = []
+    L.glowmi_fc_noalloc_max_scratch_bytes.restype = sz
     L.glowmi_tuning_set.argtypes = [ctypes.c_char_p, i32]
     L.glowmi_tuning_reset.argtypes = []
     L.glowmi_tuning_reset.restype = None
@@ -187,6 +190,17 @@ def fc(a, w, bias, y, M: int, K: int, N: int, act: int = ACT_NONE, workspace=Non
     _check(library().glowmi_fc(_ptr(a, "float32", M * K, "a"), _ptr(w, "float32", K * N, "w"),
                                _ptr(bias, "float32", N, "bias"), _ptr(y, "float32", M * N, "y"), M, K, N, act, wp,
                                wb, _stream(stream)))
+
+
+def fc_noalloc(a, w, bias, y, M: int, K: int, N: int, act: int = ACT_NONE, stream=None) -> None:
+    """glowmi_fc without a workspace argument and without any allocation (library-owned static scratch)."""
+    _check(library().glowmi_fc_noalloc(_ptr(a, "float32", M * K, "a"), _ptr(w, "float32", K * N, "w"),
+                                       _ptr(bias, "float32", N, "bias"), _ptr(y, "float32", M * N, "y"), M, K, N,
+                                       act, _stream(stream)))
+
+
+def fc_noalloc_max_scratch_bytes() -> int:
+    return int(library().glowmi_fc_noalloc_max_scratch_bytes())
 
 
 def tuning_set(name: str, value: int) -> None:

@@ -276,6 +276,40 @@ glowmi_status setup_fc_f32(const float* a, const float* w, const float* bias, fl
   return GLOWMI_OK;
 }
 
+// ---- the scratch buffer of the entry point that allocates nothing (glowmi_fc_noalloc) --------------
+// One copy per GPU, held until the process ends.  In host code the array's name is only a stand-in: the
+// device address comes from hipGetSymbolAddress, once per device, and is what the kernels are given.
+constexpr size_t kScratchBytes = 8u << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+struct ScratchSlot {
+  std::once_flag once;
+  hipError_t status = hipErrorNotInitialized;
+  void* ptr = nullptr;
+};
+ScratchSlot g_scratch_slots[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up on the first call there).
+hipError_t scratch_pointer(void** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  ScratchSlot& slot = g_scratch_slots[dev];
+  std::call_once(slot.once, [&slot]() {
+    void* p = nullptr;
+    slot.status = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    slot.ptr = slot.status == hipSuccess ? p : nullptr;
+  });
+  if (slot.status != hipSuccess) return slot.status;
+  if (!slot.ptr) return hipErrorInvalidSymbol;
+  *out = slot.ptr;
+  return hipSuccess;
+}
 }  // namespace
 
 namespace glowmi {
@@ -400,6 +434,29 @@ glowmi_status glowmi_fc(const float* a, const float* w, const float* bias, float
   glowmi_status st = setup_fc_f32(a, w, bias, y, M, K, N, act, p);
   if (st != GLOWMI_OK) return st;
   const glowmi::Plan plan = plan_with_workspace(p, glowmi::plan_f32, workspace, workspace_bytes);
+  const char* variant = "";
+  return finish(glowmi::launch_f32(p, plan, stream, &variant), variant);
+}
+
+size_t glowmi_fc_noalloc_max_scratch_bytes(void) { return kScratchBytes; }
+
+glowmi_status glowmi_fc_noalloc(const float* a, const float* w, const float* bias, float* y, int32_t M,
+                                int32_t K, int32_t N, glowmi_act act, hipStream_t stream) {
+  glowmi::Problem p;
+  glowmi_status st = setup_fc_f32(a, w, bias, y, M, K, N, act, p);
+  if (st != GLOWMI_OK) return st;
+  const glowmi::Plan plan = glowmi::plan_f32(p, true);      // the same plan glowmi_fc takes with a full workspace
+  const size_t need = split_bytes(plan, p);
+  if (need > kScratchBytes)
+    return fail(GLOWMI_ERR_UNSUPPORTED,
+                "FullyConnected %d x %d x %d needs %zu bytes of split-reduction scratch, more than the %zu the "
+                "library's static buffer holds: use glowmi_fc with a workspace", M, K, N, need, kScratchBytes);
+  if (need > 0) {
+    void* ptr = nullptr;
+    const hipError_t e = scratch_pointer(&ptr);
+    if (e != hipSuccess) return fail(GLOWMI_ERR_HIP, "static scratch buffer unavailable: %s", hipGetErrorString(e));
+    p.partial = ptr;     // every partial sum is written before it is read: nothing needs clearing
+  }
   const char* variant = "";
   return finish(glowmi::launch_f32(p, plan, stream, &variant), variant);
 }

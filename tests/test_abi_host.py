@@ -155,6 +155,19 @@ def test_tuning_knobs():
     assert glowmi.fc_workspace_bytes(64, 4096, 4096) == base
 
 
+def test_fc_noalloc_rejects_what_its_scratch_cannot_hold():
+    cap = glowmi.fc_noalloc_max_scratch_bytes()
+    assert cap == 8 << 20
+    M, K, N = 64, 25088, 4096
+    assert glowmi.fc_workspace_bytes(M, K, N) > cap
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.fc_noalloc(FAKE, FAKE, None, FAKE, M, K, N, stream=0)
+    assert e.value.status == 3 and "scratch" in str(e.value)
+    with pytest.raises(glowmi.GlowmiError) as e:      # the usual validation comes first
+        glowmi.fc_noalloc(FAKE, FAKE + 4, None, FAKE, 4, 4, 4, stream=0)
+    assert e.value.status == 4
+
+
 def test_binding_checks_tensors_before_the_call():
     """A tensor on the wrong device, of the wrong type, non-contiguous or too small never reaches the library."""
     import torch

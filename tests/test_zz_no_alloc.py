@@ -1,0 +1,63 @@
+"""glowmi_fc_noalloc (the entry point that allocates nothing: split-reduction partial sums in a
+static buffer inside the library image) against glowmi_fc with a caller workspace, through the C ABI.
+Two calls in a row share the buffer, the second with a smaller input; a third shape exercises a
+different kernel family (tiled, split through the same buffer).  Same kernels and same plan on both
+sides, so the outputs must agree to the fp32 bar (|a - b| <= 1e-5 + 1e-4 |b|) and are in fact
+expected to be identical; both are also held to the oracle.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_1805_00907_amd import workloads as wl
+
+
+def _run_both(M, K, N, seed, act):
+    import torch
+    import gpu_util as G
+    import paper_1805_00907_amd as glowmi
+    layer = wl.FcLayer("noalloc", M, K, N, act)
+    a, w, b = wl.fc_inputs_f32(layer, seed)
+    need = glowmi.fc_workspace_bytes(M, K, N)
+    assert 0 < need <= glowmi.fc_noalloc_max_scratch_bytes(), "the case must use the scratch buffer"
+    ad, wd, bd = G.dev(a), G.dev(w), G.dev(b)
+    y_ref = G.poison((M, N), torch.float32)
+    glowmi.fc(ad, wd, bd, y_ref, M, K, N, act, G.workspace(need))
+    variant_ref = glowmi.last_variant()
+    y_new = G.poison((M, N), torch.float32)
+    glowmi.fc_noalloc(ad, wd, bd, y_new, M, K, N, act)
+    variant_new = glowmi.last_variant()
+    torch.cuda.synchronize()
+    assert variant_new == variant_ref, (variant_new, variant_ref)
+    got, ref = y_new.cpu().numpy(), y_ref.cpu().numpy()
+    G.assert_close_f32(got, ref, f"fc_noalloc vs fc {M}x{K}x{N} [{variant_new}]")
+    G.assert_close_f32(got, oracle.fc_f32(a, w, b, act=act), f"fc_noalloc vs oracle {M}x{K}x{N} [{variant_new}]")
+    return got, ref
+
+
+def test_fc_noalloc_two_calls_in_a_row_second_smaller():
+    big, big_ref = _run_both(16, 8192, 2048, 4100, wl.ACT_RELU)        # 16 x 8192 x 2048: weight stream, grid split
+    small, small_ref = _run_both(4, 1024, 520, 4101, wl.ACT_NONE)      # smaller: stale partial sums stay behind it
+    np.testing.assert_array_equal(big, big_ref)
+    np.testing.assert_array_equal(small, small_ref)
+    # and the first shape again after the smaller one, then a tiled split-reduction shape
+    again, again_ref = _run_both(16, 8192, 2048, 4100, wl.ACT_RELU)
+    np.testing.assert_array_equal(again, big)
+    _run_both(48, 4096, 256, 4102, wl.ACT_RELU)
+
+
+def test_fc_noalloc_rejects_oversized_and_leaves_output_untouched():
+    import torch
+    import gpu_util as G
+    import paper_1805_00907_amd as glowmi
+    M, K, N = 64, 25088, 4096
+    assert glowmi.fc_workspace_bytes(M, K, N) > glowmi.fc_noalloc_max_scratch_bytes()
+    y = G.poison((8,), torch.float32)
+    with pytest.raises(glowmi.GlowmiError) as e:
+        glowmi.library().glowmi_fc_noalloc     # symbol exists
+        glowmi.fc_noalloc(y.data_ptr(), y.data_ptr(), None, y.data_ptr(), M, K, N, wl.ACT_NONE)
+    assert e.value.status == 3
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(y).all())
