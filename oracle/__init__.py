@@ -27,6 +27,15 @@ ACT_RELU = 1
 
 OK, BAD_SHAPE, BAD_QUANT, ACC_OVERFLOW = 0, 1, 2, 3
 
+# kinds of a general chain's ops (Section 5.2: any run of data-parallel operators is stacked)
+OP_ADD_TENSOR, OP_MUL_SCALAR, OP_MAX_SCALAR, OP_CLIP = 1, 2, 3, 4
+
+
+class ChainOp(ctypes.Structure):
+    """oracle_chain_op: kind; a, b scalars; tensor pointer; the tensor's scale/offset (quantized add)."""
+    _fields_ = [("kind", ctypes.c_int32), ("a", ctypes.c_float), ("b", ctypes.c_float),
+                ("tensor", ctypes.c_void_p), ("t_scale", ctypes.c_float), ("t_offset", ctypes.c_int32)]
+
 
 class OracleError(RuntimeError):
     def __init__(self, code: int, where: str):
@@ -77,6 +86,12 @@ def _bind(path: str) -> ctypes.CDLL:
                                         vp, i64, vp]
     L.oracle_qfc.argtypes = [vp, f32, i32, vp, f32, i32, vp, vp, f32, i32, i64, i64, i64,
                              ctypes.c_int, vp]
+    cp = ctypes.POINTER(ChainOp)
+    L.oracle_conv2d_f32_chain.argtypes = [vp, vp, vp, cp, i32, vp, vp]
+    L.oracle_qconv2d_chain.argtypes = [vp, f32, i32, vp, f32, i32, vp, cp, i32, vp, f32, i32, vp, vp]
+    L.oracle_chain_threshold.argtypes = [f32, ctypes.c_double]
+    L.oracle_chain_threshold.restype = i32
+    L.oracle_fold_batchnorm.argtypes = [vp] * 6 + [f32, i64, i64, vp, vp]
     return L
 
 
@@ -350,14 +365,76 @@ def qfc(aq, a_scale, a_off, wq, w_scale, w_off, bias_q, y_scale, y_off, act=ACT_
 
 def fold_batchnorm(w, bias, gamma, beta, mean, var, eps: float):
     """Batch normalization merged into the preceding convolution (the paper does this before code
-    generation, Section 5.3): y = gamma * (conv - mean) / sqrt(var + eps) + beta becomes a
-    convolution with w' = w * gamma / sqrt(var + eps), b' = (b - mean) * gamma / sqrt(var + eps) + beta.
-    float64 arithmetic, one rounding to float32 at the end.  -> (w', b')"""
-    w64 = np.asarray(w, dtype=np.float32).astype(np.float64)
-    k = w64.shape[0]
-    g, bt, mu, vr = (np.asarray(a, dtype=np.float32).astype(np.float64).reshape(k) for a in (gamma, beta, mean, var))
-    b64 = np.zeros(k) if bias is None else np.asarray(bias, dtype=np.float32).astype(np.float64).reshape(k)
-    scale = g / np.sqrt(vr + np.float64(np.float32(eps)))
-    w_f = w64 * scale.reshape((k,) + (1,) * (w64.ndim - 1))
-    b_f = (b64 - mu) * scale + bt
-    return w_f.astype(np.float32), b_f.astype(np.float32)
+    generation, Section 5.3).  -> (w', b'), float32; the arithmetic is in the C file."""
+    w = _arr(w, np.float32)
+    k = w.shape[0]
+    per = w.size // k
+    g, bt, mu, vr = (_arr(np.asarray(a, dtype=np.float32).reshape(k), np.float32) for a in (gamma, beta, mean, var))
+    b = None if bias is None else _arr(np.asarray(bias, dtype=np.float32).reshape(k), np.float32)
+    w_out, b_out = np.empty_like(w), np.empty((k,), dtype=np.float32)
+    rc = lib().oracle_fold_batchnorm(_ptr(w), _ptr(b), _ptr(g), _ptr(bt), _ptr(mu), _ptr(vr), eps, k, per,
+                                     _ptr(w_out), _ptr(b_out))
+    if rc:
+        raise OracleError(rc, "fold_batchnorm")
+    return w_out, b_out
+
+
+def _chain_ops(ops, yshape, tensor_dtype):
+    """ops: list of ("add", tensor[, scale, offset]) | ("mul", c) | ("max", v) | ("clip", lo, hi).
+    -> (ctypes array, list of arrays kept alive)."""
+    arr = (ChainOp * max(1, len(ops)))()
+    keep = []
+    for i, op in enumerate(ops):
+        kind = op[0]
+        if kind == "add":
+            t = _arr(op[1], tensor_dtype, yshape)
+            keep.append(t)
+            scale, offset = (op[2], op[3]) if len(op) > 2 else (1.0, 0)
+            arr[i] = ChainOp(OP_ADD_TENSOR, 0.0, 0.0, t.ctypes.data, scale, offset)
+        elif kind == "mul":
+            arr[i] = ChainOp(OP_MUL_SCALAR, op[1], 0.0, None, 1.0, 0)
+        elif kind == "max":
+            arr[i] = ChainOp(OP_MAX_SCALAR, op[1], 0.0, None, 1.0, 0)
+        elif kind == "clip":
+            arr[i] = ChainOp(OP_CLIP, op[1], op[2], None, 1.0, 0)
+        else:
+            raise ValueError(kind)
+    return arr, keep
+
+
+def conv2d_f32_chain(x, w, bias, ops, stride=(1, 1), pads=(0, 0, 0, 0), groups=1) -> np.ndarray:
+    """chain(conv + bias): the ops applied in order to every output element (Section 5.2 stacking)."""
+    x = _arr(x, np.float32); w = _arr(w, np.float32)
+    p, yshape = _conv_params(x.shape, w.shape, stride, pads, groups)
+    b = None if bias is None else _arr(bias, np.float32, (w.shape[0],))
+    if min(yshape) <= 0:
+        raise OracleError(BAD_SHAPE, "conv2d_f32_chain")
+    arr, keep = _chain_ops(ops, yshape, np.float32)
+    y = np.empty(yshape, dtype=np.float32)
+    rc = lib().oracle_conv2d_f32_chain(_ptr(x), _ptr(w), _ptr(b), arr, len(ops), _ptr(y), _ptr(p))
+    if rc:
+        raise OracleError(rc, "conv2d_f32_chain")
+    return y
+
+
+def qconv2d_chain(xq, x_scale, x_off, wq, w_scale, w_off, bias_q, ops, y_scale, y_off, stride=(1, 1),
+                  pads=(0, 0, 0, 0), groups=1, return_acc=False):
+    """The quantized chain: ops on the int32 accumulator in order, then one requantize."""
+    xq = _arr(xq, np.int8); wq = _arr(wq, np.int8)
+    p, yshape = _conv_params(xq.shape, wq.shape, stride, pads, groups)
+    b = None if bias_q is None else _arr(bias_q, np.int32, (wq.shape[0],))
+    if min(yshape) <= 0:
+        raise OracleError(BAD_SHAPE, "qconv2d_chain")
+    arr, keep = _chain_ops(ops, yshape, np.int8)
+    y = np.empty(yshape, dtype=np.int8)
+    acc = np.empty(yshape, dtype=np.int32) if return_acc else None
+    rc = lib().oracle_qconv2d_chain(_ptr(xq), x_scale, x_off, _ptr(wq), w_scale, w_off, _ptr(b), arr, len(ops),
+                                    _ptr(y), y_scale, y_off, _ptr(p), _ptr(acc))
+    if rc:
+        raise OracleError(rc, "qconv2d_chain")
+    return (y, acc) if return_acc else y
+
+
+def chain_threshold(v: float, s: float) -> int:
+    """A real max/clip bound v on an accumulator grid of step s: floor(v / s + 0.5), saturated to int32."""
+    return int(lib().oracle_chain_threshold(v, s))

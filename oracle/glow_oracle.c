@@ -24,6 +24,12 @@
  *                              code-generation figure of Section 5.3): Y = act(conv + bias + addend).
  *                              Quantized: the addend is rescaled (Section 4.3 rescale node) to the
  *                              accumulator's scale sx*sw and added before the one requantize.
+ *   - general chains         : Section 5.2 again: ANY run of data-parallel operators behind the
+ *                              contraction is stacked.  oracle_conv2d_f32_chain / oracle_qconv2d_chain
+ *                              apply a list of {add tensor, multiply by scalar, max with scalar, clip}
+ *                              in the order given.
+ *   - batch-norm fold        : Section 5.3 (batch normalization is merged into the convolution
+ *                              that precedes it before code is generated).
  *
  * Readings taken where the paper is silent (all listed in the design notes of the repository):
  *   cross-correlation (no filter flip); zero padding in the real domain; floor in the output-size
@@ -31,7 +37,11 @@
  *   and offset 0; requantization multiplier sx*sw/sy represented as m * 2^-sh with a 31-bit
  *   mantissa, rounding half up; saturation to [-128, 127]; a quantized addend (scale sr, offset
    r_off) enters the int32 accumulator as round_half_up((r - r_off) * sr / (sx*sw)) with the same
-   mantissa/shift representation of sr/(sx*sw).
+   mantissa/shift representation of sr/(sx*sw).  A general quantized chain runs on the int32
+ *   accumulator, whose real value is acc * s with s = sx*sw at first: a scalar multiply by c > 0
+ *   changes s to s*c and leaves the integer alone (exact); max / clip thresholds are rounded half up
+ *   to the accumulator's grid, T = floor(v / s + 0.5); an added tensor is rescaled to the current s;
+ *   the one requantize at the end uses s_final / sy.
  *
  * Floating point: every sum is accumulated in double in the loop order written here and rounded
  * once to float.  Integer: sums are accumulated in 64-bit and must fit 32-bit (checked).
@@ -451,4 +461,180 @@ int oracle_qfc(const int8_t *a, float sa, int32_t a_off, const int8_t *w, float 
       if (y) y[m * N + n] = (int8_t)oracle_requantize((int32_t)s, mant, shift, y_off, lo);
     }
   return overflow ? ORACLE_ACC_OVERFLOW : ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * General element-wise chains behind the contraction (Section 5.2: operator stacking of consecutive
+ * data-parallel operators).  An op list is applied in the order given to every output element.
+ * ---------------------------------------------------------------------------------------------- */
+enum { ORACLE_OP_ADD_TENSOR = 1, ORACLE_OP_MUL_SCALAR = 2, ORACLE_OP_MAX_SCALAR = 3, ORACLE_OP_CLIP = 4 };
+
+typedef struct {
+  int32_t kind;          /* ORACLE_OP_*                                                        */
+  float a, b;            /* MUL: factor a; MAX: threshold a; CLIP: bounds a <= b                */
+  const void *tensor;    /* ADD_TENSOR: [n][oh][ow][k] like the output (float, or int8 codes)   */
+  float t_scale;         /* quantized ADD_TENSOR: the tensor's scale                            */
+  int32_t t_offset;      /*                       and offset                                    */
+} oracle_chain_op;
+
+/* fp32: y = chain(conv + bias), every step in double, one rounding at the end. */
+int oracle_conv2d_f32_chain(const float *x, const float *w, const float *bias, const oracle_chain_op *ops,
+                            int32_t n_ops, float *y, const int64_t *p) {
+  conv_shape cs;
+  int rc = conv_shape_init(&cs, p);
+  if (rc) return rc;
+  if (n_ops < 0 || (n_ops > 0 && !ops)) return ORACLE_BAD_SHAPE;
+  for (int32_t i = 0; i < n_ops; ++i) {
+    if (ops[i].kind < ORACLE_OP_ADD_TENSOR || ops[i].kind > ORACLE_OP_CLIP) return ORACLE_BAD_SHAPE;
+    if (ops[i].kind == ORACLE_OP_ADD_TENSOR && !ops[i].tensor) return ORACLE_BAD_SHAPE;
+    if (ops[i].kind == ORACLE_OP_CLIP && !(ops[i].a <= ops[i].b)) return ORACLE_BAD_SHAPE;
+  }
+#pragma omp parallel for collapse(2) schedule(static)
+  for (int64_t n = 0; n < cs.n; ++n)
+    for (int64_t oh = 0; oh < cs.oh; ++oh)
+      for (int64_t ow = 0; ow < cs.ow; ++ow)
+        for (int64_t k = 0; k < cs.k; ++k) {
+          const int64_t o = ((n * cs.oh + oh) * cs.ow + ow) * cs.k + k;
+          /* the contraction and the bias exactly as in conv_f32_one, kept in double */
+          const int64_t cg = cs.c / cs.groups, kg = cs.k / cs.groups, g = k / kg;
+          double v = 0.0;
+          for (int64_t r = 0; r < cs.r; ++r) {
+            const int64_t ih = oh * cs.stride_h - cs.pad_t + r;
+            if (ih < 0 || ih >= cs.h) continue;
+            for (int64_t s = 0; s < cs.s; ++s) {
+              const int64_t iw = ow * cs.stride_w - cs.pad_l + s;
+              if (iw < 0 || iw >= cs.w) continue;
+              for (int64_t cc = 0; cc < cg; ++cc)
+                v += (double)x[((n * cs.h + ih) * cs.w + iw) * cs.c + g * cg + cc] *
+                     (double)w[((k * cs.r + r) * cs.s + s) * cg + cc];
+            }
+          }
+          if (bias) v += (double)bias[k];
+          for (int32_t i = 0; i < n_ops; ++i) {
+            const oracle_chain_op *op = &ops[i];
+            if (op->kind == ORACLE_OP_ADD_TENSOR) v += (double)((const float *)op->tensor)[o];
+            else if (op->kind == ORACLE_OP_MUL_SCALAR) v *= (double)op->a;
+            else if (op->kind == ORACLE_OP_MAX_SCALAR) { if (v < (double)op->a) v = (double)op->a; }
+            else { if (v < (double)op->a) v = (double)op->a; if (v > (double)op->b) v = (double)op->b; }
+          }
+          y[o] = (float)v;
+        }
+  return ORACLE_OK;
+}
+
+/* A positive real multiplier as mant * 2^-shift, mant in [2^30, 2^31), shift in [1, 62]. */
+static int multiplier_to_fixed(double mr, int32_t *mant, int32_t *shift) {
+  if (!(mr > 0.0) || isinf(mr)) return ORACLE_BAD_QUANT;
+  int e = 0;
+  const double f = frexp(mr, &e);
+  int64_t m = llround(f * 2147483648.0);
+  if (m == 2147483648LL) { m = 1073741824LL; e += 1; }
+  const int sh = 31 - e;
+  if (sh < 1 || sh > 62) return ORACLE_BAD_QUANT;
+  *mant = (int32_t)m;
+  *shift = (int32_t)sh;
+  return ORACLE_OK;
+}
+
+/* A real threshold v on the accumulator's grid of step s: floor(v / s + 0.5), saturated to int32. */
+int32_t oracle_chain_threshold(float v, double s) {
+  const double t = floor((double)v / s + 0.5);
+  if (t != t) return 0;
+  if (t <= -2147483648.0) return INT32_MIN;
+  if (t >= 2147483647.0) return INT32_MAX;
+  return (int32_t)t;
+}
+
+/* Quantized: the chain on the int32 accumulator (see the readings at the top), then one requantize.
+ * acc_out (may be NULL) receives the accumulator after the chain. */
+int oracle_qconv2d_chain(const int8_t *x, float sx, int32_t x_off, const int8_t *w, float sw, int32_t w_off,
+                         const int32_t *bias, const oracle_chain_op *ops, int32_t n_ops, int8_t *y, float sy,
+                         int32_t y_off, const int64_t *p, int32_t *acc_out) {
+  conv_shape cs;
+  int rc = conv_shape_init(&cs, p);
+  if (rc) return rc;
+  if (!offsets_ok(x_off, w_off, y_off)) return ORACLE_BAD_QUANT;
+  if (!(sx > 0.0f) || !(sw > 0.0f) || !(sy > 0.0f) || isinf(sx) || isinf(sw) || isinf(sy)) return ORACLE_BAD_QUANT;
+  if (n_ops < 0 || n_ops > 16 || (n_ops > 0 && !ops)) return ORACLE_BAD_SHAPE;
+  /* per-op integer parameters, from the scale the accumulator has when the op is reached */
+  int32_t t_lo[16], t_hi[16], a_mant[16], a_shift[16];
+  double s = (double)sx * (double)sw;
+  for (int32_t i = 0; i < n_ops; ++i) {
+    const oracle_chain_op *op = &ops[i];
+    t_lo[i] = t_hi[i] = a_mant[i] = 0; a_shift[i] = 1;
+    if (op->kind == ORACLE_OP_ADD_TENSOR) {
+      if (!op->tensor || op->t_offset < -128 || op->t_offset > 127) return ORACLE_BAD_QUANT;
+      if (!(op->t_scale > 0.0f) || isinf(op->t_scale)) return ORACLE_BAD_QUANT;
+      rc = multiplier_to_fixed((double)op->t_scale / s, &a_mant[i], &a_shift[i]);
+      if (rc) return rc;
+    } else if (op->kind == ORACLE_OP_MUL_SCALAR) {
+      if (!(op->a > 0.0f) || isinf(op->a)) return ORACLE_BAD_QUANT;
+      s = s * (double)op->a;
+      if (!(s > 0.0) || isinf(s)) return ORACLE_BAD_QUANT;
+    } else if (op->kind == ORACLE_OP_MAX_SCALAR) {
+      if (op->a != op->a) return ORACLE_BAD_QUANT;
+      t_lo[i] = oracle_chain_threshold(op->a, s);
+    } else if (op->kind == ORACLE_OP_CLIP) {
+      if (!(op->a <= op->b)) return ORACLE_BAD_QUANT;
+      t_lo[i] = oracle_chain_threshold(op->a, s);
+      t_hi[i] = oracle_chain_threshold(op->b, s);
+    } else {
+      return ORACLE_BAD_SHAPE;
+    }
+  }
+  int32_t mant = 0, shift = 0;
+  rc = multiplier_to_fixed(s / (double)sy, &mant, &shift);
+  if (rc) return rc;
+  int overflow = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : overflow)
+  for (int64_t n = 0; n < cs.n; ++n)
+    for (int64_t oh = 0; oh < cs.oh; ++oh)
+      for (int64_t ow = 0; ow < cs.ow; ++ow)
+        for (int64_t k = 0; k < cs.k; ++k) {
+          const int64_t o = ((n * cs.oh + oh) * cs.ow + ow) * cs.k + k;
+          int32_t a32 = 0;
+          if (qconv_acc_one(x, x_off, w, w_off, bias, 0, &cs, n, oh, ow, k, &a32)) { overflow |= 1; continue; }
+          int64_t a = a32;
+          int bad = 0;
+          for (int32_t i = 0; i < n_ops; ++i) {
+            const oracle_chain_op *op = &ops[i];
+            if (op->kind == ORACLE_OP_ADD_TENSOR) {
+              a += oracle_rescale_term((int32_t)((const int8_t *)op->tensor)[o] - op->t_offset, a_mant[i], a_shift[i]);
+              if (a > INT32_MAX || a < INT32_MIN) { bad = 1; break; }
+            } else if (op->kind == ORACLE_OP_MAX_SCALAR) {
+              if (a < t_lo[i]) a = t_lo[i];
+            } else if (op->kind == ORACLE_OP_CLIP) {
+              if (a < t_lo[i]) a = t_lo[i];
+              if (a > t_hi[i]) a = t_hi[i];
+            }                                     /* MUL_SCALAR: nothing happens to the integer */
+          }
+          if (bad) { overflow |= 1; continue; }
+          if (acc_out) acc_out[o] = (int32_t)a;
+          if (y) y[o] = (int8_t)oracle_requantize((int32_t)a, mant, shift, y_off, -128);
+        }
+  return overflow ? ORACLE_ACC_OVERFLOW : ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------------------------------
+ * Batch normalization merged into the convolution in front of it (Section 5.3):
+ *   gamma * (conv(x, w) + b - mean) / sqrt(var + eps) + beta  ==  conv(x, w') + b'
+ *   w'[k][...] = w[k][...] * gamma[k] / sqrt(var[k] + eps)
+ *   b'[k]      = (b[k] - mean[k]) * gamma[k] / sqrt(var[k] + eps) + beta[k]
+ * evaluated in double, rounded once.  per = elements of one filter; bias may be NULL (zeros).
+ * ---------------------------------------------------------------------------------------------- */
+int oracle_fold_batchnorm(const float *w, const float *bias, const float *gamma, const float *beta,
+                          const float *mean, const float *var, float eps, int64_t k, int64_t per, float *w_out,
+                          float *b_out) {
+  if (k <= 0 || per <= 0) return ORACLE_BAD_SHAPE;
+  for (int64_t i = 0; i < k; ++i) {
+    const double denom = (double)var[i] + (double)eps;
+    if (!(denom > 0.0) || isinf(denom)) return ORACLE_BAD_SHAPE;
+  }
+  for (int64_t i = 0; i < k; ++i) {
+    const double scale = (double)gamma[i] / sqrt((double)var[i] + (double)eps);
+    for (int64_t e = 0; e < per; ++e) w_out[i * per + e] = (float)((double)w[i * per + e] * scale);
+    const double b = bias ? (double)bias[i] : 0.0;
+    b_out[i] = (float)((b - (double)mean[i]) * scale + (double)beta[i]);
+  }
+  return ORACLE_OK;
 }

@@ -577,6 +577,218 @@ def pin_qconv_add():
         np.testing.assert_array_equal(same, oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, st, pd, g))
 
 
+
+# ---------------------------------------------------------------------------------------------------
+# general element-wise chains behind the contraction (Section 5.2: any run of data-parallel operators)
+# ---------------------------------------------------------------------------------------------------
+
+def _apply_chain_real(v, ops):
+    """The op list on a float64 array, in order (add tensors are float64 arrays of v's shape)."""
+    v = np.array(v, dtype=np.float64)
+    for op in ops:
+        if op[0] == "add":
+            v = v + np.asarray(op[1], dtype=np.float64)
+        elif op[0] == "mul":
+            v = v * float(np.float32(op[1]))
+        elif op[0] == "max":
+            v = np.maximum(v, float(np.float32(op[1])))
+        elif op[0] == "clip":
+            v = np.minimum(np.maximum(v, float(np.float32(op[1]))), float(np.float32(op[2])))
+    return v
+
+
+def pin_conv_chain_f32():
+    """chain(conv + bias) against the im2col reference with the same ops applied in numpy float64; the
+    order of the ops matters and is respected; degenerate lists reduce to operators pinned above."""
+    rng = np.random.default_rng(41)
+    for (n, h, w, c, k, r, s, st, pd, g) in TINY_SHAPES[:7]:
+        x = _rand(rng, (n, h, w, c)); wt = _rand(rng, (k, r, s, c // g)); b = _rand(rng, (k,))
+        pre = im2col_matmul(x, wt, b, st, pd, g)
+        t1 = (2.0 * _rand(rng, pre.shape)).astype(np.float32); t2 = _rand(rng, pre.shape)
+        lists = [
+            [],
+            [("max", 0.0)],
+            [("add", t1)],
+            [("add", t1), ("max", 0.0)],
+            [("max", 0.0), ("add", t1)],                                  # the other order: a different result
+            [("mul", 0.37), ("add", t1), ("clip", -0.25, 0.6)],
+            [("add", t1), ("mul", -1.5), ("add", t2), ("max", -0.1)],      # fp32 chains take any factor, two tensors
+            [("clip", -0.5, 0.5), ("mul", 3.0), ("clip", -1.0, 1.25), ("add", t2)],
+        ]
+        outs = []
+        for ops in lists:
+            got = oracle.conv2d_f32_chain(x, wt, b, ops, st, pd, g).astype(np.float64)
+            np.testing.assert_allclose(got, _apply_chain_real(pre, ops), rtol=1e-6, atol=1e-6, err_msg=str([o[0] for o in ops]))
+            outs.append(got)
+        if pre.size > 50:
+            assert np.abs(outs[3] - outs[4]).max() > 0.1               # order is not ignored
+        # special cases that reduce to the pinned plain operators, bit for bit
+        np.testing.assert_array_equal(oracle.conv2d_f32_chain(x, wt, b, [], st, pd, g), oracle.conv2d_f32(x, wt, b, st, pd, g))
+        np.testing.assert_array_equal(oracle.conv2d_f32_chain(x, wt, b, [("max", 0.0)], st, pd, g),
+                                      oracle.conv2d_f32(x, wt, b, st, pd, g, act=oracle.ACT_RELU))
+        np.testing.assert_array_equal(oracle.conv2d_f32_chain(x, wt, b, [("add", t1), ("max", 0.0)], st, pd, g),
+                                      oracle.conv2d_f32_add(x, wt, b, t1, st, pd, g, act=oracle.ACT_RELU))
+        # no bias
+        got = oracle.conv2d_f32_chain(x, wt, None, [("mul", 2.0)], st, pd, g).astype(np.float64)
+        np.testing.assert_allclose(got, 2.0 * im2col_matmul(x, wt, None, st, pd, g), rtol=1e-6, atol=1e-6)
+    # closed forms: 1x1 identity filter, y = clip(2 * (x + b) + t, lo, hi); multiply by zero wipes the contraction
+    x = _rand(rng, (2, 4, 3, 5)); b = _rand(rng, (5,)); t = _rand(rng, (2, 4, 3, 5))
+    eye = np.eye(5, dtype=np.float32).reshape(5, 1, 1, 5)
+    got = oracle.conv2d_f32_chain(x, eye, b, [("mul", 2.0), ("add", t), ("clip", -1.0, 1.5)])
+    exp = np.clip(2.0 * (x.astype(np.float64) + b) + t, -1.0, 1.5)
+    np.testing.assert_allclose(got.astype(np.float64), exp, rtol=1e-7, atol=1e-7)
+    got = oracle.conv2d_f32_chain(x, eye, b, [("mul", 0.0), ("add", t)])
+    np.testing.assert_array_equal(got, t)
+    for bad in ([("clip", 1.0, -1.0)],):
+        try:
+            oracle.conv2d_f32_chain(x, eye, b, bad)
+        except oracle.OracleError as e:
+            assert e.code == oracle.BAD_SHAPE
+        else:
+            raise AssertionError("inverted clip bounds accepted")
+
+
+def _exact_threshold(v, s):
+    """floor(v / s + 1/2) in exact rationals (v a float32 value, s a double)."""
+    return math.floor(Fraction(float(np.float32(v))) / Fraction(s) + Fraction(1, 2))
+
+
+def pin_chain_threshold():
+    # hand cases on a power-of-two grid: ties go up, both signs
+    assert [oracle.chain_threshold(v, 0.125) for v in (0.3125, -0.3125, 0.25, -0.25, 0.0, 0.06, -0.07)] == \
+        [3, -2, 2, -2, 0, 0, -1]
+    assert oracle.chain_threshold(1e30, 1e-6) == 2**31 - 1 and oracle.chain_threshold(-1e30, 1e-6) == -2**31
+    rng = np.random.default_rng(42)
+    for _ in range(2000):
+        v = float(np.float32(rng.uniform(-50, 50)))
+        s = float(rng.uniform(1e-5, 0.3))
+        exact = _exact_threshold(v, s)
+        got = oracle.chain_threshold(v, s)
+        # the double quotient is rounded once: it can differ from the exact rule only within 2^-40 of a tie
+        frac = Fraction(v) / Fraction(s) + Fraction(1, 2)
+        near_tie = abs(frac - round(frac)) < Fraction(1, 1 << 40)
+        assert got == exact or near_tie, (v, s, got, exact)
+
+
+def pin_qconv_chain():
+    """The quantized chain composed from parts pinned elsewhere (plain accumulator; exact-rational
+    rescale terms, thresholds and requantize), its special cases that are operators pinned above, and
+    the real-valued rule within one code."""
+    rng = np.random.default_rng(43)
+    for (n, h, w, c, k, r, s, st, pd, g) in TINY_SHAPES[1:7]:
+        xq = rng.integers(-128, 128, size=(n, h, w, c), dtype=np.int8)
+        wq = rng.integers(-40, 41, size=(k, r, s, c // g), dtype=np.int8)
+        bq = rng.integers(-3000, 3000, size=(k,), dtype=np.int32)
+        sx, sw, sy = (float(np.float32(v)) for v in (0.05, 0.01, 0.9 * r * s))
+        sr, sr2 = (float(np.float32(v)) for v in rng.uniform(0.02, 0.2, size=2))
+        x_off, w_off, y_off, r_off, r2_off = (int(v) for v in rng.integers(-20, 21, size=5))
+        _, acc = oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, st, pd, g, return_acc=True)
+        rq = rng.integers(-128, 128, size=acc.shape, dtype=np.int8)
+        rq2 = rng.integers(-128, 128, size=acc.shape, dtype=np.int8)
+        s0 = float(np.float64(sx) * np.float64(sw))          # the accumulator's scale, formed in double
+        real0 = acc.astype(np.float64) * sx * sw
+        span = float(np.abs(real0).max())
+
+        # ---- special cases: operators pinned above, bit for bit
+        np.testing.assert_array_equal(oracle.qconv2d_chain(xq, sx, x_off, wq, sw, w_off, bq, [], sy, y_off, st, pd, g),
+                                      oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, st, pd, g))
+        np.testing.assert_array_equal(
+            oracle.qconv2d_chain(xq, sx, x_off, wq, sw, w_off, bq, [("max", 0.0)], sy, y_off, st, pd, g),
+            oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, st, pd, g, act=oracle.ACT_RELU))
+        for tail, act in (([], oracle.ACT_NONE), ([("max", 0.0)], oracle.ACT_RELU)):
+            np.testing.assert_array_equal(
+                oracle.qconv2d_chain(xq, sx, x_off, wq, sw, w_off, bq, [("add", rq, sr, r_off)] + tail, sy, y_off, st, pd, g),
+                oracle.qconv2d_add(xq, sx, x_off, wq, sw, w_off, bq, rq, sr, r_off, sy, y_off, st, pd, g, act=act))
+        # a multiply by 2^j is the same operator with the output scale divided by 2^j (exact in float)
+        for j in (-2, 1, 3):
+            np.testing.assert_array_equal(
+                oracle.qconv2d_chain(xq, sx, x_off, wq, sw, w_off, bq, [("mul", 2.0 ** j)], sy, y_off, st, pd, g),
+                oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, float(np.float32(sy * 2.0 ** -j)), y_off, st, pd, g))
+
+        # ---- general lists against exact rationals; multipliers with power-of-two factors are exact,
+        # others are held to the tolerance of a 31-bit mantissa
+        lo_v, hi_v = float(np.float32(-0.3 * span)), float(np.float32(0.45 * span))
+        lists = [
+            [("max", lo_v)],
+            [("clip", lo_v, hi_v)],
+            [("add", rq, sr, r_off), ("clip", lo_v, hi_v)],
+            [("clip", lo_v, hi_v), ("add", rq, sr, r_off)],                               # the other order
+            [("mul", 4.0), ("add", rq, sr, r_off), ("max", float(np.float32(0.1 * span)))],
+            [("add", rq, sr, r_off), ("mul", 0.5), ("add", rq2, sr2, r2_off), ("clip", lo_v, hi_v)],
+            [("mul", 0.7321), ("max", 0.0), ("add", rq2, sr2, r2_off)],
+        ]
+        m_plain, sh_plain = oracle.requant_params(sx, sw, sy)
+        outs, accs = [], []
+        for ops in lists:
+            got, acc_after = oracle.qconv2d_chain(xq, sx, x_off, wq, sw, w_off, bq, ops, sy, y_off, st, pd, g,
+                                                  return_acc=True)
+            outs.append(got)
+            accs.append(acc_after)
+            exp_acc = acc.astype(object).reshape(-1).copy()      # python ints
+            s_cur, pow2, exact = s0, 0, True
+            real = real0.copy().reshape(-1)
+            for op in ops:
+                if op[0] == "mul":
+                    cval = float(np.float32(op[1]))
+                    s_cur = float(np.float64(s_cur) * np.float64(cval))
+                    real = real * cval
+                    if cval in (0.5, 4.0):
+                        pow2 += int(math.log2(cval))
+                    else:
+                        exact = False
+                elif op[0] == "add":
+                    t, ts, toff = op[1].reshape(-1), op[2], op[3]
+                    real = real + (t.astype(np.float64) - toff) * ts
+                    ratio = Fraction(ts) / Fraction(s_cur)
+                    if exact:
+                        rm, rsh = oracle.rescale_params(ts, sx, sw)   # pinned; a factor 2^pow2 only moves the shift
+                        rsh += pow2
+                        assert abs(Fraction(rm, 1 << rsh) - ratio) <= ratio / (1 << 30)
+                        exp_acc = np.array([int(a) + _exact_rescale(int(q) - toff, rm, rsh) for a, q in zip(exp_acc, t)],
+                                           dtype=object)
+                    else:
+                        exp_acc = None
+                elif op[0] in ("max", "clip"):
+                    bounds = [float(np.float32(b)) for b in op[1:]]
+                    real = np.maximum(real, bounds[0])
+                    if len(bounds) > 1:
+                        real = np.minimum(real, bounds[1])
+                    if exp_acc is not None:
+                        ts_ = [_exact_threshold(b, s_cur) for b in bounds]
+                        exp_acc = np.array([max(int(a), ts_[0]) for a in exp_acc], dtype=object)
+                        if len(ts_) > 1:
+                            exp_acc = np.array([min(int(a), ts_[1]) for a in exp_acc], dtype=object)
+            if exp_acc is not None:
+                np.testing.assert_array_equal(acc_after.reshape(-1).astype(object), exp_acc, err_msg=str([o[0] for o in ops]))
+                if exact:      # final multiplier = the plain one times 2^pow2
+                    exp = np.array([_exact_requant(int(a), m_plain, sh_plain - pow2, y_off, -128) for a in exp_acc],
+                                   dtype=np.int64)
+                    np.testing.assert_array_equal(got.reshape(-1).astype(np.int64), exp)
+            # the real-valued rule of Section 4.1 on the chain evaluated in real numbers, within one code
+            # (each rescaled tensor term is off by at most half an accumulator step, each bound likewise)
+            realq = real / sy + y_off
+            inside = (realq > -126) & (realq < 126)
+            assert inside.any()
+            assert np.all(np.abs(got.reshape(-1).astype(np.float64) - realq)[inside] <= 1.0 + 1e-6), [o[0] for o in ops]
+        assert (accs[2] != accs[3]).any()                               # order is not ignored
+        # a clipped result lies between the codes of its bounds and equals the unclipped one inside them
+        plain = oracle.qconv2d(xq, sx, x_off, wq, sw, w_off, bq, sy, y_off, st, pd, g).astype(np.int64)
+        clipped = outs[1].astype(np.int64)
+        lo_c = _exact_requant(_exact_threshold(lo_v, s0), m_plain, sh_plain, y_off, -128)
+        hi_c = _exact_requant(_exact_threshold(hi_v, s0), m_plain, sh_plain, y_off, -128)
+        assert clipped.min() >= lo_c and clipped.max() <= hi_c and (clipped == lo_c).any() and (clipped == hi_c).any()
+        inner = (plain > lo_c) & (plain < hi_c)
+        np.testing.assert_array_equal(clipped[inner], plain[inner])
+    for bad_ops, code in (([("mul", 0.0)], oracle.BAD_QUANT), ([("mul", -2.0)], oracle.BAD_QUANT),
+                          ([("clip", 1.0, -1.0)], oracle.BAD_QUANT), ([("add", rq, 0.0, 0)], oracle.BAD_QUANT),
+                          ([("add", rq, 0.1, 200)], oracle.BAD_QUANT)):
+        try:
+            oracle.qconv2d_chain(xq, sx, x_off, wq, sw, w_off, bq, bad_ops, sy, y_off, st, pd, g)
+        except oracle.OracleError as e:
+            assert e.code == code, (bad_ops[0][0], e.code)
+        else:
+            raise AssertionError(f"accepted {bad_ops[0][0]}")
+
 ALL_PINS = [
     pin_shape_examples,
     pin_conv_vs_im2col,
@@ -601,6 +813,9 @@ ALL_PINS = [
     pin_conv_add_f32,
     pin_rescale_params_and_term,
     pin_qconv_add,
+    pin_conv_chain_f32,
+    pin_chain_threshold,
+    pin_qconv_chain,
     pin_rescale_node,
     pin_fold_batchnorm,
 ]

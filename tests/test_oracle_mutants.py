@@ -76,6 +76,38 @@ MUTANTS = [
     ("rescale_node_offset_sign", "(int32_t)in[i] - in_offset", "(int32_t)in[i] + in_offset", None),
     ("rescale_node_wrong_out_offset", "mant, shift, out_offset, -128);", "mant, shift, in_offset, -128);", None),
     ("overflow_unchecked", "if (s > INT32_MAX || s < INT32_MIN) { overflow |= 1; continue; }", "", None),
+    # general chains
+    ("chain_f32_add_dropped", "if (op->kind == ORACLE_OP_ADD_TENSOR) v += (double)((const float *)op->tensor)[o];",
+     "if (op->kind == ORACLE_OP_ADD_TENSOR) v += 0.0;", None),
+    ("chain_f32_order_reversed", "const oracle_chain_op *op = &ops[i];\n            if (op->kind == ORACLE_OP_ADD_TENSOR) v +=",
+     "const oracle_chain_op *op = &ops[n_ops - 1 - i];\n            if (op->kind == ORACLE_OP_ADD_TENSOR) v +=", None),
+    ("chain_f32_mul_adds", "v *= (double)op->a;", "v += (double)op->a;", None),
+    ("chain_f32_max_is_min", "{ if (v < (double)op->a) v = (double)op->a; }", "{ if (v > (double)op->a) v = (double)op->a; }", None),
+    ("chain_f32_clip_upper_ignored", "if (v > (double)op->b) v = (double)op->b; }", "}", None),
+    ("chain_f32_bias_dropped", "if (bias) v += (double)bias[k];", "", None),
+    ("chain_q_order_reversed", "const oracle_chain_op *op = &ops[i];\n            if (op->kind == ORACLE_OP_ADD_TENSOR) {\n              a +=",
+     "const oracle_chain_op *op = &ops[n_ops - 1 - i];\n            if (op->kind == ORACLE_OP_ADD_TENSOR) {\n              a +=", None),
+    ("chain_q_mul_keeps_scale", "s = s * (double)op->a;", "s = s;", None),
+    ("chain_q_mul_divides", "s = s * (double)op->a;", "s = s / (double)op->a;", None),
+    ("chain_q_threshold_truncates", "const double t = floor((double)v / s + 0.5);", "const double t = trunc((double)v / s);", None),
+    ("chain_q_threshold_multiplies", "const double t = floor((double)v / s + 0.5);", "const double t = floor((double)v * s + 0.5);", None),
+    ("chain_q_add_uses_initial_scale", "rc = multiplier_to_fixed((double)op->t_scale / s, &a_mant[i], &a_shift[i]);",
+     "rc = multiplier_to_fixed((double)op->t_scale / ((double)sx * (double)sw), &a_mant[i], &a_shift[i]);", None),
+    ("chain_q_add_offset_sign", "((const int8_t *)op->tensor)[o] - op->t_offset", "((const int8_t *)op->tensor)[o] + op->t_offset", None),
+    ("chain_q_clip_upper_is_lower", "t_hi[i] = oracle_chain_threshold(op->b, s);", "t_hi[i] = oracle_chain_threshold(op->a, s);", None),
+    ("chain_q_max_is_min", "} else if (op->kind == ORACLE_OP_MAX_SCALAR) {\n              if (a < t_lo[i]) a = t_lo[i];",
+     "} else if (op->kind == ORACLE_OP_MAX_SCALAR) {\n              if (a > t_lo[i]) a = t_lo[i];", None),
+    ("chain_q_final_scale_ignores_mul", "rc = multiplier_to_fixed(s / (double)sy, &mant, &shift);",
+     "rc = multiplier_to_fixed((double)sx * (double)sw / (double)sy, &mant, &shift);", None),
+    # batch-norm fold
+    ("bnfold_mean_sign", "b_out[i] = (float)((b - (double)mean[i]) * scale + (double)beta[i]);",
+     "b_out[i] = (float)((b + (double)mean[i]) * scale + (double)beta[i]);", None),
+    ("bnfold_no_sqrt", "const double scale = (double)gamma[i] / sqrt((double)var[i] + (double)eps);",
+     "const double scale = (double)gamma[i] / ((double)var[i] + (double)eps);", None),
+    ("bnfold_beta_scaled", "b_out[i] = (float)((b - (double)mean[i]) * scale + (double)beta[i]);",
+     "b_out[i] = (float)((b - (double)mean[i] + (double)beta[i]) * scale);", None),
+    ("bnfold_filter_unscaled", "w_out[i * per + e] = (float)((double)w[i * per + e] * scale);",
+     "w_out[i * per + e] = w[i * per + e];", None),
 ]
 
 
