@@ -191,6 +191,63 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
                                    size_t workspace_bytes, hipStream_t stream);
 
 /*
+ * General element-wise chains.  Section 5.2: whenever data-parallel operators follow one another they
+ * are stacked and executed in one pass over the data, whatever they are; the fixed chain above is the
+ * most common instance.  Here the caller gives the run of operators that follows the contraction as a
+ * list of up to GLOWMI_MAX_CHAIN_OPS ops, applied IN ORDER to every output element after the bias:
+ *     GLOWMI_OP_ADD_TENSOR  v += tensor[element]        tensor: device, shape/layout/type of y, 16-byte
+ *                                                       aligned; may be y itself, no other overlap with y
+ *     GLOWMI_OP_MUL_SCALAR  v *= a
+ *     GLOWMI_OP_MAX_SCALAR  v  = max(v, a)              (a = 0: Relu)
+ *     GLOWMI_OP_CLIP        v  = min(max(v, a), b)      a <= b
+ * There is no separate activation: n_ops = 0 is the bare contraction + bias.
+ *
+ * fp32 (glowmi_conv2d_chainv): each op is evaluated in fp32 on the accumulator in registers; a, b must
+ * not be NaN.
+ *
+ * Quantized (glowmi_qconv2d_chainv), a reading, since the paper only says that rescale nodes convert
+ * between ranges (Section 4.3): the chain runs on the int32 accumulator, whose real value is acc * s with
+ * s = x.scale * w.scale at first (formed in double).
+ *     MUL_SCALAR (a > 0 required)  s becomes s * a; the integer is untouched (exact)
+ *     MAX_SCALAR / CLIP            the bounds are put on the accumulator's grid, T = floor(a / s + 0.5)
+ *                                  saturated to int32, then plain integer max / min
+ *     ADD_TENSOR                   acc += round((tensor - tensor_q.offset) * tensor_q.scale / s), multiplier
+ *                                  in the mantissa/shift form of glowmi_chain (shift in [12, 62])
+ *     at the end                   y = saturate(round(acc * s_final / y.scale) + y.offset) to [-128, 127]
+ * Lists that are one of the fixed shapes ({}, {max 0}, {add}, {add, max 0}) give exactly the results of
+ * glowmi_(q)conv2d(_chain) and take the same kernels; any other list runs on the generic tiled kernels.
+ * Errors: GLOWMI_ERR_UNSUPPORTED for n_ops > GLOWMI_MAX_CHAIN_OPS or an unknown kind, GLOWMI_ERR_NULL /
+ * GLOWMI_ERR_ALIGN for a tensor, GLOWMI_ERR_QUANT for scalars or scales outside the stated ranges
+ * (quantized) and GLOWMI_ERR_SHAPE for NaN scalars or a > b (fp32).  Workspace: at least
+ * glowmi_(q)conv2d_chainv_workspace_bytes() for the same descriptor and list, or NULL.
+ */
+typedef enum glowmi_op_kind {
+  GLOWMI_OP_ADD_TENSOR = 1,
+  GLOWMI_OP_MUL_SCALAR = 2,
+  GLOWMI_OP_MAX_SCALAR = 3,
+  GLOWMI_OP_CLIP = 4
+} glowmi_op_kind;
+
+#define GLOWMI_MAX_CHAIN_OPS 4
+
+typedef struct glowmi_chain_op {
+  glowmi_op_kind kind;
+  float a, b;              /* scalars of MUL / MAX / CLIP                                   */
+  const void* tensor;      /* ADD_TENSOR operand                                            */
+  glowmi_qparam tensor_q;  /* quantized form: its scale/offset                              */
+} glowmi_chain_op;
+
+glowmi_status glowmi_conv2d_chainv(const float* x, const float* w, const float* bias, float* y,
+                                   const glowmi_conv_desc* d, const glowmi_chain_op* ops, int32_t n_ops,
+                                   void* workspace, size_t workspace_bytes, hipStream_t stream);
+size_t glowmi_conv2d_chainv_workspace_bytes(const glowmi_conv_desc* d, const glowmi_chain_op* ops, int32_t n_ops);
+glowmi_status glowmi_qconv2d_chainv(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
+                                    const int32_t* bias, int8_t* y, glowmi_qparam yq, const glowmi_conv_desc* d,
+                                    const glowmi_chain_op* ops, int32_t n_ops, void* workspace,
+                                    size_t workspace_bytes, hipStream_t stream);
+size_t glowmi_qconv2d_chainv_workspace_bytes(const glowmi_conv_desc* d, const glowmi_chain_op* ops, int32_t n_ops);
+
+/*
  * A straight sequence of convolution layers (with their stacked chains) run back to back on one
  * stream out of ONE caller-provided arena.  The paper's low-level IR marks the lifetime of every
  * activation (alloc/dealloc, Section 3.5) and all of them are then allocated statically in a single

@@ -9,12 +9,15 @@ from .binding import (  # noqa: F401
     ACT_NONE,
     ACT_RELU,
     Chain,
+    ChainOp,
     ConvDesc,
     GlowmiError,
     QParam,
     SeqLayer,
     conv2d,
     conv2d_chain,
+    conv2d_chainv,
+    conv2d_chainv_workspace_bytes,
     conv2d_workspace_bytes,
     conv_out_shape,
     dequantize,
@@ -28,6 +31,8 @@ from .binding import (  # noqa: F401
     library_path,
     qconv2d,
     qconv2d_chain,
+    qconv2d_chainv,
+    qconv2d_chainv_workspace_bytes,
     qconv2d_workspace_bytes,
     qfc,
     qfc_workspace_bytes,

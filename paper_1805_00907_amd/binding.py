@@ -32,6 +32,16 @@ class Chain(ctypes.Structure):
     _fields_ = [("addend", ctypes.c_void_p), ("addend_q", QParam), ("act", ctypes.c_int)]
 
 
+OP_ADD_TENSOR, OP_MUL_SCALAR, OP_MAX_SCALAR, OP_CLIP = 1, 2, 3, 4
+MAX_CHAIN_OPS = 4
+
+
+class ChainOp(ctypes.Structure):
+    """glowmi_chain_op: kind; scalars a, b; tensor operand and (quantized form) its scale/offset."""
+    _fields_ = [("kind", ctypes.c_int), ("a", ctypes.c_float), ("b", ctypes.c_float), ("tensor", ctypes.c_void_p),
+                ("tensor_q", QParam)]
+
+
 class SeqLayer(ctypes.Structure):
     """glowmi_seq_layer: one layer of a back-to-back sequence."""
     _fields_ = [("desc", ConvDesc), ("w", ctypes.c_void_p), ("bias", ctypes.c_void_p), ("wq", QParam),
@@ -87,6 +97,13 @@ def library() -> ctypes.CDLL:
     cp = ctypes.POINTER(Chain)
     L.glowmi_conv2d_chain.argtypes = [vp, vp, vp, vp, dp, cp, vp, sz, vp]
     L.glowmi_qconv2d_chain.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, dp, cp, vp, sz, vp]
+    op = ctypes.POINTER(ChainOp)
+    L.glowmi_conv2d_chainv.argtypes = [vp, vp, vp, vp, dp, op, i32, vp, sz, vp]
+    L.glowmi_conv2d_chainv_workspace_bytes.argtypes = [dp, op, i32]
+    L.glowmi_conv2d_chainv_workspace_bytes.restype = sz
+    L.glowmi_qconv2d_chainv.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, dp, op, i32, vp, sz, vp]
+    L.glowmi_qconv2d_chainv_workspace_bytes.argtypes = [dp, op, i32]
+    L.glowmi_qconv2d_chainv_workspace_bytes.restype = sz
     sp = ctypes.POINTER(SeqLayer)
     L.glowmi_seq_arena_bytes.argtypes = [sp, i32, i32]
     L.glowmi_seq_arena_bytes.restype = sz
@@ -246,6 +263,56 @@ def qconv2d_chain(x, xq: QParam, w, wq: QParam, bias, y, yq: QParam, desc: ConvD
     _check(library().glowmi_qconv2d_chain(_ptr(x, "int8", nx, "x"), xq, _ptr(w, "int8", nw, "w"), wq,
                                           _ptr(bias, "int32", desc.k, "bias"), _ptr(y, "int8", ny, "y"), yq,
                                           ctypes.byref(desc), ctypes.byref(chain), wp, wb, _stream(stream)))
+
+
+def chain_ops(ops, dtype: str = "float32", count: Optional[int] = None):
+    """ctypes array of ChainOp from a list of ("add", tensor[, QParam]) | ("mul", a) | ("max", a) |
+    ("clip", a, b).  Tensors are device tensors of the output's element type (or raw addresses)."""
+    arr = (ChainOp * max(1, len(ops)))()
+    for i, o in enumerate(ops):
+        if o[0] == "add":
+            q = o[2] if len(o) > 2 else QParam(1.0, 0)
+            arr[i] = ChainOp(OP_ADD_TENSOR, 0.0, 0.0, _ptr(o[1], dtype, count, f"op {i} tensor"), q)
+        elif o[0] == "mul":
+            arr[i] = ChainOp(OP_MUL_SCALAR, o[1], 0.0, None, QParam(1.0, 0))
+        elif o[0] == "max":
+            arr[i] = ChainOp(OP_MAX_SCALAR, o[1], 0.0, None, QParam(1.0, 0))
+        elif o[0] == "clip":
+            arr[i] = ChainOp(OP_CLIP, o[1], o[2], None, QParam(1.0, 0))
+        else:
+            raise ValueError(f"unknown chain op {o[0]!r}")
+    return arr
+
+
+def conv2d_chainv_workspace_bytes(desc: ConvDesc, ops) -> int:
+    arr = chain_ops(ops)
+    return int(library().glowmi_conv2d_chainv_workspace_bytes(ctypes.byref(desc), arr, len(ops)))
+
+
+def conv2d_chainv(x, w, bias, y, desc: ConvDesc, ops, workspace=None, stream=None) -> None:
+    """y = ops applied in order to (conv + bias): a general stack of data-parallel operators."""
+    wp, wb = _ws(workspace)
+    nx, nw, ny = _conv_counts(desc)
+    arr = chain_ops(ops, "float32", ny)
+    _check(library().glowmi_conv2d_chainv(_ptr(x, "float32", nx, "x"), _ptr(w, "float32", nw, "w"),
+                                          _ptr(bias, "float32", desc.k, "bias"), _ptr(y, "float32", ny, "y"),
+                                          ctypes.byref(desc), arr, len(ops), wp, wb, _stream(stream)))
+
+
+def qconv2d_chainv_workspace_bytes(desc: ConvDesc, ops) -> int:
+    arr = chain_ops(ops, "int8")
+    return int(library().glowmi_qconv2d_chainv_workspace_bytes(ctypes.byref(desc), arr, len(ops)))
+
+
+def qconv2d_chainv(x, xq: QParam, w, wq: QParam, bias, y, yq: QParam, desc: ConvDesc, ops, workspace=None,
+                   stream=None) -> None:
+    """Quantized general chain: the ops act on the int32 accumulator, then one requantize."""
+    wp, wb = _ws(workspace)
+    nx, nw, ny = _conv_counts(desc)
+    arr = chain_ops(ops, "int8", ny)
+    _check(library().glowmi_qconv2d_chainv(_ptr(x, "int8", nx, "x"), xq, _ptr(w, "int8", nw, "w"), wq,
+                                           _ptr(bias, "int32", desc.k, "bias"), _ptr(y, "int8", ny, "y"), yq,
+                                           ctypes.byref(desc), arr, len(ops), wp, wb, _stream(stream)))
 
 
 def qfc_workspace_bytes(M: int, K: int, N: int) -> int:

@@ -35,7 +35,7 @@ glowmi_status fail(glowmi_status s, const char* fmt, ...) {
 namespace {
 const char* const kKnobNames[KNOB_COUNT] = {
     "F32_TILE", "F32_SPLIT", "F32_PW_MIN_ITEMS", "F32_SMALL_MAX_TILES", "F32_SMALL_NO_SPLIT",
-    "F32_SMALL_SPLIT_MAX_TILES", "F32_SMALL_MIN_WGS", "F32_FC_SMALL_OFF", "SMALLC_TH",
+    "F32_SMALL_SPLIT_MAX_TILES", "F32_SMALL_MIN_WGS", "F32_FC_SMALL_OFF", "F32_FC_SMALL_VW", "SMALLC_TH",
     "I8_TILE", "I8_WIDE_SPLIT", "I8_WIDE_NBUF", "SMALLC_I8_WGS", "I8_PW_MIN_ITEMS",
     "I8_FC_SMALL_MAX_M", "I8_K3_MIN_BLOCKS", "I8_K3_WAVES", "I8_K3_GATHER", "I8_DEEP_OFF",
 };
@@ -533,6 +533,209 @@ void glowmi_tuning_reset(void) {
   for (int i = 0; i < glowmi::KNOB_COUNT; ++i) glowmi::g_knobs[i].store(glowmi::kKnobUnset, std::memory_order_relaxed);
 }
 
+}  // extern "C"
+
+// ---- general chains ---------------------------------------------------------------------------------
+namespace {
+
+// The op lists that are one of the fixed chain shapes take the entry points (and kernels) of those.
+bool fixed_shape(const glowmi_chain_op* ops, int32_t n, glowmi_chain* chain) {
+  chain->addend = nullptr;
+  chain->addend_q.scale = 1.0f;
+  chain->addend_q.offset = 0;
+  chain->act = GLOWMI_ACT_NONE;
+  int i = 0;
+  if (i < n && ops[i].kind == GLOWMI_OP_ADD_TENSOR && ops[i].tensor) {
+    chain->addend = ops[i].tensor;
+    chain->addend_q = ops[i].tensor_q;
+    ++i;
+  }
+  if (i < n && ops[i].kind == GLOWMI_OP_MAX_SCALAR && ops[i].a == 0.0f) {
+    chain->act = GLOWMI_ACT_RELU;
+    ++i;
+  }
+  return i == n;
+}
+
+glowmi_status check_op_list(const glowmi_chain_op* ops, int32_t n) {
+  if (n < 0 || n > GLOWMI_MAX_CHAIN_OPS)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "a chain has 0 to %d ops (got %d)", GLOWMI_MAX_CHAIN_OPS, n);
+  if (n > 0 && !ops) return fail(GLOWMI_ERR_NULL, "op list is NULL");
+  for (int32_t i = 0; i < n; ++i)
+    if (ops[i].kind < GLOWMI_OP_ADD_TENSOR || ops[i].kind > GLOWMI_OP_CLIP)
+      return fail(GLOWMI_ERR_UNSUPPORTED, "op %d: unknown kind %d", i, (int)ops[i].kind);
+  return GLOWMI_OK;
+}
+
+// Fill p.chain for the fp32 form; y_bytes for the overlap rule of added tensors.
+glowmi_status fill_chain_f32(glowmi::Problem& p, const glowmi_chain_op* ops, int32_t n, const void* y, size_t y_bytes) {
+  p.chain_n = n;
+  p.addend = nullptr;
+  p.act = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    glowmi::ChainOpDev& o = p.chain[i];
+    o.kind = (int32_t)ops[i].kind;
+    o.a = ops[i].a; o.b = ops[i].b;
+    o.tensor = nullptr;
+    switch (ops[i].kind) {
+      case GLOWMI_OP_ADD_TENSOR: {
+        if (!ops[i].tensor) return fail(GLOWMI_ERR_NULL, "op %d: tensor is NULL", i);
+        glowmi_status st = check_addend(ops[i].tensor, y, y_bytes);
+        if (st != GLOWMI_OK) return st;
+        o.tensor = ops[i].tensor;
+        break;
+      }
+      case GLOWMI_OP_MUL_SCALAR:
+      case GLOWMI_OP_MAX_SCALAR:
+        if (std::isnan(ops[i].a)) return fail(GLOWMI_ERR_SHAPE, "op %d: scalar is NaN", i);
+        break;
+      case GLOWMI_OP_CLIP:
+        if (!(ops[i].a <= ops[i].b)) return fail(GLOWMI_ERR_SHAPE, "op %d: clip bounds %g > %g or NaN", i, (double)ops[i].a, (double)ops[i].b);
+        break;
+    }
+  }
+  return GLOWMI_OK;
+}
+
+// A real bound on an accumulator grid of step s: floor(v / s + 0.5), saturated to int32.
+int32_t grid_bound(float v, double s) {
+  const double t = std::floor((double)v / s + 0.5);
+  if (t != t) return 0;
+  if (t <= -2147483648.0) return INT32_MIN;
+  if (t >= 2147483647.0) return INT32_MAX;
+  return (int32_t)t;
+}
+
+glowmi_status multiplier_params_fwd(double mr, int32_t* mant, int32_t* shift);
+
+// Fill p.chain, p.mant, p.shift, p.lo for the quantized form.
+glowmi_status fill_chain_i8(glowmi::Problem& p, const glowmi_chain_op* ops, int32_t n, glowmi_qparam xq, glowmi_qparam wq,
+                            glowmi_qparam yq, const void* y, size_t y_bytes) {
+  p.chain_n = n;
+  p.addend = nullptr;
+  p.act = 0;
+  p.lo = -128;
+  double s = (double)xq.scale * (double)wq.scale;     // the accumulator's scale
+  for (int32_t i = 0; i < n; ++i) {
+    glowmi::ChainOpDev& o = p.chain[i];
+    o.kind = (int32_t)ops[i].kind;
+    o.a = ops[i].a; o.b = ops[i].b;
+    o.tensor = nullptr;
+    o.ia = o.ib = 0; o.t_off = 0; o.t_mant = 0; o.t_shift = 1;
+    switch (ops[i].kind) {
+      case GLOWMI_OP_ADD_TENSOR: {
+        if (!ops[i].tensor) return fail(GLOWMI_ERR_NULL, "op %d: tensor is NULL", i);
+        glowmi_status st = check_addend(ops[i].tensor, y, y_bytes);
+        if (st != GLOWMI_OK) return st;
+        const glowmi_qparam tq = ops[i].tensor_q;
+        if (!std::isfinite(tq.scale) || tq.scale <= 0.0f || tq.offset < -128 || tq.offset > 127)
+          return fail(GLOWMI_ERR_QUANT, "op %d: tensor scale %g / offset %d unusable", i, (double)tq.scale, tq.offset);
+        if ((st = multiplier_params_fwd((double)tq.scale / s, &o.t_mant, &o.t_shift)) != GLOWMI_OK) return st;
+        if (o.t_shift < kMinAddendShift)
+          return fail(GLOWMI_ERR_QUANT, "op %d: tensor scale %g is more than 2^%d times the accumulator's scale %g", i,
+                      (double)tq.scale, 31 - kMinAddendShift, s);
+        o.t_off = tq.offset;
+        o.tensor = ops[i].tensor;
+        break;
+      }
+      case GLOWMI_OP_MUL_SCALAR:
+        if (!std::isfinite(ops[i].a) || ops[i].a <= 0.0f)
+          return fail(GLOWMI_ERR_QUANT, "op %d: a quantized chain multiplies by positive finite factors only (got %g)", i, (double)ops[i].a);
+        s = s * (double)ops[i].a;
+        if (!std::isfinite(s) || s <= 0.0) return fail(GLOWMI_ERR_QUANT, "op %d: accumulator scale left the double range", i);
+        break;
+      case GLOWMI_OP_MAX_SCALAR:
+        if (std::isnan(ops[i].a)) return fail(GLOWMI_ERR_QUANT, "op %d: scalar is NaN", i);
+        o.ia = grid_bound(ops[i].a, s);
+        break;
+      case GLOWMI_OP_CLIP:
+        if (!(ops[i].a <= ops[i].b)) return fail(GLOWMI_ERR_QUANT, "op %d: clip bounds %g > %g or NaN", i, (double)ops[i].a, (double)ops[i].b);
+        o.ia = grid_bound(ops[i].a, s);
+        o.ib = grid_bound(ops[i].b, s);
+        break;
+    }
+  }
+  if (!std::isfinite(yq.scale) || yq.scale <= 0.0f) return fail(GLOWMI_ERR_QUANT, "output scale %g unusable", (double)yq.scale);
+  int32_t mant = 0, shift = 0;
+  glowmi_status st = multiplier_params_fwd(s / (double)yq.scale, &mant, &shift);
+  if (st != GLOWMI_OK) return st;
+  p.mant = mant; p.shift = shift;
+  return GLOWMI_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t glowmi_conv2d_chainv_workspace_bytes(const glowmi_conv_desc* d, const glowmi_chain_op* ops, int32_t n_ops) {
+  Geometry geo;
+  if (check_desc(d, &geo) != GLOWMI_OK || check_op_list(ops, n_ops) != GLOWMI_OK) return 0;
+  glowmi_chain chain;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  if (fixed_shape(ops, n_ops, &chain)) p.addend = chain.addend;
+  else p.chain_n = n_ops;
+  return split_bytes(glowmi::plan_f32(p, true), p);
+}
+
+glowmi_status glowmi_conv2d_chainv(const float* x, const float* w, const float* bias, float* y,
+                                   const glowmi_conv_desc* d, const glowmi_chain_op* ops, int32_t n_ops,
+                                   void* workspace, size_t workspace_bytes, hipStream_t stream) {
+  glowmi_status st = check_op_list(ops, n_ops);
+  if (st != GLOWMI_OK) return st;
+  glowmi_chain chain;
+  if (fixed_shape(ops, n_ops, &chain)) return glowmi_conv2d_chain(x, w, bias, y, d, &chain, workspace, workspace_bytes, stream);
+  Geometry geo;
+  if ((st = check_desc(d, &geo)) != GLOWMI_OK) return st;
+  if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 4)) != GLOWMI_OK) return st;
+  p.x = x; p.w = w; p.bias = bias; p.y = y;
+  if ((st = fill_chain_f32(p, ops, n_ops, y, (size_t)geo.y_elems * 4u)) != GLOWMI_OK) return st;
+  const glowmi::Plan plan = plan_with_workspace(p, glowmi::plan_f32, workspace, workspace_bytes);
+  const char* variant = "";
+  return finish(glowmi::launch_f32(p, plan, stream, &variant), variant);
+}
+
+size_t glowmi_qconv2d_chainv_workspace_bytes(const glowmi_conv_desc* d, const glowmi_chain_op* ops, int32_t n_ops) {
+  Geometry geo;
+  if (check_desc(d, &geo) != GLOWMI_OK || check_op_list(ops, n_ops) != GLOWMI_OK) return 0;
+  glowmi_chain chain;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  if (fixed_shape(ops, n_ops, &chain)) p.addend = chain.addend;
+  else p.chain_n = n_ops;
+  return split_bytes(glowmi::plan_i8(p, true), p);
+}
+
+glowmi_status glowmi_qconv2d_chainv(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
+                                    const int32_t* bias, int8_t* y, glowmi_qparam yq, const glowmi_conv_desc* d,
+                                    const glowmi_chain_op* ops, int32_t n_ops, void* workspace,
+                                    size_t workspace_bytes, hipStream_t stream) {
+  glowmi_status st = check_op_list(ops, n_ops);
+  if (st != GLOWMI_OK) return st;
+  glowmi_chain chain;
+  if (fixed_shape(ops, n_ops, &chain))
+    return glowmi_qconv2d_chain(x, xq, w, wq, bias, y, yq, d, &chain, workspace, workspace_bytes, stream);
+  Geometry geo;
+  if ((st = check_desc(d, &geo)) != GLOWMI_OK) return st;
+  if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 1)) != GLOWMI_OK) return st;
+  if ((st = quant_setup(p, xq, wq, yq, GLOWMI_ACT_NONE)) != GLOWMI_OK) return st;
+  p.x = x; p.w = w; p.bias = bias; p.y = y;
+  if ((st = fill_chain_i8(p, ops, n_ops, xq, wq, yq, y, (size_t)geo.y_elems)) != GLOWMI_OK) return st;
+  const glowmi::Plan plan = plan_with_workspace(p, glowmi::plan_i8, workspace, workspace_bytes);
+  const char* variant = "";
+  return finish(glowmi::launch_i8(p, plan, stream, &variant), variant);
+}
+
+}  // extern "C"
+
+extern "C" {
+
 static glowmi_status check_elementwise(const void* in, const void* out, size_t count, size_t in_elem,
                                        size_t out_elem, bool in_place_ok) {
   if (!in || !out) return fail(GLOWMI_ERR_NULL, "input and output pointers must not be NULL");
@@ -633,6 +836,10 @@ glowmi_status glowmi_rescale_params(float r_scale, float x_scale, float w_scale,
     if (!std::isfinite(v) || v <= 0.0f) return fail(GLOWMI_ERR_QUANT, "scale %g is not finite and positive", (double)v);
   return multiplier_params((double)r_scale / ((double)x_scale * (double)w_scale), mant, shift);
 }
+
+namespace {
+glowmi_status multiplier_params_fwd(double mr, int32_t* mant, int32_t* shift) { return multiplier_params(mr, mant, shift); }
+}  // namespace
 
 static glowmi_status multiplier_params(double mr, int32_t* mant, int32_t* shift) {
   if (!std::isfinite(mr) || mr <= 0.0) return fail(GLOWMI_ERR_QUANT, "combined multiplier %g is unusable", mr);

@@ -18,7 +18,7 @@ namespace glowmi {
 // dispatch path calls getenv.  kKnobUnset means "the planner's own choice".
 enum Knob {
   KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
-  KNOB_F32_SMALL_SPLIT_MAX_TILES, KNOB_F32_SMALL_MIN_WGS, KNOB_F32_FC_SMALL_OFF, KNOB_SMALLC_TH,
+  KNOB_F32_SMALL_SPLIT_MAX_TILES, KNOB_F32_SMALL_MIN_WGS, KNOB_F32_FC_SMALL_OFF, KNOB_F32_FC_SMALL_VW, KNOB_SMALLC_TH,
   KNOB_I8_TILE, KNOB_I8_WIDE_SPLIT, KNOB_I8_WIDE_NBUF, KNOB_SMALLC_I8_WGS, KNOB_I8_PW_MIN_ITEMS,
   KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER, KNOB_I8_DEEP_OFF,
   KNOB_COUNT
@@ -57,6 +57,20 @@ inline FastDiv make_fastdiv(uint32_t d) {
   return f;
 }
 
+// One link of a general element-wise chain behind the contraction (Section 5.2 of the paper: any run
+// of data-parallel operators is stacked onto the producer).  fp32 uses a/b; the quantized form uses
+// the integer bounds ia/ib on the int32 accumulator and, for an added tensor, its offset and the
+// multiplier mant * 2^-shift that brings a code difference to the accumulator's current scale.
+enum ChainKind { CHAIN_ADD_TENSOR = 1, CHAIN_MUL_SCALAR = 2, CHAIN_MAX_SCALAR = 3, CHAIN_CLIP = 4 };
+constexpr int kMaxChainOps = 4;
+struct ChainOpDev {
+  int32_t kind;
+  float a, b;
+  int32_t ia, ib;
+  int32_t t_off, t_mant, t_shift;
+  const void* tensor;     // [M][k] like the output (float or int8); may be the output itself
+};
+
 struct Problem {
   const void* x;      // input  [n][h][w][c]            (float or int8)
   const void* w;      // filter [k][r][s][cg]  or FC weight [Kgemm][k] when b_is_kn
@@ -84,6 +98,10 @@ struct Problem {
   int32_t lo;               // lower clamp bound
   int32_t r_off, r_mant, r_shift;   // quantized addend: its offset and the multiplier that brings a
                                     // code difference to the accumulator's scale, mant * 2^-shift
+  // general chain (chain_n > 0): replaces addend/act; only the generic 64 x 64 tiled kernels and the
+  // finishing kernels of a split reduction implement it
+  int32_t chain_n;
+  ChainOpDev chain[kMaxChainOps];
 };
 
 // Which kernel family a call takes, and how the reduction is split over workgroups.  The ABI layer

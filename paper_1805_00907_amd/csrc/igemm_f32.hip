@@ -95,7 +95,7 @@ struct Item {
   int slab_begin, slab_end;
 };
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK, bool CHAINV = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const Problem p, int tiles_m,
                                                                           int tiles_n, int total_work) {
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
@@ -381,8 +381,40 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
       }
     }
   };
+  // General chain (CHAINV instantiations only): the op list of the problem applied in order to every
+  // element, in registers, before the one store -- any stack of data-parallel operators, not just the
+  // fixed bias -> add -> Relu shape.  The op kinds are uniform over the launch (scalar branches).
+  auto epilogue_chainv = [&](const Item& it) {
+    const int row_base = it.tm * BM + wm * WTM + lhalf * 4;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = it.tn * BN + wn * WTN + j * 32 + lrow;
+      const bool cok = col < p.kg;
+      const int ch = it.g * p.kg + col;
+      const float bv = (cok && bias) ? bias[ch] : 0.f;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int r = i * 32 + (e >> 2) * 8 + (e & 3);
+          if (!cok || row_base + r >= p.M) continue;
+          const size_t off = (size_t)(row_base + r) * p.k + ch;
+          float v = (LONGK ? total[i][j][e] : acc[i][j][e]) + bv;
+          for (int o = 0; o < p.chain_n; ++o) {
+            const ChainOpDev& op = p.chain[o];
+            if (op.kind == CHAIN_ADD_TENSOR) v += static_cast<const float*>(op.tensor)[off];
+            else if (op.kind == CHAIN_MUL_SCALAR) v *= op.a;
+            else if (op.kind == CHAIN_MAX_SCALAR) v = fmaxf(v, op.a);
+            else v = fminf(fmaxf(v, op.a), op.b);
+          }
+          Y[off] = v;
+        }
+      }
+    }
+  };
   auto epilogue = [&](const Item& it) {
-    if (addend && p.split_k == 1) epilogue_as(it, std::true_type{});
+    if (CHAINV && p.split_k == 1) epilogue_chainv(it);
+    else if (!CHAINV && addend && p.split_k == 1) epilogue_as(it, std::true_type{});
     else epilogue_as(it, std::false_type{});
   };
 
@@ -444,6 +476,27 @@ __global__ __launch_bounds__(256) void splitk_finish_f32(const float* __restrict
       for (int e = 0; e < W; ++e) v[e] = fmaxf(v[e], 0.f);
     }
     *reinterpret_cast<vec*>(y + i) = v;
+  }
+}
+
+// Finish of a split reduction whose element-wise chain is a general op list: partial sums in split
+// order, bias, then the ops in order, one store.
+__global__ __launch_bounds__(256) void splitk_finish_chain_f32(const Problem p, int total) {
+  const float* __restrict__ partial = static_cast<const float*>(p.partial);
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  float* y = static_cast<float*>(p.y);
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    float v = 0.f;
+    for (int s = 0; s < p.split_k; ++s) v += partial[(size_t)s * total + i];
+    if (bias) v += bias[i % p.k];
+    for (int o = 0; o < p.chain_n; ++o) {
+      const ChainOpDev& op = p.chain[o];
+      if (op.kind == CHAIN_ADD_TENSOR) v += static_cast<const float*>(op.tensor)[i];
+      else if (op.kind == CHAIN_MUL_SCALAR) v *= op.a;
+      else if (op.kind == CHAIN_MAX_SCALAR) v = fmaxf(v, op.a);
+      else v = fminf(fmaxf(v, op.a), op.b);
+    }
+    y[i] = v;
   }
 }
 
@@ -576,9 +629,9 @@ __global__ __launch_bounds__(64 * SK_WAVES) void fc_skinny16_f32_kernel(
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool LONGK, bool CHAINV = false>
 hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
-  auto kern = igemm_f32_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN, LONGK>;
+  auto kern = igemm_f32_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN, LONGK, CHAINV>;
   constexpr int lds_bytes = lds_floats<BM, BN, B_KN>() * (int)sizeof(float);
   constexpr int nthreads = 64 * WAVES_M * WAVES_N;
   // once per instantiation; initialisation of a function-local static is thread-safe
@@ -615,7 +668,8 @@ Plan plan_f32(const Problem& p, bool allow_split) {
   pl.slabs = 1;
   pl.split_k = 1;
   pl.slabs_per_split = 1;
-  const int forced_tile = knob(KNOB_F32_TILE);           // experiments and tests: force a generic tile variant
+  int forced_tile = knob(KNOB_F32_TILE);                 // experiments and tests: force a generic tile variant
+  if (p.chain_n > 0) forced_tile = 0;                    // a general chain: only the generic 64 x 64 kernel implements it
   const bool forced = forced_tile != kKnobUnset;
   if (!forced) {
     // kernels of their own, no workspace
@@ -767,6 +821,15 @@ hipError_t launch_f32(const Problem& p_in, const Plan& plan, hipStream_t stream,
                        static_cast<float*>(p.y), static_cast<float*>(p.partial), p.M, p.Kgemm, p.k, p.act,
                        plan.split_k, plan.slabs_per_split);
     e = hipGetLastError();
+  } else if (p.chain_n > 0) {
+    if (fc || plan.tile != 0) return hipErrorInvalidValue;
+    const bool longk = plan.slabs_per_split > FLUSH_SLABS;
+    snprintf(name, sizeof(name), "igemm_f32_64x64w4_conv_%s%s_chainv", vec ? "vec" : "scalar", longk ? "_longk" : "");
+    *variant = name;
+    if (vec) e = longk ? launch_variant<64, 64, 2, 2, true, false, true, true>(p, plan, stream)
+                       : launch_variant<64, 64, 2, 2, true, false, false, true>(p, plan, stream);
+    else e = longk ? launch_variant<64, 64, 2, 2, false, false, true, true>(p, plan, stream)
+                   : launch_variant<64, 64, 2, 2, false, false, false, true>(p, plan, stream);
   } else {
     snprintf(name, sizeof(name), "igemm_f32_%s_%s_%s%s", kTilesF32[plan.tile].name, fc ? "fc" : "conv",
              vec ? "vec" : "scalar", plan.slabs_per_split > FLUSH_SLABS ? "_longk" : "");
@@ -782,7 +845,13 @@ hipError_t launch_f32(const Problem& p_in, const Plan& plan, hipStream_t stream,
     }
   }
   if (e != hipSuccess) return e;
-  if (plan.split_k > 1) {
+  if (plan.split_k > 1 && p.chain_n > 0) {
+    const int total = p.M * p.k;
+    int blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(splitk_finish_chain_f32, dim3(blocks), dim3(256), 0, stream, p, total);
+    e = hipGetLastError();
+  } else if (plan.split_k > 1) {
     const int total = p.M * p.k;
     const bool wide = p.k % 4 == 0 && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;   // y, partial, addend are 16-byte aligned
     int blocks = (total / (wide ? 4 : 1) + 255) / 256;

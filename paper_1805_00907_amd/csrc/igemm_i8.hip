@@ -60,7 +60,21 @@ __device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_of
                      : requantize_as<false>(acc, mant, shift, y_off, lo);   // uniform branch
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
+// The ops of a general chain on one int32 accumulator value (quantized form: a scalar multiply only
+// changed the scale on the host, bounds are integers on the accumulator's grid, an added tensor's code
+// difference is rescaled to the accumulator's current scale).  `off` indexes [M][k] tensors.
+__device__ __forceinline__ int apply_chain_i8(const Problem& p, int v, size_t off) {
+  for (int o = 0; o < p.chain_n; ++o) {
+    const ChainOpDev& op = p.chain[o];
+    if (op.kind == CHAIN_ADD_TENSOR)
+      v += rescale_term((int)static_cast<const signed char*>(op.tensor)[off] - op.t_off, op.t_mant, op.t_shift);
+    else if (op.kind == CHAIN_MAX_SCALAR) v = v < op.ia ? op.ia : v;
+    else if (op.kind == CHAIN_CLIP) { v = v < op.ia ? op.ia : v; v = v > op.ib ? op.ib : v; }
+  }
+  return v;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool CHAINV = false>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const Problem p, int tiles_m,
                                                                          int tiles_n, int total_work) {
   constexpr int NTHREADS = 64 * WAVES_M * WAVES_N;
@@ -362,7 +376,10 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_i8_kernel(const 
 #pragma unroll
           for (int t = 0; t < 4; ++t) {
             int v = (int)((unsigned)acc[i][j][q4 * 4 + t] + (unsigned)ct[t] - rowterm);
-            if (addend) {                                             // uniform: tensor-add link of the chain
+            if (CHAINV) {                                             // general op list
+              const int col = tn * BN + lc + t;
+              if (row < p.M && col < p.kg) v = apply_chain_i8(p, v, (size_t)row * p.k + g * p.kg + col);
+            } else if (addend) {                                      // uniform: tensor-add link of the chain
               const int col = tn * BN + lc + t;
               const int code = (row < p.M && col < p.kg) ? (int)addend[(size_t)row * p.k + g * p.kg + col] : p.r_off;
               v += rescale_term(code - p.r_off, p.r_mant, p.r_shift);
@@ -455,9 +472,23 @@ __global__ __launch_bounds__(256) void splitk_finish_i8(const int* __restrict__ 
   }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN>
+// Finish of a split reduction whose element-wise chain is a general op list.
+__global__ __launch_bounds__(256) void splitk_finish_chain_i8(const Problem p, int total) {
+  const int* __restrict__ partial = static_cast<const int*>(p.partial);
+  const int* __restrict__ bias = static_cast<const int*>(p.bias);
+  signed char* y = static_cast<signed char*>(p.y);
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < total; i += gridDim.x * blockDim.x) {
+    unsigned a = 0;
+    for (int s = 0; s < p.split_k; ++s) a += (unsigned)partial[(size_t)s * total + i];
+    if (bias) a += (unsigned)bias[i % p.k];
+    const int v = apply_chain_i8(p, (int)a, (size_t)i);
+    y[i] = (signed char)requantize(v, p.mant, p.shift, p.y_off, p.lo);
+  }
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool VEC, bool B_KN, bool CHAINV = false>
 hipError_t launch_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
-  auto kern = igemm_i8_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN>;
+  auto kern = igemm_i8_kernel<BM, BN, WAVES_M, WAVES_N, VEC, B_KN, CHAINV>;
   constexpr int lds_bytes = 2 * (BM + BN) * LDQ;
   constexpr int nthreads = 64 * WAVES_M * WAVES_N;
   // once per instantiation; initialisation of a function-local static is thread-safe
@@ -499,7 +530,8 @@ Plan plan_i8(const Problem& p, bool allow_split) {
   pl.slabs = 1;
   pl.split_k = 1;
   pl.slabs_per_split = 1;
-  const int forced = knob_or(KNOB_I8_TILE, -1);   // experiments and tests: force a tile variant
+  int forced = knob_or(KNOB_I8_TILE, -1);         // experiments and tests: force a tile variant
+  if (p.chain_n > 0) forced = 0;                  // a general chain: only the generic 64 x 64 kernel implements it
   if (forced < 0) {
     // kernels of their own, no workspace
     if (smallc_i8_applicable(p) && !p.addend) { pl.kernel = KERNEL_SMALLC; return pl; }
@@ -576,6 +608,11 @@ hipError_t launch_i8(const Problem& p_in, const Plan& plan, hipStream_t stream, 
   hipError_t e;
   if (plan.kernel == KERNEL_WIDE) {
     e = launch_wide_i8(p, plan, stream, variant);
+  } else if (p.chain_n > 0) {
+    if (fc || plan.tile != 0) return hipErrorInvalidValue;
+    *variant = vec ? "igemm_i8_64x64w4_conv_vec_chainv" : "igemm_i8_64x64w4_conv_scalar_chainv";
+    e = vec ? launch_variant<64, 64, 2, 2, true, false, true>(p, plan, stream)
+            : launch_variant<64, 64, 2, 2, false, false, true>(p, plan, stream);
   } else {
     static thread_local char name[64];
     snprintf(name, sizeof(name), "igemm_i8_%s_%s_%s", kTilesI8[plan.tile].name, fc ? "fc" : "conv",
@@ -590,7 +627,13 @@ hipError_t launch_i8(const Problem& p_in, const Plan& plan, hipStream_t stream, 
     }
   }
   if (e != hipSuccess) return e;
-  if (plan.split_k > 1) {
+  if (plan.split_k > 1 && p.chain_n > 0) {
+    const int total = p.M * p.k;
+    int blocks = (total + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(splitk_finish_chain_i8, dim3(blocks), dim3(256), 0, stream, p, total);
+    e = hipGetLastError();
+  } else if (plan.split_k > 1) {
     const int total = p.M * p.k;
     const bool wide = p.k % 4 == 0 && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;   // y, partial are 16-byte aligned
     int blocks = (total / (wide ? 4 : 1) + 255) / 256;

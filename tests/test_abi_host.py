@@ -221,6 +221,46 @@ def test_chain_errors():
     assert status == 1                                # NULL chain
 
 
+def test_chainv_errors():
+    d = _desc()
+    ok = glowmi.QParam(0.1, 0)
+    far = FAKE + (1 << 20)
+
+    def f32(ops):
+        try:
+            glowmi.conv2d_chainv(FAKE, FAKE, None, FAKE, d, ops, stream=0)
+        except glowmi.GlowmiError as e:
+            return e.status
+        return 0
+
+    def q(ops):
+        try:
+            glowmi.qconv2d_chainv(FAKE, ok, FAKE, ok, None, FAKE, ok, d, ops, stream=0)
+        except glowmi.GlowmiError as e:
+            return e.status
+        return 0
+
+    assert f32([("mul", 1.0)] * 5) == 3                           # too many ops
+    assert f32([("mul", 2.0), ("add", None)]) == 1                # NULL tensor
+    assert f32([("mul", 2.0), ("add", far + 4)]) == 4             # misaligned tensor
+    assert f32([("mul", 2.0), ("add", FAKE + 16)]) == 3           # overlaps the output without being it
+    assert f32([("clip", 1.0, -1.0)]) == 2
+    assert f32([("mul", float("nan"))]) == 2
+    assert q([("mul", 0.0)]) == 5 and q([("mul", -1.0)]) == 5 and q([("mul", float("inf"))]) == 5
+    assert q([("clip", 1.0, -1.0)]) == 5
+    assert q([("mul", 2.0), ("add", far, glowmi.QParam(0.0, 0))]) == 5
+    assert q([("mul", 2.0), ("add", far, glowmi.QParam(0.1, 300))]) == 5
+    assert q([("mul", 2.0), ("add", far, glowmi.QParam(1e9, 0))]) == 5       # multiplier far too large
+    lib = glowmi.library()
+    bad_kind = (glowmi.ChainOp * 1)(glowmi.ChainOp(9, 0.0, 0.0, None, ok))
+    assert lib.glowmi_conv2d_chainv(FAKE, FAKE, None, FAKE, ctypes.byref(d), bad_kind, 1, None, 0, 0) == 3
+    assert lib.glowmi_conv2d_chainv(FAKE, FAKE, None, FAKE, ctypes.byref(d), None, 2, None, 0, 0) == 1
+    # workspace query follows the list: a fixed shape asks for what the fixed entry point asks
+    big = glowmi.ConvDesc(1, 7, 7, 512, 512, 3, 3, 1, 1, 1, 1, 1, 1, 1)
+    assert glowmi.conv2d_chainv_workspace_bytes(big, [("max", 0.0)]) == glowmi.conv2d_workspace_bytes(big)
+    assert glowmi.conv2d_chainv_workspace_bytes(big, [("mul", 2.0)]) > 0
+
+
 def test_fold_batchnorm_matches_oracle():
     """Host-only entry point: runs without a GPU.  Same double arithmetic, so bit-identical."""
     rng = np.random.default_rng(8)
