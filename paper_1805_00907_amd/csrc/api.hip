@@ -35,7 +35,7 @@ glowmi_status fail(glowmi_status s, const char* fmt, ...) {
 namespace {
 const char* const kKnobNames[KNOB_COUNT] = {
     "F32_TILE", "F32_SPLIT", "F32_PW_MIN_ITEMS", "F32_SMALL_MAX_TILES", "F32_SMALL_NO_SPLIT",
-    "F32_SMALL_SPLIT_MAX_TILES", "F32_SMALL_MIN_WGS", "F32_FC_SMALL_OFF", "F32_FC_SMALL_VW", "SMALLC_TH",
+    "F32_SMALL_SPLIT_MAX_TILES", "F32_SMALL_MIN_WGS", "F32_FC_SMALL_OFF", "F32_FC_SMALL_VW", "F32_FC_SMALL_MAX_KB", "SMALLC_TH",
     "I8_TILE", "I8_WIDE_SPLIT", "I8_WIDE_NBUF", "SMALLC_I8_WGS", "I8_PW_MIN_ITEMS",
     "I8_FC_SMALL_MAX_M", "I8_K3_MIN_BLOCKS", "I8_K3_WAVES", "I8_K3_GATHER", "I8_DEEP_OFF",
 };
@@ -397,6 +397,7 @@ size_t glowmi_conv2d_workspace_bytes(const glowmi_conv_desc* d) {
   if (check_desc(d, &geo) != GLOWMI_OK) return 0;
   glowmi::Problem p;
   fill_conv(p, d, geo);
+  if (set_operand_bytes(p, geo.x_elems, geo.w_elems, 4) != GLOWMI_OK) return 0;   // the planner sees what the call sees
   return split_bytes(glowmi::plan_f32(p, true), p);
 }
 
@@ -424,6 +425,7 @@ size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N) {
   if (check_fc(M, K, N) != GLOWMI_OK) return 0;
   glowmi::Problem p;
   fill_fc(p, M, K, N);
+  if (set_operand_bytes(p, (long long)M * K, (long long)K * N, 4) != GLOWMI_OK) return 0;
   return split_bytes(glowmi::plan_f32(p, true), p);
 }
 
@@ -466,6 +468,7 @@ size_t glowmi_qconv2d_workspace_bytes(const glowmi_conv_desc* d) {
   if (check_desc(d, &geo) != GLOWMI_OK) return 0;
   glowmi::Problem p;
   fill_conv(p, d, geo);
+  if (set_operand_bytes(p, geo.x_elems, geo.w_elems, 1) != GLOWMI_OK) return 0;
   return split_bytes(glowmi::plan_i8(p, true), p);
 }
 
@@ -496,6 +499,7 @@ size_t glowmi_qfc_workspace_bytes(int32_t M, int32_t K, int32_t N) {
   if (check_fc(M, K, N) != GLOWMI_OK) return 0;
   glowmi::Problem p;
   fill_fc(p, M, K, N);
+  if (set_operand_bytes(p, (long long)M * K, (long long)K * N, 1) != GLOWMI_OK) return 0;
   return split_bytes(glowmi::plan_i8(p, true), p);
 }
 
@@ -673,6 +677,7 @@ size_t glowmi_conv2d_chainv_workspace_bytes(const glowmi_conv_desc* d, const glo
   glowmi_chain chain;
   glowmi::Problem p;
   fill_conv(p, d, geo);
+  if (set_operand_bytes(p, geo.x_elems, geo.w_elems, 4) != GLOWMI_OK) return 0;
   if (fixed_shape(ops, n_ops, &chain)) p.addend = chain.addend;
   else p.chain_n = n_ops;
   return split_bytes(glowmi::plan_f32(p, true), p);
@@ -704,6 +709,7 @@ size_t glowmi_qconv2d_chainv_workspace_bytes(const glowmi_conv_desc* d, const gl
   glowmi_chain chain;
   glowmi::Problem p;
   fill_conv(p, d, geo);
+  if (set_operand_bytes(p, geo.x_elems, geo.w_elems, 1) != GLOWMI_OK) return 0;
   if (fixed_shape(ops, n_ops, &chain)) p.addend = chain.addend;
   else p.chain_n = n_ops;
   return split_bytes(glowmi::plan_i8(p, true), p);

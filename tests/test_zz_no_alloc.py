@@ -39,13 +39,13 @@ def _run_both(M, K, N, seed, act):
 
 def test_fc_noalloc_two_calls_in_a_row_second_smaller():
     big, big_ref = _run_both(16, 8192, 2048, 4100, wl.ACT_RELU)        # 16 x 8192 x 2048: weight stream, grid split
-    small, small_ref = _run_both(4, 1024, 520, 4101, wl.ACT_NONE)      # smaller: stale partial sums stay behind it
+    small, small_ref = _run_both(4, 4096, 1024, 4101, wl.ACT_NONE)     # smaller: stale partial sums stay behind it
     np.testing.assert_array_equal(big, big_ref)
     np.testing.assert_array_equal(small, small_ref)
     # and the first shape again after the smaller one, then a tiled split-reduction shape
     again, again_ref = _run_both(16, 8192, 2048, 4100, wl.ACT_RELU)
     np.testing.assert_array_equal(again, big)
-    _run_both(48, 4096, 256, 4102, wl.ACT_RELU)
+    _run_both(80, 4096, 256, 4102, wl.ACT_RELU)
 
 
 def test_fc_noalloc_rejects_oversized_and_leaves_output_untouched():
