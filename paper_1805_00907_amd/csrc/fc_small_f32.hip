@@ -178,10 +178,16 @@ bool fc_small_f32_applicable(const Problem& p) {
   if (!p.b_is_kn || p.groups != 1 || p.addend || p.chain_n > 0) return false;
   if (knob_or(KNOB_F32_FC_SMALL_OFF, 0) != 0) return false;
   if (p.M > 64 || p.Kgemm % 4 != 0 || p.Kgemm < 64) return false;
-  // One workgroup per column strip pulls its strip of the matrix at the rate one CU sustains from
-  // memory (measured: about 45 GB/s), so beyond a few megabytes the kernels that split the reduction
-  // over the grid win although they need a second launch (measured per launch, back to back:
-  // 1 x 2048 x 1000 8.4 us here vs 11.3 us, 64 x 2048 x 1000 9.5 vs 13.0, 16 x 4096 x 1000 14.5 vs 10.6)
+  // One workgroup per column strip pulls its strip of the matrix at the rate ONE CU sustains from
+  // memory: about 45 GB/s when the weights are resident in the last-level cache and a third of that
+  // when they come from HBM.  Measured per launch, (rows x K x N): launched back to back on warm weights
+  // 1 x 2048 x 1000 8.4 us here vs 11.3 us for the weight-streaming kernel + finishing kernel,
+  // 64 x 2048 x 1000 9.5 vs 13.0 us (tiled), 16 x 4096 x 1000 14.5 vs 10.6 us; with the weights cold (other
+  // layers in between) 1 x 2048 x 1000 13.1 vs 10.8 us, 64 x 2048 x 1000 15.5 vs 15.0 us.  So up to 16 rows
+  // the streaming kernel, which spreads the matrix over every CU, stays the planner's choice (the knob
+  // F32_FC_SMALL_MIN_M lowers the bound for tests and experiments); with 17 to 64 rows this kernel
+  // replaces the tiled one for matrices of a few megabytes.
+  if (p.M < knob_or(KNOB_F32_FC_SMALL_MIN_M, 17)) return false;
   const long long max_kb = knob_or(KNOB_F32_FC_SMALL_MAX_KB, 8704);      // the knob: experiments and tests
   if ((long long)p.w_bytes > (max_kb << 10) || p.w_bytes > 0x7FFFFFFFu || p.x_bytes > 0x7FFFFFFFu) return false;
   return true;

@@ -328,7 +328,7 @@ def test_workspace_queries_are_pure():
     # the query plans with the operand sizes the call will see: a matrix too large for the single-launch
     # kernel gets the split-reduction workspace, a small one needs none
     assert glowmi.fc_workspace_bytes(16, 4096, 4096) > 0
-    assert glowmi.fc_workspace_bytes(1, 2048, 1000) == 0
+    assert glowmi.fc_workspace_bytes(40, 2048, 1000) == 0
     assert glowmi.fc_workspace_bytes(0, 1, 1) == 0
     big = glowmi.ConvDesc(16, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1)
     assert glowmi.conv2d_workspace_bytes(big) == 0          # plenty of tiles: no split

@@ -32,6 +32,7 @@ def test_fc_small_f32(shape, vw, knobs):
     if vw:
         knobs.set("F32_FC_SMALL_VW", vw)
     knobs.set("F32_FC_SMALL_MAX_KB", 1 << 20)        # take this kernel at any size (the planner stops at 8.5 MB)
+    knobs.set("F32_FC_SMALL_MIN_M", 1)               # and for any number of rows (the planner starts at 17)
     layer = wl.FcLayer("fs", M, K, N)
     a, w, b = wl.fc_inputs_f32(layer, 12000 + M + K + N, dist="uniform_fan_in")
     for act, bias in ((wl.ACT_RELU, b), (wl.ACT_NONE, None)):
@@ -55,19 +56,27 @@ def test_fc_small_f32_bias_at_a_four_byte_address_and_output_guards():
     bpad[1:] = torch.from_numpy(b)
     bias = bpad[1:]                                   # 4 bytes past a 16-byte boundary
     assert bias.data_ptr() % 16 == 4
+    glowmi.tuning_set("F32_FC_SMALL_MIN_M", 1)
     whole, y = G.guarded((M, N), torch.float32)
     glowmi.fc(ad, wd, bias, y, M, K, N, wl.ACT_RELU)
     torch.cuda.synchronize()
     assert glowmi.last_variant().startswith("fc_small_f32")
+    glowmi.tuning_reset()
     assert G.guards_intact(whole, torch.float32), "write outside the output tensor"
     G.assert_close_f32(y.cpu().numpy(), oracle.fc_f32(a, w, b, act=wl.ACT_RELU), "bias at a 4-byte address")
 
 
-def test_fc_small_f32_can_be_switched_off(knobs):
+def test_fc_small_f32_is_the_planners_choice_from_17_rows_and_can_be_switched_off(knobs):
     G = _gpu()
-    knobs.set("F32_FC_SMALL_OFF", 1)
-    layer = wl.FcLayer("fs", 4, 256, 64)
+    layer = wl.FcLayer("fs", 40, 256, 64)
     a, w, b = wl.fc_inputs_f32(layer, 12200)
+    got, variant = G.gpu_fc_f32(a, w, b, wl.ACT_RELU)
+    assert variant.startswith("fc_small_f32"), variant
+    G.assert_close_f32(got, oracle.fc_f32(a, w, b, act=wl.ACT_RELU), f"[{variant}]")
+    a16, w16, b16 = wl.fc_inputs_f32(wl.FcLayer("fs", 16, 256, 64), 12201)
+    got, variant = G.gpu_fc_f32(a16, w16, b16, wl.ACT_RELU)
+    assert variant == "fc_skinny16_f32", variant
+    knobs.set("F32_FC_SMALL_OFF", 1)
     got, variant = G.gpu_fc_f32(a, w, b, wl.ACT_RELU)
     assert not variant.startswith("fc_small_f32"), variant
     G.assert_close_f32(got, oracle.fc_f32(a, w, b, act=wl.ACT_RELU), f"[{variant}]")
