@@ -16,8 +16,12 @@ TOP/s, GB/s of algorithmic bytes, fraction of the layer's MFMA/HBM roofline, and
     (its HBM figure is then a cache figure), "cold" when the tensors exceed it; for every HBM-bound
     layer `us_cold` is the time per launch when the launches rotate over copies of the tensors that
     together exceed 512 MB, so that every launch streams from HBM;
-  * `us_graph`: for layers under 10 us, the time per launch of 100 back-to-back launches replayed as
+  * `us_graph`: for layers under 16 us, the time per launch of 100 back-to-back launches replayed as
     one HIP graph (launch-amortised figure).
+The top-level key `launch_floor_us` times the library's smallest kernel (16 elements of
+glowmi_dequantize, one workgroup) the same ways -- per launch between events, back to back, and as 100
+launches in one graph: what any single launch costs on this machine whatever it computes, so that the gap
+of a microsecond-scale layer to its roofline can be attributed.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--only] [--no-cpu-baseline]
 """
@@ -41,7 +45,7 @@ PEAK_HBM = 8.0e12              # B/s
 LLC_BYTES = 256 << 20          # last-level (Infinity) cache
 COLD_ROTATION_BYTES = 512 << 20
 GRAPH_LAUNCHES = 100
-SMALL_LAYER_US = 10.0
+SMALL_LAYER_US = 16.0
 
 WORKLOADS = ["vgg19_fp32", "resnet50_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8",
              "resnet50_tail_fp32", "resnet50_tail_int8", "resnet50_block_fp32", "resnet50_block_int8"]
@@ -312,6 +316,46 @@ def _time_cold(layer, stream, torch):
     return _median([a.elapsed_time(b) for a, b in ev]) * 1e3, copies
 
 
+class _Floor:
+    """The smallest launch the library has (one workgroup, 16 elements), timed like a layer."""
+
+    def __init__(self, torch, glowmi):
+        self.q = torch.zeros(16, dtype=torch.int8, device="cuda:0")
+        self.x = torch.empty(16, dtype=torch.float32, device="cuda:0")
+        self.qp = glowmi.QParam(0.5, 0)
+        self.glowmi = glowmi
+
+    def launch(self, stream):
+        self.glowmi.dequantize(self.q, self.x, self.qp, stream=stream)
+
+
+def launch_floor(torch, glowmi):
+    stream = torch.cuda.current_stream()
+    f = _Floor(torch, glowmi)
+    for _ in range(20):
+        f.launch(stream)
+    torch.cuda.synchronize()
+    ev = []
+    for _ in range(50):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        f.launch(stream)
+        e1.record(stream)
+        ev.append((e0, e1))
+    torch.cuda.synchronize()
+    eager = _median([a.elapsed_time(b) for a, b in ev]) * 1e3
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(200):
+        f.launch(stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    back_to_back = e0.elapsed_time(e1) * 1e3 / 200
+    return {"eager_events": round(eager, 2), "eager_back_to_back": round(back_to_back, 2),
+            "graph": round(_time_graph_amortised(f, torch), 2),
+            "what": "glowmi_dequantize of 16 elements (one workgroup)"}
+
+
 def run_workload(name, args, torch, glowmi, cpu_budget_s):
     from paper_1805_00907_amd import workloads as wl
     stream = torch.cuda.current_stream()
@@ -440,11 +484,23 @@ def run_workload(name, args, torch, glowmi, cpu_budget_s):
                         "launch": "hip graph replay" if args.graph else "eager",
                         "note": "ResNet-50/VGG-19 layer shapes, seeded synthetic values; no trained weights"},
              "roofline": roofline}
-    if not args.no_cpu_baseline:
-        block["cpu_baseline"] = _cpu_baseline(name, dtype, cfg_index, 1e12, cpu_budget_s)
     block["layers"] = layer_rows
+    # the CPU oracle is timed after ALL GPU measurements (see main): its threads would otherwise compete
+    # with the launching thread, and the GPU would idle and clock down between workloads
+    block["_cpu_args"] = (name, dtype, cfg_index, 1e12, cpu_budget_s)
     del layers
     torch.cuda.empty_cache()
+    return block
+
+
+def _finish_block(block, want_cpu):
+    """Attach the CPU baseline (keeping the key order value .. roofline, cpu_baseline, layers)."""
+    cpu_args = block.pop("_cpu_args")
+    if not want_cpu:
+        return block
+    layers = block.pop("layers")
+    block["cpu_baseline"] = _cpu_baseline(*cpu_args)
+    block["layers"] = layers
     return block
 
 
@@ -486,7 +542,14 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    floor = None if args.quick else launch_floor(torch, glowmi)
     head = run_workload(args.workload, args, torch, glowmi, cpu_budget_s=15.0)
+    others = {}
+    if not args.only:
+        others = {name: run_workload(name, args, torch, glowmi, cpu_budget_s=4.0)
+                  for name in ALSO if name != args.workload}
+    head = _finish_block(head, not args.no_cpu_baseline)
+    others = {name: _finish_block(b, not args.no_cpu_baseline) for name, b in others.items()}
     out = {
         "metric": f"{head['unit']} per conv/FC layer set ({args.workload}), with per-layer % of MFMA/HBM roofline",
         "value": head["value"], "unit": head["unit"], "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -496,10 +559,11 @@ def main():
     }
     if "cpu_baseline" in head:
         out["cpu_baseline"] = head["cpu_baseline"]
+    if floor is not None:
+        out["launch_floor_us"] = floor
     out["layers"] = head["layers"]
-    if not args.only:
-        out["workloads"] = {name: run_workload(name, args, torch, glowmi, cpu_budget_s=4.0)
-                            for name in ALSO if name != args.workload}
+    if others:
+        out["workloads"] = others
     print(json.dumps(out))
 
 

@@ -37,7 +37,7 @@ const char* const kKnobNames[KNOB_COUNT] = {
     "F32_TILE", "F32_SPLIT", "F32_PW_MIN_ITEMS", "F32_SMALL_MAX_TILES", "F32_SMALL_NO_SPLIT",
     "F32_SMALL_SPLIT_MAX_TILES", "F32_SMALL_MIN_WGS", "F32_FC_SMALL_OFF", "F32_FC_SMALL_VW", "F32_FC_SMALL_MAX_KB", "F32_FC_SMALL_MIN_M", "SMALLC_TH",
     "I8_TILE", "I8_WIDE_SPLIT", "I8_WIDE_NBUF", "SMALLC_I8_WGS", "I8_PW_MIN_ITEMS",
-    "I8_FC_SMALL_MAX_M", "I8_K3_MIN_BLOCKS", "I8_K3_WAVES", "I8_K3_GATHER", "I8_DEEP_OFF",
+    "I8_FC_SMALL_MAX_M", "I8_K3_MIN_BLOCKS", "I8_K3_WAVES", "I8_K3_GATHER",
 };
 std::atomic<int> g_knobs[KNOB_COUNT];
 std::once_flag g_knobs_once;

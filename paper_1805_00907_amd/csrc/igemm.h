@@ -20,7 +20,7 @@ enum Knob {
   KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
   KNOB_F32_SMALL_SPLIT_MAX_TILES, KNOB_F32_SMALL_MIN_WGS, KNOB_F32_FC_SMALL_OFF, KNOB_F32_FC_SMALL_VW, KNOB_F32_FC_SMALL_MAX_KB, KNOB_F32_FC_SMALL_MIN_M, KNOB_SMALLC_TH,
   KNOB_I8_TILE, KNOB_I8_WIDE_SPLIT, KNOB_I8_WIDE_NBUF, KNOB_SMALLC_I8_WGS, KNOB_I8_PW_MIN_ITEMS,
-  KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER, KNOB_I8_DEEP_OFF,
+  KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER,
   KNOB_COUNT
 };
 constexpr int kKnobUnset = INT_MIN;
@@ -115,8 +115,7 @@ enum KernelKind {
   KERNEL_PW,            // pointwise convolution, persistent workgroups
   KERNEL_K3C64,         // int8 3x3 over 64 channels
   KERNEL_FC_SMALL,      // FullyConnected with few rows in one launch (fp32: fc_small_f32.hip, int8: fc_small_i8.hip)
-  KERNEL_WIDE,          // int8 large contractions (igemm_i8_wide.hip)
-  KERNEL_DEEP           // int8 deep reduction on few pixels in one launch (conv_deep_i8.hip)
+  KERNEL_WIDE           // int8 large contractions (igemm_i8_wide.hip)
 };
 struct Plan {
   int kernel;           // KernelKind
@@ -149,9 +148,6 @@ int conv_small_f32_splits(const Problem& p);   // > 1: the split form of that ke
 // fp32 FullyConnected with few rows and a small weight matrix, in one launch (fc_small_f32.hip).
 bool fc_small_f32_applicable(const Problem& p);
 hipError_t launch_fc_small_f32(const Problem& p, hipStream_t stream, const char** variant);
-// int8 convolution with a deep reduction on few pixels, in one launch (conv_deep_i8.hip).
-bool deep_i8_applicable(const Problem& p);
-hipError_t launch_deep_i8(const Problem& p, hipStream_t stream, const char** variant);
 bool pw_i8_applicable(const Problem& p);
 hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** variant);
 // int8 3x3 convolution over 64 input channels on many pixels (conv_k3c64_i8.hip).

@@ -538,7 +538,6 @@ Plan plan_i8(const Problem& p, bool allow_split) {
     if (pw_i8_applicable(p)) { pl.kernel = KERNEL_PW; return pl; }
     if (k3c64_i8_applicable(p)) { pl.kernel = KERNEL_K3C64; return pl; }
     if (fc_small_i8_applicable(p)) { pl.kernel = KERNEL_FC_SMALL; return pl; }
-    if (deep_i8_applicable(p)) { pl.kernel = KERNEL_DEEP; return pl; }
   }
   pl.bk = BKQ;
   pl.slabs = (p.Kgemm + BKQ - 1) / BKQ;
@@ -596,7 +595,6 @@ hipError_t launch_i8(const Problem& p_in, const Plan& plan, hipStream_t stream, 
     case KERNEL_PW: return launch_pw_i8(p_in, stream, variant);
     case KERNEL_K3C64: return launch_k3c64_i8(p_in, stream, variant);
     case KERNEL_FC_SMALL: return launch_fc_small_i8(p_in, stream, variant);
-    case KERNEL_DEEP: return launch_deep_i8(p_in, stream, variant);
     default: break;
   }
   if (plan.split_k > 1 && !p_in.partial) return hipErrorInvalidValue;   // the ABI layer never plans a split without a workspace

@@ -134,3 +134,47 @@ def test_launch_on_a_caller_stream_and_back_to_back():
     G.assert_close_f32(y1.cpu().numpy(), r1, "first layer on a caller stream")
     r2 = oracle.conv2d_f32(y1.cpu().numpy(), w2, b2, (1, 1), (0, 0, 0, 0), 1, act=wl.ACT_NONE)
     G.assert_close_f32(y2.cpu().numpy(), r2, "second layer on a caller stream")
+
+
+@pytest.mark.parametrize("case", ["fc_skinny16", "conv_small", "conv_tiled_split", "fc_tiled"])
+def test_bias_at_a_four_byte_address(case):
+    """The ABI asks only 4-byte alignment of the bias: every kernel family reads it correctly from an
+    address 4 bytes past a 16-byte boundary."""
+    import torch
+    import paper_1805_00907_amd as glowmi
+    G = _gpu()
+    rng = np.random.default_rng(9500)
+
+    def shifted(b):
+        pad = torch.zeros(b.size + 1, dtype=torch.float32, device="cuda:0")
+        pad[1:] = torch.from_numpy(b)
+        view = pad[1:]
+        assert view.data_ptr() % 16 == 4
+        return view
+
+    if case in ("fc_skinny16", "fc_tiled"):
+        M, K, N = (8, 512, 264) if case == "fc_skinny16" else (70, 4096, 96)
+        a = rng.uniform(-1, 1, size=(M, K)).astype(np.float32)
+        w = (rng.uniform(-1, 1, size=(K, N)) / np.sqrt(K)).astype(np.float32)
+        b = rng.uniform(-0.1, 0.1, size=(N,)).astype(np.float32)
+        y = G.poison((M, N), torch.float32)
+        glowmi.fc(G.dev(a), G.dev(w), shifted(b), y, M, K, N, wl.ACT_RELU, G.workspace(glowmi.fc_workspace_bytes(M, K, N)))
+        torch.cuda.synchronize()
+        variant = glowmi.last_variant()
+        assert ("skinny16" in variant) == (case == "fc_skinny16"), variant
+        G.assert_close_f32(y.cpu().numpy(), oracle.fc_f32(a, w, b, act=wl.ACT_RELU), f"{case} [{variant}]")
+        return
+    if case == "conv_small":
+        shape, wshape, pd = (1, 14, 14, 64), (64, 3, 3, 64), (1, 1, 1, 1)
+    else:
+        shape, wshape, pd = (1, 7, 7, 512), (96, 3, 3, 512), (1, 1, 1, 1)
+    x = rng.uniform(-1, 1, size=shape).astype(np.float32)
+    wt = (rng.uniform(-1, 1, size=wshape) / np.sqrt(np.prod(wshape[1:]))).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(wshape[0],)).astype(np.float32)
+    desc = G.make_desc(x.shape, wt.shape, (1, 1), pd, 1)
+    oh, ow = glowmi.conv_out_shape(desc)
+    y = G.poison((shape[0], oh, ow, wshape[0]), torch.float32)
+    glowmi.conv2d(G.dev(x), G.dev(wt), shifted(b), y, desc, wl.ACT_RELU, G.workspace(glowmi.conv2d_workspace_bytes(desc)))
+    torch.cuda.synchronize()
+    variant = glowmi.last_variant()
+    G.assert_close_f32(y.cpu().numpy(), oracle.conv2d_f32(x, wt, b, (1, 1), pd, 1, act=wl.ACT_RELU), f"{case} [{variant}]")
