@@ -41,6 +41,18 @@ if ROOT not in sys.path:
 # MI355X published peaks (dense)
 PEAK_FP32_MFMA = 157.3e12      # FLOP/s, fp32 matrix
 PEAK_INT8_MFMA = 5.0e15        # OP/s
+PEAK_BF16_MFMA = 2.5e15        # FLOP/s, bf16 matrix (the fp32 three-piece kernel multiplies bf16 pieces)
+P3_PRODUCTS = 6                # bf16 products that kernel takes per fp32 multiply-add
+
+
+def _mfma_peak(dtype, variant=""):
+    """(published peak of the matrix-core dtype the kernel multiplies in, matrix-core products per algorithmic
+    multiply-add).  The fp32 three-piece kernel runs on the bf16 cores with six products per fp32 product."""
+    if dtype != "f32":
+        return PEAK_INT8_MFMA, 1
+    if "igemm_f32_p3" in variant:
+        return PEAK_BF16_MFMA, P3_PRODUCTS
+    return PEAK_FP32_MFMA, 1
 PEAK_HBM = 8.0e12              # B/s
 LLC_BYTES = 256 << 20          # last-level (Infinity) cache
 COLD_ROTATION_BYTES = 512 << 20
@@ -92,10 +104,7 @@ class Layer:
         elem = 4 if dtype == "f32" else 1
         self.ops = spec.ops
         self.bytes = spec.alg_bytes(elem)
-        peak = PEAK_FP32_MFMA if dtype == "f32" else PEAK_INT8_MFMA
-        t_mfma, t_hbm = self.ops / peak, self.bytes / PEAK_HBM
-        self.bound = "mfma" if t_mfma >= t_hbm else "hbm"
-        self.t_roof = max(t_mfma, t_hbm)
+        self.set_variant("")
         if self.is_conv:
             self.desc = glowmi.ConvDesc(spec.n, spec.h, spec.w, spec.c, spec.k, spec.r, spec.s, spec.stride,
                                         spec.stride, spec.pad, spec.pad, spec.pad, spec.pad, spec.groups)
@@ -130,6 +139,14 @@ class Layer:
         self.ws = torch.empty(nws, dtype=torch.uint8, device=dev) if nws else None
         self.glowmi = glowmi
         self.variant = ""
+
+    def set_variant(self, variant):
+        """The roofline of a layer depends on which matrix cores its kernel multiplies on."""
+        self.variant = variant
+        self.mfma_peak, self.products = _mfma_peak(self.dtype, variant)
+        t_mfma, t_hbm = self.ops / self.mfma_peak, self.bytes / PEAK_HBM
+        self.bound = "mfma" if t_mfma >= t_hbm else "hbm"
+        self.t_roof = max(t_mfma, t_hbm)
 
     def device_bytes(self):
         return sum(t.numel() * t.element_size() for t in (getattr(self, n) for n in self.TENSORS) if t is not None)
@@ -372,7 +389,10 @@ def run_workload(name, args, torch, glowmi, cpu_budget_s):
 
     for l in layers:                      # first touch + variant names
         l.launch(stream)
-        l.variant = ("sequence:" if isinstance(l, Sequence) else "") + glowmi.last_variant()
+        if isinstance(l, Sequence):
+            l.variant = "sequence:" + glowmi.last_variant()
+        else:
+            l.set_variant(glowmi.last_variant())
     torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
@@ -440,9 +460,29 @@ def run_workload(name, args, torch, glowmi, cpu_budget_s):
         dom_ms = [dom_ev[s][j][0].elapsed_time(dom_ev[s][j][1]) for s in range(args.steps) for j in range(len(dom_idx))]
     avg_launch_s = sum(dom_ms) / len(dom_ms) * 1e-3
     dom_layers = [layers[i] for i in dom_idx]
+    call_s = None
+    if "igemm_f32_p3" in dominant and not args.graph:
+        # One call of that kernel's layer = two packing kernels + the contraction.  The roofline figure is the
+        # contraction kernel's own duration (what rocprofv3 reports for it): timed again with the packing
+        # switched off, the planes of the same operands still being in each layer's workspace.
+        call_s = avg_launch_s
+        glowmi.tuning_set("F32_P3_REUSE_PLANES", 1)
+        try:
+            kev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in dom_layers]
+                   for _ in range(args.steps)]
+            for srow in kev:
+                for l, (e0, e1) in zip(dom_layers, srow):
+                    e0.record(stream)
+                    l.launch(stream)
+                    e1.record(stream)
+            torch.cuda.synchronize()
+        finally:
+            glowmi.tuning_reset()
+        kms = [e0.elapsed_time(e1) for srow in kev for (e0, e1) in srow]
+        avg_launch_s = sum(kms) / len(kms) * 1e-3
     dom_ops = sum(l.ops for l in dom_layers) / len(dom_layers)          # algorithmic ops per launch
     dom_bytes = sum(l.bytes for l in dom_layers) / len(dom_layers)
-    mfma_peak = PEAK_FP32_MFMA if dtype == "f32" else PEAK_INT8_MFMA
+    mfma_peak, products = _mfma_peak(dtype, dominant)
     dom_bound = "mfma" if dom_ops / mfma_peak >= dom_bytes / PEAK_HBM else "hbm"
     if dom_bound == "mfma":
         achieved, peak, runit = dom_ops / avg_launch_s / 1e12, mfma_peak / 1e12, unit
@@ -456,6 +496,14 @@ def run_workload(name, args, torch, glowmi, cpu_budget_s):
     roofline = {"bound": dom_bound, "achieved": round(achieved, 3), "peak": peak, "unit": runit,
                 "frac": round(achieved / peak, 4), "traffic": traffic, "kernel": dominant,
                 "launches_per_step": len(dom_idx), "avg_launch_us": round(avg_launch_s * 1e6, 2)}
+    if products > 1 and dom_bound == "mfma":
+        # `frac` is algorithmic fp32 flops against the bf16 peak; the matrix pipes execute `products` bf16
+        # multiply-adds per algorithmic one, so their utilisation is products x frac
+        roofline.update({"mfma_dtype": "bf16, fp32 accumulate", "products_per_mac": products,
+                         "pipe_frac": round(products * achieved / peak, 4),
+                         "fp32_mfma_peak": PEAK_FP32_MFMA / 1e12})
+    if call_s is not None:
+        roofline["call_us_with_packing"] = round(call_s * 1e6, 2)
 
     layer_rows = []
     for l, ms in zip(layers, per_layer_ms):
@@ -465,6 +513,8 @@ def run_workload(name, args, torch, glowmi, cpu_budget_s):
                "GB/s": round(l.bytes / t / 1e9, 1), "bound": l.bound,
                "roofline_frac": round(l.t_roof / t, 4),
                "llc": "warm" if l.device_bytes() <= LLC_BYTES else "cold"}
+        if getattr(l, "products", 1) > 1:
+            row["pipe_frac"] = round(l.products * l.ops / l.mfma_peak / t, 4)
         if not args.quick:
             if l.bound == "hbm" and row["llc"] == "warm":
                 us_cold, copies = _time_cold(l, stream, torch)

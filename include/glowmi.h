@@ -18,15 +18,23 @@
  *    boundary will do), else GLOWMI_ERR_ALIGN.  bias may be NULL (treated as zeros).
  *  - Calls are asynchronous on `stream`, never synchronise the device and never allocate.
  *  - `workspace` is optional scratch in device memory (16-byte aligned).  With NULL / 0 bytes the
- *    call still computes the same result; with at least glowmi_*_workspace_bytes() bytes the
- *    library may split the reduction dimension over more workgroups (small-M layers).  The
- *    contents on entry do not matter and are undefined on return.  Two calls that share a
- *    workspace must be ordered on one stream.
+ *    call still computes the same result to the same accuracy; with at least
+ *    glowmi_*_workspace_bytes() bytes the library may split the reduction dimension over more
+ *    workgroups (small-M layers) and, for large fp32 contractions, repack both operands there (three
+ *    bf16 pieces per value, 6 bytes per element: see "Results" below), which is faster.  A workspace
+ *    smaller than that figure is not used at all.  The contents on entry do not matter and are
+ *    undefined on return.  Two calls that share a workspace must be ordered on one stream.
  *  - Arguments are validated on the host before anything is launched.  On any error nothing is
  *    launched, y is untouched, the status says why and glowmi_last_error() gives a sentence.
  *  - Every tensor must hold fewer than 2^31 elements (GLOWMI_ERR_UNSUPPORTED otherwise).
- *  - Results: fp32 entry points accumulate in fp32 (order unspecified); the int8 entry points are
- *    exact integer arithmetic and reproducible bit for bit.
+ *  - Results: fp32 entry points accumulate in fp32 (order unspecified).  Products are fp32 products:
+ *    either the fp32 matrix cores' own, or -- large contractions with a workspace -- both operands
+ *    cut exactly into three bf16 pieces (x = hi + mid + lo) and the six piece products of weight
+ *    down to 2^-16 multiplied exactly on the bf16 matrix cores; the three dropped products are below
+ *    2^-22 of |x*y|, the size of one fp32 rounding.  Either way |result - exact| stays within a few
+ *    2^-22 * (|A||W| + |bias|) componentwise.  With non-finite inputs the outputs they reach are
+ *    non-finite, but an infinity may come out as NaN.  The int8 entry points are exact integer
+ *    arithmetic and reproducible bit for bit.
  */
 #ifndef GLOWMI_H
 #define GLOWMI_H
@@ -104,13 +112,14 @@ size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N);
 
 /*
  * glowmi_fc for callers that cannot allocate and have no workspace to hand over: code under HIP graph
- * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels and
- * results as glowmi_fc called with a workspace of glowmi_fc_workspace_bytes(); the split-reduction
- * partial sums go to a buffer that is part of the library image (a static array in device memory of
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and checks as glowmi_fc,
+ * and the kernels and results glowmi_fc gives with a workspace that holds its split-reduction partial sums
+ * (operands are never repacked here: the fp32 matrix-core kernels are used whatever the size); the partial
+ * sums go to a buffer that is part of the library image (a static array in device memory of
  * glowmi_fc_noalloc_max_scratch_bytes() = 8 MiB, one copy per GPU the library is used on, held until
  * the process ends).  The call allocates nothing and calls no allocating routine.
- *   - A shape whose partial sums need more than that (glowmi_fc_workspace_bytes(M, K, N) above the
- *     maximum) is rejected with GLOWMI_ERR_UNSUPPORTED and a message; nothing is launched.
+ *   - A shape whose partial sums need more than that is rejected with GLOWMI_ERR_UNSUPPORTED and a message;
+ *     nothing is launched.
  *   - Every call on one GPU shares that GPU's buffer: calls must be ordered on one stream (or otherwise
  *     serialised); calls that overlap on one GPU race.  Nothing in the buffer needs to start at zero
  *     (every partial sum is written before it is read), so its stale contents are harmless.

@@ -34,7 +34,7 @@ glowmi_status fail(glowmi_status s, const char* fmt, ...) {
 // ---- tuning knobs: seeded once from the environment, changed only through glowmi_tuning_set ----
 namespace {
 const char* const kKnobNames[KNOB_COUNT] = {
-    "F32_TILE", "F32_SPLIT", "F32_PW_MIN_ITEMS", "F32_SMALL_MAX_TILES", "F32_SMALL_NO_SPLIT",
+    "F32_TILE", "F32_SPLIT", "F32_P3", "F32_P3_MIN_M", "F32_P3_RATIO", "F32_P3_BN", "F32_P3_REUSE_PLANES", "F32_PW_MIN_ITEMS", "F32_SMALL_MAX_TILES", "F32_SMALL_NO_SPLIT",
     "F32_SMALL_SPLIT_MAX_TILES", "F32_SMALL_MIN_WGS", "F32_FC_SMALL_OFF", "F32_FC_SMALL_VW", "F32_FC_SMALL_MAX_KB", "F32_FC_SMALL_MIN_M", "SMALLC_TH",
     "I8_TILE", "I8_WIDE_SPLIT", "I8_WIDE_NBUF", "SMALLC_I8_WGS", "I8_PW_MIN_ITEMS",
     "I8_FC_SMALL_MAX_M", "I8_K3_MIN_BLOCKS", "I8_K3_WAVES", "I8_K3_GATHER",
@@ -132,6 +132,7 @@ void fill_divs(glowmi::Problem& p) {
 
 void fill_conv(glowmi::Problem& p, const glowmi_conv_desc* d, const Geometry& geo) {
   std::memset(&p, 0, sizeof(p));
+  p.allow_pack = 1;
   p.n = d->n; p.h = d->h; p.w_ = d->w; p.c = d->c;
   p.k = d->k; p.r = d->r; p.s = d->s;
   p.oh = geo.oh; p.ow = geo.ow;
@@ -157,6 +158,7 @@ glowmi_status check_fc(int32_t M, int32_t K, int32_t N) {
 // FullyConnected as the same contraction: rows are "images" of a 1x1 map with K channels.
 void fill_fc(glowmi::Problem& p, int32_t M, int32_t K, int32_t N) {
   std::memset(&p, 0, sizeof(p));
+  p.allow_pack = 1;
   p.n = M; p.h = 1; p.w_ = 1; p.c = K;
   p.k = N; p.r = 1; p.s = 1;
   p.oh = 1; p.ow = 1;
@@ -246,20 +248,26 @@ glowmi_status finish(hipError_t e, const char* variant) {
   return GLOWMI_OK;
 }
 
+// Workspace a plan wants: repacked operands first (a multiple of 256 bytes), then the partial sums of a split reduction.
 size_t split_bytes(const glowmi::Plan& pl, const glowmi::Problem& p) {
-  return pl.split_k > 1 ? (size_t)pl.split_k * (size_t)p.M * (size_t)p.k * 4u : 0u;
+  return pl.pack_bytes + (pl.split_k > 1 ? (size_t)pl.split_k * (size_t)p.M * (size_t)p.k * 4u : 0u);
 }
 
-// Plan once per call: with the split the planner wants when the workspace can hold its partial sums,
-// without a split otherwise.  Sets p.partial accordingly.
+// Plan once per call: with what the planner wants from a workspace (repacked operands, a split reduction)
+// when the caller's workspace can hold it, without either otherwise.  Sets p.planes and p.partial accordingly.
 template <typename PlanFn>
 glowmi::Plan plan_with_workspace(glowmi::Problem& p, PlanFn plan_fn, void* workspace, size_t workspace_bytes) {
   glowmi::Plan plan = plan_fn(p, true);
   const size_t need = split_bytes(plan, p);
   p.partial = nullptr;
+  p.planes = nullptr;
   if (need > 0) {
-    if (workspace_usable(workspace, workspace_bytes, need)) p.partial = workspace;
-    else plan = plan_fn(p, false);
+    if (workspace_usable(workspace, workspace_bytes, need)) {
+      if (plan.pack_bytes > 0) p.planes = workspace;
+      if (plan.split_k > 1) p.partial = static_cast<unsigned char*>(workspace) + plan.pack_bytes;
+    } else {
+      plan = plan_fn(p, false);
+    }
   }
   return plan;
 }
@@ -447,7 +455,8 @@ glowmi_status glowmi_fc_noalloc(const float* a, const float* w, const float* bia
   glowmi::Problem p;
   glowmi_status st = setup_fc_f32(a, w, bias, y, M, K, N, act, p);
   if (st != GLOWMI_OK) return st;
-  const glowmi::Plan plan = glowmi::plan_f32(p, true);      // the same plan glowmi_fc takes with a full workspace
+  p.allow_pack = 0;     // the static buffer is for partial sums only: operands are never repacked into it
+  const glowmi::Plan plan = glowmi::plan_f32(p, true);      // otherwise the plan glowmi_fc takes with a full workspace
   const size_t need = split_bytes(plan, p);
   if (need > kScratchBytes)
     return fail(GLOWMI_ERR_UNSUPPORTED,

@@ -17,7 +17,7 @@ namespace glowmi {
 // library is first used and can be changed afterwards only through glowmi_tuning_set(): nothing on the
 // dispatch path calls getenv.  kKnobUnset means "the planner's own choice".
 enum Knob {
-  KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
+  KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_P3, KNOB_F32_P3_MIN_M, KNOB_F32_P3_RATIO, KNOB_F32_P3_BN, KNOB_F32_P3_REUSE_PLANES, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
   KNOB_F32_SMALL_SPLIT_MAX_TILES, KNOB_F32_SMALL_MIN_WGS, KNOB_F32_FC_SMALL_OFF, KNOB_F32_FC_SMALL_VW, KNOB_F32_FC_SMALL_MAX_KB, KNOB_F32_FC_SMALL_MIN_M, KNOB_SMALLC_TH,
   KNOB_I8_TILE, KNOB_I8_WIDE_SPLIT, KNOB_I8_WIDE_NBUF, KNOB_SMALLC_I8_WGS, KNOB_I8_PW_MIN_ITEMS,
   KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER,
@@ -77,6 +77,7 @@ struct Problem {
   const void* bias;   // [k] float or int32, may be null
   void* y;            // output [M][k]
   void* partial;      // split-K partial sums [split_k][M][k] (float or int32), null when split_k == 1
+  const void* planes; // fp32 three-piece form: the bf16 planes of the input, then (at wp_offset) of the weights; workspace
   const void* addend; // tensor operand of the element-wise chain [M][k] (float or int8), may be null:
                       // added to the accumulator after the bias and before the activation
   int32_t n, h, w_, c;
@@ -92,6 +93,8 @@ struct Problem {
   uint32_t x_bytes, w_bytes; // sizes of the input and weight tensors (hardware-checked buffer loads)
   int32_t act;              // 0 none, 1 relu
   int32_t b_is_kn;          // FC weight layout
+  int32_t allow_pack;       // the caller's workspace may hold repacked operands (fp32 three-piece form)
+  uint32_t wp_offset;       // byte offset of the weight planes inside `planes`
   // quantized form only
   int32_t x_off, w_off, y_off;
   int32_t mant, shift;      // requantize multiplier
@@ -115,7 +118,8 @@ enum KernelKind {
   KERNEL_PW,            // pointwise convolution, persistent workgroups
   KERNEL_K3C64,         // int8 3x3 over 64 channels
   KERNEL_FC_SMALL,      // FullyConnected with few rows in one launch (fp32: fc_small_f32.hip, int8: fc_small_i8.hip)
-  KERNEL_WIDE           // int8 large contractions (igemm_i8_wide.hip)
+  KERNEL_WIDE,          // int8 large contractions (igemm_i8_wide.hip)
+  KERNEL_P3             // fp32 large contractions on the bf16 matrix cores, operands cut into three pieces (igemm_f32_p3.hip)
 };
 struct Plan {
   int kernel;           // KernelKind
@@ -125,6 +129,7 @@ struct Plan {
   int slabs;            // ceil(Kgemm / bk)
   int split_k;
   int slabs_per_split;
+  size_t pack_bytes = 0;  // workspace bytes for repacked operands, ahead of the partial sums (KERNEL_P3)
 };
 Plan plan_f32(const Problem& p, bool allow_split);
 Plan plan_i8(const Problem& p, bool allow_split);
@@ -148,6 +153,12 @@ int conv_small_f32_splits(const Problem& p);   // > 1: the split form of that ke
 // fp32 FullyConnected with few rows and a small weight matrix, in one launch (fc_small_f32.hip).
 bool fc_small_f32_applicable(const Problem& p);
 hipError_t launch_fc_small_f32(const Problem& p, hipStream_t stream, const char** variant);
+// fp32 large contractions as six bf16 MFMAs per product over operands cut into three bf16 planes (igemm_f32_p3.hip).
+bool p3_f32_applicable(const Problem& p);
+Plan plan_p3_f32(const Problem& p);
+hipError_t launch_p3_f32(const Problem& p, const Plan& plan, hipStream_t stream, const char** variant);
+// Finishing kernel of a split fp32 reduction (igemm_f32.hip): sums p.partial in split order, bias, addend, activation.
+hipError_t launch_splitk_finish_f32(const Problem& p, const Plan& plan, hipStream_t stream);
 bool pw_i8_applicable(const Problem& p);
 hipError_t launch_pw_i8(const Problem& p, hipStream_t stream, const char** variant);
 // int8 3x3 convolution over 64 input channels on many pixels (conv_k3c64_i8.hip).

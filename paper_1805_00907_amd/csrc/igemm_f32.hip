@@ -675,6 +675,8 @@ Plan plan_f32(const Problem& p, bool allow_split) {
   if (!forced) {
     // kernels of their own, no workspace
     if (smallc_f32_applicable(p) && !p.addend) { pl.kernel = KERNEL_SMALLC; return pl; }
+    // large contractions with a workspace to repack the operands into: the bf16 three-piece kernel
+    if (allow_split && p.allow_pack && p3_f32_applicable(p)) return plan_p3_f32(p);
     if (pw_f32_applicable(p)) { pl.kernel = KERNEL_PW; return pl; }
     if (conv_small_f32_applicable(p)) { pl.kernel = KERNEL_SMALL; return pl; }
     if (fc_small_f32_applicable(p)) { pl.kernel = KERNEL_FC_SMALL; return pl; }
@@ -793,12 +795,26 @@ hipError_t launch_tile(const Problem& p, const Plan& plan, hipStream_t stream, b
 }
 }  // namespace
 
+hipError_t launch_splitk_finish_f32(const Problem& p, const Plan& plan, hipStream_t stream) {
+  const int total = p.M * p.k;
+  const bool wide = p.k % 4 == 0 && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;   // y, partial, addend are 16-byte aligned
+  int blocks = (total / (wide ? 4 : 1) + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  auto kern = wide ? splitk_finish_f32<4> : splitk_finish_f32<1>;
+  hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, stream,
+                     static_cast<const float*>(p.partial), static_cast<const float*>(p.bias),
+                     static_cast<const float*>(p.addend),
+                     static_cast<float*>(p.y), total, p.k, plan.split_k, p.act);
+  return hipGetLastError();
+}
+
 hipError_t launch_f32(const Problem& p_in, const Plan& plan, hipStream_t stream, const char** variant) {
   switch (plan.kernel) {
     case KERNEL_SMALLC: return launch_smallc_f32(p_in, stream, variant);
     case KERNEL_PW: return launch_pw_f32(p_in, stream, variant);
     case KERNEL_SMALL: return launch_conv_small_f32(p_in, stream, variant);
     case KERNEL_FC_SMALL: return launch_fc_small_f32(p_in, stream, variant);
+    case KERNEL_P3: return launch_p3_f32(p_in, plan, stream, variant);
     default: break;
   }
   if (plan.split_k > 1 && !p_in.partial) return hipErrorInvalidValue;   // the ABI layer never plans a split without a workspace
@@ -853,16 +869,7 @@ hipError_t launch_f32(const Problem& p_in, const Plan& plan, hipStream_t stream,
     hipLaunchKernelGGL(splitk_finish_chain_f32, dim3(blocks), dim3(256), 0, stream, p, total);
     e = hipGetLastError();
   } else if (plan.split_k > 1) {
-    const int total = p.M * p.k;
-    const bool wide = p.k % 4 == 0 && (reinterpret_cast<uintptr_t>(p.bias) & 15) == 0;   // y, partial, addend are 16-byte aligned
-    int blocks = (total / (wide ? 4 : 1) + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    auto kern = wide ? splitk_finish_f32<4> : splitk_finish_f32<1>;
-    hipLaunchKernelGGL(kern, dim3(blocks), dim3(256), 0, stream,
-                       static_cast<const float*>(p.partial), static_cast<const float*>(p.bias),
-                       static_cast<const float*>(p.addend),
-                       static_cast<float*>(p.y), total, p.k, plan.split_k, p.act);
-    e = hipGetLastError();
+    e = launch_splitk_finish_f32(p, plan, stream);
   }
   return e;
 }

@@ -1,0 +1,553 @@
+// fp32 Convolution / FullyConnected on the bf16 matrix cores, exact to fp32 level: the contraction of
+// Section 3.4 / 3.1 of the paper (MatMul + broadcast add, the convolution loop nest) with every fp32
+// operand cut into three bf16 pieces first.
+//
+//   x = hi + mid + lo exactly (mask off the upper 16 bits of the word, subtract, repeat: each piece
+//   keeps eight significant bits and every subtraction is exact), and a product x*y is taken as the six
+//   piece products down to weight 2^-16: hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi.
+//   v_mfma_f32_32x32x16_bf16 multiplies bf16 exactly and accumulates in fp32, so what is lost against an
+//   fp32 multiply-add chain is the dropped mid*lo, lo*mid, lo*lo (below 2^-22 of |x*y|, the size of the
+//   rounding an fp32 FMA makes anyway).  Six bf16 MFMAs cover 16 reduction steps of a 32 x 32 block in
+//   192 matrix-pipe cycles; v_mfma_f32_32x32x2_f32 needs 512 for the same.
+//
+// Cutting the operands inside the contraction kernel costs about six vector instructions per staged
+// element, again for every tile that stages it (a 3 x 3 layer stages each input element 9 x N/128
+// times), and measured that eats most of the gain.  So the pieces are made ONCE per call by a packing
+// pass into three bf16 planes per operand (workspace), FullyConnected weights ([K][N]) transposed to
+// K-contiguous on the way, and the contraction kernel has no vector ALU work in its loop at all:
+//   - 128 pixels x 64*WN channels per workgroup; 2 x WN wavefronts tile the output (64 x 64 each) and two such
+//     sets split every slab's 32 reduction indices between them (16 each): a wavefront then reads 512 bytes
+//     of fragments per MFMA, which together with the incoming slabs keeps LDS at three quarters of its
+//     bandwidth when the matrix pipes are full (64 x 32 per wavefront without the split needs all of it and
+//     was measured LDS-bound); the two partial tiles are exchanged through LDS at the end and each
+//     wavefront finishes half of them;
+//   - slabs of 32 reduction indices = one 64-byte row piece per plane, always inside one filter tap
+//     (channels per group are walked in steps of 32), so tap and channel offset are scalars;
+//   - both operands' planes go from global memory straight into LDS (buffer loads with the LDS bit) into a
+//     ring of NBUF slab buffers, NBUF - 1 slabs in flight; lanes that are out of range (rows past the
+//     tensor, channel tail, taps on padding) get zeros from the hardware, which is what they must be;
+//   - lane l of a load fetches chunk (l % 4) ^ ((l / 16) % 4) of row l / 4: the four 16-byte chunks of a
+//     row are XOR-swizzled so that the 16 rows one phase of a fragment ds_read_b128 touches fall on 16
+//     different bank groups, without padding;
+//   - the epilogue is the fp32 one (bias, tensor add, Relu on the accumulators, one store), or partial
+//     tiles for a split reduction that the common finishing kernel sums in split order.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <type_traits>
+
+#include "igemm.h"
+#include "lds_direct.h"
+
+namespace glowmi {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+constexpr int PBM = 128;                 // pixels per workgroup tile
+constexpr int PBK = 32;                  // reduction indices per slab
+constexpr int PROW = 2 * PBK;            // bytes of one plane row in LDS
+constexpr int P3_FLUSH = 32;             // accumulators are folded into a second set every 1024 reduction steps
+constexpr size_t kPlaneAlign = 256;
+
+// ------------------------------------------------------------------------------------------------
+// Packing: fp32 -> three bf16 planes
+// ------------------------------------------------------------------------------------------------
+struct Pieces { unsigned h, m, l; };     // each piece's bf16 is the upper half of the word
+__device__ __forceinline__ Pieces split3(float x) {
+  Pieces r;
+  r.h = __builtin_bit_cast(unsigned, x) & 0xffff0000u;
+  const float r1 = x - __builtin_bit_cast(float, r.h);
+  r.m = __builtin_bit_cast(unsigned, r1) & 0xffff0000u;
+  r.l = __builtin_bit_cast(unsigned, r1 - __builtin_bit_cast(float, r.m));   // eight significant bits: already a bf16
+  return r;
+}
+// the upper halves of two words side by side: a in the low half (earlier index), b in the high half
+__device__ __forceinline__ unsigned pack_upper(unsigned a, unsigned b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
+__device__ __forceinline__ void split8(const float (&v)[8], v4u& h, v4u& m, v4u& l) {
+  Pieces e[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) e[i] = split3(v[i]);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    h[i] = pack_upper(e[2 * i].h, e[2 * i + 1].h);
+    m[i] = pack_upper(e[2 * i].m, e[2 * i + 1].m);
+    l[i] = pack_upper(e[2 * i].l, e[2 * i + 1].l);
+  }
+}
+
+// src: count8 groups of 8 consecutive floats; dst: three planes of plane_elems bf16 each, same order.
+__global__ __launch_bounds__(256) void pack3_rows_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
+                                                         long long count8, long long plane_elems) {
+  const long long stride = (long long)gridDim.x * 256;
+  for (long long g = (long long)blockIdx.x * 256 + threadIdx.x; g < count8; g += stride) {
+    const v4f a = *reinterpret_cast<const v4f*>(src + 8 * g);
+    const v4f b = *reinterpret_cast<const v4f*>(src + 8 * g + 4);
+    const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+    v4u h, m, l;
+    split8(v, h, m, l);
+    *reinterpret_cast<v4u*>(dst + 8 * g) = h;
+    *reinterpret_cast<v4u*>(dst + plane_elems + 8 * g) = m;
+    *reinterpret_cast<v4u*>(dst + 2 * plane_elems + 8 * g) = l;
+  }
+}
+
+// FullyConnected weight [K][N] (N contiguous) -> three planes [N][K] (K contiguous).  K % 8 == 0.
+// One workgroup per 64 (k) x 32 (n) tile, transposed through LDS.
+__global__ __launch_bounds__(256) void pack3_transposed_kernel(const float* __restrict__ w, unsigned short* __restrict__ dst,
+                                                               int K, int N, int tiles_n) {
+  __shared__ float tile[64][33];
+  const int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
+  const int k0 = tk * 64, n0 = tn * 32;
+  const int tid = threadIdx.x;
+  {
+    const int n = tid & 31, kr = tid >> 5;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int k = kr + 8 * q;
+      tile[k][n] = (k0 + k < K && n0 + n < N) ? w[(size_t)(k0 + k) * N + n0 + n] : 0.f;
+    }
+  }
+  __syncthreads();
+  const int n = tid >> 3, kc = tid & 7;
+  if (n0 + n >= N || k0 + kc * 8 >= K) return;
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) v[e] = tile[kc * 8 + e][n];
+  v4u h, m, l;
+  split8(v, h, m, l);
+  const size_t plane = (size_t)K * N;
+  unsigned short* o = dst + (size_t)(n0 + n) * K + k0 + kc * 8;
+  *reinterpret_cast<v4u*>(o) = h;
+  *reinterpret_cast<v4u*>(o + plane) = m;
+  *reinterpret_cast<v4u*>(o + 2 * plane) = l;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Contraction over the planes
+// ------------------------------------------------------------------------------------------------
+// WN: 64-channel columns of wavefronts (2: 128 channels, 512 threads; 1: 64 channels, 256 threads).
+// PADDED: some filter tap of some pixel may fall on padding.  LONGK: reductions longer than P3_FLUSH slabs
+// keep a second accumulator set.  NBUF: slab buffers in the LDS ring.
+template <int WN, bool PADDED, bool LONGK, int NBUF>
+__global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem p, int tiles_m, int tiles_n,
+                                                                   int band_n, int total_work) {
+  constexpr int BN = 64 * WN;
+  constexpr int WAVES = 4 * WN;
+  constexpr int A_GROUPS = (PBM / 16) / WAVES;          // 16-row groups of the pixel tile one wavefront loads per plane
+  static_assert(A_GROUPS * WAVES * 16 == PBM && WAVES * 16 == BN, "rows divide over the wavefronts");
+  constexpr int LPI = 3 * (A_GROUPS + 1);               // loads one wavefront issues per slab
+  constexpr int A_PLANE = PBM * PROW, B_PLANE = BN * PROW;
+  constexpr int BUF = 3 * (A_PLANE + B_PLANE);
+  static_assert(NBUF * BUF >= WAVES * 32 * 64 * 4, "exchange of the partial tiles fits the slab buffers");
+
+  extern __shared__ __align__(16) unsigned char lds[];
+
+  // ---- which tile: consecutive workgroup ids go round-robin to the 8 XCDs, so id % 8 picks the XCD and
+  // each XCD gets a contiguous run of tiles, walked in bands of band_n tile columns so that the run of
+  // one XCD covers a compact block of the output.
+  const int per_xcd = gridDim.x >> 3;
+  const int wk = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+  if (wk >= total_work) return;
+  const int plane = tiles_m * tiles_n;
+  const int pl_i = wk / plane, wi = wk - pl_i * plane;
+  const int g = pl_i % p.groups;
+  const int split = pl_i / p.groups;
+  const int band = wi / (tiles_m * band_n);
+  const int in_band = wi - band * tiles_m * band_n;
+  const int band_w = tiles_n - band * band_n < band_n ? tiles_n - band * band_n : band_n;
+  const int tm = in_band / band_w;
+  const int tn = band * band_n + (in_band - tm * band_w);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kgrp = wave / (2 * WN);                      // which 16 of every slab's 32 reduction indices
+  const int wm = (wave / WN) & 1, wn = wave % WN;
+  const int lrow = lane & 31, lhalf = lane >> 5;
+
+  const unsigned xpb = p.x_bytes >> 1, wpb = p.w_bytes >> 1;          // bytes of one bf16 plane
+  const v4i rsrc_x = make_rsrc(p.planes, 3u * xpb);
+  const v4i rsrc_w = make_rsrc(static_cast<const unsigned char*>(p.planes) + p.wp_offset, 3u * wpb);
+  constexpr unsigned OOB = 0x80000000u;   // planes are at most 512 MiB each: OOB + 2 planes neither wraps nor lands inside
+
+  const int spt = (p.cg + PBK - 1) / PBK;               // slabs per filter tap
+  const int total_slabs = p.r * p.s * spt;
+  const int slab_begin = split * p.slabs_per_split;
+  int slab_end = slab_begin + p.slabs_per_split;
+  if (slab_end > total_slabs) slab_end = total_slabs;
+
+  // ---- staging state.  A load covers 16 tile rows: lane l the row (l / 4) of the group and chunk position l % 4,
+  // where chunk (l % 4) ^ swz(row) of that row is stored, swz(row) = (row / 4) % 4 = (l / 16) % 4.
+  const int cch = (lane & 3) ^ ((lane >> 4) & 3);
+  unsigned a_base[A_GROUPS], a_mask[A_GROUPS];
+  {
+    const int ohow = p.oh * p.ow;
+#pragma unroll
+    for (int t = 0; t < A_GROUPS; ++t) {
+      const int m = tm * PBM + 16 * (wave + WAVES * t) + (lane >> 2);
+      a_base[t] = OOB;
+      a_mask[t] = 0;
+      if (m < p.M) {
+        const int img = p.div_ohow.div(m);
+        const int rem = m - img * ohow;
+        const int oh = p.div_ow.div(rem);
+        const int ow = rem - oh * p.ow;
+        const int ih0 = oh * p.stride_h - p.pad_t, iw0 = ow * p.stride_w - p.pad_l;
+        // byte offset of the window origin's channel run in plane 0 (may wrap below 0: only used with an inside tap)
+        a_base[t] = 2u * (unsigned)(((img * p.h + ih0) * p.w_ + iw0) * p.c + g * p.cg + cch * 8);
+        const int rlo = ih0 < 0 ? -ih0 : 0, rhi = p.h - ih0 < p.r ? p.h - ih0 : p.r;
+        const int slo = iw0 < 0 ? -iw0 : 0, shi = p.w_ - iw0 < p.s ? p.w_ - iw0 : p.s;
+        const unsigned rm = rhi > rlo ? (1u << rhi) - (1u << rlo) : 0u;
+        const unsigned sm = shi > slo ? (1u << shi) - (1u << slo) : 0u;
+        a_mask[t] = rm | (sm << 16);
+      }
+    }
+  }
+  unsigned b_base;                                      // byte offset of the filter row's chunk in plane 0
+  {
+    const int n = tn * BN + 16 * wave + (lane >> 2);
+    b_base = n < p.kg ? 2u * ((unsigned)(g * p.kg + n) * (unsigned)p.Kgemm + (unsigned)(cch * 8)) : OOB;
+  }
+  // scalar walk over (tap, channel block): the next slab to issue
+  int tap_r, tap_s, tap_c0, next_slab = slab_begin;
+  {
+    const int t = slab_begin / spt;
+    tap_c0 = (slab_begin - t * spt) * PBK;
+    tap_r = t / p.s;
+    tap_s = t - tap_r * p.s;
+  }
+
+  // The loads of the next slab to issue, in LPI pieces so that they can be dealt out between the MFMAs of a trip
+  // (a wavefront whose load waits for a slot in the address unit's queue issues nothing else meanwhile).
+  unsigned is_a[A_GROUPS], is_b, is_lds;
+  auto issue_prepare = [&](int buf) {
+    is_lds = __builtin_amdgcn_readfirstlane(lds_offset_of(lds) + buf * BUF + wave * 16 * PROW);
+    const bool live = next_slab < slab_end;             // ring positions past the end: zeros, no memory traffic
+    const bool cok = live && tap_c0 + cch * 8 < p.cg;   // channel tail of a tap
+    const unsigned tap_off = 2u * (unsigned)((tap_r * p.w_ + tap_s) * p.c + tap_c0);
+    const unsigned k_off = 2u * (unsigned)((tap_r * p.s + tap_s) * p.cg + tap_c0);
+#pragma unroll
+    for (int t = 0; t < A_GROUPS; ++t) {
+      bool ok = cok && a_base[t] != OOB;
+      if constexpr (PADDED) ok = ok && ((a_mask[t] >> tap_r) & (a_mask[t] >> (16 + tap_s)) & 1u);
+      is_a[t] = ok ? a_base[t] + tap_off : OOB;
+    }
+    is_b = (cok && b_base != OOB) ? b_base + k_off : OOB;
+    ++next_slab;
+    tap_c0 += PBK;
+    if (tap_c0 >= p.cg) {
+      tap_c0 = 0;
+      if (++tap_s == p.s) { tap_s = 0; ++tap_r; }
+    }
+  };
+  auto issue_piece = [&](int j) {                        // j = 0 .. LPI - 1, compile-time
+    const int pc = j % 3, t = j / 3;
+    if (t < A_GROUPS) load16_to_lds(rsrc_x, is_lds + pc * A_PLANE + t * WAVES * 16 * PROW, is_a[t] + pc * xpb);
+    else load16_to_lds(rsrc_w, is_lds + 3 * A_PLANE + pc * B_PLANE, is_b + pc * wpb);
+  };
+  auto issue = [&](int buf) {
+    issue_prepare(buf);
+#pragma unroll
+    for (int j = 0; j < LPI; ++j) issue_piece(j);
+  };
+
+  // acc[i][j]: 32 pixels (rows of the MFMA result) x 32 channels (columns, one per lane)
+  v16f acc[2][2], total[LONGK ? 2 : 1][LONGK ? 2 : 1];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        acc[i][j][e] = 0.f;
+        if (LONGK) total[i][j][e] = 0.f;
+      }
+
+  // a lane holds 8 consecutive reduction indices of its row: chunk 2 * kgrp + lhalf, stored at chunk ^ swz(row)
+  const int pos = ((kgrp * 2 + lhalf) ^ ((lrow >> 2) & 3)) << 4;
+  const int frag_a = (wm * 64 + lrow) * PROW + pos;
+  const int frag_b = 3 * A_PLANE + (wn * 64 + lrow) * PROW + pos;
+  // All fragments of a slab are read up front (12 ds_read_b128) in the order the MFMAs use them, and the
+  // refill loads are dealt out between the MFMAs.
+  constexpr int TA[6] = {2, 0, 1, 1, 0, 0}, TB[6] = {0, 2, 1, 0, 1, 0};   // (input piece, filter piece), smallest terms first
+  auto trip = [&](int buf, int refill_buf) {
+    const unsigned char* base = lds + buf * BUF;
+    v8bf a[3][2], b[3][2];
+    constexpr int ORDER_A[3] = {2, 0, 1}, ORDER_B[3] = {0, 2, 1};
+#pragma unroll
+    for (int o = 0; o < 3; ++o) {
+      const int pa = ORDER_A[o], pb = ORDER_B[o];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        a[pa][i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(base + pa * A_PLANE + frag_a + i * 32 * PROW));
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        b[pb][j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(base + pb * B_PLANE + frag_b + j * 32 * PROW));
+    }
+    issue_prepare(refill_buf);
+    __builtin_amdgcn_sched_barrier(0);
+    constexpr int MFMAS = 6 * 4, EVERY = MFMAS / LPI;   // 24 MFMAs, a load after every EVERY of them
+    static_assert(EVERY >= 1, "more loads than MFMAs");
+#pragma unroll
+    for (int q = 0; q < MFMAS; ++q) {
+      const int t = q / 4, i = (q / 2) % 2, j = q % 2;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[TA[t]][i], b[TB[t]][j], acc[i][j], 0, 0, 0);
+      if (q % EVERY == EVERY - 1 && q / EVERY < LPI) {
+        __builtin_amdgcn_sched_barrier(0);
+        issue_piece(q / EVERY);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  };
+
+  // ---- main loop.  Trip s: wait for slab s (the younger slabs stay in flight), barrier (everyone's part of
+  // slab s has landed and everyone is done with the buffer multiplied last trip), read slab s's fragments,
+  // refill that older buffer with slab s + NBUF - 1, multiply slab s.  Loads are issued on every trip, past the end as zero fills, so the waits are
+  // compile-time constants.  Unrolled NBUF times so that buffer indices are constants.
+  {
+#pragma unroll
+    for (int d = 0; d < NBUF - 1; ++d) issue(d);
+    int since_flush = 0;
+    for (int s0 = slab_begin; s0 < slab_end; s0 += NBUF) {
+#pragma unroll
+      for (int u = 0; u < NBUF; ++u) {
+        if (s0 + u < slab_end) {                          // uniform
+          __builtin_amdgcn_s_waitcnt(vmcnt_imm((NBUF - 2) * LPI));
+          __syncthreads();
+          trip(u, (u + NBUF - 1) % NBUF);
+          if (LONGK && ++since_flush == P3_FLUSH) {
+            since_flush = 0;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+              for (int j = 0; j < 2; ++j) {
+                total[i][j] += acc[i][j];
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+              }
+          }
+        }
+      }
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // the zero fills past the end have landed too
+    __syncthreads();                                      // every wavefront is done with the slab buffers
+  }
+
+  // ---- exchange: the two wavefronts that hold partial sums of the same 64 x 64 sub-tile (one per half of the
+  // slabs) swap halves through LDS; the kgrp-0 wavefront finishes pixel rows 0..31 of the sub-tile, the other
+  // rows 32..63.  Both add the same two numbers, so which of them finishes a row does not change its value.
+  v16f keep[2];
+  {
+    v4f* xch = reinterpret_cast<v4f*>(lds);
+    const int pair = wm * WN + wn;
+    const int mine = (pair * 2 + kgrp) * 8, theirs = (pair * 2 + (kgrp ^ 1)) * 8;
+    auto exchange_as = [&](auto kg_tag) {
+      constexpr int KG = decltype(kg_tag)::value;         // sends block row 1 - KG, keeps block row KG
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        v16f snd = acc[1 - KG][j];
+        keep[j] = acc[KG][j];
+        if (LONGK) {
+          snd += total[1 - KG][j];
+          keep[j] += total[KG][j];
+        }
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4)
+          xch[(mine + j * 4 + e4) * 64 + lane] = v4f{snd[e4 * 4], snd[e4 * 4 + 1], snd[e4 * 4 + 2], snd[e4 * 4 + 3]};
+      }
+    };
+    if (kgrp) exchange_as(std::integral_constant<int, 1>{});
+    else exchange_as(std::integral_constant<int, 0>{});
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int e4 = 0; e4 < 4; ++e4) {
+        const v4f got = xch[(theirs + j * 4 + e4) * 64 + lane];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) keep[j][e4 * 4 + t] += got[t];
+      }
+  }
+
+  // ---- epilogue: bias (+ tensor add) + activation on the finished sums, one store; or the partial tile.
+  // 32x32 MFMA block: register e of a lane is row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
+  float* __restrict__ Y = static_cast<float*>(p.y);
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  const float* addend = static_cast<const float*>(p.addend);   // may be the output itself
+  const bool finish = p.split_k == 1;
+  const bool relu = finish && p.act == 1;
+  const bool add = finish && addend != nullptr;
+  float* dst_base = finish ? Y : static_cast<float*>(p.partial) + (size_t)split * p.M * p.k;
+  const int row_base = tm * PBM + wm * 64 + kgrp * 32 + lhalf * 4;
+  const bool full = (tm + 1) * PBM <= p.M && (tn + 1) * BN <= p.kg;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = tn * BN + wn * 64 + j * 32 + lrow;
+    const bool cok = col < p.kg;
+    const int ch = g * p.kg + col;
+    const float bv = (cok && finish && bias) ? bias[ch] : 0.f;
+    float* dst = dst_base + (size_t)row_base * p.k + ch;
+    const float* addp = add ? addend + (size_t)row_base * p.k + ch : nullptr;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int r = (e >> 2) * 8 + (e & 3);               // compile-time row inside the 32-row block
+      float v = keep[j][e] + bv;
+      const bool inside = full || (cok && row_base + r < p.M);
+      if (add && inside) v += addp[(size_t)r * p.k];
+      if (relu) v = fmaxf(v, 0.f);
+      if (inside) dst[(size_t)r * p.k] = v;
+    }
+  }
+}
+
+template <int WN, bool PADDED, bool LONGK, int NBUF>
+hipError_t launch_p3_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
+  auto kern = igemm_f32_p3_kernel<WN, PADDED, LONGK, NBUF>;
+  constexpr int lds_bytes = NBUF * 3 * (PBM + 64 * WN) * PROW;
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (attr_status != hipSuccess) return attr_status;
+  const long long total_work = (long long)plan.tiles_m * plan.tiles_n * p.groups * plan.split_k;
+  const long long grid_x = ((total_work + 7) / 8) * 8;
+  const long long per_xcd = grid_x / 8;
+  int band_n = 1;
+  while ((long long)band_n * band_n * 2 < per_xcd && band_n < plan.tiles_n) ++band_n;
+  dim3 grid((unsigned)grid_x, 1, 1), block(256 * WN, 1, 1);
+  hipLaunchKernelGGL(kern, grid, block, lds_bytes, stream, p, plan.tiles_m, plan.tiles_n, band_n, (int)total_work);
+  return hipGetLastError();
+}
+
+template <int WN, int NBUF>
+hipError_t launch_p3_flags(const Problem& p, const Plan& plan, hipStream_t stream, bool padded, bool longk) {
+  if (padded) return longk ? launch_p3_variant<WN, true, true, NBUF>(p, plan, stream)
+                           : launch_p3_variant<WN, true, false, NBUF>(p, plan, stream);
+  return longk ? launch_p3_variant<WN, false, true, NBUF>(p, plan, stream)
+               : launch_p3_variant<WN, false, false, NBUF>(p, plan, stream);
+}
+
+size_t align_up(size_t v) { return (v + kPlaneAlign - 1) / kPlaneAlign * kPlaneAlign; }
+
+}  // namespace
+
+size_t p3_pack_bytes(const Problem& p) {
+  return align_up(3 * (size_t)(p.x_bytes >> 1)) + align_up(3 * (size_t)(p.w_bytes >> 1));
+}
+
+// Worth it when the contraction is large against the one-off cost of cutting both operands (about ten bytes
+// of memory traffic per element), the operands' shapes allow 16-byte plane chunks, and there are enough
+// pixels and channels for the 128-pixel tiles.
+bool p3_f32_applicable(const Problem& p) {
+  if (knob_or(KNOB_F32_P3, 1) == 0) return false;
+  if (p.chain_n > 0 || p.cg % 8 != 0 || p.c % 8 != 0) return false;
+  if (p.b_is_kn && p.groups != 1) return false;
+  if (p.r > 15 || p.s > 15) return false;               // the padding masks hold 16 taps per direction
+  if (p.x_bytes > (1u << 30) || p.w_bytes > (1u << 30)) return false;
+  const long long min_m = knob_or(KNOB_F32_P3_MIN_M, 256);
+  if (p.M < min_m || p.kg < 64) return false;
+  // a tile's fixed part (first slabs' latency, exchange, 64 KB of stores) is worth about eight slabs: with a
+  // reduction of 256 the fp32 kernels are faster (measured: 1x1 256->1024 on 14x14 at batch 32, 72 against 44 us)
+  if (min_m > 1 && p.Kgemm < 512) return false;
+  const double flops = 2.0 * p.M * (double)p.kg * p.groups * p.Kgemm;
+  const double elems = (double)(p.x_bytes >> 2) + (double)(p.w_bytes >> 2);
+  return flops >= (double)knob_or(KNOB_F32_P3_RATIO, 1024) * elems;
+}
+
+Plan plan_p3_f32(const Problem& p) {
+  Plan pl;
+  pl.kernel = KERNEL_P3;
+  pl.bm = PBM;
+  pl.bn = p.kg > 64 ? 128 : 64;
+  if (knob_is_set(KNOB_F32_P3_BN)) pl.bn = knob(KNOB_F32_P3_BN) == 64 ? 64 : 128;
+  pl.tile = pl.bn == 128 ? 0 : 1;
+  pl.bk = PBK;
+  pl.tiles_m = (p.M + PBM - 1) / PBM;
+  pl.tiles_n = (p.kg + pl.bn - 1) / pl.bn;
+  pl.slabs = p.r * p.s * ((p.cg + PBK - 1) / PBK);
+  pl.split_k = 1;
+  pl.slabs_per_split = pl.slabs;
+  pl.pack_bytes = p3_pack_bytes(p);
+  // Split the reduction when the tiles alone leave CUs idle: one workgroup per CU for the 128-channel tile, two
+  // for the 64-channel one; among the factors that keep at least eight slabs per workgroup take the smallest that
+  // fills 90 % of its last round, else the one that fills it best.
+  const long long t = (long long)pl.tiles_m * pl.tiles_n * p.groups;
+  const long long slots = pl.bn == 128 ? 256 : 512;
+  if (t < slots && pl.slabs >= 16) {
+    const int max_split = pl.slabs / 8 < 32 ? pl.slabs / 8 : 32;
+    int best = 1;
+    double best_u = 0.0;
+    for (int sk = 1; sk <= max_split; ++sk) {
+      const int sps = (pl.slabs + sk - 1) / sk;
+      if ((pl.slabs + sps - 1) / sps != sk) continue;
+      const long long blocks = t * sk;
+      const double u = (double)blocks / (double)(((blocks + slots - 1) / slots) * slots);
+      if (u > best_u + 1e-9) { best_u = u; best = sk; }
+      if (u >= 0.9) { best = sk; break; }
+    }
+    if (knob_is_set(KNOB_F32_SPLIT)) {
+      best = knob(KNOB_F32_SPLIT);
+      if (best < 1) best = 1;
+      if (best > pl.slabs) best = pl.slabs;
+      if (best > 64) best = 64;
+    }
+    if (best > 1) {
+      pl.slabs_per_split = (pl.slabs + best - 1) / best;
+      pl.split_k = (pl.slabs + pl.slabs_per_split - 1) / pl.slabs_per_split;
+    }
+  }
+  return pl;
+}
+
+hipError_t launch_p3_f32(const Problem& p_in, const Plan& plan, hipStream_t stream, const char** variant) {
+  if (!p_in.planes) return hipErrorInvalidValue;        // the ABI layer never plans this kernel without a workspace
+  if (plan.split_k > 1 && !p_in.partial) return hipErrorInvalidValue;
+  Problem p = p_in;
+  p.split_k = plan.split_k;
+  p.slabs_per_split = plan.slabs_per_split;
+  const size_t x_elems = p.x_bytes >> 2, w_elems = p.w_bytes >> 2;
+  p.wp_offset = (uint32_t)align_up(3 * x_elems * 2);
+  unsigned short* xp = static_cast<unsigned short*>(const_cast<void*>(p.planes));
+  unsigned short* wp = reinterpret_cast<unsigned short*>(reinterpret_cast<unsigned char*>(xp) + p.wp_offset);
+  // ---- cut both operands into planes (measurement aid: with the knob set the planes that the previous call with
+  // the same operands and workspace left behind are used again, so that the contraction can be timed alone)
+  const bool repack = knob_or(KNOB_F32_P3_REUSE_PLANES, 0) == 0;
+  if (repack) {
+    const long long c8 = (long long)(x_elems / 8);
+    long long blocks = (c8 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(pack3_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<const float*>(p.x), xp,
+                       c8, (long long)x_elems);
+  }
+  if (!repack) {
+  } else if (p.b_is_kn) {
+    const int tk = (p.Kgemm + 63) / 64, tn = (p.k + 31) / 32;
+    hipLaunchKernelGGL(pack3_transposed_kernel, dim3((unsigned)(tk * tn)), dim3(256), 0, stream,
+                       static_cast<const float*>(p.w), wp, p.Kgemm, p.k, tn);
+  } else {
+    const long long c8 = (long long)(w_elems / 8);
+    long long blocks = (c8 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(pack3_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<const float*>(p.w), wp,
+                       c8, (long long)w_elems);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  // ---- the contraction
+  const bool padded = p.pad_t != 0 || p.pad_l != 0 || (p.oh - 1) * p.stride_h - p.pad_t + p.r > p.h ||
+                      (p.ow - 1) * p.stride_w - p.pad_l + p.s > p.w_;
+  const bool longk = plan.slabs_per_split > P3_FLUSH;
+  static thread_local char name[64];
+  snprintf(name, sizeof(name), "igemm_f32_p3_128x%d%s%s", plan.bn, padded ? "_pad" : "", longk ? "_longk" : "");
+  *variant = name;
+  if (plan.bn == 128) e = launch_p3_flags<2, 3>(p, plan, stream, padded, longk);
+  else e = launch_p3_flags<1, 2>(p, plan, stream, padded, longk);
+  if (e != hipSuccess) return e;
+  if (plan.split_k > 1) e = launch_splitk_finish_f32(p, plan, stream);
+  return e;
+}
+
+}  // namespace glowmi

@@ -34,48 +34,18 @@
 #include <cstdlib>
 
 #include "igemm.h"
+#include "lds_direct.h"
 #include "quant_epilogue.h"
 
 namespace glowmi {
 namespace {
 
 typedef int v2i __attribute__((ext_vector_type(2)));
-typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 constexpr int WBM = 128;                 // pixels per workgroup tile
 constexpr int WBK = 128;                 // codes per reduction slab
 constexpr int WTHREADS = 512;
-
-#define GLOWMI_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
-
-// 16 bytes per lane from a range-checked buffer straight into LDS at lds_addr + 16 * lane (lanes whose
-// offset is out of range write zeros).  Issued as inline assembly on purpose: for the intrinsic form
-// the compiler cannot tell which later LDS reads depend on which load and waits for all outstanding
-// loads before every LDS read, which would serialise the ring of slab buffers; here the kernel
-// places the vmcnt waits itself.  lds_addr is wave-uniform.
-__device__ __forceinline__ void load16_to_lds(v4i rsrc, unsigned lds_addr, unsigned voffset) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-               :
-               : "s"(lds_addr), "v"(voffset), "s"(rsrc)
-               : "memory");   // m0 is written here and nowhere else in this file (it is a reserved
-                              // register: the compiler warns about it on a clobber list and keeps
-                              // nothing live in it in a kernel without LDS-direct intrinsics)
-}
-
-__device__ __forceinline__ v4i make_rsrc(const void* base, unsigned bytes) {
-  const unsigned long long a = reinterpret_cast<unsigned long long>(base);
-  v4i r;
-  r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
-  r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((a >> 32) & 0xffffu));   // stride 0: raw buffer
-  r[2] = __builtin_amdgcn_readfirstlane((int)bytes);                              // num_records in bytes
-  r[3] = 0x00020000;
-  return r;
-}
-
-__device__ __forceinline__ unsigned lds_offset_of(const void* p) {
-  return (unsigned)(unsigned long long)GLOWMI_LDS_PTR(p);
-}
 
 __device__ __forceinline__ int sum4(int packed, int acc) {   // acc + the four signed bytes
   return __builtin_amdgcn_sdot4(packed, 0x01010101, acc, false);
@@ -85,10 +55,6 @@ __device__ __forceinline__ int requantize(int acc, int mant, int shift, int y_of
   return shift >= 33 ? requantize_as<true>(acc, mant, shift, y_off, lo)
                      : requantize_as<false>(acc, mant, shift, y_off, lo);   // uniform branch
 }
-
-// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and
-// leaves the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
-constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
 // PADDED: some filter tap of some pixel may fall on padding (otherwise the per-tap tests are dropped).
 // XSUM: the filter offset is not zero, so the input code sums per pixel are needed as well.

@@ -330,8 +330,19 @@ def test_workspace_queries_are_pure():
     assert glowmi.fc_workspace_bytes(16, 4096, 4096) > 0
     assert glowmi.fc_workspace_bytes(40, 2048, 1000) == 0
     assert glowmi.fc_workspace_bytes(0, 1, 1) == 0
+    # a large contraction asks for room to repack both operands as three bf16 planes (6 bytes per element,
+    # each operand's planes rounded up to 256 bytes); with that kernel switched off, plenty of tiles: no split
     big = glowmi.ConvDesc(16, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1)
-    assert glowmi.conv2d_workspace_bytes(big) == 0          # plenty of tiles: no split
+    x_elems, w_elems = 16 * 224 * 224 * 64, 64 * 3 * 3 * 64
+    up = lambda v: (v + 255) // 256 * 256
+    assert glowmi.conv2d_workspace_bytes(big) == up(6 * x_elems) + up(6 * w_elems)
+    glowmi.tuning_set("F32_P3", 0)
+    try:
+        assert glowmi.conv2d_workspace_bytes(big) == 0
+    finally:
+        glowmi.tuning_reset()
+    # a FullyConnected too small to pay for the repacking never asks for it
+    assert glowmi.fc_workspace_bytes(256, 4096, 4096) < 6 * (256 * 4096 + 4096 * 4096)
 
 
 def test_product_does_not_import_the_oracle():
