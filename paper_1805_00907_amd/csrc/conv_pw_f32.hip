@@ -28,6 +28,7 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include "bf16_pieces.h"
 #include "igemm.h"
 #include "pw_common.h"
 
@@ -36,6 +37,7 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int PW_THREADS = 512;
 constexpr int PW_WAVES = PW_THREADS / 64;
@@ -248,10 +250,224 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The same design on the bf16 matrix cores: every fp32 operand cut exactly into three bf16 pieces and a
+// product taken as six piece products (bf16_pieces.h), 192 matrix-pipe cycles per 16 reduction steps of a
+// 32 x 32 block instead of 512.  The filter slice is cut once per workgroup while it is staged (three
+// bf16 planes in LDS).  The input is cut where it is used: a pointwise layer stages each input element
+// once per filter slice, so cutting it costs the same ~6 vector instructions per element as a separate
+// packing pass would, without that pass's memory traffic.  A wavefront's chunk is 32 pixels x 32 channels
+// (128-byte runs, whole cache lines per load instruction), kept as fp32 in its private LDS region; the
+// lane that feeds MFMA row l, reduction indices 8h .. 8h+7, reads those eight values and cuts them in
+// registers.  Everything else (persistent workgroups, items, epilogue) as in the kernel above.
+// ---------------------------------------------------------------------------------------------------
+constexpr int PB_CHUNK = 32;                  // channels per staged chunk
+constexpr int PB_APITCH = PB_CHUNK + 4;       // floats
+constexpr int PB_AREGION = 32 * PB_APITCH;    // floats per wavefront
+
+template <int K>
+struct PwB {
+  static constexpr int BN = 16384 / K;        // output channels per workgroup
+  static constexpr int NG = BN / 64;
+  static constexpr int PITCHB = 2 * K + 16;   // bytes per filter row of one plane: an odd number of 16-byte units
+  static constexpr int PLANE = BN * PITCHB;   // bytes per plane
+  static constexpr int KC = K / PB_CHUNK;
+  static constexpr int lds_bytes = 3 * PLANE + (PW_WAVES * PB_AREGION + BN) * (int)sizeof(float);
+  static_assert(BN >= 64 && (NG & (NG - 1)) == 0 && K % PB_CHUNK == 0 && KC >= 2, "slice shape");
+  static_assert(lds_bytes <= 160 * 1024, "LDS of one CU");
+};
+
 template <int K, bool CONTIGUOUS, bool ADD>
+__global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const Problem p, const PwRange full,
+                                                                        const PwRange last, int halves) {
+  using G = PwB<K>;
+  extern __shared__ __align__(16) unsigned char smem_b[];   // filter planes [3][BN][PITCHB], A regions, bias [BN]
+  unsigned char* wlds = smem_b;
+  float* fl = reinterpret_cast<float*>(smem_b + 3 * G::PLANE);
+  float* blds = fl + PW_WAVES * PB_AREGION;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int slice = blockIdx.y;
+  float* alds = fl + wave * PB_AREGION;
+
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  const __amdgpu_buffer_rsrc_t rsrc_x =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.x), 0, (int)p.x_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_w =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.w), 0, (int)p.w_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_y =
+      __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsrc_add = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<void*>(ADD ? p.addend : p.y), 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
+
+  const PwRange& range = slice == (int)gridDim.y - 1 ? last : full;
+  const int wv = blockIdx.x * PW_WAVES + wave;
+  int it, it_end_;
+  deal_range(wv, (int)gridDim.x * PW_WAVES, range.items_div, range.items_rem, it, it_end_);
+  const int it_end = it_end_;
+  auto block_of = [&](int item) { return range.div_ngc.div(item); };
+
+  const int ohow = p.oh * p.ow;
+  const unsigned row_bytes = (unsigned)p.k * 4u;
+  const float floor_value = p.act == 1 ? 0.f : -__builtin_inff();
+
+  // Staging of one chunk: load i of a lane covers pixel 8i + lane/8 of the block, 16 bytes at channel
+  // chunk*32 + 4*(lane%8): eight whole 128-byte runs per instruction.
+  const int srow = lane >> 3, sq = lane & 7;
+  v4f st[4];
+  auto fetch_chunk = [&](int rb, int chunk) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int m = rb * 32 + 8 * i + srow;
+      if (m >= p.M) m = p.M - 1;                           // results of such rows are never stored
+      int pix = m;
+      if (!CONTIGUOUS) {
+        const int img = p.div_ohow.div(m);
+        const int rem = m - img * ohow;
+        const int oh = p.div_ow.div(rem);
+        const int ow = rem - oh * p.ow;
+        pix = (img * p.h + oh * p.stride_h) * p.w_ + ow * p.stride_w;
+      }
+      const unsigned off = ((unsigned)pix * (unsigned)K + (unsigned)(chunk * PB_CHUNK + 4 * sq)) * 4u;
+      st[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0));
+    }
+  };
+  auto commit_chunk = [&]() {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) *reinterpret_cast<v4f*>(alds + (8 * i + srow) * PB_APITCH + 4 * sq) = st[i];
+  };
+
+  const bool has_work = it < it_end;
+  if (has_work) fetch_chunk(block_of(it), 0);
+
+  // ---- filter slice -> three bf16 planes in LDS.  The slice is one contiguous run of the [k][C] filter; rows
+  // past the last output channel lie past the end of the tensor and the range-checked loads return zeros.
+  {
+    constexpr int V8_PER_ROW = K / 8;
+    constexpr int PASSES = G::BN * V8_PER_ROW / PW_THREADS;
+    const unsigned base = (unsigned)slice * (unsigned)(G::BN * K * 4);
+#pragma unroll
+    for (int q = 0; q < PASSES; ++q) {
+      const int i = tid + q * PW_THREADS;
+      const v4f lo4 = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, base + (unsigned)i * 32u, 0, 0));
+      const v4f hi4 = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, base + (unsigned)i * 32u + 16u, 0, 0));
+      const float v[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+      v4u h, m, l;
+      split8(v, h, m, l);
+      const int ch = i / V8_PER_ROW, kq = i % V8_PER_ROW;
+      unsigned char* dst = wlds + ch * G::PITCHB + kq * 16;
+      *reinterpret_cast<v4u*>(dst) = h;
+      *reinterpret_cast<v4u*>(dst + G::PLANE) = m;
+      *reinterpret_cast<v4u*>(dst + 2 * G::PLANE) = l;
+    }
+    if (tid < G::BN) {
+      const int ch = slice * G::BN + tid;
+      blds[tid] = (bias && ch < p.k) ? bias[ch] : 0.f;
+    }
+  }
+  __syncthreads();
+
+  const float* a_lane = alds + l32 * PB_APITCH + 8 * lh;
+  const unsigned char* w_lane = wlds + l32 * G::PITCHB + 16 * lh;
+
+  if (!has_work) return;
+  commit_chunk();
+  auto process = [&](auto nb_tag, int rb, int ng, int hsel, bool more, int rb_next) {
+    constexpr int NB = decltype(nb_tag)::value;
+    const unsigned item_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes +
+                              (unsigned)(slice * G::BN + ng * 64 + hsel * 32 + l32) * 4u;
+    float addv[NB][16];
+    if (ADD) {
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          addv[nb][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+              rsrc_add, item_off + 128u * nb + (unsigned)((e >> 2) * 8 + (e & 3)) * row_bytes, 0, 0));
+    }
+
+    v16f acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[nb][e] = 0.f;
+    const unsigned char* wl = w_lane + (ng * 64 + hsel * 32) * G::PITCHB;
+#pragma unroll
+    for (int c = 0; c < G::KC; ++c) {
+      // the chunk after this one: the next of this item, or the first of the next item (a reduction is at
+      // least two chunks long, so the region never still holds chunk 0 when an item ends)
+      const bool stage_next = c + 1 < G::KC || more;
+      if (stage_next) fetch_chunk(c + 1 < G::KC ? rb : rb_next, c + 1 < G::KC ? c + 1 : 0);
+#pragma unroll
+      for (int j = 0; j < PB_CHUNK / 16; ++j) {
+        // a lane holds reduction indices 16j + 8*lh .. + 7 of its pixel (input) / channel (filter)
+        const v4f a0 = *reinterpret_cast<const v4f*>(a_lane + 16 * j);
+        const v4f a1 = *reinterpret_cast<const v4f*>(a_lane + 16 * j + 4);
+        v8bf b[3][NB];
+#pragma unroll
+        for (int pc = 0; pc < 3; ++pc)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            b[pc][nb] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(
+                wl + pc * G::PLANE + nb * 32 * G::PITCHB + (c * PB_CHUNK + 16 * j) * 2));
+        const float v[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+        v4u ah, am, al;
+        split8(v, ah, am, al);
+        const v8bf a[3] = {__builtin_bit_cast(v8bf, ah), __builtin_bit_cast(v8bf, am), __builtin_bit_cast(v8bf, al)};
+#pragma unroll
+        for (int t = 0; t < 6; ++t)
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb)
+            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[t]], b[kPieceTermB[t]][nb], acc[nb], 0, 0, 0);
+      }
+      // in program order after this chunk's fragment reads: the wavefront's LDS operations execute
+      // in order, so the region is overwritten only once it has been read
+      if (stage_next) commit_chunk();
+    }
+
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const int ch = slice * G::BN + ng * 64 + (hsel + nb) * 32 + l32;
+      if (ch < p.k) {
+        const float bv = blds[ng * 64 + (hsel + nb) * 32 + l32];
+        unsigned lane_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes + (unsigned)ch * 4u;
+        asm volatile("" : "+v"(lane_off));                 // keep the per-register row offsets scalar
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const float v = fmaxf(acc[nb][e] + bv + (ADD ? addv[nb][e] : 0.f), floor_value);
+          const unsigned off = lane_off + (unsigned)((e >> 2) * 8 + (e & 3)) * row_bytes;
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, off, 0, 0);
+        }
+      }
+    }
+  };
+
+  if (!halves) {
+    for (; it < it_end; ++it) {
+      const int rb = block_of(it);
+      process(std::integral_constant<int, 2>{}, rb, it - rb * range.ngc, 0, it + 1 < it_end, block_of(it + 1));
+    }
+    return;
+  }
+  while (it < it_end) {
+    const int rb = block_of(it), hh = it - rb * range.ngc;
+    const bool pair = (hh & 1) == 0 && it + 1 < it_end;    // uniform
+    const int step = pair ? 2 : 1;
+    const bool more = it + step < it_end;
+    const int rb_next = block_of(it + step);
+    if (pair) process(std::integral_constant<int, 2>{}, rb, hh >> 1, 0, more, rb_next);
+    else process(std::integral_constant<int, 1>{}, rb, hh >> 1, hh & 1, more, rb_next);
+    it += step;
+  }
+}
+
+template <int K, bool CONTIGUOUS, bool ADD, bool BF16>
 hipError_t launch_pw(const Problem& p, hipStream_t stream) {
-  using G = Pw<K>;
-  auto kern = conv_pw_f32_kernel<K, CONTIGUOUS, ADD>;
+  using G = std::conditional_t<BF16, PwB<K>, Pw<K>>;
+  auto kern = BF16 ? conv_pw_f32_bf16_kernel<K, CONTIGUOUS, ADD> : conv_pw_f32_kernel<K, CONTIGUOUS, ADD>;
   // once per instantiation; initialisation of a function-local static is thread-safe
   static const hipError_t attr_status = hipFuncSetAttribute(
       reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G::lds_bytes);
@@ -299,22 +515,28 @@ bool pw_f32_applicable(const Problem& p) {
   return items >= pw_min_items() && items < (1LL << 30);
 }
 
-template <int K>
+template <int K, bool BF16>
 hipError_t launch_pw_k(const Problem& p, hipStream_t stream) {
   const bool contiguous = p.stride_h == 1 && p.stride_w == 1;
-  if (p.addend) return contiguous ? launch_pw<K, true, true>(p, stream) : launch_pw<K, false, true>(p, stream);
-  return contiguous ? launch_pw<K, true, false>(p, stream) : launch_pw<K, false, false>(p, stream);
+  if (p.addend) return contiguous ? launch_pw<K, true, true, BF16>(p, stream) : launch_pw<K, false, true, BF16>(p, stream);
+  return contiguous ? launch_pw<K, true, false, BF16>(p, stream) : launch_pw<K, false, false, BF16>(p, stream);
 }
 
 hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** variant) {
   const bool contiguous = p.stride_h == 1 && p.stride_w == 1;
+  // Measured at batch 32: 64 -> 256 on 56 x 56 44 -> 39 us, 256 -> 64 50 -> 47 us, 128 -> 512 + add on 28 x 28
+  // 47 -> 38 us, 256 -> 1024 + add on 14 x 14 44 -> 35 us; but 64 -> 256 + add 52 -> 56 us: that one moves
+  // 232 MB for 3.3 GFLOP and is bound by memory on either matrix core, so it keeps the leaner fp32 loop.
+  // The knob forces one form or the other (tests, comparisons).
+  const bool bf16 = knob_or(KNOB_F32_PW_BF16, (p.c == 64 && p.addend) ? 0 : 1) != 0;
   static thread_local char name[48];
-  snprintf(name, sizeof(name), "conv_pw_f32_c%d%s%s", p.c, contiguous ? "" : "_strided", p.addend ? "_add" : "");
+  snprintf(name, sizeof(name), "conv_pw_f32_c%d%s%s%s", p.c, bf16 ? "_bf16x6" : "", contiguous ? "" : "_strided",
+           p.addend ? "_add" : "");
   *variant = name;
   switch (p.c) {
-    case 64: return launch_pw_k<64>(p, stream);
-    case 128: return launch_pw_k<128>(p, stream);
-    case 256: return launch_pw_k<256>(p, stream);
+    case 64: return bf16 ? launch_pw_k<64, true>(p, stream) : launch_pw_k<64, false>(p, stream);
+    case 128: return bf16 ? launch_pw_k<128, true>(p, stream) : launch_pw_k<128, false>(p, stream);
+    case 256: return bf16 ? launch_pw_k<256, true>(p, stream) : launch_pw_k<256, false>(p, stream);
     default: return hipErrorInvalidValue;
   }
 }

@@ -36,6 +36,7 @@
 #include <cstdio>
 #include <type_traits>
 
+#include "bf16_pieces.h"
 #include "igemm.h"
 #include "lds_direct.h"
 
@@ -44,8 +45,6 @@ namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 constexpr int PBM = 128;                 // pixels per workgroup tile
 constexpr int PBK = 32;                  // reduction indices per slab
@@ -56,30 +55,6 @@ constexpr size_t kPlaneAlign = 256;
 // ------------------------------------------------------------------------------------------------
 // Packing: fp32 -> three bf16 planes
 // ------------------------------------------------------------------------------------------------
-struct Pieces { unsigned h, m, l; };     // each piece's bf16 is the upper half of the word
-__device__ __forceinline__ Pieces split3(float x) {
-  Pieces r;
-  r.h = __builtin_bit_cast(unsigned, x) & 0xffff0000u;
-  const float r1 = x - __builtin_bit_cast(float, r.h);
-  r.m = __builtin_bit_cast(unsigned, r1) & 0xffff0000u;
-  r.l = __builtin_bit_cast(unsigned, r1 - __builtin_bit_cast(float, r.m));   // eight significant bits: already a bf16
-  return r;
-}
-// the upper halves of two words side by side: a in the low half (earlier index), b in the high half
-__device__ __forceinline__ unsigned pack_upper(unsigned a, unsigned b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
-
-__device__ __forceinline__ void split8(const float (&v)[8], v4u& h, v4u& m, v4u& l) {
-  Pieces e[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) e[i] = split3(v[i]);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    h[i] = pack_upper(e[2 * i].h, e[2 * i + 1].h);
-    m[i] = pack_upper(e[2 * i].m, e[2 * i + 1].m);
-    l[i] = pack_upper(e[2 * i].l, e[2 * i + 1].l);
-  }
-}
-
 // src: count8 groups of 8 consecutive floats; dst: three planes of plane_elems bf16 each, same order.
 __global__ __launch_bounds__(256) void pack3_rows_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
                                                          long long count8, long long plane_elems) {
@@ -274,7 +249,6 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
   const int frag_b = 3 * A_PLANE + (wn * 64 + lrow) * PROW + pos;
   // All fragments of a slab are read up front (12 ds_read_b128) in the order the MFMAs use them, and the
   // refill loads are dealt out between the MFMAs.
-  constexpr int TA[6] = {2, 0, 1, 1, 0, 0}, TB[6] = {0, 2, 1, 0, 1, 0};   // (input piece, filter piece), smallest terms first
   auto trip = [&](int buf, int refill_buf) {
     const unsigned char* base = lds + buf * BUF;
     v8bf a[3][2], b[3][2];
@@ -296,7 +270,7 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
 #pragma unroll
     for (int q = 0; q < MFMAS; ++q) {
       const int t = q / 4, i = (q / 2) % 2, j = q % 2;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[TA[t]][i], b[TB[t]][j], acc[i][j], 0, 0, 0);
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[t]][i], b[kPieceTermB[t]][j], acc[i][j], 0, 0, 0);
       if (q % EVERY == EVERY - 1 && q / EVERY < LPI) {
         __builtin_amdgcn_sched_barrier(0);
         issue_piece(q / EVERY);
@@ -440,7 +414,8 @@ size_t p3_pack_bytes(const Problem& p) {
 
 // Worth it when the contraction is large against the one-off cost of cutting both operands (about ten bytes
 // of memory traffic per element), the operands' shapes allow 16-byte plane chunks, and there are enough
-// pixels and channels for the 128-pixel tiles.
+// pixels and channels for the 128-pixel tiles.  Measured break-even: about 400 flops per operand element
+// (FullyConnected 256 x 4096 x 4096, 483 flops per element: 86 us here against 106 us on the fp32 matrix cores).
 bool p3_f32_applicable(const Problem& p) {
   if (knob_or(KNOB_F32_P3, 1) == 0) return false;
   if (p.chain_n > 0 || p.cg % 8 != 0 || p.c % 8 != 0) return false;
@@ -453,8 +428,10 @@ bool p3_f32_applicable(const Problem& p) {
   // reduction of 256 the fp32 kernels are faster (measured: 1x1 256->1024 on 14x14 at batch 32, 72 against 44 us)
   if (min_m > 1 && p.Kgemm < 512) return false;
   const double flops = 2.0 * p.M * (double)p.kg * p.groups * p.Kgemm;
+  // three launches (two packing kernels and the contraction) are worth ~15 us before any work is done
+  if (min_m > 1 && flops < 2e9) return false;
   const double elems = (double)(p.x_bytes >> 2) + (double)(p.w_bytes >> 2);
-  return flops >= (double)knob_or(KNOB_F32_P3_RATIO, 1024) * elems;
+  return flops >= (double)knob_or(KNOB_F32_P3_RATIO, 400) * elems;
 }
 
 Plan plan_p3_f32(const Problem& p) {

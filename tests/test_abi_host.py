@@ -342,7 +342,7 @@ def test_workspace_queries_are_pure():
     finally:
         glowmi.tuning_reset()
     # a FullyConnected too small to pay for the repacking never asks for it
-    assert glowmi.fc_workspace_bytes(256, 4096, 4096) < 6 * (256 * 4096 + 4096 * 4096)
+    assert glowmi.fc_workspace_bytes(128, 4096, 4096) < 6 * (128 * 4096 + 4096 * 4096)
 
 
 def test_product_does_not_import_the_oracle():

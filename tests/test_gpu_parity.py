@@ -104,11 +104,18 @@ PW_SHAPES = [
 ]
 
 
+# Both forms of the pointwise kernel: products on the fp32 matrix cores, and every operand cut into three
+# bf16 pieces with six piece products on the bf16 matrix cores (same tolerance: both are fp32-level).
+PW_FORMS = [("fp32", 0), ("bf16x6", 1)]
+
+
 @pytest.mark.parametrize("shape", PW_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("act", [wl.ACT_RELU, wl.ACT_NONE])
-def test_conv2d_f32_pointwise(shape, act, knobs):
+@pytest.mark.parametrize("form", PW_FORMS, ids=lambda f: f[0])
+def test_conv2d_f32_pointwise(shape, act, form, knobs):
     G = _gpu()
     knobs.set("F32_PW_MIN_ITEMS", "1")     # take the pointwise kernel at any size
+    knobs.set("F32_PW_BF16", form[1])
     n, h, w, c, k, st = shape
     rng = np.random.default_rng(4000 + 7 * c + k)
     x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
@@ -117,7 +124,7 @@ def test_conv2d_f32_pointwise(shape, act, knobs):
     ref = oracle.conv2d_f32(x, wt, b, (st, st), (0, 0, 0, 0), 1, act=act)
     desc = G.make_desc(x.shape, wt.shape, (st, st), (0, 0, 0, 0), 1)
     got, variant = G.gpu_conv2d_f32(x, wt, b, desc, act)
-    assert variant.startswith("conv_pw_f32"), variant
+    assert variant.startswith("conv_pw_f32") and ("bf16x6" in variant) == bool(form[1]), variant
     G.assert_close_f32(got, ref, f"pointwise {shape} act {act} [{variant}]")
     got, variant = G.gpu_conv2d_f32(x, wt, None, desc, act)
     G.assert_close_f32(got, oracle.conv2d_f32(x, wt, None, (st, st), (0, 0, 0, 0), 1, act=act),
@@ -334,9 +341,11 @@ def test_conv2d_chain_f32(i, act):
 
 
 @pytest.mark.parametrize("shape", PW_SHAPES, ids=lambda s: "x".join(map(str, s)))
-def test_conv2d_chain_f32_pointwise(shape, knobs):
+@pytest.mark.parametrize("form", PW_FORMS, ids=lambda f: f[0])
+def test_conv2d_chain_f32_pointwise(shape, form, knobs):
     G = _gpu()
     knobs.set("F32_PW_MIN_ITEMS", "1")
+    knobs.set("F32_PW_BF16", form[1])
     n, h, w, c, k, st = shape
     rng = np.random.default_rng(6100 + 7 * c + k)
     x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
@@ -350,6 +359,7 @@ def test_conv2d_chain_f32_pointwise(shape, knobs):
         for in_place in (False, True):
             got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, desc, act, in_place=in_place)
             assert variant.startswith("conv_pw_f32") and variant.endswith("_add"), variant
+            assert ("bf16x6" in variant) == bool(form[1]), variant
             G.assert_close_f32(got, ref, f"pointwise chain {shape} act {act} in-place {in_place} [{variant}]")
 
 
