@@ -50,7 +50,7 @@ def _mfma_peak(dtype, variant=""):
     multiply-add).  The fp32 three-piece kernel runs on the bf16 cores with six products per fp32 product."""
     if dtype != "f32":
         return PEAK_INT8_MFMA, 1
-    if "igemm_f32_p3" in variant:
+    if "igemm_f32_p3" in variant or "bf16x6" in variant:
         return PEAK_BF16_MFMA, P3_PRODUCTS
     return PEAK_FP32_MFMA, 1
 PEAK_HBM = 8.0e12              # B/s

@@ -408,6 +408,15 @@ size_t align_up(size_t v) { return (v + kPlaneAlign - 1) / kPlaneAlign * kPlaneA
 
 }  // namespace
 
+hipError_t launch_pack3_rows(const float* src, void* dst, long long elems, hipStream_t stream) {
+  const long long c8 = elems / 8;
+  long long blocks = (c8 + 255) / 256;
+  if (blocks > 8192) blocks = 8192;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(pack3_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, static_cast<unsigned short*>(dst), c8, elems);
+  return hipGetLastError();
+}
+
 size_t p3_pack_bytes(const Problem& p) {
   return align_up(3 * (size_t)(p.x_bytes >> 1)) + align_up(3 * (size_t)(p.w_bytes >> 1));
 }
@@ -492,26 +501,19 @@ hipError_t launch_p3_f32(const Problem& p_in, const Plan& plan, hipStream_t stre
   // ---- cut both operands into planes (measurement aid: with the knob set the planes that the previous call with
   // the same operands and workspace left behind are used again, so that the contraction can be timed alone)
   const bool repack = knob_or(KNOB_F32_P3_REUSE_PLANES, 0) == 0;
+  hipError_t e = hipSuccess;
   if (repack) {
-    const long long c8 = (long long)(x_elems / 8);
-    long long blocks = (c8 + 255) / 256;
-    if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(pack3_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<const float*>(p.x), xp,
-                       c8, (long long)x_elems);
+    e = launch_pack3_rows(static_cast<const float*>(p.x), xp, (long long)x_elems, stream);
+    if (e != hipSuccess) return e;
+    if (p.b_is_kn) {
+      const int tk = (p.Kgemm + 63) / 64, tn = (p.k + 31) / 32;
+      hipLaunchKernelGGL(pack3_transposed_kernel, dim3((unsigned)(tk * tn)), dim3(256), 0, stream,
+                         static_cast<const float*>(p.w), wp, p.Kgemm, p.k, tn);
+      e = hipGetLastError();
+    } else {
+      e = launch_pack3_rows(static_cast<const float*>(p.w), wp, (long long)w_elems, stream);
+    }
   }
-  if (!repack) {
-  } else if (p.b_is_kn) {
-    const int tk = (p.Kgemm + 63) / 64, tn = (p.k + 31) / 32;
-    hipLaunchKernelGGL(pack3_transposed_kernel, dim3((unsigned)(tk * tn)), dim3(256), 0, stream,
-                       static_cast<const float*>(p.w), wp, p.Kgemm, p.k, tn);
-  } else {
-    const long long c8 = (long long)(w_elems / 8);
-    long long blocks = (c8 + 255) / 256;
-    if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(pack3_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, static_cast<const float*>(p.w), wp,
-                       c8, (long long)w_elems);
-  }
-  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // ---- the contraction
   const bool padded = p.pad_t != 0 || p.pad_l != 0 || (p.oh - 1) * p.stride_h - p.pad_t + p.r > p.h ||

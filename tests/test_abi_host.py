@@ -332,15 +332,18 @@ def test_workspace_queries_are_pure():
     assert glowmi.fc_workspace_bytes(0, 1, 1) == 0
     # a large contraction asks for room to repack both operands as three bf16 planes (6 bytes per element,
     # each operand's planes rounded up to 256 bytes); with that kernel switched off, plenty of tiles: no split
-    big = glowmi.ConvDesc(16, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1)
-    x_elems, w_elems = 16 * 224 * 224 * 64, 64 * 3 * 3 * 64
     up = lambda v: (v + 255) // 256 * 256
+    big = glowmi.ConvDesc(16, 112, 112, 128, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1)
+    x_elems, w_elems = 16 * 112 * 112 * 128, 128 * 3 * 3 * 128
     assert glowmi.conv2d_workspace_bytes(big) == up(6 * x_elems) + up(6 * w_elems)
     glowmi.tuning_set("F32_P3", 0)
     try:
         assert glowmi.conv2d_workspace_bytes(big) == 0
     finally:
         glowmi.tuning_reset()
+    # 3x3 over 64 channels on many pixels: only the filter is repacked
+    c64 = glowmi.ConvDesc(16, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1)
+    assert glowmi.conv2d_workspace_bytes(c64) == up(6 * 64 * 3 * 3 * 64)
     # a FullyConnected too small to pay for the repacking never asks for it
     assert glowmi.fc_workspace_bytes(128, 4096, 4096) < 6 * (128 * 4096 + 4096 * 4096)
 
