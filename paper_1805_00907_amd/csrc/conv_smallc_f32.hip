@@ -17,7 +17,9 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <type_traits>
 
+#include "bf16_pieces.h"
 #include "igemm.h"
 
 namespace glowmi {
@@ -226,10 +228,237 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
   }
 }
 
+// ---------------------------------------------------------------------------------------------------
+// The same design on the bf16 matrix cores: every operand cut exactly into three bf16 pieces, six piece
+// products per fp32 product (bf16_pieces.h).  v_mfma_f32_32x32x16_bf16 wants eight consecutive reduction
+// indices per lane, so the reduction is ordered filter row by filter row with each row's S*C run padded to
+// a multiple of 8 (7 x 3 = 21 -> 24): a lane's eight values are then eight consecutive patch elements, and
+// where the run is over they overlap the neighbouring pixels' data, which the zero pieces of the filter
+// cancel (the patch holds finite values or zeros everywhere, including one spare row).  The patch is cut
+// once per tile while it is written to LDS (three bf16 planes); the filter fragments (11 steps x 3 pieces
+// x 8 values per lane) are cut once per workgroup and stay in registers.  11 x 6 bf16 MFMAs of 32 cycles
+// replace 74 fp32 MFMAs of 64 per 32 x 32 block.
+// ---------------------------------------------------------------------------------------------------
 template <int R, int S, int C, int STRIDE, int TH>
+struct SmallCB {
+  static constexpr int K = R * S * C;
+  static constexpr int RUN = S * C;                      // contiguous (s, c) run per filter row
+  static constexpr int RUN8 = (RUN + 7) / 8;             // groups of 8 per filter row
+  static constexpr int GROUPS = R * RUN8;                // groups of 8 reduction indices (padded)
+  static constexpr int STEPS = (GROUPS + 1) / 2;         // MFMA steps (two groups each)
+  static constexpr int PH = (TH - 1) * STRIDE + R;       // patch rows
+  static constexpr int PWC = ((TW - 1) * STRIDE + S) * C;   // patch row length in elements
+  static constexpr int PITCH = ((PWC + 8 + 15) / 16) * 16;  // elements; the last pixel's padded run stays inside the row
+  static constexpr int PLANE = (PH + 2) * PITCH;         // elements; two spare rows: the padded steps read them
+  static constexpr int PATCH = 3 * PLANE;                // elements of one buffer
+  static constexpr int LOADS = (PH * PWC + SC_THREADS - 1) / SC_THREADS;
+  static constexpr int lds_bytes = (2 * PATCH * 2 > 32 * K * 4 ? 2 * PATCH * 2 : 32 * K * 4);
+  // patch offset (elements) of group g relative to a pixel's patch origin
+  static constexpr int off(int g) { return (g / RUN8) * PITCH + (g % RUN8) * 8; }
+};
+
+template <int R, int S, int C, int STRIDE, int TH>
+__global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_bf16_kernel(const Problem p, int tiles_y, int tiles_x,
+                                                                            int total_tiles) {
+  using G = SmallCB<R, S, C, STRIDE, TH>;
+  static_assert(TH == 4, "tile height: one 32-pixel block per wavefront");
+  static_assert((STRIDE * C) % 2 == 0 && G::PITCH % 2 == 0, "a pixel's run starts on a 4-byte boundary");
+  constexpr int NB = TH / 4;
+  extern __shared__ __align__(16) unsigned short patchb[];   // [2][3][PH + 2][PITCH]; first the filter halves as fp32
+  float* wstage = reinterpret_cast<float*>(patchb);
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int lrow = lane & 31, lhalf = lane >> 5;
+  const int wpix = wave >> 1;
+  const int wch = wave & 1;
+  const int n_tile = blockIdx.y;
+
+  const float* __restrict__ X = static_cast<const float*>(p.x);
+  const float* __restrict__ Wt = static_cast<const float*>(p.w);
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
+      p.y, 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
+
+  const int ch = n_tile * 64 + wch * 32 + lrow;
+  const bool ch_ok = ch < p.k;
+  const float bv = (ch_ok && bias) ? bias[ch] : 0.f;
+
+  // ---- per-lane patch bases (elements).  Step t multiplies groups 2t (lanes 0..31) and 2t + 1 (lanes 32..63);
+  // off(2t + 1) - off(2t) is 8 except where 2t is the last group of a filter row; a second base covers those
+  // steps, so every read uses a compile-time offset.
+  const int pix_origin = ((wpix * 2 * NB + (lrow >> 4)) * STRIDE) * G::PITCH + (lrow & 15) * STRIDE * C;
+  const int base_norm = pix_origin + lhalf * 8;
+  const int base_cross = pix_origin + lhalf * (G::PITCH - (G::RUN8 - 1) * 8);
+
+  float stage[G::LOADS];
+  auto load_patch = [&](int tile) {
+    const int tx = tile % tiles_x;
+    const int t2 = tile / tiles_x;
+    const int ty = t2 % tiles_y;
+    const int img = t2 / tiles_y;
+    const int ih0 = ty * TH * STRIDE - p.pad_t;
+    const int fx0 = (tx * TW * STRIDE - p.pad_l) * C;
+    const int row_floats = p.w_ * C;
+#pragma unroll
+    for (int i = 0; i < G::LOADS; ++i) {
+      const int idx = tid + i * SC_THREADS;
+      const int pr = idx / G::PWC, pc = idx % G::PWC;
+      const int ih = ih0 + pr, fx = fx0 + pc;
+      const bool ok = idx < G::PH * G::PWC && (unsigned)ih < (unsigned)p.h && (unsigned)fx < (unsigned)row_floats;
+      stage[i] = ok ? X[((size_t)img * p.h + ih) * row_floats + fx] : 0.f;
+    }
+  };
+  auto store_patch = [&](int buf) {
+    unsigned short* dst = patchb + buf * G::PATCH;
+#pragma unroll
+    for (int i = 0; i < G::LOADS; ++i) {
+      const int idx = tid + i * SC_THREADS;
+      if (idx < G::PH * G::PWC) {
+        const Pieces pc = split3(stage[i]);
+        unsigned short* d = dst + (idx / G::PWC) * G::PITCH + idx % G::PWC;
+        d[0] = (unsigned short)(pc.h >> 16);
+        d[G::PLANE] = (unsigned short)(pc.m >> 16);
+        d[2 * G::PLANE] = (unsigned short)(pc.l >> 16);
+      }
+    }
+  };
+
+  int tile = blockIdx.x;
+  if (tile >= total_tiles) return;
+  load_patch(tile);                        // in flight while the filter is fetched
+
+  // ---- filter fragments: lane (channel, half) keeps, for every step t and piece, the eight values of group
+  // 2t + half.  The 32 channels of each channel half are copied into LDS with coalesced loads (in the space of
+  // the patch buffers) and the lanes pick from there; rows past the last output channel lie past the end of
+  // the tensor and the range-checked loads return zeros.
+  v8bf wfrag[G::STEPS][3];
+  {
+    const __amdgpu_buffer_rsrc_t rsrc_w =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Wt), 0, (int)p.w_bytes, 0x00020000);
+    constexpr int HALF_FLOATS = 32 * G::K;
+    constexpr int W_LOADS = (HALF_FLOATS + SC_THREADS - 1) / SC_THREADS;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const unsigned base = (unsigned)((n_tile * 64 + half * 32) * G::K) * 4u;
+      float wst[W_LOADS];
+#pragma unroll
+      for (int i = 0; i < W_LOADS; ++i) {
+        const int e = tid + i * SC_THREADS;
+        wst[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                               rsrc_w, e < HALF_FLOATS ? base + 4u * e : 0xFFFFFFFCu, 0, 0));
+      }
+#pragma unroll
+      for (int i = 0; i < W_LOADS; ++i) {
+        const int e = tid + i * SC_THREADS;
+        if (e < HALF_FLOATS) wstage[e] = wst[i];
+      }
+      __syncthreads();
+      if (wch == half) {
+#pragma unroll
+        for (int t = 0; t < G::STEPS; ++t) {
+          float v[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            // group 2t + lhalf: filter row gr, positions 8 * part + e of its run
+            const int g0 = 2 * t, g1 = 2 * t + 1;
+            const int r0 = g0 / G::RUN8, q0 = (g0 % G::RUN8) * 8 + e;
+            const int r1 = g1 / G::RUN8, q1 = (g1 % G::RUN8) * 8 + e;
+            const bool ok0 = r0 < R && q0 < G::RUN, ok1 = r1 < R && q1 < G::RUN;    // compile-time
+            const float v0 = ok0 ? wstage[lrow * G::K + r0 * G::RUN + q0] : 0.f;
+            const float v1 = ok1 ? wstage[lrow * G::K + r1 * G::RUN + q1] : 0.f;
+            v[e] = lhalf ? v1 : v0;
+          }
+          v4u h, m, l;
+          split8(v, h, m, l);
+          wfrag[t][0] = __builtin_bit_cast(v8bf, h);
+          wfrag[t][1] = __builtin_bit_cast(v8bf, m);
+          wfrag[t][2] = __builtin_bit_cast(v8bf, l);
+        }
+      }
+      __syncthreads();
+    }
+  }
+  // zero both buffers once: the spare rows and the row tails are never overwritten by patch stores and must
+  // hold finite values (they meet zero filter pieces)
+  for (int i = tid; i < 2 * G::PATCH / 2; i += SC_THREADS) reinterpret_cast<unsigned*>(patchb)[i] = 0u;
+  __syncthreads();
+  store_patch(0);
+  __syncthreads();
+  int buf = 0;
+  for (;;) {
+    const int next = tile + gridDim.x;
+    const bool has_next = next < total_tiles;
+    if (has_next) load_patch(next);
+
+    v16f acc[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    const unsigned short* src = patchb + buf * G::PATCH;
+    const unsigned short* pn = src + base_norm;
+    const unsigned short* pcx = src + base_cross;
+#pragma unroll
+    for (int t = 0; t < G::STEPS; ++t) {
+      constexpr int blk = 2 * STRIDE * G::PITCH;                     // second 32-pixel block: two output rows down
+      const bool cross = (2 * t) % G::RUN8 == G::RUN8 - 1;           // compile-time after unrolling
+      const unsigned short* b = (cross ? pcx : pn) + G::off(2 * t);
+      v8bf a[3][NB];
+#pragma unroll
+      for (int pc = 0; pc < 3; ++pc)
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+          const unsigned* q = reinterpret_cast<const unsigned*>(b + pc * G::PLANE + i * blk);   // 4-byte aligned
+          a[pc][i] = __builtin_bit_cast(v8bf, v4u{q[0], q[1], q[2], q[3]});
+        }
+#pragma unroll
+      for (int tt = 0; tt < 6; ++tt)
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[tt]][i], wfrag[t][kPieceTermB[tt]], acc[i], 0, 0, 0);
+    }
+
+    if (has_next) store_patch(buf ^ 1);
+
+    // ---- epilogue of this tile: as in the kernel above
+    {
+      const int tx = tile % tiles_x;
+      const int t2 = tile / tiles_x;
+      const int ty = t2 % tiles_y;
+      const int img = t2 / tiles_y;
+      const int ow0 = tx * TW + 4 * lhalf;
+      const int cols_left = ch_ok ? p.ow - ow0 : 0;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int oh0 = ty * TH + wpix * 2 * NB + i * 2;
+        const int rows_left = p.oh - oh0;
+        const unsigned base = (unsigned)(((img * p.oh + oh0) * p.ow + ow0) * p.k + ch) * 4u;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int drow = e >> 3, dcol = (e & 3) + 8 * ((e >> 2) & 1);
+          float v = acc[i][e] + bv;
+          if (p.act == 1) v = fmaxf(v, 0.f);
+          const bool ok = dcol < cols_left && drow < rows_left;
+          const unsigned soff = (unsigned)((drow * p.ow + dcol) * p.k) * 4u;
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, ok ? base : 0x80000000u, soff, 0);
+        }
+      }
+    }
+    if (!has_next) break;
+    __syncthreads();
+    buf ^= 1;
+    tile = next;
+  }
+}
+
+template <int R, int S, int C, int STRIDE, int TH, bool BF16>
 hipError_t launch_smallc(const Problem& p, hipStream_t stream) {
-  using G = SmallC<R, S, C, STRIDE, TH>;
-  auto kern = conv_smallc_f32_kernel<R, S, C, STRIDE, TH>;
+  using G = std::conditional_t<BF16, SmallCB<R, S, C, STRIDE, TH>, SmallC<R, S, C, STRIDE, TH>>;
+  auto kern = [] {
+    if constexpr (BF16) return conv_smallc_f32_bf16_kernel<R, S, C, STRIDE, TH>;
+    else return conv_smallc_f32_kernel<R, S, C, STRIDE, TH>;
+  }();
   // once per instantiation; initialisation of a function-local static is thread-safe
   struct Setup { hipError_t status; int wg_per_cu; };
   static const Setup setup = [&]() {
@@ -267,14 +496,21 @@ bool smallc_f32_applicable(const Problem& p) {
 }
 
 hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** variant) {
-  *variant = "conv_smallc_f32_7x7s2c3";
+  // The bf16 form pays a longer prologue (the filter fragments are cut per workgroup): batch 32 90 -> 61 us, but
+  // batch 1 (196 tiles, launch-bound) 11.8 -> 14.5 us, which therefore keeps the fp32 form.  The knob forces one.
+  const long long tiles4 = (long long)p.n * ((p.oh + 3) / 4) * ((p.ow + TW - 1) / TW);
+  const bool bf16 = knob_or(KNOB_F32_SMALLC_BF16, tiles4 >= 2048 ? 1 : 0) != 0;
+  *variant = bf16 ? "conv_smallc_f32_7x7s2c3_bf16x6" : "conv_smallc_f32_7x7s2c3";
   // the taller tile is the faster one per tile (two independent MFMA chains per wavefront); the
   // shorter one doubles the number of tiles, which pays while there are fewer than about two per
   // resident workgroup (batch 1: 13.8 -> 11.1 us; batch 32: 97.8 vs 100.5 us)
   const long long tiles8 = (long long)p.n * ((p.oh + 7) / 8) * ((p.ow + TW - 1) / TW);
   int th = tiles8 < 1536 ? 4 : 8;
   if (knob_is_set(KNOB_SMALLC_TH)) th = knob(KNOB_SMALLC_TH) == 8 ? 8 : 4;   // experiments
-  return th == 8 ? launch_smallc<7, 7, 3, 2, 8>(p, stream) : launch_smallc<7, 7, 3, 2, 4>(p, stream);
+  // (the bf16 form keeps 132 registers of filter fragments per lane: with two pixel blocks per wavefront it
+  // spills, so it always takes the four-row tile)
+  if (bf16) return launch_smallc<7, 7, 3, 2, 4, true>(p, stream);
+  return th == 8 ? launch_smallc<7, 7, 3, 2, 8, false>(p, stream) : launch_smallc<7, 7, 3, 2, 4, false>(p, stream);
 }
 
 }  // namespace glowmi

@@ -32,9 +32,12 @@ FIRST_LAYER = [
 ]
 
 
+# both forms: products on the fp32 matrix cores, and three exact bf16 pieces per operand with six piece products
 @pytest.mark.parametrize("i", range(len(FIRST_LAYER)))
-def test_first_layer_f32(i):
+@pytest.mark.parametrize("form", [("fp32", 0), ("bf16x6", 1)], ids=lambda f: f[0])
+def test_first_layer_f32(i, form, knobs):
     G = _gpu()
+    knobs.set("F32_SMALLC_BF16", form[1])
     n, h, w, k, pd = FIRST_LAYER[i]
     rng = np.random.default_rng(9900 + i)
     x = rng.uniform(-1, 1, size=(n, h, w, 3)).astype(np.float32)
@@ -44,7 +47,7 @@ def test_first_layer_f32(i):
     for act in (wl.ACT_RELU, wl.ACT_NONE):
         ref = oracle.conv2d_f32(x, wt, b, (2, 2), pd, 1, act=act)
         got, variant = G.gpu_conv2d_f32(x, wt, b, desc, act)
-        assert variant.startswith("conv_smallc_f32"), variant
+        assert variant.startswith("conv_smallc_f32") and variant.endswith("bf16x6") == bool(form[1]), variant
         G.assert_close_f32(got, ref, f"first layer fp32 {FIRST_LAYER[i]} act {act} [{variant}]")
 
 
