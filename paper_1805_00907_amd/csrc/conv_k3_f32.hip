@@ -1,0 +1,294 @@
+// fp32 3x3 Convolution (stride 1) with 64 or more input channels and more than 64 output channels on maps that
+// tile well into 16 x 16 pixel blocks -- the body of a VGG stack -- on the bf16 matrix cores with every operand
+// cut exactly into three bf16 pieces and six piece products per fp32 product (bf16_pieces.h).  The arithmetic is
+// the loop nest of Section 3.1 of the paper with the bias add and Relu stacked onto it (Section 5.2); this is one
+// more kind of convolution with a strategy of its own (Section 5.3).
+//
+// The generic three-piece kernel (igemm_f32_p3.hip) fetches every input element nine times (once per tap) as
+// planes that a packing pass had to write first, and measured a third of its time is the fill path.  Here
+//   - a workgroup owns a 16 x 16 block of output pixels x 128 output channels and walks the input channels in
+//     chunks of 32.  The chunk's 18 x 18 x 32 input patch is read from the fp32 input ONCE (coalesced 32-byte
+//     pieces, zeros outside the image from the range-checked loads), cut into pieces in registers and kept in
+//     LDS as three bf16 planes (61 KB); all nine taps read their MFMA fragments from it at shifted addresses.
+//     No packing pass over the input, and a ninth of the input traffic;
+//   - the filter is cut once per call by the packing kernel into three planes in the workspace and streamed
+//     slab by slab (one tap x 32 channels x 128 output channels, 24 KB) straight into a ring of two LDS
+//     buffers;
+//   - eight wavefronts = four pixel quarters (4 rows x 16 columns: two 32-pixel MFMA blocks) x two channel halves,
+//     64 x 64 outputs each over the whole slab: 48 MFMAs per wavefront between two barriers, 512 bytes of
+//     fragments per MFMA, no exchange of partial tiles;
+//   - workgroups are persistent; the next chunk's (or the next tile's first) patch is fetched into registers
+//     while the current chunk is multiplied, so only cutting and writing it is exposed;
+//   - a pixel's four 16-byte chunks are stored at chunk ^ ((pixel / 4) % 4), which spreads the 16 pixels one
+//     fragment-read phase touches over all bank groups.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <type_traits>
+
+#include "bf16_pieces.h"
+#include "igemm.h"
+#include "lds_direct.h"
+
+namespace glowmi {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int GT = 16;                         // tile side in output pixels
+constexpr int GP = GT + 2;                     // patch side
+constexpr int G_PATCH_PX = GP * GP;            // 324 pixels
+constexpr int G_CH = 32;                       // input channels per chunk = reduction indices per slab
+constexpr int G_PIXB = 2 * G_CH;               // bytes of a pixel's chunk in one plane
+constexpr int G_APLANE = G_PATCH_PX * G_PIXB;  // 20736
+constexpr int G_BN = 128;                      // output channels per tile
+constexpr int G_BROW = 2 * G_CH;               // bytes of a filter row piece in one plane
+constexpr int G_BPLANE = G_BN * G_BROW;        // 8192
+constexpr int G_BBUF = 3 * G_BPLANE;           // one slab
+constexpr int G_NBUF = 2;
+constexpr int G_LDS = 3 * G_APLANE + G_NBUF * G_BBUF;
+constexpr int G_THREADS = 512;
+constexpr int G_ITEMS = G_PATCH_PX * (G_CH / 8);   // (pixel, 8-channel piece) items of a patch chunk
+constexpr int G_PASSES = (G_ITEMS + G_THREADS - 1) / G_THREADS;   // 3
+constexpr int G_PREF = 2 * G_PASSES;           // prefetch loads per thread
+static_assert(G_LDS <= 160 * 1024, "LDS of one CU");
+
+template <bool ADD>
+__global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem p, int tiles_y, int tiles_x,
+                                                                  int tiles_c, int total) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  unsigned char* bring = lds + 3 * G_APLANE;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wn = wave >> 2;                             // channel half: 64 of the tile's 128 output channels
+  const int wm = wave & 3;                              // pixel quarter: tile rows 4wm .. 4wm + 3
+  const int lrow = lane & 31, lhalf = lane >> 5;
+
+  const float* __restrict__ X = static_cast<const float*>(p.x);
+  const __amdgpu_buffer_rsrc_t rsrc_x =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X), 0, (int)p.x_bytes, 0x00020000);
+  const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
+  const v4i rsrc_w = make_rsrc(p.planes, 3u * wpb);
+  constexpr unsigned OOB = 0x80000000u;
+  constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
+
+  const int chunks = p.c / G_CH;                        // p.c % 32 == 0 on this kernel
+  const int slabs = 9 * chunks;
+
+  // ---- tile decode: channel tile fastest (workgroups that share a patch run side by side), then x, y, image
+  auto decode = [&](int t, int& img, int& ty, int& tx, int& ct) {
+    ct = t % tiles_c;
+    t /= tiles_c;
+    tx = t % tiles_x;
+    t /= tiles_x;
+    ty = t % tiles_y;
+    img = t / tiles_y;
+  };
+
+  // ---- patch chunk: item q = tid + 512 * pass is (pixel q / 4 of the patch, channels 8 * (q % 4) .. of the chunk)
+  v4f pre[G_PASSES][2];
+  auto fetch_patch = [&](int t, int chunk) {
+    int img, ty, tx, ct;
+    decode(t, img, ty, tx, ct);
+#pragma unroll
+    for (int q = 0; q < G_PASSES; ++q) {
+      const int item = tid + q * G_THREADS;
+      const int pp = item >> 2, c8 = item & 3;
+      const int py = pp / GP, px = pp - py * GP;
+      const int iy = ty * GT - p.pad_t + py, ix = tx * GT - p.pad_l + px;
+      const bool ok = item < G_ITEMS && (unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w_;
+      const unsigned off =
+          ok ? ((unsigned)((img * p.h + iy) * p.w_ + ix) * (unsigned)p.c + (unsigned)(chunk * G_CH + c8 * 8)) * 4u : OOBX;
+      pre[q][0] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0));
+      pre[q][1] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off == OOBX ? OOBX : off + 16u, 0, 0));
+    }
+  };
+  auto commit_patch = [&]() {
+#pragma unroll
+    for (int q = 0; q < G_PASSES; ++q) {
+      const int item = tid + q * G_THREADS;
+      if (item < G_ITEMS) {
+        const int pp = item >> 2, c8 = item & 3;
+        const float v[8] = {pre[q][0][0], pre[q][0][1], pre[q][0][2], pre[q][0][3],
+                            pre[q][1][0], pre[q][1][1], pre[q][1][2], pre[q][1][3]};
+        v4u h, m, l;
+        split8(v, h, m, l);
+        unsigned char* dst = lds + pp * G_PIXB + ((c8 ^ ((pp >> 2) & 3)) << 4);
+        *reinterpret_cast<v4u*>(dst) = h;
+        *reinterpret_cast<v4u*>(dst + G_APLANE) = m;
+        *reinterpret_cast<v4u*>(dst + 2 * G_APLANE) = l;
+      }
+    }
+  };
+
+  // ---- filter slab loads: 24 wavefront loads per slab (3 planes x 8 groups of 16 rows), three per wavefront
+  // (its 16 rows of each plane).  Lane l: row l / 4 of the group, chunk position l % 4 holding chunk
+  // (l % 4) ^ ((row / 4) % 4) of the row.
+  const int bch = (lane & 3) ^ ((lane >> 4) & 3);
+  auto issue_b = [&](int ct, int slab, int buf) {
+    const int chunk = slab / 9, tap = slab - chunk * 9;
+    const unsigned dst = __builtin_amdgcn_readfirstlane(lds_offset_of(bring) + buf * G_BBUF + wave * 16 * G_BROW);
+    const int n = ct * G_BN + wave * 16 + (lane >> 2);
+    const bool ok = slab < slabs && n < p.k;           // past the last slab: zero fills, no memory traffic
+    const unsigned off = ok ? 2u * ((unsigned)n * (unsigned)p.Kgemm + (unsigned)(tap * p.c + chunk * G_CH + bch * 8)) : OOB;
+#pragma unroll
+    for (int pc = 0; pc < 3; ++pc) load16_to_lds(rsrc_w, dst + pc * G_BPLANE, off + pc * wpb);
+  };
+
+  // ---- fragment addresses.  Input: MFMA block i of this wavefront is tile rows 4wm + 2i, + 1 (16 pixels each);
+  // lane lrow is pixel (lrow / 16, lrow % 16) of the block.  Filter: row = output channel wn * 64 + j * 32 + lrow.
+  int pp0[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) pp0[i] = (4 * wm + 2 * i + (lrow >> 4)) * GP + (lrow & 15);
+  const int b_row = (wn * 64 + lrow) * G_BROW;
+  const int b_sw = (lrow >> 2) & 3;
+
+  float* __restrict__ Y = static_cast<float*>(p.y);
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  const float* addend = static_cast<const float*>(p.addend);   // may be the output itself
+  const bool relu = p.act == 1;
+
+  int t = blockIdx.x;
+  if (t >= total) return;
+  fetch_patch(t, 0);
+  for (; t < total; t += gridDim.x) {
+    int img, ty, tx, ct;
+    decode(t, img, ty, tx, ct);
+    const int t_next = t + gridDim.x;
+    __syncthreads();                                    // everyone is done with the previous tile's last slab buffer
+    issue_b(ct, 0, 0);
+
+    v16f acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    int s = 0;
+    for (int chunk = 0; chunk < chunks; ++chunk) {
+      // ---- the chunk's patch: everyone is done with the previous one, write it, publish it (the barrier of the
+      // first trip below), and start fetching the next: the next chunk of this tile or chunk 0 of the next tile
+      __syncthreads();
+      commit_patch();
+      const bool fetching = chunk + 1 < chunks || t_next < total;     // uniform
+      if (chunk + 1 < chunks) fetch_patch(t, chunk + 1);
+      else if (t_next < total) fetch_patch(t_next, 0);
+      // ---- nine taps.  Trip: slab s has landed (the prefetch issued after it may still be in flight on the first
+      // trip of a chunk; later trips wait for everything, by then about a slab's time has passed), barrier,
+      // refill the other buffer with slab s + 1, multiply slab s.
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap, ++s) {
+        if (tap == 0 && fetching) __builtin_amdgcn_s_waitcnt(vmcnt_imm(G_PREF));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        __syncthreads();
+        issue_b(ct, s + 1, (s + 1) & 1);
+        const int tr = tap / 3, ts = tap - tr * 3;                     // compile-time
+        const unsigned char* bb = bring + (s & 1) * G_BBUF + b_row;
+        int a_base[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a_base[i] = pp0[i] + tr * GP + ts;
+#pragma unroll
+        for (int k16 = 0; k16 < 2; ++k16) {
+          const int c8 = k16 * 2 + lhalf;                              // this lane's 16-byte chunk of the pixel / filter row
+          v8bf a[3][2], b[3][2];
+          constexpr int ORDER_A[3] = {2, 0, 1}, ORDER_B[3] = {0, 2, 1};   // the order the MFMAs use them in
+          int a_off[2];
+#pragma unroll
+          for (int i = 0; i < 2; ++i) a_off[i] = a_base[i] * G_PIXB + ((c8 ^ ((a_base[i] >> 2) & 3)) << 4);
+          const int b_off = (c8 ^ b_sw) << 4;
+#pragma unroll
+          for (int o = 0; o < 3; ++o) {
+            const int pa = ORDER_A[o], pb = ORDER_B[o];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+              a[pa][i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(lds + pa * G_APLANE + a_off[i]));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+              b[pb][j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(bb + pb * G_BPLANE + j * 32 * G_BROW + b_off));
+          }
+#pragma unroll
+          for (int q = 0; q < 24; ++q) {
+            const int tt = q / 4, i = (q / 2) % 2, j = q % 2;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[tt]][i], b[kPieceTermB[tt]][j], acc[i][j], 0, 0, 0);
+          }
+        }
+      }
+    }
+
+    // ---- epilogue.  Register e of a lane is pixel (e/4)*8 + 4*lhalf + e%4 of the 32-pixel block, i.e. tile row
+    // 4wm + 2i + pixel / 16, column pixel % 16; channel wn * 64 + j * 32 + lrow.
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int ch = ct * G_BN + wn * 64 + j * 32 + lrow;
+      const bool cok = ch < p.k;
+      const float bv = (cok && bias) ? bias[ch] : 0.f;
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int oy0 = ty * GT + 4 * wm + 2 * i, ox0 = tx * GT;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int px = (e >> 2) * 8 + lhalf * 4 + (e & 3);
+          const int oy = oy0 + (px >> 4), ox = ox0 + (px & 15);
+          if (cok && oy < p.oh && ox < p.ow) {
+            const size_t o = ((size_t)(img * p.oh + oy) * p.ow + ox) * p.k + ch;
+            float v = acc[i][j][e] + bv;
+            if (ADD) v += addend[o];
+            if (relu) v = fmaxf(v, 0.f);
+            Y[o] = v;
+          }
+        }
+      }
+    }
+  }
+}
+
+template <bool ADD>
+hipError_t launch_k3g_variant(const Problem& p, hipStream_t stream) {
+  auto kern = conv_k3_f32_kernel<ADD>;
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G_LDS);
+  if (attr_status != hipSuccess) return attr_status;
+  const int num_cu = num_compute_units();
+  if (num_cu < 1) return hipErrorInvalidDevice;
+  const int tiles_y = (p.oh + GT - 1) / GT, tiles_x = (p.ow + GT - 1) / GT, tiles_c = (p.k + G_BN - 1) / G_BN;
+  const long long total = (long long)p.n * tiles_y * tiles_x * tiles_c;
+  const long long grid = total < num_cu ? total : num_cu;   // one persistent workgroup per CU
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(G_THREADS), G_LDS, stream, p, tiles_y, tiles_x, tiles_c, (int)total);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool k3_f32_applicable(const Problem& p) {
+  if (knob_or(KNOB_F32_K3, 1) == 0) return false;
+  if (p.b_is_kn || p.chain_n > 0 || p.groups != 1 || p.r != 3 || p.s != 3) return false;
+  if (p.stride_h != 1 || p.stride_w != 1) return false;
+  if (p.c < 64 || p.c % G_CH != 0 || p.k <= 64) return false;
+  if (p.x_bytes > 0xF0000000u || p.w_bytes > (1u << 30)) return false;
+  const long long ty = (p.oh + GT - 1) / GT, tx = (p.ow + GT - 1) / GT, tc = (p.k + G_BN - 1) / G_BN;
+  const long long tiles = (long long)p.n * ty * tx * tc;
+  if (tiles >= (1LL << 30)) return false;
+  if (knob_or(KNOB_F32_K3_ANY, 0) != 0) return true;    // tests: any size
+  // the tiles must be mostly full (a 28 x 28 or 56 x 56 map fills 77 % of its 16 x 16 blocks, which still beats the
+  // generic kernel: 512 -> 512 on 28 x 28 at batch 16 is 256 tiles = one round here, 361 -> 329 us; a 14 x 14 map at
+  // batch 16 has only 64 tiles, 105 -> 252 us, and stays there), and there must be a tile for every CU
+  const double fill = (double)p.oh * p.ow / (double)(ty * tx * GT * GT) * ((double)p.k / (double)(tc * G_BN));
+  return fill >= 0.75 && tiles >= 256;
+}
+
+size_t k3_f32_pack_bytes(const Problem& p) { return ((size_t)3 * (p.w_bytes >> 1) + 255) / 256 * 256; }
+
+hipError_t launch_k3_f32(const Problem& p, hipStream_t stream, const char** variant) {
+  if (!p.planes) return hipErrorInvalidValue;           // the ABI layer never plans this kernel without a workspace
+  hipError_t e = launch_pack3_rows(static_cast<const float*>(p.w), const_cast<void*>(p.planes), (long long)(p.w_bytes >> 2), stream);
+  if (e != hipSuccess) return e;
+  *variant = p.addend ? "conv_k3_f32_bf16x6_add" : "conv_k3_f32_bf16x6";
+  return p.addend ? launch_k3g_variant<true>(p, stream) : launch_k3g_variant<false>(p, stream);
+}
+
+}  // namespace glowmi

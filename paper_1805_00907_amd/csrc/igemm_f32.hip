@@ -681,6 +681,12 @@ Plan plan_f32(const Problem& p, bool allow_split) {
       pl.pack_bytes = k3c64_f32_pack_bytes(p);
       return pl;
     }
+    // 3x3 stride 1 with many channels on maps that tile into 16 x 16 blocks, again only the filter repacked
+    if (allow_split && p.allow_pack && k3_f32_applicable(p)) {
+      pl.kernel = KERNEL_K3;
+      pl.pack_bytes = k3_f32_pack_bytes(p);
+      return pl;
+    }
     // large contractions with a workspace to repack the operands into: the bf16 three-piece kernel
     if (allow_split && p.allow_pack && p3_f32_applicable(p)) return plan_p3_f32(p);
     if (pw_f32_applicable(p)) { pl.kernel = KERNEL_PW; return pl; }
@@ -822,6 +828,7 @@ hipError_t launch_f32(const Problem& p_in, const Plan& plan, hipStream_t stream,
     case KERNEL_FC_SMALL: return launch_fc_small_f32(p_in, stream, variant);
     case KERNEL_P3: return launch_p3_f32(p_in, plan, stream, variant);
     case KERNEL_K3C64: return launch_k3c64_f32(p_in, stream, variant);
+    case KERNEL_K3: return launch_k3_f32(p_in, stream, variant);
     default: break;
   }
   if (plan.split_k > 1 && !p_in.partial) return hipErrorInvalidValue;   // the ABI layer never plans a split without a workspace

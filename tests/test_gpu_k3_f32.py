@@ -1,0 +1,90 @@
+"""The fp32 3x3 stride-1 kernel for many channels (16 x 16 pixel tiles x 128 output channels, the input walked
+in 32-channel chunks whose patch is cut into three bf16 planes in LDS, six bf16 MFMAs per product) through the
+C ABI against the CPU oracle, element by element, at |gpu - oracle| <= 1e-5 + 1e-4 |oracle|: one, two (even)
+and three (odd) channel chunks, ragged pixel and channel tiles, every kind of padding, more tiles than CUs
+(persistent workgroups, patch prefetch across tiles), the tensor-add link, no bias.  The planner's shape
+conditions are lifted through a tuning knob so that small shapes reach the kernel.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_1805_00907_amd import workloads as wl
+
+
+def _gpu():
+    import gpu_util
+    return gpu_util
+
+
+# n  h  w  c  k  pads (top, left, bottom, right)
+SHAPES = [
+    (1, 16, 16, 64, 128, (1, 1, 1, 1)),     # one tile, two chunks
+    (2, 20, 37, 96, 128, (1, 1, 1, 1)),     # three chunks (odd: the slab ring ends on the other buffer), ragged tiles
+    (1, 18, 18, 128, 200, (0, 0, 0, 0)),    # no padding, ragged second channel tile
+    (3, 13, 14, 64, 72, (1, 0, 0, 1)),      # asymmetric padding, one ragged channel tile
+    (1, 3, 40, 256, 136, (0, 1, 0, 1)),     # one output row, eight chunks
+    (1, 33, 3, 64, 130, (1, 0, 1, 0)),      # one output column
+    (1, 12, 12, 64, 128, (2, 3, 2, 1)),     # padding wider than the filter needs
+    (9, 56, 56, 64, 128, (1, 1, 1, 1)),     # 144 tiles
+    (5, 112, 112, 64, 96, (1, 1, 1, 1)),    # 245 tiles
+    (3, 112, 112, 128, 256, (1, 1, 1, 1)),  # 294 tiles: some workgroups take two (prefetch across tiles)
+]
+
+
+def _case(i):
+    n, h, w, c, k, pd = SHAPES[i]
+    rng = np.random.default_rng(34000 + i)
+    x = rng.uniform(-1, 1, size=(n, h, w, c)).astype(np.float32)
+    wt = (rng.standard_normal(size=(k, 3, 3, c)) / np.sqrt(9 * c)).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(k,)).astype(np.float32)
+    return x, wt, b, pd
+
+
+@pytest.mark.parametrize("i", range(len(SHAPES)))
+def test_conv_k3_f32(i, knobs):
+    G = _gpu()
+    knobs.set("F32_K3_ANY", 1)
+    x, wt, b, pd = _case(i)
+    desc = G.make_desc(x.shape, wt.shape, (1, 1), pd, 1)
+    for act, bias in ((wl.ACT_RELU, b), (wl.ACT_NONE, None)):
+        ref = oracle.conv2d_f32(x, wt, bias, (1, 1), pd, 1, act=act)
+        got, variant = G.gpu_conv2d_f32(x, wt, bias, desc, act)
+        assert variant == "conv_k3_f32_bf16x6", variant
+        G.assert_close_f32(got, ref, f"case {i} act {act} [{variant}]")
+
+
+@pytest.mark.parametrize("i", [1, 2, 3])
+@pytest.mark.parametrize("in_place", [False, True])
+def test_conv_k3_f32_tensor_add_link(i, in_place, knobs):
+    G = _gpu()
+    knobs.set("F32_K3_ANY", 1)
+    x, wt, b, pd = _case(i)
+    n, h, w, _ = x.shape
+    oh, ow = h + pd[0] + pd[2] - 2, w + pd[1] + pd[3] - 2
+    add = np.random.default_rng(34100 + i).uniform(-1, 1, size=(n, oh, ow, wt.shape[0])).astype(np.float32)
+    ref = oracle.conv2d_f32_add(x, wt, b, add, (1, 1), pd, 1, act=wl.ACT_RELU)
+    got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, G.make_desc(x.shape, wt.shape, (1, 1), pd, 1), wl.ACT_RELU,
+                                          in_place=in_place)
+    assert variant == "conv_k3_f32_bf16x6_add", variant
+    G.assert_close_f32(got, ref, f"case {i} add link in_place {in_place}")
+
+
+def test_conv_k3_f32_is_the_planners_choice_only_where_the_map_tiles_well(knobs):
+    G = _gpu()
+    x, wt, b, pd = _case(1)
+    desc = G.make_desc(x.shape, wt.shape, (1, 1), pd, 1)
+    ref = oracle.conv2d_f32(x, wt, b, (1, 1), pd, 1, act=wl.ACT_RELU)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)            # 12 tiles, 20 x 37 map: not taken
+    assert not variant.startswith("conv_k3_f32"), variant
+    G.assert_close_f32(got, ref, f"[{variant}]")
+    knobs.set("F32_K3_ANY", 1)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU, use_workspace=False)
+    assert not variant.startswith("conv_k3_f32"), variant
+    G.assert_close_f32(got, ref, f"no workspace [{variant}]")
+    knobs.set("F32_K3", 0)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)
+    assert not variant.startswith("conv_k3_f32"), variant
+    G.assert_close_f32(got, ref, f"switched off [{variant}]")
