@@ -340,7 +340,7 @@ def test_workspace_queries_are_pure():
     assert need >= planes and (need - planes) % (4 * y_elems) == 0    # + the partial sums of a split reduction
     glowmi.tuning_set("F32_P3", 0)
     try:
-        assert glowmi.conv2d_workspace_bytes(big) < planes
+        assert glowmi.conv2d_workspace_bytes(big) % (4 * y_elems) == 0     # partial sums only
     finally:
         glowmi.tuning_reset()
     # 3x3 stride 1 on maps that tile into 16 x 16 blocks: only the filter is repacked
