@@ -423,8 +423,10 @@ size_t p3_pack_bytes(const Problem& p) {
 
 // Worth it when the contraction is large against the one-off cost of cutting both operands (about ten bytes
 // of memory traffic per element), the operands' shapes allow 16-byte plane chunks, and there are enough
-// pixels and channels for the 128-pixel tiles.  Measured break-even: about 400 flops per operand element
-// (FullyConnected 256 x 4096 x 4096, 483 flops per element: 86 us here against 106 us on the fp32 matrix cores).
+// pixels and channels for the 128-pixel tiles.  Measured break-even: 400-600 flops per operand element
+// (FullyConnected 256 x 4096 x 4096, 483 flops per element: launched back to back 86 us here against 106 us on
+// the fp32 matrix cores, but 102 against 99 us inside a step of other layers, where its 100 MB of planes are
+// written and read cold; 512 x 4096 x 4096, 910 per element: 135 against 205 us).
 bool p3_f32_applicable(const Problem& p) {
   if (knob_or(KNOB_F32_P3, 1) == 0) return false;
   if (p.chain_n > 0 || p.cg % 8 != 0 || p.c % 8 != 0) return false;
@@ -440,7 +442,7 @@ bool p3_f32_applicable(const Problem& p) {
   // three launches (two packing kernels and the contraction) are worth ~15 us before any work is done
   if (min_m > 1 && flops < 2e9) return false;
   const double elems = (double)(p.x_bytes >> 2) + (double)(p.w_bytes >> 2);
-  return flops >= (double)knob_or(KNOB_F32_P3_RATIO, 400) * elems;
+  return flops >= (double)knob_or(KNOB_F32_P3_RATIO, 600) * elems;
 }
 
 Plan plan_p3_f32(const Problem& p) {
