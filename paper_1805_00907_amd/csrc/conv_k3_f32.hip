@@ -36,35 +36,48 @@ namespace {
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 
-constexpr int GT = 16;                         // tile side in output pixels
-constexpr int GP = GT + 2;                     // patch side
-constexpr int G_PATCH_PX = GP * GP;            // 324 pixels
+constexpr int GT = 16;                         // tile height in output pixels
 constexpr int G_CH = 32;                       // input channels per chunk = reduction indices per slab
 constexpr int G_PIXB = 2 * G_CH;               // bytes of a pixel's chunk in one plane
-constexpr int G_APLANE = G_PATCH_PX * G_PIXB;  // 20736
-constexpr int G_BN = 128;                      // output channels per tile
 constexpr int G_BROW = 2 * G_CH;               // bytes of a filter row piece in one plane
-constexpr int G_BPLANE = G_BN * G_BROW;        // 8192
-constexpr int G_BBUF = 3 * G_BPLANE;           // one slab
 constexpr int G_NBUF = 2;
-constexpr int G_LDS = 3 * G_APLANE + G_NBUF * G_BBUF;
 constexpr int G_THREADS = 512;
-constexpr int G_ITEMS = G_PATCH_PX * (G_CH / 8);   // (pixel, 8-channel piece) items of a patch chunk
-constexpr int G_PASSES = (G_ITEMS + G_THREADS - 1) / G_THREADS;   // 3
-constexpr int G_PREF = 2 * G_PASSES;           // prefetch loads per thread
-static_assert(G_LDS <= 160 * 1024, "LDS of one CU");
+constexpr int G_DUMMY = 1024;                  // landing area of the loads issued only to keep the counts equal
 
-template <bool ADD>
+// Tile shapes: TW output columns x 16 rows, BN output channels.  512 threads = eight wavefronts of 64 pixels x 64
+// channels each: (16 x 16) x 128 is four pixel quarters x two channel halves, (16 x 32) x 64 eight pixel eighths.
+template <int TW, int BN>
+struct K3 {
+  static_assert((TW == 16 && BN == 128) || (TW == 32 && BN == 64), "tile shapes");
+  static constexpr int PW = TW + 2;                          // patch width
+  static constexpr int PATCH_PX = (GT + 2) * PW;
+  static constexpr int APLANE = PATCH_PX * G_PIXB;
+  static constexpr int BPLANE = BN * G_BROW;
+  static constexpr int BBUF = 3 * BPLANE;                    // one slab
+  static constexpr int LDS = 3 * APLANE + G_NBUF * BBUF + G_DUMMY;
+  static constexpr int ITEMS = PATCH_PX * (G_CH / 8);        // (pixel, 8-channel piece) items of a patch chunk
+  static constexpr int PASSES = (ITEMS + G_THREADS - 1) / G_THREADS;
+  static constexpr int PREF = 2 * PASSES;                    // prefetch loads per thread
+  static constexpr int WLOADS = 3 * BN / 16;                 // wavefront loads per filter slab (16 rows each)
+  static constexpr int LPW = (WLOADS + 7) / 8;               // per wavefront (the last ones may be zero fills into the dummy area)
+  static constexpr int WAVES_N = BN / 64;
+  static_assert(LDS <= 160 * 1024, "LDS of one CU");
+};
+
+template <bool ADD, int TW, int BN>
 __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem p, int tiles_y, int tiles_x,
                                                                   int tiles_c, int total) {
+  using T = K3<TW, BN>;
+  constexpr int GP = T::PW, G_APLANE = T::APLANE, G_BPLANE = T::BPLANE, G_BBUF = T::BBUF, G_BN = BN;
+  constexpr int G_ITEMS = T::ITEMS, G_PASSES = T::PASSES, G_PREF = T::PREF;
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char* bring = lds + 3 * G_APLANE;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wn = wave >> 2;                             // channel half: 64 of the tile's 128 output channels
-  const int wm = wave & 3;                              // pixel quarter: tile rows 4wm .. 4wm + 3
+  const int wn = wave % T::WAVES_N;                     // which 64 of the tile's output channels
+  const int wm = wave / T::WAVES_N;                     // which 64 of the tile's pixels (row-major inside the tile)
   const int lrow = lane & 31, lhalf = lane >> 5;
 
   const float* __restrict__ X = static_cast<const float*>(p.x);
@@ -98,7 +111,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
       const int item = tid + q * G_THREADS;
       const int pp = item >> 2, c8 = item & 3;
       const int py = pp / GP, px = pp - py * GP;
-      const int iy = ty * GT - p.pad_t + py, ix = tx * GT - p.pad_l + px;
+      const int iy = ty * GT - p.pad_t + py, ix = tx * TW - p.pad_l + px;
       const bool ok = item < G_ITEMS && (unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w_;
       const unsigned off =
           ok ? ((unsigned)((img * p.h + iy) * p.w_ + ix) * (unsigned)p.c + (unsigned)(chunk * G_CH + c8 * 8)) * 4u : OOBX;
@@ -124,25 +137,38 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
     }
   };
 
-  // ---- filter slab loads: 24 wavefront loads per slab (3 planes x 8 groups of 16 rows), three per wavefront
-  // (its 16 rows of each plane).  Lane l: row l / 4 of the group, chunk position l % 4 holding chunk
+  // ---- filter slab loads: 3 planes x BN / 16 groups of 16 rows per slab; wavefront w issues numbers w, w + 8, ..
+  // (LPW of them; a number past the last is a zero fill into the dummy area, so that every wavefront has the same
+  // number of loads outstanding).  Lane l: row l / 4 of the group, chunk position l % 4 holding chunk
   // (l % 4) ^ ((row / 4) % 4) of the row.
   const int bch = (lane & 3) ^ ((lane >> 4) & 3);
   auto issue_b = [&](int ct, int slab, int buf) {
     const int chunk = slab / 9, tap = slab - chunk * 9;
-    const unsigned dst = __builtin_amdgcn_readfirstlane(lds_offset_of(bring) + buf * G_BBUF + wave * 16 * G_BROW);
-    const int n = ct * G_BN + wave * 16 + (lane >> 2);
-    const bool ok = slab < slabs && n < p.k;           // past the last slab: zero fills, no memory traffic
-    const unsigned off = ok ? 2u * ((unsigned)n * (unsigned)p.Kgemm + (unsigned)(tap * p.c + chunk * G_CH + bch * 8)) : OOB;
+    const unsigned lbase = __builtin_amdgcn_readfirstlane(lds_offset_of(bring) + buf * G_BBUF);
+    const unsigned k_off = (unsigned)(tap * p.c + chunk * G_CH + bch * 8);
 #pragma unroll
-    for (int pc = 0; pc < 3; ++pc) load16_to_lds(rsrc_w, dst + pc * G_BPLANE, off + pc * wpb);
+    for (int u = 0; u < T::LPW; ++u) {
+      const int j = wave + 8 * u;                        // load number: plane j / (BN / 16), row group j % (BN / 16)
+      const int plane = j / (BN / 16), rg = j % (BN / 16);
+      const int n = ct * G_BN + rg * 16 + (lane >> 2);
+      const bool real = j < T::WLOADS;
+      const bool ok = real && slab < slabs && n < p.k;   // past the last slab: zero fills, no memory traffic
+      const unsigned off = ok ? 2u * ((unsigned)n * (unsigned)p.Kgemm + k_off) + (unsigned)plane * wpb : OOB;
+      const unsigned dst = real ? lbase + plane * G_BPLANE + rg * 16 * G_BROW
+                                : __builtin_amdgcn_readfirstlane(lds_offset_of(bring) + G_NBUF * G_BBUF);
+      load16_to_lds(rsrc_w, dst, off);
+    }
   };
 
-  // ---- fragment addresses.  Input: MFMA block i of this wavefront is tile rows 4wm + 2i, + 1 (16 pixels each);
-  // lane lrow is pixel (lrow / 16, lrow % 16) of the block.  Filter: row = output channel wn * 64 + j * 32 + lrow.
+  // ---- fragment addresses.  Input: MFMA block i of this wavefront holds tile pixels 64wm + 32i .. + 31 in row-major
+  // order (TW = 16: two rows of 16; TW = 32: one row); lane lrow is the lrow-th of them.  Filter: row = output
+  // channel wn * 64 + j * 32 + lrow.
   int pp0[2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) pp0[i] = (4 * wm + 2 * i + (lrow >> 4)) * GP + (lrow & 15);
+  for (int i = 0; i < 2; ++i) {
+    const int tp = 64 * wm + 32 * i + lrow;
+    pp0[i] = (tp / TW) * GP + tp % TW;
+  }
   const int b_row = (wn * 64 + lrow) * G_BROW;
   const int b_sw = (lrow >> 2) & 3;
 
@@ -151,7 +177,9 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   const float* addend = static_cast<const float*>(p.addend);   // may be the output itself
   const bool relu = p.act == 1;
 
-  int t = blockIdx.x;
+  // Consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous run of tiles, so that the
+  // channel tiles that share a patch (consecutive tile numbers) fetch it through the same L2.
+  int t = (gridDim.x & 7) == 0 ? (int)((blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
   if (t >= total) return;
   fetch_patch(t, 0);
   for (; t < total; t += gridDim.x) {
@@ -220,8 +248,8 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
       }
     }
 
-    // ---- epilogue.  Register e of a lane is pixel (e/4)*8 + 4*lhalf + e%4 of the 32-pixel block, i.e. tile row
-    // 4wm + 2i + pixel / 16, column pixel % 16; channel wn * 64 + j * 32 + lrow.
+    // ---- epilogue.  Register e of a lane is pixel (e/4)*8 + 4*lhalf + e%4 of the 32-pixel block, i.e. tile pixel
+    // 64wm + 32i + that; channel wn * 64 + j * 32 + lrow.
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int ch = ct * G_BN + wn * 64 + j * 32 + lrow;
@@ -229,11 +257,10 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
       const float bv = (cok && bias) ? bias[ch] : 0.f;
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
-        const int oy0 = ty * GT + 4 * wm + 2 * i, ox0 = tx * GT;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-          const int px = (e >> 2) * 8 + lhalf * 4 + (e & 3);
-          const int oy = oy0 + (px >> 4), ox = ox0 + (px & 15);
+          const int tp = 64 * wm + 32 * i + (e >> 2) * 8 + lhalf * 4 + (e & 3);
+          const int oy = ty * GT + tp / TW, ox = tx * TW + tp % TW;
           if (cok && oy < p.oh && ox < p.ow) {
             const size_t o = ((size_t)(img * p.oh + oy) * p.ow + ox) * p.k + ch;
             float v = acc[i][j][e] + bv;
@@ -247,20 +274,24 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   }
 }
 
-template <bool ADD>
+template <bool ADD, int TW, int BN>
 hipError_t launch_k3g_variant(const Problem& p, hipStream_t stream) {
-  auto kern = conv_k3_f32_kernel<ADD>;
+  using T = K3<TW, BN>;
+  auto kern = conv_k3_f32_kernel<ADD, TW, BN>;
   static const hipError_t attr_status = hipFuncSetAttribute(
-      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, G_LDS);
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, T::LDS);
   if (attr_status != hipSuccess) return attr_status;
   const int num_cu = num_compute_units();
   if (num_cu < 1) return hipErrorInvalidDevice;
-  const int tiles_y = (p.oh + GT - 1) / GT, tiles_x = (p.ow + GT - 1) / GT, tiles_c = (p.k + G_BN - 1) / G_BN;
+  const int tiles_y = (p.oh + GT - 1) / GT, tiles_x = (p.ow + TW - 1) / TW, tiles_c = (p.k + BN - 1) / BN;
   const long long total = (long long)p.n * tiles_y * tiles_x * tiles_c;
   const long long grid = total < num_cu ? total : num_cu;   // one persistent workgroup per CU
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(G_THREADS), G_LDS, stream, p, tiles_y, tiles_x, tiles_c, (int)total);
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(G_THREADS), T::LDS, stream, p, tiles_y, tiles_x, tiles_c, (int)total);
   return hipGetLastError();
 }
+
+// Few output channels take the wide pixel tile with 64 channels, the rest 16 x 16 pixels x 128 channels.
+bool k3_wide_tile(const Problem& p) { return p.k <= 64; }
 
 }  // namespace
 
@@ -268,16 +299,17 @@ bool k3_f32_applicable(const Problem& p) {
   if (knob_or(KNOB_F32_K3, 1) == 0) return false;
   if (p.b_is_kn || p.chain_n > 0 || p.groups != 1 || p.r != 3 || p.s != 3) return false;
   if (p.stride_h != 1 || p.stride_w != 1) return false;
-  if (p.c < 64 || p.c % G_CH != 0 || p.k <= 64) return false;
+  if (p.c < 64 || p.c % G_CH != 0) return false;
   if (p.x_bytes > 0xF0000000u || p.w_bytes > (1u << 30)) return false;
-  const long long ty = (p.oh + GT - 1) / GT, tx = (p.ow + GT - 1) / GT, tc = (p.k + G_BN - 1) / G_BN;
+  const int tw = k3_wide_tile(p) ? 32 : 16, bn = k3_wide_tile(p) ? 64 : 128;
+  const long long ty = (p.oh + GT - 1) / GT, tx = (p.ow + tw - 1) / tw, tc = (p.k + bn - 1) / bn;
   const long long tiles = (long long)p.n * ty * tx * tc;
   if (tiles >= (1LL << 30)) return false;
   if (knob_or(KNOB_F32_K3_ANY, 0) != 0) return true;    // tests: any size
   // the tiles must be mostly full (a 28 x 28 or 56 x 56 map fills 77 % of its 16 x 16 blocks, which still beats the
   // generic kernel: 512 -> 512 on 28 x 28 at batch 16 is 256 tiles = one round here, 361 -> 329 us; a 14 x 14 map at
   // batch 16 has only 64 tiles, 105 -> 252 us, and stays there), and there must be a tile for every CU
-  const double fill = (double)p.oh * p.ow / (double)(ty * tx * GT * GT) * ((double)p.k / (double)(tc * G_BN));
+  const double fill = (double)p.oh * p.ow / (double)(ty * tx * GT * tw) * ((double)p.k / (double)(tc * bn));
   return fill >= 0.75 && tiles >= 256;
 }
 
@@ -287,8 +319,12 @@ hipError_t launch_k3_f32(const Problem& p, hipStream_t stream, const char** vari
   if (!p.planes) return hipErrorInvalidValue;           // the ABI layer never plans this kernel without a workspace
   hipError_t e = launch_pack3_rows(static_cast<const float*>(p.w), const_cast<void*>(p.planes), (long long)(p.w_bytes >> 2), stream);
   if (e != hipSuccess) return e;
+  if (k3_wide_tile(p)) {
+    *variant = p.addend ? "conv_k3_f32_bf16x6_16x32x64_add" : "conv_k3_f32_bf16x6_16x32x64";
+    return p.addend ? launch_k3g_variant<true, 32, 64>(p, stream) : launch_k3g_variant<false, 32, 64>(p, stream);
+  }
   *variant = p.addend ? "conv_k3_f32_bf16x6_add" : "conv_k3_f32_bf16x6";
-  return p.addend ? launch_k3g_variant<true>(p, stream) : launch_k3g_variant<false>(p, stream);
+  return p.addend ? launch_k3g_variant<true, 16, 128>(p, stream) : launch_k3g_variant<false, 16, 128>(p, stream);
 }
 
 }  // namespace glowmi

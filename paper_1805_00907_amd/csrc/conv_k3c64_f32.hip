@@ -154,7 +154,9 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
   const float* addend = static_cast<const float*>(p.addend);   // may be the output itself
   const bool relu = p.act == 1;
 
-  int t = blockIdx.x;
+  // Consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous run of tiles, so that the
+  // channel tiles that share a patch (consecutive tile numbers) fetch it through the same L2.
+  int t = (gridDim.x & 7) == 0 ? (int)((blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
   if (t >= total) return;
   fetch_patch(t);
   for (; t < total; t += gridDim.x) {

@@ -1,7 +1,7 @@
 """The fp32 3x3 stride-1 kernel for many channels (16 x 16 pixel tiles x 128 output channels, the input walked
 in 32-channel chunks whose patch is cut into three bf16 planes in LDS, six bf16 MFMAs per product) through the
 C ABI against the CPU oracle, element by element, at |gpu - oracle| <= 1e-5 + 1e-4 |oracle|: one, two (even)
-and three (odd) channel chunks, ragged pixel and channel tiles, every kind of padding, more tiles than CUs
+and three (odd) channel chunks, both tile shapes (16 x 16 pixels x 128 channels, 16 x 32 x 64), ragged pixel and channel tiles, every kind of padding, more tiles than CUs
 (persistent workgroups, patch prefetch across tiles), the tensor-add link, no bias.  The planner's shape
 conditions are lifted through a tuning knob so that small shapes reach the kernel.
 """
@@ -31,6 +31,14 @@ SHAPES = [
     (9, 56, 56, 64, 128, (1, 1, 1, 1)),     # 144 tiles
     (5, 112, 112, 64, 96, (1, 1, 1, 1)),    # 245 tiles
     (3, 112, 112, 128, 256, (1, 1, 1, 1)),  # 294 tiles: some workgroups take two (prefetch across tiles)
+    # 64 output channels or fewer: the 16 x 32 pixel tile with 64 channels
+    (1, 16, 32, 64, 64, (1, 1, 1, 1)),      # exactly one tile
+    (2, 21, 45, 96, 64, (1, 1, 1, 1)),      # ragged tiles, three chunks
+    (1, 18, 70, 64, 40, (0, 0, 0, 0)),      # no padding, ragged channel tile
+    (3, 9, 33, 128, 64, (1, 0, 0, 1)),      # asymmetric padding
+    (1, 40, 3, 64, 16, (1, 0, 1, 0)),       # one output column
+    (6, 112, 112, 64, 64, (1, 1, 1, 1)),    # 168 tiles
+    (5, 224, 224, 64, 64, (1, 1, 1, 1)),    # 490 tiles: workgroups take two (prefetch across tiles)
 ]
 
 
@@ -47,16 +55,17 @@ def _case(i):
 def test_conv_k3_f32(i, knobs):
     G = _gpu()
     knobs.set("F32_K3_ANY", 1)
+    knobs.set("F32_K3C64", 0)               # the 64-input-channel kernel would take the largest C = 64 case
     x, wt, b, pd = _case(i)
     desc = G.make_desc(x.shape, wt.shape, (1, 1), pd, 1)
     for act, bias in ((wl.ACT_RELU, b), (wl.ACT_NONE, None)):
         ref = oracle.conv2d_f32(x, wt, bias, (1, 1), pd, 1, act=act)
         got, variant = G.gpu_conv2d_f32(x, wt, bias, desc, act)
-        assert variant == "conv_k3_f32_bf16x6", variant
+        assert variant == ("conv_k3_f32_bf16x6_16x32x64" if wt.shape[0] <= 64 else "conv_k3_f32_bf16x6"), variant
         G.assert_close_f32(got, ref, f"case {i} act {act} [{variant}]")
 
 
-@pytest.mark.parametrize("i", [1, 2, 3])
+@pytest.mark.parametrize("i", [1, 2, 3, 11, 12])
 @pytest.mark.parametrize("in_place", [False, True])
 def test_conv_k3_f32_tensor_add_link(i, in_place, knobs):
     G = _gpu()
@@ -68,7 +77,7 @@ def test_conv_k3_f32_tensor_add_link(i, in_place, knobs):
     ref = oracle.conv2d_f32_add(x, wt, b, add, (1, 1), pd, 1, act=wl.ACT_RELU)
     got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, G.make_desc(x.shape, wt.shape, (1, 1), pd, 1), wl.ACT_RELU,
                                           in_place=in_place)
-    assert variant == "conv_k3_f32_bf16x6_add", variant
+    assert variant.startswith("conv_k3_f32_bf16x6") and variant.endswith("_add"), variant
     G.assert_close_f32(got, ref, f"case {i} add link in_place {in_place}")
 
 
