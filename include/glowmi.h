@@ -334,12 +334,10 @@ glowmi_status glowmi_rescale_params(float r_scale, float x_scale, float w_scale,
  * from environment variables GLOWMI_<name>.  Every setting computes the same result (int8: bit for
  * bit; fp32: within the accuracy stated at the top of this file, the kernels differ in rounding order and
  * in which matrix cores form the products: "F32_P3", "F32_K3", "F32_K3C64", "F32_PW_BF16",
- * "F32_SMALLC_BF16" = 0 keep a layer on the fp32 matrix cores); only the choice of kernel changes.  One knob
- * is a measurement aid and not safe in general: "F32_P3_REUSE_PLANES" = 1 makes the repacking fp32 kernel
- * skip its packing pass and use whatever planes the workspace holds, which is right only directly after a
- * call with the same operands and workspace.  glowmi_tuning_reset() returns every knob to "the planner's
- * own choice" (it does not re-read the environment).  Not thread-safe against concurrent launches that
- * should see a consistent setting.  GLOWMI_ERR_UNSUPPORTED for an unknown name.
+ * "F32_SMALLC_BF16" = 0 keep a layer on the fp32 matrix cores); only the choice of kernel changes.
+ * glowmi_tuning_reset() returns every knob to "the planner's own choice" (it does not re-read the
+ * environment).  Not thread-safe against concurrent launches that should see a consistent setting.
+ * GLOWMI_ERR_UNSUPPORTED for an unknown name.
  */
 glowmi_status glowmi_tuning_set(const char* name, int32_t value);
 void glowmi_tuning_reset(void);

@@ -17,7 +17,7 @@ namespace glowmi {
 // library is first used and can be changed afterwards only through glowmi_tuning_set(): nothing on the
 // dispatch path calls getenv.  kKnobUnset means "the planner's own choice".
 enum Knob {
-  KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_P3, KNOB_F32_P3_MIN_M, KNOB_F32_P3_RATIO, KNOB_F32_P3_BN, KNOB_F32_P3_REUSE_PLANES, KNOB_F32_K3C64, KNOB_F32_K3C64_MIN_TILES, KNOB_F32_K3, KNOB_F32_K3_ANY, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_PW_BF16, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
+  KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_P3, KNOB_F32_P3_MIN_M, KNOB_F32_P3_RATIO, KNOB_F32_P3_BN, KNOB_F32_K3C64, KNOB_F32_K3C64_MIN_TILES, KNOB_F32_K3, KNOB_F32_K3_ANY, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_PW_BF16, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
   KNOB_F32_SMALL_SPLIT_MAX_TILES, KNOB_F32_SMALL_MIN_WGS, KNOB_F32_FC_SMALL_OFF, KNOB_F32_FC_SMALL_VW, KNOB_F32_FC_SMALL_MAX_KB, KNOB_F32_FC_SMALL_MIN_M, KNOB_SMALLC_TH, KNOB_F32_SMALLC_BF16,
   KNOB_I8_TILE, KNOB_I8_WIDE_SPLIT, KNOB_I8_WIDE_NBUF, KNOB_SMALLC_I8_WGS, KNOB_I8_PW_MIN_ITEMS,
   KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER,

@@ -500,21 +500,16 @@ hipError_t launch_p3_f32(const Problem& p_in, const Plan& plan, hipStream_t stre
   p.wp_offset = (uint32_t)align_up(3 * x_elems * 2);
   unsigned short* xp = static_cast<unsigned short*>(const_cast<void*>(p.planes));
   unsigned short* wp = reinterpret_cast<unsigned short*>(reinterpret_cast<unsigned char*>(xp) + p.wp_offset);
-  // ---- cut both operands into planes (measurement aid: with the knob set the planes that the previous call with
-  // the same operands and workspace left behind are used again, so that the contraction can be timed alone)
-  const bool repack = knob_or(KNOB_F32_P3_REUSE_PLANES, 0) == 0;
-  hipError_t e = hipSuccess;
-  if (repack) {
-    e = launch_pack3_rows(static_cast<const float*>(p.x), xp, (long long)x_elems, stream);
-    if (e != hipSuccess) return e;
-    if (p.b_is_kn) {
-      const int tk = (p.Kgemm + 63) / 64, tn = (p.k + 31) / 32;
-      hipLaunchKernelGGL(pack3_transposed_kernel, dim3((unsigned)(tk * tn)), dim3(256), 0, stream,
-                         static_cast<const float*>(p.w), wp, p.Kgemm, p.k, tn);
-      e = hipGetLastError();
-    } else {
-      e = launch_pack3_rows(static_cast<const float*>(p.w), wp, (long long)w_elems, stream);
-    }
+  // ---- cut both operands into planes
+  hipError_t e = launch_pack3_rows(static_cast<const float*>(p.x), xp, (long long)x_elems, stream);
+  if (e != hipSuccess) return e;
+  if (p.b_is_kn) {
+    const int tk = (p.Kgemm + 63) / 64, tn = (p.k + 31) / 32;
+    hipLaunchKernelGGL(pack3_transposed_kernel, dim3((unsigned)(tk * tn)), dim3(256), 0, stream,
+                       static_cast<const float*>(p.w), wp, p.Kgemm, p.k, tn);
+    e = hipGetLastError();
+  } else {
+    e = launch_pack3_rows(static_cast<const float*>(p.w), wp, (long long)w_elems, stream);
   }
   if (e != hipSuccess) return e;
   // ---- the contraction
