@@ -375,8 +375,21 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
 
   if (!has_work) return;
   commit_chunk();
+  // With C = 64 the cut pixel fragments of a block stay in registers (48 per lane) and serve every channel group
+  // the wavefront computes for that block: only the first item of a block stages and cuts, the others neither
+  // touch the input nor the vector ALU for it.  (With C = 128 the 96 registers spill.)
+  constexpr bool CACHE = K == 64;
+  v8bf a_cache[CACHE ? G::KC : 1][2][3];
+  int cached_rb = -1;
+  const int rb_last = block_of(it_end - 1);
   auto process = [&](auto nb_tag, int rb, int ng, int hsel, bool more, int rb_next) {
     constexpr int NB = decltype(nb_tag)::value;
+    const bool fresh = !CACHE || rb != cached_rb;          // uniform
+    if (CACHE) {                                           // the next block whose first chunk must be staged
+      more = rb < rb_last;
+      rb_next = rb + 1;
+      cached_rb = rb;
+    }
     const unsigned item_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes +
                               (unsigned)(slice * G::BN + ng * 64 + hsel * 32 + l32) * 4u;
     float addv[NB][16];
@@ -399,13 +412,10 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
     for (int c = 0; c < G::KC; ++c) {
       // the chunk after this one: the next of this item, or the first of the next item (a reduction is at
       // least two chunks long, so the region never still holds chunk 0 when an item ends)
-      const bool stage_next = c + 1 < G::KC || more;
+      const bool stage_next = fresh && (c + 1 < G::KC || more);
       if (stage_next) fetch_chunk(c + 1 < G::KC ? rb : rb_next, c + 1 < G::KC ? c + 1 : 0);
 #pragma unroll
       for (int j = 0; j < PB_CHUNK / 16; ++j) {
-        // a lane holds reduction indices 16j + 8*lh .. + 7 of its pixel (input) / channel (filter)
-        const v4f a0 = *reinterpret_cast<const v4f*>(a_lane + 16 * j);
-        const v4f a1 = *reinterpret_cast<const v4f*>(a_lane + 16 * j + 4);
         v8bf b[3][NB];
 #pragma unroll
         for (int pc = 0; pc < 3; ++pc)
@@ -413,10 +423,25 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
           for (int nb = 0; nb < NB; ++nb)
             b[pc][nb] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(
                 wl + pc * G::PLANE + nb * 32 * G::PITCHB + (c * PB_CHUNK + 16 * j) * 2));
-        const float v[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
-        v4u ah, am, al;
-        split8(v, ah, am, al);
-        const v8bf a[3] = {__builtin_bit_cast(v8bf, ah), __builtin_bit_cast(v8bf, am), __builtin_bit_cast(v8bf, al)};
+        v8bf a[3];
+        if (fresh) {
+          // a lane holds reduction indices 16j + 8*lh .. + 7 of its pixel (input) / channel (filter)
+          const v4f a0 = *reinterpret_cast<const v4f*>(a_lane + 16 * j);
+          const v4f a1 = *reinterpret_cast<const v4f*>(a_lane + 16 * j + 4);
+          const float v[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+          v4u ah, am, al;
+          split8(v, ah, am, al);
+          a[0] = __builtin_bit_cast(v8bf, ah);
+          a[1] = __builtin_bit_cast(v8bf, am);
+          a[2] = __builtin_bit_cast(v8bf, al);
+          if (CACHE) {
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc) a_cache[c][j][pc] = a[pc];
+          }
+        } else {
+#pragma unroll
+          for (int pc = 0; pc < 3; ++pc) a[pc] = a_cache[CACHE ? c : 0][j][pc];
+        }
 #pragma unroll
         for (int t = 0; t < 6; ++t)
 #pragma unroll
@@ -524,11 +549,11 @@ hipError_t launch_pw_k(const Problem& p, hipStream_t stream) {
 
 hipError_t launch_pw_f32(const Problem& p, hipStream_t stream, const char** variant) {
   const bool contiguous = p.stride_h == 1 && p.stride_w == 1;
-  // Measured at batch 32: 64 -> 256 on 56 x 56 44 -> 39 us, 256 -> 64 50 -> 47 us, 128 -> 512 + add on 28 x 28
-  // 47 -> 38 us, 256 -> 1024 + add on 14 x 14 44 -> 35 us; but 64 -> 256 + add 52 -> 56 us: that one moves
-  // 232 MB for 3.3 GFLOP and is bound by memory on either matrix core, so it keeps the leaner fp32 loop.
-  // The knob forces one form or the other (tests, comparisons).
-  const bool bf16 = knob_or(KNOB_F32_PW_BF16, (p.c == 64 && p.addend) ? 0 : 1) != 0;
+  // Measured at batch 32 (fp32 matrix cores -> here): 64 -> 256 on 56 x 56 44 -> 33 us, 256 -> 64 50 -> 44 us,
+  // 64 -> 256 + add 52 -> 50 us (that one moves 232 MB for 3.3 GFLOP and is bound by memory on either matrix
+  // core), 128 -> 512 + add on 28 x 28 47 -> 39 us, 256 -> 1024 + add on 14 x 14 44 -> 37 us.  The knob selects
+  // the fp32 matrix-core form (tests, comparisons).
+  const bool bf16 = knob_or(KNOB_F32_PW_BF16, 1) != 0;
   static thread_local char name[48];
   snprintf(name, sizeof(name), "conv_pw_f32_c%d%s%s%s", p.c, bf16 ? "_bf16x6" : "", contiguous ? "" : "_strided",
            p.addend ? "_add" : "");
