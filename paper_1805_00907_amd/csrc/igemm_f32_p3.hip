@@ -56,10 +56,10 @@ constexpr size_t kPlaneAlign = 256;
 // Packing: fp32 -> three bf16 planes
 // ------------------------------------------------------------------------------------------------
 // src: count8 groups of 8 consecutive floats; dst: three planes of plane_elems bf16 each, same order.
-__global__ __launch_bounds__(256) void pack3_rows_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
-                                                         long long count8, long long plane_elems) {
-  const long long stride = (long long)gridDim.x * 256;
-  for (long long g = (long long)blockIdx.x * 256 + threadIdx.x; g < count8; g += stride) {
+__device__ __forceinline__ void pack3_rows(const float* __restrict__ src, unsigned short* __restrict__ dst,
+                                           long long count8, long long plane_elems, int block, int blocks) {
+  const long long stride = (long long)blocks * 256;
+  for (long long g = (long long)block * 256 + threadIdx.x; g < count8; g += stride) {
     const v4f a = *reinterpret_cast<const v4f*>(src + 8 * g);
     const v4f b = *reinterpret_cast<const v4f*>(src + 8 * g + 4);
     const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
@@ -73,10 +73,9 @@ __global__ __launch_bounds__(256) void pack3_rows_kernel(const float* __restrict
 
 // FullyConnected weight [K][N] (N contiguous) -> three planes [N][K] (K contiguous).  K % 8 == 0.
 // One workgroup per 64 (k) x 32 (n) tile, transposed through LDS.
-__global__ __launch_bounds__(256) void pack3_transposed_kernel(const float* __restrict__ w, unsigned short* __restrict__ dst,
-                                                               int K, int N, int tiles_n) {
-  __shared__ float tile[64][33];
-  const int tk = blockIdx.x / tiles_n, tn = blockIdx.x - tk * tiles_n;
+__device__ __forceinline__ void pack3_transposed(const float* __restrict__ w, unsigned short* __restrict__ dst, int K, int N,
+                                                 int tiles_n, int block, float (&tile)[64][33]) {
+  const int tk = block / tiles_n, tn = block - tk * tiles_n;
   const int k0 = tk * 64, n0 = tn * 32;
   const int tid = threadIdx.x;
   {
@@ -100,6 +99,25 @@ __global__ __launch_bounds__(256) void pack3_transposed_kernel(const float* __re
   *reinterpret_cast<v4u*>(o) = h;
   *reinterpret_cast<v4u*>(o + plane) = m;
   *reinterpret_cast<v4u*>(o + 2 * plane) = l;
+}
+
+__global__ __launch_bounds__(256) void pack3_rows_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
+                                                         long long count8, long long plane_elems) {
+  pack3_rows(src, dst, count8, plane_elems, (int)blockIdx.x, (int)gridDim.x);
+}
+
+// Both operands of one contraction in one launch: the first blocks_x workgroups cut the input, the rest the
+// weights, either in their own order or (FullyConnected, transposed != 0) one 64 x 32 tile per workgroup.
+__global__ __launch_bounds__(256) void pack3_pair_kernel(const float* __restrict__ x, unsigned short* __restrict__ xp,
+                                                         long long x_count8, long long x_elems, int blocks_x,
+                                                         const float* __restrict__ w, unsigned short* __restrict__ wp,
+                                                         long long w_count8, long long w_elems, int transposed, int K,
+                                                         int N, int tiles_n) {
+  __shared__ float tile[64][33];
+  const int b = (int)blockIdx.x;
+  if (b < blocks_x) pack3_rows(x, xp, x_count8, x_elems, b, blocks_x);
+  else if (transposed) pack3_transposed(w, wp, K, N, tiles_n, b - blocks_x, tile);
+  else pack3_rows(w, wp, w_count8, w_elems, b - blocks_x, (int)gridDim.x - blocks_x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -500,17 +518,27 @@ hipError_t launch_p3_f32(const Problem& p_in, const Plan& plan, hipStream_t stre
   p.wp_offset = (uint32_t)align_up(3 * x_elems * 2);
   unsigned short* xp = static_cast<unsigned short*>(const_cast<void*>(p.planes));
   unsigned short* wp = reinterpret_cast<unsigned short*>(reinterpret_cast<unsigned char*>(xp) + p.wp_offset);
-  // ---- cut both operands into planes
-  hipError_t e = launch_pack3_rows(static_cast<const float*>(p.x), xp, (long long)x_elems, stream);
-  if (e != hipSuccess) return e;
-  if (p.b_is_kn) {
-    const int tk = (p.Kgemm + 63) / 64, tn = (p.k + 31) / 32;
-    hipLaunchKernelGGL(pack3_transposed_kernel, dim3((unsigned)(tk * tn)), dim3(256), 0, stream,
-                       static_cast<const float*>(p.w), wp, p.Kgemm, p.k, tn);
-    e = hipGetLastError();
-  } else {
-    e = launch_pack3_rows(static_cast<const float*>(p.w), wp, (long long)w_elems, stream);
+  // ---- cut both operands into planes, one launch
+  {
+    const long long xc8 = (long long)(x_elems / 8), wc8 = (long long)(w_elems / 8);
+    long long bx = (xc8 + 255) / 256;
+    if (bx > 8192) bx = 8192;
+    if (bx < 1) bx = 1;
+    long long bw;
+    int tn = 0;
+    if (p.b_is_kn) {
+      tn = (p.k + 31) / 32;
+      bw = (long long)((p.Kgemm + 63) / 64) * tn;
+    } else {
+      bw = (wc8 + 255) / 256;
+      if (bw > 4096) bw = 4096;
+      if (bw < 1) bw = 1;
+    }
+    hipLaunchKernelGGL(pack3_pair_kernel, dim3((unsigned)(bx + bw)), dim3(256), 0, stream, static_cast<const float*>(p.x), xp,
+                       xc8, (long long)x_elems, (int)bx, static_cast<const float*>(p.w), wp, wc8, (long long)w_elems,
+                       p.b_is_kn, p.Kgemm, p.k, tn);
   }
+  hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   // ---- the contraction
   const bool padded = p.pad_t != 0 || p.pad_l != 0 || (p.oh - 1) * p.stride_h - p.pad_t + p.r > p.h ||
