@@ -200,6 +200,50 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
                                    size_t workspace_bytes, hipStream_t stream);
 
 /*
+ * Filters transformed ahead of time.  Section 5.3 (the filter-layout figure and the three kinds of
+ * convolution): the weights of a layer are constants, so the compiler changes their memory layout once, at
+ * compile time, into the form the selected convolution reads.  The form here is the one every fp32 kernel on
+ * the bf16 matrix cores reads: each weight cut exactly into three bf16 pieces (see "Results" above), kept as
+ * three planes of bf16, a convolution filter in its own [k][r][s][c/groups] order, a FullyConnected weight
+ * transposed to [N][K].  glowmi_conv2d / glowmi_fc make these planes inside every call (in the workspace);
+ * a caller that keeps the weights fixed makes them once and hands them to the *_packed entry points, which
+ * are otherwise the same calls with the same results bit for bit.
+ *   glowmi_conv2d_filter_planes_bytes / glowmi_fc_filter_planes_bytes
+ *       bytes of the planes (6 per weight, rounded up to 256), or 0 when the shape has no plane form
+ *       (c/groups, or K of a FullyConnected layer, not a multiple of 8; more than 2^28 weights; bad descriptor).
+ *   glowmi_conv2d_pack_filter / glowmi_fc_pack_filter
+ *       write the planes of `w` to `planes` (device, 16-byte aligned, planes_bytes >= the figure above;
+ *       GLOWMI_ERR_UNSUPPORTED when that figure is 0, GLOWMI_ERR_SHAPE when planes_bytes is too small).
+ *       Asynchronous on `stream`; `w` is not written.
+ *   glowmi_conv2d_packed / glowmi_fc_packed
+ *       glowmi_conv2d_chain / glowmi_fc with `w_planes` = the planes made from this very `w` for this very
+ *       descriptor (or K, N); the library cannot check that and results are undefined otherwise.  `w` itself
+ *       is still required: layers that take a kernel which does not read planes use it, and ignore w_planes.
+ *       w_planes = NULL makes the call the plain one.  chain of glowmi_conv2d_packed must not be NULL.
+ *       GLOWMI_ERR_ALIGN for w_planes not 16-byte aligned, GLOWMI_ERR_UNSUPPORTED for w_planes != NULL on a
+ *       shape without a plane form.
+ *   glowmi_conv2d_packed_workspace_bytes / glowmi_fc_packed_workspace_bytes
+ *       the workspace of a *_packed call with w_planes != NULL.  On the same kernel it is the plain call's
+ *       minus the weights' planes (a 3x3 layer on the tile kernels needs none at all); a layer that only pays
+ *       for the bf16 kernels once its weights need no cutting (a FullyConnected of a few hundred rows) takes
+ *       them here and not in the plain call, and then asks for room for the input's planes.
+ */
+size_t glowmi_conv2d_filter_planes_bytes(const glowmi_conv_desc* d);
+glowmi_status glowmi_conv2d_pack_filter(const float* w, const glowmi_conv_desc* d, void* planes,
+                                        size_t planes_bytes, hipStream_t stream);
+size_t glowmi_conv2d_packed_workspace_bytes(const glowmi_conv_desc* d);
+glowmi_status glowmi_conv2d_packed(const float* x, const float* w, const void* w_planes, const float* bias,
+                                   float* y, const glowmi_conv_desc* d, const glowmi_chain* chain,
+                                   void* workspace, size_t workspace_bytes, hipStream_t stream);
+size_t glowmi_fc_filter_planes_bytes(int32_t K, int32_t N);
+glowmi_status glowmi_fc_pack_filter(const float* w, int32_t K, int32_t N, void* planes, size_t planes_bytes,
+                                    hipStream_t stream);
+size_t glowmi_fc_packed_workspace_bytes(int32_t M, int32_t K, int32_t N);
+glowmi_status glowmi_fc_packed(const float* a, const float* w, const void* w_planes, const float* bias,
+                               float* y, int32_t M, int32_t K, int32_t N, glowmi_act act, void* workspace,
+                               size_t workspace_bytes, hipStream_t stream);
+
+/*
  * General element-wise chains.  Section 5.2: whenever data-parallel operators follow one another they
  * are stacked and executed in one pass over the data, whatever they are; the fixed chain above is the
  * most common instance.  Here the caller gives the run of operators that follows the contraction as a

@@ -83,6 +83,17 @@ def library() -> ctypes.CDLL:
     L.glowmi_fc_workspace_bytes.argtypes = [i32, i32, i32]
     L.glowmi_fc_workspace_bytes.restype = sz
     L.glowmi_fc_noalloc.argtypes = [vp, vp, vp, vp, i32, i32, i32, ctypes.c_int, vp]
+    L.glowmi_conv2d_filter_planes_bytes.argtypes = [dp]
+    L.glowmi_conv2d_filter_planes_bytes.restype = sz
+    L.glowmi_conv2d_pack_filter.argtypes = [vp, dp, vp, sz, vp]
+    L.glowmi_conv2d_packed_workspace_bytes.argtypes = [dp]
+    L.glowmi_conv2d_packed_workspace_bytes.restype = sz
+    L.glowmi_fc_filter_planes_bytes.argtypes = [i32, i32]
+    L.glowmi_fc_filter_planes_bytes.restype = sz
+    L.glowmi_fc_pack_filter.argtypes = [vp, i32, i32, vp, sz, vp]
+    L.glowmi_fc_packed_workspace_bytes.argtypes = [i32, i32, i32]
+    L.glowmi_fc_packed_workspace_bytes.restype = sz
+    L.glowmi_fc_packed.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, ctypes.c_int, vp, sz, vp]
     L.glowmi_fc_noalloc_max_scratch_bytes.argtypes = []
     L.glowmi_fc_noalloc_max_scratch_bytes.restype = sz
     L.glowmi_tuning_set.argtypes = [ctypes.c_char_p, i32]
@@ -97,6 +108,7 @@ def library() -> ctypes.CDLL:
     cp = ctypes.POINTER(Chain)
     L.glowmi_conv2d_chain.argtypes = [vp, vp, vp, vp, dp, cp, vp, sz, vp]
     L.glowmi_qconv2d_chain.argtypes = [vp, QParam, vp, QParam, vp, vp, QParam, dp, cp, vp, sz, vp]
+    L.glowmi_conv2d_packed.argtypes = [vp, vp, vp, vp, vp, dp, cp, vp, sz, vp]
     op = ctypes.POINTER(ChainOp)
     L.glowmi_conv2d_chainv.argtypes = [vp, vp, vp, vp, dp, op, i32, vp, sz, vp]
     L.glowmi_conv2d_chainv_workspace_bytes.argtypes = [dp, op, i32]
@@ -252,6 +264,70 @@ def conv2d_chain(x, w, bias, y, desc: ConvDesc, addend=None, act: int = ACT_NONE
     _check(library().glowmi_conv2d_chain(_ptr(x, "float32", nx, "x"), _ptr(w, "float32", nw, "w"),
                                          _ptr(bias, "float32", desc.k, "bias"), _ptr(y, "float32", ny, "y"),
                                          ctypes.byref(desc), ctypes.byref(chain), wp, wb, _stream(stream)))
+
+
+def _planes(planes, need: int) -> Tuple[Optional[int], int]:
+    """Address and size of a plane buffer (any element type); it must hold `need` bytes when that is known."""
+    if planes is None:
+        return None, 0
+    if not planes.is_cuda or not planes.is_contiguous():
+        raise ValueError("planes: expected a contiguous device tensor")
+    have = planes.numel() * planes.element_size()
+    if need and have < need:
+        raise ValueError(f"planes: {have} bytes, the filter's planes take {need}")
+    return planes.data_ptr(), have
+
+
+def conv2d_filter_planes_bytes(desc: ConvDesc) -> int:
+    return int(library().glowmi_conv2d_filter_planes_bytes(ctypes.byref(desc)))
+
+
+def conv2d_pack_filter(w, desc: ConvDesc, planes, stream=None) -> None:
+    """Writes the bf16 planes of the filter `w` (made once, ahead of the calls that use them) to `planes`."""
+    _, nw, _ = _conv_counts(desc)
+    pp, pb = _planes(planes, 0)
+    _check(library().glowmi_conv2d_pack_filter(_ptr(w, "float32", nw, "w"), ctypes.byref(desc), pp, pb,
+                                               _stream(stream)))
+
+
+def conv2d_packed_workspace_bytes(desc: ConvDesc) -> int:
+    return int(library().glowmi_conv2d_packed_workspace_bytes(ctypes.byref(desc)))
+
+
+def conv2d_packed(x, w, w_planes, bias, y, desc: ConvDesc, addend=None, act: int = ACT_NONE, workspace=None,
+                  stream=None) -> None:
+    """conv2d_chain with the filter's planes from conv2d_pack_filter (None: the plain call)."""
+    wp, wb = _ws(workspace)
+    nx, nw, ny = _conv_counts(desc)
+    pp, _ = _planes(w_planes, conv2d_filter_planes_bytes(desc))
+    chain = Chain(_ptr(addend, "float32", ny, "addend"), QParam(1.0, 0), act)
+    _check(library().glowmi_conv2d_packed(_ptr(x, "float32", nx, "x"), _ptr(w, "float32", nw, "w"), pp,
+                                          _ptr(bias, "float32", desc.k, "bias"), _ptr(y, "float32", ny, "y"),
+                                          ctypes.byref(desc), ctypes.byref(chain), wp, wb, _stream(stream)))
+
+
+def fc_filter_planes_bytes(K: int, N: int) -> int:
+    return int(library().glowmi_fc_filter_planes_bytes(K, N))
+
+
+def fc_pack_filter(w, K: int, N: int, planes, stream=None) -> None:
+    """Writes the bf16 planes of the [K][N] weight `w` (transposed to [N][K]) to `planes`."""
+    pp, pb = _planes(planes, 0)
+    _check(library().glowmi_fc_pack_filter(_ptr(w, "float32", K * N, "w"), K, N, pp, pb, _stream(stream)))
+
+
+def fc_packed_workspace_bytes(M: int, K: int, N: int) -> int:
+    return int(library().glowmi_fc_packed_workspace_bytes(M, K, N))
+
+
+def fc_packed(a, w, w_planes, bias, y, M: int, K: int, N: int, act: int = ACT_NONE, workspace=None,
+              stream=None) -> None:
+    """fc with the weight's planes from fc_pack_filter (None: the plain call)."""
+    wp, wb = _ws(workspace)
+    pp, _ = _planes(w_planes, fc_filter_planes_bytes(K, N))
+    _check(library().glowmi_fc_packed(_ptr(a, "float32", M * K, "a"), _ptr(w, "float32", K * N, "w"), pp,
+                                      _ptr(bias, "float32", N, "bias"), _ptr(y, "float32", M * N, "y"), M, K, N,
+                                      act, wp, wb, _stream(stream)))
 
 
 def qconv2d_chain(x, xq: QParam, w, wq: QParam, bias, y, yq: QParam, desc: ConvDesc, addend=None,

@@ -272,6 +272,39 @@ glowmi::Plan plan_with_workspace(glowmi::Problem& p, PlanFn plan_fn, void* works
   return plan;
 }
 
+// Bytes of the bf16 planes of a layer's weights, 0 when the shape has no plane form: the kernels that read
+// planes fetch 8 consecutive reduction indices of one output channel at a time and address a plane with 29 bits.
+constexpr long long kMaxPlaneElems = 1LL << 28;
+size_t conv_planes_bytes(const glowmi_conv_desc* d, const Geometry& geo) {
+  if ((d->c / d->groups) % 8 != 0 || geo.w_elems > kMaxPlaneElems) return 0;
+  return glowmi::filter_planes_bytes((size_t)geo.w_elems);
+}
+size_t fc_planes_bytes(int32_t K, int32_t N) {
+  if (K % 8 != 0 || (long long)K * N > kMaxPlaneElems) return 0;
+  return glowmi::filter_planes_bytes((size_t)K * (size_t)N);
+}
+
+// The planes argument of the *_packed entry points: NULL, or aligned planes of a shape that has a plane form.
+glowmi_status check_w_planes(const void* w_planes, size_t planes_bytes) {
+  if (!w_planes) return GLOWMI_OK;
+  if (planes_bytes == 0)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "this shape has no plane form of its weights: pass w_planes = NULL");
+  if (!aligned(w_planes, 16)) return fail(GLOWMI_ERR_ALIGN, "w_planes must be 16-byte aligned");
+  return GLOWMI_OK;
+}
+
+glowmi_status check_pack_args(const float* w, void* planes, size_t planes_bytes, size_t need) {
+  if (!w || !planes) return fail(GLOWMI_ERR_NULL, "weight and plane pointers must not be NULL");
+  if (!aligned(w, 16) || !aligned(planes, 16))
+    return fail(GLOWMI_ERR_ALIGN, "weight and plane pointers must be 16-byte aligned");
+  if (need == 0)
+    return fail(GLOWMI_ERR_UNSUPPORTED, "this shape has no plane form of its weights (reduction extent per "
+                "output channel not a multiple of 8, or more than 2^28 weights)");
+  if (planes_bytes < need)
+    return fail(GLOWMI_ERR_SHAPE, "planes_bytes %zu is less than the %zu the planes take", planes_bytes, need);
+  return GLOWMI_OK;
+}
+
 glowmi_status setup_fc_f32(const float* a, const float* w, const float* bias, float* y, int32_t M, int32_t K,
                            int32_t N, glowmi_act act, glowmi::Problem& p) {
   glowmi_status st = check_fc(M, K, N);
@@ -324,7 +357,7 @@ namespace glowmi {
 
 glowmi_status prepare_conv2d_chain(const float* x, const float* w, const float* bias, float* y,
                                    const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
-                                   size_t workspace_bytes, PreparedCall* out) {
+                                   size_t workspace_bytes, PreparedCall* out, const void* w_planes) {
   if (!chain) return fail(GLOWMI_ERR_NULL, "chain must not be NULL");
   const glowmi_act act = chain->act;
   Geometry geo;
@@ -333,10 +366,12 @@ glowmi_status prepare_conv2d_chain(const float* x, const float* w, const float* 
   if ((st = check_ptrs(x, w, bias, y)) != GLOWMI_OK) return st;
   if ((st = check_act(act)) != GLOWMI_OK) return st;
   if ((st = check_addend(chain->addend, y, (size_t)geo.y_elems * 4u)) != GLOWMI_OK) return st;
+  if ((st = check_w_planes(w_planes, conv_planes_bytes(d, geo))) != GLOWMI_OK) return st;
   Problem& p = out->p;
   fill_conv(p, d, geo);
   if ((st = set_operand_bytes(p, geo.x_elems, geo.w_elems, 4)) != GLOWMI_OK) return st;
   p.x = x; p.w = w; p.bias = bias; p.y = y; p.act = (int)act;
+  p.w_packed = w_planes;
   p.addend = chain->addend;
   out->plan = plan_with_workspace(p, plan_f32, workspace, workspace_bytes);
   out->quantized = false;
@@ -440,9 +475,78 @@ size_t glowmi_fc_workspace_bytes(int32_t M, int32_t K, int32_t N) {
 glowmi_status glowmi_fc(const float* a, const float* w, const float* bias, float* y, int32_t M,
                         int32_t K, int32_t N, glowmi_act act, void* workspace,
                         size_t workspace_bytes, hipStream_t stream) {
+  return glowmi_fc_packed(a, w, nullptr, bias, y, M, K, N, act, workspace, workspace_bytes, stream);
+}
+
+// ---- filters transformed ahead of time ----------------------------------------------------------------
+// The planner only asks whether planes were given, so the workspace queries plan with a stand-in address.
+static const unsigned char kPlanesGiven = 0;
+
+size_t glowmi_conv2d_filter_planes_bytes(const glowmi_conv_desc* d) {
+  Geometry geo;
+  if (check_desc(d, &geo) != GLOWMI_OK) return 0;
+  return conv_planes_bytes(d, geo);
+}
+
+glowmi_status glowmi_conv2d_pack_filter(const float* w, const glowmi_conv_desc* d, void* planes,
+                                        size_t planes_bytes, hipStream_t stream) {
+  Geometry geo;
+  glowmi_status st = check_desc(d, &geo);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_pack_args(w, planes, planes_bytes, conv_planes_bytes(d, geo))) != GLOWMI_OK) return st;
+  return finish(glowmi::launch_pack_filter(w, planes, 0, 0, 0, geo.w_elems, stream), "pack_filter_rows");
+}
+
+size_t glowmi_conv2d_packed_workspace_bytes(const glowmi_conv_desc* d) {
+  Geometry geo;
+  if (check_desc(d, &geo) != GLOWMI_OK) return 0;
+  glowmi::Problem p;
+  fill_conv(p, d, geo);
+  if (set_operand_bytes(p, geo.x_elems, geo.w_elems, 4) != GLOWMI_OK) return 0;
+  if (conv_planes_bytes(d, geo) > 0) p.w_packed = &kPlanesGiven;
+  return split_bytes(glowmi::plan_f32(p, true), p);
+}
+
+glowmi_status glowmi_conv2d_packed(const float* x, const float* w, const void* w_planes, const float* bias,
+                                   float* y, const glowmi_conv_desc* d, const glowmi_chain* chain,
+                                   void* workspace, size_t workspace_bytes, hipStream_t stream) {
+  glowmi::PreparedCall call;
+  glowmi_status st =
+      glowmi::prepare_conv2d_chain(x, w, bias, y, d, chain, workspace, workspace_bytes, &call, w_planes);
+  if (st != GLOWMI_OK) return st;
+  return glowmi::run_prepared(call, stream);
+}
+
+size_t glowmi_fc_filter_planes_bytes(int32_t K, int32_t N) {
+  if (check_fc(1, K, N) != GLOWMI_OK) return 0;
+  return fc_planes_bytes(K, N);
+}
+
+glowmi_status glowmi_fc_pack_filter(const float* w, int32_t K, int32_t N, void* planes, size_t planes_bytes,
+                                    hipStream_t stream) {
+  glowmi_status st = check_fc(1, K, N);
+  if (st != GLOWMI_OK) return st;
+  if ((st = check_pack_args(w, planes, planes_bytes, fc_planes_bytes(K, N))) != GLOWMI_OK) return st;
+  return finish(glowmi::launch_pack_filter(w, planes, 1, K, N, (long long)K * N, stream), "pack_filter_transposed");
+}
+
+size_t glowmi_fc_packed_workspace_bytes(int32_t M, int32_t K, int32_t N) {
+  if (check_fc(M, K, N) != GLOWMI_OK) return 0;
+  glowmi::Problem p;
+  fill_fc(p, M, K, N);
+  if (set_operand_bytes(p, (long long)M * K, (long long)K * N, 4) != GLOWMI_OK) return 0;
+  if (fc_planes_bytes(K, N) > 0) p.w_packed = &kPlanesGiven;
+  return split_bytes(glowmi::plan_f32(p, true), p);
+}
+
+glowmi_status glowmi_fc_packed(const float* a, const float* w, const void* w_planes, const float* bias,
+                               float* y, int32_t M, int32_t K, int32_t N, glowmi_act act, void* workspace,
+                               size_t workspace_bytes, hipStream_t stream) {
   glowmi::Problem p;
   glowmi_status st = setup_fc_f32(a, w, bias, y, M, K, N, act, p);
   if (st != GLOWMI_OK) return st;
+  if ((st = check_w_planes(w_planes, fc_planes_bytes(K, N))) != GLOWMI_OK) return st;
+  p.w_packed = w_planes;
   const glowmi::Plan plan = plan_with_workspace(p, glowmi::plan_f32, workspace, workspace_bytes);
   const char* variant = "";
   return finish(glowmi::launch_f32(p, plan, stream, &variant), variant);

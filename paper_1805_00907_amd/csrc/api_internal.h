@@ -18,10 +18,11 @@ struct PreparedCall {
 };
 
 // Validate the arguments of glowmi_conv2d_chain / glowmi_qconv2d_chain and plan the launch (tile,
-// split of the reduction given the workspace).  Nothing is launched.
+// split of the reduction given the workspace).  Nothing is launched.  w_planes: the filter's bf16 planes made
+// ahead of time (glowmi_conv2d_pack_filter), or null.
 glowmi_status prepare_conv2d_chain(const float* x, const float* w, const float* bias, float* y,
                                    const glowmi_conv_desc* d, const glowmi_chain* chain, void* workspace,
-                                   size_t workspace_bytes, PreparedCall* out);
+                                   size_t workspace_bytes, PreparedCall* out, const void* w_planes = nullptr);
 glowmi_status prepare_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8_t* w, glowmi_qparam wq,
                                     const int32_t* bias, int8_t* y, glowmi_qparam yq, const glowmi_conv_desc* d,
                                     const glowmi_chain* chain, void* workspace, size_t workspace_bytes,

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   const __amdgpu_buffer_rsrc_t rsrc_x =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X), 0, (int)p.x_bytes, 0x00020000);
   const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
-  const v4i rsrc_w = make_rsrc(p.planes, 3u * wpb);
+  const v4i rsrc_w = make_rsrc(p.w_planes, 3u * wpb);
   constexpr unsigned OOB = 0x80000000u;
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
@@ -313,11 +313,11 @@ bool k3_f32_applicable(const Problem& p) {
   return fill >= 0.75 && tiles >= 256;
 }
 
-size_t k3_f32_pack_bytes(const Problem& p) { return ((size_t)3 * (p.w_bytes >> 1) + 255) / 256 * 256; }
+size_t k3_f32_pack_bytes(const Problem& p) { return p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2); }
 
-hipError_t launch_k3_f32(const Problem& p, hipStream_t stream, const char** variant) {
-  if (!p.planes) return hipErrorInvalidValue;           // the ABI layer never plans this kernel without a workspace
-  hipError_t e = launch_pack3_rows(static_cast<const float*>(p.w), const_cast<void*>(p.planes), (long long)(p.w_bytes >> 2), stream);
+hipError_t launch_k3_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
+  Problem p = p_in;
+  hipError_t e = stage_filter_planes(p, p.planes, stream);
   if (e != hipSuccess) return e;
   if (k3_wide_tile(p)) {
     *variant = p.addend ? "conv_k3_f32_bf16x6_16x32x64_add" : "conv_k3_f32_bf16x6_16x32x64";

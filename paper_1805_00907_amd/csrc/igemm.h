@@ -77,7 +77,9 @@ struct Problem {
   const void* bias;   // [k] float or int32, may be null
   void* y;            // output [M][k]
   void* partial;      // split-K partial sums [split_k][M][k] (float or int32), null when split_k == 1
-  const void* planes; // fp32 three-piece form: the bf16 planes of the input, then (at wp_offset) of the weights; workspace
+  const void* planes; // fp32 three-piece form: workspace for the bf16 planes of the input, then of the weights
+  const void* w_packed; // the weights' planes as the caller made them ahead of time (glowmi_*_pack_filter), or null
+  const void* w_planes; // where the kernel reads the weights' planes: w_packed, or inside `planes` (set by the launcher)
   const void* addend; // tensor operand of the element-wise chain [M][k] (float or int8), may be null:
                       // added to the accumulator after the bias and before the activation
   int32_t n, h, w_, c;
@@ -94,7 +96,6 @@ struct Problem {
   int32_t act;              // 0 none, 1 relu
   int32_t b_is_kn;          // FC weight layout
   int32_t allow_pack;       // the caller's workspace may hold repacked operands (fp32 three-piece form)
-  uint32_t wp_offset;       // byte offset of the weight planes inside `planes`
   // quantized form only
   int32_t x_off, w_off, y_off;
   int32_t mant, shift;      // requantize multiplier
@@ -160,6 +161,14 @@ Plan plan_p3_f32(const Problem& p);
 hipError_t launch_p3_f32(const Problem& p, const Plan& plan, hipStream_t stream, const char** variant);
 // Cuts `elems` (a multiple of 8) fp32 values into three bf16 planes of `elems` each at dst (igemm_f32_p3.hip).
 hipError_t launch_pack3_rows(const float* src, void* dst, long long elems, hipStream_t stream);
+// The weights' planes, the form every bf16 six-product kernel reads them in: three planes of w_elems bf16 each,
+// convolution filters in their own [k][r][s][cg] order, FullyConnected weights transposed to [N][K].
+// filter_planes_bytes: bytes of that form (a multiple of 256).  launch_pack_filter: writes it (b_is_kn: transposed).
+// stage_filter_planes: sets p.w_planes to the planes the caller made ahead of time (p.w_packed) or cuts the filter
+// into `dst` now and points there.
+size_t filter_planes_bytes(size_t w_elems);
+hipError_t launch_pack_filter(const float* w, void* dst, int b_is_kn, int K, int N, long long w_elems, hipStream_t stream);
+hipError_t stage_filter_planes(Problem& p, const void* dst, hipStream_t stream);
 // fp32 3x3 stride-1 convolution over 64 input channels on many pixels, on the bf16 matrix cores (conv_k3c64_f32.hip).
 bool k3c64_f32_applicable(const Problem& p);
 size_t k3c64_f32_pack_bytes(const Problem& p);

@@ -106,6 +106,12 @@ __global__ __launch_bounds__(256) void pack3_rows_kernel(const float* __restrict
   pack3_rows(src, dst, count8, plane_elems, (int)blockIdx.x, (int)gridDim.x);
 }
 
+__global__ __launch_bounds__(256) void pack3_transposed_kernel(const float* __restrict__ w, unsigned short* __restrict__ dst,
+                                                               int K, int N, int tiles_n) {
+  __shared__ float tile[64][33];
+  pack3_transposed(w, dst, K, N, tiles_n, (int)blockIdx.x, tile);
+}
+
 // Both operands of one contraction in one launch: the first blocks_x workgroups cut the input, the rest the
 // weights, either in their own order or (FullyConnected, transposed != 0) one 64 x 32 tile per workgroup.
 __global__ __launch_bounds__(256) void pack3_pair_kernel(const float* __restrict__ x, unsigned short* __restrict__ xp,
@@ -165,7 +171,7 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
 
   const unsigned xpb = p.x_bytes >> 1, wpb = p.w_bytes >> 1;          // bytes of one bf16 plane
   const v4i rsrc_x = make_rsrc(p.planes, 3u * xpb);
-  const v4i rsrc_w = make_rsrc(static_cast<const unsigned char*>(p.planes) + p.wp_offset, 3u * wpb);
+  const v4i rsrc_w = make_rsrc(p.w_planes, 3u * wpb);
   constexpr unsigned OOB = 0x80000000u;   // planes are at most 512 MiB each: OOB + 2 planes neither wraps nor lands inside
 
   const int spt = (p.cg + PBK - 1) / PBK;               // slabs per filter tap
@@ -435,8 +441,29 @@ hipError_t launch_pack3_rows(const float* src, void* dst, long long elems, hipSt
   return hipGetLastError();
 }
 
+size_t filter_planes_bytes(size_t w_elems) { return align_up(6 * w_elems); }
+
+hipError_t launch_pack_filter(const float* w, void* dst, int b_is_kn, int K, int N, long long w_elems, hipStream_t stream) {
+  if (!b_is_kn) return launch_pack3_rows(w, dst, w_elems, stream);
+  const int tn = (N + 31) / 32;
+  const long long blocks = (long long)((K + 63) / 64) * tn;
+  hipLaunchKernelGGL(pack3_transposed_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, static_cast<unsigned short*>(dst), K, N, tn);
+  return hipGetLastError();
+}
+
+hipError_t stage_filter_planes(Problem& p, const void* dst, hipStream_t stream) {
+  if (p.w_packed) {
+    p.w_planes = p.w_packed;
+    return hipSuccess;
+  }
+  if (!dst) return hipErrorInvalidValue;                // the ABI layer never plans these kernels without a workspace
+  p.w_planes = dst;
+  return launch_pack_filter(static_cast<const float*>(p.w), const_cast<void*>(dst), p.b_is_kn, p.Kgemm, p.k,
+                            (long long)(p.w_bytes >> 2), stream);
+}
+
 size_t p3_pack_bytes(const Problem& p) {
-  return align_up(3 * (size_t)(p.x_bytes >> 1)) + align_up(3 * (size_t)(p.w_bytes >> 1));
+  return align_up(3 * (size_t)(p.x_bytes >> 1)) + (p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2));
 }
 
 // Worth it when the contraction is large against the one-off cost of cutting both operands (about ten bytes
@@ -459,7 +486,7 @@ bool p3_f32_applicable(const Problem& p) {
   const double flops = 2.0 * p.M * (double)p.kg * p.groups * p.Kgemm;
   // three launches (two packing kernels and the contraction) are worth ~15 us before any work is done
   if (min_m > 1 && flops < 2e9) return false;
-  const double elems = (double)(p.x_bytes >> 2) + (double)(p.w_bytes >> 2);
+  const double elems = (double)(p.x_bytes >> 2) + (p.w_packed ? 0.0 : (double)(p.w_bytes >> 2));   // what this call cuts
   return flops >= (double)knob_or(KNOB_F32_P3_RATIO, 600) * elems;
 }
 
@@ -509,17 +536,22 @@ Plan plan_p3_f32(const Problem& p) {
 }
 
 hipError_t launch_p3_f32(const Problem& p_in, const Plan& plan, hipStream_t stream, const char** variant) {
-  if (!p_in.planes) return hipErrorInvalidValue;        // the ABI layer never plans this kernel without a workspace
+  if (!p_in.planes) return hipErrorInvalidValue;        // the ABI layer never plans this kernel without a workspace (the input's planes)
   if (plan.split_k > 1 && !p_in.partial) return hipErrorInvalidValue;
   Problem p = p_in;
   p.split_k = plan.split_k;
   p.slabs_per_split = plan.slabs_per_split;
   const size_t x_elems = p.x_bytes >> 2, w_elems = p.w_bytes >> 2;
-  p.wp_offset = (uint32_t)align_up(3 * x_elems * 2);
   unsigned short* xp = static_cast<unsigned short*>(const_cast<void*>(p.planes));
-  unsigned short* wp = reinterpret_cast<unsigned short*>(reinterpret_cast<unsigned char*>(xp) + p.wp_offset);
-  // ---- cut both operands into planes, one launch
-  {
+  unsigned short* wp = reinterpret_cast<unsigned short*>(reinterpret_cast<unsigned char*>(xp) + align_up(3 * x_elems * 2));
+  if (p.w_packed) {
+    // ---- the weights' planes were made ahead of time: only the input is cut
+    p.w_planes = p.w_packed;
+    const hipError_t e = launch_pack3_rows(static_cast<const float*>(p.x), xp, (long long)x_elems, stream);
+    if (e != hipSuccess) return e;
+  } else {
+    // ---- cut both operands into planes, one launch
+    p.w_planes = wp;
     const long long xc8 = (long long)(x_elems / 8), wc8 = (long long)(w_elems / 8);
     long long bx = (xc8 + 255) / 256;
     if (bx > 8192) bx = 8192;

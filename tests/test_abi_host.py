@@ -353,6 +353,47 @@ def test_workspace_queries_are_pure():
     assert glowmi.fc_workspace_bytes(128, 4096, 4096) < 6 * (128 * 4096 + 4096 * 4096)
 
 
+def test_packed_filter_queries_and_errors():
+    """Filters transformed ahead of time: sizes, and every refusal happens before a launch."""
+    up = lambda v: (v + 255) // 256 * 256
+    vgg2 = glowmi.ConvDesc(16, 112, 112, 128, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1)
+    assert glowmi.conv2d_filter_planes_bytes(vgg2) == up(6 * 128 * 3 * 3 * 128)
+    assert glowmi.conv2d_packed_workspace_bytes(vgg2) == 0            # the tile kernel needs nothing else
+    big = glowmi.ConvDesc(32, 7, 7, 512, 512, 3, 3, 1, 1, 1, 1, 1, 1, 1)
+    planes = glowmi.conv2d_filter_planes_bytes(big)
+    assert planes == up(6 * 512 * 3 * 3 * 512)
+    assert glowmi.conv2d_packed_workspace_bytes(big) == glowmi.conv2d_workspace_bytes(big) - planes
+    first = glowmi.ConvDesc(1, 224, 224, 3, 64, 7, 7, 2, 2, 3, 3, 3, 3, 1)       # 3 channels: no plane form
+    assert glowmi.conv2d_filter_planes_bytes(first) == 0
+    assert glowmi.conv2d_packed_workspace_bytes(first) == glowmi.conv2d_workspace_bytes(first)
+    assert glowmi.conv2d_filter_planes_bytes(glowmi.ConvDesc(1, 4, 4, 8, 8, 5, 5, 1, 1, 0, 0, 0, 0, 1)) == 0   # bad desc
+    assert glowmi.fc_filter_planes_bytes(4096, 1000) == up(6 * 4096 * 1000)
+    assert glowmi.fc_filter_planes_bytes(4100, 4096) == 0             # K not a multiple of 8
+    assert glowmi.fc_filter_planes_bytes(0, 8) == 0
+    # with the weights' planes given, a FullyConnected of 256 rows is worth the bf16 kernel: room for the input's planes
+    assert glowmi.fc_packed_workspace_bytes(256, 4096, 4096) >= up(6 * 256 * 4096)
+    assert glowmi.fc_packed_workspace_bytes(1024, 9216, 4096) == \
+        glowmi.fc_workspace_bytes(1024, 9216, 4096) - glowmi.fc_filter_planes_bytes(9216, 4096)
+    lib = glowmi.library()
+    import ctypes
+    chain = glowmi.Chain(None, glowmi.QParam(1.0, 0), 0)
+    args = lambda d, planes_ptr, w=FAKE: (FAKE, w, planes_ptr, None, FAKE, ctypes.byref(d), ctypes.byref(chain), None, 0, 0)
+    assert lib.glowmi_conv2d_packed(*args(first, FAKE)) == 3          # planes for a shape without a plane form
+    assert "plane form" in lib.glowmi_last_error().decode()
+    assert lib.glowmi_conv2d_packed(*args(vgg2, FAKE + 8)) == 4       # misaligned planes
+    assert lib.glowmi_conv2d_packed(*args(vgg2, FAKE, FAKE + 4)) == 4  # the usual checks still apply
+    assert lib.glowmi_conv2d_packed(FAKE, FAKE, FAKE, None, FAKE, ctypes.byref(vgg2), None, None, 0, 0) == 1   # chain NULL
+    assert lib.glowmi_fc_packed(FAKE, FAKE, FAKE, None, FAKE, 64, 4100, 64, 0, None, 0, 0) == 3
+    assert lib.glowmi_fc_packed(FAKE, FAKE, FAKE + 2, None, FAKE, 64, 4096, 64, 0, None, 0, 0) == 4
+    assert lib.glowmi_conv2d_pack_filter(FAKE, ctypes.byref(first), FAKE, 1 << 20, 0) == 3
+    assert lib.glowmi_conv2d_pack_filter(FAKE, ctypes.byref(vgg2), FAKE, up(6 * 128 * 9 * 128) - 1, 0) == 2   # buffer too small
+    assert lib.glowmi_conv2d_pack_filter(None, ctypes.byref(vgg2), FAKE, 1 << 30, 0) == 1
+    assert lib.glowmi_conv2d_pack_filter(FAKE, ctypes.byref(vgg2), FAKE + 4, 1 << 30, 0) == 4
+    assert lib.glowmi_fc_pack_filter(FAKE, 4100, 64, FAKE, 1 << 30, 0) == 3
+    assert lib.glowmi_fc_pack_filter(FAKE, 4096, 64, FAKE, 100, 0) == 2
+    assert lib.glowmi_fc_pack_filter(FAKE, 0, 64, FAKE, 100, 0) == 2
+
+
 def test_product_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_1805_00907_amd")
     for dirpath, _, files in os.walk(pkg):
