@@ -306,6 +306,10 @@ bool k3_f32_applicable(const Problem& p) {
   const long long tiles = (long long)p.n * ty * tx * tc;
   if (tiles >= (1LL << 30)) return false;
   if (knob_or(KNOB_F32_K3_ANY, 0) != 0) return true;    // tests: any size
+  // more than 64 output channels: the kernel whose tile shape follows the map; worth it when most of what the
+  // machine multiplies is real output (a 14 x 14 map at batch 16 gives 64 tiles for 256 CUs and stays on the
+  // generic three-piece kernel)
+  if (!k3_wide_tile(p) && knob_or(KNOB_F32_K3V, 1) != 0) return k3v_f32_efficiency(p) >= 0.6;
   // the tiles must be mostly full (a 28 x 28 or 56 x 56 map fills 77 % of its 16 x 16 blocks, which still beats the
   // generic kernel: 512 -> 512 on 28 x 28 at batch 16 is 256 tiles = one round here, 361 -> 329 us; a 14 x 14 map at
   // batch 16 has only 64 tiles, 105 -> 252 us, and stays there), and there must be a tile for every CU
@@ -319,6 +323,7 @@ hipError_t launch_k3_f32(const Problem& p_in, hipStream_t stream, const char** v
   Problem p = p_in;
   hipError_t e = stage_filter_planes(p, p.planes, stream);
   if (e != hipSuccess) return e;
+  if (!k3_wide_tile(p) && knob_or(KNOB_F32_K3V, 1) != 0 && !k3v_f32_prefers_fixed_tile(p)) return launch_k3v_f32(p, stream, variant);
   if (k3_wide_tile(p)) {
     *variant = p.addend ? "conv_k3_f32_bf16x6_16x32x64_add" : "conv_k3_f32_bf16x6_16x32x64";
     return p.addend ? launch_k3g_variant<true, 32, 64>(p, stream) : launch_k3g_variant<false, 32, 64>(p, stream);

@@ -1,0 +1,395 @@
+// fp32 3x3 Convolution (stride 1) with 64 or more input channels and more than 64 output channels -- the body of a
+// VGG stack -- on the bf16 matrix cores with every operand cut exactly into three bf16 pieces and six piece
+// products per fp32 product (bf16_pieces.h), with a pixel tile whose SHAPE IS CHOSEN PER LAYER.  The arithmetic is
+// the loop nest of Section 3.1 of the paper with the bias add and Relu stacked onto it (Section 5.2); Section 5.3
+// gives every kind of convolution a tile size of its own, chosen from what the hardware holds.
+//
+// Why the shape matters.  A workgroup multiplies a block of output pixels x 128 output channels and runs alone on
+// its CU, so a layer costs (tiles per CU, rounded up) x (time of a tile).  A fixed 16 x 16 block wastes a quarter
+// of the machine on the maps of such a stack: 28 x 28 and 56 x 56 fill 77 % of their 16 x 16 blocks, and the
+// 784 blocks of 16 images of 112 x 112 are 3.06 rounds on 256 CUs, i.e. four.  Here a tile is th x tw pixels with
+// th * tw <= 32 * NB, NB = 5..8 MFMA row blocks of 32 pixels, and the time of a tile is proportional to NB: 7 x 28
+// pixels (NB = 7) cover a 28 x 28 map exactly in 256 tiles of 7/8 the work, 8 x 28 a 56 x 56 map, 14 x 16 a
+// 112 x 112 map in 3.5 rounds of 7/8 tiles.  The host picks the shape that minimises rounds x NB.
+//
+// What makes NB free to choose: the tile's NB pixel blocks x 4 channel columns of 32 are dealt to the eight
+// wavefronts as four squares of 2 x 2 blocks over pixel blocks 0-3 (wavefronts 0-3) and four strips of
+// (NB - 4) x 1 blocks over the rest (wavefronts 4-7, one channel column each).  Wavefronts w and w + 4 share a SIMD,
+// so every SIMD carries NB block products per 16 reduction indices whatever NB is, although its two wavefronts
+// carry unequal parts.  No partial tiles to exchange; per 16 reduction indices the squares read 4 x 3 fragments
+// for 24 MFMAs and the strips (NB - 3) x 3 for (NB - 4) x 6.
+//
+// Otherwise as the fixed-tile kernel (conv_k3_f32.hip): the input is walked in chunks of 32 channels whose
+// (th + 2) x (tw + 2) patch is read ONCE from the fp32 input, cut in registers and kept in LDS as three bf16
+// planes, all nine taps reading their fragments from it at shifted addresses; the filter's planes (cut once per
+// call, or ahead of time by the caller) are streamed slab by slab into a ring of two LDS buffers; workgroups are
+// persistent and fetch the next patch into registers while the current chunk is multiplied.
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <type_traits>
+
+#include "bf16_pieces.h"
+#include "igemm.h"
+#include "lds_direct.h"
+
+namespace glowmi {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+constexpr int V_CH = 32;                       // input channels per chunk = reduction indices per slab
+constexpr int V_PIXB = 2 * V_CH;               // bytes of a pixel's chunk in one plane
+constexpr int V_BROW = 2 * V_CH;               // bytes of a filter row piece in one plane
+constexpr int V_BN = 128;                      // output channels per tile
+constexpr int V_THREADS = 512;
+constexpr int V_MAXPX = 352;                   // largest patch (th + 2) * (tw + 2)
+constexpr int V_MAXTW = 64;
+constexpr int V_APLANE = V_MAXPX * V_PIXB;
+constexpr int V_BPLANE = V_BN * V_BROW;
+constexpr int V_BBUF = 3 * V_BPLANE;           // one slab: a tap x 32 channels x 128 output channels x 3 planes
+constexpr int V_STAGE = 3 * V_APLANE + 2 * V_BBUF;
+constexpr int V_PASSES = (V_MAXPX * (V_CH / 8) + V_THREADS - 1) / V_THREADS;
+constexpr int V_PREF = 2 * V_PASSES;           // prefetch loads per thread
+constexpr int V_LPW = 3 * V_BN / 16 / 8;       // filter loads per wavefront and slab (16 rows each)
+static_assert(V_LPW * 8 * 16 == 3 * V_BN, "filter loads divide over the wavefronts");
+
+static_assert(V_STAGE <= 160 * 1024, "LDS of one CU");
+
+template <bool ADD, int NB>
+__global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Problem p, int th, int tw, int tiles_y,
+                                                                   int tiles_x, int tiles_c, int total) {
+  extern __shared__ __align__(16) unsigned char lds[];
+  unsigned char* bring = lds + 3 * V_APLANE;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int lrow = lane & 31, lhalf = lane >> 5;
+
+  const float* __restrict__ X = static_cast<const float*>(p.x);
+  const __amdgpu_buffer_rsrc_t rsrc_x =
+      __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X), 0, (int)p.x_bytes, 0x00020000);
+  const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
+  const v4i rsrc_w = make_rsrc(p.w_planes, 3u * wpb);
+  constexpr unsigned OOB = 0x80000000u;
+  constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
+
+  const int pw = tw + 2;
+  const int patch_px = (th + 2) * pw;
+  const int tile_px = th * tw;
+  const float inv_tw = 1.0f / (float)tw, inv_pw = 1.0f / (float)pw;
+  // n / d for the small non-negative n of this kernel (below 512, d <= 66): (n + 0.5) / d is at least 0.5 / d away
+  // from every integer, far more than the rounding of the reciprocal and the product
+  auto div_small = [](int n, float inv) { return (int)(((float)n + 0.5f) * inv); };
+
+  const int chunks = p.c / V_CH;                        // p.c % 32 == 0 on this kernel
+  const int slabs = 9 * chunks;
+
+  // ---- tile decode: channel tile fastest (workgroups that share a patch run side by side), then x, y, image
+  auto decode = [&](int t, int& img, int& ty, int& tx, int& ct) {
+    ct = t % tiles_c;
+    t /= tiles_c;
+    tx = t % tiles_x;
+    t /= tiles_x;
+    ty = t % tiles_y;
+    img = t / tiles_y;
+  };
+
+  // ---- patch chunk: item q = tid + 512 * pass is (pixel q / 4 of the patch, channels 8 * (q % 4) .. of the chunk);
+  // the pixel's place in the patch is the same for every tile, so it is taken apart once
+  int pyx[V_PASSES];
+#pragma unroll
+  for (int q = 0; q < V_PASSES; ++q) {
+    const int pp = (tid + q * V_THREADS) >> 2;
+    const int py = div_small(pp, inv_pw);
+    pyx[q] = pp < patch_px ? (py << 16) | (pp - py * pw) : -1;
+  }
+  v4f pre[V_PASSES][2];
+  auto fetch_patch = [&](int t, int chunk) {
+    int img, ty, tx, ct;
+    decode(t, img, ty, tx, ct);
+#pragma unroll
+    for (int q = 0; q < V_PASSES; ++q) {
+      const int c8 = (tid + q * V_THREADS) & 3;
+      const int iy = ty * th - p.pad_t + (pyx[q] >> 16), ix = tx * tw - p.pad_l + (pyx[q] & 0xffff);
+      const bool ok = pyx[q] >= 0 && (unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w_;
+      const unsigned off =
+          ok ? ((unsigned)((img * p.h + iy) * p.w_ + ix) * (unsigned)p.c + (unsigned)(chunk * V_CH + c8 * 8)) * 4u : OOBX;
+      pre[q][0] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0));
+      pre[q][1] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off == OOBX ? OOBX : off + 16u, 0, 0));
+    }
+  };
+  auto commit_patch = [&]() {
+#pragma unroll
+    for (int q = 0; q < V_PASSES; ++q) {
+      if (pyx[q] >= 0) {
+        const int item = tid + q * V_THREADS;
+        const int pp = item >> 2, c8 = item & 3;
+        const float v[8] = {pre[q][0][0], pre[q][0][1], pre[q][0][2], pre[q][0][3],
+                            pre[q][1][0], pre[q][1][1], pre[q][1][2], pre[q][1][3]};
+        v4u h, m, l;
+        split8(v, h, m, l);
+        unsigned char* dst = lds + pp * V_PIXB + ((c8 ^ ((pp >> 2) & 3)) << 4);
+        *reinterpret_cast<v4u*>(dst) = h;
+        *reinterpret_cast<v4u*>(dst + V_APLANE) = m;
+        *reinterpret_cast<v4u*>(dst + 2 * V_APLANE) = l;
+      }
+    }
+  };
+
+  // ---- filter slab loads: 3 planes x 8 groups of 16 rows per slab; wavefront w loads row group w of every plane.
+  // Lane l: row l / 4 of the group, chunk position l % 4 holding chunk (l % 4) ^ ((row / 4) % 4) of the row.
+  const int bch = (lane & 3) ^ ((lane >> 4) & 3);
+  auto issue_b = [&](int ct, int slab, int buf) {
+    const int chunk = slab / 9, tap = slab - chunk * 9;
+    const unsigned lbase = __builtin_amdgcn_readfirstlane(lds_offset_of(bring) + buf * V_BBUF + wave * 16 * V_BROW);
+    const unsigned k_off = (unsigned)(tap * p.c + chunk * V_CH + bch * 8);
+    const int n = ct * V_BN + wave * 16 + (lane >> 2);
+    const unsigned row_off = n < p.k ? 2u * ((unsigned)n * (unsigned)p.Kgemm + k_off) : OOB;
+#pragma unroll
+    for (int plane = 0; plane < V_LPW; ++plane)
+      load16_to_lds(rsrc_w, lbase + plane * V_BPLANE, row_off == OOB ? OOB : row_off + (unsigned)plane * wpb);
+  };
+
+  const int b_sw = (lrow >> 2) & 3;
+
+  float* __restrict__ Y = static_cast<float*>(p.y);
+  const float* __restrict__ bias = static_cast<const float*>(p.bias);
+  const float* addend = static_cast<const float*>(p.addend);   // may be the output itself
+  const bool relu = p.act == 1;
+
+  // Consecutive workgroup ids go round-robin to the 8 XCDs: give each XCD a contiguous run of tiles, so that the
+  // channel tiles that share a patch (consecutive tile numbers) fetch it through the same L2.
+  const int t_first = (gridDim.x & 7) == 0 ? (int)((blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
+  if (t_first >= total) return;
+
+  // ---- the persistent loop over tiles for a wavefront that owns PX pixel blocks from block px_first on and CH
+  // 32-channel columns from column ch_first on.  Both kinds of wavefront run the same sequence of barriers and
+  // loads; only the fragments read and multiplied differ.
+  auto run = [&](auto px_c, auto ch_c, int px_first, int ch_first) {
+    constexpr int PX = decltype(px_c)::value, CH = decltype(ch_c)::value;
+    // MFMA block i holds tile pixels 32 i .. 32 i + 31 in row-major order of the th x tw tile; lane lrow is the
+    // lrow-th of them (pixels past the tile read patch pixel 0 and are never stored)
+    int pp0[PX];
+#pragma unroll
+    for (int i = 0; i < PX; ++i) {
+      const int tp = 32 * (px_first + i) + lrow;
+      const int r = div_small(tp, inv_tw);
+      pp0[i] = tp < tile_px ? r * pw + (tp - r * tw) : 0;
+    }
+    const int b_row = (ch_first * 32 + lrow) * V_BROW;
+    int t = t_first;
+    fetch_patch(t, 0);
+    for (; t < total; t += gridDim.x) {
+      int img, ty, tx, ct;
+      decode(t, img, ty, tx, ct);
+      const int t_next = t + gridDim.x;
+      __syncthreads();                                  // everyone is done with the previous tile's last slab buffer
+      issue_b(ct, 0, 0);
+
+      v16f acc[PX][CH];
+#pragma unroll
+      for (int i = 0; i < PX; ++i)
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+      int s = 0;
+      for (int chunk = 0; chunk < chunks; ++chunk) {
+        // ---- the chunk's patch: everyone is done with the previous one, write it, publish it (the barrier of the
+        // first trip below), and start fetching the next: the next chunk of this tile or chunk 0 of the next tile
+        __syncthreads();
+        commit_patch();
+        const bool fetching = chunk + 1 < chunks || t_next < total;     // uniform
+        if (chunk + 1 < chunks) fetch_patch(t, chunk + 1);
+        else if (t_next < total) fetch_patch(t_next, 0);
+        // ---- nine taps.  Trip: slab s has landed (the prefetch issued after it may still be in flight on the first
+        // trip of a chunk), barrier, refill the other buffer with slab s + 1, multiply slab s.
+        int tap_off = 0, ts = 0;
+#pragma unroll 1
+        for (int tap = 0; tap < 9; ++tap, ++s) {
+          if (tap == 0 && fetching) __builtin_amdgcn_s_waitcnt(vmcnt_imm(V_PREF));
+          else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+          __syncthreads();
+          if (s + 1 < slabs) issue_b(ct, s + 1, (s + 1) & 1);
+          const unsigned char* bb = bring + (s & 1) * V_BBUF + b_row;
+          int ab[PX];
+#pragma unroll
+          for (int i = 0; i < PX; ++i) ab[i] = pp0[i] + tap_off;
+#pragma unroll
+          for (int k16 = 0; k16 < 2; ++k16) {
+            const int c8 = k16 * 2 + lhalf;                            // this lane's 16-byte chunk of the pixel / filter row
+            v8bf a[3][PX], b[3][CH];
+            constexpr int ORDER_A[3] = {2, 0, 1}, ORDER_B[3] = {0, 2, 1};   // the order the MFMAs use them in
+#pragma unroll
+            for (int o = 0; o < 3; ++o) {
+              const int pa = ORDER_A[o], pb = ORDER_B[o];
+#pragma unroll
+              for (int i = 0; i < PX; ++i)
+                a[pa][i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(
+                                                        lds + pa * V_APLANE + ab[i] * V_PIXB + ((c8 ^ ((ab[i] >> 2) & 3)) << 4)));
+#pragma unroll
+              for (int j = 0; j < CH; ++j)
+                b[pb][j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(bb + pb * V_BPLANE + j * 32 * V_BROW + ((c8 ^ b_sw) << 4)));
+            }
+#pragma unroll
+            for (int tt = 0; tt < 6; ++tt)
+#pragma unroll
+              for (int i = 0; i < PX; ++i)
+#pragma unroll
+                for (int j = 0; j < CH; ++j)
+                  acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[tt]][i], b[kPieceTermB[tt]][j], acc[i][j], 0, 0, 0);
+          }
+          if (++ts == 3) { ts = 0; tap_off += pw - 2; } else tap_off += 1;   // next tap: one column on, or down a patch row
+        }
+      }
+
+      // ---- epilogue.  Register e of a lane is pixel (e/4)*8 + 4*lhalf + e%4 of the 32-pixel block; channel = lrow
+      // of the 32-channel column.
+      int lh4 = lhalf * 4;
+      asm volatile("" : "+v"(lh4));      // keeps the pixel arithmetic below inside the tile loop (hoisted, it is spilled)
+#pragma unroll
+      for (int j = 0; j < CH; ++j) {
+        const int ch = ct * V_BN + (ch_first + j) * 32 + lrow;
+        const bool cok = ch < p.k;
+        const float bv = (cok && bias) ? bias[ch] : 0.f;
+#pragma unroll
+        for (int i = 0; i < PX; ++i) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            int tp = 32 * (px_first + i) + q * 8 + lh4;
+            int r = div_small(tp, inv_tw);
+            int c = tp - r * tw;
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+              const int oy = ty * th + r, ox = tx * tw + c;
+              if (cok && tp < tile_px && oy < p.oh && ox < p.ow) {
+                const size_t o = ((size_t)(img * p.oh + oy) * p.ow + ox) * p.k + ch;
+                float v = acc[i][j][4 * q + e4] + bv;
+                if (ADD) v += addend[o];
+                if (relu) v = fmaxf(v, 0.f);
+                Y[o] = v;
+              }
+              ++tp;
+              if (++c == tw) { c = 0; ++r; }
+            }
+          }
+        }
+      }
+    }
+  };
+  // Wavefronts 0-3: 2 x 2 blocks each over pixel blocks 0-3 (pixel pair w / 2, channel pair w % 2).
+  // Wavefronts 4-7: the remaining NB - 4 pixel blocks of channel column w - 4.
+  if (wave < 4) run(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{}, 2 * (wave >> 1), 2 * (wave & 1));
+  else run(std::integral_constant<int, NB - 4>{}, std::integral_constant<int, 1>{}, 4, wave - 4);
+}
+
+struct TileShape {
+  int th, tw, nb;
+};
+
+bool shape_ok(int th, int tw) {
+  return th >= 1 && tw >= 1 && tw <= V_MAXTW && th * tw <= 256 && (th + 2) * (tw + 2) <= V_MAXPX;
+}
+
+long long tiles_of(const Problem& p, const TileShape& s) {
+  return (long long)p.n * ((p.oh + s.th - 1) / s.th) * ((p.ow + s.tw - 1) / s.tw) * ((p.k + V_BN - 1) / V_BN);
+}
+
+// The tile shape of a layer: among all th x tw with 5 to 8 pixel blocks, the one with the least
+// (rounds of tiles over the CUs) x (blocks per tile + the fixed part of a tile, about a third of a block);
+// ties go to the shape that wastes fewer pixels, then the smaller patch, then the wider tile.
+TileShape pick_tile(const Problem& p, int num_cu) {
+  const int force_th = knob_or(KNOB_F32_K3_TH, 0), force_tw = knob_or(KNOB_F32_K3_TW, 0);
+  if (force_th > 0 && force_tw > 0 && shape_ok(force_th, force_tw)) {       // tests and experiments
+    const int nb = (force_th * force_tw + 31) / 32;
+    return TileShape{force_th, force_tw, nb < 5 ? 5 : nb};
+  }
+  TileShape best{16, 16, 8};
+  double best_cost = 1e300, best_fill = 0.0;
+  int best_patch = 0;
+  for (int tw = 4; tw <= V_MAXTW; ++tw) {
+    for (int th = 1; th * tw <= 256; ++th) {
+      if (!shape_ok(th, tw) || th * tw <= 128) continue;
+      const TileShape s{th, tw, (th * tw + 31) / 32};
+      const long long tiles = tiles_of(p, s);
+      const long long rounds = (tiles + num_cu - 1) / num_cu;
+      const double cost = (double)rounds * (s.nb + 0.3);
+      const double fill = (double)p.oh * p.ow /
+                          ((double)((p.oh + th - 1) / th) * th * (double)((p.ow + tw - 1) / tw) * tw) * (th * tw) / (32.0 * s.nb);
+      const int patch = (th + 2) * (tw + 2);
+      const bool better = cost < best_cost - 1e-9 ||
+                          (cost < best_cost + 1e-9 &&
+                           (fill > best_fill + 1e-9 ||
+                            (fill > best_fill - 1e-9 && (patch < best_patch || (patch == best_patch && tw > best.tw)))));
+      if (better) {
+        best = s;
+        best_cost = cost;
+        best_fill = fill;
+        best_patch = patch;
+      }
+    }
+  }
+  return best;
+}
+
+template <bool ADD, int NB>
+hipError_t launch_k3v_variant(const Problem& p, const TileShape& s, int num_cu, hipStream_t stream) {
+  auto kern = conv_k3v_f32_kernel<ADD, NB>;
+  static const hipError_t attr_status = hipFuncSetAttribute(
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, V_STAGE);
+  if (attr_status != hipSuccess) return attr_status;
+  const int tiles_y = (p.oh + s.th - 1) / s.th, tiles_x = (p.ow + s.tw - 1) / s.tw, tiles_c = (p.k + V_BN - 1) / V_BN;
+  const long long total = (long long)p.n * tiles_y * tiles_x * tiles_c;
+  const long long grid = total < num_cu ? total : num_cu;   // one persistent workgroup per CU
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(V_THREADS), V_STAGE, stream, p, s.th, s.tw, tiles_y, tiles_x, tiles_c,
+                     (int)total);
+  return hipGetLastError();
+}
+
+template <bool ADD>
+hipError_t launch_k3v_blocks(const Problem& p, const TileShape& s, int num_cu, hipStream_t stream) {
+  switch (s.nb) {
+    case 5: return launch_k3v_variant<ADD, 5>(p, s, num_cu, stream);
+    case 6: return launch_k3v_variant<ADD, 6>(p, s, num_cu, stream);
+    case 7: return launch_k3v_variant<ADD, 7>(p, s, num_cu, stream);
+    case 8: return launch_k3v_variant<ADD, 8>(p, s, num_cu, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+// Share of the machine's block products that are real outputs when this layer runs on the kernel:
+// outputs / (rounds x CUs x pixels and channels of a tile).
+double k3v_f32_efficiency(const Problem& p) {
+  const int num_cu = num_compute_units() > 0 ? num_compute_units() : 256;
+  const TileShape s = pick_tile(p, num_cu);
+  const long long tiles = tiles_of(p, s);
+  if (tiles >= (1LL << 30)) return 0.0;
+  const long long rounds = (tiles + num_cu - 1) / num_cu;
+  return (double)p.M * p.k / ((double)rounds * num_cu * 32.0 * s.nb * V_BN);
+}
+
+// The planner's own pick is the 16 x 16 tile: the fixed-tile kernel does that one with 2 x 2 blocks in every wavefront.
+bool k3v_f32_prefers_fixed_tile(const Problem& p) {
+  if (knob_or(KNOB_F32_K3_TH, 0) > 0 && knob_or(KNOB_F32_K3_TW, 0) > 0) return false;
+  const int num_cu = num_compute_units() > 0 ? num_compute_units() : 256;
+  const TileShape s = pick_tile(p, num_cu);
+  return s.th == 16 && s.tw == 16;
+}
+
+hipError_t launch_k3v_f32(const Problem& p, hipStream_t stream, const char** variant) {
+  const int num_cu = num_compute_units();
+  if (num_cu < 1) return hipErrorInvalidDevice;
+  const TileShape s = pick_tile(p, num_cu);
+  static thread_local char name[64];
+  snprintf(name, sizeof(name), "conv_k3_f32_bf16x6_%dx%d%s", s.th, s.tw, p.addend ? "_add" : "");
+  *variant = name;
+  return p.addend ? launch_k3v_blocks<true>(p, s, num_cu, stream) : launch_k3v_blocks<false>(p, s, num_cu, stream);
+}
+
+}  // namespace glowmi

@@ -17,7 +17,7 @@ namespace glowmi {
 // library is first used and can be changed afterwards only through glowmi_tuning_set(): nothing on the
 // dispatch path calls getenv.  kKnobUnset means "the planner's own choice".
 enum Knob {
-  KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_P3, KNOB_F32_P3_MIN_M, KNOB_F32_P3_RATIO, KNOB_F32_P3_BN, KNOB_F32_K3C64, KNOB_F32_K3C64_MIN_TILES, KNOB_F32_K3, KNOB_F32_K3_ANY, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_PW_BF16, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
+  KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_P3, KNOB_F32_P3_MIN_M, KNOB_F32_P3_RATIO, KNOB_F32_P3_BN, KNOB_F32_K3C64, KNOB_F32_K3C64_MIN_TILES, KNOB_F32_K3, KNOB_F32_K3_ANY, KNOB_F32_K3V, KNOB_F32_K3_TH, KNOB_F32_K3_TW, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_PW_BF16, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
   KNOB_F32_SMALL_SPLIT_MAX_TILES, KNOB_F32_SMALL_MIN_WGS, KNOB_F32_FC_SMALL_OFF, KNOB_F32_FC_SMALL_VW, KNOB_F32_FC_SMALL_MAX_KB, KNOB_F32_FC_SMALL_MIN_M, KNOB_SMALLC_TH, KNOB_F32_SMALLC_BF16,
   KNOB_I8_TILE, KNOB_I8_WIDE_SPLIT, KNOB_I8_WIDE_NBUF, KNOB_SMALLC_I8_WGS, KNOB_I8_PW_MIN_ITEMS,
   KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER,
@@ -177,6 +177,11 @@ hipError_t launch_k3c64_f32(const Problem& p, hipStream_t stream, const char** v
 bool k3_f32_applicable(const Problem& p);
 size_t k3_f32_pack_bytes(const Problem& p);
 hipError_t launch_k3_f32(const Problem& p, hipStream_t stream, const char** variant);
+// The same layers with more than 64 output channels on a pixel tile whose shape is chosen per layer (conv_k3v_f32.hip);
+// p.w_planes must be set.  k3v_f32_efficiency: share of the machine's block products that are real outputs there.
+double k3v_f32_efficiency(const Problem& p);
+bool k3v_f32_prefers_fixed_tile(const Problem& p);
+hipError_t launch_k3v_f32(const Problem& p, hipStream_t stream, const char** variant);
 // Finishing kernel of a split fp32 reduction (igemm_f32.hip): sums p.partial in split order, bias, addend, activation.
 hipError_t launch_splitk_finish_f32(const Problem& p, const Plan& plan, hipStream_t stream);
 bool pw_i8_applicable(const Problem& p);

@@ -2,9 +2,13 @@
 in 32-channel chunks whose patch is cut into three bf16 planes in LDS, six bf16 MFMAs per product) through the
 C ABI against the CPU oracle, element by element, at |gpu - oracle| <= 1e-5 + 1e-4 |oracle|: one, two (even)
 and three (odd) channel chunks, both tile shapes (16 x 16 pixels x 128 channels, 16 x 32 x 64), ragged pixel and channel tiles, every kind of padding, more tiles than CUs
-(persistent workgroups, patch prefetch across tiles), the tensor-add link, no bias.  The planner's shape
+(persistent workgroups, patch prefetch across tiles), the tensor-add link, no bias; for more than 64 output
+channels both the kernel whose pixel tile is shaped per layer (every count of pixel blocks, forced tile shapes) and
+the fixed 16 x 16 one.  The planner's shape
 conditions are lifted through a tuning knob so that small shapes reach the kernel.
 """
+import re
+
 import numpy as np
 import pytest
 
@@ -51,18 +55,55 @@ def _case(i):
     return x, wt, b, pd
 
 
+def _expected_variant(k, form, variant):
+    if k <= 64:
+        return variant == "conv_k3_f32_bf16x6_16x32x64"
+    if form == "fixed":
+        return variant == "conv_k3_f32_bf16x6"
+    # the tile shape picked for the layer; a pick of 16 x 16 goes to the fixed-tile kernel
+    return re.fullmatch(r"conv_k3_f32_bf16x6(_\d+x\d+)?", variant) is not None
+
+
 @pytest.mark.parametrize("i", range(len(SHAPES)))
-def test_conv_k3_f32(i, knobs):
+@pytest.mark.parametrize("form", ["shaped", "fixed"])
+def test_conv_k3_f32(i, form, knobs):
     G = _gpu()
     knobs.set("F32_K3_ANY", 1)
     knobs.set("F32_K3C64", 0)               # the 64-input-channel kernel would take the largest C = 64 case
+    knobs.set("F32_K3V", 1 if form == "shaped" else 0)
     x, wt, b, pd = _case(i)
     desc = G.make_desc(x.shape, wt.shape, (1, 1), pd, 1)
     for act, bias in ((wl.ACT_RELU, b), (wl.ACT_NONE, None)):
         ref = oracle.conv2d_f32(x, wt, bias, (1, 1), pd, 1, act=act)
         got, variant = G.gpu_conv2d_f32(x, wt, bias, desc, act)
-        assert variant == ("conv_k3_f32_bf16x6_16x32x64" if wt.shape[0] <= 64 else "conv_k3_f32_bf16x6"), variant
+        assert _expected_variant(wt.shape[0], form, variant), variant
         G.assert_close_f32(got, ref, f"case {i} act {act} [{variant}]")
+
+
+# th, tw: every count of pixel blocks (5 to 8), tiles that fill their last block and tiles that do not, the widest
+# and the narrowest, rows that wrap inside a 32-pixel block at every phase, a tile larger than the whole map
+TILE_SHAPES = [(16, 16), (7, 28), (8, 28), (14, 16), (4, 56), (9, 28), (5, 27), (6, 30), (3, 64), (13, 13), (2, 3),
+               (32, 8), (40, 40)]
+
+
+@pytest.mark.parametrize("shape", TILE_SHAPES, ids=lambda s: f"{s[0]}x{s[1]}")
+@pytest.mark.parametrize("i", [1, 3, 6, 7])
+def test_conv_k3_f32_every_tile_shape(i, shape, knobs):
+    G = _gpu()
+    knobs.set("F32_K3_ANY", 1)
+    knobs.set("F32_K3C64", 0)
+    th, tw = shape
+    knobs.set("F32_K3_TH", th)
+    knobs.set("F32_K3_TW", tw)
+    x, wt, b, pd = _case(i)
+    desc = G.make_desc(x.shape, wt.shape, (1, 1), pd, 1)
+    ref = oracle.conv2d_f32(x, wt, b, (1, 1), pd, 1, act=wl.ACT_RELU)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)
+    if (th, tw) == (40, 40):                # not a shape the kernel has (more than 256 pixels): the planner's own pick
+        assert re.fullmatch(r"conv_k3_f32_bf16x6(_\d+x\d+)?", variant), variant
+    else:
+        assert variant == f"conv_k3_f32_bf16x6_{th}x{tw}", variant
+    G.assert_close_f32(got, ref, f"case {i} tile {th}x{tw}")
 
 
 @pytest.mark.parametrize("i", [1, 2, 3, 11, 12])
