@@ -528,7 +528,8 @@ def run_workload(name, args, torch, glowmi, cpu_budget_s):
         # multiply-adds per algorithmic one, so their utilisation is products x frac
         roofline.update({"mfma_dtype": "bf16, fp32 accumulate", "products_per_mac": products,
                          "pipe_frac": round(products * achieved / peak, 4),
-                         "fp32_mfma_peak": PEAK_FP32_MFMA / 1e12})
+                         "fp32_mfma_peak": PEAK_FP32_MFMA / 1e12,
+                         "frac_of_fp32_mfma_peak": round(achieved * 1e12 / PEAK_FP32_MFMA, 4)})
     if "igemm_f32_p3" in dominant:
         # one call of this kernel's layer = two packing kernels (operands cut into bf16 planes) + the contraction;
         # the event pair brackets the call, so the packing is inside avg_launch_us (profiles/ has the kernels apart)
