@@ -44,7 +44,7 @@ constexpr int V_PIXB = 2 * V_CH;               // bytes of a pixel's chunk in on
 constexpr int V_BROW = 2 * V_CH;               // bytes of a filter row piece in one plane
 constexpr int V_BN = 128;                      // output channels per tile
 constexpr int V_THREADS = 512;
-constexpr int V_MAXPX = 352;                   // largest patch (th + 2) * (tw + 2)
+constexpr int V_MAXPX = 360;                   // largest patch (th + 2) * (tw + 4): rows are kept two pixels apart, see below
 constexpr int V_MAXTW = 64;
 constexpr int V_APLANE = V_MAXPX * V_PIXB;
 constexpr int V_BPLANE = V_BN * V_BROW;
@@ -76,7 +76,15 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
   constexpr unsigned OOB = 0x80000000u;
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
-  const int pw = tw + 2;
+  // Patch rows have a pitch of tw + 4 pixels (tw + 2 used), and a pixel's four 16-byte chunks are stored at
+  // chunk ^ ((y * tw + x) / 4 % 4) for patch row y, column x.  A fragment read takes 16 lanes at a time: 16
+  // consecutive pixels of the th x tw tile in row-major order, shifted by the tap, i.e. runs of consecutive
+  // pixels from consecutive patch rows.  LDS serves 16 such 16-byte reads per cycle when their addresses
+  // differ modulo 256 bytes; with this pitch and swizzle address / 16 modulo 16 is (y * tw + x) mod 16 (the
+  // pitch - tw = 4 pixels = 16 chunks drop out), which runs on without a break from one tile row to the next
+  // whatever tw is.  (With the natural pitch tw + 2 and a swizzle by the linear pixel index a 14-pixel row
+  // measured half the LDS read rate.)
+  const int pw = tw + 4;
   const int patch_px = (th + 2) * pw;
   const int tile_px = th * tw;
   const float inv_tw = 1.0f / (float)tw, inv_pw = 1.0f / (float)pw;
@@ -104,7 +112,7 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
   for (int q = 0; q < V_PASSES; ++q) {
     const int pp = (tid + q * V_THREADS) >> 2;
     const int py = div_small(pp, inv_pw);
-    pyx[q] = pp < patch_px ? (py << 16) | (pp - py * pw) : -1;
+    pyx[q] = (pp < patch_px && pp - py * pw < tw + 2) ? (py << 16) | (pp - py * pw) : -1;   // the pitch's last two columns stay empty
   }
   v4f pre[V_PASSES][2];
   auto fetch_patch = [&](int t, int chunk) {
@@ -131,7 +139,8 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
                             pre[q][1][0], pre[q][1][1], pre[q][1][2], pre[q][1][3]};
         v4u h, m, l;
         split8(v, h, m, l);
-        unsigned char* dst = lds + pp * V_PIXB + ((c8 ^ ((pp >> 2) & 3)) << 4);
+        const int key = (pyx[q] >> 16) * tw + (pyx[q] & 0xffff);
+        unsigned char* dst = lds + pp * V_PIXB + ((c8 ^ ((key >> 2) & 3)) << 4);
         *reinterpret_cast<v4u*>(dst) = h;
         *reinterpret_cast<v4u*>(dst + V_APLANE) = m;
         *reinterpret_cast<v4u*>(dst + 2 * V_APLANE) = l;
@@ -172,12 +181,13 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
     constexpr int PX = decltype(px_c)::value, CH = decltype(ch_c)::value;
     // MFMA block i holds tile pixels 32 i .. 32 i + 31 in row-major order of the th x tw tile; lane lrow is the
     // lrow-th of them (pixels past the tile read patch pixel 0 and are never stored)
-    int pp0[PX];
+    int pp0[PX], key0[PX];
 #pragma unroll
     for (int i = 0; i < PX; ++i) {
       const int tp = 32 * (px_first + i) + lrow;
       const int r = div_small(tp, inv_tw);
       pp0[i] = tp < tile_px ? r * pw + (tp - r * tw) : 0;
+      key0[i] = tp < tile_px ? tp : 0;                     // r * tw + column
     }
     const int b_row = (ch_first * 32 + lrow) * V_BROW;
     int t = t_first;
@@ -208,7 +218,7 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
         else if (t_next < total) fetch_patch(t_next, 0);
         // ---- nine taps.  Trip: slab s has landed (the prefetch issued after it may still be in flight on the first
         // trip of a chunk), barrier, refill the other buffer with slab s + 1, multiply slab s.
-        int tap_off = 0, ts = 0;
+        int tap_off = 0, tap_key = 0, ts = 0;
 #pragma unroll 1
         for (int tap = 0; tap < 9; ++tap, ++s) {
           if (tap == 0 && fetching) __builtin_amdgcn_s_waitcnt(vmcnt_imm(V_PREF));
@@ -216,9 +226,12 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
           __syncthreads();
           if (s + 1 < slabs) issue_b(ct, s + 1, (s + 1) & 1);
           const unsigned char* bb = bring + (s & 1) * V_BBUF + b_row;
-          int ab[PX];
+          int ab[PX], sw[PX];
 #pragma unroll
-          for (int i = 0; i < PX; ++i) ab[i] = pp0[i] + tap_off;
+          for (int i = 0; i < PX; ++i) {
+            ab[i] = (pp0[i] + tap_off) * V_PIXB;
+            sw[i] = ((key0[i] + tap_key) >> 2) & 3;
+          }
 #pragma unroll
           for (int k16 = 0; k16 < 2; ++k16) {
             const int c8 = k16 * 2 + lhalf;                            // this lane's 16-byte chunk of the pixel / filter row
@@ -230,7 +243,7 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
 #pragma unroll
               for (int i = 0; i < PX; ++i)
                 a[pa][i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(
-                                                        lds + pa * V_APLANE + ab[i] * V_PIXB + ((c8 ^ ((ab[i] >> 2) & 3)) << 4)));
+                                                        lds + pa * V_APLANE + ab[i] + ((c8 ^ sw[i]) << 4)));
 #pragma unroll
               for (int j = 0; j < CH; ++j)
                 b[pb][j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(bb + pb * V_BPLANE + j * 32 * V_BROW + ((c8 ^ b_sw) << 4)));
@@ -243,7 +256,14 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
                 for (int j = 0; j < CH; ++j)
                   acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[tt]][i], b[kPieceTermB[tt]][j], acc[i][j], 0, 0, 0);
           }
-          if (++ts == 3) { ts = 0; tap_off += pw - 2; } else tap_off += 1;   // next tap: one column on, or down a patch row
+          if (++ts == 3) {                                 // next tap: down a patch row, or one column on
+            ts = 0;
+            tap_off += pw - 2;
+            tap_key += tw - 2;
+          } else {
+            ++tap_off;
+            ++tap_key;
+          }
         }
       }
 
@@ -292,7 +312,7 @@ struct TileShape {
 };
 
 bool shape_ok(int th, int tw) {
-  return th >= 1 && tw >= 1 && tw <= V_MAXTW && th * tw <= 256 && (th + 2) * (tw + 2) <= V_MAXPX;
+  return th >= 1 && tw >= 1 && tw <= V_MAXTW && th * tw <= 256 && (th + 2) * (tw + 4) <= V_MAXPX;
 }
 
 long long tiles_of(const Problem& p, const TileShape& s) {
@@ -320,7 +340,7 @@ TileShape pick_tile(const Problem& p, int num_cu) {
       const double cost = (double)rounds * (s.nb + 0.3);
       const double fill = (double)p.oh * p.ow /
                           ((double)((p.oh + th - 1) / th) * th * (double)((p.ow + tw - 1) / tw) * tw) * (th * tw) / (32.0 * s.nb);
-      const int patch = (th + 2) * (tw + 2);
+      const int patch = (th + 2) * (tw + 4);
       const bool better = cost < best_cost - 1e-9 ||
                           (cost < best_cost + 1e-9 &&
                            (fill > best_fill + 1e-9 ||
