@@ -9,7 +9,7 @@
 //   - a workgroup owns a 16 x 16 block of output pixels x 128 output channels and walks the input channels in
 //     chunks of 32.  The chunk's 18 x 18 x 32 input patch is read from the fp32 input ONCE (coalesced 32-byte
 //     pieces, zeros outside the image from the range-checked loads), cut into pieces in registers and kept in
-//     LDS as three bf16 planes (61 KB); all nine taps read their MFMA fragments from it at shifted addresses.
+//     LDS as three bf16 planes (68 KB); all nine taps read their MFMA fragments from it at shifted addresses.
 //     No packing pass over the input, and a ninth of the input traffic;
 //   - the filter is cut once per call by the packing kernel into three planes in the workspace and streamed
 //     slab by slab (one tap x 32 channels x 128 output channels, 24 KB) straight into a ring of two LDS
@@ -19,8 +19,9 @@
 //     fragments per MFMA, no exchange of partial tiles;
 //   - workgroups are persistent; the next chunk's (or the next tile's first) patch is fetched into registers
 //     while the current chunk is multiplied, so only cutting and writing it is exposed;
-//   - a pixel's four 16-byte chunks are stored at chunk ^ ((pixel / 4) % 4), which spreads the 16 pixels one
-//     fragment-read phase touches over all bank groups.
+//   - patch rows are kept TW + 4 pixels apart and a pixel's four 16-byte chunks are stored at
+//     chunk ^ ((key / 4) % 4), key = TW * patch row + patch column, which spreads the tile rows a fragment read
+//     touches over all bank groups whatever the tap.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -49,7 +50,7 @@ constexpr int G_DUMMY = 1024;                  // landing area of the loads issu
 template <int TW, int BN>
 struct K3 {
   static_assert((TW == 16 && BN == 128) || (TW == 32 && BN == 64), "tile shapes");
-  static constexpr int PW = TW + 2;                          // patch width
+  static constexpr int PW = TW + 4;                          // patch row pitch in pixels: TW + 2 used (see the swizzle below)
   static constexpr int PATCH_PX = (GT + 2) * PW;
   static constexpr int APLANE = PATCH_PX * G_PIXB;
   static constexpr int BPLANE = BN * G_BROW;
@@ -112,7 +113,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
       const int pp = item >> 2, c8 = item & 3;
       const int py = pp / GP, px = pp - py * GP;
       const int iy = ty * GT - p.pad_t + py, ix = tx * TW - p.pad_l + px;
-      const bool ok = item < G_ITEMS && (unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w_;
+      const bool ok = item < G_ITEMS && px < TW + 2 && (unsigned)iy < (unsigned)p.h && (unsigned)ix < (unsigned)p.w_;
       const unsigned off =
           ok ? ((unsigned)((img * p.h + iy) * p.w_ + ix) * (unsigned)p.c + (unsigned)(chunk * G_CH + c8 * 8)) * 4u : OOBX;
       pre[q][0] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0));
@@ -129,7 +130,8 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
                             pre[q][1][0], pre[q][1][1], pre[q][1][2], pre[q][1][3]};
         v4u h, m, l;
         split8(v, h, m, l);
-        unsigned char* dst = lds + pp * G_PIXB + ((c8 ^ ((pp >> 2) & 3)) << 4);
+        const int key = pp - 4 * (pp / GP);               // TW * patch row + patch column
+        unsigned char* dst = lds + pp * G_PIXB + ((c8 ^ ((key >> 2) & 3)) << 4);
         *reinterpret_cast<v4u*>(dst) = h;
         *reinterpret_cast<v4u*>(dst + G_APLANE) = m;
         *reinterpret_cast<v4u*>(dst + 2 * G_APLANE) = l;
@@ -163,11 +165,18 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   // ---- fragment addresses.  Input: MFMA block i of this wavefront holds tile pixels 64wm + 32i .. + 31 in row-major
   // order (TW = 16: two rows of 16; TW = 32: one row); lane lrow is the lrow-th of them.  Filter: row = output
   // channel wn * 64 + j * 32 + lrow.
-  int pp0[2];
+  // Swizzle: a pixel's four 16-byte chunks sit at chunk ^ ((key / 4) % 4) with key = TW * patch row + patch column,
+  // the pixel's index at the TILE's pitch, and patch rows are TW + 4 pixels apart.  The 32 lanes of a fragment read
+  // are 32 consecutive tile pixels shifted by the tap, i.e. 32 consecutive keys, and address / 16 modulo 16 is then
+  // key modulo 16 (the pitch's extra 4 pixels = 16 chunks drop out): no two of 16 consecutive lanes share a bank
+  // group.  (At the natural pitch TW + 2 with the patch index as key the second tile row of a read falls on the
+  // first row's banks: measured half the LDS read rate.)
+  int pp0[2], key0[2];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int tp = 64 * wm + 32 * i + lrow;
     pp0[i] = (tp / TW) * GP + tp % TW;
+    key0[i] = tp;
   }
   const int b_row = (wn * 64 + lrow) * G_BROW;
   const int b_sw = (lrow >> 2) & 3;
@@ -217,9 +226,12 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
         issue_b(ct, s + 1, (s + 1) & 1);
         const int tr = tap / 3, ts = tap - tr * 3;                     // compile-time
         const unsigned char* bb = bring + (s & 1) * G_BBUF + b_row;
-        int a_base[2];
+        int a_base[2], a_key[2];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a_base[i] = pp0[i] + tr * GP + ts;
+        for (int i = 0; i < 2; ++i) {
+          a_base[i] = pp0[i] + tr * GP + ts;
+          a_key[i] = key0[i] + tr * TW + ts;
+        }
 #pragma unroll
         for (int k16 = 0; k16 < 2; ++k16) {
           const int c8 = k16 * 2 + lhalf;                              // this lane's 16-byte chunk of the pixel / filter row
@@ -227,7 +239,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
           constexpr int ORDER_A[3] = {2, 0, 1}, ORDER_B[3] = {0, 2, 1};   // the order the MFMAs use them in
           int a_off[2];
 #pragma unroll
-          for (int i = 0; i < 2; ++i) a_off[i] = a_base[i] * G_PIXB + ((c8 ^ ((a_base[i] >> 2) & 3)) << 4);
+          for (int i = 0; i < 2; ++i) a_off[i] = a_base[i] * G_PIXB + ((c8 ^ ((a_key[i] >> 2) & 3)) << 4);
           const int b_off = (c8 ^ b_sw) << 4;
 #pragma unroll
           for (int o = 0; o < 3; ++o) {

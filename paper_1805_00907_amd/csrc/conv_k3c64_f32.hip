@@ -19,8 +19,8 @@
 //     MFMA); partial tiles exchanged through LDS at the end;
 //   - workgroups are persistent: the next tile's patch is fetched into registers while the current tile is
 //     multiplied, so only cutting and writing it (about a tenth of a tile's MFMA time) is exposed;
-//   - a pixel's eight 16-byte chunks are stored at chunk ^ ((pixel / 2) % 8), which spreads the 16 pixels one
-//     fragment-read phase touches over all bank groups.
+//   - a pixel's eight 16-byte chunks are stored at chunk ^ ((key / 2) % 8), key = 16 * patch row + patch column,
+//     which spreads the two tile rows a fragment read touches over all bank groups whatever the tap.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
@@ -112,7 +112,9 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
                             pre[q][1][0], pre[q][1][1], pre[q][1][2], pre[q][1][3]};
         v4u h, m, l;
         split8(v, h, m, l);
-        unsigned char* dst = lds + pp * K_PIXB + ((c8 ^ ((pp >> 1) & 7)) << 4);
+        const int py = pp / KP;
+        const int key = pp - 2 * py;                     // py * 16 + px: the pixel's index at the tile's own pitch
+        unsigned char* dst = lds + pp * K_PIXB + ((c8 ^ ((key >> 1) & 7)) << 4);
         *reinterpret_cast<v4u*>(dst) = h;
         *reinterpret_cast<v4u*>(dst + K_APLANE) = m;
         *reinterpret_cast<v4u*>(dst + 2 * K_APLANE) = l;
@@ -143,9 +145,16 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
 
   // ---- fragment addresses.  Input: MFMA block i of this wavefront is tile rows 4wm + 2i, + 1 (16 pixels each);
   // lane lrow is pixel (lrow / 16, lrow % 16) of the block.  Filter: row = output channel j * 32 + lrow.
-  int pp0[2];
+  // The swizzle key is the pixel's index at the tile's own pitch (16), not at the patch's (18): the 32 lanes of a
+  // fragment read are two tile rows of 16, i.e. 32 consecutive keys whatever the tap, and their addresses then
+  // differ modulo 256 bytes within every 16 of them (keyed by the patch index, the second row's pixels fall on
+  // the first row's banks: measured half the LDS read rate).
+  int pp0[2], key0[2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) pp0[i] = (4 * wm + 2 * i + (lrow >> 4)) * KP + (lrow & 15);
+  for (int i = 0; i < 2; ++i) {
+    pp0[i] = (4 * wm + 2 * i + (lrow >> 4)) * KP + (lrow & 15);
+    key0[i] = (4 * wm + 2 * i) * KT + lrow;
+  }
   const int b_pos = ((kgrp * 2 + lhalf) ^ ((lrow >> 2) & 3)) << 4;
   const int frag_b = lrow * K_BROW + b_pos;
 
@@ -193,7 +202,8 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int pp = pp0[i] + tr * KP + ts;
-        a_off[i] = pp * K_PIXB + ((c8 ^ ((pp >> 1) & 7)) << 4);
+        const int key = key0[i] + tr * KT + ts;
+        a_off[i] = pp * K_PIXB + ((c8 ^ ((key >> 1) & 7)) << 4);
       }
 #pragma unroll
       for (int o = 0; o < 3; ++o) {
