@@ -267,3 +267,55 @@ def test_fc_packed_takes_the_bf16_kernel_where_the_plain_call_does_not():
     torch.cuda.synchronize()
     assert not glowmi.last_variant().startswith("igemm_f32_p3")
     G.assert_close_f32(y2.cpu().numpy(), ref, "packed fc without a workspace")
+
+
+@pytest.mark.parametrize("kind", ["three_piece_split", "tile_kernel"])
+def test_packed_calls_replay_from_a_hip_graph(kind, knobs):
+    """The packed calls launch only kernels (cutting the input, the contraction, the finishing kernel of a split
+    reduction): captured once, every replay - with the program's own eager work and synchronisation in between -
+    must reproduce the eager result bit for bit."""
+    import torch
+    import paper_1805_00907_amd as glowmi
+    G = _gpu()
+    if kind == "three_piece_split":
+        knobs.set("F32_P3_MIN_M", 1)
+        knobs.set("F32_P3_RATIO", 0)
+        knobs.set("F32_K3", 0)
+        knobs.set("F32_SPLIT", 3)
+        x, wt, b = _conv_inputs(36800, 2, 15, 15, 72, 136, 5, 5)
+        st, pd, prefix = 2, 2, "igemm_f32_p3"
+    else:
+        knobs.set("F32_K3_ANY", 1)
+        knobs.set("F32_K3C64", 0)
+        x, wt, b = _conv_inputs(36801, 2, 28, 28, 96, 160, 3, 3)
+        st, pd, prefix = 1, 1, "conv_k3_f32_bf16x6"
+    desc = G.make_desc(x.shape, wt.shape, (st, st), (pd, pd, pd, pd), 1)
+    ref = oracle.conv2d_f32(x, wt, b, (st, st), (pd, pd, pd, pd), 1, act=wl.ACT_RELU)
+    xd, wd, bd = G.dev(x), G.dev(wt), G.dev(b)
+    planes = torch.empty(glowmi.conv2d_filter_planes_bytes(desc), dtype=torch.uint8, device="cuda:0")
+    glowmi.conv2d_pack_filter(wd, desc, planes)
+    ws = G.workspace(glowmi.conv2d_packed_workspace_bytes(desc))
+    y = G.poison(ref.shape, torch.float32)
+    glowmi.conv2d_packed(xd, wd, planes, bd, y, desc, act=wl.ACT_RELU, workspace=ws)
+    torch.cuda.synchronize()
+    assert glowmi.last_variant().startswith(prefix), glowmi.last_variant()
+    eager = y.cpu().numpy()
+    G.assert_close_f32(eager, ref, f"eager [{glowmi.last_variant()}]")
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        glowmi.conv2d_packed(xd, wd, planes, bd, y, desc, act=wl.ACT_RELU, workspace=ws, stream=side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            glowmi.conv2d_packed(xd, wd, planes, bd, y, desc, act=wl.ACT_RELU, workspace=ws, stream=side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        y.fill_(float("nan"))
+        if ws is not None:
+            ws.fill_(0x5A)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y.cpu().numpy(), eager, err_msg=f"graph replay {rep}")
+        scratch = torch.empty(1 << 16, device="cuda:0").normal_()      # the program's own eager work
+        float(scratch.sum())
