@@ -328,6 +328,14 @@ TileShape pick_tile(const Problem& p, int num_cu) {
     const int nb = (force_th * force_tw + 31) / 32;
     return TileShape{force_th, force_tw, nb < 5 ? 5 : nb};
   }
+  // the search below looks at a few hundred shapes: a layer asks three times per call (planner, kernel choice,
+  // launch) and a caller issues the same layers again and again, so the last answer is kept per thread
+  struct Memo {
+    int n, oh, ow, k, num_cu;
+    TileShape shape;
+  };
+  static thread_local Memo memo = {0, 0, 0, 0, 0, {16, 16, 8}};
+  if (memo.n == p.n && memo.oh == p.oh && memo.ow == p.ow && memo.k == p.k && memo.num_cu == num_cu) return memo.shape;
   TileShape best{16, 16, 8};
   double best_cost = 1e300, best_fill = 0.0;
   int best_patch = 0;
@@ -353,6 +361,7 @@ TileShape pick_tile(const Problem& p, int num_cu) {
       }
     }
   }
+  memo = Memo{p.n, p.oh, p.ow, p.k, num_cu, best};
   return best;
 }
 
