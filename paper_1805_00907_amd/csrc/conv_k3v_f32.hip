@@ -9,8 +9,8 @@
 // of the machine on the maps of such a stack: 28 x 28 and 56 x 56 fill 77 % of their 16 x 16 blocks, and the
 // 784 blocks of 16 images of 112 x 112 are 3.06 rounds on 256 CUs, i.e. four.  Here a tile is th x tw pixels with
 // th * tw <= 32 * NB, NB = 5..8 MFMA row blocks of 32 pixels, and the time of a tile is proportional to NB: 7 x 28
-// pixels (NB = 7) cover a 28 x 28 map exactly in 256 tiles of 7/8 the work, 8 x 28 a 56 x 56 map, 14 x 16 a
-// 112 x 112 map in 3.5 rounds of 7/8 tiles.  The host picks the shape that minimises rounds x NB.
+// pixels (NB = 7) cover a 28 x 28 map exactly in 256 tiles of 7/8 the work, 8 x 28 a 56 x 56 map and a
+// 112 x 112 map (the latter in 3.5 rounds of 7/8 tiles).  The host picks the shape that minimises rounds x NB.
 //
 // What makes NB free to choose: the tile's NB pixel blocks x 4 channel columns of 32 are dealt to the eight
 // wavefronts as four squares of 2 x 2 blocks over pixel blocks 0-3 (wavefronts 0-3) and four strips of
