@@ -207,7 +207,8 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
  * three planes of bf16, a convolution filter in its own [k][r][s][c/groups] order, a FullyConnected weight
  * transposed to [N][K].  glowmi_conv2d / glowmi_fc make these planes inside every call (in the workspace);
  * a caller that keeps the weights fixed makes them once and hands them to the *_packed entry points, which
- * are otherwise the same calls with the same results bit for bit.
+ * are otherwise the same calls: bit for bit the same results where the same kernel serves both, and within
+ * the accuracy stated at the top where a layer takes the bf16 kernels only once its weights need no cutting.
  *   glowmi_conv2d_filter_planes_bytes / glowmi_fc_filter_planes_bytes
  *       bytes of the planes (6 per weight, rounded up to 256), or 0 when the shape has no plane form
  *       (c/groups, or K of a FullyConnected layer, not a multiple of 8; more than 2^28 weights; bad descriptor).
