@@ -42,17 +42,21 @@ if ROOT not in sys.path:
 # MI355X published peaks (dense)
 PEAK_FP32_MFMA = 157.3e12      # FLOP/s, fp32 matrix
 PEAK_INT8_MFMA = 5.0e15        # OP/s
-PEAK_BF16_MFMA = 2.5e15        # FLOP/s, bf16 matrix (the fp32 three-piece kernel multiplies bf16 pieces)
-P3_PRODUCTS = 6                # bf16 products that kernel takes per fp32 multiply-add
+PEAK_F16_MFMA = 2.5e15         # FLOP/s, fp16 and bf16 matrix (the large fp32 kernels multiply fp16 or bf16 pieces)
+F16_PRODUCTS = 3               # fp16 piece products per fp32 multiply-add (two pieces per operand)
+BF16_PRODUCTS = 6              # bf16 piece products per fp32 multiply-add (three pieces per operand)
 
 
 def _mfma_peak(dtype, variant=""):
     """(published peak of the matrix-core dtype the kernel multiplies in, matrix-core products per algorithmic
-    multiply-add).  The fp32 three-piece kernel runs on the bf16 cores with six products per fp32 product."""
+    multiply-add).  The large fp32 kernels run on the fp16 cores with three piece products per fp32 product, the
+    pointwise and first-layer ones on the bf16 cores with six."""
     if dtype != "f32":
         return PEAK_INT8_MFMA, 1
-    if "igemm_f32_p3" in variant or "bf16x6" in variant:
-        return PEAK_BF16_MFMA, P3_PRODUCTS
+    if "igemm_f32_p3" in variant or "f16x3" in variant:
+        return PEAK_F16_MFMA, F16_PRODUCTS
+    if "bf16x6" in variant:
+        return PEAK_F16_MFMA, BF16_PRODUCTS
     return PEAK_FP32_MFMA, 1
 PEAK_HBM = 8.0e12              # B/s
 LLC_BYTES = 256 << 20          # last-level (Infinity) cache
@@ -69,8 +73,8 @@ CHAINED = {"resnet50_block_fp32", "resnet50_block_int8"}   # layers feed each ot
 
 def _kernel_of(variant):
     """The kernel a variant name stands for: the 3x3 kernel whose pixel tile is shaped per layer reports the shape
-    (conv_k3_f32_bf16x6_14x16, .._8x28: one kernel, launched with different tile extents)."""
-    return re.sub(r"^(conv_k3_f32_bf16x6)_\d+x\d+((?:_add)?)$", r"\1\2", variant)
+    (conv_k3_f32_f16x3_14x16, .._8x28: one kernel, launched with different tile extents)."""
+    return re.sub(r"^(conv_k3_f32_f16x3)_\d+x\d+((?:_add)?)$", r"\1\2", variant)
 
 
 def _build_workload(name):
@@ -151,7 +155,7 @@ class Layer:
 
     def pack_filter(self, torch, stream):
         """The paper's compile-time step (Section 5.3: a filter's memory layout is changed once, for the kernel
-        that reads it): cut the constant fp32 weights into the bf16 planes, outside every timed region.
+        that reads it): cut the constant fp32 weights into the fp16 planes, outside every timed region.
         Returns the time it took in microseconds, None when this layer's shape has no plane form."""
         g, s = self.glowmi, self.spec
         if self.dtype != "f32":
@@ -524,14 +528,15 @@ def run_workload(name, args, torch, glowmi, cpu_budget_s):
     if shapes != [dominant]:
         roofline["variants"] = shapes        # the same kernel with the pixel-tile shape picked for each layer
     if products > 1 and dom_bound == "mfma":
-        # `frac` is algorithmic fp32 flops against the bf16 peak; the matrix pipes execute `products` bf16
-        # multiply-adds per algorithmic one, so their utilisation is products x frac
-        roofline.update({"mfma_dtype": "bf16, fp32 accumulate", "products_per_mac": products,
+        # `frac` is algorithmic fp32 flops against the fp16 / bf16 peak; the matrix pipes execute `products`
+        # multiply-adds of pieces per algorithmic one, so their utilisation is products x frac
+        roofline.update({"mfma_dtype": ("fp16" if products == F16_PRODUCTS else "bf16") + ", fp32 accumulate",
+                         "products_per_mac": products,
                          "pipe_frac": round(products * achieved / peak, 4),
                          "fp32_mfma_peak": PEAK_FP32_MFMA / 1e12,
                          "frac_of_fp32_mfma_peak": round(achieved * 1e12 / PEAK_FP32_MFMA, 4)})
     if "igemm_f32_p3" in dominant:
-        # one call of this kernel's layer = two packing kernels (operands cut into bf16 planes) + the contraction;
+        # one call of this kernel's layer = the range pass and the packing kernel (operands cut into fp16 planes) + the contraction;
         # the event pair brackets the call, so the packing is inside avg_launch_us (profiles/ has the kernels apart)
         roofline["launch_includes_packing"] = True
 
@@ -590,7 +595,7 @@ def run_workload(name, args, torch, glowmi, cpu_budget_s):
             packed = {"value": round(total_ops / (p_ms * 1e-3) / 1e12, 3), "unit": unit, "steps": args.steps,
                       "ms_per_step": round(p_ms, 4),
                       "pack_us_once": round(sum(u for u in pack_us if u is not None), 1),
-                      "note": "same step through glowmi_*_packed: the weights' bf16 planes made once by "
+                      "note": "same step through glowmi_*_packed: the weights' fp16 planes made once by "
                               "glowmi_*_pack_filter outside the timed region (pack_us_once, all layers); "
                               "not the headline"}
             for row, l, ms, u in zip(layer_rows, layers, packed_ms, pack_us):

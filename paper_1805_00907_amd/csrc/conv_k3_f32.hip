@@ -1,22 +1,23 @@
 // fp32 3x3 Convolution (stride 1) with 64 or more input channels and more than 64 output channels on maps that
-// tile well into 16 x 16 pixel blocks -- the body of a VGG stack -- on the bf16 matrix cores with every operand
-// cut exactly into three bf16 pieces and six piece products per fp32 product (bf16_pieces.h).  The arithmetic is
+// tile well into 16 x 16 pixel blocks -- the body of a VGG stack -- on the fp16 matrix cores with every operand
+// cut into two fp16 pieces and three piece products per fp32 product (f16_pieces.h).  The arithmetic is
 // the loop nest of Section 3.1 of the paper with the bias add and Relu stacked onto it (Section 5.2); this is one
 // more kind of convolution with a strategy of its own (Section 5.3).
 //
-// The generic three-piece kernel (igemm_f32_p3.hip) fetches every input element nine times (once per tap) as
+// The generic kernel over planes (igemm_f32_p3.hip) fetches every input element nine times (once per tap) as
 // planes that a packing pass had to write first, and measured a third of its time is the fill path.  Here
 //   - a workgroup owns a 16 x 16 block of output pixels x 128 output channels and walks the input channels in
 //     chunks of 32.  The chunk's 18 x 18 x 32 input patch is read from the fp32 input ONCE (coalesced 32-byte
 //     pieces, zeros outside the image from the range-checked loads), cut into pieces in registers and kept in
-//     LDS as three bf16 planes (68 KB); all nine taps read their MFMA fragments from it at shifted addresses.
-//     No packing pass over the input, and a ninth of the input traffic;
-//   - the filter is cut once per call by the packing kernel into three planes in the workspace and streamed
-//     slab by slab (one tap x 32 channels x 128 output channels, 24 KB) straight into a ring of two LDS
+//     LDS as two fp16 planes (45 KB); all nine taps read their MFMA fragments from it at shifted addresses.
+//     No packing pass over the input (only the pass that finds its largest magnitude), and a ninth of the
+//     input traffic;
+//   - the filter is cut once per call by the packing kernel into two planes in the workspace and streamed
+//     slab by slab (one tap x 32 channels x 128 output channels, 16 KB) straight into a ring of two LDS
 //     buffers;
 //   - eight wavefronts = four pixel quarters (4 rows x 16 columns: two 32-pixel MFMA blocks) x two channel halves,
-//     64 x 64 outputs each over the whole slab: 48 MFMAs per wavefront between two barriers, 512 bytes of
-//     fragments per MFMA, no exchange of partial tiles;
+//     64 x 64 outputs each over the whole slab: 24 MFMAs per wavefront between two barriers, no exchange of
+//     partial tiles;
 //   - workgroups are persistent; the next chunk's (or the next tile's first) patch is fetched into registers
 //     while the current chunk is multiplied, so only cutting and writing it is exposed;
 //   - patch rows are kept TW + 4 pixels apart and a pixel's four 16-byte chunks are stored at
@@ -27,7 +28,7 @@
 #include <cstdio>
 #include <type_traits>
 
-#include "bf16_pieces.h"
+#include "f16_pieces.h"
 #include "igemm.h"
 #include "lds_direct.h"
 
@@ -54,12 +55,12 @@ struct K3 {
   static constexpr int PATCH_PX = (GT + 2) * PW;
   static constexpr int APLANE = PATCH_PX * G_PIXB;
   static constexpr int BPLANE = BN * G_BROW;
-  static constexpr int BBUF = 3 * BPLANE;                    // one slab
-  static constexpr int LDS = 3 * APLANE + G_NBUF * BBUF + G_DUMMY;
+  static constexpr int BBUF = 2 * BPLANE;                    // one slab
+  static constexpr int LDS = 2 * APLANE + G_NBUF * BBUF + G_DUMMY;
   static constexpr int ITEMS = PATCH_PX * (G_CH / 8);        // (pixel, 8-channel piece) items of a patch chunk
   static constexpr int PASSES = (ITEMS + G_THREADS - 1) / G_THREADS;
   static constexpr int PREF = 2 * PASSES;                    // prefetch loads per thread
-  static constexpr int WLOADS = 3 * BN / 16;                 // wavefront loads per filter slab (16 rows each)
+  static constexpr int WLOADS = 2 * BN / 16;                 // wavefront loads per filter slab (16 rows each)
   static constexpr int LPW = (WLOADS + 7) / 8;               // per wavefront (the last ones may be zero fills into the dummy area)
   static constexpr int WAVES_N = BN / 64;
   static_assert(LDS <= 160 * 1024, "LDS of one CU");
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   constexpr int GP = T::PW, G_APLANE = T::APLANE, G_BPLANE = T::BPLANE, G_BBUF = T::BBUF, G_BN = BN;
   constexpr int G_ITEMS = T::ITEMS, G_PASSES = T::PASSES, G_PREF = T::PREF;
   extern __shared__ __align__(16) unsigned char lds[];
-  unsigned char* bring = lds + 3 * G_APLANE;
+  unsigned char* bring = lds + 2 * G_APLANE;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -85,8 +86,11 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   const __amdgpu_buffer_rsrc_t rsrc_x =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X), 0, (int)p.x_bytes, 0x00020000);
   const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
-  const v4i rsrc_w = make_rsrc(p.w_planes, 3u * wpb);
+  const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
+  // the operands' scale exponents, from their largest magnitudes
+  const int se_x = scale_exponent(wave_max_words(p.x_range, p.x_range_n));
+  const int neg_se = -(se_x + scale_exponent(wave_max_words(p.w_range, 1)));
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   const int chunks = p.c / G_CH;                        // p.c % 32 == 0 on this kernel
@@ -128,18 +132,17 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
         const int pp = item >> 2, c8 = item & 3;
         const float v[8] = {pre[q][0][0], pre[q][0][1], pre[q][0][2], pre[q][0][3],
                             pre[q][1][0], pre[q][1][1], pre[q][1][2], pre[q][1][3]};
-        v4u h, m, l;
-        split8(v, h, m, l);
+        v4u p1, p2;
+        cut8(v, se_x, p1, p2);
         const int key = pp - 4 * (pp / GP);               // TW * patch row + patch column
         unsigned char* dst = lds + pp * G_PIXB + ((c8 ^ ((key >> 2) & 3)) << 4);
-        *reinterpret_cast<v4u*>(dst) = h;
-        *reinterpret_cast<v4u*>(dst + G_APLANE) = m;
-        *reinterpret_cast<v4u*>(dst + 2 * G_APLANE) = l;
+        *reinterpret_cast<v4u*>(dst) = p1;
+        *reinterpret_cast<v4u*>(dst + G_APLANE) = p2;
       }
     }
   };
 
-  // ---- filter slab loads: 3 planes x BN / 16 groups of 16 rows per slab; wavefront w issues numbers w, w + 8, ..
+  // ---- filter slab loads: 2 planes x BN / 16 groups of 16 rows per slab; wavefront w issues numbers w, w + 8, ..
   // (LPW of them; a number past the last is a zero fill into the dummy area, so that every wavefront has the same
   // number of loads outstanding).  Lane l: row l / 4 of the group, chunk position l % 4 holding chunk
   // (l % 4) ^ ((row / 4) % 4) of the row.
@@ -198,13 +201,16 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
     __syncthreads();                                    // everyone is done with the previous tile's last slab buffer
     issue_b(ct, 0, 0);
 
-    v16f acc[2][2];
+    v16f acc[2][2], acc_lo[2][2];                       // the h1 h1' products; the cross terms (weight 2^-11)
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        for (int e = 0; e < 16; ++e) {
+          acc[i][j][e] = 0.f;
+          acc_lo[i][j][e] = 0.f;
+        }
 
     int s = 0;
     for (int chunk = 0; chunk < chunks; ++chunk) {
@@ -235,26 +241,27 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
 #pragma unroll
         for (int k16 = 0; k16 < 2; ++k16) {
           const int c8 = k16 * 2 + lhalf;                              // this lane's 16-byte chunk of the pixel / filter row
-          v8bf a[3][2], b[3][2];
-          constexpr int ORDER_A[3] = {2, 0, 1}, ORDER_B[3] = {0, 2, 1};   // the order the MFMAs use them in
+          v8h a[2][2], b[2][2];
           int a_off[2];
 #pragma unroll
           for (int i = 0; i < 2; ++i) a_off[i] = a_base[i] * G_PIXB + ((c8 ^ ((a_key[i] >> 2) & 3)) << 4);
           const int b_off = (c8 ^ b_sw) << 4;
 #pragma unroll
-          for (int o = 0; o < 3; ++o) {
-            const int pa = ORDER_A[o], pb = ORDER_B[o];
+          for (int o = 0; o < 2; ++o) {
+            const int pa = o, pb = 1 - o;                                // the order the MFMAs use them in: cross terms first
 #pragma unroll
             for (int i = 0; i < 2; ++i)
-              a[pa][i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(lds + pa * G_APLANE + a_off[i]));
+              a[pa][i] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(lds + pa * G_APLANE + a_off[i]));
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-              b[pb][j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(bb + pb * G_BPLANE + j * 32 * G_BROW + b_off));
+              b[pb][j] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(bb + pb * G_BPLANE + j * 32 * G_BROW + b_off));
           }
 #pragma unroll
-          for (int q = 0; q < 24; ++q) {
+          for (int q = 0; q < 12; ++q) {
             const int tt = q / 4, i = (q / 2) % 2, j = q % 2;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[tt]][i], b[kPieceTermB[tt]][j], acc[i][j], 0, 0, 0);
+            if (tt == 0) acc_lo[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], b[1][j], acc_lo[i][j], 0, 0, 0);
+            else if (tt == 1) acc_lo[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[1][i], b[0][j], acc_lo[i][j], 0, 0, 0);
+            else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], b[0][j], acc[i][j], 0, 0, 0);
           }
         }
       }
@@ -275,7 +282,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
           const int oy = ty * GT + tp / TW, ox = tx * TW + tp % TW;
           if (cok && oy < p.oh && ox < p.ow) {
             const size_t o = ((size_t)(img * p.oh + oy) * p.ow + ox) * p.k + ch;
-            float v = acc[i][j][e] + bv;
+            float v = join_sets(acc[i][j][e], acc_lo[i][j][e], neg_se) + bv;
             if (ADD) v += addend[o];
             if (relu) v = fmaxf(v, 0.f);
             Y[o] = v;
@@ -320,7 +327,7 @@ bool k3_f32_applicable(const Problem& p) {
   if (knob_or(KNOB_F32_K3_ANY, 0) != 0) return true;    // tests: any size
   // more than 64 output channels: the kernel whose tile shape follows the map; worth it when most of what the
   // machine multiplies is real output (a 14 x 14 map at batch 16 gives 64 tiles for 256 CUs and stays on the
-  // generic three-piece kernel)
+  // generic kernel over planes)
   if (!k3_wide_tile(p) && knob_or(KNOB_F32_K3V, 1) != 0) return k3v_f32_efficiency(p) >= 0.6;
   // the tiles must be mostly full (a 28 x 28 or 56 x 56 map fills 77 % of its 16 x 16 blocks, which still beats the
   // generic kernel: 512 -> 512 on 28 x 28 at batch 16 is 256 tiles = one round here, 361 -> 329 us; a 14 x 14 map at
@@ -329,18 +336,18 @@ bool k3_f32_applicable(const Problem& p) {
   return fill >= 0.75 && tiles >= 256;
 }
 
-size_t k3_f32_pack_bytes(const Problem& p) { return p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2); }
+size_t k3_f32_pack_bytes(const Problem& p) { return ranges_and_filter_bytes(p); }
 
 hipError_t launch_k3_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
   Problem p = p_in;
-  hipError_t e = stage_filter_planes(p, p.planes, stream);
+  hipError_t e = stage_ranges_and_filter(p, p.planes, stream);
   if (e != hipSuccess) return e;
   if (!k3_wide_tile(p) && knob_or(KNOB_F32_K3V, 1) != 0 && !k3v_f32_prefers_fixed_tile(p)) return launch_k3v_f32(p, stream, variant);
   if (k3_wide_tile(p)) {
-    *variant = p.addend ? "conv_k3_f32_bf16x6_16x32x64_add" : "conv_k3_f32_bf16x6_16x32x64";
+    *variant = p.addend ? "conv_k3_f32_f16x3_16x32x64_add" : "conv_k3_f32_f16x3_16x32x64";
     return p.addend ? launch_k3g_variant<true, 32, 64>(p, stream) : launch_k3g_variant<false, 32, 64>(p, stream);
   }
-  *variant = p.addend ? "conv_k3_f32_bf16x6_add" : "conv_k3_f32_bf16x6";
+  *variant = p.addend ? "conv_k3_f32_f16x3_add" : "conv_k3_f32_f16x3";
   return p.addend ? launch_k3g_variant<true, 16, 128>(p, stream) : launch_k3g_variant<false, 16, 128>(p, stream);
 }
 

@@ -1,6 +1,6 @@
 // fp32 3x3 Convolution (stride 1) over 64 input channels on many pixels -- the first layer pair of a VGG
-// stack, the 3x3 layers of a residual network's first stage -- on the bf16 matrix cores with every operand
-// cut exactly into three bf16 pieces and six piece products per fp32 product (bf16_pieces.h).  One more kind
+// stack, the 3x3 layers of a residual network's first stage -- on the fp16 matrix cores with every operand
+// cut into two fp16 pieces and three piece products per fp32 product (f16_pieces.h).  One more kind
 // of convolution with a strategy of its own (Section 5.3 of the paper); the arithmetic is the loop nest of
 // Section 3.1 with the bias add and Relu stacked onto it (Section 5.2).
 //
@@ -8,15 +8,16 @@
 // times (once per tap) for only 64 output channels each and is bound by the path from L2 into the CUs.  Here
 //   - a workgroup owns a 16 x 16 block of output pixels x 64 output channels.  Its 18 x 18 x 64 input patch is
 //     read from global memory ONCE (fp32, coalesced 32-byte pieces, zeros outside the image from the
-//     range-checked loads), cut into pieces in registers and kept in LDS as three bf16 planes (124 KB); all
+//     range-checked loads), cut into pieces in registers and kept in LDS as two fp16 planes (83 KB); all
 //     nine taps read their MFMA fragments from it at shifted addresses.  Per tile 83 KB of input are fetched
-//     instead of 442 KB of planes, and no packing pass over the input is needed;
-//   - the filter (64 x 576) is cut once per call by the packing kernel into three planes in the workspace
-//     (221 KB, L2-resident) and streamed slab by slab (one tap x 32 channels, 12 KB) straight into a ring of
+//     instead of nine times its planes, and no packing pass over the input is needed (only the pass that finds
+//     its largest magnitude);
+//   - the filter (64 x 576) is cut once per call by the packing kernel into two planes in the workspace
+//     (147 KB, L2-resident) and streamed slab by slab (one tap x 32 channels, 8 KB) straight into a ring of
 //     two LDS buffers;
 //   - eight wavefronts: four pixel quarters (4 rows x 16 columns = two 32-pixel MFMA blocks) x two sets that
-//     split every slab's 32 reduction indices, 64 x 64 outputs per wavefront (512 bytes of fragments per
-//     MFMA); partial tiles exchanged through LDS at the end;
+//     split every slab's 32 reduction indices, 64 x 64 outputs per wavefront; partial tiles exchanged through
+//     LDS at the end;
 //   - workgroups are persistent: the next tile's patch is fetched into registers while the current tile is
 //     multiplied, so only cutting and writing it (about a tenth of a tile's MFMA time) is exposed;
 //   - a pixel's eight 16-byte chunks are stored at chunk ^ ((key / 2) % 8), key = 16 * patch row + patch column,
@@ -26,7 +27,7 @@
 #include <cstdio>
 #include <type_traits>
 
-#include "bf16_pieces.h"
+#include "f16_pieces.h"
 #include "igemm.h"
 #include "lds_direct.h"
 
@@ -43,22 +44,21 @@ constexpr int K_PIXB = 128;                    // bytes of a pixel's 64 channels
 constexpr int K_APLANE = K_PATCH_PX * K_PIXB;  // 41472
 constexpr int K_BROW = 64;                     // bytes of a filter row piece (32 reduction indices) in one plane
 constexpr int K_BPLANE = 64 * K_BROW;          // 4096: 64 output channels
-constexpr int K_BBUF = 3 * K_BPLANE;           // one slab
+constexpr int K_BBUF = 2 * K_BPLANE;           // one slab
 constexpr int K_NBUF = 2;
-constexpr int K_DUMMY = 1024;                  // landing area of the loads issued only to keep the counts equal
-constexpr int K_LDS = 3 * K_APLANE + K_NBUF * K_BBUF + K_DUMMY;
+constexpr int K_LDS = 2 * K_APLANE + K_NBUF * K_BBUF;
 constexpr int K_THREADS = 512;
 constexpr int K_ITEMS = K_PATCH_PX * 8;        // (pixel, 8-channel chunk) pieces of a patch
 constexpr int K_PASSES = (K_ITEMS + K_THREADS - 1) / K_THREADS;   // 6
 constexpr int K_SLABS = 18;                    // 9 taps x 2 channel halves
 static_assert(K_LDS <= 160 * 1024, "LDS of one CU");
-static_assert(3 * K_APLANE >= 8 * 32 * 64 * 4, "exchange of the partial tiles fits the patch area");
+static_assert(2 * K_APLANE >= 8 * 32 * 64 * 4, "exchange of the partial tiles fits the patch area");
 
 template <bool ADD>
 __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Problem p, int tiles_y, int tiles_x,
                                                                      int tiles_c, int total) {
   extern __shared__ __align__(16) unsigned char lds[];
-  unsigned char* bring = lds + 3 * K_APLANE;
+  unsigned char* bring = lds + 2 * K_APLANE;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -71,8 +71,11 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
   const __amdgpu_buffer_rsrc_t rsrc_x =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X), 0, (int)p.x_bytes, 0x00020000);
   const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
-  const v4i rsrc_w = make_rsrc(p.w_planes, 3u * wpb);
+  const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
+  // the operands' scale exponents, from their largest magnitudes
+  const int se_x = scale_exponent(wave_max_words(p.x_range, p.x_range_n));
+  const int neg_se = -(se_x + scale_exponent(wave_max_words(p.w_range, 1)));
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   // ---- tile decode: channel tile fastest (workgroups that share a patch run side by side), then x, y, image
@@ -110,36 +113,30 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
         const int pp = item >> 3, c8 = item & 7;
         const float v[8] = {pre[q][0][0], pre[q][0][1], pre[q][0][2], pre[q][0][3],
                             pre[q][1][0], pre[q][1][1], pre[q][1][2], pre[q][1][3]};
-        v4u h, m, l;
-        split8(v, h, m, l);
+        v4u p1, p2;
+        cut8(v, se_x, p1, p2);
         const int py = pp / KP;
         const int key = pp - 2 * py;                     // py * 16 + px: the pixel's index at the tile's own pitch
         unsigned char* dst = lds + pp * K_PIXB + ((c8 ^ ((key >> 1) & 7)) << 4);
-        *reinterpret_cast<v4u*>(dst) = h;
-        *reinterpret_cast<v4u*>(dst + K_APLANE) = m;
-        *reinterpret_cast<v4u*>(dst + 2 * K_APLANE) = l;
+        *reinterpret_cast<v4u*>(dst) = p1;
+        *reinterpret_cast<v4u*>(dst + K_APLANE) = p2;
       }
     }
   };
 
-  // ---- filter slab loads: 12 wavefront loads per slab (3 planes x 4 groups of 16 rows); wavefront w issues
-  // number w and number w + 8, the latter a zero fill into the dummy area for w >= 4 so that every
-  // wavefront has the same number of loads outstanding.  Lane l: row l / 4 of the group, chunk position l % 4
-  // holding chunk (l % 4) ^ ((row / 4) % 4) of the row (the swizzle of igemm_f32_p3.hip).
+  // ---- filter slab loads: 8 wavefront loads per slab (2 planes x 4 groups of 16 rows), one per wavefront.
+  // Lane l: row l / 4 of the group, chunk position l % 4 holding chunk (l % 4) ^ ((row / 4) % 4) of the row
+  // (the swizzle of igemm_f32_p3.hip).
   const int bch = (lane & 3) ^ ((lane >> 4) & 3);
   auto issue_b = [&](int ct, int slab, int buf) {
     const int tap = slab >> 1, half = slab & 1;
     const unsigned lbase = __builtin_amdgcn_readfirstlane(lds_offset_of(bring) + buf * K_BBUF);
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const int j = wave + 8 * u;                        // 0..15, real below 12
-      const int plane = j >> 2, rg = j & 3;
+    {
+      const int plane = wave >> 2, rg = wave & 3;
       const int n = ct * 64 + rg * 16 + (lane >> 2);
-      const bool ok = j < 12 && slab < K_SLABS && n < p.k;
+      const bool ok = slab < K_SLABS && n < p.k;         // past the last slab: a zero fill, no memory traffic
       const unsigned off = ok ? 2u * ((unsigned)n * 576u + (unsigned)(tap * 64 + half * 32 + bch * 8)) + (unsigned)plane * wpb : OOB;
-      const unsigned dst = j < 12 ? lbase + plane * K_BPLANE + rg * 16 * K_BROW
-                                  : __builtin_amdgcn_readfirstlane(lds_offset_of(lds) + 3 * K_APLANE + K_NBUF * K_BBUF);
-      load16_to_lds(rsrc_w, dst, off);
+      load16_to_lds(rsrc_w, lbase + plane * K_BPLANE + rg * 16 * K_BROW, off);
     }
   };
 
@@ -177,13 +174,16 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
     if (t_next < total) fetch_patch(t_next);            // in flight during this tile's MFMAs (uniform branch)
     issue_b(ct, 0, 0);
 
-    v16f acc[2][2];
+    v16f acc[2][2], acc_lo[2][2];                       // the h1 h1' products; the cross terms (weight 2^-11)
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+        for (int e = 0; e < 16; ++e) {
+          acc[i][j][e] = 0.f;
+          acc_lo[i][j][e] = 0.f;
+        }
 
     // ---- 18 slabs.  Trip s: slab s has landed (one slab in flight), barrier (also: the patch is written, everyone
     // is done with the other buffer), refill the other buffer with slab s + 1, multiply slab s.
@@ -196,8 +196,7 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
       const int tr = tap / 3, ts = tap - tr * 3;
       const int c8 = half * 4 + kgrp * 2 + lhalf;       // this lane's 16-byte chunk of the pixel
       const unsigned char* bb = bring + (s & 1) * K_BBUF + frag_b;
-      v8bf a[3][2], b[3][2];
-      constexpr int ORDER_A[3] = {2, 0, 1}, ORDER_B[3] = {0, 2, 1};   // the order the MFMAs use them in
+      v8h a[2][2], b[2][2];
       int a_off[2];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
@@ -206,19 +205,21 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
         a_off[i] = pp * K_PIXB + ((c8 ^ ((key >> 1) & 7)) << 4);
       }
 #pragma unroll
-      for (int o = 0; o < 3; ++o) {
-        const int pa = ORDER_A[o], pb = ORDER_B[o];
+      for (int o = 0; o < 2; ++o) {
+        const int pa = o, pb = 1 - o;                    // the order the MFMAs use them in: cross terms first
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-          a[pa][i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(lds + pa * K_APLANE + a_off[i]));
+          a[pa][i] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(lds + pa * K_APLANE + a_off[i]));
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          b[pb][j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(bb + pb * K_BPLANE + j * 32 * K_BROW));
+          b[pb][j] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(bb + pb * K_BPLANE + j * 32 * K_BROW));
       }
 #pragma unroll
-      for (int q = 0; q < 24; ++q) {
+      for (int q = 0; q < 12; ++q) {
         const int tt = q / 4, i = (q / 2) % 2, j = q % 2;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[tt]][i], b[kPieceTermB[tt]][j], acc[i][j], 0, 0, 0);
+        if (tt == 0) acc_lo[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], b[1][j], acc_lo[i][j], 0, 0, 0);
+        else if (tt == 1) acc_lo[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[1][i], b[0][j], acc_lo[i][j], 0, 0, 0);
+        else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], b[0][j], acc[i][j], 0, 0, 0);
       }
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));           // the zero fill past the last slab (and, conservatively, the prefetch)
@@ -234,11 +235,15 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
         constexpr int KG = decltype(kg_tag)::value;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-          keep[j] = acc[KG][j];
+          v16f snd;
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {                 // the two accumulator sets joined
+            keep[j][e] = __builtin_fmaf(acc_lo[KG][j][e], kLowPieceWeight, acc[KG][j][e]);
+            snd[e] = __builtin_fmaf(acc_lo[1 - KG][j][e], kLowPieceWeight, acc[1 - KG][j][e]);
+          }
 #pragma unroll
           for (int e4 = 0; e4 < 4; ++e4)
-            xch[(mine + j * 4 + e4) * 64 + lane] = v4f{acc[1 - KG][j][e4 * 4], acc[1 - KG][j][e4 * 4 + 1],
-                                                       acc[1 - KG][j][e4 * 4 + 2], acc[1 - KG][j][e4 * 4 + 3]};
+            xch[(mine + j * 4 + e4) * 64 + lane] = v4f{snd[e4 * 4], snd[e4 * 4 + 1], snd[e4 * 4 + 2], snd[e4 * 4 + 3]};
         }
       };
       if (kgrp) exchange_as(std::integral_constant<int, 1>{});
@@ -250,7 +255,7 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
         for (int e4 = 0; e4 < 4; ++e4) {
           const v4f got = xch[(theirs + j * 4 + e4) * 64 + lane];
 #pragma unroll
-          for (int tq = 0; tq < 4; ++tq) keep[j][e4 * 4 + tq] += got[tq];
+          for (int tq = 0; tq < 4; ++tq) keep[j][e4 * 4 + tq] = __builtin_ldexpf(keep[j][e4 * 4 + tq] + got[tq], neg_se);   // scaled back
         }
     }
 
@@ -306,13 +311,13 @@ bool k3c64_f32_applicable(const Problem& p) {
   return tiles >= knob_or(KNOB_F32_K3C64_MIN_TILES, 512);
 }
 
-size_t k3c64_f32_pack_bytes(const Problem& p) { return p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2); }
+size_t k3c64_f32_pack_bytes(const Problem& p) { return ranges_and_filter_bytes(p); }
 
 hipError_t launch_k3c64_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
   Problem p = p_in;
-  hipError_t e = stage_filter_planes(p, p.planes, stream);
+  hipError_t e = stage_ranges_and_filter(p, p.planes, stream);
   if (e != hipSuccess) return e;
-  *variant = p.addend ? "conv_k3c64_f32_bf16x6_add" : "conv_k3c64_f32_bf16x6";
+  *variant = p.addend ? "conv_k3c64_f32_f16x3_add" : "conv_k3c64_f32_f16x3";
   return p.addend ? launch_k3_variant<true>(p, stream) : launch_k3_variant<false>(p, stream);
 }
 

@@ -1,6 +1,6 @@
 // fp32 3x3 Convolution (stride 1) with 64 or more input channels and more than 64 output channels -- the body of a
-// VGG stack -- on the bf16 matrix cores with every operand cut exactly into three bf16 pieces and six piece
-// products per fp32 product (bf16_pieces.h), with a pixel tile whose SHAPE IS CHOSEN PER LAYER.  The arithmetic is
+// VGG stack -- on the fp16 matrix cores with every operand cut into two fp16 pieces and three piece products per
+// fp32 product (f16_pieces.h), with a pixel tile whose SHAPE IS CHOSEN PER LAYER.  The arithmetic is
 // the loop nest of Section 3.1 of the paper with the bias add and Relu stacked onto it (Section 5.2); Section 5.3
 // gives every kind of convolution a tile size of its own, chosen from what the hardware holds.
 //
@@ -16,11 +16,11 @@
 // wavefronts as four squares of 2 x 2 blocks over pixel blocks 0-3 (wavefronts 0-3) and four strips of
 // (NB - 4) x 1 blocks over the rest (wavefronts 4-7, one channel column each).  Wavefronts w and w + 4 share a SIMD,
 // so every SIMD carries NB block products per 16 reduction indices whatever NB is, although its two wavefronts
-// carry unequal parts.  No partial tiles to exchange; per 16 reduction indices the squares read 4 x 3 fragments
-// for 24 MFMAs and the strips (NB - 3) x 3 for (NB - 4) x 6.
+// carry unequal parts.  No partial tiles to exchange; per 16 reduction indices the squares read 4 x 2 fragments
+// for 12 MFMAs and the strips (NB - 3) x 2 for (NB - 4) x 3.
 //
 // Otherwise as the fixed-tile kernel (conv_k3_f32.hip): the input is walked in chunks of 32 channels whose
-// (th + 2) x (tw + 2) patch is read ONCE from the fp32 input, cut in registers and kept in LDS as three bf16
+// (th + 2) x (tw + 2) patch is read ONCE from the fp32 input, cut in registers and kept in LDS as two fp16
 // planes, all nine taps reading their fragments from it at shifted addresses; the filter's planes (cut once per
 // call, or ahead of time by the caller) are streamed slab by slab into a ring of two LDS buffers; workgroups are
 // persistent and fetch the next patch into registers while the current chunk is multiplied.
@@ -29,7 +29,7 @@
 #include <cstdio>
 #include <type_traits>
 
-#include "bf16_pieces.h"
+#include "f16_pieces.h"
 #include "igemm.h"
 #include "lds_direct.h"
 
@@ -48,12 +48,12 @@ constexpr int V_MAXPX = 360;                   // largest patch (th + 2) * (tw +
 constexpr int V_MAXTW = 64;
 constexpr int V_APLANE = V_MAXPX * V_PIXB;
 constexpr int V_BPLANE = V_BN * V_BROW;
-constexpr int V_BBUF = 3 * V_BPLANE;           // one slab: a tap x 32 channels x 128 output channels x 3 planes
-constexpr int V_STAGE = 3 * V_APLANE + 2 * V_BBUF;
+constexpr int V_BBUF = 2 * V_BPLANE;           // one slab: a tap x 32 channels x 128 output channels x 2 planes
+constexpr int V_STAGE = 2 * V_APLANE + 2 * V_BBUF;
 constexpr int V_PASSES = (V_MAXPX * (V_CH / 8) + V_THREADS - 1) / V_THREADS;
 constexpr int V_PREF = 2 * V_PASSES;           // prefetch loads per thread
-constexpr int V_LPW = 3 * V_BN / 16 / 8;       // filter loads per wavefront and slab (16 rows each)
-static_assert(V_LPW * 8 * 16 == 3 * V_BN, "filter loads divide over the wavefronts");
+constexpr int V_LPW = 2 * V_BN / 16 / 8;       // filter loads per wavefront and slab (16 rows each)
+static_assert(V_LPW * 8 * 16 == 2 * V_BN, "filter loads divide over the wavefronts");
 
 static_assert(V_STAGE <= 160 * 1024, "LDS of one CU");
 
@@ -61,7 +61,7 @@ template <bool ADD, int NB>
 __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Problem p, int th, int tw, int tiles_y,
                                                                    int tiles_x, int tiles_c, int total) {
   extern __shared__ __align__(16) unsigned char lds[];
-  unsigned char* bring = lds + 3 * V_APLANE;
+  unsigned char* bring = lds + 2 * V_APLANE;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -72,8 +72,11 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
   const __amdgpu_buffer_rsrc_t rsrc_x =
       __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(X), 0, (int)p.x_bytes, 0x00020000);
   const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
-  const v4i rsrc_w = make_rsrc(p.w_planes, 3u * wpb);
+  const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
+  // the operands' scale exponents, from their largest magnitudes
+  const int se_x = scale_exponent(wave_max_words(p.x_range, p.x_range_n));
+  const int neg_se = -(se_x + scale_exponent(wave_max_words(p.w_range, 1)));
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   // Patch rows have a pitch of tw + 4 pixels (tw + 2 used), and a pixel's four 16-byte chunks are stored at
@@ -137,18 +140,17 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
         const int pp = item >> 2, c8 = item & 3;
         const float v[8] = {pre[q][0][0], pre[q][0][1], pre[q][0][2], pre[q][0][3],
                             pre[q][1][0], pre[q][1][1], pre[q][1][2], pre[q][1][3]};
-        v4u h, m, l;
-        split8(v, h, m, l);
+        v4u p1, p2;
+        cut8(v, se_x, p1, p2);
         const int key = (pyx[q] >> 16) * tw + (pyx[q] & 0xffff);
         unsigned char* dst = lds + pp * V_PIXB + ((c8 ^ ((key >> 2) & 3)) << 4);
-        *reinterpret_cast<v4u*>(dst) = h;
-        *reinterpret_cast<v4u*>(dst + V_APLANE) = m;
-        *reinterpret_cast<v4u*>(dst + 2 * V_APLANE) = l;
+        *reinterpret_cast<v4u*>(dst) = p1;
+        *reinterpret_cast<v4u*>(dst + V_APLANE) = p2;
       }
     }
   };
 
-  // ---- filter slab loads: 3 planes x 8 groups of 16 rows per slab; wavefront w loads row group w of every plane.
+  // ---- filter slab loads: 2 planes x 8 groups of 16 rows per slab; wavefront w loads row group w of every plane.
   // Lane l: row l / 4 of the group, chunk position l % 4 holding chunk (l % 4) ^ ((row / 4) % 4) of the row.
   const int bch = (lane & 3) ^ ((lane >> 4) & 3);
   auto issue_b = [&](int ct, int slab, int buf) {
@@ -199,13 +201,16 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
       __syncthreads();                                  // everyone is done with the previous tile's last slab buffer
       issue_b(ct, 0, 0);
 
-      v16f acc[PX][CH];
+      v16f acc[PX][CH], acc_lo[PX][CH];                 // the h1 h1' products; the cross terms (weight 2^-11)
 #pragma unroll
       for (int i = 0; i < PX; ++i)
 #pragma unroll
         for (int j = 0; j < CH; ++j)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+          for (int e = 0; e < 16; ++e) {
+            acc[i][j][e] = 0.f;
+            acc_lo[i][j][e] = 0.f;
+          }
 
       int s = 0;
       for (int chunk = 0; chunk < chunks; ++chunk) {
@@ -235,26 +240,28 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
 #pragma unroll
           for (int k16 = 0; k16 < 2; ++k16) {
             const int c8 = k16 * 2 + lhalf;                            // this lane's 16-byte chunk of the pixel / filter row
-            v8bf a[3][PX], b[3][CH];
-            constexpr int ORDER_A[3] = {2, 0, 1}, ORDER_B[3] = {0, 2, 1};   // the order the MFMAs use them in
+            v8h a[2][PX], b[2][CH];
 #pragma unroll
-            for (int o = 0; o < 3; ++o) {
-              const int pa = ORDER_A[o], pb = ORDER_B[o];
+            for (int o = 0; o < 2; ++o) {
+              const int pa = o, pb = 1 - o;                              // the order the MFMAs use them in: cross terms first
 #pragma unroll
               for (int i = 0; i < PX; ++i)
-                a[pa][i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(
-                                                        lds + pa * V_APLANE + ab[i] + ((c8 ^ sw[i]) << 4)));
+                a[pa][i] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(
+                                                       lds + pa * V_APLANE + ab[i] + ((c8 ^ sw[i]) << 4)));
 #pragma unroll
               for (int j = 0; j < CH; ++j)
-                b[pb][j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(bb + pb * V_BPLANE + j * 32 * V_BROW + ((c8 ^ b_sw) << 4)));
+                b[pb][j] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(bb + pb * V_BPLANE + j * 32 * V_BROW + ((c8 ^ b_sw) << 4)));
             }
 #pragma unroll
-            for (int tt = 0; tt < 6; ++tt)
+            for (int tt = 0; tt < 3; ++tt)
 #pragma unroll
               for (int i = 0; i < PX; ++i)
 #pragma unroll
-                for (int j = 0; j < CH; ++j)
-                  acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[tt]][i], b[kPieceTermB[tt]][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < CH; ++j) {
+                  if (tt == 0) acc_lo[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], b[1][j], acc_lo[i][j], 0, 0, 0);
+                  else if (tt == 1) acc_lo[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[1][i], b[0][j], acc_lo[i][j], 0, 0, 0);
+                  else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], b[0][j], acc[i][j], 0, 0, 0);
+                }
           }
           if (++ts == 3) {                                 // next tap: down a patch row, or one column on
             ts = 0;
@@ -288,7 +295,7 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
               const int oy = ty * th + r, ox = tx * tw + c;
               if (cok && tp < tile_px && oy < p.oh && ox < p.ow) {
                 const size_t o = ((size_t)(img * p.oh + oy) * p.ow + ox) * p.k + ch;
-                float v = acc[i][j][4 * q + e4] + bv;
+                float v = join_sets(acc[i][j][4 * q + e4], acc_lo[i][j][4 * q + e4], neg_se) + bv;
                 if (ADD) v += addend[o];
                 if (relu) v = fmaxf(v, 0.f);
                 Y[o] = v;
@@ -416,7 +423,7 @@ hipError_t launch_k3v_f32(const Problem& p, hipStream_t stream, const char** var
   if (num_cu < 1) return hipErrorInvalidDevice;
   const TileShape s = pick_tile(p, num_cu);
   static thread_local char name[64];
-  snprintf(name, sizeof(name), "conv_k3_f32_bf16x6_%dx%d%s", s.th, s.tw, p.addend ? "_add" : "");
+  snprintf(name, sizeof(name), "conv_k3_f32_f16x3_%dx%d%s", s.th, s.tw, p.addend ? "_add" : "");
   *variant = name;
   return p.addend ? launch_k3v_blocks<true>(p, s, num_cu, stream) : launch_k3v_blocks<false>(p, s, num_cu, stream);
 }

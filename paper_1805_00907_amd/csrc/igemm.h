@@ -77,9 +77,12 @@ struct Problem {
   const void* bias;   // [k] float or int32, may be null
   void* y;            // output [M][k]
   void* partial;      // split-K partial sums [split_k][M][k] (float or int32), null when split_k == 1
-  const void* planes; // fp32 three-piece form: workspace for the bf16 planes of the input, then of the weights
+  const void* planes; // fp32 on the fp16 matrix cores: workspace for the input's planes (or only its partial maxima), then the weights' planes
   const void* w_packed; // the weights' planes as the caller made them ahead of time (glowmi_*_pack_filter), or null
   const void* w_planes; // where the kernel reads the weights' planes: w_packed, or inside `planes` (set by the launcher)
+  const unsigned* x_range; // x_range_n words whose largest is the bits of the input's largest magnitude (set by the launcher)
+  const unsigned* w_range; // one word: the same for the weights (the trailer of their planes)
+  int32_t x_range_n;
   const void* addend; // tensor operand of the element-wise chain [M][k] (float or int8), may be null:
                       // added to the accumulator after the bias and before the activation
   int32_t n, h, w_, c;
@@ -120,8 +123,8 @@ enum KernelKind {
   KERNEL_K3C64,         // 3x3 over 64 input channels (int8: conv_k3c64_i8.hip, fp32: conv_k3c64_f32.hip)
   KERNEL_FC_SMALL,      // FullyConnected with few rows in one launch (fp32: fc_small_f32.hip, int8: fc_small_i8.hip)
   KERNEL_WIDE,          // int8 large contractions (igemm_i8_wide.hip)
-  KERNEL_K3,            // fp32 3x3 stride-1 convolution on well-tiling maps, bf16 matrix cores (conv_k3_f32.hip)
-  KERNEL_P3             // fp32 large contractions on the bf16 matrix cores, operands cut into three pieces (igemm_f32_p3.hip)
+  KERNEL_K3,            // fp32 3x3 stride-1 convolution on well-tiling maps, fp16 matrix cores (conv_k3_f32.hip)
+  KERNEL_P3             // fp32 large contractions on the fp16 matrix cores, operands cut into two pieces (igemm_f32_p3.hip)
 };
 struct Plan {
   int kernel;           // KernelKind
@@ -155,21 +158,28 @@ int conv_small_f32_splits(const Problem& p);   // > 1: the split form of that ke
 // fp32 FullyConnected with few rows and a small weight matrix, in one launch (fc_small_f32.hip).
 bool fc_small_f32_applicable(const Problem& p);
 hipError_t launch_fc_small_f32(const Problem& p, hipStream_t stream, const char** variant);
-// fp32 large contractions as six bf16 MFMAs per product over operands cut into three bf16 planes (igemm_f32_p3.hip).
+// fp32 large contractions as three fp16 MFMAs per product over operands cut into two fp16 planes (igemm_f32_p3.hip).
 bool p3_f32_applicable(const Problem& p);
 Plan plan_p3_f32(const Problem& p);
 hipError_t launch_p3_f32(const Problem& p, const Plan& plan, hipStream_t stream, const char** variant);
-// Cuts `elems` (a multiple of 8) fp32 values into three bf16 planes of `elems` each at dst (igemm_f32_p3.hip).
-hipError_t launch_pack3_rows(const float* src, void* dst, long long elems, hipStream_t stream);
-// The weights' planes, the form every bf16 six-product kernel reads them in: three planes of w_elems bf16 each,
-// convolution filters in their own [k][r][s][cg] order, FullyConnected weights transposed to [N][K].
-// filter_planes_bytes: bytes of that form (a multiple of 256).  launch_pack_filter: writes it (b_is_kn: transposed).
-// stage_filter_planes: sets p.w_planes to the planes the caller made ahead of time (p.w_packed) or cuts the filter
-// into `dst` now and points there.
+// A tensor's largest magnitude is found as kRangeWords partial maxima (a pass over the tensor), reduced by whoever
+// needs it.  A tensor's planes: two fp16 planes of `elems` each, padded to 256 bytes, then a trailer of
+// kPlaneTrailerBytes (word 0: the bits of the largest magnitude, the second half: the partial maxima).
+constexpr int kRangeWords = 512;
+constexpr size_t kRangeBytes = 4 * (size_t)kRangeWords;
+constexpr size_t kPlaneTrailerBytes = 2 * kRangeBytes;
+// The weights' planes, the form every fp16 three-product kernel reads them in: convolution filters in their own
+// [k][r][s][cg] order, FullyConnected weights transposed to [N][K].
+// filter_planes_bytes: bytes of that form (a multiple of 256).  launch_pack_filter: measures and writes it
+// (b_is_kn: transposed).  stage_ranges_and_filter, for the kernels that cut the input themselves: measures the
+// input into the first kRangeBytes of `area` (p.x_range), and either takes the planes the caller made ahead of time
+// (p.w_packed) or measures and cuts the filter into the rest of `area`; sets p.w_planes / p.w_range.
+// ranges_and_filter_bytes: what `area` must hold.
 size_t filter_planes_bytes(size_t w_elems);
 hipError_t launch_pack_filter(const float* w, void* dst, int b_is_kn, int K, int N, long long w_elems, hipStream_t stream);
-hipError_t stage_filter_planes(Problem& p, const void* dst, hipStream_t stream);
-// fp32 3x3 stride-1 convolution over 64 input channels on many pixels, on the bf16 matrix cores (conv_k3c64_f32.hip).
+hipError_t stage_ranges_and_filter(Problem& p, const void* area, hipStream_t stream);
+size_t ranges_and_filter_bytes(const Problem& p);
+// fp32 3x3 stride-1 convolution over 64 input channels on many pixels, on the fp16 matrix cores (conv_k3c64_f32.hip).
 bool k3c64_f32_applicable(const Problem& p);
 size_t k3c64_f32_pack_bytes(const Problem& p);
 hipError_t launch_k3c64_f32(const Problem& p, hipStream_t stream, const char** variant);

@@ -675,8 +675,9 @@ Plan plan_f32(const Problem& p, bool allow_split) {
   if (!forced) {
     // kernels of their own, no workspace
     if (smallc_f32_applicable(p) && !p.addend) { pl.kernel = KERNEL_SMALLC; return pl; }
-    // 3x3 over 64 channels on many pixels, with the filter's planes given or room in the workspace for them
-    const bool filter_planes = p.w_packed != nullptr || (allow_split && p.allow_pack);   // given, or room to make them
+    // 3x3 over 64 channels on many pixels, with room in the workspace for the input's partial maxima and (unless
+    // the caller made them ahead of time) the filter's planes
+    const bool filter_planes = allow_split && p.allow_pack;
     if (filter_planes && k3c64_f32_applicable(p)) {
       pl.kernel = KERNEL_K3C64;
       pl.pack_bytes = k3c64_f32_pack_bytes(p);
@@ -688,7 +689,7 @@ Plan plan_f32(const Problem& p, bool allow_split) {
       pl.pack_bytes = k3_f32_pack_bytes(p);
       return pl;
     }
-    // large contractions with a workspace to repack the operands into: the bf16 three-piece kernel
+    // large contractions with a workspace to repack the operands into: the kernel over fp16 planes
     if (allow_split && p.allow_pack && p3_f32_applicable(p)) return plan_p3_f32(p);
     if (pw_f32_applicable(p)) { pl.kernel = KERNEL_PW; return pl; }
     if (conv_small_f32_applicable(p)) { pl.kernel = KERNEL_SMALL; return pl; }

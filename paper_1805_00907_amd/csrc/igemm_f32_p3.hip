@@ -1,26 +1,23 @@
-// fp32 Convolution / FullyConnected on the bf16 matrix cores, exact to fp32 level: the contraction of
+// fp32 Convolution / FullyConnected on the fp16 matrix cores, accurate to fp32 level: the contraction of
 // Section 3.4 / 3.1 of the paper (MatMul + broadcast add, the convolution loop nest) with every fp32
-// operand cut into three bf16 pieces first.
+// operand cut into two fp16 pieces first (f16_pieces.h).
 //
-//   x = hi + mid + lo exactly (mask off the upper 16 bits of the word, subtract, repeat: each piece
-//   keeps eight significant bits and every subtraction is exact), and a product x*y is taken as the six
-//   piece products down to weight 2^-16: hi*hi, hi*mid, mid*hi, mid*mid, hi*lo, lo*hi.
-//   v_mfma_f32_32x32x16_bf16 multiplies bf16 exactly and accumulates in fp32, so what is lost against an
-//   fp32 multiply-add chain is the dropped mid*lo, lo*mid, lo*lo (below 2^-22 of |x*y|, the size of the
-//   rounding an fp32 FMA makes anyway).  Six bf16 MFMAs cover 16 reduction steps of a 32 x 32 block in
-//   192 matrix-pipe cycles; v_mfma_f32_32x32x2_f32 needs 512 for the same.
+//   A tensor is scaled by a power of two taken from its largest magnitude (found by a pass over the tensor,
+//   range_kernel) and every scaled value v is cut into h1 = fp16(v) and H2 = fp16((v - h1) * 2^11); a product
+//   is taken as h1 h1' + 2^-11 (h1 H2' + H2 h1'): three v_mfma_f32_32x32x16_f16, which multiply fp16 exactly
+//   and accumulate in fp32, the cross terms in an accumulator set of their own.  What is lost against an fp32
+//   multiply-add chain is 2^-22 H2 H2' and the cuts' own rounding, each at most 2^-22 of |v v'|.  Three MFMAs
+//   cover 16 reduction steps of a 32 x 32 block in 96 matrix-pipe cycles; v_mfma_f32_32x32x2_f32 needs 512 for
+//   the same (and the earlier form of this kernel, three bf16 pieces and six products, 192).
 //
 // Cutting the operands inside the contraction kernel costs about six vector instructions per staged
 // element, again for every tile that stages it (a 3 x 3 layer stages each input element 9 x N/128
 // times), and measured that eats most of the gain.  So the pieces are made ONCE per call by a packing
-// pass into three bf16 planes per operand (workspace), FullyConnected weights ([K][N]) transposed to
+// pass into two fp16 planes per operand (workspace), FullyConnected weights ([K][N]) transposed to
 // K-contiguous on the way, and the contraction kernel has no vector ALU work in its loop at all:
 //   - 128 pixels x 64*WN channels per workgroup; 2 x WN wavefronts tile the output (64 x 64 each) and two such
-//     sets split every slab's 32 reduction indices between them (16 each): a wavefront then reads 512 bytes
-//     of fragments per MFMA, which together with the incoming slabs keeps LDS at three quarters of its
-//     bandwidth when the matrix pipes are full (64 x 32 per wavefront without the split needs all of it and
-//     was measured LDS-bound); the two partial tiles are exchanged through LDS at the end and each
-//     wavefront finishes half of them;
+//     sets split every slab's 32 reduction indices between them (16 each); the two partial tiles are
+//     exchanged through LDS at the end and each wavefront finishes half of them;
 //   - slabs of 32 reduction indices = one 64-byte row piece per plane, always inside one filter tap
 //     (channels per group are walked in steps of 32), so tap and channel offset are scalars;
 //   - both operands' planes go from global memory straight into LDS (buffer loads with the LDS bit) into a
@@ -29,14 +26,14 @@
 //   - lane l of a load fetches chunk (l % 4) ^ ((l / 16) % 4) of row l / 4: the four 16-byte chunks of a
 //     row are XOR-swizzled so that the 16 rows one phase of a fragment ds_read_b128 touches fall on 16
 //     different bank groups, without padding;
-//   - the epilogue is the fp32 one (bias, tensor add, Relu on the accumulators, one store), or partial
-//     tiles for a split reduction that the common finishing kernel sums in split order.
+//   - the epilogue is the fp32 one (the two accumulator sets joined and scaled back, bias, tensor add, Relu,
+//     one store), or partial tiles for a split reduction that the common finishing kernel sums in split order.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
 #include <type_traits>
 
-#include "bf16_pieces.h"
+#include "f16_pieces.h"
 #include "igemm.h"
 #include "lds_direct.h"
 
@@ -53,28 +50,102 @@ constexpr int P3_FLUSH = 32;             // accumulators are folded into a secon
 constexpr size_t kPlaneAlign = 256;
 
 // ------------------------------------------------------------------------------------------------
-// Packing: fp32 -> three bf16 planes
+// Range pass and packing: fp32 -> two fp16 planes
 // ------------------------------------------------------------------------------------------------
-// src: count8 groups of 8 consecutive floats; dst: three planes of plane_elems bf16 each, same order.
-__device__ __forceinline__ void pack3_rows(const float* __restrict__ src, unsigned short* __restrict__ dst,
-                                           long long count8, long long plane_elems, int block, int blocks) {
+// Largest magnitude of a tensor as kRangeWords partial maxima (bits of |v|, which order like the values; a NaN
+// orders above everything and so reaches the scale, where it turns the results into NaN as it should): workgroup
+// b of a tensor's kRangeWords walks float4 number b, b + kRangeWords, .. and writes word b.  No atomics and
+// nothing to clear beforehand; whoever needs the maximum takes the largest of the words (wave_max_words).
+__device__ __forceinline__ void range_part(const float* __restrict__ src, long long count4, unsigned* __restrict__ out,
+                                           int block, unsigned* red) {
+  unsigned m = 0;
+  const long long stride = (long long)kRangeWords * 256;
+  long long g = (long long)block * 256 + threadIdx.x;
+  for (; g + 3 * stride < count4; g += 4 * stride) {     // four loads in flight per thread
+    const v4u a = *reinterpret_cast<const v4u*>(src + 4 * g);
+    const v4u b = *reinterpret_cast<const v4u*>(src + 4 * (g + stride));
+    const v4u c = *reinterpret_cast<const v4u*>(src + 4 * (g + 2 * stride));
+    const v4u d = *reinterpret_cast<const v4u*>(src + 4 * (g + 3 * stride));
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const unsigned ma = a[e] & 0x7fffffffu, mb = b[e] & 0x7fffffffu, mc = c[e] & 0x7fffffffu, md = d[e] & 0x7fffffffu;
+      const unsigned m1 = ma > mb ? ma : mb, m2 = mc > md ? mc : md;
+      const unsigned m3 = m1 > m2 ? m1 : m2;
+      m = m3 > m ? m3 : m;
+    }
+  }
+  for (; g < count4; g += stride) {
+    const v4u a = *reinterpret_cast<const v4u*>(src + 4 * g);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const unsigned ma = a[e] & 0x7fffffffu;
+      m = ma > m ? ma : m;
+    }
+  }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const unsigned o = (unsigned)__shfl_xor((int)m, d, 64);
+    m = o > m ? o : m;
+  }
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned r = red[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) r = red[i] > r ? red[i] : r;
+    out[block] = r;
+  }
+}
+
+// One launch for both operands: workgroups 0 .. kRangeWords - 1 the input, the next kRangeWords the weights
+// (launched without them when the weights' planes were made ahead of time).
+__global__ __launch_bounds__(256) void range_kernel(const float* __restrict__ x, long long x_count4, unsigned* __restrict__ x_out,
+                                                    const float* __restrict__ w, long long w_count4, unsigned* __restrict__ w_out) {
+  __shared__ unsigned red[4];
+  const int b = (int)blockIdx.x;
+  if (b < kRangeWords) range_part(x, x_count4, x_out, b, red);
+  else range_part(w, w_count4, w_out, b - kRangeWords, red);
+}
+
+// The trailer behind a tensor's two planes: word 0 holds the bits of the tensor's largest magnitude (what the
+// planes were scaled by follows from it), words kRangeWords .. 2 kRangeWords - 1 the partial maxima the range pass
+// left there.
+__device__ __forceinline__ int take_scale(const unsigned* __restrict__ trailer, bool publish) {
+  __shared__ int se_shared;
+  if (threadIdx.x < 64) {                                // the first wavefront reduces, the others wait for it
+    const unsigned mx = wave_max_words(trailer + kRangeWords, kRangeWords);
+    if (threadIdx.x == 0) {
+      se_shared = scale_exponent(mx);
+      if (publish) const_cast<unsigned*>(trailer)[0] = mx;
+    }
+  }
+  __syncthreads();
+  return se_shared;
+}
+
+// src: count8 groups of 8 consecutive floats; dst: two planes of plane_elems fp16 each, same order.
+__device__ __forceinline__ void pack2_rows(const float* __restrict__ src, unsigned short* __restrict__ dst,
+                                           long long count8, long long plane_elems, int block, int blocks,
+                                           unsigned* __restrict__ trailer) {
+  const int se = take_scale(trailer, block == 0);
   const long long stride = (long long)blocks * 256;
   for (long long g = (long long)block * 256 + threadIdx.x; g < count8; g += stride) {
     const v4f a = *reinterpret_cast<const v4f*>(src + 8 * g);
     const v4f b = *reinterpret_cast<const v4f*>(src + 8 * g + 4);
     const float v[8] = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
-    v4u h, m, l;
-    split8(v, h, m, l);
-    *reinterpret_cast<v4u*>(dst + 8 * g) = h;
-    *reinterpret_cast<v4u*>(dst + plane_elems + 8 * g) = m;
-    *reinterpret_cast<v4u*>(dst + 2 * plane_elems + 8 * g) = l;
+    v4u p1, p2;
+    cut8(v, se, p1, p2);
+    *reinterpret_cast<v4u*>(dst + 8 * g) = p1;
+    *reinterpret_cast<v4u*>(dst + plane_elems + 8 * g) = p2;
   }
 }
 
-// FullyConnected weight [K][N] (N contiguous) -> three planes [N][K] (K contiguous).  K % 8 == 0.
+// FullyConnected weight [K][N] (N contiguous) -> two planes [N][K] (K contiguous).  K % 8 == 0.
 // One workgroup per 64 (k) x 32 (n) tile, transposed through LDS.
-__device__ __forceinline__ void pack3_transposed(const float* __restrict__ w, unsigned short* __restrict__ dst, int K, int N,
-                                                 int tiles_n, int block, float (&tile)[64][33]) {
+__device__ __forceinline__ void pack2_transposed(const float* __restrict__ w, unsigned short* __restrict__ dst, int K, int N,
+                                                 int tiles_n, int block, float (&tile)[64][33],
+                                                 unsigned* __restrict__ trailer) {
+  const int se = take_scale(trailer, block == 0);
   const int tk = block / tiles_n, tn = block - tk * tiles_n;
   const int k0 = tk * 64, n0 = tn * 32;
   const int tid = threadIdx.x;
@@ -92,38 +163,39 @@ __device__ __forceinline__ void pack3_transposed(const float* __restrict__ w, un
   float v[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) v[e] = tile[kc * 8 + e][n];
-  v4u h, m, l;
-  split8(v, h, m, l);
+  v4u p1, p2;
+  cut8(v, se, p1, p2);
   const size_t plane = (size_t)K * N;
   unsigned short* o = dst + (size_t)(n0 + n) * K + k0 + kc * 8;
-  *reinterpret_cast<v4u*>(o) = h;
-  *reinterpret_cast<v4u*>(o + plane) = m;
-  *reinterpret_cast<v4u*>(o + 2 * plane) = l;
+  *reinterpret_cast<v4u*>(o) = p1;
+  *reinterpret_cast<v4u*>(o + plane) = p2;
 }
 
-__global__ __launch_bounds__(256) void pack3_rows_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
-                                                         long long count8, long long plane_elems) {
-  pack3_rows(src, dst, count8, plane_elems, (int)blockIdx.x, (int)gridDim.x);
+__global__ __launch_bounds__(256) void pack2_rows_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
+                                                         long long count8, long long plane_elems,
+                                                         unsigned* __restrict__ trailer) {
+  pack2_rows(src, dst, count8, plane_elems, (int)blockIdx.x, (int)gridDim.x, trailer);
 }
 
-__global__ __launch_bounds__(256) void pack3_transposed_kernel(const float* __restrict__ w, unsigned short* __restrict__ dst,
-                                                               int K, int N, int tiles_n) {
+__global__ __launch_bounds__(256) void pack2_transposed_kernel(const float* __restrict__ w, unsigned short* __restrict__ dst,
+                                                               int K, int N, int tiles_n, unsigned* __restrict__ trailer) {
   __shared__ float tile[64][33];
-  pack3_transposed(w, dst, K, N, tiles_n, (int)blockIdx.x, tile);
+  pack2_transposed(w, dst, K, N, tiles_n, (int)blockIdx.x, tile, trailer);
 }
 
 // Both operands of one contraction in one launch: the first blocks_x workgroups cut the input, the rest the
 // weights, either in their own order or (FullyConnected, transposed != 0) one 64 x 32 tile per workgroup.
-__global__ __launch_bounds__(256) void pack3_pair_kernel(const float* __restrict__ x, unsigned short* __restrict__ xp,
+__global__ __launch_bounds__(256) void pack2_pair_kernel(const float* __restrict__ x, unsigned short* __restrict__ xp,
                                                          long long x_count8, long long x_elems, int blocks_x,
+                                                         unsigned* __restrict__ x_trailer,
                                                          const float* __restrict__ w, unsigned short* __restrict__ wp,
                                                          long long w_count8, long long w_elems, int transposed, int K,
-                                                         int N, int tiles_n) {
+                                                         int N, int tiles_n, unsigned* __restrict__ w_trailer) {
   __shared__ float tile[64][33];
   const int b = (int)blockIdx.x;
-  if (b < blocks_x) pack3_rows(x, xp, x_count8, x_elems, b, blocks_x);
-  else if (transposed) pack3_transposed(w, wp, K, N, tiles_n, b - blocks_x, tile);
-  else pack3_rows(w, wp, w_count8, w_elems, b - blocks_x, (int)gridDim.x - blocks_x);
+  if (b < blocks_x) pack2_rows(x, xp, x_count8, x_elems, b, blocks_x, x_trailer);
+  else if (transposed) pack2_transposed(w, wp, K, N, tiles_n, b - blocks_x, tile, w_trailer);
+  else pack2_rows(w, wp, w_count8, w_elems, b - blocks_x, (int)gridDim.x - blocks_x, w_trailer);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -139,9 +211,9 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
   constexpr int WAVES = 4 * WN;
   constexpr int A_GROUPS = (PBM / 16) / WAVES;          // 16-row groups of the pixel tile one wavefront loads per plane
   static_assert(A_GROUPS * WAVES * 16 == PBM && WAVES * 16 == BN, "rows divide over the wavefronts");
-  constexpr int LPI = 3 * (A_GROUPS + 1);               // loads one wavefront issues per slab
+  constexpr int LPI = 2 * (A_GROUPS + 1);               // loads one wavefront issues per slab
   constexpr int A_PLANE = PBM * PROW, B_PLANE = BN * PROW;
-  constexpr int BUF = 3 * (A_PLANE + B_PLANE);
+  constexpr int BUF = 2 * (A_PLANE + B_PLANE);
   static_assert(NBUF * BUF >= WAVES * 32 * 64 * 4, "exchange of the partial tiles fits the slab buffers");
 
   extern __shared__ __align__(16) unsigned char lds[];
@@ -169,10 +241,12 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
   const int wm = (wave / WN) & 1, wn = wave % WN;
   const int lrow = lane & 31, lhalf = lane >> 5;
 
-  const unsigned xpb = p.x_bytes >> 1, wpb = p.w_bytes >> 1;          // bytes of one bf16 plane
-  const v4i rsrc_x = make_rsrc(p.planes, 3u * xpb);
-  const v4i rsrc_w = make_rsrc(p.w_planes, 3u * wpb);
-  constexpr unsigned OOB = 0x80000000u;   // planes are at most 512 MiB each: OOB + 2 planes neither wraps nor lands inside
+  const unsigned xpb = p.x_bytes >> 1, wpb = p.w_bytes >> 1;          // bytes of one fp16 plane
+  const v4i rsrc_x = make_rsrc(p.planes, 2u * xpb);
+  const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
+  constexpr unsigned OOB = 0x80000000u;   // planes are at most 512 MiB each: OOB + a plane neither wraps nor lands inside
+  // what the two accumulator sets are scaled back by: the operands' scale exponents, from their largest magnitudes
+  const int neg_se = -(scale_exponent(wave_max_words(p.x_range, p.x_range_n)) + scale_exponent(wave_max_words(p.w_range, 1)));
 
   const int spt = (p.cg + PBK - 1) / PBK;               // slabs per filter tap
   const int total_slabs = p.r * p.s * spt;
@@ -245,9 +319,9 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
     }
   };
   auto issue_piece = [&](int j) {                        // j = 0 .. LPI - 1, compile-time
-    const int pc = j % 3, t = j / 3;
+    const int pc = j % 2, t = j / 2;
     if (t < A_GROUPS) load16_to_lds(rsrc_x, is_lds + pc * A_PLANE + t * WAVES * 16 * PROW, is_a[t] + pc * xpb);
-    else load16_to_lds(rsrc_w, is_lds + 3 * A_PLANE + pc * B_PLANE, is_b + pc * wpb);
+    else load16_to_lds(rsrc_w, is_lds + 2 * A_PLANE + pc * B_PLANE, is_b + pc * wpb);
   };
   auto issue = [&](int buf) {
     issue_prepare(buf);
@@ -255,8 +329,9 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
     for (int j = 0; j < LPI; ++j) issue_piece(j);
   };
 
-  // acc[i][j]: 32 pixels (rows of the MFMA result) x 32 channels (columns, one per lane)
-  v16f acc[2][2], total[LONGK ? 2 : 1][LONGK ? 2 : 1];
+  // acc[i][j]: 32 pixels (rows of the MFMA result) x 32 channels (columns, one per lane); acc the h1 h1' products,
+  // acc_lo the cross terms (weight 2^-11)
+  v16f acc[2][2], acc_lo[2][2], total[LONGK ? 2 : 1][LONGK ? 2 : 1];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -264,37 +339,39 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         acc[i][j][e] = 0.f;
+        acc_lo[i][j][e] = 0.f;
         if (LONGK) total[i][j][e] = 0.f;
       }
 
   // a lane holds 8 consecutive reduction indices of its row: chunk 2 * kgrp + lhalf, stored at chunk ^ swz(row)
   const int pos = ((kgrp * 2 + lhalf) ^ ((lrow >> 2) & 3)) << 4;
   const int frag_a = (wm * 64 + lrow) * PROW + pos;
-  const int frag_b = 3 * A_PLANE + (wn * 64 + lrow) * PROW + pos;
-  // All fragments of a slab are read up front (12 ds_read_b128) in the order the MFMAs use them, and the
+  const int frag_b = 2 * A_PLANE + (wn * 64 + lrow) * PROW + pos;
+  // All fragments of a slab are read up front (8 ds_read_b128) in the order the MFMAs use them, and the
   // refill loads are dealt out between the MFMAs.
   auto trip = [&](int buf, int refill_buf) {
     const unsigned char* base = lds + buf * BUF;
-    v8bf a[3][2], b[3][2];
-    constexpr int ORDER_A[3] = {2, 0, 1}, ORDER_B[3] = {0, 2, 1};
+    v8h a[2][2], b[2][2];
 #pragma unroll
-    for (int o = 0; o < 3; ++o) {
-      const int pa = ORDER_A[o], pb = ORDER_B[o];
+    for (int o = 0; o < 2; ++o) {
+      const int pa = o, pb = 1 - o;                       // the cross terms come first: a1 with b2, then a2 with b1
 #pragma unroll
       for (int i = 0; i < 2; ++i)
-        a[pa][i] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(base + pa * A_PLANE + frag_a + i * 32 * PROW));
+        a[pa][i] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(base + pa * A_PLANE + frag_a + i * 32 * PROW));
 #pragma unroll
       for (int j = 0; j < 2; ++j)
-        b[pb][j] = __builtin_bit_cast(v8bf, *reinterpret_cast<const v4i*>(base + pb * B_PLANE + frag_b + j * 32 * PROW));
+        b[pb][j] = __builtin_bit_cast(v8h, *reinterpret_cast<const v4i*>(base + pb * B_PLANE + frag_b + j * 32 * PROW));
     }
     issue_prepare(refill_buf);
     __builtin_amdgcn_sched_barrier(0);
-    constexpr int MFMAS = 6 * 4, EVERY = MFMAS / LPI;   // 24 MFMAs, a load after every EVERY of them
+    constexpr int MFMAS = 3 * 4, EVERY = MFMAS / LPI;   // 12 MFMAs, a load after every EVERY of them
     static_assert(EVERY >= 1, "more loads than MFMAs");
 #pragma unroll
     for (int q = 0; q < MFMAS; ++q) {
       const int t = q / 4, i = (q / 2) % 2, j = q % 2;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[t]][i], b[kPieceTermB[t]][j], acc[i][j], 0, 0, 0);
+      if (t == 0) acc_lo[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], b[1][j], acc_lo[i][j], 0, 0, 0);
+      else if (t == 1) acc_lo[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[1][i], b[0][j], acc_lo[i][j], 0, 0, 0);
+      else acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], b[0][j], acc[i][j], 0, 0, 0);
       if (q % EVERY == EVERY - 1 && q / EVERY < LPI) {
         __builtin_amdgcn_sched_barrier(0);
         issue_piece(q / EVERY);
@@ -324,9 +401,12 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
             for (int i = 0; i < 2; ++i)
 #pragma unroll
               for (int j = 0; j < 2; ++j) {
-                total[i][j] += acc[i][j];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+                for (int e = 0; e < 16; ++e) {
+                  total[i][j][e] += __builtin_fmaf(acc_lo[i][j][e], kLowPieceWeight, acc[i][j][e]);
+                  acc[i][j][e] = 0.f;
+                  acc_lo[i][j][e] = 0.f;
+                }
               }
           }
         }
@@ -348,8 +428,13 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
       constexpr int KG = decltype(kg_tag)::value;         // sends block row 1 - KG, keeps block row KG
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        v16f snd = acc[1 - KG][j];
-        keep[j] = acc[KG][j];
+        v16f snd, kp;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {                   // the two accumulator sets joined
+          snd[e] = __builtin_fmaf(acc_lo[1 - KG][j][e], kLowPieceWeight, acc[1 - KG][j][e]);
+          kp[e] = __builtin_fmaf(acc_lo[KG][j][e], kLowPieceWeight, acc[KG][j][e]);
+        }
+        keep[j] = kp;
         if (LONGK) {
           snd += total[1 - KG][j];
           keep[j] += total[KG][j];
@@ -368,7 +453,7 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
       for (int e4 = 0; e4 < 4; ++e4) {
         const v4f got = xch[(theirs + j * 4 + e4) * 64 + lane];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) keep[j][e4 * 4 + t] += got[t];
+        for (int t = 0; t < 4; ++t) keep[j][e4 * 4 + t] = __builtin_ldexpf(keep[j][e4 * 4 + t] + got[t], neg_se);   // scaled back
       }
   }
 
@@ -406,7 +491,7 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
 template <int WN, bool PADDED, bool LONGK, int NBUF>
 hipError_t launch_p3_variant(const Problem& p, const Plan& plan, hipStream_t stream) {
   auto kern = igemm_f32_p3_kernel<WN, PADDED, LONGK, NBUF>;
-  constexpr int lds_bytes = NBUF * 3 * (PBM + 64 * WN) * PROW;
+  constexpr int lds_bytes = NBUF * 2 * (PBM + 64 * WN) * PROW;
   static const hipError_t attr_status = hipFuncSetAttribute(
       reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
   if (attr_status != hipSuccess) return attr_status;
@@ -432,38 +517,72 @@ size_t align_up(size_t v) { return (v + kPlaneAlign - 1) / kPlaneAlign * kPlaneA
 
 }  // namespace
 
-hipError_t launch_pack3_rows(const float* src, void* dst, long long elems, hipStream_t stream) {
-  const long long c8 = elems / 8;
-  long long blocks = (c8 + 255) / 256;
-  if (blocks > 8192) blocks = 8192;
-  if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(pack3_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, src, static_cast<unsigned short*>(dst), c8, elems);
+// A tensor's planes in memory: two fp16 planes of `elems` each, padded to 256 bytes, then the trailer.
+size_t tensor_planes_bytes(size_t elems) { return align_up(4 * elems) + kPlaneTrailerBytes; }
+size_t filter_planes_bytes(size_t w_elems) { return tensor_planes_bytes(w_elems); }
+unsigned* planes_trailer(const void* planes, size_t elems) {
+  return reinterpret_cast<unsigned*>(static_cast<unsigned char*>(const_cast<void*>(planes)) + align_up(4 * elems));
+}
+
+hipError_t launch_ranges(const float* x, long long x_elems, unsigned* x_out, const float* w, long long w_elems,
+                         unsigned* w_out, hipStream_t stream) {
+  const unsigned blocks = (unsigned)kRangeWords * (w ? 2u : 1u);
+  hipLaunchKernelGGL(range_kernel, dim3(blocks), dim3(256), 0, stream, x, x_elems / 4, x_out, w, w_elems / 4, w_out);
   return hipGetLastError();
 }
 
-size_t filter_planes_bytes(size_t w_elems) { return align_up(6 * w_elems); }
-
-hipError_t launch_pack_filter(const float* w, void* dst, int b_is_kn, int K, int N, long long w_elems, hipStream_t stream) {
-  if (!b_is_kn) return launch_pack3_rows(w, dst, w_elems, stream);
+namespace {
+// Cuts the weights whose partial maxima already lie in the trailer of dst.
+hipError_t launch_cut_filter(const float* w, void* dst, int b_is_kn, int K, int N, long long w_elems, hipStream_t stream) {
+  unsigned* trailer = planes_trailer(dst, (size_t)w_elems);
+  if (!b_is_kn) {
+    const long long c8 = w_elems / 8;
+    long long blocks = (c8 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(pack2_rows_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, static_cast<unsigned short*>(dst), c8,
+                       w_elems, trailer);
+    return hipGetLastError();
+  }
   const int tn = (N + 31) / 32;
   const long long blocks = (long long)((K + 63) / 64) * tn;
-  hipLaunchKernelGGL(pack3_transposed_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, static_cast<unsigned short*>(dst), K, N, tn);
+  hipLaunchKernelGGL(pack2_transposed_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, static_cast<unsigned short*>(dst), K,
+                     N, tn, trailer);
   return hipGetLastError();
 }
+}  // namespace
 
-hipError_t stage_filter_planes(Problem& p, const void* dst, hipStream_t stream) {
-  if (p.w_packed) {
-    p.w_planes = p.w_packed;
-    return hipSuccess;
-  }
-  if (!dst) return hipErrorInvalidValue;                // the ABI layer never plans these kernels without a workspace
-  p.w_planes = dst;
-  return launch_pack_filter(static_cast<const float*>(p.w), const_cast<void*>(dst), p.b_is_kn, p.Kgemm, p.k,
-                            (long long)(p.w_bytes >> 2), stream);
+hipError_t launch_pack_filter(const float* w, void* dst, int b_is_kn, int K, int N, long long w_elems, hipStream_t stream) {
+  const hipError_t e = launch_ranges(w, w_elems, planes_trailer(dst, (size_t)w_elems) + kRangeWords, nullptr, 0, nullptr, stream);
+  if (e != hipSuccess) return e;
+  return launch_cut_filter(w, dst, b_is_kn, K, N, w_elems, stream);
 }
 
+// For the kernels that cut the input themselves (conv_k3*_f32): `area` starts with the kRangeBytes that take the
+// input's partial maxima, the weights' planes follow unless the caller made them ahead of time.
+hipError_t stage_ranges_and_filter(Problem& p, const void* area, hipStream_t stream) {
+  if (!area) return hipErrorInvalidValue;               // the ABI layer never plans these kernels without a workspace
+  unsigned* x_out = static_cast<unsigned*>(const_cast<void*>(area));
+  const long long x_elems = (long long)(p.x_bytes >> 2), w_elems = (long long)(p.w_bytes >> 2);
+  p.x_range = x_out;
+  p.x_range_n = kRangeWords;
+  if (p.w_packed) {
+    p.w_planes = p.w_packed;
+    p.w_range = planes_trailer(p.w_packed, (size_t)w_elems);
+    return launch_ranges(static_cast<const float*>(p.x), x_elems, x_out, nullptr, 0, nullptr, stream);
+  }
+  void* dst = static_cast<unsigned char*>(const_cast<void*>(area)) + kRangeBytes;
+  p.w_planes = dst;
+  p.w_range = planes_trailer(dst, (size_t)w_elems);
+  hipError_t e = launch_ranges(static_cast<const float*>(p.x), x_elems, x_out, static_cast<const float*>(p.w), w_elems,
+                               planes_trailer(dst, (size_t)w_elems) + kRangeWords, stream);
+  if (e != hipSuccess) return e;
+  return launch_cut_filter(static_cast<const float*>(p.w), dst, p.b_is_kn, p.Kgemm, p.k, w_elems, stream);
+}
+size_t ranges_and_filter_bytes(const Problem& p) { return kRangeBytes + (p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2)); }
+
 size_t p3_pack_bytes(const Problem& p) {
-  return align_up(3 * (size_t)(p.x_bytes >> 1)) + (p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2));
+  return tensor_planes_bytes(p.x_bytes >> 2) + (p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2));
 }
 
 // Worth it when the contraction is large against the one-off cost of cutting both operands (about ten bytes
@@ -543,19 +662,31 @@ hipError_t launch_p3_f32(const Problem& p_in, const Plan& plan, hipStream_t stre
   p.slabs_per_split = plan.slabs_per_split;
   const size_t x_elems = p.x_bytes >> 2, w_elems = p.w_bytes >> 2;
   unsigned short* xp = static_cast<unsigned short*>(const_cast<void*>(p.planes));
-  unsigned short* wp = reinterpret_cast<unsigned short*>(reinterpret_cast<unsigned char*>(xp) + align_up(3 * x_elems * 2));
+  unsigned short* wp = reinterpret_cast<unsigned short*>(reinterpret_cast<unsigned char*>(xp) + tensor_planes_bytes(x_elems));
+  unsigned* x_trailer = planes_trailer(xp, x_elems);
+  p.x_range = x_trailer;                                // word 0, written by the packing kernel
+  p.x_range_n = 1;
+  const long long xc8 = (long long)(x_elems / 8), wc8 = (long long)(w_elems / 8);
+  long long bx = (xc8 + 255) / 256;
+  if (bx > 8192) bx = 8192;
+  if (bx < 1) bx = 1;
+  hipError_t e;
   if (p.w_packed) {
-    // ---- the weights' planes were made ahead of time: only the input is cut
+    // ---- the weights' planes were made ahead of time: only the input is measured and cut
     p.w_planes = p.w_packed;
-    const hipError_t e = launch_pack3_rows(static_cast<const float*>(p.x), xp, (long long)x_elems, stream);
+    p.w_range = planes_trailer(p.w_packed, w_elems);
+    e = launch_ranges(static_cast<const float*>(p.x), (long long)x_elems, x_trailer + kRangeWords, nullptr, 0, nullptr, stream);
     if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(pack2_rows_kernel, dim3((unsigned)bx), dim3(256), 0, stream, static_cast<const float*>(p.x), xp, xc8,
+                       (long long)x_elems, x_trailer);
   } else {
-    // ---- cut both operands into planes, one launch
+    // ---- both operands: one launch for their largest magnitudes, one that cuts them into planes
     p.w_planes = wp;
-    const long long xc8 = (long long)(x_elems / 8), wc8 = (long long)(w_elems / 8);
-    long long bx = (xc8 + 255) / 256;
-    if (bx > 8192) bx = 8192;
-    if (bx < 1) bx = 1;
+    unsigned* w_trailer = planes_trailer(wp, w_elems);
+    p.w_range = w_trailer;
+    e = launch_ranges(static_cast<const float*>(p.x), (long long)x_elems, x_trailer + kRangeWords,
+                      static_cast<const float*>(p.w), (long long)w_elems, w_trailer + kRangeWords, stream);
+    if (e != hipSuccess) return e;
     long long bw;
     int tn = 0;
     if (p.b_is_kn) {
@@ -566,11 +697,11 @@ hipError_t launch_p3_f32(const Problem& p_in, const Plan& plan, hipStream_t stre
       if (bw > 4096) bw = 4096;
       if (bw < 1) bw = 1;
     }
-    hipLaunchKernelGGL(pack3_pair_kernel, dim3((unsigned)(bx + bw)), dim3(256), 0, stream, static_cast<const float*>(p.x), xp,
-                       xc8, (long long)x_elems, (int)bx, static_cast<const float*>(p.w), wp, wc8, (long long)w_elems,
-                       p.b_is_kn, p.Kgemm, p.k, tn);
+    hipLaunchKernelGGL(pack2_pair_kernel, dim3((unsigned)(bx + bw)), dim3(256), 0, stream, static_cast<const float*>(p.x), xp,
+                       xc8, (long long)x_elems, (int)bx, x_trailer, static_cast<const float*>(p.w), wp, wc8,
+                       (long long)w_elems, p.b_is_kn, p.Kgemm, p.k, tn, w_trailer);
   }
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
   // ---- the contraction
   const bool padded = p.pad_t != 0 || p.pad_l != 0 || (p.oh - 1) * p.stride_h - p.pad_t + p.r > p.h ||

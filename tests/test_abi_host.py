@@ -330,48 +330,52 @@ def test_workspace_queries_are_pure():
     assert glowmi.fc_workspace_bytes(16, 4096, 4096) > 0
     assert glowmi.fc_workspace_bytes(40, 2048, 1000) == 0
     assert glowmi.fc_workspace_bytes(0, 1, 1) == 0
-    # a large contraction asks for room to repack both operands as three bf16 planes (6 bytes per element,
-    # each operand's planes rounded up to 256 bytes); with that kernel switched off, plenty of tiles: no split
+    # a large contraction asks for room to repack both operands as two fp16 planes (4 bytes per element, each
+    # operand's planes rounded up to 256 bytes, plus a 4 KB trailer: the largest magnitude and the partial maxima
+    # it was taken from); with that kernel switched off, plenty of tiles: no split
     up = lambda v: (v + 255) // 256 * 256
+    planes_of = lambda elems: up(4 * elems) + 4096
     big = glowmi.ConvDesc(16, 14, 14, 512, 512, 3, 3, 1, 1, 1, 1, 1, 1, 1)
     x_elems, w_elems, y_elems = 16 * 14 * 14 * 512, 512 * 3 * 3 * 512, 16 * 14 * 14 * 512
     need = glowmi.conv2d_workspace_bytes(big)
-    planes = up(6 * x_elems) + up(6 * w_elems)
+    planes = planes_of(x_elems) + planes_of(w_elems)
     assert need >= planes and (need - planes) % (4 * y_elems) == 0    # + the partial sums of a split reduction
     glowmi.tuning_set("F32_P3", 0)
     try:
         assert glowmi.conv2d_workspace_bytes(big) % (4 * y_elems) == 0     # partial sums only
     finally:
         glowmi.tuning_reset()
-    # 3x3 stride 1 on maps that tile into 16 x 16 blocks: only the filter is repacked
+    # 3x3 stride 1 on maps that tile into 16 x 16 blocks: only the filter is repacked; the input leaves 2 KB of
+    # partial maxima
     vgg2 = glowmi.ConvDesc(16, 112, 112, 128, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1)
-    assert glowmi.conv2d_workspace_bytes(vgg2) == up(6 * 128 * 3 * 3 * 128)
-    # 3x3 over 64 channels on many pixels: only the filter is repacked
+    assert glowmi.conv2d_workspace_bytes(vgg2) == 2048 + planes_of(128 * 3 * 3 * 128)
+    # 3x3 over 64 channels on many pixels: likewise
     c64 = glowmi.ConvDesc(16, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1)
-    assert glowmi.conv2d_workspace_bytes(c64) == up(6 * 64 * 3 * 3 * 64)
+    assert glowmi.conv2d_workspace_bytes(c64) == 2048 + planes_of(64 * 3 * 3 * 64)
     # a FullyConnected too small to pay for the repacking never asks for it
-    assert glowmi.fc_workspace_bytes(128, 4096, 4096) < 6 * (128 * 4096 + 4096 * 4096)
+    assert glowmi.fc_workspace_bytes(128, 4096, 4096) < 4 * (128 * 4096 + 4096 * 4096)
 
 
 def test_packed_filter_queries_and_errors():
     """Filters transformed ahead of time: sizes, and every refusal happens before a launch."""
     up = lambda v: (v + 255) // 256 * 256
+    planes_of = lambda elems: up(4 * elems) + 4096                    # two fp16 planes and the trailer
     vgg2 = glowmi.ConvDesc(16, 112, 112, 128, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1)
-    assert glowmi.conv2d_filter_planes_bytes(vgg2) == up(6 * 128 * 3 * 3 * 128)
-    assert glowmi.conv2d_packed_workspace_bytes(vgg2) == 0            # the tile kernel needs nothing else
+    assert glowmi.conv2d_filter_planes_bytes(vgg2) == planes_of(128 * 3 * 3 * 128)
+    assert glowmi.conv2d_packed_workspace_bytes(vgg2) == 2048         # the tile kernel: the input's partial maxima only
     big = glowmi.ConvDesc(32, 7, 7, 512, 512, 3, 3, 1, 1, 1, 1, 1, 1, 1)
     planes = glowmi.conv2d_filter_planes_bytes(big)
-    assert planes == up(6 * 512 * 3 * 3 * 512)
+    assert planes == planes_of(512 * 3 * 3 * 512)
     assert glowmi.conv2d_packed_workspace_bytes(big) == glowmi.conv2d_workspace_bytes(big) - planes
     first = glowmi.ConvDesc(1, 224, 224, 3, 64, 7, 7, 2, 2, 3, 3, 3, 3, 1)       # 3 channels: no plane form
     assert glowmi.conv2d_filter_planes_bytes(first) == 0
     assert glowmi.conv2d_packed_workspace_bytes(first) == glowmi.conv2d_workspace_bytes(first)
     assert glowmi.conv2d_filter_planes_bytes(glowmi.ConvDesc(1, 4, 4, 8, 8, 5, 5, 1, 1, 0, 0, 0, 0, 1)) == 0   # bad desc
-    assert glowmi.fc_filter_planes_bytes(4096, 1000) == up(6 * 4096 * 1000)
+    assert glowmi.fc_filter_planes_bytes(4096, 1000) == planes_of(4096 * 1000)
     assert glowmi.fc_filter_planes_bytes(4100, 4096) == 0             # K not a multiple of 8
     assert glowmi.fc_filter_planes_bytes(0, 8) == 0
-    # with the weights' planes given, a FullyConnected of 256 rows is worth the bf16 kernel: room for the input's planes
-    assert glowmi.fc_packed_workspace_bytes(256, 4096, 4096) >= up(6 * 256 * 4096)
+    # with the weights' planes given, a FullyConnected of 256 rows is worth the kernel over planes: room for the input's planes
+    assert glowmi.fc_packed_workspace_bytes(256, 4096, 4096) >= planes_of(256 * 4096)
     assert glowmi.fc_packed_workspace_bytes(1024, 9216, 4096) == \
         glowmi.fc_workspace_bytes(1024, 9216, 4096) - glowmi.fc_filter_planes_bytes(9216, 4096)
     lib = glowmi.library()
@@ -386,7 +390,7 @@ def test_packed_filter_queries_and_errors():
     assert lib.glowmi_fc_packed(FAKE, FAKE, FAKE, None, FAKE, 64, 4100, 64, 0, None, 0, 0) == 3
     assert lib.glowmi_fc_packed(FAKE, FAKE, FAKE + 2, None, FAKE, 64, 4096, 64, 0, None, 0, 0) == 4
     assert lib.glowmi_conv2d_pack_filter(FAKE, ctypes.byref(first), FAKE, 1 << 20, 0) == 3
-    assert lib.glowmi_conv2d_pack_filter(FAKE, ctypes.byref(vgg2), FAKE, up(6 * 128 * 9 * 128) - 1, 0) == 2   # buffer too small
+    assert lib.glowmi_conv2d_pack_filter(FAKE, ctypes.byref(vgg2), FAKE, planes_of(128 * 9 * 128) - 1, 0) == 2   # buffer too small
     assert lib.glowmi_conv2d_pack_filter(None, ctypes.byref(vgg2), FAKE, 1 << 30, 0) == 1
     assert lib.glowmi_conv2d_pack_filter(FAKE, ctypes.byref(vgg2), FAKE + 4, 1 << 30, 0) == 4
     assert lib.glowmi_fc_pack_filter(FAKE, 4100, 64, FAKE, 1 << 30, 0) == 3

@@ -57,11 +57,11 @@ def _case(i):
 
 def _expected_variant(k, form, variant):
     if k <= 64:
-        return variant == "conv_k3_f32_bf16x6_16x32x64"
+        return variant == "conv_k3_f32_f16x3_16x32x64"
     if form == "fixed":
-        return variant == "conv_k3_f32_bf16x6"
+        return variant == "conv_k3_f32_f16x3"
     # the tile shape picked for the layer; a pick of 16 x 16 goes to the fixed-tile kernel
-    return re.fullmatch(r"conv_k3_f32_bf16x6(_\d+x\d+)?", variant) is not None
+    return re.fullmatch(r"conv_k3_f32_f16x3(_\d+x\d+)?", variant) is not None
 
 
 @pytest.mark.parametrize("i", range(len(SHAPES)))
@@ -100,9 +100,9 @@ def test_conv_k3_f32_every_tile_shape(i, shape, knobs):
     ref = oracle.conv2d_f32(x, wt, b, (1, 1), pd, 1, act=wl.ACT_RELU)
     got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)
     if (th, tw) == (40, 40):                # not a shape the kernel has (more than 256 pixels): the planner's own pick
-        assert re.fullmatch(r"conv_k3_f32_bf16x6(_\d+x\d+)?", variant), variant
+        assert re.fullmatch(r"conv_k3_f32_f16x3(_\d+x\d+)?", variant), variant
     else:
-        assert variant == f"conv_k3_f32_bf16x6_{th}x{tw}", variant
+        assert variant == f"conv_k3_f32_f16x3_{th}x{tw}", variant
     G.assert_close_f32(got, ref, f"case {i} tile {th}x{tw}")
 
 
@@ -118,7 +118,7 @@ def test_conv_k3_f32_tensor_add_link(i, in_place, knobs):
     ref = oracle.conv2d_f32_add(x, wt, b, add, (1, 1), pd, 1, act=wl.ACT_RELU)
     got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, G.make_desc(x.shape, wt.shape, (1, 1), pd, 1), wl.ACT_RELU,
                                           in_place=in_place)
-    assert variant.startswith("conv_k3_f32_bf16x6") and variant.endswith("_add"), variant
+    assert variant.startswith("conv_k3_f32_f16x3") and variant.endswith("_add"), variant
     G.assert_close_f32(got, ref, f"case {i} add link in_place {in_place}")
 
 

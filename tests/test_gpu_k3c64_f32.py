@@ -54,7 +54,7 @@ def test_conv_k3c64_f32(i, knobs):
     for act, bias in ((wl.ACT_RELU, b), (wl.ACT_NONE, None)):
         ref = oracle.conv2d_f32(x, wt, bias, (1, 1), pd, 1, act=act)
         got, variant = G.gpu_conv2d_f32(x, wt, bias, desc, act)
-        assert variant == "conv_k3c64_f32_bf16x6", variant
+        assert variant == "conv_k3c64_f32_f16x3", variant
         G.assert_close_f32(got, ref, f"case {i} act {act} [{variant}]")
 
 
@@ -70,7 +70,7 @@ def test_conv_k3c64_f32_tensor_add_link(i, in_place, knobs):
     ref = oracle.conv2d_f32_add(x, wt, b, add, (1, 1), pd, 1, act=wl.ACT_RELU)
     got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, G.make_desc(x.shape, wt.shape, (1, 1), pd, 1), wl.ACT_RELU,
                                           in_place=in_place)
-    assert variant == "conv_k3c64_f32_bf16x6_add", variant
+    assert variant == "conv_k3c64_f32_f16x3_add", variant
     G.assert_close_f32(got, ref, f"case {i} add link in_place {in_place}")
 
 

@@ -1,10 +1,12 @@
 """Filters transformed ahead of time (glowmi_*_pack_filter + glowmi_*_packed) through the C ABI.
 
-The planes themselves are checked against what they are defined to be: three bf16 values per weight that
-sum back to the weight exactly, each the leading 8 significant bits of what the previous ones left, a
-convolution filter in its own order and a FullyConnected weight transposed.  The *_packed calls are checked
+The planes themselves are checked against what they are defined to be: the tensor scaled by the power of two
+that brings its largest magnitude below 2^15, every scaled weight cut into h1 = fp16(v) and
+H2 = fp16((v - h1) * 2^11) (round to nearest even; below fp16's normal range H2 alone carries the value), a
+convolution filter in its own order and a FullyConnected weight transposed, the largest magnitude's bits in the
+trailer.  The *_packed calls are checked
 against the CPU oracle element by element at |gpu - oracle| <= 1e-5 + 1e-4 |oracle| on each kernel that
-reads planes (the three-piece contraction, both 3x3 tile kernels), with and without a workspace, with the
+reads planes (the contraction over planes, both 3x3 tile kernels), with and without a workspace, with the
 tensor-add link, a split reduction and a ragged FullyConnected; and against the plain call on the same
 kernel, whose result they must reproduce bit for bit.  A layer whose kernel reads no planes ignores them.
 """
@@ -22,25 +24,39 @@ def _gpu():
     return gpu_util
 
 
-def _bf16_planes_as_f32(planes_u16):
-    return (planes_u16.astype(np.uint32) << 16).view(np.float32)
+def _planes_layout(elems):
+    """(bytes of the two planes, offset of the trailer, total bytes)."""
+    padded = (4 * elems + 255) // 256 * 256
+    return 4 * elems, padded, padded + 4096
 
 
-def _check_planes(planes, w_in_plane_order):
-    """planes: uint16 [3][...]; the weights in the order the planes keep them."""
-    h, m, l = (_bf16_planes_as_f32(planes[i]) for i in range(3))
-    w = w_in_plane_order
-    # exact three-piece sum (every partial sum of pieces of one value is an fp32 number)
-    assert np.array_equal((h + m) + l, w)
-    # each piece is the truncation of what is left to 8 significant bits: same bits above, zeros below
-    bits = lambda a: np.ascontiguousarray(a).view(np.uint32)
-    assert np.array_equal(bits(h), bits(w) & 0xFFFF0000)
-    r1 = w - h
-    assert np.array_equal(bits(m), bits(r1) & 0xFFFF0000)
-    assert np.array_equal(l, r1 - m)
+def _check_planes(host_bytes, w_in_plane_order):
+    """host_bytes: the plane buffer; the weights in the order the planes keep them."""
+    w = np.ascontiguousarray(w_in_plane_order)
+    plane_bytes, trailer_at, total = _planes_layout(w.size)
+    assert host_bytes.size == total
+    planes = host_bytes[:plane_bytes].view(np.float16).reshape((2,) + w.shape)
+    max_bits = int((w.view(np.uint32) & 0x7FFFFFFF).max())
+    assert int(host_bytes[trailer_at:trailer_at + 4].view(np.uint32)[0]) == max_bits
+    se = 141 - max((max_bits >> 23) & 0xFF, 1)
+    v = np.ldexp(w, se).astype(np.float32)                      # exact: a power of two
+    assert np.abs(v).max() < 2.0 ** 15
+    h1 = v.astype(np.float16)
+    h1[np.abs(v) < 2.0 ** -14] = 0
+    r = v - h1.astype(np.float32)                               # exact in fp32
+    h2 = (r * np.float32(2048)).astype(np.float16)
+    assert np.array_equal(planes[0].view(np.uint16), h1.view(np.uint16))
+    assert np.array_equal(planes[1].view(np.uint16), h2.view(np.uint16))
+    # what the pieces stand for: within 2^-22 of the value (11 significant bits each, round to nearest); under fp16's
+    # normal range (the second piece alone) within 2^-11 of it, or 2^-36 absolute once the second piece is subnormal too
+    back = planes[0].astype(np.float64) + planes[1].astype(np.float64) / 2048.0
+    v64 = np.abs(v.astype(np.float64))
+    err = np.abs(back - v.astype(np.float64))
+    rel = np.where(v64 < 2.0 ** -14, 2.0 ** -11, 2.0 ** -22)
+    assert np.all(err <= np.maximum(rel * v64, 2.0 ** -36))
 
 
-def test_conv_filter_planes_are_the_exact_three_piece_cut():
+def test_conv_filter_planes_are_the_two_piece_cut():
     import torch
     import paper_1805_00907_amd as glowmi
     G = _gpu()
@@ -51,14 +67,13 @@ def test_conv_filter_planes_are_the_exact_three_piece_cut():
     w[1::7, 0, 0, 1::4] = np.exp2(rng.integers(-8, 8, size=w[1::7, 0, 0, 1::4].shape)).astype(np.float32)
     desc = glowmi.ConvDesc(1, 8, 8, c, k, r, s, 1, 1, 1, 1, 1, 1, 1)
     nbytes = glowmi.conv2d_filter_planes_bytes(desc)
-    assert nbytes >= 6 * w.size
+    assert nbytes == _planes_layout(w.size)[2]
     buf = torch.full((nbytes + 512,), 0x5A, dtype=torch.uint8, device="cuda:0")
     glowmi.conv2d_pack_filter(G.dev(w), desc, buf[256:256 + nbytes])
     torch.cuda.synchronize()
     host = buf.cpu().numpy()
     assert (host[:256] == 0x5A).all() and (host[256 + nbytes:] == 0x5A).all(), "write outside the plane buffer"
-    planes = host[256:256 + 6 * w.size].view(np.uint16).reshape(3, k, r, s, c)
-    _check_planes(planes, w)
+    _check_planes(host[256:256 + nbytes], w)
 
 
 @pytest.mark.parametrize("K,N", [(64, 32), (136, 200), (4104, 130), (8, 1000)])
@@ -74,8 +89,7 @@ def test_fc_filter_planes_are_the_transposed_cut(K, N):
     torch.cuda.synchronize()
     host = buf.cpu().numpy()
     assert (host[:256] == 0x5A).all() and (host[256 + nbytes:] == 0x5A).all(), "write outside the plane buffer"
-    planes = host[256:256 + 6 * w.size].view(np.uint16).reshape(3, N, K)
-    _check_planes(planes, np.ascontiguousarray(w.T))
+    _check_planes(host[256:256 + nbytes], np.ascontiguousarray(w.T))
 
 
 def _conv_both_ways(x, wt, b, desc, act, addend=None, use_workspace=True):
@@ -122,7 +136,7 @@ P3_SHAPES = [
 
 
 @pytest.mark.parametrize("i", range(len(P3_SHAPES)))
-def test_conv_packed_three_piece_contraction(i, knobs):
+def test_conv_packed_contraction_over_planes(i, knobs):
     G = _gpu()
     n, h, w, c, k, r, s, st, pd, g, split = P3_SHAPES[i]
     knobs.set("F32_P3_MIN_M", 1)
@@ -166,9 +180,9 @@ def test_conv_packed_3x3_tile_kernel(i, use_workspace, knobs):
         ref = oracle.conv2d_f32_add(x, wt, b, add, (1, 1), (1, 1, 1, 1), 1, act=wl.ACT_RELU)
     (plain, v_plain), (packed, v_packed) = _conv_both_ways(x, wt, b, desc, wl.ACT_RELU, addend=add,
                                                            use_workspace=use_workspace)
-    # with the planes given the tile kernel needs no workspace at all; the plain call without one cannot take it
-    assert v_packed.startswith("conv_k3_f32_bf16x6"), v_packed
-    assert v_plain.startswith("conv_k3_f32_bf16x6") == use_workspace, v_plain
+    # the tile kernel needs a workspace either way: the input's partial maxima, and the plain call's planes
+    assert v_packed.startswith("conv_k3_f32_f16x3") == use_workspace, v_packed
+    assert v_plain.startswith("conv_k3_f32_f16x3") == use_workspace, v_plain
     G.assert_close_f32(packed, ref, f"packed 3x3 case {i} [{v_packed}]")
     G.assert_close_f32(plain, ref, f"plain 3x3 case {i} [{v_plain}]")
     if use_workspace:
@@ -185,7 +199,7 @@ def test_conv_packed_3x3_c64_kernel(shape, knobs):
     desc = G.make_desc(x.shape, wt.shape, (1, 1), (1, 1, 1, 1), 1)
     ref = oracle.conv2d_f32(x, wt, b, (1, 1), (1, 1, 1, 1), 1, act=wl.ACT_NONE)
     (plain, v_plain), (packed, v_packed) = _conv_both_ways(x, wt, b, desc, wl.ACT_NONE)
-    assert v_packed.startswith("conv_k3c64_f32_bf16x6") and v_packed == v_plain, (v_plain, v_packed)
+    assert v_packed.startswith("conv_k3c64_f32_f16x3") and v_packed == v_plain, (v_plain, v_packed)
     G.assert_close_f32(packed, ref, f"packed 3x3 c64 {shape} [{v_packed}]")
     assert np.array_equal(packed, plain)
 
@@ -206,7 +220,7 @@ def test_conv_packed_planes_are_ignored_by_kernels_that_read_none(knobs):
         glowmi.conv2d_packed(G.dev(x), G.dev(wt), garbage, G.dev(b), y, desc, act=wl.ACT_RELU, workspace=ws)
         torch.cuda.synchronize()
         variant = glowmi.last_variant()
-        assert "bf16x6" not in variant or variant.startswith("conv_pw") or variant.startswith("conv_smallc"), variant
+        assert "f16x3" not in variant, variant
         assert not variant.startswith("igemm_f32_p3"), variant
         G.assert_close_f32(y.cpu().numpy(), ref, f"planes ignored [{variant}]")
 
@@ -241,9 +255,9 @@ def test_fc_packed(shape, split, knobs):
     assert v_plain == variant and np.array_equal(got, plain)
 
 
-def test_fc_packed_takes_the_bf16_kernel_where_the_plain_call_does_not():
-    """256 x 4096 x 4096 with the default planner: cutting 16 M weights in every call costs more than the bf16
-    kernel gains, so the plain call stays on the fp32 matrix cores; with the planes given it moves."""
+def test_fc_packed_takes_the_plane_kernel_where_the_plain_call_does_not():
+    """256 x 4096 x 4096 with the default planner: cutting 16 M weights in every call costs more than the kernel
+    over planes gains, so the plain call stays on the fp32 matrix cores; with the planes given it moves."""
     import torch
     import paper_1805_00907_amd as glowmi
     G = _gpu()
@@ -269,7 +283,7 @@ def test_fc_packed_takes_the_bf16_kernel_where_the_plain_call_does_not():
     G.assert_close_f32(y2.cpu().numpy(), ref, "packed fc without a workspace")
 
 
-@pytest.mark.parametrize("kind", ["three_piece_split", "tile_kernel"])
+@pytest.mark.parametrize("kind", ["planes_split", "tile_kernel"])
 def test_packed_calls_replay_from_a_hip_graph(kind, knobs):
     """The packed calls launch only kernels (cutting the input, the contraction, the finishing kernel of a split
     reduction): captured once, every replay - with the program's own eager work and synchronisation in between -
@@ -277,7 +291,7 @@ def test_packed_calls_replay_from_a_hip_graph(kind, knobs):
     import torch
     import paper_1805_00907_amd as glowmi
     G = _gpu()
-    if kind == "three_piece_split":
+    if kind == "planes_split":
         knobs.set("F32_P3_MIN_M", 1)
         knobs.set("F32_P3_RATIO", 0)
         knobs.set("F32_K3", 0)
@@ -288,7 +302,7 @@ def test_packed_calls_replay_from_a_hip_graph(kind, knobs):
         knobs.set("F32_K3_ANY", 1)
         knobs.set("F32_K3C64", 0)
         x, wt, b = _conv_inputs(36801, 2, 28, 28, 96, 160, 3, 3)
-        st, pd, prefix = 1, 1, "conv_k3_f32_bf16x6"
+        st, pd, prefix = 1, 1, "conv_k3_f32_f16x3"
     desc = G.make_desc(x.shape, wt.shape, (st, st), (pd, pd, pd, pd), 1)
     ref = oracle.conv2d_f32(x, wt, b, (st, st), (pd, pd, pd, pd), 1, act=wl.ACT_RELU)
     xd, wd, bd = G.dev(x), G.dev(wt), G.dev(b)
