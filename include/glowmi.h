@@ -20,21 +20,28 @@
  *  - `workspace` is optional scratch in device memory (16-byte aligned).  With NULL / 0 bytes the
  *    call still computes the same result to the same accuracy; with at least
  *    glowmi_*_workspace_bytes() bytes the library may split the reduction dimension over more
- *    workgroups (small-M layers) and, for large fp32 contractions, repack both operands there (three
- *    bf16 pieces per value, 6 bytes per element: see "Results" below), which is faster.  A workspace
+ *    workgroups (small-M layers) and, for large fp32 contractions, repack both operands there (two
+ *    fp16 pieces per value, 4 bytes per element: see "Results" below), which is faster.  A workspace
  *    smaller than that figure is not used at all.  The contents on entry do not matter and are
  *    undefined on return.  Two calls that share a workspace must be ordered on one stream.
  *  - Arguments are validated on the host before anything is launched.  On any error nothing is
  *    launched, y is untouched, the status says why and glowmi_last_error() gives a sentence.
  *  - Every tensor must hold fewer than 2^31 elements (GLOWMI_ERR_UNSUPPORTED otherwise).
  *  - Results: fp32 entry points accumulate in fp32 (order unspecified).  Products are fp32 products:
- *    either the fp32 matrix cores' own, or -- large contractions with a workspace -- both operands
- *    cut exactly into three bf16 pieces (x = hi + mid + lo) and the six piece products of weight
- *    down to 2^-16 multiplied exactly on the bf16 matrix cores; the three dropped products are below
- *    2^-22 of |x*y|, the size of one fp32 rounding.  Either way |result - exact| stays within a few
- *    2^-22 * (|A||W| + |bias|) componentwise.  With non-finite inputs the outputs they reach are
- *    non-finite, but an infinity may come out as NaN.  The int8 entry points are exact integer
- *    arithmetic and reproducible bit for bit.
+ *    either the fp32 matrix cores' own, or -- large contractions with a workspace -- formed on the
+ *    fp16 matrix cores from operands cut into two fp16 pieces each: a tensor is scaled by the power of
+ *    two that brings its largest magnitude under 2^15 (exact), a scaled value v becomes h1 = fp16(v) and
+ *    H2 = fp16((v - h1) * 2^11), 22 significant bits together, and a product is the three piece products
+ *    h1 h1' + 2^-11 (h1 H2' + H2 h1'), multiplied exactly and accumulated in fp32; a product is then
+ *    within 3 * 2^-22 of |x*y|, a few fp32 roundings.  Either way |result - exact| stays within a few
+ *    2^-22 * (|A||W| + |bias|) componentwise for tensors whose elements lie within 2^28 of their tensor's
+ *    largest magnitude; smaller elements keep 11 significant bits and the product of two such elements,
+ *    one from each operand, is dropped, which adds at most 2^-38 * max|A| * max|W| * (reduction length).
+ *    Scaling an operand by a power of two scales the result by it and changes nothing else.  With
+ *    non-finite inputs the outputs they reach are non-finite (an infinity may come out as NaN); on the
+ *    fp16 matrix cores an infinity or NaN anywhere in an operand makes EVERY output of that call NaN (no
+ *    scale fits such a tensor).  The int8 entry points are exact integer arithmetic and reproducible bit
+ *    for bit.
  */
 #ifndef GLOWMI_H
 #define GLOWMI_H
@@ -203,14 +210,16 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
  * Filters transformed ahead of time.  Section 5.3 (the filter-layout figure and the three kinds of
  * convolution): the weights of a layer are constants, so the compiler changes their memory layout once, at
  * compile time, into the form the selected convolution reads.  The form here is the one every fp32 kernel on
- * the bf16 matrix cores reads: each weight cut exactly into three bf16 pieces (see "Results" above), kept as
- * three planes of bf16, a convolution filter in its own [k][r][s][c/groups] order, a FullyConnected weight
- * transposed to [N][K].  glowmi_conv2d / glowmi_fc make these planes inside every call (in the workspace);
- * a caller that keeps the weights fixed makes them once and hands them to the *_packed entry points, which
- * are otherwise the same calls: bit for bit the same results where the same kernel serves both, and within
- * the accuracy stated at the top where a layer takes the bf16 kernels only once its weights need no cutting.
+ * the fp16 matrix cores reads: the weights scaled by the power of two that follows from their largest
+ * magnitude and cut into two fp16 pieces each (see "Results" above), kept as two planes of fp16, a convolution
+ * filter in its own [k][r][s][c/groups] order, a FullyConnected weight transposed to [N][K], followed by a
+ * trailer that holds the largest magnitude.  glowmi_conv2d / glowmi_fc make these planes inside every call
+ * (in the workspace); a caller that keeps the weights fixed makes them once and hands them to the *_packed
+ * entry points, which are otherwise the same calls: bit for bit the same results where the same kernel serves
+ * both, and within the accuracy stated at the top where a layer takes the fp16 kernels only once its weights
+ * need no cutting.
  *   glowmi_conv2d_filter_planes_bytes / glowmi_fc_filter_planes_bytes
- *       bytes of the planes (6 per weight, rounded up to 256), or 0 when the shape has no plane form
+ *       bytes of the planes (4 per weight, rounded up to 256, plus 4096 of trailer), or 0 when the shape has no plane form
  *       (c/groups, or K of a FullyConnected layer, not a multiple of 8; more than 2^28 weights; bad descriptor).
  *   glowmi_conv2d_pack_filter / glowmi_fc_pack_filter
  *       write the planes of `w` to `planes` (device, 16-byte aligned, planes_bytes >= the figure above;
@@ -225,9 +234,10 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
  *       shape without a plane form.
  *   glowmi_conv2d_packed_workspace_bytes / glowmi_fc_packed_workspace_bytes
  *       the workspace of a *_packed call with w_planes != NULL.  On the same kernel it is the plain call's
- *       minus the weights' planes (a 3x3 layer on the tile kernels needs none at all); a layer that only pays
- *       for the bf16 kernels once its weights need no cutting (a FullyConnected of a few hundred rows) takes
- *       them here and not in the plain call, and then asks for room for the input's planes.
+ *       minus the weights' planes (a 3x3 layer on the tile kernels keeps 2 KB, for the pass that finds the
+ *       input's largest magnitude); a layer that only pays for the fp16 kernels once its weights need no
+ *       cutting (a FullyConnected of a few hundred rows) takes them here and not in the plain call, and then
+ *       asks for room for the input's planes.
  */
 size_t glowmi_conv2d_filter_planes_bytes(const glowmi_conv_desc* d);
 glowmi_status glowmi_conv2d_pack_filter(const float* w, const glowmi_conv_desc* d, void* planes,

@@ -89,8 +89,9 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
   // the operands' scale exponents, from their largest magnitudes
-  const int se_x = scale_exponent(wave_max_words(p.x_range, p.x_range_n));
-  const int neg_se = -(se_x + scale_exponent(wave_max_words(p.w_range, 1)));
+  const unsigned x_max_bits = wave_max_words(p.x_range, p.x_range_n);
+  const int se_x = scale_exponent(x_max_bits);
+  const ScaleBack sb = scale_back(x_max_bits, wave_max_words(p.w_range, 1));
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   const int chunks = p.c / G_CH;                        // p.c % 32 == 0 on this kernel
@@ -282,7 +283,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
           const int oy = ty * GT + tp / TW, ox = tx * TW + tp % TW;
           if (cok && oy < p.oh && ox < p.ow) {
             const size_t o = ((size_t)(img * p.oh + oy) * p.ow + ox) * p.k + ch;
-            float v = join_sets(acc[i][j][e], acc_lo[i][j][e], neg_se) + bv;
+            float v = join_sets(acc[i][j][e], acc_lo[i][j][e], sb) + bv;
             if (ADD) v += addend[o];
             if (relu) v = fmaxf(v, 0.f);
             Y[o] = v;

@@ -74,8 +74,9 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
   const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
   // the operands' scale exponents, from their largest magnitudes
-  const int se_x = scale_exponent(wave_max_words(p.x_range, p.x_range_n));
-  const int neg_se = -(se_x + scale_exponent(wave_max_words(p.w_range, 1)));
+  const unsigned x_max_bits = wave_max_words(p.x_range, p.x_range_n);
+  const int se_x = scale_exponent(x_max_bits);
+  const ScaleBack sb = scale_back(x_max_bits, wave_max_words(p.w_range, 1));
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   // ---- tile decode: channel tile fastest (workgroups that share a patch run side by side), then x, y, image
@@ -255,7 +256,7 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
         for (int e4 = 0; e4 < 4; ++e4) {
           const v4f got = xch[(theirs + j * 4 + e4) * 64 + lane];
 #pragma unroll
-          for (int tq = 0; tq < 4; ++tq) keep[j][e4 * 4 + tq] = __builtin_ldexpf(keep[j][e4 * 4 + tq] + got[tq], neg_se);   // scaled back
+          for (int tq = 0; tq < 4; ++tq) keep[j][e4 * 4 + tq] = __builtin_ldexpf(keep[j][e4 * 4 + tq] + got[tq], sb.neg_se) + sb.poison;   // scaled back
         }
     }
 

@@ -75,8 +75,9 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
   const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
   // the operands' scale exponents, from their largest magnitudes
-  const int se_x = scale_exponent(wave_max_words(p.x_range, p.x_range_n));
-  const int neg_se = -(se_x + scale_exponent(wave_max_words(p.w_range, 1)));
+  const unsigned x_max_bits = wave_max_words(p.x_range, p.x_range_n);
+  const int se_x = scale_exponent(x_max_bits);
+  const ScaleBack sb = scale_back(x_max_bits, wave_max_words(p.w_range, 1));
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   // Patch rows have a pitch of tw + 4 pixels (tw + 2 used), and a pixel's four 16-byte chunks are stored at
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
               const int oy = ty * th + r, ox = tx * tw + c;
               if (cok && tp < tile_px && oy < p.oh && ox < p.ow) {
                 const size_t o = ((size_t)(img * p.oh + oy) * p.ow + ox) * p.k + ch;
-                float v = join_sets(acc[i][j][4 * q + e4], acc_lo[i][j][4 * q + e4], neg_se) + bv;
+                float v = join_sets(acc[i][j][4 * q + e4], acc_lo[i][j][4 * q + e4], sb) + bv;
                 if (ADD) v += addend[o];
                 if (relu) v = fmaxf(v, 0.f);
                 Y[o] = v;

@@ -77,9 +77,21 @@ __device__ __forceinline__ void cut8(const float (&v)[8], int se, v4u& p1, v4u& 
   }
 }
 
+// The two operands' largest magnitudes (bits) -> what the accumulators are scaled back by, and what is added to
+// every result: 0, or NaN when an operand holds an infinity or a NaN (its largest "magnitude" is then not finite and
+// no scale fits: the whole call's results are NaN rather than finite numbers that are wrong).
+struct ScaleBack { int neg_se; float poison; };
+__device__ __forceinline__ ScaleBack scale_back(unsigned x_max_bits, unsigned w_max_bits) {
+  ScaleBack s;
+  s.neg_se = -(scale_exponent(x_max_bits) + scale_exponent(w_max_bits));
+  const bool finite = x_max_bits < 0x7f800000u && w_max_bits < 0x7f800000u;
+  s.poison = finite ? 0.f : __builtin_nanf("");
+  return s;
+}
+
 // A finished sum from the two accumulator sets of scaled operands.
-__device__ __forceinline__ float join_sets(float hi, float lo, int neg_se) {
-  return __builtin_ldexpf(__builtin_fmaf(lo, kLowPieceWeight, hi), neg_se);
+__device__ __forceinline__ float join_sets(float hi, float lo, ScaleBack sb) {
+  return __builtin_ldexpf(__builtin_fmaf(lo, kLowPieceWeight, hi), sb.neg_se) + sb.poison;
 }
 
 }  // namespace glowmi

@@ -10,7 +10,8 @@ pieces; a product is three piece products accumulated in fp32.  From that follow
   * elements more than 2^28 below their tensor's largest magnitude keep 11 significant bits, and the product of two
     such elements (one from each operand, below 2^-56 of the largest product) is dropped: the error all of this
     adds stays below 2^-38 of (largest |x|) * (largest |w|) * (reduction length);
-  * all-zero operands, and an input whose largest element is an fp32 subnormal, give the bias.
+  * all-zero operands, and an input whose largest element is an fp32 subnormal, give the bias;
+  * an infinity or NaN anywhere in an operand makes every output NaN.
 """
 import numpy as np
 import pytest
@@ -142,3 +143,17 @@ def test_zero_and_subnormal_operands(kind, knobs):
     got = _run(tiny, wt, b, prefix)
     ref = oracle.conv2d_f32(tiny, wt, b, (1, 1), pd, 1, act=wl.ACT_NONE)
     _gpu().assert_close_f32(got, ref, "subnormal input")
+
+
+@pytest.mark.parametrize("kind", KERNELS)
+@pytest.mark.parametrize("what", ["inf_in_input", "nan_in_filter"])
+def test_a_non_finite_operand_makes_every_output_nan(kind, what, knobs):
+    """No power of two scales a tensor that holds an infinity or a NaN: instead of finite numbers that are wrong,
+    the whole call's output is NaN."""
+    x, wt, b, prefix = _layer(kind, knobs, 37400)
+    if what == "inf_in_input":
+        x[1, 7, 9, 3] = np.inf
+    else:
+        wt[5, 1, 1, 2] = np.nan
+    got = _run(x, wt, b, prefix)
+    assert np.all(np.isnan(got))
