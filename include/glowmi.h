@@ -29,19 +29,20 @@
  *  - Every tensor must hold fewer than 2^31 elements (GLOWMI_ERR_UNSUPPORTED otherwise).
  *  - Results: fp32 entry points accumulate in fp32 (order unspecified).  Products are fp32 products:
  *    either the fp32 matrix cores' own, or -- large contractions with a workspace -- formed on the
- *    fp16 matrix cores from operands cut into two fp16 pieces each: a tensor is scaled by the power of
- *    two that brings its largest magnitude under 2^15 (exact), a scaled value v becomes h1 = fp16(v) and
+ *    fp16 matrix cores from operands cut into two fp16 pieces each: a tensor (for the input of a 3x3 tile
+ *    kernel: each patch a workgroup stages) is scaled by the power of two that brings its largest magnitude
+ *    under 2^15 (exact), a scaled value v becomes h1 = fp16(v) and
  *    H2 = fp16((v - h1) * 2^11), 22 significant bits together, and a product is the three piece products
  *    h1 h1' + 2^-11 (h1 H2' + H2 h1'), multiplied exactly and accumulated in fp32; a product is then
  *    within 3 * 2^-22 of |x*y|, a few fp32 roundings.  Either way |result - exact| stays within a few
- *    2^-22 * (|A||W| + |bias|) componentwise for tensors whose elements lie within 2^28 of their tensor's
- *    largest magnitude; smaller elements keep 11 significant bits and the product of two such elements,
+ *    2^-22 * (|A||W| + |bias|) componentwise for tensors whose elements lie within 2^28 of the largest
+ *    magnitude they are scaled by; smaller elements keep 11 significant bits and the product of two such elements,
  *    one from each operand, is dropped, which adds at most 2^-38 * max|A| * max|W| * (reduction length).
  *    Scaling an operand by a power of two scales the result by it and changes nothing else.  With
  *    non-finite inputs the outputs they reach are non-finite (an infinity may come out as NaN); on the
- *    fp16 matrix cores an infinity or NaN anywhere in an operand makes EVERY output of that call NaN (no
- *    scale fits such a tensor).  The int8 entry points are exact integer arithmetic and reproducible bit
- *    for bit.
+ *    fp16 matrix cores outputs they do not reach may turn into NaN as well, up to every output of the
+ *    call (no scale fits a tensor or patch that holds one), but never into wrong finite values.  The int8
+ *    entry points are exact integer arithmetic and reproducible bit for bit.
  */
 #ifndef GLOWMI_H
 #define GLOWMI_H
@@ -234,10 +235,9 @@ glowmi_status glowmi_qconv2d_chain(const int8_t* x, glowmi_qparam xq, const int8
  *       shape without a plane form.
  *   glowmi_conv2d_packed_workspace_bytes / glowmi_fc_packed_workspace_bytes
  *       the workspace of a *_packed call with w_planes != NULL.  On the same kernel it is the plain call's
- *       minus the weights' planes (a 3x3 layer on the tile kernels keeps 2 KB, for the pass that finds the
- *       input's largest magnitude); a layer that only pays for the fp16 kernels once its weights need no
- *       cutting (a FullyConnected of a few hundred rows) takes them here and not in the plain call, and then
- *       asks for room for the input's planes.
+ *       minus the weights' planes (a 3x3 layer on the tile kernels needs none at all); a layer that only pays
+ *       for the fp16 kernels once its weights need no cutting (a FullyConnected of a few hundred rows) takes
+ *       them here and not in the plain call, and then asks for room for the input's planes.
  */
 size_t glowmi_conv2d_filter_planes_bytes(const glowmi_conv_desc* d);
 glowmi_status glowmi_conv2d_pack_filter(const float* w, const glowmi_conv_desc* d, void* planes,

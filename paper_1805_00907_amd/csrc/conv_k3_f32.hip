@@ -56,7 +56,8 @@ struct K3 {
   static constexpr int APLANE = PATCH_PX * G_PIXB;
   static constexpr int BPLANE = BN * G_BROW;
   static constexpr int BBUF = 2 * BPLANE;                    // one slab
-  static constexpr int LDS = 2 * APLANE + G_NBUF * BBUF + G_DUMMY;
+  static constexpr int STAGE = 2 * APLANE + G_NBUF * BBUF + G_DUMMY;
+  static constexpr int LDS = STAGE + 32;                     // + the eight wavefronts' largest magnitudes of the patch being written
   static constexpr int ITEMS = PATCH_PX * (G_CH / 8);        // (pixel, 8-channel piece) items of a patch chunk
   static constexpr int PASSES = (ITEMS + G_THREADS - 1) / G_THREADS;
   static constexpr int PREF = 2 * PASSES;                    // prefetch loads per thread
@@ -74,6 +75,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   constexpr int G_ITEMS = T::ITEMS, G_PASSES = T::PASSES, G_PREF = T::PREF;
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char* bring = lds + 2 * G_APLANE;
+  unsigned* maxw = reinterpret_cast<unsigned*>(lds + T::STAGE);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -88,10 +90,12 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
   const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
   const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
-  // the operands' scale exponents, from their largest magnitudes
-  const unsigned x_max_bits = wave_max_words(p.x_range, p.x_range_n);
-  const int se_x = scale_exponent(x_max_bits);
-  const ScaleBack sb = scale_back(x_max_bits, wave_max_words(p.w_range, 1));
+  // The filter's scale exponent follows from its largest magnitude (the trailer of its planes).  The input is scaled
+  // patch by patch: the workgroup takes the largest magnitude of the patch chunk it is about to write (from the
+  // prefetch registers), which costs no pass over the input; within a tile the exponent only ever goes down, and
+  // when it does the accumulators are scaled along (exact: a power of two).
+  const unsigned w_max_bits = wave_max_words(p.w_range, 1);
+  const int se_w = scale_exponent(w_max_bits);
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   const int chunks = p.c / G_CH;                        // p.c % 32 == 0 on this kernel
@@ -125,7 +129,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
       pre[q][1] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off == OOBX ? OOBX : off + 16u, 0, 0));
     }
   };
-  auto commit_patch = [&]() {
+  auto commit_patch = [&](int se_x) {
 #pragma unroll
     for (int q = 0; q < G_PASSES; ++q) {
       const int item = tid + q * G_THREADS;
@@ -214,11 +218,36 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
         }
 
     int s = 0;
+    int se_x = 0;
+    bool finite = w_max_bits < 0x7f800000u;
     for (int chunk = 0; chunk < chunks; ++chunk) {
-      // ---- the chunk's patch: everyone is done with the previous one, write it, publish it (the barrier of the
-      // first trip below), and start fetching the next: the next chunk of this tile or chunk 0 of the next tile
+      // ---- the chunk's patch: its largest magnitude (every wavefront leaves that of its share), everyone is done
+      // with the previous patch, scale, write it, publish it (the barrier of the first trip below), and start
+      // fetching the next: the next chunk of this tile or chunk 0 of the next tile
+      const unsigned share_max = wave_max_of(pre);
+      if (lane == 0) maxw[wave] = share_max;
       __syncthreads();
-      commit_patch();
+      {
+        const unsigned m = max_of_eight(maxw);
+        finite = finite && m < 0x7f800000u;
+        const int need = scale_exponent(m);
+        if (chunk == 0) {
+          se_x = need;
+        } else if (need < se_x) {                         // uniform, rare: larger values than any chunk before
+          const int d = need - se_x;
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int e = 0; e < 16; ++e) {
+                acc[i][j][e] = __builtin_ldexpf(acc[i][j][e], d);
+                acc_lo[i][j][e] = __builtin_ldexpf(acc_lo[i][j][e], d);
+              }
+          se_x = need;
+        }
+      }
+      commit_patch(se_x);
       const bool fetching = chunk + 1 < chunks || t_next < total;     // uniform
       if (chunk + 1 < chunks) fetch_patch(t, chunk + 1);
       else if (t_next < total) fetch_patch(t_next, 0);
@@ -270,6 +299,7 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
 
     // ---- epilogue.  Register e of a lane is pixel (e/4)*8 + 4*lhalf + e%4 of the 32-pixel block, i.e. tile pixel
     // 64wm + 32i + that; channel wn * 64 + j * 32 + lrow.
+    const ScaleBack sb = scale_back_of(se_x, se_w, finite);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int ch = ct * G_BN + wn * 64 + j * 32 + lrow;
@@ -337,11 +367,11 @@ bool k3_f32_applicable(const Problem& p) {
   return fill >= 0.75 && tiles >= 256;
 }
 
-size_t k3_f32_pack_bytes(const Problem& p) { return ranges_and_filter_bytes(p); }
+size_t k3_f32_pack_bytes(const Problem& p) { return p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2); }
 
 hipError_t launch_k3_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
   Problem p = p_in;
-  hipError_t e = stage_ranges_and_filter(p, p.planes, stream);
+  hipError_t e = stage_filter_planes(p, p.planes, stream);
   if (e != hipSuccess) return e;
   if (!k3_wide_tile(p) && knob_or(KNOB_F32_K3V, 1) != 0 && !k3v_f32_prefers_fixed_tile(p)) return launch_k3v_f32(p, stream, variant);
   if (k3_wide_tile(p)) {

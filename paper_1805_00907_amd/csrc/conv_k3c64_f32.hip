@@ -46,7 +46,8 @@ constexpr int K_BROW = 64;                     // bytes of a filter row piece (3
 constexpr int K_BPLANE = 64 * K_BROW;          // 4096: 64 output channels
 constexpr int K_BBUF = 2 * K_BPLANE;           // one slab
 constexpr int K_NBUF = 2;
-constexpr int K_LDS = 2 * K_APLANE + K_NBUF * K_BBUF;
+constexpr int K_STAGE = 2 * K_APLANE + K_NBUF * K_BBUF;
+constexpr int K_LDS = K_STAGE + 32;            // + the eight wavefronts' largest magnitudes of the patch being written
 constexpr int K_THREADS = 512;
 constexpr int K_ITEMS = K_PATCH_PX * 8;        // (pixel, 8-channel chunk) pieces of a patch
 constexpr int K_PASSES = (K_ITEMS + K_THREADS - 1) / K_THREADS;   // 6
@@ -59,6 +60,7 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
                                                                      int tiles_c, int total) {
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char* bring = lds + 2 * K_APLANE;
+  unsigned* maxw = reinterpret_cast<unsigned*>(lds + K_STAGE);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -73,10 +75,10 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
   const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
   const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
-  // the operands' scale exponents, from their largest magnitudes
-  const unsigned x_max_bits = wave_max_words(p.x_range, p.x_range_n);
-  const int se_x = scale_exponent(x_max_bits);
-  const ScaleBack sb = scale_back(x_max_bits, wave_max_words(p.w_range, 1));
+  // The filter's scale exponent follows from its largest magnitude (the trailer of its planes).  The input is scaled
+  // patch by patch: the workgroup takes the largest magnitude of the patch it is about to write (from the prefetch
+  // registers), which costs no pass over the input.
+  const unsigned w_max_bits = wave_max_words(p.w_range, 1);
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   // ---- tile decode: channel tile fastest (workgroups that share a patch run side by side), then x, y, image
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
       pre[q][1] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off == OOBX ? OOBX : off + 16u, 0, 0));
     }
   };
-  auto commit_patch = [&]() {
+  auto commit_patch = [&](int se_x) {
 #pragma unroll
     for (int q = 0; q < K_PASSES; ++q) {
       const int item = tid + q * K_THREADS;
@@ -169,8 +171,13 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
   for (; t < total; t += gridDim.x) {
     int img, ty, tx, ct;
     decode(t, img, ty, tx, ct);
+    const unsigned share_max = wave_max_of(pre);        // every wavefront leaves the largest magnitude of its share
+    if (lane == 0) maxw[wave] = share_max;
     __syncthreads();                                    // the previous tile's exchange has been read: the patch area is free
-    commit_patch();
+    const unsigned x_max_bits = max_of_eight(maxw);
+    const int se_x = scale_exponent(x_max_bits);
+    const ScaleBack sb = scale_back(x_max_bits, w_max_bits);
+    commit_patch(se_x);
     const int t_next = t + gridDim.x;
     if (t_next < total) fetch_patch(t_next);            // in flight during this tile's MFMAs (uniform branch)
     issue_b(ct, 0, 0);
@@ -312,11 +319,11 @@ bool k3c64_f32_applicable(const Problem& p) {
   return tiles >= knob_or(KNOB_F32_K3C64_MIN_TILES, 512);
 }
 
-size_t k3c64_f32_pack_bytes(const Problem& p) { return ranges_and_filter_bytes(p); }
+size_t k3c64_f32_pack_bytes(const Problem& p) { return p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2); }
 
 hipError_t launch_k3c64_f32(const Problem& p_in, hipStream_t stream, const char** variant) {
   Problem p = p_in;
-  hipError_t e = stage_ranges_and_filter(p, p.planes, stream);
+  hipError_t e = stage_filter_planes(p, p.planes, stream);
   if (e != hipSuccess) return e;
   *variant = p.addend ? "conv_k3c64_f32_f16x3_add" : "conv_k3c64_f32_f16x3";
   return p.addend ? launch_k3_variant<true>(p, stream) : launch_k3_variant<false>(p, stream);

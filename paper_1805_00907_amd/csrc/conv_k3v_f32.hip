@@ -55,13 +55,15 @@ constexpr int V_PREF = 2 * V_PASSES;           // prefetch loads per thread
 constexpr int V_LPW = 2 * V_BN / 16 / 8;       // filter loads per wavefront and slab (16 rows each)
 static_assert(V_LPW * 8 * 16 == 2 * V_BN, "filter loads divide over the wavefronts");
 
-static_assert(V_STAGE <= 160 * 1024, "LDS of one CU");
+constexpr int V_LDS = V_STAGE + 32;            // + the eight wavefronts' largest magnitudes of the patch being written
+static_assert(V_LDS <= 160 * 1024, "LDS of one CU");
 
 template <bool ADD, int NB>
 __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Problem p, int th, int tw, int tiles_y,
                                                                    int tiles_x, int tiles_c, int total) {
   extern __shared__ __align__(16) unsigned char lds[];
   unsigned char* bring = lds + 2 * V_APLANE;
+  unsigned* maxw = reinterpret_cast<unsigned*>(lds + V_STAGE);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -74,10 +76,12 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
   const unsigned wpb = p.w_bytes >> 1;                  // bytes of one filter plane
   const v4i rsrc_w = make_rsrc(p.w_planes, 2u * wpb);
   constexpr unsigned OOB = 0x80000000u;
-  // the operands' scale exponents, from their largest magnitudes
-  const unsigned x_max_bits = wave_max_words(p.x_range, p.x_range_n);
-  const int se_x = scale_exponent(x_max_bits);
-  const ScaleBack sb = scale_back(x_max_bits, wave_max_words(p.w_range, 1));
+  // The filter's scale exponent follows from its largest magnitude (the trailer of its planes).  The input is scaled
+  // patch by patch: the workgroup takes the largest magnitude of the patch chunk it is about to write (from the
+  // prefetch registers), which costs no pass over the input; within a tile the exponent only ever goes down, and
+  // when it does the accumulators are scaled along (exact: a power of two).
+  const unsigned w_max_bits = wave_max_words(p.w_range, 1);
+  const int se_w = scale_exponent(w_max_bits);
   constexpr unsigned OOBX = 0xFFFFFF00u;                // beyond any fp32 tensor this library accepts
 
   // Patch rows have a pitch of tw + 4 pixels (tw + 2 used), and a pixel's four 16-byte chunks are stored at
@@ -133,7 +137,7 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
       pre[q][1] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off == OOBX ? OOBX : off + 16u, 0, 0));
     }
   };
-  auto commit_patch = [&]() {
+  auto commit_patch = [&](int se_x) {
 #pragma unroll
     for (int q = 0; q < V_PASSES; ++q) {
       if (pyx[q] >= 0) {
@@ -214,11 +218,36 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
           }
 
       int s = 0;
+      int se_x = 0;
+      bool finite = w_max_bits < 0x7f800000u;
       for (int chunk = 0; chunk < chunks; ++chunk) {
-        // ---- the chunk's patch: everyone is done with the previous one, write it, publish it (the barrier of the
-        // first trip below), and start fetching the next: the next chunk of this tile or chunk 0 of the next tile
+        // ---- the chunk's patch: its largest magnitude (every wavefront leaves that of its share), everyone is done
+        // with the previous patch, scale, write it, publish it (the barrier of the first trip below), and start
+        // fetching the next: the next chunk of this tile or chunk 0 of the next tile
+        const unsigned share_max = wave_max_of(pre);
+        if (lane == 0) maxw[wave] = share_max;
         __syncthreads();
-        commit_patch();
+        {
+          const unsigned m = max_of_eight(maxw);
+          finite = finite && m < 0x7f800000u;
+          const int need = scale_exponent(m);
+          if (chunk == 0) {
+            se_x = need;
+          } else if (need < se_x) {                       // uniform, rare: larger values than any chunk before
+            const int d = need - se_x;
+#pragma unroll
+            for (int i = 0; i < PX; ++i)
+#pragma unroll
+              for (int j = 0; j < CH; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                  acc[i][j][e] = __builtin_ldexpf(acc[i][j][e], d);
+                  acc_lo[i][j][e] = __builtin_ldexpf(acc_lo[i][j][e], d);
+                }
+            se_x = need;
+          }
+        }
+        commit_patch(se_x);
         const bool fetching = chunk + 1 < chunks || t_next < total;     // uniform
         if (chunk + 1 < chunks) fetch_patch(t, chunk + 1);
         else if (t_next < total) fetch_patch(t_next, 0);
@@ -277,6 +306,7 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
 
       // ---- epilogue.  Register e of a lane is pixel (e/4)*8 + 4*lhalf + e%4 of the 32-pixel block; channel = lrow
       // of the 32-channel column.
+      const ScaleBack sb = scale_back_of(se_x, se_w, finite);
       int lh4 = lhalf * 4;
       asm volatile("" : "+v"(lh4));      // keeps the pixel arithmetic below inside the tile loop (hoisted, it is spilled)
 #pragma unroll
@@ -377,12 +407,12 @@ template <bool ADD, int NB>
 hipError_t launch_k3v_variant(const Problem& p, const TileShape& s, int num_cu, hipStream_t stream) {
   auto kern = conv_k3v_f32_kernel<ADD, NB>;
   static const hipError_t attr_status = hipFuncSetAttribute(
-      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, V_STAGE);
+      reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, V_LDS);
   if (attr_status != hipSuccess) return attr_status;
   const int tiles_y = (p.oh + s.th - 1) / s.th, tiles_x = (p.ow + s.tw - 1) / s.tw, tiles_c = (p.k + V_BN - 1) / V_BN;
   const long long total = (long long)p.n * tiles_y * tiles_x * tiles_c;
   const long long grid = total < num_cu ? total : num_cu;   // one persistent workgroup per CU
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(V_THREADS), V_STAGE, stream, p, s.th, s.tw, tiles_y, tiles_x, tiles_c,
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(V_THREADS), V_LDS, stream, p, s.th, s.tw, tiles_y, tiles_x, tiles_c,
                      (int)total);
   return hipGetLastError();
 }

@@ -53,6 +53,38 @@ __device__ __forceinline__ unsigned wave_max_words(const unsigned* __restrict__ 
   return (unsigned)__builtin_amdgcn_readfirstlane((int)m);
 }
 
+// Largest magnitude (bits) among 8 * N prefetched values held as N pairs of float4, over the whole wavefront.
+template <int N, typename V4>
+__device__ __forceinline__ unsigned wave_max_of(const V4 (&pre)[N][2]) {
+  unsigned m = 0;
+#pragma unroll
+  for (int q = 0; q < N; ++q)
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const unsigned b = __builtin_bit_cast(unsigned, pre[q][h][e]) & 0x7fffffffu;
+        m = b > m ? b : m;
+      }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    const unsigned o = (unsigned)__shfl_xor((int)m, d, 64);
+    m = o > m ? o : m;
+  }
+  return (unsigned)__builtin_amdgcn_readfirstlane((int)m);
+}
+
+// The largest of the eight words the wavefronts of a workgroup left at `words` (LDS).
+__device__ __forceinline__ unsigned max_of_eight(const unsigned* words) {
+  const v4u a = *reinterpret_cast<const v4u*>(words), b = *reinterpret_cast<const v4u*>(words + 4);
+  unsigned m = a[0];
+#pragma unroll
+  for (int e = 1; e < 4; ++e) m = a[e] > m ? a[e] : m;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) m = b[e] > m ? b[e] : m;
+  return (unsigned)__builtin_amdgcn_readfirstlane((int)m);
+}
+
 struct Cut2 { _Float16 h1, h2; };
 __device__ __forceinline__ Cut2 cut2(float x, int se) {
   const float v = __builtin_ldexpf(x, se);
@@ -85,6 +117,13 @@ __device__ __forceinline__ ScaleBack scale_back(unsigned x_max_bits, unsigned w_
   ScaleBack s;
   s.neg_se = -(scale_exponent(x_max_bits) + scale_exponent(w_max_bits));
   const bool finite = x_max_bits < 0x7f800000u && w_max_bits < 0x7f800000u;
+  s.poison = finite ? 0.f : __builtin_nanf("");
+  return s;
+}
+// The same from the scale exponents in use and whether every magnitude seen was finite.
+__device__ __forceinline__ ScaleBack scale_back_of(int se_x, int se_w, bool finite) {
+  ScaleBack s;
+  s.neg_se = -(se_x + se_w);
   s.poison = finite ? 0.f : __builtin_nanf("");
   return s;
 }

@@ -171,14 +171,11 @@ constexpr size_t kPlaneTrailerBytes = 2 * kRangeBytes;
 // The weights' planes, the form every fp16 three-product kernel reads them in: convolution filters in their own
 // [k][r][s][cg] order, FullyConnected weights transposed to [N][K].
 // filter_planes_bytes: bytes of that form (a multiple of 256).  launch_pack_filter: measures and writes it
-// (b_is_kn: transposed).  stage_ranges_and_filter, for the kernels that cut the input themselves: measures the
-// input into the first kRangeBytes of `area` (p.x_range), and either takes the planes the caller made ahead of time
-// (p.w_packed) or measures and cuts the filter into the rest of `area`; sets p.w_planes / p.w_range.
-// ranges_and_filter_bytes: what `area` must hold.
+// (b_is_kn: transposed).  stage_filter_planes, for the kernels that cut the input themselves: takes the planes the
+// caller made ahead of time (p.w_packed) or measures and cuts the filter into `dst` now; sets p.w_planes / p.w_range.
 size_t filter_planes_bytes(size_t w_elems);
 hipError_t launch_pack_filter(const float* w, void* dst, int b_is_kn, int K, int N, long long w_elems, hipStream_t stream);
-hipError_t stage_ranges_and_filter(Problem& p, const void* area, hipStream_t stream);
-size_t ranges_and_filter_bytes(const Problem& p);
+hipError_t stage_filter_planes(Problem& p, const void* dst, hipStream_t stream);
 // fp32 3x3 stride-1 convolution over 64 input channels on many pixels, on the fp16 matrix cores (conv_k3c64_f32.hip).
 bool k3c64_f32_applicable(const Problem& p);
 size_t k3c64_f32_pack_bytes(const Problem& p);

@@ -675,9 +675,8 @@ Plan plan_f32(const Problem& p, bool allow_split) {
   if (!forced) {
     // kernels of their own, no workspace
     if (smallc_f32_applicable(p) && !p.addend) { pl.kernel = KERNEL_SMALLC; return pl; }
-    // 3x3 over 64 channels on many pixels, with room in the workspace for the input's partial maxima and (unless
-    // the caller made them ahead of time) the filter's planes
-    const bool filter_planes = allow_split && p.allow_pack;
+    // 3x3 over 64 channels on many pixels, with the filter's planes given or room in the workspace for them
+    const bool filter_planes = p.w_packed != nullptr || (allow_split && p.allow_pack);   // given, or room to make them
     if (filter_planes && k3c64_f32_applicable(p)) {
       pl.kernel = KERNEL_K3C64;
       pl.pack_bytes = k3c64_f32_pack_bytes(p);

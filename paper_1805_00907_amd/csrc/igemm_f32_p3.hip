@@ -566,28 +566,21 @@ hipError_t launch_pack_filter(const float* w, void* dst, int b_is_kn, int K, int
   return launch_cut_filter(w, dst, b_is_kn, K, N, w_elems, stream);
 }
 
-// For the kernels that cut the input themselves (conv_k3*_f32): `area` starts with the kRangeBytes that take the
-// input's partial maxima, the weights' planes follow unless the caller made them ahead of time.
-hipError_t stage_ranges_and_filter(Problem& p, const void* area, hipStream_t stream) {
-  if (!area) return hipErrorInvalidValue;               // the ABI layer never plans these kernels without a workspace
-  unsigned* x_out = static_cast<unsigned*>(const_cast<void*>(area));
-  const long long x_elems = (long long)(p.x_bytes >> 2), w_elems = (long long)(p.w_bytes >> 2);
-  p.x_range = x_out;
-  p.x_range_n = kRangeWords;
+// For the kernels that cut the input themselves (conv_k3*_f32): the planes the caller made ahead of time, or the
+// filter measured and cut into `dst` now.
+hipError_t stage_filter_planes(Problem& p, const void* dst, hipStream_t stream) {
+  const size_t w_elems = p.w_bytes >> 2;
   if (p.w_packed) {
     p.w_planes = p.w_packed;
-    p.w_range = planes_trailer(p.w_packed, (size_t)w_elems);
-    return launch_ranges(static_cast<const float*>(p.x), x_elems, x_out, nullptr, 0, nullptr, stream);
+    p.w_range = planes_trailer(p.w_packed, w_elems);
+    return hipSuccess;
   }
-  void* dst = static_cast<unsigned char*>(const_cast<void*>(area)) + kRangeBytes;
+  if (!dst) return hipErrorInvalidValue;                // the ABI layer never plans these kernels without a workspace
   p.w_planes = dst;
-  p.w_range = planes_trailer(dst, (size_t)w_elems);
-  hipError_t e = launch_ranges(static_cast<const float*>(p.x), x_elems, x_out, static_cast<const float*>(p.w), w_elems,
-                               planes_trailer(dst, (size_t)w_elems) + kRangeWords, stream);
-  if (e != hipSuccess) return e;
-  return launch_cut_filter(static_cast<const float*>(p.w), dst, p.b_is_kn, p.Kgemm, p.k, w_elems, stream);
+  p.w_range = planes_trailer(dst, w_elems);
+  return launch_pack_filter(static_cast<const float*>(p.w), const_cast<void*>(dst), p.b_is_kn, p.Kgemm, p.k, (long long)w_elems,
+                            stream);
 }
-size_t ranges_and_filter_bytes(const Problem& p) { return kRangeBytes + (p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2)); }
 
 size_t p3_pack_bytes(const Problem& p) {
   return tensor_planes_bytes(p.x_bytes >> 2) + (p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2));

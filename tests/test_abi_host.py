@@ -345,13 +345,12 @@ def test_workspace_queries_are_pure():
         assert glowmi.conv2d_workspace_bytes(big) % (4 * y_elems) == 0     # partial sums only
     finally:
         glowmi.tuning_reset()
-    # 3x3 stride 1 on maps that tile into 16 x 16 blocks: only the filter is repacked; the input leaves 2 KB of
-    # partial maxima
+    # 3x3 stride 1 on maps that tile into 16 x 16 blocks: only the filter is repacked
     vgg2 = glowmi.ConvDesc(16, 112, 112, 128, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1)
-    assert glowmi.conv2d_workspace_bytes(vgg2) == 2048 + planes_of(128 * 3 * 3 * 128)
-    # 3x3 over 64 channels on many pixels: likewise
+    assert glowmi.conv2d_workspace_bytes(vgg2) == planes_of(128 * 3 * 3 * 128)
+    # 3x3 over 64 channels on many pixels: only the filter is repacked
     c64 = glowmi.ConvDesc(16, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1, 1, 1, 1)
-    assert glowmi.conv2d_workspace_bytes(c64) == 2048 + planes_of(64 * 3 * 3 * 64)
+    assert glowmi.conv2d_workspace_bytes(c64) == planes_of(64 * 3 * 3 * 64)
     # a FullyConnected too small to pay for the repacking never asks for it
     assert glowmi.fc_workspace_bytes(128, 4096, 4096) < 4 * (128 * 4096 + 4096 * 4096)
 
@@ -362,7 +361,7 @@ def test_packed_filter_queries_and_errors():
     planes_of = lambda elems: up(4 * elems) + 4096                    # two fp16 planes and the trailer
     vgg2 = glowmi.ConvDesc(16, 112, 112, 128, 128, 3, 3, 1, 1, 1, 1, 1, 1, 1)
     assert glowmi.conv2d_filter_planes_bytes(vgg2) == planes_of(128 * 3 * 3 * 128)
-    assert glowmi.conv2d_packed_workspace_bytes(vgg2) == 2048         # the tile kernel: the input's partial maxima only
+    assert glowmi.conv2d_packed_workspace_bytes(vgg2) == 0            # the tile kernel needs nothing else
     big = glowmi.ConvDesc(32, 7, 7, 512, 512, 3, 3, 1, 1, 1, 1, 1, 1, 1)
     planes = glowmi.conv2d_filter_planes_bytes(big)
     assert planes == planes_of(512 * 3 * 3 * 512)
