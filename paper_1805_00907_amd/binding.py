@@ -283,7 +283,7 @@ def conv2d_filter_planes_bytes(desc: ConvDesc) -> int:
 
 
 def conv2d_pack_filter(w, desc: ConvDesc, planes, stream=None) -> None:
-    """Writes the bf16 planes of the filter `w` (made once, ahead of the calls that use them) to `planes`."""
+    """Writes the fp16 planes of the filter `w` (made once, ahead of the calls that use them) to `planes`."""
     _, nw, _ = _conv_counts(desc)
     pp, pb = _planes(planes, 0)
     _check(library().glowmi_conv2d_pack_filter(_ptr(w, "float32", nw, "w"), ctypes.byref(desc), pp, pb,
@@ -311,7 +311,7 @@ def fc_filter_planes_bytes(K: int, N: int) -> int:
 
 
 def fc_pack_filter(w, K: int, N: int, planes, stream=None) -> None:
-    """Writes the bf16 planes of the [K][N] weight `w` (transposed to [N][K]) to `planes`."""
+    """Writes the fp16 planes of the [K][N] weight `w` (transposed to [N][K]) to `planes`."""
     pp, pb = _planes(planes, 0)
     _check(library().glowmi_fc_pack_filter(_ptr(w, "float32", K * N, "w"), K, N, pp, pb, _stream(stream)))
 

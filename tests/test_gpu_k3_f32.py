@@ -1,5 +1,5 @@
 """The fp32 3x3 stride-1 kernel for many channels (16 x 16 pixel tiles x 128 output channels, the input walked
-in 32-channel chunks whose patch is cut into three bf16 planes in LDS, six bf16 MFMAs per product) through the
+in 32-channel chunks whose patch is scaled and cut into two fp16 planes in LDS, three fp16 MFMAs per product) through the
 C ABI against the CPU oracle, element by element, at |gpu - oracle| <= 1e-5 + 1e-4 |oracle|: one, two (even)
 and three (odd) channel chunks, both tile shapes (16 x 16 pixels x 128 channels, 16 x 32 x 64), ragged pixel and channel tiles, every kind of padding, more tiles than CUs
 (persistent workgroups, patch prefetch across tiles), the tensor-add link, no bias; for more than 64 output

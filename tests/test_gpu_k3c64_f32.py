@@ -1,5 +1,5 @@
-"""The fp32 3x3 / 64-input-channel kernel (16 x 16 pixel tiles, the input patch cut into three bf16 planes in
-LDS, six bf16 MFMAs per product) through the C ABI against the CPU oracle, element by element, at
+"""The fp32 3x3 / 64-input-channel kernel (16 x 16 pixel tiles, the input patch scaled and cut into two fp16 planes
+in LDS, three fp16 MFMAs per product) through the C ABI against the CPU oracle, element by element, at
 |gpu - oracle| <= 1e-5 + 1e-4 |oracle|: maps that are and are not multiples of the tile, one pixel wide or
 high, padding 0 / 1 / asymmetric / wider than the filter needs, ragged and several channel tiles, more
 tiles than CUs (persistent workgroups walk several, the next patch prefetched), the tensor-add link in and

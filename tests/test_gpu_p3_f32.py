@@ -1,5 +1,5 @@
-"""The fp32 three-piece kernel (operands cut into three bf16 planes by a packing pass, six bf16 MFMAs per
-product, fp32 accumulation) through the C ABI against the CPU oracle, element by element, at
+"""The fp32 contraction over planes (operands scaled by a power of two and cut into two fp16 planes by a packing
+pass, three fp16 MFMAs per product, fp32 accumulation) through the C ABI against the CPU oracle, element by element, at
 |gpu - oracle| <= 1e-5 + 1e-4 |oracle|: both tile widths, ragged pixel and channel tiles, channel counts
 that are not a multiple of the 32-index slab, groups, strides, padding on every side, FullyConnected
 with ragged K and N ([K][N] weights transposed by the packing pass), the tensor-add link, a split
@@ -152,7 +152,7 @@ def test_p3_wide_value_range_is_held_to_fp32_accuracy(knobs):
 
 
 def test_p3_error_is_no_larger_than_the_fp32_matrix_core_path(knobs):
-    """Same layer through both kernels: the three-piece form's error against the fp64 oracle stays within
+    """Same layer through both kernels: the piece-product form's error against the fp64 oracle stays within
     twice that of v_mfma_f32_32x32x2_f32 accumulation (both are fp32-level; neither is reduced precision)."""
     G = _gpu()
     x, wt, b, st, pd, g = _conv_case(8)
