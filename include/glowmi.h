@@ -389,7 +389,8 @@ glowmi_status glowmi_rescale_params(float r_scale, float x_scale, float w_scale,
  * from environment variables GLOWMI_<name>.  Every setting computes the same result (int8: bit for
  * bit; fp32: within the accuracy stated at the top of this file, the kernels differ in rounding order and
  * in which matrix cores form the products: "F32_P3", "F32_K3", "F32_K3C64", "F32_PW_BF16",
- * "F32_SMALLC_BF16" = 0 keep a layer on the fp32 matrix cores; "F32_K3V" = 0 keeps the 3x3 kernel on its
+ * "F32_SMALLC_BF16" (the first-layer kernel's piece-product form, whatever the pieces' type) = 0 keep a layer on the
+ * fp32 matrix cores; "F32_K3V" = 0 keeps the 3x3 kernel on its
  * fixed 16 x 16 pixel tile and "F32_K3_TH" / "F32_K3_TW" force a tile of that many rows / columns, at most 256
  * pixels, 64 columns and (rows + 2) x (columns + 4) <= 360, else ignored); only the choice of kernel changes.
  * glowmi_tuning_reset() returns every knob to "the planner's own choice" (it does not re-read the

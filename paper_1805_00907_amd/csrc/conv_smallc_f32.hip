@@ -19,7 +19,7 @@
 #include <cstdlib>
 #include <type_traits>
 
-#include "bf16_pieces.h"
+#include "f16_pieces.h"
 #include "igemm.h"
 
 namespace glowmi {
@@ -229,15 +229,19 @@ __global__ __launch_bounds__(SC_THREADS) void conv_smallc_f32_kernel(const Probl
 }
 
 // ---------------------------------------------------------------------------------------------------
-// The same design on the bf16 matrix cores: every operand cut exactly into three bf16 pieces, six piece
-// products per fp32 product (bf16_pieces.h).  v_mfma_f32_32x32x16_bf16 wants eight consecutive reduction
+// The same design on the fp16 matrix cores: every operand scaled by a power of two and cut into two fp16
+// pieces, three piece products per fp32 product, the cross terms in an accumulator set of their own
+// (f16_pieces.h).  v_mfma_f32_32x32x16_f16 wants eight consecutive reduction
 // indices per lane, so the reduction is ordered filter row by filter row with each row's S*C run padded to
 // a multiple of 8 (7 x 3 = 21 -> 24): a lane's eight values are then eight consecutive patch elements, and
 // where the run is over they overlap the neighbouring pixels' data, which the zero pieces of the filter
 // cancel (the patch holds finite values or zeros everywhere, including one spare row).  The patch is cut
-// once per tile while it is written to LDS (three bf16 planes); the filter fragments (11 steps x 3 pieces
-// x 8 values per lane) are cut once per workgroup and stay in registers.  11 x 6 bf16 MFMAs of 32 cycles
-// replace 74 fp32 MFMAs of 64 per 32 x 32 block.
+// once per tile while it is written to LDS (two fp16 planes), scaled by its own largest magnitude (the
+// workgroup takes it from the registers the patch was fetched into: one more barrier per tile); the filter
+// fragments (11 steps x 2 pieces x 8 values per lane) are cut once per workgroup, scaled by the largest
+// magnitude of the workgroup's 64 filters, and stay in registers.  11 x 3 fp16 MFMAs of 32 cycles
+// replace 74 fp32 MFMAs of 64 per 32 x 32 block (the first form of this kernel took 11 x 6 bf16 MFMAs over
+// three bf16 pieces per operand: batch 32 62 -> 52 us).
 // ---------------------------------------------------------------------------------------------------
 template <int R, int S, int C, int STRIDE, int TH>
 struct SmallCB {
@@ -250,22 +254,25 @@ struct SmallCB {
   static constexpr int PWC = ((TW - 1) * STRIDE + S) * C;   // patch row length in elements
   static constexpr int PITCH = ((PWC + 8 + 15) / 16) * 16;  // elements; the last pixel's padded run stays inside the row
   static constexpr int PLANE = (PH + 2) * PITCH;         // elements; two spare rows: the padded steps read them
-  static constexpr int PATCH = 3 * PLANE;                // elements of one buffer
+  static constexpr int PATCH = 2 * PLANE;                // elements of one buffer
   static constexpr int LOADS = (PH * PWC + SC_THREADS - 1) / SC_THREADS;
-  static constexpr int lds_bytes = (2 * PATCH * 2 > 32 * K * 4 ? 2 * PATCH * 2 : 32 * K * 4);
+  static constexpr int stage_bytes = (2 * PATCH * 2 > 32 * K * 4 ? 2 * PATCH * 2 : 32 * K * 4);
+  static constexpr int lds_bytes = stage_bytes + 32;     // + the eight wavefronts' largest magnitudes
   // patch offset (elements) of group g relative to a pixel's patch origin
   static constexpr int off(int g) { return (g / RUN8) * PITCH + (g % RUN8) * 8; }
 };
 
 template <int R, int S, int C, int STRIDE, int TH>
-__global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_bf16_kernel(const Problem p, int tiles_y, int tiles_x,
+__global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_f16_kernel(const Problem p, int tiles_y, int tiles_x,
                                                                             int total_tiles) {
   using G = SmallCB<R, S, C, STRIDE, TH>;
   static_assert(TH == 4, "tile height: one 32-pixel block per wavefront");
   static_assert((STRIDE * C) % 2 == 0 && G::PITCH % 2 == 0, "a pixel's run starts on a 4-byte boundary");
   constexpr int NB = TH / 4;
-  extern __shared__ __align__(16) unsigned short patchb[];   // [2][3][PH + 2][PITCH]; first the filter halves as fp32
+  extern __shared__ __align__(16) unsigned short patchb[];   // [2][2][PH + 2][PITCH]; first the filter halves as fp32
   float* wstage = reinterpret_cast<float*>(patchb);
+  unsigned* maxw = reinterpret_cast<unsigned*>(reinterpret_cast<unsigned char*>(patchb) + G::stage_bytes);
+  static_assert(SC_THREADS == 256, "four wavefronts leave their largest magnitudes in words 0-3; words 4-7 stay zero");
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -309,49 +316,89 @@ __global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_bf16_kernel(con
       stage[i] = ok ? X[((size_t)img * p.h + ih) * row_floats + fx] : 0.f;
     }
   };
-  auto store_patch = [&](int buf) {
+  auto store_patch = [&](int buf, int se) {
     unsigned short* dst = patchb + buf * G::PATCH;
 #pragma unroll
     for (int i = 0; i < G::LOADS; ++i) {
       const int idx = tid + i * SC_THREADS;
       if (idx < G::PH * G::PWC) {
-        const Pieces pc = split3(stage[i]);
+        const Cut2 pc = cut2(stage[i], se);
         unsigned short* d = dst + (idx / G::PWC) * G::PITCH + idx % G::PWC;
-        d[0] = (unsigned short)(pc.h >> 16);
-        d[G::PLANE] = (unsigned short)(pc.m >> 16);
-        d[2 * G::PLANE] = (unsigned short)(pc.l >> 16);
+        d[0] = __builtin_bit_cast(unsigned short, pc.h1);
+        d[G::PLANE] = __builtin_bit_cast(unsigned short, pc.h2);
       }
     }
+  };
+  // Largest magnitude (bits) of the patch held in `stage`, over the wavefront; the workgroup's follows from the
+  // eight words the wavefronts leave in maxw.
+  auto stage_max = [&]() {
+    unsigned m = 0;
+#pragma unroll
+    for (int i = 0; i < G::LOADS; ++i) {
+      const unsigned b = __builtin_bit_cast(unsigned, stage[i]) & 0x7fffffffu;
+      m = b > m ? b : m;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+      const unsigned o = (unsigned)__shfl_xor((int)m, d, 64);
+      m = o > m ? o : m;
+    }
+    return m;
   };
 
   int tile = blockIdx.x;
   if (tile >= total_tiles) return;
+  if (tid >= 4 && tid < 8) maxw[tid] = 0u;  // never written again; visible after the first barrier
   load_patch(tile);                        // in flight while the filter is fetched
 
   // ---- filter fragments: lane (channel, half) keeps, for every step t and piece, the eight values of group
   // 2t + half.  The 32 channels of each channel half are copied into LDS with coalesced loads (in the space of
   // the patch buffers) and the lanes pick from there; rows past the last output channel lie past the end of
-  // the tensor and the range-checked loads return zeros.
-  v8bf wfrag[G::STEPS][3];
+  // the tensor and the range-checked loads return zeros.  Both halves are fetched first: their largest magnitude
+  // is the scale the fragments are cut at.
+  v8h wfrag[G::STEPS][2];
+  int se_w;
+  bool finite;
   {
     const __amdgpu_buffer_rsrc_t rsrc_w =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(Wt), 0, (int)p.w_bytes, 0x00020000);
     constexpr int HALF_FLOATS = 32 * G::K;
     constexpr int W_LOADS = (HALF_FLOATS + SC_THREADS - 1) / SC_THREADS;
+    float wst[2][W_LOADS];
+    unsigned wm = 0;
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const unsigned base = (unsigned)((n_tile * 64 + half * 32) * G::K) * 4u;
-      float wst[W_LOADS];
 #pragma unroll
       for (int i = 0; i < W_LOADS; ++i) {
         const int e = tid + i * SC_THREADS;
-        wst[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
-                                               rsrc_w, e < HALF_FLOATS ? base + 4u * e : 0xFFFFFFFCu, 0, 0));
+        wst[half][i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(
+                                                     rsrc_w, e < HALF_FLOATS ? base + 4u * e : 0xFFFFFFFCu, 0, 0));
+      }
+    }
+#pragma unroll
+    for (int half = 0; half < 2; ++half)
+#pragma unroll
+      for (int i = 0; i < W_LOADS; ++i) {
+        const unsigned b = __builtin_bit_cast(unsigned, wst[half][i]) & 0x7fffffffu;
+        wm = b > wm ? b : wm;
       }
 #pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+      const unsigned o = (unsigned)__shfl_xor((int)wm, d, 64);
+      wm = o > wm ? o : wm;
+    }
+    if (lane == 0) maxw[wave] = wm;
+    __syncthreads();
+    const unsigned w_max_bits = max_of_eight(maxw);
+    se_w = scale_exponent(w_max_bits);
+    finite = w_max_bits < 0x7f800000u;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+#pragma unroll
       for (int i = 0; i < W_LOADS; ++i) {
         const int e = tid + i * SC_THREADS;
-        if (e < HALF_FLOATS) wstage[e] = wst[i];
+        if (e < HALF_FLOATS) wstage[e] = wst[half][i];
       }
       __syncthreads();
       if (wch == half) {
@@ -369,11 +416,10 @@ __global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_bf16_kernel(con
             const float v1 = ok1 ? wstage[lrow * G::K + r1 * G::RUN + q1] : 0.f;
             v[e] = lhalf ? v1 : v0;
           }
-          v4u h, m, l;
-          split8(v, h, m, l);
-          wfrag[t][0] = __builtin_bit_cast(v8bf, h);
-          wfrag[t][1] = __builtin_bit_cast(v8bf, m);
-          wfrag[t][2] = __builtin_bit_cast(v8bf, l);
+          v4u p1, p2;
+          cut8(v, se_w, p1, p2);
+          wfrag[t][0] = __builtin_bit_cast(v8h, p1);
+          wfrag[t][1] = __builtin_bit_cast(v8h, p2);
         }
       }
       __syncthreads();
@@ -382,8 +428,18 @@ __global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_bf16_kernel(con
   // zero both buffers once: the spare rows and the row tails are never overwritten by patch stores and must
   // hold finite values (they meet zero filter pieces)
   for (int i = tid; i < 2 * G::PATCH / 2; i += SC_THREADS) reinterpret_cast<unsigned*>(patchb)[i] = 0u;
+  {
+    const unsigned share = stage_max();
+    if (lane == 0) maxw[wave] = share;                   // (the filter's words were read before the last barrier)
+  }
   __syncthreads();
-  store_patch(0);
+  int se_x;                                              // scale exponent of the patch in `buf`
+  {
+    const unsigned m = max_of_eight(maxw);
+    finite = finite && m < 0x7f800000u;
+    se_x = scale_exponent(m);
+  }
+  store_patch(0, se_x);
   __syncthreads();
   int buf = 0;
   for (;;) {
@@ -391,11 +447,14 @@ __global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_bf16_kernel(con
     const bool has_next = next < total_tiles;
     if (has_next) load_patch(next);
 
-    v16f acc[NB];
+    v16f acc[NB], acc_lo[NB];                            // the h1 h1' products; the cross terms (weight 2^-11)
 #pragma unroll
     for (int i = 0; i < NB; ++i)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+      for (int e = 0; e < 16; ++e) {
+        acc[i][e] = 0.f;
+        acc_lo[i][e] = 0.f;
+      }
     const unsigned short* src = patchb + buf * G::PATCH;
     const unsigned short* pn = src + base_norm;
     const unsigned short* pcx = src + base_cross;
@@ -404,22 +463,34 @@ __global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_bf16_kernel(con
       constexpr int blk = 2 * STRIDE * G::PITCH;                     // second 32-pixel block: two output rows down
       const bool cross = (2 * t) % G::RUN8 == G::RUN8 - 1;           // compile-time after unrolling
       const unsigned short* b = (cross ? pcx : pn) + G::off(2 * t);
-      v8bf a[3][NB];
+      v8h a[2][NB];
 #pragma unroll
-      for (int pc = 0; pc < 3; ++pc)
+      for (int pc = 0; pc < 2; ++pc)
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
           const unsigned* q = reinterpret_cast<const unsigned*>(b + pc * G::PLANE + i * blk);   // 4-byte aligned
-          a[pc][i] = __builtin_bit_cast(v8bf, v4u{q[0], q[1], q[2], q[3]});
+          a[pc][i] = __builtin_bit_cast(v8h, v4u{q[0], q[1], q[2], q[3]});
         }
 #pragma unroll
-      for (int tt = 0; tt < 6; ++tt)
-#pragma unroll
-        for (int i = 0; i < NB; ++i)
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kPieceTermA[tt]][i], wfrag[t][kPieceTermB[tt]], acc[i], 0, 0, 0);
+      for (int i = 0; i < NB; ++i) {
+        acc_lo[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], wfrag[t][1], acc_lo[i], 0, 0, 0);
+        acc_lo[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[1][i], wfrag[t][0], acc_lo[i], 0, 0, 0);
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[0][i], wfrag[t][0], acc[i], 0, 0, 0);
+      }
     }
 
-    if (has_next) store_patch(buf ^ 1);
+    // ---- the next tile's patch: its largest magnitude, then (everyone is done with the other buffer since the
+    // barrier that ended the last tile) scaled, cut and written while this tile's results are stored
+    const ScaleBack sb = scale_back_of(se_x, se_w, finite);
+    if (has_next) {
+      const unsigned share = stage_max();
+      if (lane == 0) maxw[wave] = share;
+      __syncthreads();
+      const unsigned m = max_of_eight(maxw);
+      finite = finite && m < 0x7f800000u;
+      se_x = scale_exponent(m);
+      store_patch(buf ^ 1, se_x);
+    }
 
     // ---- epilogue of this tile: as in the kernel above
     {
@@ -437,7 +508,7 @@ __global__ __launch_bounds__(SC_THREADS, 2) void conv_smallc_f32_bf16_kernel(con
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int drow = e >> 3, dcol = (e & 3) + 8 * ((e >> 2) & 1);
-          float v = acc[i][e] + bv;
+          float v = join_sets(acc[i][e], acc_lo[i][e], sb) + bv;
           if (p.act == 1) v = fmaxf(v, 0.f);
           const bool ok = dcol < cols_left && drow < rows_left;
           const unsigned soff = (unsigned)((drow * p.ow + dcol) * p.k) * 4u;
@@ -456,7 +527,7 @@ template <int R, int S, int C, int STRIDE, int TH, bool BF16>
 hipError_t launch_smallc(const Problem& p, hipStream_t stream) {
   using G = std::conditional_t<BF16, SmallCB<R, S, C, STRIDE, TH>, SmallC<R, S, C, STRIDE, TH>>;
   auto kern = [] {
-    if constexpr (BF16) return conv_smallc_f32_bf16_kernel<R, S, C, STRIDE, TH>;
+    if constexpr (BF16) return conv_smallc_f32_f16_kernel<R, S, C, STRIDE, TH>;
     else return conv_smallc_f32_kernel<R, S, C, STRIDE, TH>;
   }();
   // once per instantiation; initialisation of a function-local static is thread-safe
@@ -496,19 +567,20 @@ bool smallc_f32_applicable(const Problem& p) {
 }
 
 hipError_t launch_smallc_f32(const Problem& p, hipStream_t stream, const char** variant) {
-  // The bf16 form pays a longer prologue (the filter fragments are cut per workgroup): batch 32 90 -> 61 us, but
-  // batch 1 (196 tiles, launch-bound) 11.8 -> 14.5 us, which therefore keeps the fp32 form.  The knob forces one.
+  // The fp16-piece form pays a longer prologue (the filter fragments are cut per workgroup): batch 32 90 -> 52 us,
+  // batch 8 27 -> 22 us, but batch 1 (196 tiles, launch-bound) 8.2 -> 11.7 us, which therefore keeps the fp32 form.
+  // The knob forces one.
   const long long tiles4 = (long long)p.n * ((p.oh + 3) / 4) * ((p.ow + TW - 1) / TW);
-  const bool bf16 = knob_or(KNOB_F32_SMALLC_BF16, tiles4 >= 2048 ? 1 : 0) != 0;
-  *variant = bf16 ? "conv_smallc_f32_7x7s2c3_bf16x6" : "conv_smallc_f32_7x7s2c3";
+  const bool bf16 = knob_or(KNOB_F32_SMALLC_BF16, tiles4 >= 1536 ? 1 : 0) != 0;
+  *variant = bf16 ? "conv_smallc_f32_7x7s2c3_f16x3" : "conv_smallc_f32_7x7s2c3";
   // the taller tile is the faster one per tile (two independent MFMA chains per wavefront); the
   // shorter one doubles the number of tiles, which pays while there are fewer than about two per
   // resident workgroup (batch 1: 13.8 -> 11.1 us; batch 32: 97.8 vs 100.5 us)
   const long long tiles8 = (long long)p.n * ((p.oh + 7) / 8) * ((p.ow + TW - 1) / TW);
   int th = tiles8 < 1536 ? 4 : 8;
   if (knob_is_set(KNOB_SMALLC_TH)) th = knob(KNOB_SMALLC_TH) == 8 ? 8 : 4;   // experiments
-  // (the bf16 form keeps 132 registers of filter fragments per lane: with two pixel blocks per wavefront it
-  // spills, so it always takes the four-row tile)
+  // (the fp16-piece form keeps 88 registers of filter fragments per lane and two accumulator sets: with two pixel
+  // blocks per wavefront it would spill, so it always takes the four-row tile)
   if (bf16) return launch_smallc<7, 7, 3, 2, 4, true>(p, stream);
   return th == 8 ? launch_smallc<7, 7, 3, 2, 8, false>(p, stream) : launch_smallc<7, 7, 3, 2, 4, false>(p, stream);
 }

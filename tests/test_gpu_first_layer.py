@@ -32,9 +32,9 @@ FIRST_LAYER = [
 ]
 
 
-# both forms: products on the fp32 matrix cores, and three exact bf16 pieces per operand with six piece products
+# both forms: products on the fp32 matrix cores, and two scaled fp16 pieces per operand with three piece products
 @pytest.mark.parametrize("i", range(len(FIRST_LAYER)))
-@pytest.mark.parametrize("form", [("fp32", 0), ("bf16x6", 1)], ids=lambda f: f[0])
+@pytest.mark.parametrize("form", [("fp32", 0), ("f16x3", 1)], ids=lambda f: f[0])
 def test_first_layer_f32(i, form, knobs):
     G = _gpu()
     knobs.set("F32_SMALLC_BF16", form[1])
@@ -47,8 +47,65 @@ def test_first_layer_f32(i, form, knobs):
     for act in (wl.ACT_RELU, wl.ACT_NONE):
         ref = oracle.conv2d_f32(x, wt, b, (2, 2), pd, 1, act=act)
         got, variant = G.gpu_conv2d_f32(x, wt, b, desc, act)
-        assert variant.startswith("conv_smallc_f32") and variant.endswith("bf16x6") == bool(form[1]), variant
+        assert variant.startswith("conv_smallc_f32") and variant.endswith("f16x3") == bool(form[1]), variant
         G.assert_close_f32(got, ref, f"first layer fp32 {FIRST_LAYER[i]} act {act} [{variant}]")
+
+
+def _first_layer_f16(knobs, seed, n=2, h=37, w=53, k=80):
+    knobs.set("F32_SMALLC_BF16", 1)
+    rng = np.random.default_rng(seed)
+    x = rng.uniform(-1, 1, size=(n, h, w, 3)).astype(np.float32)
+    wt = (rng.uniform(-1, 1, size=(k, 7, 7, 3)) / 12).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(k,)).astype(np.float32)
+    return x, wt, b
+
+
+def _run_first_layer(x, wt, b):
+    G = _gpu()
+    desc = G.make_desc(x.shape, wt.shape, (2, 2), (3, 3, 3, 3), 1)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_NONE)
+    assert variant == "conv_smallc_f32_7x7s2c3_f16x3", variant
+    return got
+
+
+@pytest.mark.parametrize("ex,ew", [(80, -90), (-100, 40), (100, -90), (-50, -50)])
+def test_first_layer_f16_power_of_two_scaling_changes_only_the_scale(ex, ew, knobs):
+    """The fp16-piece form scales every patch and every workgroup's filters by a power of two of their own: scaling an
+    operand by a power of two scales the result by it and changes nothing else, bit for bit."""
+    x, wt, b = _first_layer_f16(knobs, 9990)
+    base = _run_first_layer(x, wt, b)
+    got = _run_first_layer(np.ldexp(x, ex).astype(np.float32), np.ldexp(wt, ew).astype(np.float32),
+                           np.ldexp(b, ex + ew).astype(np.float32))
+    assert np.all(np.isfinite(got))
+    assert np.array_equal(np.ldexp(got.astype(np.float64), -(ex + ew)), base.astype(np.float64))
+
+
+def test_first_layer_f16_wide_value_range_and_special_operands(knobs):
+    """Magnitudes over 24 binades inside each tensor to the componentwise fp32-level bound; all-zero operands give the
+    bias; an infinity makes the outputs it reaches non-finite and leaves no wrong finite value anywhere."""
+    x, wt, b = _first_layer_f16(knobs, 9991)
+    rng = np.random.default_rng(9992)
+    xs = (x * np.exp2(rng.integers(-12, 12, size=x.shape))).astype(np.float32)
+    ws = (wt * np.exp2(rng.integers(-12, 12, size=wt.shape))).astype(np.float32)
+    ws[::3, :, :, 1] = 0.0
+    pd = (3, 3, 3, 3)
+    got = _run_first_layer(xs, ws, b)
+    exact = oracle.conv2d_f32(xs, ws, b, (2, 2), pd, 1, act=wl.ACT_NONE).astype(np.float64)
+    scale = oracle.conv2d_f32(np.abs(xs), np.abs(ws), np.abs(b), (2, 2), pd, 1, act=wl.ACT_NONE).astype(np.float64)
+    assert np.all(np.isfinite(got))
+    assert float((np.abs(got - exact) / scale).max()) <= 4 * 2.0 ** -22 + 2.0 ** -24
+    got = _run_first_layer(np.zeros_like(x), wt, b)
+    assert np.array_equal(got, np.broadcast_to(b, got.shape))
+    got = _run_first_layer(x, np.zeros_like(wt), b)
+    assert np.array_equal(got, np.broadcast_to(b, got.shape))
+    xi = x.copy()
+    xi[1, 20, 30, 1] = np.inf
+    got = _run_first_layer(xi, wt, b)
+    ref = oracle.conv2d_f32(xi, wt, b, (2, 2), pd, 1, act=wl.ACT_NONE)
+    reached = ~np.isfinite(ref)
+    assert reached.any() and not np.isfinite(got[reached]).any()
+    rest = ~reached & ~np.isnan(got)
+    assert np.all(np.abs(got[rest] - ref[rest]) <= 1e-5 + 1e-4 * np.abs(ref[rest]))
 
 
 @pytest.mark.parametrize("i", range(len(FIRST_LAYER)))
