@@ -149,34 +149,53 @@ __device__ __forceinline__ void pack2_rows(const float* __restrict__ src, unsign
 }
 
 // FullyConnected weight [K][N] (N contiguous) -> two planes [N][K] (K contiguous).  K % 8 == 0.
-// One workgroup per 64 (k) x 32 (n) tile, transposed through LDS.
+// One workgroup per 64 (k) x 64 (n) tile, transposed through LDS: rows of 256 bytes are read with one float4 per lane
+// where N allows it (every load instruction covers whole 256-byte runs), a thread then gathers eight consecutive k of
+// one n from the tile and writes 16 bytes per plane.  The tile's row pitch of 65 floats keeps both the row-wise
+// stores and the column-wise gathers free of bank conflicts.
+constexpr int kPackTile = 64;
 __device__ __forceinline__ void pack2_transposed(const float* __restrict__ w, unsigned short* __restrict__ dst, int K, int N,
-                                                 int tiles_n, int block, float (&tile)[64][33],
+                                                 int tiles_n, int block, float (&tile)[kPackTile][kPackTile + 1],
                                                  unsigned* __restrict__ trailer) {
   const int se = take_scale(trailer, block == 0);
   const int tk = block / tiles_n, tn = block - tk * tiles_n;
-  const int k0 = tk * 64, n0 = tn * 32;
+  const int k0 = tk * kPackTile, n0 = tn * kPackTile;
   const int tid = threadIdx.x;
-  {
-    const int n = tid & 31, kr = tid >> 5;
+  if ((N & 3) == 0) {                                     // uniform: rows start on 16-byte boundaries
+    const int n4 = tid & 15, kr = tid >> 4;
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int k = kr + 8 * q;
+    for (int q = 0; q < 4; ++q) {
+      const int k = kr + 16 * q;
+      v4f v = {0.f, 0.f, 0.f, 0.f};
+      if (k0 + k < K && n0 + 4 * n4 < N)
+        v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(w + (size_t)(k0 + k) * N + n0 + 4 * n4));   // read once
+#pragma unroll
+      for (int e = 0; e < 4; ++e) tile[k][4 * n4 + e] = v[e];
+    }
+  } else {
+    const int n = tid & 63, kr = tid >> 6;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+      const int k = kr + 4 * q;
       tile[k][n] = (k0 + k < K && n0 + n < N) ? __builtin_nontemporal_load(w + (size_t)(k0 + k) * N + n0 + n) : 0.f;
     }
   }
   __syncthreads();
-  const int n = tid >> 3, kc = tid & 7;
-  if (n0 + n >= N || k0 + kc * 8 >= K) return;
-  float v[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) v[e] = tile[kc * 8 + e][n];
-  v4u p1, p2;
-  cut8(v, se, p1, p2);
   const size_t plane = (size_t)K * N;
-  unsigned short* o = dst + (size_t)(n0 + n) * K + k0 + kc * 8;
-  *reinterpret_cast<v4u*>(o) = p1;
-  *reinterpret_cast<v4u*>(o + plane) = p2;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    const int item = tid + 256 * pass;
+    const int n = item >> 3, kc = item & 7;
+    if (n0 + n >= N || k0 + kc * 8 >= K) continue;
+    float v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = tile[kc * 8 + e][n];
+    v4u p1, p2;
+    cut8(v, se, p1, p2);
+    unsigned short* o = dst + (size_t)(n0 + n) * K + k0 + kc * 8;
+    *reinterpret_cast<v4u*>(o) = p1;
+    *reinterpret_cast<v4u*>(o + plane) = p2;
+  }
 }
 
 __global__ __launch_bounds__(256) void pack2_rows_kernel(const float* __restrict__ src, unsigned short* __restrict__ dst,
@@ -187,19 +206,19 @@ __global__ __launch_bounds__(256) void pack2_rows_kernel(const float* __restrict
 
 __global__ __launch_bounds__(256) void pack2_transposed_kernel(const float* __restrict__ w, unsigned short* __restrict__ dst,
                                                                int K, int N, int tiles_n, unsigned* __restrict__ trailer) {
-  __shared__ float tile[64][33];
+  __shared__ float tile[kPackTile][kPackTile + 1];
   pack2_transposed(w, dst, K, N, tiles_n, (int)blockIdx.x, tile, trailer);
 }
 
 // Both operands of one contraction in one launch: the first blocks_x workgroups cut the input, the rest the
-// weights, either in their own order or (FullyConnected, transposed != 0) one 64 x 32 tile per workgroup.
+// weights, either in their own order or (FullyConnected, transposed != 0) one 64 x 64 tile per workgroup.
 __global__ __launch_bounds__(256) void pack2_pair_kernel(const float* __restrict__ x, unsigned short* __restrict__ xp,
                                                          long long x_count8, long long x_elems, int blocks_x,
                                                          unsigned* __restrict__ x_trailer,
                                                          const float* __restrict__ w, unsigned short* __restrict__ wp,
                                                          long long w_count8, long long w_elems, int transposed, int K,
                                                          int N, int tiles_n, unsigned* __restrict__ w_trailer) {
-  __shared__ float tile[64][33];
+  __shared__ float tile[kPackTile][kPackTile + 1];
   const int b = (int)blockIdx.x;
   if (b < blocks_x) pack2_rows(x, xp, x_count8, x_elems, b, blocks_x, x_trailer);
   else if (transposed) pack2_transposed(w, wp, K, N, tiles_n, b - blocks_x, tile, w_trailer);
@@ -552,7 +571,7 @@ hipError_t launch_cut_filter(const float* w, void* dst, int b_is_kn, int K, int 
                        w_elems, trailer);
     return hipGetLastError();
   }
-  const int tn = (N + 31) / 32;
+  const int tn = (N + kPackTile - 1) / kPackTile;
   const long long blocks = (long long)((K + 63) / 64) * tn;
   hipLaunchKernelGGL(pack2_transposed_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, w, static_cast<unsigned short*>(dst), K,
                      N, tn, trailer);
@@ -586,12 +605,12 @@ size_t p3_pack_bytes(const Problem& p) {
   return tensor_planes_bytes(p.x_bytes >> 2) + (p.w_packed ? 0 : filter_planes_bytes(p.w_bytes >> 2));
 }
 
-// Worth it when the contraction is large against the one-off cost of cutting both operands (about ten bytes
-// of memory traffic per element), the operands' shapes allow 16-byte plane chunks, and there are enough
-// pixels and channels for the 128-pixel tiles.  Measured break-even: 400-600 flops per operand element
-// (FullyConnected 256 x 4096 x 4096, 483 flops per element: launched back to back 86 us here against 106 us on
-// the fp32 matrix cores, but 102 against 99 us inside a step of other layers, where its 100 MB of planes are
-// written and read cold; 512 x 4096 x 4096, 910 per element: 135 against 205 us).
+// Worth it when the contraction is large against the one-off cost of measuring and cutting both operands (twelve
+// bytes of memory traffic per element), the operands' shapes allow 16-byte plane chunks, and there are enough
+// pixels and channels for the 128-pixel tiles.  Measured break-even: about 400 flops per operand element that the
+// call has to cut (FullyConnected 256 x 4096 x 4096, 483 flops per element: 91 us here against 117 us on the fp32
+// matrix cores inside a step of other layers, 84 against 103 launched back to back; 256 x 9216 x 4096 169 against
+// 230 us).
 bool p3_f32_applicable(const Problem& p) {
   if (knob_or(KNOB_F32_P3, 1) == 0) return false;
   if (p.chain_n > 0 || p.cg % 8 != 0 || p.c % 8 != 0) return false;
@@ -607,7 +626,7 @@ bool p3_f32_applicable(const Problem& p) {
   // three launches (two packing kernels and the contraction) are worth ~15 us before any work is done
   if (min_m > 1 && flops < 2e9) return false;
   const double elems = (double)(p.x_bytes >> 2) + (p.w_packed ? 0.0 : (double)(p.w_bytes >> 2));   // what this call cuts
-  return flops >= (double)knob_or(KNOB_F32_P3_RATIO, 600) * elems;
+  return flops >= (double)knob_or(KNOB_F32_P3_RATIO, 400) * elems;
 }
 
 Plan plan_p3_f32(const Problem& p) {
@@ -691,7 +710,7 @@ hipError_t launch_p3_f32(const Problem& p_in, const Plan& plan, hipStream_t stre
     long long bw;
     int tn = 0;
     if (p.b_is_kn) {
-      tn = (p.k + 31) / 32;
+      tn = (p.k + kPackTile - 1) / kPackTile;
       bw = (long long)((p.Kgemm + 63) / 64) * tn;
     } else {
       bw = (wc8 + 255) / 256;

@@ -256,12 +256,13 @@ def test_fc_packed(shape, split, knobs):
 
 
 def test_fc_packed_takes_the_plane_kernel_where_the_plain_call_does_not():
-    """256 x 4096 x 4096 with the default planner: cutting 16 M weights in every call costs more than the kernel
-    over planes gains, so the plain call stays on the fp32 matrix cores; with the planes given it moves."""
+    """256 x 8192 x 512 with the default planner: 341 flops per operand element when the call has to cut 4 M weights
+    as well, less than the kernel over planes needs to pay for the cutting, so the plain call stays on the fp32 matrix
+    cores; with the planes given only the input is cut and the call moves."""
     import torch
     import paper_1805_00907_amd as glowmi
     G = _gpu()
-    M, K, N = 256, 4096, 4096
+    M, K, N = 256, 8192, 512
     a, w, b = wl.fc_inputs_f32(wl.FcLayer("packed", M, K, N), 36700, dist="uniform_fan_in")
     ref = oracle.fc_f32(a, w, b, act=wl.ACT_NONE)
     plain, v_plain = G.gpu_fc_f32(a, w, b, wl.ACT_NONE)
@@ -273,8 +274,8 @@ def test_fc_packed_takes_the_plane_kernel_where_the_plain_call_does_not():
     glowmi.fc_packed(ad, wd, planes, bd, y, M, K, N, wl.ACT_NONE, G.workspace(glowmi.fc_packed_workspace_bytes(M, K, N)))
     torch.cuda.synchronize()
     assert glowmi.last_variant().startswith("igemm_f32_p3"), glowmi.last_variant()
-    G.assert_close_f32(y.cpu().numpy(), ref, "packed fc 256x4096x4096")
-    G.assert_close_f32(plain, ref, "plain fc 256x4096x4096")
+    G.assert_close_f32(y.cpu().numpy(), ref, "packed fc 256x8192x512")
+    G.assert_close_f32(plain, ref, "plain fc 256x8192x512")
     # without a workspace for the input's planes the packed call falls back like the plain one
     y2 = G.poison((M, N), torch.float32)
     glowmi.fc_packed(ad, wd, planes, bd, y2, M, K, N, wl.ACT_NONE, None)
