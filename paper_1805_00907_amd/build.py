@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libglowmi.so")
-SOURCES = ["api.hip", "igemm_f32.hip", "igemm_i8.hip", "igemm_i8_wide.hip", "conv_k3c64_i8.hip", "fc_small_i8.hip", "conv_smallc_f32.hip", "conv_pw_f32.hip", "conv_small_f32.hip", "conv_smallc_i8.hip", "conv_pw_i8.hip", "elementwise.hip", "sequence.hip", "fc_small_f32.hip", "igemm_f32_p3.hip", "conv_k3c64_f32.hip", "conv_k3_f32.hip", "conv_k3v_f32.hip"]
+SOURCES = ["api.hip", "igemm_f32.hip", "igemm_i8.hip", "igemm_i8_wide.hip", "conv_k3c64_i8.hip", "fc_small_i8.hip", "conv_smallc_f32.hip", "conv_pw_f32.hip", "conv_small_f32.hip", "conv_smallc_i8.hip", "conv_pw_i8.hip", "elementwise.hip", "sequence.hip", "fc_small_f32.hip", "igemm_f32_p3.hip", "conv_k3c64_f32.hip", "conv_k3_f32.hip", "conv_k3v_f32.hip", "conv_dw.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",

@@ -37,7 +37,7 @@ const char* const kKnobNames[KNOB_COUNT] = {
     "F32_TILE", "F32_SPLIT", "F32_P3", "F32_P3_MIN_M", "F32_P3_RATIO", "F32_P3_BN", "F32_K3C64", "F32_K3C64_MIN_TILES", "F32_K3", "F32_K3_ANY", "F32_K3V", "F32_K3_TH", "F32_K3_TW", "F32_PW_MIN_ITEMS", "F32_PW_BF16", "F32_SMALL_MAX_TILES", "F32_SMALL_NO_SPLIT",
     "F32_SMALL_SPLIT_MAX_TILES", "F32_SMALL_MIN_WGS", "F32_FC_SMALL_OFF", "F32_FC_SMALL_VW", "F32_FC_SMALL_MAX_KB", "F32_FC_SMALL_MIN_M", "SMALLC_TH", "F32_SMALLC_BF16",
     "I8_TILE", "I8_WIDE_SPLIT", "I8_WIDE_NBUF", "SMALLC_I8_WGS", "I8_PW_MIN_ITEMS",
-    "I8_FC_SMALL_MAX_M", "I8_K3_MIN_BLOCKS", "I8_K3_WAVES", "I8_K3_GATHER",
+    "I8_FC_SMALL_MAX_M", "I8_K3_MIN_BLOCKS", "I8_K3_WAVES", "I8_K3_GATHER", "DW",
 };
 std::atomic<int> g_knobs[KNOB_COUNT];
 std::once_flag g_knobs_once;

@@ -20,7 +20,7 @@ enum Knob {
   KNOB_F32_TILE, KNOB_F32_SPLIT, KNOB_F32_P3, KNOB_F32_P3_MIN_M, KNOB_F32_P3_RATIO, KNOB_F32_P3_BN, KNOB_F32_K3C64, KNOB_F32_K3C64_MIN_TILES, KNOB_F32_K3, KNOB_F32_K3_ANY, KNOB_F32_K3V, KNOB_F32_K3_TH, KNOB_F32_K3_TW, KNOB_F32_PW_MIN_ITEMS, KNOB_F32_PW_BF16, KNOB_F32_SMALL_MAX_TILES, KNOB_F32_SMALL_NO_SPLIT,
   KNOB_F32_SMALL_SPLIT_MAX_TILES, KNOB_F32_SMALL_MIN_WGS, KNOB_F32_FC_SMALL_OFF, KNOB_F32_FC_SMALL_VW, KNOB_F32_FC_SMALL_MAX_KB, KNOB_F32_FC_SMALL_MIN_M, KNOB_SMALLC_TH, KNOB_F32_SMALLC_BF16,
   KNOB_I8_TILE, KNOB_I8_WIDE_SPLIT, KNOB_I8_WIDE_NBUF, KNOB_SMALLC_I8_WGS, KNOB_I8_PW_MIN_ITEMS,
-  KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER,
+  KNOB_I8_FC_SMALL_MAX_M, KNOB_I8_K3_MIN_BLOCKS, KNOB_I8_K3_WAVES, KNOB_I8_K3_GATHER, KNOB_DW,
   KNOB_COUNT
 };
 constexpr int kKnobUnset = INT_MIN;
@@ -124,7 +124,8 @@ enum KernelKind {
   KERNEL_FC_SMALL,      // FullyConnected with few rows in one launch (fp32: fc_small_f32.hip, int8: fc_small_i8.hip)
   KERNEL_WIDE,          // int8 large contractions (igemm_i8_wide.hip)
   KERNEL_K3,            // fp32 3x3 stride-1 convolution on well-tiling maps, fp16 matrix cores (conv_k3_f32.hip)
-  KERNEL_P3             // fp32 large contractions on the fp16 matrix cores, operands cut into two pieces (igemm_f32_p3.hip)
+  KERNEL_P3,            // fp32 large contractions on the fp16 matrix cores, operands cut into two pieces (igemm_f32_p3.hip)
+  KERNEL_DW             // depthwise 3x3 convolution, fp32 and int8 (conv_dw.hip)
 };
 struct Plan {
   int kernel;           // KernelKind
@@ -189,6 +190,11 @@ hipError_t launch_k3_f32(const Problem& p, hipStream_t stream, const char** vari
 double k3v_f32_efficiency(const Problem& p);
 bool k3v_f32_prefers_fixed_tile(const Problem& p);
 hipError_t launch_k3v_f32(const Problem& p, hipStream_t stream, const char** variant);
+// Depthwise 3x3 convolution, stride 1 or 2, channels a multiple of four, no tensor operand behind it (conv_dw.hip).
+bool dw_f32_applicable(const Problem& p);
+hipError_t launch_dw_f32(const Problem& p, hipStream_t stream, const char** variant);
+bool dw_i8_applicable(const Problem& p);
+hipError_t launch_dw_i8(const Problem& p, hipStream_t stream, const char** variant);
 // Finishing kernel of a split fp32 reduction (igemm_f32.hip): sums p.partial in split order, bias, addend, activation.
 hipError_t launch_splitk_finish_f32(const Problem& p, const Plan& plan, hipStream_t stream);
 bool pw_i8_applicable(const Problem& p);

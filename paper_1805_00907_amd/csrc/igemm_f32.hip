@@ -674,6 +674,7 @@ Plan plan_f32(const Problem& p, bool allow_split) {
   const bool forced = forced_tile != kKnobUnset;
   if (!forced) {
     // kernels of their own, no workspace
+    if (dw_f32_applicable(p)) { pl.kernel = KERNEL_DW; return pl; }
     if (smallc_f32_applicable(p) && !p.addend) { pl.kernel = KERNEL_SMALLC; return pl; }
     // 3x3 over 64 channels on many pixels, with the filter's planes given or room in the workspace for them
     const bool filter_planes = p.w_packed != nullptr || (allow_split && p.allow_pack);   // given, or room to make them
@@ -823,6 +824,7 @@ hipError_t launch_splitk_finish_f32(const Problem& p, const Plan& plan, hipStrea
 
 hipError_t launch_f32(const Problem& p_in, const Plan& plan, hipStream_t stream, const char** variant) {
   switch (plan.kernel) {
+    case KERNEL_DW: return launch_dw_f32(p_in, stream, variant);
     case KERNEL_SMALLC: return launch_smallc_f32(p_in, stream, variant);
     case KERNEL_PW: return launch_pw_f32(p_in, stream, variant);
     case KERNEL_SMALL: return launch_conv_small_f32(p_in, stream, variant);

@@ -534,6 +534,7 @@ Plan plan_i8(const Problem& p, bool allow_split) {
   if (p.chain_n > 0) forced = 0;                  // a general chain: only the generic 64 x 64 kernel implements it
   if (forced < 0) {
     // kernels of their own, no workspace
+    if (dw_i8_applicable(p)) { pl.kernel = KERNEL_DW; return pl; }
     if (smallc_i8_applicable(p) && !p.addend) { pl.kernel = KERNEL_SMALLC; return pl; }
     if (pw_i8_applicable(p)) { pl.kernel = KERNEL_PW; return pl; }
     if (k3c64_i8_applicable(p)) { pl.kernel = KERNEL_K3C64; return pl; }
@@ -591,6 +592,7 @@ Plan plan_i8(const Problem& p, bool allow_split) {
 
 hipError_t launch_i8(const Problem& p_in, const Plan& plan, hipStream_t stream, const char** variant) {
   switch (plan.kernel) {
+    case KERNEL_DW: return launch_dw_i8(p_in, stream, variant);
     case KERNEL_SMALLC: return launch_smallc_i8(p_in, stream, variant);
     case KERNEL_PW: return launch_pw_i8(p_in, stream, variant);
     case KERNEL_K3C64: return launch_k3c64_i8(p_in, stream, variant);

@@ -1,0 +1,141 @@
+"""Depthwise 3x3 convolution (groups == channels, one filter per channel), fp32 and int8, through the C ABI
+against the CPU oracle element by element: fp32 within 1e-5 + 1e-4 |oracle|, int8 bit-exact.  Strides 1 and 2,
+every kind of padding, output widths that are not a multiple of the four-pixel runs the kernel walks, channel
+counts from one quad to more than a wavefront's worth, a batch, no bias, both requantize forms, a filter offset,
+uniformly drawn codes (saturation), and a layer at a network's real size.  Shapes the kernel does not take
+(channels not a multiple of four, another filter size, a tensor operand behind the layer, groups of more than
+one channel) must still be right on the generic kernels.
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle
+from paper_1805_00907_amd import workloads as wl
+
+
+def _gpu():
+    import gpu_util
+    return gpu_util
+
+
+# n  h  w  c  stride  pads (top, left, bottom, right)
+SHAPES = [
+    (1, 8, 8, 4, 1, (1, 1, 1, 1)),          # one channel quad
+    (2, 13, 17, 8, 1, (1, 1, 1, 1)),        # ragged runs (17 = 4 * 4 + 1), a batch
+    (1, 9, 22, 64, 1, (0, 0, 0, 0)),        # no padding, 20 output columns
+    (3, 14, 15, 132, 1, (1, 0, 0, 1)),      # asymmetric padding, 33 quads: wavefronts straddle pixels
+    (1, 5, 6, 256, 1, (2, 2, 2, 2)),        # padding wider than the filter needs
+    (2, 16, 19, 32, 2, (1, 1, 1, 1)),       # stride 2, odd width
+    (1, 15, 15, 96, 2, (0, 1, 1, 0)),       # stride 2, asymmetric padding
+    (1, 3, 3, 16, 1, (0, 0, 0, 0)),         # a single output pixel
+    (4, 28, 28, 128, 1, (1, 1, 1, 1)),      # more runs than one pass of the grid's threads per quad on small chips
+    (1, 112, 112, 64, 2, (1, 1, 1, 1)),     # a network's first depthwise stage
+]
+
+
+def _layer(i):
+    n, h, w, c, st, pd = SHAPES[i]
+    return n, h, w, c, st, pd
+
+
+@pytest.mark.parametrize("i", range(len(SHAPES)))
+def test_depthwise_f32(i):
+    G = _gpu()
+    n, h, w, c, st, pd = _layer(i)
+    rng = np.random.default_rng(38000 + i)
+    x = rng.standard_normal(size=(n, h, w, c)).astype(np.float32)
+    wt = (rng.standard_normal(size=(c, 3, 3, 1)) / 3).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(c,)).astype(np.float32)
+    desc = G.make_desc(x.shape, wt.shape, (st, st), pd, c)
+    for act, bias in ((wl.ACT_RELU, b), (wl.ACT_NONE, None)):
+        ref = oracle.conv2d_f32(x, wt, bias, (st, st), pd, c, act=act)
+        got, variant = G.gpu_conv2d_f32(x, wt, bias, desc, act)
+        assert variant == f"conv_dw_f32_3x3s{st}", variant
+        G.assert_close_f32(got, ref, f"depthwise fp32 {SHAPES[i]} act {act}")
+        got, variant = G.gpu_conv2d_f32(x, wt, bias, desc, act, use_workspace=False)
+        assert variant == f"conv_dw_f32_3x3s{st}", variant
+        G.assert_close_f32(got, ref, f"depthwise fp32 {SHAPES[i]} act {act} without a workspace")
+
+
+@pytest.mark.parametrize("i", range(len(SHAPES)))
+@pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", -7)])
+def test_depthwise_int8(i, dist, w_off):
+    G = _gpu()
+    n, h, w, c, st, pd = _layer(i)
+    layer = wl.ConvLayer(f"dw{i}", n, h, w, c, c, 3, 3, st, 1, c)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 38100 + i, dist=dist, w_off=w_off)
+    desc = G.make_desc(xq.shape, wq.shape, (st, st), pd, c)
+    for act, bias in ((wl.ACT_RELU, bq), (wl.ACT_NONE, None)):
+        ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bias, qp.y_scale, qp.y_off,
+                             (st, st), pd, c, act=act)
+        got, variant = G.gpu_qconv2d(xq, wq, bias, qp, desc, act)
+        assert variant == f"conv_dw_i8_3x3s{st}", variant
+        G.assert_equal_i8(got, ref, f"depthwise int8 {SHAPES[i]} {dist} act {act}")
+
+
+@pytest.mark.parametrize("y_scale_factor", [2.0, 64.0])
+def test_depthwise_int8_both_requantize_forms(y_scale_factor):
+    """Multipliers of 1/4 and more take the 64-bit form, smaller ones the multiply-high."""
+    G = _gpu()
+    layer = wl.ConvLayer("dwq", 2, 12, 14, 24, 24, 3, 3, 1, 1, 24)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 38200, dist="normal", w_off=3)
+    qp = wl.QParams(qp.x_scale, qp.x_off, qp.w_scale, qp.w_off, qp.x_scale * qp.w_scale * y_scale_factor, qp.y_off)
+    desc = G.make_desc(xq.shape, wq.shape, (1, 1), (1, 1, 1, 1), 24)
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                         (1, 1), (1, 1, 1, 1), 24, act=wl.ACT_NONE)
+    got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, wl.ACT_NONE)
+    assert variant == "conv_dw_i8_3x3s1", variant
+    G.assert_equal_i8(got, ref, f"depthwise int8, multiplier 1/{y_scale_factor}")
+
+
+def test_shapes_the_depthwise_kernel_leaves_to_the_generic_ones():
+    G = _gpu()
+    rng = np.random.default_rng(38300)
+    cases = [
+        (6, 6, 3, 1),       # channels not a multiple of four
+        (8, 8, 5, 1),       # 5 x 5 filter
+        (16, 4, 3, 1),      # four groups of four channels: not depthwise
+        (8, 8, 3, 3),       # stride 3
+    ]
+    for c, groups, r, st in cases:
+        x = rng.standard_normal(size=(2, 11, 13, c)).astype(np.float32)
+        wt = (rng.standard_normal(size=(c, r, r, c // groups)) / r).astype(np.float32)
+        b = rng.uniform(-0.1, 0.1, size=(c,)).astype(np.float32)
+        pd = (r // 2,) * 4
+        desc = G.make_desc(x.shape, wt.shape, (st, st), pd, groups)
+        ref = oracle.conv2d_f32(x, wt, b, (st, st), pd, groups, act=wl.ACT_RELU)
+        got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)
+        assert not variant.startswith("conv_dw"), (variant, c, groups, r, st)
+        G.assert_close_f32(got, ref, f"generic path c {c} groups {groups} filter {r} stride {st}")
+    # a tensor operand behind a depthwise layer: the generic kernels' chain
+    c = 16
+    x = rng.standard_normal(size=(1, 9, 9, c)).astype(np.float32)
+    wt = (rng.standard_normal(size=(c, 3, 3, 1)) / 3).astype(np.float32)
+    b = rng.uniform(-0.1, 0.1, size=(c,)).astype(np.float32)
+    add = rng.standard_normal(size=(1, 9, 9, c)).astype(np.float32)
+    desc = G.make_desc(x.shape, wt.shape, (1, 1), (1, 1, 1, 1), c)
+    ref = oracle.conv2d_f32_add(x, wt, b, add, (1, 1), (1, 1, 1, 1), c, act=wl.ACT_RELU)
+    got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, desc, wl.ACT_RELU)
+    assert not variant.startswith("conv_dw"), variant
+    G.assert_close_f32(got, ref, "depthwise with a tensor add behind it")
+
+
+def test_depthwise_at_a_networks_size_fp32_and_int8():
+    """128 channels on 56 x 56 at batch 32, the shape bench.py times: every output element."""
+    G = _gpu()
+    layer = wl.ConvLayer("dw_c128_56", 32, 56, 56, 128, 128, 3, 3, 1, 1, 128)
+    x, wt, b = wl.conv_inputs_f32(layer, 38400)
+    desc = G.desc_of(layer)
+    ref = oracle.conv2d_f32(x, wt, b, (1, 1), (1, 1, 1, 1), 128, act=wl.ACT_RELU)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)
+    assert variant == "conv_dw_f32_3x3s1", variant
+    G.assert_close_f32(got, ref, "depthwise fp32 128 @56 batch 32")
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 38401)
+    ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
+                         (1, 1), (1, 1, 1, 1), 128, act=wl.ACT_RELU)
+    for fill in (77, -5):
+        got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, wl.ACT_RELU, fill=fill)
+        assert variant == "conv_dw_i8_3x3s1", variant
+        G.assert_equal_i8(got, ref, f"depthwise int8 128 @56 batch 32 (output pre-filled with {fill})")
