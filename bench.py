@@ -65,7 +65,8 @@ GRAPH_LAUNCHES = 100
 SMALL_LAYER_US = 16.0
 
 WORKLOADS = ["vgg19_fp32", "resnet50_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8",
-             "resnet50_tail_fp32", "resnet50_tail_int8", "resnet50_block_fp32", "resnet50_block_int8"]
+             "resnet50_tail_fp32", "resnet50_tail_int8", "resnet50_block_fp32", "resnet50_block_int8",
+             "depthwise_fp32", "depthwise_int8"]
 HEADLINE = "vgg19_fp32"        # largest single-GPU baseline configuration
 ALSO = ["resnet50_fp32", "resnet50_int8", "fc_sweep_fp32", "fc_sweep_int8"]   # the other baseline configurations
 CHAINED = {"resnet50_block_fp32", "resnet50_block_int8"}   # layers feed each other: run as one sequence
@@ -97,6 +98,10 @@ def _build_workload(name):
         return "f32", 6, wl.resnet50_bottleneck(32)
     if name == "resnet50_block_int8":
         return "i8", 6, wl.resnet50_bottleneck(32)
+    if name == "depthwise_fp32":       # one 3x3 filter per channel: nine products per output, a stream through HBM
+        return "f32", 7, wl.depthwise_layers(32)
+    if name == "depthwise_int8":
+        return "i8", 7, wl.depthwise_layers(32)
     raise SystemExit(f"unknown workload {name}; choose from {WORKLOADS}")
 
 

@@ -392,7 +392,9 @@ glowmi_status glowmi_rescale_params(float r_scale, float x_scale, float w_scale,
  * "F32_SMALLC_BF16" (the first-layer kernel's piece-product form, whatever the pieces' type) = 0 keep a layer on the
  * fp32 matrix cores; "F32_K3V" = 0 keeps the 3x3 kernel on its
  * fixed 16 x 16 pixel tile and "F32_K3_TH" / "F32_K3_TW" force a tile of that many rows / columns, at most 256
- * pixels, 64 columns and (rows + 2) x (columns + 4) <= 360, else ignored); only the choice of kernel changes.
+ * pixels, 64 columns and (rows + 2) x (columns + 4) <= 360, else ignored; "DW" = 0 keeps depthwise 3x3 layers,
+ * groups == c == k, off their own kernel, 2 / 3 make its threads walk one / two output rows at a time); only the
+ * choice of kernel changes.
  * glowmi_tuning_reset() returns every knob to "the planner's own choice" (it does not re-read the
  * environment).  Not thread-safe against concurrent launches that should see a consistent setting.
  * GLOWMI_ERR_UNSUPPORTED for an unknown name.

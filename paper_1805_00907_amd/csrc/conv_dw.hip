@@ -4,15 +4,17 @@
 // output through the chip: nothing here is a matrix product, so no matrix cores and no LDS; what matters is that
 // every byte is fetched in whole cache lines and as few times as possible.
 //   - a thread owns four consecutive channels (fp32: one 16-byte piece of a pixel; int8: one dword) and a run of
-//     DW_RUN consecutive output pixels of one row; consecutive threads own consecutive channel quads, so a
-//     wavefront's load covers whole pixels (C = 128: two pixels of 512 bytes per fp32 load instruction);
-//   - the 3 x (DW_RUN - 1) * stride + 3 input columns the run needs are loaded once into registers and serve all
-//     of its outputs (stride 1: 18 loads for 4 outputs instead of 36); rows and columns outside the image come
-//     back as zeros from range-checked buffer loads (int8: and are then replaced by the code of real zero);
+//     DW_RUN consecutive output pixels on one or two output rows; consecutive threads own consecutive channel
+//     quads, so a wavefront's load covers whole pixels (C = 128: two pixels of 512 bytes per fp32 load instruction);
+//   - the input window of the run (two rows at stride 1: 4 x 6 pixels for 8 outputs) is loaded once into registers
+//     and serves all of its outputs; rows and columns outside the image come back as zeros from range-checked
+//     buffer loads (int8: and are then replaced by the code of real zero);
 //   - a thread's channel quad never changes (the grid is a multiple of the channel quads), so its 36 filter values
 //     and its bias are fetched once and stay in registers while it walks over runs;
+//   - neighbouring runs share input rows, so every XCD works on one contiguous eighth of the runs and finds the
+//     shared rows in its own L2 (12.8 M outputs of 128 channels at 56 x 56: 32 -> 24 us);
 //   - bias, Relu (int8: the requantize of Section 4.3 with Relu as the lower clamp bound) and one 16-byte (int8:
-//     4-byte) store per output pixel.
+//     4-byte) store per output pixel, predicated on the pixel being inside the output.
 // Other filter sizes, strides above 2, channel counts that are not a multiple of four and layers with a tensor
 // operand behind them stay on the generic kernels.
 #include <hip/hip_runtime.h>
@@ -26,26 +28,67 @@ namespace glowmi {
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
-typedef int v4i_ __attribute__((ext_vector_type(4)));
 
-constexpr int DW_RUN = 4;                      // output pixels per run
+constexpr int DW_RUN = 4;                      // output pixels of one row per run
 constexpr int DW_THREADS = 256;
 constexpr unsigned DW_OOB = 0xFFFFFF00u;       // beyond any tensor these kernels accept: loads give zeros
 
 struct DwGrid {
   int cq;                                      // channel quads
   int runs_w;                                  // runs per output row
-  long long runs;                              // n * oh * runs_w
+  int strips;                                  // strips of ROWS output rows per image
+  long long runs;                              // n * strips * runs_w
   int slots;                                   // threads per channel quad
+  int blocks;                                  // workgroups that hold threads
+  int per_xcd;                                 // workgroups per XCD (the launch has 8 * per_xcd)
 };
 
-template <int STRIDE>
+// Workgroups are dealt to the eight XCDs in turn; a filter window's rows are shared by neighbouring runs, so
+// each XCD takes one contiguous eighth of the runs and finds its neighbours' rows in its own L2.
+__device__ __forceinline__ long long dw_thread(const DwGrid& g) {
+  const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3;
+  const int logical = xcd * g.per_xcd + idx;
+  if (idx >= g.per_xcd || logical >= g.blocks) return -1;
+  return (long long)logical * DW_THREADS + threadIdx.x;
+}
+
+struct DwRun {
+  int img, oh0, ow0;
+};
+
+__device__ __forceinline__ DwRun dw_run(const DwGrid& g, unsigned run, int rows) {
+  DwRun r;
+  const unsigned rw = run % (unsigned)g.runs_w;
+  const unsigned t2 = run / (unsigned)g.runs_w;
+  r.oh0 = (int)(t2 % (unsigned)g.strips) * rows;
+  r.img = (int)(t2 / (unsigned)g.strips);
+  r.ow0 = (int)rw * DW_RUN;
+  return r;
+}
+
+// Byte offsets of the XROWS x COLS input pixels of a run, for the thread's channels: the window's first pixel plus
+// whole rows and columns, or the out-of-range mark where the row or column lies outside the image.
+template <int XROWS, int COLS>
+struct DwWindow {
+  unsigned base;            // of pixel (ih0, iw0), channel c0; wraps when that pixel is outside: never used then
+  bool row_ok[XROWS], col_ok[COLS];
+  __device__ __forceinline__ DwWindow(const Problem& p, const DwRun& rn, int stride, unsigned c0_bytes, unsigned elem) {
+    const int ih0 = rn.oh0 * stride - p.pad_t, iw0 = rn.ow0 * stride - p.pad_l;
+    base = (unsigned)((rn.img * p.h + ih0) * p.w_ + iw0) * ((unsigned)p.c * elem) + c0_bytes;
+#pragma unroll
+    for (int r = 0; r < XROWS; ++r) row_ok[r] = (unsigned)(ih0 + r) < (unsigned)p.h;
+#pragma unroll
+    for (int c = 0; c < COLS; ++c) col_ok[c] = (unsigned)(iw0 + c) < (unsigned)p.w_;
+  }
+};
+
+template <int STRIDE, int ROWS>
 __global__ __launch_bounds__(DW_THREADS) void conv_dw_f32_kernel(const Problem p, const DwGrid g) {
-  constexpr int COLS = (DW_RUN - 1) * STRIDE + 3;
-  const long long gid = (long long)blockIdx.x * DW_THREADS + threadIdx.x;
-  if (gid >= (long long)g.cq * g.slots) return;
-  const int cq = (int)(gid % g.cq);
-  const int slot = (int)(gid / g.cq);
+  constexpr int COLS = (DW_RUN - 1) * STRIDE + 3, XROWS = (ROWS - 1) * STRIDE + 3;
+  const long long gid = dw_thread(g);
+  if (gid < 0 || gid >= (long long)g.cq * g.slots) return;
+  const int cq = (int)((unsigned)gid % (unsigned)g.cq);
+  const int slot = (int)((unsigned)gid / (unsigned)g.cq);
   const int c0 = cq * 4;
 
   const float* __restrict__ W = static_cast<const float*>(p.w);
@@ -54,62 +97,70 @@ __global__ __launch_bounds__(DW_THREADS) void conv_dw_f32_kernel(const Problem p
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.x), 0, (int)p.x_bytes, 0x00020000);
   float* __restrict__ Y = static_cast<float*>(p.y);
 
-  // filter [k][3][3][1]: channel c's nine values are contiguous
+  // filter [k][3][3][1]: channel c's nine values are contiguous, the quad's 36 values one 144-byte piece:
+  // nine 16-byte loads, then sorted by tap
+  v4f wq[9];
+#pragma unroll
+  for (int i = 0; i < 9; ++i) wq[i] = reinterpret_cast<const v4f*>(W + (size_t)c0 * 9)[i];
   v4f w[9];
 #pragma unroll
-  for (int t = 0; t < 9; ++t) w[t] = v4f{W[(c0 + 0) * 9 + t], W[(c0 + 1) * 9 + t], W[(c0 + 2) * 9 + t], W[(c0 + 3) * 9 + t]};
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) w[t][e] = wq[(e * 9 + t) / 4][(e * 9 + t) % 4];
   v4f bv = {0.f, 0.f, 0.f, 0.f};
-  if (bias) bv = v4f{bias[c0], bias[c0 + 1], bias[c0 + 2], bias[c0 + 3]};
+  if (bias) bv = v4f{bias[c0], bias[c0 + 1], bias[c0 + 2], bias[c0 + 3]};     // bias is only 4-byte aligned
   const bool relu = p.act == 1;
+  const unsigned col_bytes = (unsigned)p.c * 4u, row_bytes = (unsigned)p.w_ * col_bytes;
 
-  for (long long run = slot; run < g.runs; run += g.slots) {
-    const int rw = (int)(run % g.runs_w);
-    const long long t2 = run / g.runs_w;
-    const int oh = (int)(t2 % p.oh);
-    const int img = (int)(t2 / p.oh);
-    const int ow0 = rw * DW_RUN;
-    const int ih0 = oh * STRIDE - p.pad_t, iw0 = ow0 * STRIDE - p.pad_l;
+  for (unsigned run = (unsigned)slot; run < (unsigned)g.runs; run += (unsigned)g.slots) {
+    const DwRun rn = dw_run(g, run, ROWS);
+    const DwWindow<XROWS, COLS> win(p, rn, STRIDE, (unsigned)c0 * 4u, 4u);
 
-    v4f x[3][COLS];
+    v4f x[XROWS][COLS];
 #pragma unroll
-    for (int r = 0; r < 3; ++r) {
-      const int ih = ih0 + r;
-      const bool row_ok = (unsigned)ih < (unsigned)p.h;
+    for (int r = 0; r < XROWS; ++r)
 #pragma unroll
-      for (int c = 0; c < COLS; ++c) {
-        const int iw = iw0 + c;
-        const bool ok = row_ok && (unsigned)iw < (unsigned)p.w_;
-        const unsigned off = ok ? ((unsigned)((img * p.h + ih) * p.w_ + iw) * (unsigned)p.c + (unsigned)c0) * 4u : DW_OOB;
-        x[r][c] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0));
+      for (int c = 0; c < COLS; ++c)
+        x[r][c] = __builtin_bit_cast(
+            v4f, __builtin_amdgcn_raw_buffer_load_b128(
+                     rsrc_x, win.row_ok[r] && win.col_ok[c] ? win.base + r * row_bytes + c * col_bytes : DW_OOB, 0, 0));
+    float* yrow = Y + ((size_t)(rn.img * p.oh + rn.oh0) * p.ow + rn.ow0) * p.k + c0;
+#pragma unroll
+    for (int ro = 0; ro < ROWS; ++ro) {
+#pragma unroll
+      for (int o = 0; o < DW_RUN; ++o) {
+        v4f acc = bv;
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+          for (int s = 0; s < 3; ++s) acc += x[ro * STRIDE + r][o * STRIDE + s] * w[r * 3 + s];
+        if (relu) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[e] = fmaxf(acc[e], 0.f);
+        }
+        if (rn.oh0 + ro < p.oh && rn.ow0 + o < p.ow)
+          *reinterpret_cast<v4f*>(yrow + ((size_t)ro * p.ow + o) * p.k) = acc;
       }
-    }
-#pragma unroll
-    for (int o = 0; o < DW_RUN; ++o) {
-      const int ow = ow0 + o;
-      if (ow >= p.ow) break;
-      v4f acc = bv;
-#pragma unroll
-      for (int r = 0; r < 3; ++r)
-#pragma unroll
-        for (int s = 0; s < 3; ++s) acc += x[r][o * STRIDE + s] * w[r * 3 + s];
-      if (relu) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[e] = fmaxf(acc[e], 0.f);
-      }
-      *reinterpret_cast<v4f*>(Y + ((size_t)(img * p.oh + oh) * p.ow + ow) * p.k + c0) = acc;
     }
   }
 }
 
-// The int8 form: codes minus offsets multiplied in int32 (a tap on padding is the code of real zero, i.e. adds
-// nothing), int32 bias, requantize with the integer multiplier, Relu as the lower clamp bound, four codes per store.
-template <int STRIDE>
+// The int8 form.  A thread's dword of the input holds the codes of its four channels at one pixel; the three
+// codes of a channel along a filter row are gathered into one dword with two byte permutes and multiplied with
+// the row's three filter codes by one four-way dot product.  Offsets are taken out of the sum,
+//   sum (x - xo)(w - wo) = sum x w - wo sum x - xo sum (w - wo),
+// where a tap on padding holds the code xo (it then adds nothing, as real zero must): the last term is a constant
+// of the channel and joins the bias, the middle one costs a second dot product and is left out (PLAIN) when the
+// filter has no offset.  All of it is arithmetic modulo 2^32, so the order does not matter.  Then the requantize
+// of Section 4.3 with the integer multiplier (PLAIN: the form with the rounding constant and the output offset
+// folded into one addend), Relu as the lower clamp bound, four codes per store.
+template <int STRIDE, int ROWS, bool PLAIN>
 __global__ __launch_bounds__(DW_THREADS) void conv_dw_i8_kernel(const Problem p, const DwGrid g) {
-  constexpr int COLS = (DW_RUN - 1) * STRIDE + 3;
-  const long long gid = (long long)blockIdx.x * DW_THREADS + threadIdx.x;
-  if (gid >= (long long)g.cq * g.slots) return;
-  const int cq = (int)(gid % g.cq);
-  const int slot = (int)(gid / g.cq);
+  constexpr int COLS = (DW_RUN - 1) * STRIDE + 3, XROWS = (ROWS - 1) * STRIDE + 3;
+  const long long gid = dw_thread(g);
+  if (gid < 0 || gid >= (long long)g.cq * g.slots) return;
+  const int cq = (int)((unsigned)gid % (unsigned)g.cq);
+  const int slot = (int)((unsigned)gid / (unsigned)g.cq);
   const int c0 = cq * 4;
 
   const signed char* __restrict__ W = static_cast<const signed char*>(p.w);
@@ -118,60 +169,76 @@ __global__ __launch_bounds__(DW_THREADS) void conv_dw_i8_kernel(const Problem p,
       __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p.x), 0, (int)p.x_bytes, 0x00020000);
   signed char* __restrict__ Y = static_cast<signed char*>(p.y);
 
-  int w[9][4];
+  // the quad's 36 filter codes are nine dwords; per channel and filter row one dword (w0, w1, w2, 0)
+  unsigned wq[9];
 #pragma unroll
-  for (int t = 0; t < 9; ++t)
+  for (int i = 0; i < 9; ++i) wq[i] = reinterpret_cast<const unsigned*>(W + (size_t)c0 * 9)[i];
+  int wr[3][4];
+  int kb[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) w[t][e] = (int)W[(c0 + e) * 9 + t] - p.w_off;
-  int bv[4] = {0, 0, 0, 0};
-  if (bias) {
-#pragma unroll
-    for (int e = 0; e < 4; ++e) bv[e] = bias[c0 + e];
-  }
-  const int xo_fill = (p.x_off & 0xff) * 0x01010101;     // padding = the code of real zero
-  const bool fast = p.shift >= 33;                        // uniform
-
-  for (long long run = slot; run < g.runs; run += g.slots) {
-    const int rw = (int)(run % g.runs_w);
-    const long long t2 = run / g.runs_w;
-    const int oh = (int)(t2 % p.oh);
-    const int img = (int)(t2 / p.oh);
-    const int ow0 = rw * DW_RUN;
-    const int ih0 = oh * STRIDE - p.pad_t, iw0 = ow0 * STRIDE - p.pad_l;
-
-    int x[3][COLS];
+  for (int e = 0; e < 4; ++e) {
+    int wsum = 0;
 #pragma unroll
     for (int r = 0; r < 3; ++r) {
-      const int ih = ih0 + r;
-      const bool row_ok = (unsigned)ih < (unsigned)p.h;
+      // codes i .. i + 2 of the 36 start in byte i % 4 of dword i / 4: an alignbyte of two dwords, top byte cleared
+      const int i = e * 9 + r * 3;
+      const unsigned lo = wq[i / 4], hi = wq[(i / 4 + 1) % 9];
+      const unsigned d = (i % 4 == 0 ? lo : __builtin_amdgcn_alignbyte(hi, lo, i % 4)) & 0x00ffffffu;
+      wr[r][e] = (int)d;
+      wsum = __builtin_amdgcn_sdot4((int)d, 0x00010101, wsum, false);
+    }
+    kb[e] = (bias ? bias[c0 + e] : 0) - p.x_off * (wsum - 9 * p.w_off);
+  }
+  const unsigned xo_fill = (unsigned)(p.x_off & 0xff) * 0x01010101u;     // padding = the code of real zero
+  const FoldedRequant fold = make_folded_requant(p.shift, p.y_off);
+  const bool fast = p.shift >= 33;                                        // uniform
+  const int lo_v = p.lo;
+  const unsigned col_bytes = (unsigned)p.c, row_bytes = (unsigned)p.w_ * col_bytes;
+
+  for (unsigned run = (unsigned)slot; run < (unsigned)g.runs; run += (unsigned)g.slots) {
+    const DwRun rn = dw_run(g, run, ROWS);
+    const DwWindow<XROWS, COLS> win(p, rn, STRIDE, (unsigned)c0, 1u);
+
+    unsigned x[XROWS][COLS];
+#pragma unroll
+    for (int r = 0; r < XROWS; ++r)
 #pragma unroll
       for (int c = 0; c < COLS; ++c) {
-        const int iw = iw0 + c;
-        const bool ok = row_ok && (unsigned)iw < (unsigned)p.w_;
-        const unsigned off = ok ? (unsigned)((img * p.h + ih) * p.w_ + iw) * (unsigned)p.c + (unsigned)c0 : DW_OOB;
-        const int v = __builtin_amdgcn_raw_buffer_load_b32(rsrc_x, off, 0, 0);   // issued whatever `ok` is: zeros when out of range
+        const bool ok = win.row_ok[r] && win.col_ok[c];
+        const unsigned v = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(
+            rsrc_x, ok ? win.base + r * row_bytes + c * col_bytes : DW_OOB, 0, 0);
         x[r][c] = ok ? v : xo_fill;
       }
-    }
+    signed char* yrow = Y + ((size_t)(rn.img * p.oh + rn.oh0) * p.ow + rn.ow0) * p.k + c0;
 #pragma unroll
-    for (int o = 0; o < DW_RUN; ++o) {
-      const int ow = ow0 + o;
-      if (ow >= p.ow) break;
-      int q[4];
+    for (int ro = 0; ro < ROWS; ++ro) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        int acc = bv[e];
+      for (int o = 0; o < DW_RUN; ++o) {
+        int q[4];
 #pragma unroll
-        for (int r = 0; r < 3; ++r)
+        for (int e = 0; e < 4; ++e) {
+          int acc = kb[e], xsum = 0;
 #pragma unroll
-          for (int s = 0; s < 3; ++s) {
-            const int code = (int)(signed char)(x[r][o * STRIDE + s] >> (8 * e));
-            acc += (code - p.x_off) * w[r * 3 + s][e];
+          for (int r = 0; r < 3; ++r) {
+            const unsigned* row = x[ro * STRIDE + r] + o * STRIDE;
+            // bytes (row[0].e, row[1].e, 0, 0), then (.., .., row[2].e, 0): selectors 0..3 name the second
+            // operand's bytes, 4..7 the first operand's, 12 a zero byte
+            const unsigned two = __builtin_amdgcn_perm(row[1], row[0], 0x0c0c0000u | (unsigned)e | ((4u + e) << 8));
+            const unsigned three = __builtin_amdgcn_perm(row[2], two, 0x0c000100u | ((4u + e) << 16));
+            acc = __builtin_amdgcn_sdot4((int)three, wr[r][e], acc, false);
+            if (!PLAIN) xsum = __builtin_amdgcn_sdot4((int)three, 0x00010101, xsum, false);
           }
-        q[e] = fast ? requantize_as<true>(acc, p.mant, p.shift, p.y_off, p.lo)
-                    : requantize_as<false>(acc, p.mant, p.shift, p.y_off, p.lo);
+          if (PLAIN) {
+            q[e] = requantize_folded(acc, p.mant, fold, lo_v);
+          } else {
+            acc -= p.w_off * xsum;
+            q[e] = fast ? requantize_as<true>(acc, p.mant, p.shift, p.y_off, p.lo)
+                        : requantize_as<false>(acc, p.mant, p.shift, p.y_off, p.lo);
+          }
+        }
+        if (rn.oh0 + ro < p.oh && rn.ow0 + o < p.ow)
+          *reinterpret_cast<unsigned*>(yrow + ((size_t)ro * p.ow + o) * p.k) = pack_codes(q[0], q[1], q[2], q[3]);
       }
-      *reinterpret_cast<unsigned*>(Y + ((size_t)(img * p.oh + oh) * p.ow + ow) * p.k + c0) = pack_codes(q[0], q[1], q[2], q[3]);
     }
   }
 }
@@ -182,28 +249,42 @@ bool dw_shape(const Problem& p) {
   if (p.groups != p.c || p.k != p.c || p.cg != 1 || p.kg != 1) return false;
   if (p.r != 3 || p.s != 3 || p.stride_h != p.stride_w || (p.stride_h != 1 && p.stride_h != 2)) return false;
   if (p.c % 4 != 0) return false;
+  if ((long long)p.n * p.oh * p.ow * p.k >= (1LL << 31)) return false;      // 32-bit run and thread indices
   return p.x_bytes < 0xF0000000u;
 }
 
-DwGrid dw_grid(const Problem& p) {
+// Output rows per run.  Two rows share two of their three (stride 2: one of their three) input rows in registers;
+// at stride 2 the five-row window costs more registers than the sharing saves.  Knob DW: 0 off, 1 this choice,
+// 2 one row, 3 two rows.
+int dw_rows(const Problem& p) {
+  const int v = knob_or(KNOB_DW, 1);
+  if (v == 2 || v == 3) return v - 1;
+  return p.stride_h == 1 ? 2 : 1;
+}
+
+DwGrid dw_grid(const Problem& p, int rows) {
   DwGrid g;
   g.cq = p.c / 4;
   g.runs_w = (p.ow + DW_RUN - 1) / DW_RUN;
-  g.runs = (long long)p.n * p.oh * g.runs_w;
-  // enough threads to fill the chip (256 CUs x 2048) without leaving a thread less than one run
-  long long slots = (256LL * 2048 + g.cq - 1) / g.cq;
-  if (slots > g.runs) slots = g.runs;
+  g.strips = (p.oh + rows - 1) / rows;
+  g.runs = (long long)p.n * g.strips * g.runs_w;
+  // a thread for every run up to 2048 threads per CU; above that every thread walks the same number of runs
+  long long cap = (256LL * 2048 + g.cq - 1) / g.cq;
+  if (cap < 1) cap = 1;
+  const long long passes = (g.runs + cap - 1) / cap;
+  long long slots = passes > 0 ? (g.runs + passes - 1) / passes : 1;
   if (slots < 1) slots = 1;
   g.slots = (int)slots;
+  const long long threads = (long long)g.cq * g.slots;
+  g.blocks = (int)((threads + DW_THREADS - 1) / DW_THREADS);
+  g.per_xcd = (g.blocks + 7) / 8;
   return g;
 }
 
 template <typename Kern>
-hipError_t launch_dw(Kern kern, const Problem& p, hipStream_t stream) {
-  const DwGrid g = dw_grid(p);
-  const long long threads = (long long)g.cq * g.slots;
-  const long long blocks = (threads + DW_THREADS - 1) / DW_THREADS;
-  hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(DW_THREADS), 0, stream, p, g);
+hipError_t launch_dw(Kern kern, const Problem& p, int rows, hipStream_t stream) {
+  const DwGrid g = dw_grid(p, rows);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(8 * g.per_xcd)), dim3(DW_THREADS), 0, stream, p, g);
   return hipGetLastError();
 }
 
@@ -213,13 +294,27 @@ bool dw_f32_applicable(const Problem& p) { return dw_shape(p); }
 bool dw_i8_applicable(const Problem& p) { return dw_shape(p); }
 
 hipError_t launch_dw_f32(const Problem& p, hipStream_t stream, const char** variant) {
-  *variant = p.stride_h == 1 ? "conv_dw_f32_3x3s1" : "conv_dw_f32_3x3s2";
-  return p.stride_h == 1 ? launch_dw(conv_dw_f32_kernel<1>, p, stream) : launch_dw(conv_dw_f32_kernel<2>, p, stream);
+  const int rows = dw_rows(p);
+  if (p.stride_h == 1) {
+    *variant = "conv_dw_f32_3x3s1";
+    return rows == 1 ? launch_dw(conv_dw_f32_kernel<1, 1>, p, 1, stream) : launch_dw(conv_dw_f32_kernel<1, 2>, p, 2, stream);
+  }
+  *variant = "conv_dw_f32_3x3s2";
+  return rows == 1 ? launch_dw(conv_dw_f32_kernel<2, 1>, p, 1, stream) : launch_dw(conv_dw_f32_kernel<2, 2>, p, 2, stream);
 }
 
 hipError_t launch_dw_i8(const Problem& p, hipStream_t stream, const char** variant) {
-  *variant = p.stride_h == 1 ? "conv_dw_i8_3x3s1" : "conv_dw_i8_3x3s2";
-  return p.stride_h == 1 ? launch_dw(conv_dw_i8_kernel<1>, p, stream) : launch_dw(conv_dw_i8_kernel<2>, p, stream);
+  const int rows = dw_rows(p);
+  // the plain form: no filter offset, and a requantize shift the folded addend covers
+  const bool plain = p.w_off == 0 && p.shift >= 33 && p.shift <= 54;
+  if (p.stride_h == 1) {
+    *variant = "conv_dw_i8_3x3s1";
+    if (plain) return rows == 1 ? launch_dw(conv_dw_i8_kernel<1, 1, true>, p, 1, stream) : launch_dw(conv_dw_i8_kernel<1, 2, true>, p, 2, stream);
+    return rows == 1 ? launch_dw(conv_dw_i8_kernel<1, 1, false>, p, 1, stream) : launch_dw(conv_dw_i8_kernel<1, 2, false>, p, 2, stream);
+  }
+  *variant = "conv_dw_i8_3x3s2";
+  if (plain) return rows == 1 ? launch_dw(conv_dw_i8_kernel<2, 1, true>, p, 1, stream) : launch_dw(conv_dw_i8_kernel<2, 2, true>, p, 2, stream);
+  return rows == 1 ? launch_dw(conv_dw_i8_kernel<2, 1, false>, p, 1, stream) : launch_dw(conv_dw_i8_kernel<2, 2, false>, p, 2, stream);
 }
 
 }  // namespace glowmi

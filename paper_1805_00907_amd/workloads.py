@@ -127,6 +127,15 @@ def resnet50_bottleneck(batch: int) -> List[ConvLayer]:
     ]
 
 
+def depthwise_layers(batch: int) -> List[ConvLayer]:
+    """Depthwise 3x3 layers (groups == channels: every channel has its own 3x3 filter) on the feature-map sizes
+    of a 224 x 224 classification network that halves the map and doubles the channels stage by stage."""
+    b = batch
+    shapes = [(112, 32, 1), (112, 64, 2), (56, 128, 1), (56, 128, 2), (28, 256, 1), (28, 256, 2), (14, 512, 1),
+              (14, 512, 2), (7, 1024, 1)]
+    return [ConvLayer(f"dw_3x3s{st}_c{c}_{hw}@b{b}", b, hw, hw, c, c, 3, 3, st, 1, groups=c) for hw, c, st in shapes]
+
+
 def addend_f32(layer: ConvLayer, seed: int) -> np.ndarray:
     """Shortcut tensor of a block tail: unit-variance activations of the output's shape."""
     rng = np.random.default_rng(seed + 500)

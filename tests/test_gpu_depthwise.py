@@ -40,9 +40,14 @@ def _layer(i):
     return n, h, w, c, st, pd
 
 
+ROW_FORMS = [1, 2, 3]      # knob DW: the planner's choice, one output row per run, two
+
+
 @pytest.mark.parametrize("i", range(len(SHAPES)))
-def test_depthwise_f32(i):
+@pytest.mark.parametrize("rows", ROW_FORMS)
+def test_depthwise_f32(i, rows, knobs):
     G = _gpu()
+    knobs.set("DW", rows)
     n, h, w, c, st, pd = _layer(i)
     rng = np.random.default_rng(38000 + i)
     x = rng.standard_normal(size=(n, h, w, c)).astype(np.float32)
@@ -61,8 +66,10 @@ def test_depthwise_f32(i):
 
 @pytest.mark.parametrize("i", range(len(SHAPES)))
 @pytest.mark.parametrize("dist,w_off", [("normal", 0), ("uniform", -7)])
-def test_depthwise_int8(i, dist, w_off):
+@pytest.mark.parametrize("rows", ROW_FORMS)
+def test_depthwise_int8(i, dist, w_off, rows, knobs):
     G = _gpu()
+    knobs.set("DW", rows)
     n, h, w, c, st, pd = _layer(i)
     layer = wl.ConvLayer(f"dw{i}", n, h, w, c, c, 3, 3, st, 1, c)
     xq, wq, bq, qp = wl.conv_inputs_q(layer, 38100 + i, dist=dist, w_off=w_off)
@@ -75,12 +82,15 @@ def test_depthwise_int8(i, dist, w_off):
         G.assert_equal_i8(got, ref, f"depthwise int8 {SHAPES[i]} {dist} act {act}")
 
 
-@pytest.mark.parametrize("y_scale_factor", [2.0, 64.0])
-def test_depthwise_int8_both_requantize_forms(y_scale_factor):
-    """Multipliers of 1/4 and more take the 64-bit form, smaller ones the multiply-high."""
+@pytest.mark.parametrize("y_scale_factor", [2.0, 64.0, 2.0 ** 26])
+@pytest.mark.parametrize("w_off", [0, 3])
+def test_depthwise_int8_every_requantize_form(y_scale_factor, w_off):
+    """Multipliers of 1/4 and more take the 64-bit form, smaller ones the multiply-high, which without a filter
+    offset has the rounding constant and the output offset folded into one addend down to multipliers of 2^-24;
+    below that the unfolded form again."""
     G = _gpu()
     layer = wl.ConvLayer("dwq", 2, 12, 14, 24, 24, 3, 3, 1, 1, 24)
-    xq, wq, bq, qp = wl.conv_inputs_q(layer, 38200, dist="normal", w_off=3)
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, 38200, dist="normal", w_off=w_off)
     qp = wl.QParams(qp.x_scale, qp.x_off, qp.w_scale, qp.w_off, qp.x_scale * qp.w_scale * y_scale_factor, qp.y_off)
     desc = G.make_desc(xq.shape, wq.shape, (1, 1), (1, 1, 1, 1), 24)
     ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
@@ -90,7 +100,7 @@ def test_depthwise_int8_both_requantize_forms(y_scale_factor):
     G.assert_equal_i8(got, ref, f"depthwise int8, multiplier 1/{y_scale_factor}")
 
 
-def test_shapes_the_depthwise_kernel_leaves_to_the_generic_ones():
+def test_shapes_the_depthwise_kernel_leaves_to_the_generic_ones(knobs):
     G = _gpu()
     rng = np.random.default_rng(38300)
     cases = [
@@ -120,6 +130,12 @@ def test_shapes_the_depthwise_kernel_leaves_to_the_generic_ones():
     got, variant = G.gpu_conv2d_f32_chain(x, wt, b, add, desc, wl.ACT_RELU)
     assert not variant.startswith("conv_dw"), variant
     G.assert_close_f32(got, ref, "depthwise with a tensor add behind it")
+    # the knob at 0: the generic kernels on a shape the depthwise kernel would take
+    knobs.set("DW", 0)
+    ref = oracle.conv2d_f32(x, wt, b, (1, 1), (1, 1, 1, 1), c, act=wl.ACT_RELU)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)
+    assert not variant.startswith("conv_dw"), variant
+    G.assert_close_f32(got, ref, "depthwise on the generic kernels")
 
 
 def test_depthwise_at_a_networks_size_fp32_and_int8():
