@@ -155,3 +155,94 @@ def test_depthwise_at_a_networks_size_fp32_and_int8():
         got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, wl.ACT_RELU, fill=fill)
         assert variant == "conv_dw_i8_3x3s1", variant
         G.assert_equal_i8(got, ref, f"depthwise int8 128 @56 batch 32 (output pre-filled with {fill})")
+
+
+# ---------------------------------------------------------------------------------------------------
+# a depthwise-separable block as one sequence out of one arena: depthwise 3x3 + Relu -> pointwise 1x1 + Relu
+# ---------------------------------------------------------------------------------------------------
+def _separable_layers(n, hw, c, k, stride):
+    dw = wl.ConvLayer("s1", n, hw, hw, c, c, 3, 3, stride, 1, groups=c)
+    return [dw, wl.ConvLayer("s2", n, dw.oh, dw.ow, c, k, 1, 1, 1, 0)]
+
+
+@pytest.mark.parametrize("n,hw,c,k,stride", [(2, 14, 32, 64, 1), (1, 15, 64, 128, 2), (3, 9, 8, 24, 1)])
+def test_separable_block_f32_sequence(n, hw, c, k, stride):
+    """Each layer of the sequence against the oracle fed with the GPU's own previous activation, and a captured
+    graph of the sequence replayed against the eager result (no memset nodes, default-priority stream)."""
+    import torch
+    import paper_1805_00907_amd as glowmi
+    G = _gpu()
+    specs = _separable_layers(n, hw, c, k, stride)
+    data = [wl.conv_inputs_f32(s, 38500 + i) for i, s in enumerate(specs)]
+    x = data[0][0]
+    xd = G.dev(x)
+    dev_w = [(G.dev(w), G.dev(b)) for (_, w, b) in data]
+    tuples = [(G.desc_of(s), w, b, s.act, s.add) for s, (w, b) in zip(specs, dev_w)]
+    outs = []
+    for upto in (1, 2):
+        arr = glowmi.seq_layers(tuples[:upto])
+        arena = torch.empty(max(glowmi.seq_arena_bytes(arr, False), 16), dtype=torch.uint8, device="cuda:0")
+        s = specs[upto - 1]
+        y = G.poison((n, s.oh, s.ow, s.k), torch.float32)
+        glowmi.seq_conv2d(xd, arr, y, arena)
+        torch.cuda.synchronize()
+        outs.append(y.cpu().numpy())
+    prev = x
+    for i, s in enumerate(specs):
+        _, w, b = data[i]
+        ref = oracle.conv2d_f32(prev, w, b, (s.stride, s.stride), (s.pad,) * 4, s.groups, act=s.act)
+        G.assert_close_f32(outs[i], ref, f"separable block layer {i}")
+        prev = outs[i]
+    arr = glowmi.seq_layers(tuples)
+    arena = torch.empty(max(glowmi.seq_arena_bytes(arr, False), 16), dtype=torch.uint8, device="cuda:0")
+    y = G.poison(outs[1].shape, torch.float32)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        glowmi.seq_conv2d(xd, arr, y, arena, side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            glowmi.seq_conv2d(xd, arr, y, arena, side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(y.cpu().numpy(), outs[1], err_msg=f"graph replay {rep}")
+        scratch = torch.empty(1 << 16, device="cuda:0").normal_()      # the program's own eager work
+        float(scratch.sum())
+
+
+@pytest.mark.parametrize("n,hw,c,k,stride", [(2, 14, 32, 64, 1), (1, 15, 64, 128, 2), (3, 9, 8, 24, 1)])
+def test_separable_block_int8_sequence(n, hw, c, k, stride):
+    """Integer arithmetic end to end: the block must match the oracle's two layers bit for bit."""
+    import torch
+    import paper_1805_00907_amd as glowmi
+    G = _gpu()
+    specs = _separable_layers(n, hw, c, k, stride)
+    data = [wl.conv_inputs_q(s, 38600 + i) for i, s in enumerate(specs)]
+    xq = data[0][0]
+    qps = [d[3] for d in data]
+    in_q = [(qps[0].x_scale, qps[0].x_off), (qps[0].y_scale, qps[0].y_off)]     # a layer reads its predecessor's type
+    xd = G.dev(xq)
+    tuples, keep = [], []
+    for i, s in enumerate(specs):
+        _, w, b, qp = data[i]
+        wd, bd = G.dev(w), G.dev(b)
+        keep.append((wd, bd))
+        tuples.append((G.desc_of(s), wd, bd, s.act, s.add, glowmi.QParam(qp.w_scale, qp.w_off),
+                       glowmi.QParam(qp.y_scale, qp.y_off)))
+    arr = glowmi.seq_layers(tuples)
+    arena = torch.empty(max(glowmi.seq_arena_bytes(arr, True), 16), dtype=torch.uint8, device="cuda:0")
+    last = specs[-1]
+    y = G.poison((n, last.oh, last.ow, last.k), torch.int8)
+    glowmi.seq_qconv2d(xd, glowmi.QParam(*in_q[0]), arr, y, arena)
+    torch.cuda.synchronize()
+    prev = xq
+    for i, s in enumerate(specs):
+        _, w, b, qp = data[i]
+        prev = oracle.qconv2d(prev, in_q[i][0], in_q[i][1], w, qp.w_scale, qp.w_off, b, qp.y_scale, qp.y_off,
+                              (s.stride, s.stride), (s.pad,) * 4, s.groups, act=s.act)
+    G.assert_equal_i8(y.cpu().numpy(), prev, "int8 separable block sequence")
+    assert 0.02 < np.mean((prev > -128) & (prev < 127)), "almost everything saturates"
