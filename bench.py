@@ -327,10 +327,18 @@ def _cpu_baseline(workload, dtype, cfg_index, unit_scale, budget_s):
     cap = max(rows_of(s) for s in specs)
     while cap > 1 and sum(shrink(s, cap).ops for s in specs) / rate > budget_s:
         cap //= 2
-    ops, t = run([shrink(s, cap) for s in specs])
+    sample = [shrink(s, cap) for s in specs]
+    ops, t = run(sample)
+    passes = 1
+    # the probe at one row underrates the host, so the capped sample often ends well inside the budget: a budget of
+    # ten seconds and more (the headline's) is filled to two thirds with further passes over the same sample
+    while budget_s >= 10 and t < budget_s * 2 / 3 and passes < 16:
+        o2, t2 = run(sample)
+        ops, t, passes = ops + o2, t + t2, passes + 1
     full = cap >= max(rows_of(s) for s in specs)
-    desc = (f"every layer of {workload} once at full size" if full
-            else f"every layer of {workload} once, batch/rows capped at {cap}")
+    times = "once" if passes == 1 else f"{passes} times"
+    desc = (f"every layer of {workload} {times} at full size" if full
+            else f"every layer of {workload} {times}, batch/rows capped at {cap}")
     return {"value": ops / t / unit_scale, "unit": "TFLOP/s" if dtype == "f32" else "TOP/s",
             "cores": oracle.num_threads(), "kind": "oracle", "sample": desc, "seconds": round(t, 2)}
 
