@@ -2,7 +2,7 @@
 against the CPU oracle element by element: fp32 within 1e-5 + 1e-4 |oracle|, int8 bit-exact.  Strides 1 and 2,
 every kind of padding, output widths that are not a multiple of the four-pixel runs the kernel walks, channel
 counts from one quad to more than a wavefront's worth, a batch, no bias, both requantize forms, a filter offset,
-uniformly drawn codes (saturation), and a layer at a network's real size.  Shapes the kernel does not take
+uniformly drawn codes (saturation), and every layer bench.py times at its full size.  Shapes the kernel does not take
 (channels not a multiple of four, another filter size, a tensor operand behind the layer, groups of more than
 one channel) must still be right on the generic kernels.
 """
@@ -138,23 +138,26 @@ def test_shapes_the_depthwise_kernel_leaves_to_the_generic_ones(knobs):
     G.assert_close_f32(got, ref, "depthwise on the generic kernels")
 
 
-def test_depthwise_at_a_networks_size_fp32_and_int8():
-    """128 channels on 56 x 56 at batch 32, the shape bench.py times: every output element."""
+@pytest.mark.parametrize("i", range(9))
+def test_depthwise_layers_bench_times_fp32_and_int8(i):
+    """Each of the nine layers of bench.py's depthwise workloads at batch 32, with the seeds bench.py uses: every
+    output element, int8 into two differently pre-filled outputs."""
     G = _gpu()
-    layer = wl.ConvLayer("dw_c128_56", 32, 56, 56, 128, 128, 3, 3, 1, 1, 128)
-    x, wt, b = wl.conv_inputs_f32(layer, 38400)
+    layer = wl.depthwise_layers(32)[i]
+    st, pd = (layer.stride, layer.stride), (layer.pad,) * 4
+    x, wt, b = wl.conv_inputs_f32(layer, wl.layer_seed(7, i))
     desc = G.desc_of(layer)
-    ref = oracle.conv2d_f32(x, wt, b, (1, 1), (1, 1, 1, 1), 128, act=wl.ACT_RELU)
-    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, wl.ACT_RELU)
-    assert variant == "conv_dw_f32_3x3s1", variant
-    G.assert_close_f32(got, ref, "depthwise fp32 128 @56 batch 32")
-    xq, wq, bq, qp = wl.conv_inputs_q(layer, 38401)
+    ref = oracle.conv2d_f32(x, wt, b, st, pd, layer.groups, act=layer.act)
+    got, variant = G.gpu_conv2d_f32(x, wt, b, desc, layer.act)
+    assert variant == f"conv_dw_f32_3x3s{layer.stride}", variant
+    G.assert_close_f32(got, ref, f"{layer.name} fp32")
+    xq, wq, bq, qp = wl.conv_inputs_q(layer, wl.layer_seed(7, i))
     ref = oracle.qconv2d(xq, qp.x_scale, qp.x_off, wq, qp.w_scale, qp.w_off, bq, qp.y_scale, qp.y_off,
-                         (1, 1), (1, 1, 1, 1), 128, act=wl.ACT_RELU)
+                         st, pd, layer.groups, act=layer.act)
     for fill in (77, -5):
-        got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, wl.ACT_RELU, fill=fill)
-        assert variant == "conv_dw_i8_3x3s1", variant
-        G.assert_equal_i8(got, ref, f"depthwise int8 128 @56 batch 32 (output pre-filled with {fill})")
+        got, variant = G.gpu_qconv2d(xq, wq, bq, qp, desc, layer.act, fill=fill)
+        assert variant == f"conv_dw_i8_3x3s{layer.stride}", variant
+        G.assert_equal_i8(got, ref, f"{layer.name} int8 (output pre-filled with {fill})")
 
 
 # ---------------------------------------------------------------------------------------------------
