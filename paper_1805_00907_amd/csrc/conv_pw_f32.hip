@@ -316,9 +316,17 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
 
   // Staging of one chunk: load i of a lane covers pixel 8i + lane/8 of the block, 16 bytes at channel
   // chunk*32 + 4*(lane%8): eight whole 128-byte runs per instruction.
+  // Up to two chunks are kept in flight per wavefront (a chunk is multiplied in a fraction of the memory latency, and
+  // what a CU streams is the bytes it has in flight over that latency): chunk c + 2 is fetched into the registers
+  // chunk c was committed from.  A reduction is an even number of chunks long, so a chunk's slot is its index's parity.
   const int srow = lane >> 3, sq = lane & 7;
-  v4f st[4];
-  auto fetch_chunk = [&](int rb, int chunk) {
+  v4f st2[2][4];
+  static_assert(G::KC % 2 == 0, "slot of a chunk = parity of its index, also across items");
+  // (64 channels with the add link: two chunks ahead spill; 256 channels: measured no gain, 39.6 -> 40.5 us on
+  // 32 x 56 x 56 x 256 -> 64; 64 -> 256: 35.3 -> 32.4 us, 128 -> 512 with the add link: 37.7 -> 36.4 us)
+  constexpr int AHEAD = (K == 64 && ADD) || K == 256 ? 1 : 2;
+  auto fetch_chunk = [&](int slot, int rb, int chunk) {      // slot: a constant once the chunk loop is unrolled
+    v4f (&st)[4] = st2[slot];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       int m = rb * 32 + 8 * i + srow;
@@ -335,13 +343,17 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
       st[i] = __builtin_bit_cast(v4f, __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0));
     }
   };
-  auto commit_chunk = [&]() {
+  auto commit_chunk = [&](int slot) {
+    const v4f (&st)[4] = st2[slot];
 #pragma unroll
     for (int i = 0; i < 4; ++i) *reinterpret_cast<v4f*>(alds + (8 * i + srow) * PB_APITCH + 4 * sq) = st[i];
   };
 
   const bool has_work = it < it_end;
-  if (has_work) fetch_chunk(block_of(it), 0);
+  if (has_work) {
+    fetch_chunk(0, block_of(it), 0);
+    if (AHEAD == 2) fetch_chunk(1, block_of(it), 1);
+  }
 
   // ---- filter slice -> three bf16 planes in LDS.  The slice is one contiguous run of the [k][C] filter; rows
   // past the last output channel lie past the end of the tensor and the range-checked loads return zeros.
@@ -374,7 +386,7 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
   const unsigned char* w_lane = wlds + l32 * G::PITCHB + 16 * lh;
 
   if (!has_work) return;
-  commit_chunk();
+  commit_chunk(0);
   // With C = 64 the cut pixel fragments of a block stay in registers (48 per lane) and serve every channel group
   // the wavefront computes for that block: only the first item of a block stages and cuts, the others neither
   // touch the input nor the vector ALU for it.  (With C = 128 the 96 registers spill.)
@@ -413,7 +425,9 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
       // the chunk after this one: the next of this item, or the first of the next item (a reduction is at
       // least two chunks long, so the region never still holds chunk 0 when an item ends)
       const bool stage_next = fresh && (c + 1 < G::KC || more);
-      if (stage_next) fetch_chunk(c + 1 < G::KC ? rb : rb_next, c + 1 < G::KC ? c + 1 : 0);
+      // two ahead: chunk c's registers are free (committed), the chunk two on goes there
+      if (fresh && (c + AHEAD < G::KC || more))
+        fetch_chunk((c + AHEAD) % 2, c + AHEAD < G::KC ? rb : rb_next, (c + AHEAD) % G::KC);
 #pragma unroll
       for (int j = 0; j < PB_CHUNK / 16; ++j) {
         v8bf b[3][NB];
@@ -450,7 +464,7 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
       }
       // in program order after this chunk's fragment reads: the wavefront's LDS operations execute
       // in order, so the region is overwritten only once it has been read
-      if (stage_next) commit_chunk();
+      if (stage_next) commit_chunk((c + 1) % 2);
     }
 
 #pragma unroll
