@@ -159,6 +159,8 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
   const int frag_b = lrow * K_BROW + b_pos;
 
   float* __restrict__ Y = static_cast<float*>(p.y);
+  const __amdgpu_buffer_rsrc_t rsrc_y =
+      __builtin_amdgcn_make_buffer_rsrc(p.y, 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
   const float* __restrict__ bias = static_cast<const float*>(p.bias);
   const float* addend = static_cast<const float*>(p.addend);   // may be the output itself
   const bool relu = p.act == 1;
@@ -168,6 +170,17 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
   int t = (gridDim.x & 7) == 0 ? (int)((blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
   if (t >= total) return;
   fetch_patch(t);
+  // Vector-memory operations complete in order, stores included, and one counter covers them all: a slab load issued
+  // behind a tile's 32 output stores cannot be waited for without waiting for the stores (measured: a fifth of the
+  // kernel's time).  Without the add link the first two slabs of the NEXT tile are therefore issued before a tile's
+  // stores (both slab buffers are free by then), every lane issues exactly 32 stores per tile (lanes outside the output
+  // store out of the buffer's range), and the first two trips wait for "all but the operations issued after the slab":
+  // the other slab, the 32 stores, the 12 loads of the next patch.  From the third trip on the wait is for everything,
+  // and the stores have had the patch's conversion and two trips to drain.
+  constexpr bool EARLY = !ADD;
+  constexpr int N_STORES = 32, N_PATCH = 2 * K_PASSES;
+  static_assert(1 + N_STORES + N_PATCH <= 63, "vmcnt is six bits");
+  bool first = true;
   for (; t < total; t += gridDim.x) {
     int img, ty, tx, ct;
     decode(t, img, ty, tx, ct);
@@ -179,8 +192,25 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
     const ScaleBack sb = scale_back(x_max_bits, w_max_bits);
     commit_patch(se_x);
     const int t_next = t + gridDim.x;
-    if (t_next < total) fetch_patch(t_next);            // in flight during this tile's MFMAs (uniform branch)
-    issue_b(ct, 0, 0);
+    const bool prefetching = t_next < total;            // uniform
+    if (!EARLY) {
+      if (prefetching) fetch_patch(t_next);             // in flight during this tile's MFMAs
+      issue_b(ct, 0, 0);
+    } else {
+      if (first) {
+        issue_b(ct, 0, 0);
+        issue_b(ct, 1, 1);
+      }
+      if (prefetching) fetch_patch(t_next);
+    }
+    // the tile's bias values now: a load in the epilogue would make the compiler wait there for everything issued
+    // before it, the next tile's slabs included
+    float bias_v[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int ch = ct * 64 + j * 32 + lrow;
+      bias_v[j] = (ch < p.k && bias) ? bias[ch] : 0.f;
+    }
 
     v16f acc[2][2], acc_lo[2][2];                       // the h1 h1' products; the cross terms (weight 2^-11)
 #pragma unroll
@@ -197,9 +227,24 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
     // is done with the other buffer), refill the other buffer with slab s + 1, multiply slab s.
 #pragma unroll 2
     for (int s = 0; s < K_SLABS; ++s) {
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      if (EARLY && s < 2) {
+        // issued after slab s: (slab 1,) the previous tile's stores unless this is the first tile, the next patch
+        if (s == 0) {
+          if (first && prefetching) __builtin_amdgcn_s_waitcnt(vmcnt_imm(1 + N_PATCH));
+          else if (first) __builtin_amdgcn_s_waitcnt(vmcnt_imm(1));
+          else if (prefetching) __builtin_amdgcn_s_waitcnt(vmcnt_imm(1 + N_STORES + N_PATCH));
+          else __builtin_amdgcn_s_waitcnt(vmcnt_imm(1 + N_STORES));
+        } else {
+          if (first && prefetching) __builtin_amdgcn_s_waitcnt(vmcnt_imm(N_PATCH));
+          else if (first) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+          else if (prefetching) __builtin_amdgcn_s_waitcnt(vmcnt_imm(N_STORES + N_PATCH));
+          else __builtin_amdgcn_s_waitcnt(vmcnt_imm(N_STORES));
+        }
+      } else {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      }
       __syncthreads();
-      issue_b(ct, s + 1, (s + 1) & 1);                  // past the last slab: zero fills, no memory traffic
+      if (!EARLY || s > 0) issue_b(ct, s + 1, (s + 1) & 1);   // past the last slab: zero fills, no memory traffic
       const int tap = s >> 1, half = s & 1;
       const int tr = tap / 3, ts = tap - tr * 3;
       const int c8 = half * 4 + kgrp * 2 + lhalf;       // this lane's 16-byte chunk of the pixel
@@ -232,6 +277,13 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));           // the zero fill past the last slab (and, conservatively, the prefetch)
     __syncthreads();                                    // everyone is done with the patch and the slab buffers
+    if (EARLY && prefetching) {                         // the next tile's first two slabs, ahead of this tile's stores
+      int n_img, n_ty, n_tx, n_ct;
+      decode(t_next, n_img, n_ty, n_tx, n_ct);
+      issue_b(n_ct, 0, 0);
+      issue_b(n_ct, 1, 1);
+    }
+    first = false;
 
     // ---- exchange: the two wavefronts with partial sums of the same 64 pixels x 64 channels swap halves; the
     // kgrp-0 wavefront finishes block 0 (tile rows 4wm, 4wm + 1), the other block 1.
@@ -274,12 +326,18 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
     for (int j = 0; j < 2; ++j) {
       const int ch = ct * 64 + j * 32 + lrow;
       const bool cok = ch < p.k;
-      const float bv = (cok && bias) ? bias[ch] : 0.f;
+      const float bv = bias_v[j];
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int px = (e >> 2) * 8 + lhalf * 4 + (e & 3);
         const int oy = oy0 + (px >> 4), ox = ox0 + (px & 15);
-        if (cok && oy < p.oh && ox < p.ow) {
+        const bool ok = cok && oy < p.oh && ox < p.ow;
+        if (EARLY) {                                     // always issued: the waits above count on it
+          float v = keep[j][e] + bv;
+          if (relu) v = fmaxf(v, 0.f);
+          const unsigned off = ok ? ((unsigned)((img * p.oh + oy) * p.ow + ox) * (unsigned)p.k + (unsigned)ch) * 4u : OOBX;
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, off, 0, 0);
+        } else if (ok) {
           const size_t o = ((size_t)(img * p.oh + oy) * p.ow + ox) * p.k + ch;
           float v = keep[j][e] + bv;
           if (ADD) v += addend[o];
@@ -312,7 +370,7 @@ bool k3c64_f32_applicable(const Problem& p) {
   if (knob_or(KNOB_F32_K3C64, 1) == 0) return false;
   if (p.b_is_kn || p.chain_n > 0 || p.groups != 1 || p.c != 64 || p.r != 3 || p.s != 3) return false;
   if (p.stride_h != 1 || p.stride_w != 1) return false;
-  if (p.x_bytes > 0xF0000000u) return false;
+  if (p.x_bytes > 0xF0000000u || (long long)p.M * p.k * 4 > 0xF0000000LL) return false;     // 32-bit byte offsets
   const long long tiles = (long long)p.n * ((p.oh + KT - 1) / KT) * ((p.ow + KT - 1) / KT) * ((p.k + 63) / 64);
   if (tiles >= (1LL << 30)) return false;
   // enough tiles to give every CU a few (a tile's patch is fetched while the previous one is multiplied)
