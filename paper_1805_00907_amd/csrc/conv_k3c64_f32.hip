@@ -19,7 +19,9 @@
 //     split every slab's 32 reduction indices, 64 x 64 outputs per wavefront; partial tiles exchanged through
 //     LDS at the end;
 //   - workgroups are persistent: the next tile's patch is fetched into registers while the current tile is
-//     multiplied, so only cutting and writing it (about a tenth of a tile's MFMA time) is exposed;
+//     multiplied, so only cutting and writing it (about a tenth of a tile's MFMA time) is exposed; the next tile's
+//     first two slabs are issued ahead of a tile's output stores, so that no slab load has to be waited for behind
+//     them (loads and stores complete in order under one counter);
 //   - a pixel's eight 16-byte chunks are stored at chunk ^ ((key / 2) % 8), key = 16 * patch row + patch column,
 //     which spreads the two tile rows a fragment read touches over all bank groups whatever the tap.
 #include <hip/hip_runtime.h>
