@@ -33,6 +33,9 @@ SHAPES = [
     (5, 56, 56, 64, (1, 1, 1, 1)),      # 80 tiles
     (2, 224, 100, 64, (1, 1, 1, 1)),    # 196 tiles: more than... fewer than CUs; see below for the persistent walk
     (6, 112, 112, 64, (1, 1, 1, 1)),    # 294 tiles: some workgroups take two
+    (4, 80, 80, 160, (1, 1, 1, 1)),     # 300 tiles in three channel tiles: a workgroup's second tile is another channel
+                                        # tile (its first slabs are issued ahead of the first tile's stores)
+    (3, 150, 150, 64, (1, 1, 1, 1)),    # 300 tiles, ragged: lanes outside the output in every tile of the last row/column
 ]
 
 
