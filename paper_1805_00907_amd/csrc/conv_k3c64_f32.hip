@@ -179,6 +179,9 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
   // store out of the buffer's range), and the first two trips wait for "all but the operations issued after the slab":
   // the other slab, the 32 stores, the 12 loads of the next patch.  From the third trip on the wait is for everything,
   // and the stores have had the patch's conversion and two trips to drain.
+  // (The first patch is waited for here, once: left to the compiler, its wait sits at the head of the tile loop and
+  // there makes every later tile wait until all but eleven of the previous tile's stores have drained.)
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
   constexpr bool EARLY = !ADD;
   constexpr int N_STORES = 32, N_PATCH = 2 * K_PASSES;
   static_assert(1 + N_STORES + N_PATCH <= 63, "vmcnt is six bits");
