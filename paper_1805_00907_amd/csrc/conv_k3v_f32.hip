@@ -205,6 +205,15 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
       const int t_next = t + gridDim.x;
       __syncthreads();                                  // everyone is done with the previous tile's last slab buffer
       issue_b(ct, 0, 0);
+      // The tile's bias values now, not in the epilogue: there every store sits in a branch of its own, the compiler
+      // cannot carry "already waited for" across them and waits for ALL memory operations in front of each store's
+      // bias add, i.e. for the store before it.
+      float bias_v[CH];
+#pragma unroll
+      for (int j = 0; j < CH; ++j) {
+        const int ch = ct * V_BN + (ch_first + j) * 32 + lrow;
+        bias_v[j] = (ch < p.k && bias) ? bias[ch] : 0.f;
+      }
 
       v16f acc[PX][CH], acc_lo[PX][CH];                 // the h1 h1' products; the cross terms (weight 2^-11)
 #pragma unroll
@@ -306,6 +315,10 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
 
       // ---- epilogue.  Register e of a lane is pixel (e/4)*8 + 4*lhalf + e%4 of the 32-pixel block; channel = lrow
       // of the 32-channel column.
+      // Nothing is in flight here (the last trip waited for everything and issued nothing), but the compiler cannot
+      // see that through the loops: told so, it stops putting a wait for all memory operations in front of every
+      // store's bias add, which made each store wait for the one before it.
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
       const ScaleBack sb = scale_back_of(se_x, se_w, finite);
       int lh4 = lhalf * 4;
       asm volatile("" : "+v"(lh4));      // keeps the pixel arithmetic below inside the tile loop (hoisted, it is spilled)
@@ -313,7 +326,7 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
       for (int j = 0; j < CH; ++j) {
         const int ch = ct * V_BN + (ch_first + j) * 32 + lrow;
         const bool cok = ch < p.k;
-        const float bv = (cok && bias) ? bias[ch] : 0.f;
+        const float bv = bias_v[j];
 #pragma unroll
         for (int i = 0; i < PX; ++i) {
 #pragma unroll
