@@ -205,6 +205,14 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
     const int t_next = t + gridDim.x;
     __syncthreads();                                    // everyone is done with the previous tile's last slab buffer
     issue_b(ct, 0, 0);
+    // The tile's bias values now, not in the epilogue: there every store sits in a branch of its own, and the compiler
+    // would wait for all memory operations in front of each store's bias add, i.e. for the store before it.
+    float bias_v[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int ch = ct * G_BN + wn * 64 + j * 32 + lrow;
+      bias_v[j] = (ch < p.k && bias) ? bias[ch] : 0.f;
+    }
 
     v16f acc[2][2], acc_lo[2][2];                       // the h1 h1' products; the cross terms (weight 2^-11)
 #pragma unroll
@@ -299,12 +307,13 @@ __global__ __launch_bounds__(G_THREADS, 2) void conv_k3_f32_kernel(const Problem
 
     // ---- epilogue.  Register e of a lane is pixel (e/4)*8 + 4*lhalf + e%4 of the 32-pixel block, i.e. tile pixel
     // 64wm + 32i + that; channel wn * 64 + j * 32 + lrow.
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));           // nothing is in flight any more; the compiler cannot see it
     const ScaleBack sb = scale_back_of(se_x, se_w, finite);
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
       const int ch = ct * G_BN + wn * 64 + j * 32 + lrow;
       const bool cok = ch < p.k;
-      const float bv = (cok && bias) ? bias[ch] : 0.f;
+      const float bv = bias_v[j];
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
 #pragma unroll

@@ -359,22 +359,39 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void igemm_f32_kernel(const
     const bool full = (it.tm + 1) * BM <= p.M && (it.tn + 1) * BN <= p.kg;
     const bool finish = p.split_k == 1;
     const bool relu = finish && p.act == 1;
+    // Every store below sits in a branch of its own; a load whose result is pending when such a branch is entered
+    // makes the compiler wait for ALL memory operations inside it, i.e. for the store before it.  So the loads come
+    // first, in groups, each followed by one wait that the compiler can see: the bias values of the item, then per
+    // 32 x 32 block the sixteen addend values.
+    float bias_v[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = it.tn * BN + wn * WTN + j * 32 + lrow;
+      bias_v[j] = (col < p.kg && finish && bias) ? bias[it.g * p.kg + col] : 0.f;
+    }
+    __builtin_amdgcn_s_waitcnt(0);                       // vmcnt(0), and the other counters: nothing else is in flight here
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = it.tn * BN + wn * WTN + j * 32 + lrow;
       const bool cok = col < p.kg;
       const int ch = it.g * p.kg + col;
-      const float bv = (cok && finish && bias) ? bias[ch] : 0.f;
+      const float bv = bias_v[j];
       float* dst = dst_base + (size_t)row_base * p.k + ch;
       const float* add = ADD ? addend + (size_t)row_base * p.k + ch : nullptr;
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
+        float addv[16];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int r = i * 32 + (e >> 2) * 8 + (e & 3);
+          addv[e] = (ADD && (full || (cok && row_base + r < p.M))) ? add[(size_t)r * p.k] : 0.f;
+        }
+        if (ADD) __builtin_amdgcn_s_waitcnt(0);
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
           const int r = i * 32 + (e >> 2) * 8 + (e & 3);          // compile-time row inside the wave tile
-          float v = (LONGK ? total[i][j][e] : acc[i][j][e]) + bv;
+          float v = (LONGK ? total[i][j][e] : acc[i][j][e]) + bv + addv[e];
           const bool inside = full || (cok && row_base + r < p.M);
-          if (ADD && inside) v += add[(size_t)r * p.k];
           if (relu) v = fmaxf(v, 0.f);
           if (inside) dst[(size_t)r * p.k] = v;
         }

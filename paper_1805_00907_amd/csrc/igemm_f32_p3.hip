@@ -275,6 +275,16 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
   // what the two accumulator sets are scaled back by: the operands' scale exponents, from their largest magnitudes
   const ScaleBack sb = scale_back(wave_max_words(p.x_range, p.x_range_n), wave_max_words(p.w_range, 1));
 
+  // The bias values now, not in the epilogue: a load there would make the compiler wait for all memory operations
+  // in front of every store (each store is a branch of its own, and each would wait for the store before it).
+  float bias_v[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = tn * BN + wn * 64 + j * 32 + lrow;
+    const float* __restrict__ bias_p = static_cast<const float*>(p.bias);
+    bias_v[j] = (col < p.kg && p.split_k == 1 && bias_p) ? bias_p[g * p.kg + col] : 0.f;
+  }
+
   const int spt = (p.cg + PBK - 1) / PBK;               // slabs per filter tap
   const int total_slabs = p.r * p.s * spt;
   const int slab_begin = split * p.slabs_per_split;
@@ -486,8 +496,8 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
 
   // ---- epilogue: bias (+ tensor add) + activation on the finished sums, one store; or the partial tile.
   // 32x32 MFMA block: register e of a lane is row (e/4)*8 + (lane/32)*4 + e%4, column lane%32.
+  __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // nothing is in flight any more; the compiler cannot see it
   float* __restrict__ Y = static_cast<float*>(p.y);
-  const float* __restrict__ bias = static_cast<const float*>(p.bias);
   const float* addend = static_cast<const float*>(p.addend);   // may be the output itself
   const bool finish = p.split_k == 1;
   const bool relu = finish && p.act == 1;
@@ -500,15 +510,23 @@ __global__ __launch_bounds__(256 * WN, 2) void igemm_f32_p3_kernel(const Problem
     const int col = tn * BN + wn * 64 + j * 32 + lrow;
     const bool cok = col < p.kg;
     const int ch = g * p.kg + col;
-    const float bv = (cok && finish && bias) ? bias[ch] : 0.f;
+    const float bv = bias_v[j];
     float* dst = dst_base + (size_t)row_base * p.k + ch;
     const float* addp = add ? addend + (size_t)row_base * p.k + ch : nullptr;
+    // the column's sixteen addend values first, all in flight together: loaded one by one in front of their stores,
+    // each load would be waited for together with every store before it
+    float addv[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int r = (e >> 2) * 8 + (e & 3);
+      addv[e] = (add && (full || (cok && row_base + r < p.M))) ? addp[(size_t)r * p.k] : 0.f;
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));            // once, here: not in front of each of the sixteen stores
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int r = (e >> 2) * 8 + (e & 3);               // compile-time row inside the 32-row block
-      float v = keep[j][e] + bv;
+      float v = keep[j][e] + bv + addv[e];
       const bool inside = full || (cok && row_base + r < p.M);
-      if (add && inside) v += addp[(size_t)r * p.k];
       if (relu) v = fmaxf(v, 0.f);
       if (inside) dst[(size_t)r * p.k] = v;
     }
