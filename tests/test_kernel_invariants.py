@@ -1,4 +1,6 @@
-"""What the 64-channel fp32 3x3 kernel's waits count on, checked on the compiled code (no GPU needed).
+"""Properties of the compiled kernels that their speed or correctness counts on (no GPU needed).
+
+1. What the 64-channel fp32 3x3 kernel's waits count on.
 
 Without the add link the kernel issues the next tile's first two slab loads ahead of a tile's output stores and then
 waits BY COUNT (vmcnt(45) / vmcnt(44): all but the other slab, the 32 stores and the 12 loads of the next patch).
@@ -6,6 +8,11 @@ That is only right if every wavefront really issues 32 stores and 12 patch loads
 predicates: fewer operations after the slab than the wait allows to be outstanding and the slab may still be in
 flight when it is read.  The compiler is free to branch around a store whose lanes are all off, to merge stores, or
 to drop loads; this test fails the build of the library's sources if it ever does.
+
+2. No wait for all vector-memory operations between two stores of an epilogue.  Every store of these epilogues sits
+in a branch of its own; with a load still pending when such a branch is entered (a bias or addend value loaded inside
+the epilogue) the compiler puts `s_waitcnt vmcnt(0)` in front of every store, and every store then waits for the one
+before it to be written.  The kernels load those values ahead and state the wait once; this checks that it stays so.
 """
 import os
 import re
@@ -60,3 +67,35 @@ def test_k3c64_f32_issues_a_fixed_number_of_memory_operations_per_tile(tmp_path)
         if m:
             waits.add(int(m.group(1)))
     assert {45, 44, 33, 32, 13, 12, 1, 0} <= waits, sorted(waits)
+
+
+def _compile(tmp_path, name):
+    out = tmp_path / (name + ".s")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I", CSRC, "-I", os.path.join(ROOT, "include"), "-S", "--cuda-device-only",
+           "-o", str(out), os.path.join(CSRC, name + ".hip")]
+    subprocess.run(cmd, check=True, capture_output=True)
+    return out.read_text()
+
+
+def _stores_that_wait(body):
+    stores = [i for i, ln in enumerate(body) if re.match(r"(global|buffer|flat)_store", ln)]
+    waits = 0
+    for a, b in zip(stores, stores[1:]):
+        if any(ln.startswith("s_waitcnt") and "vmcnt(0)" in ln for ln in body[a + 1:b]):
+            waits += 1
+    return len(stores), waits
+
+
+@pytest.mark.skipif(not os.path.exists(HIPCC), reason="hipcc not installed")
+@pytest.mark.parametrize("source,kernel,n_stores", [
+    ("conv_k3v_f32", "conv_k3v_f32_kernelILb0ELi7E", 112),          # 64 (squares) + 48 (strips of three blocks)
+    ("conv_k3v_f32", "conv_k3v_f32_kernelILb0ELi8E", 128),
+    ("igemm_f32_p3", "igemm_f32_p3_kernelILi2ELb0ELb0ELi3E", 32),
+    ("igemm_f32_p3", "igemm_f32_p3_kernelILi2ELb1ELb1ELi3E", 32),
+])
+def test_no_epilogue_store_waits_for_the_one_before_it(tmp_path, source, kernel, n_stores):
+    body = _kernel_body(_compile(tmp_path, source), kernel)
+    stores, waiting = _stores_that_wait(body)
+    assert stores == n_stores, stores
+    assert waiting <= 2, waiting        # (the contraction over planes waits once per 32-channel column, by design)
