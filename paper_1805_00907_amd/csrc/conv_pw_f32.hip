@@ -214,9 +214,11 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_kernel(const Proble
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int ch = slice * G::BN + ng * 64 + (hsel + nb) * 32 + l32;
-      if (ch < p.k) {
+      {
+        // no branch around the stores of a channel past the last one (they go out of the buffer's range): under a
+        // branch the compiler cannot count on them, and its wait for the chunk fetched before them drains them all
         const float bv = blds[ng * 64 + (hsel + nb) * 32 + l32];
-        unsigned lane_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes + (unsigned)ch * 4u;
+        unsigned lane_off = ch < p.k ? (unsigned)(rb * 32 + 4 * lh) * row_bytes + (unsigned)ch * 4u : 0xF0000000u;
         asm volatile("" : "+v"(lane_off));                 // keep the per-register row offsets scalar
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -470,9 +472,12 @@ __global__ __launch_bounds__(PW_THREADS, 1) void conv_pw_f32_bf16_kernel(const P
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int ch = slice * G::BN + ng * 64 + (hsel + nb) * 32 + l32;
-      if (ch < p.k) {
+      {
+        // No branch around the stores of a channel past the last one: they go out of the buffer's range instead.
+        // With the stores under a branch the compiler cannot count on them having been issued, and its wait for
+        // the input chunk fetched before them (four loads) becomes a wait for all of the item's stores to drain.
         const float bv = blds[ng * 64 + (hsel + nb) * 32 + l32];
-        unsigned lane_off = (unsigned)(rb * 32 + 4 * lh) * row_bytes + (unsigned)ch * 4u;
+        unsigned lane_off = ch < p.k ? (unsigned)(rb * 32 + 4 * lh) * row_bytes + (unsigned)ch * 4u : 0xF0000000u;
         asm volatile("" : "+v"(lane_off));                 // keep the per-register row offsets scalar
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
