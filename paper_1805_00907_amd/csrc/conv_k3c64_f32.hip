@@ -332,12 +332,33 @@ __global__ __launch_bounds__(K_THREADS, 2) void conv_k3c64_f32_kernel(const Prob
       const int ch = ct * 64 + j * 32 + lrow;
       const bool cok = ch < p.k;
       const float bv = bias_v[j];
+      // the add link: a column's sixteen addend values first, all in flight together, then one wait the compiler can
+      // see -- loaded one by one in front of their stores, each would be waited for together with the store before it
+      float addv[16];
+      if (ADD) {
+        const __amdgpu_buffer_rsrc_t rsrc_add =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(addend), 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int px = (e >> 2) * 8 + lhalf * 4 + (e & 3);
+          const int oy = oy0 + (px >> 4), ox = ox0 + (px & 15);
+          const bool ok = cok && oy < p.oh && ox < p.ow;
+          const unsigned off = ok ? ((unsigned)((img * p.oh + oy) * p.ow + ox) * (unsigned)p.k + (unsigned)ch) * 4u : OOBX;
+          addv[e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_add, off, 0, 0));
+        }
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      }
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int px = (e >> 2) * 8 + lhalf * 4 + (e & 3);
         const int oy = oy0 + (px >> 4), ox = ox0 + (px & 15);
         const bool ok = cok && oy < p.oh && ox < p.ow;
-        if (EARLY) {                                     // always issued: the waits above count on it
+        if (ADD) {                                       // the same offsets as the addend's loads
+          float v = keep[j][e] + bv + addv[e];
+          if (relu) v = fmaxf(v, 0.f);
+          const unsigned off = ok ? ((unsigned)((img * p.oh + oy) * p.ow + ox) * (unsigned)p.k + (unsigned)ch) * 4u : OOBX;
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, off, 0, 0);
+        } else if (EARLY) {                                     // always issued: the waits above count on it
           float v = keep[j][e] + bv;
           if (relu) v = fmaxf(v, 0.f);
           const unsigned off = ok ? ((unsigned)((img * p.oh + oy) * p.ow + ox) * (unsigned)p.k + (unsigned)ch) * 4u : OOBX;
