@@ -359,7 +359,7 @@ bool k3_f32_applicable(const Problem& p) {
   if (p.b_is_kn || p.chain_n > 0 || p.groups != 1 || p.r != 3 || p.s != 3) return false;
   if (p.stride_h != 1 || p.stride_w != 1) return false;
   if (p.c < 64 || p.c % G_CH != 0) return false;
-  if (p.x_bytes > 0xF0000000u || p.w_bytes > (1u << 30)) return false;
+  if (p.x_bytes > 0xF0000000u || p.w_bytes > (1u << 30) || (long long)p.M * p.k * 4 > 0xF0000000LL) return false;   // 32-bit byte offsets
   const int tw = k3_wide_tile(p) ? 32 : 16, bn = k3_wide_tile(p) ? 64 : 128;
   const long long ty = (p.oh + GT - 1) / GT, tx = (p.ow + tw - 1) / tw, tc = (p.k + bn - 1) / bn;
   const long long tiles = (long long)p.n * ty * tx * tc;

@@ -327,6 +327,41 @@ __global__ __launch_bounds__(V_THREADS, 2) void conv_k3v_f32_kernel(const Proble
         const int ch = ct * V_BN + (ch_first + j) * 32 + lrow;
         const bool cok = ch < p.k;
         const float bv = bias_v[j];
+        if (ADD) {
+          // The add link: eight addend values at a time, all in flight together, then one wait the compiler can see
+          // and eight range-checked stores at the same offsets.  Loaded one by one in front of their stores, each
+          // value would be waited for together with the store before it.
+          const __amdgpu_buffer_rsrc_t rsrc_y = __builtin_amdgcn_make_buffer_rsrc(
+              p.y, 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
+          const __amdgpu_buffer_rsrc_t rsrc_add = __builtin_amdgcn_make_buffer_rsrc(
+              const_cast<float*>(addend), 0, (int)((unsigned)p.M * (unsigned)p.k * 4u), 0x00020000);
+          auto offset_of = [&](int i, int e) -> unsigned {      // register e of pixel block i
+            const int tp = 32 * (px_first + i) + (e >> 2) * 8 + lh4 + (e & 3);
+            const int r = div_small(tp, inv_tw);
+            const int c = tp - r * tw;
+            const int oy = ty * th + r, ox = tx * tw + c;
+            const bool ok = cok && tp < tile_px && oy < p.oh && ox < p.ow;
+            return ok ? ((unsigned)((img * p.oh + oy) * p.ow + ox) * (unsigned)p.k + (unsigned)ch) * 4u : OOBX;
+          };
+#pragma unroll
+          for (int i = 0; i < PX; ++i) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+              float addv[8];
+#pragma unroll
+              for (int t = 0; t < 8; ++t)
+                addv[t] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc_add, offset_of(i, 8 * h + t), 0, 0));
+              __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+#pragma unroll
+              for (int t = 0; t < 8; ++t) {
+                float v = join_sets(acc[i][j][8 * h + t], acc_lo[i][j][8 * h + t], sb) + bv + addv[t];
+                if (relu) v = fmaxf(v, 0.f);
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(int, v), rsrc_y, offset_of(i, 8 * h + t), 0, 0);
+              }
+            }
+          }
+          continue;
+        }
 #pragma unroll
         for (int i = 0; i < PX; ++i) {
 #pragma unroll
